@@ -1,0 +1,193 @@
+/*
+ * lx.h -- C ABI of the Dynamic-aware Operator for MI355X (gfx950).
+ *
+ * The library implements the sparse operators of Long Exposure, Sec. VI: a
+ * frozen-weight transformer layer evaluated only on the blocks that a binary
+ * block mask marks as active (Sec. IV-B: 1 = compute, 0 = do not compute), in
+ * the forward pass and in the input-gradient backward pass (Sec. II-D: what is
+ * inactive in the forward pass is excluded from the backward pass; Sec. V-C:
+ * the backward savings mirror the forward ones).
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer unless its comment says HOST.
+ *     lx_blocklist itself is a HOST struct holding DEVICE pointers.
+ *   - The caller owns every buffer, including workspaces.  The library never
+ *     allocates or frees device memory, never synchronises the host with the
+ *     device, and enqueues work only on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream).  Calls return as soon as the work is
+ *     enqueued.
+ *   - All arguments are validated on the host BEFORE anything is launched;
+ *     on any status other than LX_OK nothing has been enqueued and no output
+ *     has been touched.  Contents of device-resident index lists are trusted
+ *     (checking them would need a host synchronisation).
+ *   - Outputs are fully overwritten: rows / heads without an active block are
+ *     written as zeros (LSE as -inf), never left stale.
+ *   - Matrices are row-major with the last dimension contiguous.  Data
+ *     pointers must be 16-byte aligned.
+ *   - bf16 runs keep fp32 accumulators; intermediates that feed a second
+ *     matrix product (H, dZ, P, dS) are rounded to bf16 once.
+ */
+#ifndef LX_H_
+#define LX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LX_OK = 0,
+  LX_ERR_INVALID_ARG = 1, /* null pointer, non-positive or inconsistent size, misalignment */
+  LX_ERR_UNSUPPORTED = 2, /* dtype / block size / head size not built */
+  LX_ERR_WORKSPACE = 3,   /* workspace missing or smaller than the *_workspace_bytes query */
+  LX_ERR_RUNTIME = 4      /* a HIP launch reported an error */
+} lx_status;
+
+typedef enum { LX_F32 = 0, LX_BF16 = 1 } lx_dtype;
+
+/*
+ * Row-compressed active-block list: the "list of data block indices" of
+ * Sec. VI-A and the "indices of activated neuron blocks" of Sec. VI-B.
+ * Row r owns col_idx[row_ptr[r] .. row_ptr[r+1]), ascending, no duplicates.
+ *   FFN:        rows = T / tile_t (token tiles),      cols = F / blk_n (neuron blocks)
+ *   attention:  rows = mask_batch * Hh * (S/64),      cols = S / 64
+ *               (query-block rows for the row list; key-block rows for the
+ *               column list used by the backward pass)
+ * nnz_cap is a host-known upper bound on the number of active blocks (rows*cols
+ * if nothing better is known); it sizes H_act and bounds launch grids, because
+ * the true count lives only on the device.
+ */
+typedef struct {
+  int32_t rows;
+  int32_t cols;
+  const int32_t* row_ptr; /* DEVICE [rows + 1], row_ptr[0] == 0 */
+  const int32_t* col_idx; /* DEVICE [>= nnz_cap] */
+  int32_t nnz_cap;
+} lx_blocklist;
+
+/* Human-readable name of a status code (HOST string, static storage). */
+const char* lx_status_string(lx_status s);
+
+/*
+ * Mask compaction (online step of Sec. VI-A; index list of Sec. VI-B).
+ * Turns `batch` dense byte masks of rows x cols blocks into one row-compressed
+ * list with batch*rows rows.  Entry (g, r, c) is read at
+ * mask[g*batch_stride + r*row_stride + c*col_stride] (strides in bytes); any
+ * non-zero byte counts as active.  Swapping row and column strides (and
+ * rows/cols) yields the column-compressed list.
+ *   row_ptr  out, int32[batch*rows + 1]
+ *   col_idx  out, int32[col_idx_cap]; col_idx_cap must be >= batch*rows*cols
+ *            unless the caller knows a tighter bound on the active count
+ *            (entries beyond the capacity are dropped, row_ptr stays exact).
+ * The result is unique (ascending columns), hence bit-exact reproducible.
+ * Errors: INVALID_ARG for null pointers, non-positive sizes or capacity.
+ */
+lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
+                          int64_t batch_stride, int64_t row_stride, int64_t col_stride,
+                          int32_t* row_ptr, int32_t* col_idx, int32_t col_idx_cap, void* stream);
+
+/*
+ * One-time repack of the frozen weights (Sec. VI-B "memory coalescing": each
+ * product reads its weights along the contiguous dimension).  Writes the
+ * transposes W_up_t[d,F] = W_up[F,d]^T and W_down_t[F,d] = W_down[d,F]^T, which
+ * the backward call uses.  Either output may be NULL to skip it.
+ */
+lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_up,
+                              const void* W_down, void* W_up_t, void* W_down_t, void* stream);
+
+/* Workspace (bytes) for lx_sparse_ffn_fwd / lx_sparse_ffn_bwd_dx.
+ * have_h_act: the caller passes an H_act buffer to the forward call.
+ * have_packed: the caller passes W_up_t and W_down_t to the backward call. */
+size_t lx_sparse_ffn_fwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t F,
+                                         int32_t tile_t, int32_t blk_n, int32_t nnz_cap,
+                                         int32_t have_h_act);
+size_t lx_sparse_ffn_bwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t F,
+                                         int32_t tile_t, int32_t blk_n, int32_t nnz_cap,
+                                         int32_t have_packed);
+
+/*
+ * Sparse FFN forward (Sec. VI-B neuron-centric tiled products; forward
+ * equations of Sec. II-C with ReLU).  For every listed (token tile i, neuron
+ * block j):   H_ij = ReLU(X_i W_up[j,:]^T + b_up[j]);
+ *             Y_i  = sum over listed j of H_ij W_down[:, j]^T + b_down.
+ *   X      [T,d]   W_up [F,d]   W_down [d,F]   b_up [F] / b_down [d] nullable
+ *   bl     rows = T/tile_t, cols = F/blk_n
+ *   Y      out [T,d]
+ *   H_act  out, compact activations [nnz_cap][tile_t][blk_n] in list order,
+ *          needed by the backward call; NULL keeps them in the workspace only.
+ * Supported: LX_F32 with (tile_t, blk_n) in {(32,32),(64,64)}, d % 32 == 0;
+ *            LX_BF16 with (64,64), d % 64 == 0.
+ */
+lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                            int32_t blk_n, const void* X, const void* W_up, const void* b_up,
+                            const void* W_down, const void* b_down, const lx_blocklist* bl,
+                            void* Y, void* H_act, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
+ * Sparse FFN input gradient (Sec. II-D): for every listed (i, j)
+ *   dZ_ij = (dY_i W_down[:, j]) (.) [H_ij > 0];   dX_i = sum_j dZ_ij W_up[j,:].
+ *   dY [T,d]; H_act as written by the forward call (same list);
+ *   W_up_t [d,F], W_down_t [F,d]: outputs of lx_ffn_pack_weights, or both NULL,
+ *   in which case the transposes are rebuilt in the workspace on every call.
+ *   dX out [T,d].
+ */
+lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                               int32_t blk_n, const void* dY, const void* H_act,
+                               const void* W_up, const void* W_down, const void* W_up_t,
+                               const void* W_down_t, const lx_blocklist* bl, void* dX,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace (bytes) for lx_sparse_attn_bwd_dx (the forward call needs none). */
+size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, int32_t S,
+                                          int32_t D);
+
+/*
+ * Block-sparse attention forward (Sec. VI-A: SDD, softmax, DSD over a block
+ * list; here fused, the score matrix is never written).  For every batch b,
+ * head h with head_active[h] != 0, query row q:
+ *   allowed(q) = keys k whose 64x64 block (q/64, k/64) is listed for (b or 0, h)
+ *                and, if causal, k <= q  (blocks above the diagonal must not be
+ *                listed when causal);
+ *   O[q,:] = softmax over allowed(q) of (scale Q[q,:] K[k,:]^T) times V;
+ *   LSE[q] = log sum exp of the allowed scaled scores (natural log).
+ * Rows with no allowed key and inactive heads give O = 0, LSE = -inf.
+ *   Q,K,V,O  [B,Hh,S,D], element (b,h,s,c) at b*strides_bhs[0] + h*strides_bhs[1]
+ *            + s*strides_bhs[2] + c (HOST array of 3 element strides, each a
+ *            multiple of 8), all four tensors share the strides.
+ *   bl       rows = mask_batch*Hh*(S/64) ordered (batch, head, query block);
+ *            mask_batch is 1 (mask shared over the batch, Sec. V-A) or B.
+ *   head_active  uint8[Hh] or NULL (all heads active)
+ *   LSE      out float32 [B,Hh,S] contiguous
+ * Supported: LX_BF16, D in {64, 128}, S % 64 == 0.
+ */
+lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                             float scale, int32_t causal, const void* Q, const void* K,
+                             const void* V, const int64_t strides_bhs[3],
+                             const lx_blocklist* bl, int32_t mask_batch,
+                             const uint8_t* head_active, void* O, float* LSE, void* stream);
+
+/*
+ * Block-sparse attention backward over the same blocks (Sec. V-C).  With
+ * P = exp(scale Q K^T - LSE) on allowed positions and Delta = rowsum(dO (.) O):
+ *   dV = P^T dO;  dS = P (.) (dO V^T - Delta);  dQ = scale dS K;  dK = scale dS^T Q.
+ *   dO, O, dQ, dK, dV share the layout and strides of Q.
+ *   bl_rows  the forward list;  bl_cols  the same mask column-compressed:
+ *            rows = mask_batch*Hh*(S/64) ordered (batch, head, key block),
+ *            entries = query blocks.
+ *   workspace  >= lx_sparse_attn_bwd_workspace_bytes (holds Delta).
+ */
+lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                                float scale, int32_t causal, const void* Q, const void* K,
+                                const void* V, const void* O, const float* LSE, const void* dO,
+                                const int64_t strides_bhs[3], const lx_blocklist* bl_rows,
+                                const lx_blocklist* bl_cols, int32_t mask_batch,
+                                const uint8_t* head_active, void* dQ, void* dK, void* dV,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LX_H_ */

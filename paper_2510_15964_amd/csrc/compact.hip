@@ -1,0 +1,104 @@
+// Active-block list compaction (online index-list construction of Sec. VI-A;
+// neuron-block index list of Sec. VI-B).
+//
+// The masks of one layer are tiny (tens of thousands of bytes), so the whole
+// job is latency-bound: one 1024-thread workgroup does count -> scan -> scatter
+// in a single launch with no host round trip.  One wavefront owns a mask row at
+// a time: a 64-wide ballot gives the row's bit pattern, popcount its total and
+// mbcnt the rank of every set lane, so columns come out ascending.
+#include "lx_dev.h"
+
+namespace lx {
+
+constexpr int kCompactThreads = 1024;
+constexpr int kCompactWaves = kCompactThreads / kWave;
+constexpr int kChunkRows = 4096;  // rows scanned per pass (4 per thread)
+
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(
+    const uint8_t* __restrict__ mask, int batch, int rows, int cols, long long bstride,
+    long long rstride, long long cstride, int* __restrict__ row_ptr, int* __restrict__ col_idx,
+    int cap) {
+  __shared__ int offs[kChunkRows];
+  __shared__ int wave_tot[kCompactWaves];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int total_rows = batch * rows;
+  int carry = 0;
+  for (int chunk = 0; chunk < total_rows; chunk += kChunkRows) {
+    const int n = min(kChunkRows, total_rows - chunk);
+    // 1. per-row counts
+    for (int r = wave; r < n; r += kCompactWaves) {
+      const int gr = chunk + r;
+      const uint8_t* base = mask + (long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride;
+      int cnt = 0;
+      for (int c0 = 0; c0 < cols; c0 += kWave) {
+        const int c = c0 + lane;
+        const bool on = c < cols && base[(long long)c * cstride] != 0;
+        cnt += __popcll(__ballot(on));
+      }
+      if (lane == 0) offs[r] = cnt;
+    }
+    __syncthreads();
+    // 2. exclusive scan of the counts (4 consecutive rows per thread)
+    int v[4], s = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int idx = tid * 4 + e;
+      v[e] = idx < n ? offs[idx] : 0;
+      s += v[e];
+    }
+    int incl = s;
+#pragma unroll
+    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+      const int up = __shfl_up(incl, dlt);
+      if (lane >= dlt) incl += up;
+    }
+    if (lane == kWave - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    int wbase = 0, chunk_total = 0;
+#pragma unroll
+    for (int w = 0; w < kCompactWaves; ++w) {
+      const int t = wave_tot[w];
+      if (w < wave) wbase += t;
+      chunk_total += t;
+    }
+    int run = carry + wbase + incl - s;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int idx = tid * 4 + e;
+      if (idx < n) {
+        offs[idx] = run;
+        row_ptr[chunk + idx] = run;
+      }
+      run += v[e];
+    }
+    __syncthreads();
+    // 3. scatter the ascending column indices
+    for (int r = wave; r < n; r += kCompactWaves) {
+      const int gr = chunk + r;
+      const uint8_t* base = mask + (long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride;
+      int off = offs[r];
+      for (int c0 = 0; c0 < cols; c0 += kWave) {
+        const int c = c0 + lane;
+        const bool on = c < cols && base[(long long)c * cstride] != 0;
+        const unsigned long long bits = __ballot(on);
+        const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(bits >> 32),
+                                                   __builtin_amdgcn_mbcnt_lo((unsigned)bits, 0));
+        if (on && off + rank < cap) col_idx[off + rank] = c;
+        off += __popcll(bits);
+      }
+    }
+    carry += chunk_total;
+    __syncthreads();
+  }
+  if (tid == 0) row_ptr[total_rows] = carry;
+}
+
+hipError_t launch_compact(const uint8_t* mask, int batch, int rows, int cols, long long bs,
+                          long long rs, long long cs, int* row_ptr, int* col_idx, int cap,
+                          hipStream_t stream) {
+  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kCompactThreads), 0, stream, mask, batch, rows,
+                     cols, bs, rs, cs, row_ptr, col_idx, cap);
+  return hipGetLastError();
+}
+
+}  // namespace lx

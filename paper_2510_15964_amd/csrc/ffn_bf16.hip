@@ -1,0 +1,256 @@
+// bf16 sparse FFN kernels for gfx950 (Sec. VI-B: neuron-centric tiled matrix
+// products that take the list of active neuron blocks and load / compute only
+// those).  fp32 accumulation on the 32x32x16 bf16 MFMA.
+//
+// Both products of a pass are "NT" contractions whose operands are read along
+// their contiguous dimension in 128-byte segments (one 64-element bf16 K-chunk
+// of one row), which is what the weight layouts of Sec. VI-B are for:
+//   sdd  out block (i, j) = A_i [64 x K] . W[j-block rows, :]^T, K = d
+//        one workgroup owns up to four consecutive entries of token tile i's
+//        list, so the A_i chunk staged in LDS is shared by four neuron blocks;
+//        wave w computes block w (64 x 64, four 32x32 accumulators).
+//   dsd  out tile (i, 256 columns) = sum over listed j of Act_ij [64 x 64] .
+//        W[rows n0.., j-block columns]^T: the K loop walks the active list, one
+//        64-wide K-step per active block; inactive blocks are never touched.
+// Global -> register prefetch of K-step s+1 overlaps the MFMA work of step s.
+#include "lx_dev.h"
+
+namespace lx {
+
+constexpr int kThreads = 256;
+constexpr int kBK = 64;           // K-chunk per step: 64 bf16 = 128 bytes per row
+constexpr int kPitch = kBK + 8;   // LDS row pitch in elements (144 B): conflict-free b128 reads
+constexpr int kRowsB = 64;        // shared operand (token rows)
+constexpr int kRowsA = 256;       // per-wave operand (4 x 64 weight rows)
+constexpr int kSlots = (kRowsA + kRowsB) * 8 / kThreads;  // 16-byte loads per thread per step = 10
+
+struct Stage {
+  uint4 v[kSlots];
+};
+
+// slot u of thread tid covers row (tid/8 + 32u) of the combined [B rows | A rows] tile,
+// 16-byte segment tid%8.
+__device__ __forceinline__ void store_stage(const Stage& st, uint16_t* lds) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < kSlots; ++u) {
+    const int row = tid / 8 + 32 * u;
+    *reinterpret_cast<uint4*>(lds + row * kPitch + (tid % 8) * 8) = st.v[u];
+  }
+}
+
+// One 64-deep K-step from LDS: wave w multiplies its 64 A rows with the 64 shared B rows.
+// acc[ni][ti]: rows (A operand) 32ni.., columns (B operand) 32ti..
+__device__ __forceinline__ void mma_step(const uint16_t* lds, int wave, f32x16 (&acc)[2][2]) {
+  const int lane = threadIdx.x % kWave;
+  const int r = lane % 32, kq = (lane / 32) * 8;
+  const uint16_t* Bt = lds;
+  const uint16_t* At = lds + (kRowsB + 64 * wave) * kPitch;
+#pragma unroll
+  for (int kk = 0; kk < kBK; kk += 16) {
+    uint4 a[2], b[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      a[h] = *reinterpret_cast<const uint4*>(At + (32 * h + r) * kPitch + kk + kq);
+      b[h] = *reinterpret_cast<const uint4*>(Bt + (32 * h + r) * kPitch + kk + kq);
+    }
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32(a[ni], b[ti], acc[ni][ti]);
+  }
+}
+
+// MODE 0: out = bf16(max(acc + bias, 0));  MODE 1: out = gate > 0 ? bf16(acc) : 0.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+    const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, int K, uint16_t* __restrict__ out_act,
+    const uint16_t* __restrict__ gate_act) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[(kRowsA + kRowsB) * kPitch];
+  const int i = blockIdx.y;
+  const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
+  const int first = blockIdx.x * 4;
+  if (first >= n_i) return;
+  const int nb = min(4, n_i - first);
+  const int p0 = rs + first;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+
+  // per-slot row base pointers (slot -> block index is a compile-time function of u)
+  const uint16_t* src[kSlots];
+#pragma unroll
+  for (int u = 0; u < kSlots; ++u) {
+    const int row = tid / 8 + 32 * u;
+    if (u < 2) {
+      src[u] = A + ((long long)i * 64 + row) * K + (tid % 8) * 8;
+    } else {
+      const int blk = (u - 2) / 2, r = row - kRowsB - 64 * blk;
+      src[u] = blk < nb ? W + ((long long)col_idx[p0 + blk] * 64 + r) * K + (tid % 8) * 8 : nullptr;
+    }
+  }
+  Stage st;
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u)
+      st.v[u] = src[u] ? *reinterpret_cast<const uint4*>(src[u] + k0) : make_uint4(0, 0, 0, 0);
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += kBK) {
+    store_stage(st, lds);
+    __syncthreads();
+    if (k0 + kBK < K) fetch(k0 + kBK);
+    if (wave < nb) mma_step(lds, wave, acc);
+    __syncthreads();
+  }
+  if (wave >= nb) return;
+
+  const int p = p0 + wave;
+  const int j = col_idx[p];
+  const int tl = lane % 32, nq = (lane / 32) * 4;
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int t = 32 * ti + tl, n = 32 * ni + 8 * g + nq;
+        const long long o = (long long)p * 4096 + t * 64 + n;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
+        if (MODE == 0) {
+          if (bias) {
+            const uint2 bb = *reinterpret_cast<const uint2*>(bias + j * 64 + n);
+            v[0] += bf2f(bb.x & 0xFFFFu); v[1] += bf2f(bb.x >> 16);
+            v[2] += bf2f(bb.y & 0xFFFFu); v[3] += bf2f(bb.y >> 16);
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+        } else {
+          const uint2 gg = *reinterpret_cast<const uint2*>(gate_act + o);
+          if (!(bf2f(gg.x & 0xFFFFu) > 0.f)) v[0] = 0.f;
+          if (!(bf2f(gg.x >> 16) > 0.f)) v[1] = 0.f;
+          if (!(bf2f(gg.y & 0xFFFFu) > 0.f)) v[2] = 0.f;
+          if (!(bf2f(gg.y >> 16) > 0.f)) v[3] = 0.f;
+        }
+        uint2 ov;
+        ov.x = pack2bf(v[0], v[1]);
+        ov.y = pack2bf(v[2], v[3]);
+        *reinterpret_cast<uint2*>(out_act + o) = ov;
+      }
+}
+
+// out[i-tile rows, n0 .. n0+255] = sum_s act[p_s] [64 x 64] . W[n0.., j_s*64 ..]^T (+ bias)
+__global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
+    const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
+    const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, int ncols_out, uint16_t* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[(kRowsA + kRowsB) * kPitch];
+  const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
+  const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const bool wave_on = n0 + 64 * wave < ncols_out;
+
+  // slot bases without the per-step block offset
+  long long off[kSlots];
+  bool on[kSlots];
+#pragma unroll
+  for (int u = 0; u < kSlots; ++u) {
+    const int row = tid / 8 + 32 * u;
+    if (u < 2) {
+      off[u] = (long long)row * 64 + (tid % 8) * 8;  // inside the compact 64x64 activation block
+      on[u] = true;
+    } else {
+      const int n = n0 + row - kRowsB;
+      on[u] = n < ncols_out;
+      off[u] = (long long)n * ldw + (tid % 8) * 8;
+    }
+  }
+  Stage st;
+  auto fetch = [&](int s) {
+    const int p = rs + s;
+    const long long jcol = (long long)col_idx[p] * 64;
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) {
+      if (u < 2)
+        st.v[u] = *reinterpret_cast<const uint4*>(act + (long long)p * 4096 + off[u]);
+      else
+        st.v[u] = on[u] ? *reinterpret_cast<const uint4*>(W + off[u] + jcol) : make_uint4(0, 0, 0, 0);
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  if (n_i > 0) fetch(0);
+  for (int s = 0; s < n_i; ++s) {
+    store_stage(st, lds);
+    __syncthreads();
+    if (s + 1 < n_i) fetch(s + 1);
+    if (wave_on) mma_step(lds, wave, acc);
+    __syncthreads();
+  }
+  if (!wave_on) return;
+
+  const int tl = lane % 32, nq = (lane / 32) * 4;
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int t = i * 64 + 32 * ti + tl;
+        const int n = n0 + 64 * wave + 32 * ni + 8 * g + nq;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
+        if (bias) {
+          const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
+          v[0] += bf2f(bb.x & 0xFFFFu); v[1] += bf2f(bb.x >> 16);
+          v[2] += bf2f(bb.y & 0xFFFFu); v[3] += bf2f(bb.y >> 16);
+        }
+        uint2 ov;
+        ov.x = pack2bf(v[0], v[1]);
+        ov.y = pack2bf(v[2], v[3]);
+        *reinterpret_cast<uint2*>(out + (long long)t * ncols_out + n) = ov;
+      }
+}
+
+// pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
+// pass 1 (backward): A = dY, W1 = W_down_t [F,d], W2 = W_up_t [d,F], act_out = dZ_act,
+//                    act_gate = H_act, out = dX
+hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_t* A,
+                           const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
+                           const uint16_t* b2, const int* row_ptr, const int* col_idx,
+                           uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
+                           hipStream_t st) {
+  const dim3 g1((Fb + 3) / 4, Tt);
+  if (pass == 0)
+    hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, d,
+                       act_out, (const uint16_t*)nullptr);
+  else
+    hipLaunchKernelGGL(ffn_sdd_bf16<1>, g1, dim3(kThreads), 0, st, A, W1, (const uint16_t*)nullptr,
+                       row_ptr, col_idx, d, act_out, act_gate);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(ffn_dsd_bf16, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, out);
+  return hipGetLastError();
+}
+
+}  // namespace lx

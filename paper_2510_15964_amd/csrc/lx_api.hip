@@ -1,0 +1,247 @@
+// Host side of the C ABI declared in include/lx.h: argument validation,
+// workspace layout and kernel dispatch.  Nothing here allocates device memory
+// or synchronises; every check runs before the first launch so that the error
+// paths can be exercised on a machine without a GPU.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lx.h"
+#include "lx_launch.h"
+
+namespace lx {
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline size_t esize(lx_dtype dt) { return dt == LX_F32 ? 4 : 2; }
+
+static lx_status check_ffn(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                           int32_t blk_n, const lx_blocklist* bl) {
+  if (dt != LX_F32 && dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (T <= 0 || d <= 0 || F <= 0 || tile_t <= 0 || blk_n <= 0) return LX_ERR_INVALID_ARG;
+  if (dt == LX_F32) {
+    if (!((tile_t == 32 && blk_n == 32) || (tile_t == 64 && blk_n == 64))) return LX_ERR_UNSUPPORTED;
+    if (d % 32 != 0) return LX_ERR_UNSUPPORTED;
+  } else {
+    if (!(tile_t == 64 && blk_n == 64)) return LX_ERR_UNSUPPORTED;
+    if (d % 64 != 0) return LX_ERR_UNSUPPORTED;
+  }
+  if (T % tile_t != 0 || F % blk_n != 0) return LX_ERR_UNSUPPORTED;
+  if (!bl || !bl->row_ptr || !bl->col_idx) return LX_ERR_INVALID_ARG;
+  if (bl->rows != T / tile_t || bl->cols != F / blk_n) return LX_ERR_INVALID_ARG;
+  if (bl->nnz_cap < 0 || (int64_t)bl->nnz_cap > (int64_t)bl->rows * bl->cols) return LX_ERR_INVALID_ARG;
+  return LX_OK;
+}
+
+static size_t act_bytes(lx_dtype dt, int32_t tile_t, int32_t blk_n, int32_t nnz_cap) {
+  return round256((size_t)(nnz_cap > 0 ? nnz_cap : 1) * tile_t * blk_n * esize(dt));
+}
+
+}  // namespace lx
+
+using namespace lx;
+
+extern "C" {
+
+const char* lx_status_string(lx_status s) {
+  switch (s) {
+    case LX_OK: return "LX_OK";
+    case LX_ERR_INVALID_ARG: return "LX_ERR_INVALID_ARG";
+    case LX_ERR_UNSUPPORTED: return "LX_ERR_UNSUPPORTED";
+    case LX_ERR_WORKSPACE: return "LX_ERR_WORKSPACE";
+    case LX_ERR_RUNTIME: return "LX_ERR_RUNTIME";
+  }
+  return "LX_ERR_UNKNOWN";
+}
+
+lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
+                          int64_t batch_stride, int64_t row_stride, int64_t col_stride,
+                          int32_t* row_ptr, int32_t* col_idx, int32_t col_idx_cap, void* stream) {
+  if (!mask || !row_ptr || !col_idx) return LX_ERR_INVALID_ARG;
+  if (batch <= 0 || rows <= 0 || cols <= 0 || col_idx_cap <= 0) return LX_ERR_INVALID_ARG;
+  if ((int64_t)batch * rows > (int64_t)1 << 30) return LX_ERR_INVALID_ARG;
+  if (batch_stride < 0 || row_stride < 0 || col_stride < 0) return LX_ERR_INVALID_ARG;
+  hipError_t e = launch_compact(mask, batch, rows, cols, batch_stride, row_stride, col_stride,
+                                row_ptr, col_idx, col_idx_cap, (hipStream_t)stream);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_up,
+                              const void* W_down, void* W_up_t, void* W_down_t, void* stream) {
+  if (dt != LX_F32 && dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (d <= 0 || F <= 0) return LX_ERR_INVALID_ARG;
+  if ((W_up_t && !W_up) || (W_down_t && !W_down)) return LX_ERR_INVALID_ARG;
+  if (W_up_t) {
+    if (launch_transpose((int)esize(dt), W_up, F, d, W_up_t, (hipStream_t)stream) != hipSuccess)
+      return LX_ERR_RUNTIME;
+  }
+  if (W_down_t) {
+    if (launch_transpose((int)esize(dt), W_down, d, F, W_down_t, (hipStream_t)stream) != hipSuccess)
+      return LX_ERR_RUNTIME;
+  }
+  return LX_OK;
+}
+
+size_t lx_sparse_ffn_fwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t F,
+                                         int32_t tile_t, int32_t blk_n, int32_t nnz_cap,
+                                         int32_t have_h_act) {
+  (void)T; (void)d; (void)F;
+  return have_h_act ? 0 : act_bytes(dt, tile_t, blk_n, nnz_cap);
+}
+
+size_t lx_sparse_ffn_bwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t F,
+                                         int32_t tile_t, int32_t blk_n, int32_t nnz_cap,
+                                         int32_t have_packed) {
+  (void)T;
+  size_t b = act_bytes(dt, tile_t, blk_n, nnz_cap);  // dZ_act
+  if (!have_packed) b += 2 * round256((size_t)d * F * esize(dt));
+  return b;
+}
+
+lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                            int32_t blk_n, const void* X, const void* W_up, const void* b_up,
+                            const void* W_down, const void* b_down, const lx_blocklist* bl,
+                            void* Y, void* H_act, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  lx_status s = check_ffn(dt, T, d, F, tile_t, blk_n, bl);
+  if (s != LX_OK) return s;
+  if (!X || !W_up || !W_down || !Y) return LX_ERR_INVALID_ARG;
+  if (!aligned16(X) || !aligned16(W_up) || !aligned16(W_down) || !aligned16(Y) ||
+      !aligned16(H_act) || !aligned16(workspace) || !aligned16(b_up) || !aligned16(b_down))
+    return LX_ERR_INVALID_ARG;
+  void* act = H_act;
+  if (!act) {
+    const size_t need = lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, bl->nnz_cap, 0);
+    if (!workspace || workspace_bytes < need) return LX_ERR_WORKSPACE;
+    act = workspace;
+  }
+  hipError_t e;
+  if (dt == LX_F32)
+    e = launch_ffn_f32(0, tile_t, bl->rows, bl->cols, d, F, (const float*)X, (const float*)W_up,
+                       (const float*)b_up, (const float*)W_down, (const float*)b_down, bl->row_ptr,
+                       bl->col_idx, (float*)act, nullptr, (float*)Y, (hipStream_t)stream);
+  else
+    e = launch_ffn_bf16(0, bl->rows, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
+                        (const uint16_t*)b_up, (const uint16_t*)W_down, (const uint16_t*)b_down,
+                        bl->row_ptr, bl->col_idx, (uint16_t*)act, nullptr, (uint16_t*)Y,
+                        (hipStream_t)stream);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                               int32_t blk_n, const void* dY, const void* H_act,
+                               const void* W_up, const void* W_down, const void* W_up_t,
+                               const void* W_down_t, const lx_blocklist* bl, void* dX,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  lx_status s = check_ffn(dt, T, d, F, tile_t, blk_n, bl);
+  if (s != LX_OK) return s;
+  if (!dY || !H_act || !dX) return LX_ERR_INVALID_ARG;
+  const bool packed = W_up_t && W_down_t;
+  if (!packed && (W_up_t || W_down_t)) return LX_ERR_INVALID_ARG;  // both or neither
+  if (!packed && (!W_up || !W_down)) return LX_ERR_INVALID_ARG;
+  if (!aligned16(dY) || !aligned16(H_act) || !aligned16(dX) || !aligned16(W_up) ||
+      !aligned16(W_down) || !aligned16(W_up_t) || !aligned16(W_down_t) || !aligned16(workspace))
+    return LX_ERR_INVALID_ARG;
+  const size_t need =
+      lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, bl->nnz_cap, packed ? 1 : 0);
+  if (!workspace || workspace_bytes < need) return LX_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  void* dz = ws;
+  ws += act_bytes(dt, tile_t, blk_n, bl->nnz_cap);
+  hipStream_t st = (hipStream_t)stream;
+  if (!packed) {
+    void* wut = ws;
+    ws += round256((size_t)d * F * esize(dt));
+    void* wdt = ws;
+    if (launch_transpose((int)esize(dt), W_up, F, d, wut, st) != hipSuccess) return LX_ERR_RUNTIME;
+    if (launch_transpose((int)esize(dt), W_down, d, F, wdt, st) != hipSuccess) return LX_ERR_RUNTIME;
+    W_up_t = wut;
+    W_down_t = wdt;
+  }
+  hipError_t e;
+  if (dt == LX_F32)
+    e = launch_ffn_f32(1, tile_t, bl->rows, bl->cols, d, F, (const float*)dY,
+                       (const float*)W_down_t, nullptr, (const float*)W_up_t, nullptr, bl->row_ptr,
+                       bl->col_idx, (float*)dz, (const float*)H_act, (float*)dX, st);
+  else
+    e = launch_ffn_bf16(1, bl->rows, bl->cols, d, F, (const uint16_t*)dY,
+                        (const uint16_t*)W_down_t, nullptr, (const uint16_t*)W_up_t, nullptr,
+                        bl->row_ptr, bl->col_idx, (uint16_t*)dz, (const uint16_t*)H_act,
+                        (uint16_t*)dX, st);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, int32_t S,
+                                          int32_t D) {
+  (void)dt; (void)D;
+  if (B <= 0 || Hh <= 0 || S <= 0) return 0;
+  return round256((size_t)B * Hh * S * sizeof(float));
+}
+
+static lx_status check_attn(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                            const int64_t strides[3], const lx_blocklist* bl, int32_t mask_batch) {
+  if (dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (B <= 0 || Hh <= 0 || S <= 0 || D <= 0) return LX_ERR_INVALID_ARG;
+  if (D != 64 && D != 128) return LX_ERR_UNSUPPORTED;
+  if (S % 64 != 0) return LX_ERR_UNSUPPORTED;
+  if (B > 65535 || Hh > 65535) return LX_ERR_UNSUPPORTED;
+  if (!strides) return LX_ERR_INVALID_ARG;
+  for (int i = 0; i < 3; ++i)
+    if (strides[i] < 0 || strides[i] % 8 != 0) return LX_ERR_INVALID_ARG;
+  if (strides[2] < D) return LX_ERR_INVALID_ARG;
+  if (mask_batch != 1 && mask_batch != B) return LX_ERR_INVALID_ARG;
+  if (!bl || !bl->row_ptr || !bl->col_idx) return LX_ERR_INVALID_ARG;
+  if ((int64_t)bl->rows != (int64_t)mask_batch * Hh * (S / 64) || bl->cols != S / 64)
+    return LX_ERR_INVALID_ARG;
+  return LX_OK;
+}
+
+lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                             float scale, int32_t causal, const void* Q, const void* K,
+                             const void* V, const int64_t strides_bhs[3],
+                             const lx_blocklist* bl, int32_t mask_batch,
+                             const uint8_t* head_active, void* O, float* LSE, void* stream) {
+  lx_status s = check_attn(dt, B, Hh, S, D, strides_bhs, bl, mask_batch);
+  if (s != LX_OK) return s;
+  if (!Q || !K || !V || !O || !LSE) return LX_ERR_INVALID_ARG;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return LX_ERR_INVALID_ARG;
+  AttnArgs a = {};
+  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
+  a.Out = (uint16_t*)O; a.LSE = LSE;
+  a.sb = strides_bhs[0]; a.sh = strides_bhs[1]; a.ss = strides_bhs[2];
+  a.row_ptr = bl->row_ptr; a.col_idx = bl->col_idx;
+  a.head_active = head_active;
+  a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
+  return launch_attn_fwd_bf16(D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                                float scale, int32_t causal, const void* Q, const void* K,
+                                const void* V, const void* O, const float* LSE, const void* dO,
+                                const int64_t strides_bhs[3], const lx_blocklist* bl_rows,
+                                const lx_blocklist* bl_cols, int32_t mask_batch,
+                                const uint8_t* head_active, void* dQ, void* dK, void* dV,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  lx_status s = check_attn(dt, B, Hh, S, D, strides_bhs, bl_rows, mask_batch);
+  if (s != LX_OK) return s;
+  s = check_attn(dt, B, Hh, S, D, strides_bhs, bl_cols, mask_batch);
+  if (s != LX_OK) return s;
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return LX_ERR_INVALID_ARG;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return LX_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < lx_sparse_attn_bwd_workspace_bytes(dt, B, Hh, S, D))
+    return LX_ERR_WORKSPACE;
+  AttnArgs a = {};
+  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
+  a.O = (const uint16_t*)O; a.dO = (const uint16_t*)dO; a.LSEin = LSE;
+  a.dQ = (uint16_t*)dQ; a.dK = (uint16_t*)dK; a.dV = (uint16_t*)dV;
+  a.Delta = (float*)workspace;
+  a.sb = strides_bhs[0]; a.sh = strides_bhs[1]; a.ss = strides_bhs[2];
+  a.row_ptr = bl_rows->row_ptr; a.col_idx = bl_rows->col_idx;
+  a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx;
+  a.head_active = head_active;
+  a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
+  return launch_attn_bwd_bf16(D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+}  // extern "C"

@@ -1,0 +1,35 @@
+// Device-side helpers shared by the HIP kernels of this library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lx {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// float -> bfloat16 bits, round to nearest even (inputs are finite).
+__device__ __forceinline__ uint32_t f2bf(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+  return f2bf(lo) | (f2bf(hi) << 16);
+}
+__device__ __forceinline__ float bf2f(uint32_t bits16) {
+  return __builtin_bit_cast(float, bits16 << 16);
+}
+
+// 32x32x16 bf16 MFMA.  Operand a: lane l holds row (l % 32), k = 8*(l/32)..+7.
+// Operand b: lane l holds column (l % 32), same k.  Accumulator register v of
+// lane l is C[8*(v/4) + 4*(l/32) + v%4][l % 32].
+__device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+}  // namespace lx

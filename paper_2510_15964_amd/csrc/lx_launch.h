@@ -1,0 +1,36 @@
+// Internal launch interface between the C-ABI host code and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lx {
+
+struct AttnArgs {
+  const uint16_t *Q, *K, *V, *O, *dO;
+  uint16_t *Out, *dQ, *dK, *dV;
+  float *LSE, *Delta;
+  const float* LSEin;
+  long long sb, sh, ss;
+  const int *row_ptr, *col_idx;
+  const int *crow_ptr, *ccol_idx;
+  const uint8_t* head_active;
+  int Hh, S, mask_batch, causal;
+  float scale;
+};
+
+hipError_t launch_compact(const uint8_t*, int, int, int, long long, long long, long long, int*, int*,
+                          int, hipStream_t);
+hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, const float* A,
+                          const float* W1, const float* b1, const float* W2, const float* b2,
+                          const int* row_ptr, const int* col_idx, float* act_out,
+                          const float* act_gate, float* out, hipStream_t st);
+hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_t* A,
+                           const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
+                           const uint16_t* b2, const int* row_ptr, const int* col_idx,
+                           uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
+                           hipStream_t st);
+hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);
+hipError_t launch_attn_fwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_bwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
+
+}  // namespace lx

@@ -1,0 +1,200 @@
+"""Thin ctypes binding of the C-ABI library declared in include/lx.h.
+
+Only argument marshalling happens here: torch tensors supply device pointers
+and the current HIP stream; every step of the operators runs inside the
+library's kernels.  Importing this module fails loudly when the library has
+not been built (run `python paper_2510_15964_amd/build.py`); there is no CPU
+or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblx_sparse.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build the HIP library first "
+        "(python paper_2510_15964_amd/build.py). There is no fallback path.")
+
+_lib = C.CDLL(LIB_PATH)
+
+LX_OK, LX_ERR_INVALID_ARG, LX_ERR_UNSUPPORTED, LX_ERR_WORKSPACE, LX_ERR_RUNTIME = range(5)
+LX_F32, LX_BF16 = 0, 1
+
+EXPORTS = (
+    "lx_status_string", "lx_mask_compact", "lx_ffn_pack_weights",
+    "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
+    "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
+    "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx",
+)
+
+
+class lx_blocklist(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("cols", C.c_int32), ("row_ptr", C.c_void_p),
+                ("col_idx", C.c_void_p), ("nnz_cap", C.c_int32)]
+
+
+_i32, _i64, _vp, _sz, _f = C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_float
+_blp = C.POINTER(lx_blocklist)
+_lib.lx_status_string.restype = C.c_char_p
+_lib.lx_status_string.argtypes = [C.c_int]
+_lib.lx_mask_compact.argtypes = [_vp, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp]
+_lib.lx_ffn_pack_weights.argtypes = [C.c_int, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+for _n in ("lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes"):
+    getattr(_lib, _n).restype = _sz
+    getattr(_lib, _n).argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _i32, _i32]
+_lib.lx_sparse_attn_bwd_workspace_bytes.restype = _sz
+_lib.lx_sparse_attn_bwd_workspace_bytes.argtypes = [C.c_int, _i32, _i32, _i32, _i32]
+_lib.lx_sparse_ffn_fwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
+                                   _blp, _vp, _vp, _vp, _sz, _vp]
+_lib.lx_sparse_ffn_bwd_dx.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp,
+                                      _vp, _vp, _blp, _vp, _vp, _sz, _vp]
+_lib.lx_sparse_attn_fwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32, _vp, _vp, _vp,
+                                    C.POINTER(_i64), _blp, _i32, _vp, _vp, _vp, _vp]
+_lib.lx_sparse_attn_bwd_dx.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32, _vp, _vp, _vp,
+                                       _vp, _vp, _vp, C.POINTER(_i64), _blp, _blp, _i32, _vp, _vp,
+                                       _vp, _vp, _vp, _sz, _vp]
+
+
+class LxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_lib.lx_status_string(status).decode()}")
+
+
+def status_string(status: int) -> str:
+    return _lib.lx_status_string(status).decode()
+
+
+def _check(status: int, where: str):
+    if status != LX_OK:
+        raise LxError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LX_F32
+    if t.dtype == torch.bfloat16:
+        return LX_BF16
+    raise LxError(LX_ERR_UNSUPPORTED, f"dtype {t.dtype}")
+
+
+class BlockList:
+    """Device-resident row-compressed active-block list plus its host header."""
+
+    def __init__(self, rows: int, cols: int, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                 nnz_cap: int):
+        self.rows, self.cols, self.nnz_cap = rows, cols, nnz_cap
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.c = lx_blocklist(rows, cols, row_ptr.data_ptr(), col_idx.data_ptr(), nnz_cap)
+
+
+def lx_mask_compact(mask: torch.Tensor, transpose: bool = False, nnz_cap: int | None = None,
+                    out: BlockList | None = None) -> BlockList:
+    """mask: uint8 device tensor [..., R, C]; leading dims are flattened into
+    the list's rows.  transpose=True builds the column-compressed list."""
+    assert mask.dtype == torch.uint8 and mask.is_cuda and mask.is_contiguous() and mask.dim() >= 2
+    R, Cc = mask.shape[-2], mask.shape[-1]
+    batch = mask.numel() // (R * Cc)
+    if transpose:
+        rows, cols, rs, cs = Cc, R, 1, Cc
+    else:
+        rows, cols, rs, cs = R, Cc, Cc, 1
+    cap = batch * rows * cols if nnz_cap is None else nnz_cap
+    if out is None:
+        row_ptr = torch.empty(batch * rows + 1, dtype=torch.int32, device=mask.device)
+        col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device=mask.device)
+        out = BlockList(batch * rows, cols, row_ptr, col_idx, cap)
+    _check(_lib.lx_mask_compact(_ptr(mask), batch, rows, cols, R * Cc, rs, cs, _ptr(out.row_ptr),
+                                _ptr(out.col_idx), max(cap, 1), _stream()), "lx_mask_compact")
+    return out
+
+
+def lx_ffn_pack_weights(W_up: torch.Tensor, W_down: torch.Tensor):
+    F, d = W_up.shape
+    W_up_t = torch.empty((d, F), dtype=W_up.dtype, device=W_up.device)
+    W_down_t = torch.empty((F, d), dtype=W_up.dtype, device=W_up.device)
+    _check(_lib.lx_ffn_pack_weights(_dt(W_up), d, F, _ptr(W_up), _ptr(W_down), _ptr(W_up_t),
+                                    _ptr(W_down_t), _stream()), "lx_ffn_pack_weights")
+    return W_up_t, W_down_t
+
+
+def lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_h_act) -> int:
+    return _lib.lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_h_act)
+
+
+def lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed) -> int:
+    return _lib.lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed)
+
+
+def lx_sparse_attn_bwd_workspace_bytes(dt, B, Hh, S, D) -> int:
+    return _lib.lx_sparse_attn_bwd_workspace_bytes(dt, B, Hh, S, D)
+
+
+def lx_sparse_ffn_fwd(X, W_up, W_down, bl: BlockList, tile_t: int, blk_n: int, Y, H_act,
+                      b_up=None, b_down=None, workspace=None):
+    T, d = X.shape
+    F = W_up.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.lx_sparse_ffn_fwd(_dt(X), T, d, F, tile_t, blk_n, _ptr(X), _ptr(W_up), _ptr(b_up),
+                                  _ptr(W_down), _ptr(b_down), C.byref(bl.c), _ptr(Y), _ptr(H_act),
+                                  _ptr(workspace), ws_bytes, _stream()), "lx_sparse_ffn_fwd")
+    return Y
+
+
+def lx_sparse_ffn_bwd_dx(dY, H_act, W_up, W_down, bl: BlockList, tile_t: int, blk_n: int, dX,
+                         workspace, W_up_t=None, W_down_t=None):
+    T, d = dY.shape
+    F = W_up.shape[0] if W_up is not None else W_down_t.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.lx_sparse_ffn_bwd_dx(_dt(dY), T, d, F, tile_t, blk_n, _ptr(dY), _ptr(H_act),
+                                     _ptr(W_up), _ptr(W_down), _ptr(W_up_t), _ptr(W_down_t),
+                                     C.byref(bl.c), _ptr(dX), _ptr(workspace), ws_bytes, _stream()),
+           "lx_sparse_ffn_bwd_dx")
+    return dX
+
+
+def _strides(t: torch.Tensor):
+    assert t.dim() == 4 and t.stride(3) == 1
+    return (_i64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
+def lx_sparse_attn_fwd(Q, K, V, bl: BlockList, scale: float, causal: bool, O, LSE,
+                       mask_batch: int = 1, head_active=None):
+    B, Hh, S, D = Q.shape
+    for t in (K, V, O):
+        assert t.stride() == Q.stride() and t.shape == Q.shape
+    _check(_lib.lx_sparse_attn_fwd(_dt(Q), B, Hh, S, D, scale, int(causal), _ptr(Q), _ptr(K),
+                                   _ptr(V), _strides(Q), C.byref(bl.c), mask_batch,
+                                   _ptr(head_active), _ptr(O), _ptr(LSE), _stream()),
+           "lx_sparse_attn_fwd")
+    return O, LSE
+
+
+def lx_sparse_attn_bwd_dx(Q, K, V, O, LSE, dO, bl_rows: BlockList, bl_cols: BlockList,
+                          scale: float, causal: bool, dQ, dK, dV, workspace, mask_batch: int = 1,
+                          head_active=None):
+    B, Hh, S, D = Q.shape
+    for t in (K, V, O, dO, dQ, dK, dV):
+        assert t.stride() == Q.stride() and t.shape == Q.shape
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.lx_sparse_attn_bwd_dx(_dt(Q), B, Hh, S, D, scale, int(causal), _ptr(Q), _ptr(K),
+                                      _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO), _strides(Q),
+                                      C.byref(bl_rows.c), C.byref(bl_cols.c), mask_batch,
+                                      _ptr(head_active), _ptr(dQ), _ptr(dK), _ptr(dV),
+                                      _ptr(workspace), ws_bytes, _stream()),
+           "lx_sparse_attn_bwd_dx")
+    return dQ, dK, dV

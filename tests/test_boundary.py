@@ -1,0 +1,125 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol that include/lx.h declares, and rejects bad arguments before any
+launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lxmod():
+    lib = os.path.join(ROOT, "paper_2510_15964_amd", "liblx_sparse.so")
+    if not os.path.exists(lib):
+        from paper_2510_15964_amd import build
+        build.build()
+    from paper_2510_15964_amd import lx
+    return lx
+
+
+def test_exports_every_declared_symbol(lxmod):
+    hdr = open(os.path.join(ROOT, "include", "lx.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(lx_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(lxmod.EXPORTS)
+    for name in declared:
+        assert hasattr(lxmod._lib, name), name
+
+
+def test_status_strings(lxmod):
+    assert [lxmod.status_string(i) for i in range(5)] == [
+        "LX_OK", "LX_ERR_INVALID_ARG", "LX_ERR_UNSUPPORTED", "LX_ERR_WORKSPACE", "LX_ERR_RUNTIME"]
+
+
+FAKE = C.c_void_p(0x1000)      # non-null, 16-byte aligned, never dereferenced on these paths
+
+
+def _bl(lxmod, rows, cols, cap=None):
+    return lxmod.lx_blocklist(rows, cols, 0x1000, 0x1000, rows * cols if cap is None else cap)
+
+
+def test_compact_rejects_bad_arguments(lxmod):
+    f = lxmod._lib.lx_mask_compact
+    assert f(None, 1, 4, 4, 16, 4, 1, FAKE, FAKE, 16, None) == lxmod.LX_ERR_INVALID_ARG
+    assert f(FAKE, 1, 0, 4, 16, 4, 1, FAKE, FAKE, 16, None) == lxmod.LX_ERR_INVALID_ARG
+    assert f(FAKE, 1, 4, 4, 16, 4, 1, FAKE, FAKE, 0, None) == lxmod.LX_ERR_INVALID_ARG
+    assert f(FAKE, 1, 4, 4, 16, -4, 1, FAKE, FAKE, 16, None) == lxmod.LX_ERR_INVALID_ARG
+
+
+def _ffn_fwd(lxmod, dt, T, d, F, tt, bn, bl, X=FAKE, ws=None, ws_bytes=0, H=FAKE):
+    return lxmod._lib.lx_sparse_ffn_fwd(dt, T, d, F, tt, bn, X, FAKE, None, FAKE, None,
+                                        C.byref(bl) if bl is not None else None, FAKE, H, ws,
+                                        ws_bytes, None)
+
+
+def test_ffn_fwd_validation(lxmod):
+    L = lxmod
+    ok_bl = _bl(L, 8, 16)
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, ok_bl, X=None) == L.LX_ERR_INVALID_ARG
+    assert _ffn_fwd(L, L.LX_BF16, 0, 128, 1024, 64, 64, ok_bl) == L.LX_ERR_INVALID_ARG
+    assert _ffn_fwd(L, 7, 512, 128, 1024, 64, 64, ok_bl) == L.LX_ERR_UNSUPPORTED
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 32, 32, _bl(L, 16, 32)) == L.LX_ERR_UNSUPPORTED
+    assert _ffn_fwd(L, L.LX_BF16, 512, 100, 1024, 64, 64, ok_bl) == L.LX_ERR_UNSUPPORTED
+    assert _ffn_fwd(L, L.LX_BF16, 500, 128, 1024, 64, 64, ok_bl) == L.LX_ERR_UNSUPPORTED
+    assert _ffn_fwd(L, L.LX_F32, 512, 128, 1024, 48, 48, ok_bl) == L.LX_ERR_UNSUPPORTED
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, None) == L.LX_ERR_INVALID_ARG
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, _bl(L, 8, 15)) == L.LX_ERR_INVALID_ARG
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, _bl(L, 8, 16, 999)) == L.LX_ERR_INVALID_ARG
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, ok_bl,
+                    X=C.c_void_p(0x1004)) == L.LX_ERR_INVALID_ARG
+    # no H_act buffer and no / too small workspace
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, ok_bl, H=None) == L.LX_ERR_WORKSPACE
+    need = L.lx_sparse_ffn_fwd_workspace_bytes(L.LX_BF16, 512, 128, 1024, 64, 64, 128, 0)
+    assert need >= 128 * 64 * 64 * 2
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, ok_bl, H=None, ws=FAKE,
+                    ws_bytes=need - 1) == L.LX_ERR_WORKSPACE
+    assert L.lx_sparse_ffn_fwd_workspace_bytes(L.LX_BF16, 512, 128, 1024, 64, 64, 128, 1) == 0
+
+
+def test_ffn_bwd_validation(lxmod):
+    L = lxmod
+    bl = _bl(L, 8, 16)
+    f = L._lib.lx_sparse_ffn_bwd_dx
+    args = lambda **k: [k.get("dt", L.LX_BF16), 512, 128, 1024, 64, 64, k.get("dY", FAKE), FAKE,
+                        k.get("Wu", FAKE), FAKE, k.get("Wut", FAKE), k.get("Wdt", FAKE),
+                        C.byref(bl), FAKE, k.get("ws", FAKE), k.get("wsb", 1 << 30), None]
+    assert f(*args(dY=None)) == L.LX_ERR_INVALID_ARG
+    assert f(*args(Wut=None)) == L.LX_ERR_INVALID_ARG          # only one packed pointer
+    assert f(*args(wsb=16)) == L.LX_ERR_WORKSPACE
+    assert f(*args(ws=None)) == L.LX_ERR_WORKSPACE
+    packed = L.lx_sparse_ffn_bwd_workspace_bytes(L.LX_BF16, 512, 128, 1024, 64, 64, 128, 1)
+    raw = L.lx_sparse_ffn_bwd_workspace_bytes(L.LX_BF16, 512, 128, 1024, 64, 64, 128, 0)
+    assert raw >= packed + 2 * 128 * 1024 * 2
+    assert f(*args(Wut=None, Wdt=None, wsb=packed)) == L.LX_ERR_WORKSPACE
+
+
+def test_attn_validation(lxmod):
+    L = lxmod
+    f = L._lib.lx_sparse_attn_fwd
+    st = (C.c_int64 * 3)(32 * 256 * 64, 256 * 64, 64)
+    bl = _bl(L, 32 * 4, 4)
+
+    def call(dt=L.LX_BF16, B=2, Hh=32, S=256, D=64, strides=st, blist=bl, mb=1, Q=FAKE):
+        return f(dt, B, Hh, S, D, 0.125, 1, Q, FAKE, FAKE, strides, C.byref(blist), mb, None, FAKE,
+                 FAKE, None)
+
+    assert call(dt=L.LX_F32) == L.LX_ERR_UNSUPPORTED
+    assert call(D=96) == L.LX_ERR_UNSUPPORTED
+    assert call(S=250) == L.LX_ERR_UNSUPPORTED
+    assert call(Q=None) == L.LX_ERR_INVALID_ARG
+    assert call(mb=3) == L.LX_ERR_INVALID_ARG
+    assert call(blist=_bl(L, 32 * 4 - 1, 4)) == L.LX_ERR_INVALID_ARG
+    assert call(strides=(C.c_int64 * 3)(32 * 256 * 64, 256 * 64, 60)) == L.LX_ERR_INVALID_ARG
+    assert call(strides=None) == L.LX_ERR_INVALID_ARG
+    g = L._lib.lx_sparse_attn_bwd_dx
+    need = L.lx_sparse_attn_bwd_workspace_bytes(L.LX_BF16, 2, 32, 256, 64)
+    assert need >= 2 * 32 * 256 * 4
+    r = g(L.LX_BF16, 2, 32, 256, 64, 0.125, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, st, C.byref(bl),
+          C.byref(bl), 1, None, FAKE, FAKE, FAKE, FAKE, need - 1, None)
+    assert r == L.LX_ERR_WORKSPACE
+    r = g(L.LX_BF16, 2, 32, 256, 64, 0.125, 1, FAKE, FAKE, FAKE, FAKE, None, FAKE, st, C.byref(bl),
+          C.byref(bl), 1, None, FAKE, FAKE, FAKE, FAKE, need, None)
+    assert r == L.LX_ERR_INVALID_ARG

@@ -1,0 +1,192 @@
+"""GPU parity: sparse FFN forward and input gradient against the CPU oracle,
+called through the C ABI (ctypes binding)."""
+import numpy as np
+import pytest
+
+from paper_2510_15964_amd import inputs
+from util import TOL, compact_blocks, dev, host, rel_err, round_to
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lx():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2510_15964_amd import lx
+    return lx
+
+
+def run_gpu(lx, c, mask=None, packed=True, bias=False, h_from=None):
+    """Returns dict of host arrays: Y, H_act (compact), dX, and the list."""
+    import torch
+    mask = c["mask"] if mask is None else mask
+    dt, tt, bn = c["dtype"], c["tile_t"], c["blk_n"]
+    T, d, F = c["T"], c["d"], c["F"]
+    X, Wu, Wd, dY = (dev(c[k], dt) for k in ("X", "W_up", "W_down", "dY"))
+    bu = dev(c["b_up"], dt) if bias else None
+    bd = dev(c["b_down"], dt) if bias else None
+    m = torch.from_numpy(np.ascontiguousarray(mask)).cuda()
+    bl = lx.lx_mask_compact(m)
+    cap = bl.nnz_cap
+    tdt = X.dtype
+    guard = 4096
+    H_act = torch.full((cap * tt * bn + guard,), float("nan"), dtype=tdt, device="cuda")
+    Y = torch.full((T, d), float("nan"), dtype=tdt, device="cuda")
+    lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, tt, bn, Y, H_act, b_up=bu, b_down=bd)
+    nnz = int(bl.row_ptr[-1].item())
+    out = dict(Y=host(Y), H_act=host(H_act[:nnz * tt * bn]).reshape(nnz, tt, bn), nnz=nnz)
+    assert torch.isnan(H_act[cap * tt * bn:]).all(), "wrote past the H_act buffer"
+    if h_from is not None:                      # backward consumes a supplied activation buffer
+        H_in = torch.zeros_like(H_act)
+        H_in[:nnz * tt * bn] = dev(h_from.reshape(-1), dt)
+    else:
+        H_in = H_act
+    dtc = lx.LX_F32 if dt == "f32" else lx.LX_BF16
+    ws_bytes = lx.lx_sparse_ffn_bwd_workspace_bytes(dtc, T, d, F, tt, bn, cap, 1 if packed else 0)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    dX = torch.full((T, d), float("nan"), dtype=tdt, device="cuda")
+    if packed:
+        Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+        assert torch.equal(Wut, Wu.t().contiguous()) and torch.equal(Wdt, Wd.t().contiguous())
+        lx.lx_sparse_ffn_bwd_dx(dY, H_in, Wu, Wd, bl, tt, bn, dX, ws, W_up_t=Wut, W_down_t=Wdt)
+    else:
+        lx.lx_sparse_ffn_bwd_dx(dY, H_in, Wu, Wd, bl, tt, bn, dX, ws)
+    torch.cuda.synchronize()
+    out["dX"] = host(dX)
+    return out
+
+
+def run_oracle(oracle, c, mask=None, bias=False):
+    mask = c["mask"] if mask is None else mask
+    dt, tt, bn = c["dtype"], c["tile_t"], c["blk_n"]
+    H, Y = oracle.ffn_fwd(c["X"], c["W_up"], c["W_down"], mask, tt, bn,
+                          c["b_up"] if bias else None, c["b_down"] if bias else None)
+    # the backward pass takes the stored activations as input: both sides use the
+    # oracle's H rounded to the run dtype, so the ReLU gate is decided once
+    Hq = round_to(H, dt)
+    dZ, dX = oracle.ffn_bwd_dx(c["dY"], c["W_up"], c["W_down"], mask, Hq > 0, tt, bn)
+    return dict(H=H, Y=Y, dX=dX, Hq_act=compact_blocks(Hq, mask, tt, bn),
+                H_act=compact_blocks(H, mask, tt, bn))
+
+
+def compare(lx, oracle, c, mask=None, packed=True, bias=False):
+    ref = run_oracle(oracle, c, mask, bias)
+    got = run_gpu(lx, c, mask, packed, bias, h_from=ref["Hq_act"])
+    tol = TOL[c["dtype"]]
+    assert got["nnz"] == int(np.count_nonzero(c["mask"] if mask is None else mask))
+    errs = dict(H=rel_err(got["H_act"], ref["H_act"]), Y=rel_err(got["Y"], ref["Y"]),
+                dX=rel_err(got["dX"], ref["dX"]))
+    print(f"[{c['dtype']} T={c['T']} d={c['d']} F={c['F']} nnz={got['nnz']}] errors {errs}", flush=True)
+    for k, e in errs.items():
+        assert e <= tol, (k, e, tol)
+    assert np.isfinite(got["Y"]).all() and np.isfinite(got["dX"]).all()
+    return got, ref
+
+
+def test_config1_fp32_full(lx, oracle):
+    """configs[0]: OPT-125m-shaped FFN, fp32, 32x32 blocks, 30 % density."""
+    compare(lx, oracle, inputs.config1_ffn())
+
+
+@pytest.mark.parametrize("tile,T,d,F,density,seed", [
+    (32, 96, 64, 160, 0.5, 1), (64, 192, 96, 320, 0.4, 2), (64, 128, 32, 64, 1.0, 3),
+    (32, 64, 32, 96, 0.0, 4),
+])
+def test_fp32_small_shapes(lx, oracle, tile, T, d, F, density, seed):
+    c = inputs.ffn_bernoulli(T, d, F, tile, tile, density, seed, dtype="f32", w_std=0.1)
+    compare(lx, oracle, c)
+    compare(lx, oracle, c, packed=False)
+
+
+@pytest.mark.parametrize("T,d,F,density,seed", [
+    (256, 256, 1024, 0.3, 11),      # several tiles, ragged per-row counts
+    (192, 192, 704, 0.45, 12),      # d not a multiple of 256, 11 neuron blocks
+    (128, 64, 320, 1.0, 13),        # dense
+    (128, 128, 256, 0.0, 14),       # empty mask
+    (64, 576, 64, 1.0, 15),         # single block
+])
+def test_bf16_small_shapes(lx, oracle, T, d, F, density, seed):
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, density, seed, dtype="bf16", w_std=0.05)
+    compare(lx, oracle, c)
+    compare(lx, oracle, c, packed=False)
+
+
+@pytest.mark.parametrize("dtype,tile", [("f32", 32), ("bf16", 64)])
+def test_bias_and_rows_without_blocks(lx, oracle, dtype, tile):
+    c = inputs.ffn_bernoulli(4 * tile, 128, 8 * tile, tile, tile, 0.4, 21, dtype=dtype, w_std=0.1)
+    rng = np.random.default_rng(3)
+    c["b_up"] = round_to(rng.standard_normal(c["F"]) * 0.1, dtype)
+    c["b_down"] = round_to(rng.standard_normal(c["d"]), dtype)
+    c["mask"][1, :] = 0                       # a token tile with no active block
+    c["mask"][2, :] = [1, 0, 0, 0, 0, 1, 1, 1]
+    got, ref = compare(lx, oracle, c, bias=True)
+    sl = slice(tile, 2 * tile)
+    assert np.array_equal(got["Y"][sl], np.broadcast_to(c["b_down"], (tile, c["d"])))
+    assert not got["dX"][sl].any()
+    got, ref = compare(lx, oracle, c, bias=False)
+    assert not got["Y"][sl].any()
+
+
+def test_inactive_weight_blocks_are_never_read(lx, oracle):
+    """Sec. II-D on the GPU: NaN in every weight block that no token tile uses."""
+    c = inputs.ffn_bernoulli(256, 128, 1024, 64, 64, 0.3, 31, dtype="bf16", w_std=0.05)
+    c["mask"][:, [2, 5, 11]] = 0
+    ref = run_gpu(lx, c)
+    c2 = dict(c, W_up=c["W_up"].copy(), W_down=c["W_down"].copy())
+    for j in (2, 5, 11):
+        c2["W_up"][j * 64:(j + 1) * 64] = np.nan
+        c2["W_down"][:, j * 64:(j + 1) * 64] = np.nan
+    for packed in (True, False):
+        got = run_gpu(lx, c2, packed=packed)
+        for k in ("Y", "H_act", "dX"):
+            assert np.array_equal(got[k], ref[k]), k
+
+
+def test_forward_backward_chain_on_device(lx, oracle):
+    """fwd -> bwd with the device's own H_act (the normal call sequence)."""
+    c = inputs.ffn_bernoulli(256, 128, 512, 64, 64, 0.5, 41, dtype="bf16", w_std=0.05)
+    got = run_gpu(lx, c)
+    ref = run_oracle(oracle, c)
+    flips = int(np.count_nonzero((got["H_act"] > 0) != (ref["Hq_act"] > 0)))
+    print("gate flips between device and oracle activations:", flips, flush=True)
+    if flips == 0:
+        assert rel_err(got["dX"], ref["dX"]) <= TOL["bf16"]
+
+
+def test_planted_support_mask_equals_dense_on_device(lx, oracle):
+    """Mask = true ReLU support: the sparse result must equal the dense one."""
+    c = inputs.ffn_planted_support(512, 256, 2048, 64, 64, 0.5, 4.0, seed=51)
+    sparse = run_gpu(lx, c)
+    dense = run_gpu(lx, c, mask=np.ones_like(c["mask"]))
+    # same products, only all-zero blocks are skipped; accumulation order over
+    # blocks is ascending in both, so Y agrees to rounding of skipped zeros: exactly
+    assert np.array_equal(sparse["Y"], dense["Y"])
+    assert np.array_equal(sparse["dX"], dense["dX"])
+    ref = run_oracle(oracle, c)
+    assert rel_err(sparse["Y"], ref["Y"]) <= TOL["bf16"]
+
+
+def test_config2_bf16_full_size_sampled_tiles(lx, oracle):
+    """configs[1] at full size in the benchmark's launch configuration; the
+    oracle checks sampled token tiles (tiles are independent)."""
+    c = inputs.config2_ffn()
+    got = run_gpu(lx, c)
+    assert got["nnz"] == int(c["mask"].sum())
+    rp = np.concatenate([[0], np.cumsum(c["mask"].sum(1))])
+    for i in (0, 17, 63):
+        sl = slice(i * 64, (i + 1) * 64)
+        sub = dict(c, X=c["X"][sl], dY=c["dY"][sl], mask=c["mask"][i:i + 1], T=64)
+        ref = run_oracle(oracle, sub)
+        Hg = got["H_act"][rp[i]:rp[i + 1]]
+        # backward of the sampled tile with the oracle's activations
+        sub_got = run_gpu(lx, sub, h_from=ref["Hq_act"])
+        errs = (rel_err(Hg, ref["H_act"]), rel_err(got["Y"][sl], ref["Y"]),
+                rel_err(sub_got["dX"], ref["dX"]))
+        print(f"config2 tile {i}: n_active={int(c['mask'][i].sum())} errors {errs}", flush=True)
+        assert max(errs) <= TOL["bf16"]
+        # full-size launch and single-tile launch agree bit for bit on this tile
+        assert np.array_equal(sub_got["Y"], got["Y"][sl])
+    # tiles with no active block are exactly zero
+    for i in np.nonzero(c["mask"].sum(1) == 0)[0]:
+        assert not got["Y"][i * 64:(i + 1) * 64].any()

@@ -1,0 +1,60 @@
+"""Shared helpers for the parity tests (no operator arithmetic)."""
+from __future__ import annotations
+
+import numpy as np
+
+# Tolerances (max error relative to max(|ref|, rms(ref)), see rel_err):
+#   fp32: 1e-5   bf16: 2e-2
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def rel_err(got, ref) -> float:
+    """max_i |g_i - r_i| / max(|r_i|, rms(r)).  Plain element-wise relative
+    error is undefined at the many exact zeros of masked outputs, so small
+    elements are measured against the tensor's rms."""
+    g = np.asarray(got, dtype=np.float64)
+    r = np.asarray(ref, dtype=np.float64)
+    assert g.shape == r.shape, (g.shape, r.shape)
+    if r.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(r * r)))
+    if rms == 0.0:
+        return float(np.max(np.abs(g)))       # reference is all zero: must match exactly
+    return float(np.max(np.abs(g - r) / np.maximum(np.abs(r), rms)))
+
+
+def torch_dtype(name):
+    import torch
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+
+
+def dev(a, dtype="f32"):
+    """numpy float32 (already representable in `dtype`) -> device tensor."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch_dtype(dtype)).contiguous()
+
+
+def host(t):
+    return t.detach().float().cpu().numpy()
+
+
+def round_to(a, dtype):
+    """Round an fp64/fp32 array to the run dtype, returned as float32."""
+    from paper_2510_15964_amd.inputs import bf16_round
+    a32 = np.asarray(a, dtype=np.float32)
+    return bf16_round(a32) if dtype == "bf16" else a32
+
+
+def compact_blocks(dense, mask, tile_t, blk_n):
+    """Dense [T,F] -> compact [nnz, tile_t, blk_n] in row-major list order."""
+    Tt, Fb = mask.shape
+    v = dense.reshape(Tt, tile_t, Fb, blk_n).transpose(0, 2, 1, 3)
+    return np.ascontiguousarray(v[mask.astype(bool)])
+
+
+def expand_blocks(compact, mask, tile_t, blk_n, fill=0.0):
+    Tt, Fb = mask.shape
+    out = np.full((Tt, Fb, tile_t, blk_n), fill, dtype=compact.dtype)
+    out[mask.astype(bool)] = compact
+    return np.ascontiguousarray(out.transpose(0, 2, 1, 3)).reshape(Tt * tile_t, Fb * blk_n)
