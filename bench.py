@@ -1,0 +1,351 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dynamic-aware Operator hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic input:
+mask compaction, sparse FFN forward + input gradient, block-sparse attention
+forward + backward.  Inputs (activations, frozen weights, dense byte masks) are
+resident in HBM before the timed region; the frozen weights are repacked once,
+outside it.
+
+Workloads (see the design doc for the recipes):
+  opt1.3b_layer   default.  An OPT-1.3B-shaped layer over 8 x 1024 tokens:
+                  attention = configs[2] (30 % of causal blocks), FFN =
+                  configs[1] (planted ReLU support, ~10 % blocks) applied to the
+                  8192 tokens as two X[4096,2048] calls that share the weights.
+  config4         OPT-6.7B-shaped layer (configs[3]).
+  config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]).
+
+Prints ONE JSON line.  `--sweep` additionally runs the configs[4] density sweep
+and writes one line per density to gpurun_out/sweep.jsonl.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+METRIC = "sparse FFN+attn fwd+bwd-dX tokens/s and active-FLOP MFMA util @10/30% density"
+PEAK_MFMA_BF16 = 2.5e15     # FLOP/s, dense bf16 MFMA, MI355X
+PEAK_HBM = 8.0e12           # B/s
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+# ----------------------------------------------------------------------------
+# workload construction (host) and device residency
+# ----------------------------------------------------------------------------
+
+def make_workload(name: str):
+    from paper_2510_15964_amd import inputs
+    if name == "opt1.3b_layer":
+        f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
+        a = inputs.config3_attn()
+        ffn_calls = 2
+    elif name == "config4":
+        f = inputs.config4_ffn()
+        a = inputs.config4_attn()
+        ffn_calls = 1
+    elif name.startswith("config5:"):
+        rho = float(name.split(":")[1])
+        f = inputs.config5_ffn(rho)
+        a = inputs.config5_attn(rho)
+        ffn_calls = 1
+    else:
+        raise SystemExit(f"unknown workload {name!r}")
+    return f, a, ffn_calls
+
+
+class FfnJob:
+    """One lx_sparse_ffn_fwd + lx_sparse_ffn_bwd_dx call pair on T tokens."""
+
+    def __init__(self, lx, torch, f, rows, Wu, Wd, Wut, Wdt):
+        from util import dev
+        self.lx, self.torch = lx, torch
+        sl = slice(rows[0] * 64, rows[1] * 64)
+        self.X = dev(f["X"][sl], "bf16")
+        self.dY = dev(f["dY"][sl], "bf16")
+        self.mask_h = np.ascontiguousarray(f["mask"][rows[0]:rows[1]])
+        self.mask = torch.from_numpy(self.mask_h).cuda()
+        self.Wu, self.Wd, self.Wut, self.Wdt = Wu, Wd, Wut, Wdt
+        self.T, self.d = self.X.shape
+        self.F = Wu.shape[0]
+        Tt, Fb = self.mask_h.shape
+        self.nnz = int(self.mask_h.sum())
+        self.cap = Tt * Fb
+        self.bl = lx.BlockList(Tt, Fb, torch.empty(Tt + 1, dtype=torch.int32, device="cuda"),
+                               torch.empty(self.cap, dtype=torch.int32, device="cuda"), self.cap)
+        # H_act sized by the host-known active count (the mask is a host-generated input)
+        self.bl_run = lx.BlockList(Tt, Fb, self.bl.row_ptr, self.bl.col_idx, max(self.nnz, 1))
+        self.H_act = torch.empty(max(self.nnz, 1) * 4096, dtype=torch.bfloat16, device="cuda")
+        self.Y = torch.empty_like(self.X)
+        self.dX = torch.empty_like(self.X)
+        nb = lx.lx_sparse_ffn_bwd_workspace_bytes(lx.LX_BF16, self.T, self.d, self.F, 64, 64,
+                                                  max(self.nnz, 1), 1)
+        self.ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        self.used = float((self.mask_h.sum(0) > 0).mean())     # fraction of neuron blocks touched
+
+    def run(self):
+        lx = self.lx
+        lx.lx_mask_compact(self.mask, out=self.bl)
+        lx.lx_sparse_ffn_fwd(self.X, self.Wu, self.Wd, self.bl_run, 64, 64, self.Y, self.H_act)
+        lx.lx_sparse_ffn_bwd_dx(self.dY, self.H_act, self.Wu, self.Wd, self.bl_run, 64, 64, self.dX,
+                                self.ws, W_up_t=self.Wut, W_down_t=self.Wdt)
+
+    def flops_per_gemm(self):
+        return self.nnz * 2.0 * 64 * 64 * self.d
+
+    def bytes_sdd(self):   # X (or dY) + touched weight blocks + compact activations written
+        return 2.0 * (self.T * self.d + self.used * self.F * self.d + self.nnz * 4096)
+
+    def bytes_dsd(self):   # compact activations read + touched weight blocks + Y (or dX)
+        return 2.0 * (self.nnz * 4096 + self.used * self.F * self.d + self.T * self.d)
+
+
+class AttnJob:
+    def __init__(self, lx, torch, a):
+        from util import dev
+        self.lx, self.torch, self.a = lx, torch, a
+        self.Q, self.K, self.V, self.dO = (dev(a[k], "bf16") for k in ("Q", "K", "V", "dO"))
+        self.mask = torch.from_numpy(a["mask"]).cuda()
+        self.ha = torch.from_numpy(a["head_active"]).cuda()
+        B, Hh, S, D = self.Q.shape
+        self.B, self.Hh, self.S, self.D = B, Hh, S, D
+        nb = S // 64
+        mb = a["mask_batch"]
+        rows = mb * Hh * nb
+        mk = lambda: lx.BlockList(rows, nb, torch.empty(rows + 1, dtype=torch.int32, device="cuda"),
+                                  torch.empty(rows * nb, dtype=torch.int32, device="cuda"), rows * nb)
+        self.bl_r, self.bl_c = mk(), mk()
+        self.O = torch.empty_like(self.Q)
+        self.LSE = torch.empty((B, Hh, S), dtype=torch.float32, device="cuda")
+        self.dQ, self.dK, self.dV = (torch.empty_like(self.Q) for _ in range(3))
+        self.ws = torch.empty(lx.lx_sparse_attn_bwd_workspace_bytes(lx.LX_BF16, B, Hh, S, D),
+                              dtype=torch.uint8, device="cuda")
+        act = a["head_active"].astype(bool)
+        self.h_act = int(act.sum())
+        per_batch = a["mask"][:, act].sum(axis=(1, 2, 3))      # blocks per mask batch entry
+        self.nblk = float(per_batch.sum() * (B if mb == 1 else 1))
+
+    def run(self):
+        lx, a = self.lx, self.a
+        lx.lx_mask_compact(self.mask, out=self.bl_r)
+        lx.lx_mask_compact(self.mask, transpose=True, out=self.bl_c)
+        lx.lx_sparse_attn_fwd(self.Q, self.K, self.V, self.bl_r, a["scale"], a["causal"], self.O,
+                              self.LSE, mask_batch=a["mask_batch"], head_active=self.ha)
+        lx.lx_sparse_attn_bwd_dx(self.Q, self.K, self.V, self.O, self.LSE, self.dO, self.bl_r,
+                                 self.bl_c, a["scale"], a["causal"], self.dQ, self.dK, self.dV,
+                                 self.ws, mask_batch=a["mask_batch"], head_active=self.ha)
+
+    def unit_bytes(self):      # one [B, active heads, S, D] bf16 tensor
+        return 2.0 * self.B * self.h_act * self.S * self.D
+
+    def flops(self, gemms):    # `gemms` 64x64xD products per active block
+        return self.nblk * gemms * 2.0 * 64 * 64 * self.D
+
+
+# ----------------------------------------------------------------------------
+# algorithmic work per kernel launch (what the method must do)
+# ----------------------------------------------------------------------------
+
+def kernel_model(lx, ffn_jobs, attn):
+    """kernel id -> (launches per step, flops per launch, bytes per launch)."""
+    fj = ffn_jobs[0]
+    fl = float(np.mean([j.flops_per_gemm() for j in ffn_jobs]))
+    bs = float(np.mean([j.bytes_sdd() for j in ffn_jobs]))
+    bd = float(np.mean([j.bytes_dsd() for j in ffn_jobs]))
+    n = len(ffn_jobs)
+    u = attn.unit_bytes()
+    stat = 4.0 * attn.B * attn.Hh * attn.S
+    return {
+        lx.LX_K_FFN_UP: (n, fl, bs), lx.LX_K_FFN_DOWN: (n, fl, bd),
+        lx.LX_K_FFN_DH: (n, fl, bs + 2.0 * fj.nnz * 4096), lx.LX_K_FFN_DX: (n, fl, bd),
+        lx.LX_K_ATTN_FWD: (1, attn.flops(2), 4 * u + stat),
+        lx.LX_K_ATTN_BWD_DQ: (1, attn.flops(3), 6 * u + 2 * stat),
+        lx.LX_K_ATTN_BWD_DKV: (1, attn.flops(4), 6 * u + 2 * stat),
+        lx.LX_K_COMPACT: (n + 2, 0.0, 0.0),
+    }
+
+
+def cpu_baseline(f, a, ffn_tiles=3, attn_heads=24):
+    """The oracle as it stands, single thread, on a bounded sample of the same
+    workload: the first `ffn_tiles` token tiles (forward + input gradient) and
+    the first `attn_heads` active heads of batch entry 0 (forward + backward).
+    Token rates of the two halves are combined the same way a layer would run
+    them: seconds per token add up."""
+    from oracle import lx_oracle as oracle
+    from util import round_to
+    sl = slice(0, ffn_tiles * 64)
+    m = np.ascontiguousarray(f["mask"][:ffn_tiles])
+    t0 = time.perf_counter()
+    H, _ = oracle.ffn_fwd(f["X"][sl], f["W_up"], f["W_down"], m, 64, 64)
+    oracle.ffn_bwd_dx(f["dY"][sl], f["W_up"], f["W_down"], m, round_to(H, "bf16") > 0, 64, 64)
+    t_ffn = time.perf_counter() - t0
+    heads = np.nonzero(a["head_active"])[0][:attn_heads]
+    sub = {k: np.ascontiguousarray(a[k][0:1, heads]) for k in ("Q", "K", "V", "dO")}
+    mk = np.ascontiguousarray(a["mask"][0:1, heads])
+    t0 = time.perf_counter()
+    oracle.attn_fwd(sub["Q"], sub["K"], sub["V"], mk, a["scale"], a["causal"], None, a["blk"])
+    oracle.attn_bwd(sub["Q"], sub["K"], sub["V"], sub["dO"], mk, a["scale"], a["causal"], None,
+                    a["blk"])
+    t_att = time.perf_counter() - t0
+    s_per_tok_ffn = t_ffn / (ffn_tiles * 64)
+    # attention: an inactive head costs nothing; scale per-head time to all active heads
+    n_act = int(a["head_active"].sum())
+    s_per_tok_att = (t_att / len(heads)) * n_act / a["S"]
+    return {
+        "value": 1.0 / (s_per_tok_ffn + s_per_tok_att), "unit": "tokens/s", "cores": 1,
+        "kind": "oracle",
+        "sample": (f"first {ffn_tiles} token tiles of the FFN input ({t_ffn:.1f} s) and first "
+                   f"{len(heads)} active heads of batch entry 0 ({t_att:.1f} s), fwd+bwd, fp64, "
+                   "1 thread; per-token times of the two halves added"),
+    }
+
+
+def run(workload: str, steps: int, warmup: int, with_cpu: bool):
+    import torch
+    from paper_2510_15964_amd import lx
+    from util import dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no fallback path)"
+    torch.cuda.set_device(0)
+    f, a, ffn_calls = make_workload(workload)
+    Wu, Wd = dev(f["W_up"], "bf16"), dev(f["W_down"], "bf16")
+    Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)            # one-time repack of frozen weights
+    Tt = f["mask"].shape[0]
+    per = Tt // ffn_calls
+    ffn_jobs = [FfnJob(lx, torch, f, (i * per, (i + 1) * per), Wu, Wd, Wut, Wdt)
+                for i in range(ffn_calls)]
+    attn = AttnJob(lx, torch, a)
+    tokens = a["B"] * a["S"]
+    assert tokens == f["T"], "FFN and attention halves cover the same tokens"
+
+    def step():
+        for j in ffn_jobs:
+            j.run()
+        attn.run()
+
+    for _ in range(max(warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+
+    # per-kernel breakdown (untimed pre-pass, 3 steps per kernel)
+    model = kernel_model(lx, ffn_jobs, attn)
+    per_kernel = {}
+    for kid, (launches, _, _) in model.items():
+        lx.lx_profile_begin(kid, 3 * launches)
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        ms, n = lx.lx_profile_end()
+        per_kernel[kid] = (ms / 3.0, ms / max(n, 1))      # ms per step, ms per launch
+    dom = max((k for k in per_kernel if k != lx.LX_K_COMPACT), key=lambda k: per_kernel[k][0])
+
+    # timed region: exactly `steps` steps, dominant kernel bracketed by events
+    lx.lx_profile_begin(dom, steps * model[dom][0])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    dom_ms, dom_n = lx.lx_profile_end()
+    dom_avg_s = dom_ms / max(dom_n, 1) * 1e-3
+
+    ms_per_step = elapsed / steps * 1e3
+    flops_step = sum(model[k][0] * model[k][1] for k in model)
+    _, fl, by = model[dom]
+    t_mfma, t_hbm = fl / PEAK_MFMA_BF16, by / PEAK_HBM
+    if t_mfma >= t_hbm:
+        roof = {"bound": "mfma", "achieved": fl / dom_avg_s / 1e12, "peak": PEAK_MFMA_BF16 / 1e12,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": by / dom_avg_s / 1e9, "peak": PEAK_HBM / 1e9,
+                "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = lx.KERNEL_NAMES[dom]
+    roof["avg_launch_us"] = dom_avg_s * 1e6
+    roof["launches_timed"] = dom_n
+
+    ffn_ms = sum(per_kernel[k][0] for k in (lx.LX_K_FFN_UP, lx.LX_K_FFN_DOWN, lx.LX_K_FFN_DH,
+                                            lx.LX_K_FFN_DX))
+    att_ms = sum(per_kernel[k][0] for k in (lx.LX_K_ATTN_FWD, lx.LX_K_ATTN_BWD_DQ,
+                                            lx.LX_K_ATTN_BWD_DKV))
+    ffn_fl = sum(model[k][0] * model[k][1] for k in (lx.LX_K_FFN_UP, lx.LX_K_FFN_DOWN,
+                                                     lx.LX_K_FFN_DH, lx.LX_K_FFN_DX))
+    att_fl = flops_step - ffn_fl
+    out = {
+        "metric": METRIC, "value": tokens * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": workload, "tokens_per_step": tokens,
+            "ffn": {"T_per_call": ffn_jobs[0].T, "calls": ffn_calls, "d": f["d"], "F": f["F"],
+                    "block": "64x64", "block_density": float(f["mask"].mean()),
+                    "active_blocks": int(f["mask"].sum())},
+            "attn": {"B": a["B"], "heads": a["Hh"], "active_heads": attn.h_act, "S": a["S"],
+                     "D": a["D"], "causal": bool(a["causal"]),
+                     "block_density_in_causal_region": float(
+                         a["mask"].sum() / (a["mask"].shape[0] * a["Hh"] * (a["S"] // 64) *
+                                            (a["S"] // 64 + 1) / 2)),
+                     "active_blocks": attn.nblk},
+        },
+        "active_tflops": flops_step / (elapsed / steps) / 1e12,
+        "mfma_util_active_flops": flops_step / (elapsed / steps) / PEAK_MFMA_BF16,
+        "ffn": {"ms_per_step_kernels": ffn_ms, "active_tflops": ffn_fl / (ffn_ms * 1e-3) / 1e12,
+                "mfma_util": ffn_fl / (ffn_ms * 1e-3) / PEAK_MFMA_BF16},
+        "attn": {"ms_per_step_kernels": att_ms, "active_tflops": att_fl / (att_ms * 1e-3) / 1e12,
+                 "mfma_util": att_fl / (att_ms * 1e-3) / PEAK_MFMA_BF16},
+        "kernels_us_per_launch": {lx.KERNEL_NAMES[k]: round(v[1] * 1e3, 2)
+                                  for k, v in per_kernel.items()},
+        "roofline": roof,
+    }
+    if with_cpu:
+        out["cpu_baseline"] = cpu_baseline(f, a)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="opt1.3b_layer")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the configs[4] density sweep into gpurun_out/sweep.jsonl")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build is single-GPU; run with --gpus 1 "
+                         "(the path shards without communication, see DESIGN.md)")
+    if not os.path.exists(os.path.join(ROOT, "paper_2510_15964_amd", "liblx_sparse.so")):
+        import __graft_entry__
+        __graft_entry__.build()
+    from oracle import build as oracle_build
+    oracle_build.build(force=False)
+    res = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    if args.sweep:
+        from paper_2510_15964_amd.inputs import DENSITY_SWEEP
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "sweep.jsonl"), "w") as fh:
+            for rho in DENSITY_SWEEP:
+                r = run(f"config5:{rho}", max(args.steps // 5, 5), 2, False)
+                log(f"config5 rho={rho}: {r['ms_per_step']:.3f} ms/step, "
+                    f"{r['active_tflops']:.1f} active TFLOP/s")
+                fh.write(json.dumps(r) + "\n")
+                fh.flush()
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

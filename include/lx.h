@@ -67,6 +67,19 @@ typedef struct {
   int32_t nnz_cap;
 } lx_blocklist;
 
+/* Kernels that lx_profile_begin can select (one per step of the hot path). */
+typedef enum {
+  LX_K_COMPACT = 0,      /* mask compaction */
+  LX_K_FFN_UP = 1,       /* H_ij = ReLU(X_i W_up_j^T) on listed blocks */
+  LX_K_FFN_DOWN = 2,     /* Y_i = sum_j H_ij W_down_j^T */
+  LX_K_FFN_DH = 3,       /* dZ_ij = (dY_i W_down_j) (.) [H_ij > 0] */
+  LX_K_FFN_DX = 4,       /* dX_i = sum_j dZ_ij W_up_j */
+  LX_K_ATTN_FWD = 5,     /* fused SDD + softmax + DSD */
+  LX_K_ATTN_BWD_DQ = 6,  /* Delta and dQ, query side */
+  LX_K_ATTN_BWD_DKV = 7, /* dK and dV, key side */
+  LX_K_TRANSPOSE = 8     /* weight repack */
+} lx_kernel;
+
 /* Human-readable name of a status code (HOST string, static storage). */
 const char* lx_status_string(lx_status s);
 
@@ -186,6 +199,19 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
                                 const lx_blocklist* bl_cols, int32_t mask_batch,
                                 const uint8_t* head_active, void* dQ, void* dK, void* dV,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement aid for benchmarks (no part of the operators of Sec. VI; it lets a
+ * harness time one kernel of the path in place).  After lx_profile_begin every
+ * launch of `kernel` is bracketed by a pair of HIP events recorded on the
+ * launch stream (at most max_launches launches; later ones are not timed).
+ * lx_profile_end waits for those events, returns the summed kernel time in
+ * milliseconds and the number of timed launches through HOST pointers, and
+ * switches the bracketing off.  begin creates events (it allocates; call it
+ * outside timed regions); not thread-safe.
+ */
+lx_status lx_profile_begin(int32_t kernel, int32_t max_launches);
+lx_status lx_profile_end(float* total_ms, int32_t* launches);
 
 #ifdef __cplusplus
 }

@@ -382,6 +382,7 @@ static size_t dkv_lds() { return (2 * 64 * (D + 8) + 2 * D * kTP) * 2 + 128 * 4;
 
 template <int D>
 static hipError_t launch_fwd(const AttnArgs& a, int B, hipStream_t st) {
+  ProfScope ps(kKAttnFwd, st);
   hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), fwd_lds<D>(), st, a);
   return hipGetLastError();
 }
@@ -396,10 +397,16 @@ static hipError_t launch_bwd(const AttnArgs& a, int B, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), dq_lds<D>(), st, a);
+  {
+    ProfScope ps(kKAttnDq, st);
+    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), dq_lds<D>(), st, a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), dkv_lds<D>(), st, a);
+  {
+    ProfScope ps(kKAttnDkv, st);
+    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), dkv_lds<D>(), st, a);
+  }
   return hipGetLastError();
 }
 

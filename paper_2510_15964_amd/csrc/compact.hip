@@ -7,6 +7,7 @@
 // a time: a 64-wide ballot gives the row's bit pattern, popcount its total and
 // mbcnt the rank of every set lane, so columns come out ascending.
 #include "lx_dev.h"
+#include "lx_launch.h"
 
 namespace lx {
 
@@ -96,6 +97,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
 hipError_t launch_compact(const uint8_t* mask, int batch, int rows, int cols, long long bs,
                           long long rs, long long cs, int* row_ptr, int* col_idx, int cap,
                           hipStream_t stream) {
+  ProfScope ps(kKCompact, stream);
   hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kCompactThreads), 0, stream, mask, batch, rows,
                      cols, bs, rs, cs, row_ptr, col_idx, cap);
   return hipGetLastError();

@@ -14,6 +14,7 @@
 //        64-wide K-step per active block; inactive blocks are never touched.
 // Global -> register prefetch of K-step s+1 overlaps the MFMA work of step s.
 #include "lx_dev.h"
+#include "lx_launch.h"
 
 namespace lx {
 
@@ -240,14 +241,18 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st) {
   const dim3 g1((Fb + 3) / 4, Tt);
-  if (pass == 0)
-    hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, d,
-                       act_out, (const uint16_t*)nullptr);
-  else
-    hipLaunchKernelGGL(ffn_sdd_bf16<1>, g1, dim3(kThreads), 0, st, A, W1, (const uint16_t*)nullptr,
-                       row_ptr, col_idx, d, act_out, act_gate);
+  {
+    ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
+    if (pass == 0)
+      hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, d,
+                         act_out, (const uint16_t*)nullptr);
+    else
+      hipLaunchKernelGGL(ffn_sdd_bf16<1>, g1, dim3(kThreads), 0, st, A, W1,
+                         (const uint16_t*)nullptr, row_ptr, col_idx, d, act_out, act_gate);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   hipLaunchKernelGGL(ffn_dsd_bf16, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
                      (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, out);
   return hipGetLastError();

@@ -11,6 +11,7 @@
 //   dsd: out tile  = sum over listed j of Act_ij [TT x BN] . B[:, j-block]^T
 //        (down-projection, dX), the contraction runs over active blocks only.
 #include "lx_dev.h"
+#include "lx_launch.h"
 
 namespace lx {
 
@@ -116,14 +117,18 @@ static hipError_t launch_f32(int pass, int Tt, int Fb, int d, int F, const float
                              const int* col_idx, float* act_out, const float* act_gate, float* out,
                              hipStream_t st) {
   // W1: [F, d] rows = neurons (contraction over d).  W2: [d, F] (contraction over active f).
-  if (pass == 0)
-    hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 0>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1, b1,
-                       row_ptr, col_idx, d, act_out, (const float*)nullptr);
-  else
-    hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 1>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1,
-                       (const float*)nullptr, row_ptr, col_idx, d, act_out, act_gate);
+  {
+    ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
+    if (pass == 0)
+      hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 0>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1,
+                         b1, row_ptr, col_idx, d, act_out, (const float*)nullptr);
+    else
+      hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 1>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1,
+                         (const float*)nullptr, row_ptr, col_idx, d, act_out, act_gate);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   hipLaunchKernelGGL((ffn_dsd_f32<TT, BN>), dim3(d / 32, Tt), dim3(kF32Threads), 0, st,
                      (const float*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, out);
   return hipGetLastError();
@@ -162,6 +167,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ sr
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst,
                             hipStream_t st) {
   dim3 grid((C + 63) / 64, (R + 63) / 64);
+  ProfScope ps(kKTranspose, st);
   if (elem_bytes == 4)
     hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, st, (const float*)src, R, C,
                        (float*)dst);

@@ -5,10 +5,35 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/lx.h"
 #include "lx_launch.h"
 
 namespace lx {
+
+// ---- profiling aid (lx_profile_begin / lx_profile_end) -----------------------------------
+static int g_prof_id = -1;
+static int g_prof_n = 0;
+static std::vector<hipEvent_t> g_prof_start, g_prof_stop;
+
+void prof_pre(int id, hipStream_t st) {
+  if (id != g_prof_id || g_prof_n >= (int)g_prof_start.size()) return;
+  (void)hipEventRecord(g_prof_start[g_prof_n], st);
+}
+void prof_post(int id, hipStream_t st) {
+  if (id != g_prof_id || g_prof_n >= (int)g_prof_start.size()) return;
+  (void)hipEventRecord(g_prof_stop[g_prof_n], st);
+  ++g_prof_n;
+}
+static void prof_clear() {
+  for (hipEvent_t e : g_prof_start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof_stop) (void)hipEventDestroy(e);
+  g_prof_start.clear();
+  g_prof_stop.clear();
+  g_prof_id = -1;
+  g_prof_n = 0;
+}
 
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -51,6 +76,44 @@ const char* lx_status_string(lx_status s) {
     case LX_ERR_RUNTIME: return "LX_ERR_RUNTIME";
   }
   return "LX_ERR_UNKNOWN";
+}
+
+lx_status lx_profile_begin(int32_t kernel, int32_t max_launches) {
+  if (kernel < 0 || kernel >= kKCount || max_launches <= 0 || max_launches > (1 << 20))
+    return LX_ERR_INVALID_ARG;
+  prof_clear();
+  g_prof_start.resize(max_launches);
+  g_prof_stop.resize(max_launches);
+  for (int i = 0; i < max_launches; ++i) {
+    if (hipEventCreate(&g_prof_start[i]) != hipSuccess || hipEventCreate(&g_prof_stop[i]) != hipSuccess) {
+      g_prof_start.resize(i);
+      g_prof_stop.resize(i);
+      prof_clear();
+      return LX_ERR_RUNTIME;
+    }
+  }
+  g_prof_id = kernel;
+  return LX_OK;
+}
+
+lx_status lx_profile_end(float* total_ms, int32_t* launches) {
+  if (!total_ms || !launches) return LX_ERR_INVALID_ARG;
+  if (g_prof_id < 0) return LX_ERR_INVALID_ARG;
+  float total = 0.f;
+  lx_status rc = LX_OK;
+  for (int i = 0; i < g_prof_n; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_prof_stop[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_prof_start[i], g_prof_stop[i]) != hipSuccess) {
+      rc = LX_ERR_RUNTIME;
+      break;
+    }
+    total += ms;
+  }
+  *total_ms = total;
+  *launches = g_prof_n;
+  prof_clear();
+  return rc;
 }
 
 lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,

@@ -5,6 +5,22 @@
 
 namespace lx {
 
+// Kernel ids of the profiling aid (values are part of the C ABI: lx_kernel in lx.h).
+enum KernelId {
+  kKCompact = 0, kKFfnUp = 1, kKFfnDown = 2, kKFfnDh = 3, kKFfnDx = 4,
+  kKAttnFwd = 5, kKAttnDq = 6, kKAttnDkv = 7, kKTranspose = 8, kKCount = 9
+};
+void prof_pre(int id, hipStream_t st);
+void prof_post(int id, hipStream_t st);
+// Brackets the launches issued while it is alive with a pair of events when kernel `id`
+// is the one selected by lx_profile_begin; otherwise costs one integer compare.
+struct ProfScope {
+  int id;
+  hipStream_t st;
+  ProfScope(int id_, hipStream_t st_) : id(id_), st(st_) { prof_pre(id, st); }
+  ~ProfScope() { prof_post(id, st); }
+};
+
 struct AttnArgs {
   const uint16_t *Q, *K, *V, *O, *dO;
   uint16_t *Out, *dQ, *dK, *dV;

@@ -30,8 +30,12 @@ EXPORTS = (
     "lx_status_string", "lx_mask_compact", "lx_ffn_pack_weights",
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
-    "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx",
+    "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
 )
+(LX_K_COMPACT, LX_K_FFN_UP, LX_K_FFN_DOWN, LX_K_FFN_DH, LX_K_FFN_DX, LX_K_ATTN_FWD,
+ LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE) = range(9)
+KERNEL_NAMES = ("compact", "ffn_up", "ffn_down", "ffn_dh", "ffn_dx", "attn_fwd", "attn_bwd_dq",
+                "attn_bwd_dkv", "transpose")
 
 
 class lx_blocklist(C.Structure):
@@ -59,6 +63,10 @@ _lib.lx_sparse_attn_fwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32, _
 _lib.lx_sparse_attn_bwd_dx.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32, _vp, _vp, _vp,
                                        _vp, _vp, _vp, C.POINTER(_i64), _blp, _blp, _i32, _vp, _vp,
                                        _vp, _vp, _vp, _sz, _vp]
+
+
+_lib.lx_profile_begin.argtypes = [_i32, _i32]
+_lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
 
 
 class LxError(RuntimeError):
@@ -165,6 +173,17 @@ def lx_sparse_ffn_bwd_dx(dY, H_act, W_up, W_down, bl: BlockList, tile_t: int, bl
                                      C.byref(bl.c), _ptr(dX), _ptr(workspace), ws_bytes, _stream()),
            "lx_sparse_ffn_bwd_dx")
     return dX
+
+
+def lx_profile_begin(kernel: int, max_launches: int):
+    _check(_lib.lx_profile_begin(kernel, max_launches), "lx_profile_begin")
+
+
+def lx_profile_end():
+    """Returns (total kernel milliseconds, number of timed launches)."""
+    ms, n = C.c_float(0), _i32(0)
+    _check(_lib.lx_profile_end(C.byref(ms), C.byref(n)), "lx_profile_end")
+    return ms.value, n.value
 
 
 def _strides(t: torch.Tensor):

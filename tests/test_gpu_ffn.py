@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2510_15964_amd import inputs
-from util import TOL, compact_blocks, dev, host, rel_err, round_to
+from util import FRO, TOL, compact_blocks, dev, host, rel_err, rel_err_fro, round_to
 
 pytestmark = pytest.mark.gpu
 
@@ -48,7 +48,9 @@ def run_gpu(lx, c, mask=None, packed=True, bias=False, h_from=None):
     dX = torch.full((T, d), float("nan"), dtype=tdt, device="cuda")
     if packed:
         Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
-        assert torch.equal(Wut, Wu.t().contiguous()) and torch.equal(Wdt, Wd.t().contiguous())
+        bits = torch.int32 if dt == "f32" else torch.int16        # bit compare (NaN-safe)
+        assert torch.equal(Wut.view(bits), Wu.t().contiguous().view(bits))
+        assert torch.equal(Wdt.view(bits), Wd.t().contiguous().view(bits))
         lx.lx_sparse_ffn_bwd_dx(dY, H_in, Wu, Wd, bl, tt, bn, dX, ws, W_up_t=Wut, W_down_t=Wdt)
     else:
         lx.lx_sparse_ffn_bwd_dx(dY, H_in, Wu, Wd, bl, tt, bn, dX, ws)
@@ -78,8 +80,12 @@ def compare(lx, oracle, c, mask=None, packed=True, bias=False):
     errs = dict(H=rel_err(got["H_act"], ref["H_act"]), Y=rel_err(got["Y"], ref["Y"]),
                 dX=rel_err(got["dX"], ref["dX"]))
     print(f"[{c['dtype']} T={c['T']} d={c['d']} F={c['F']} nnz={got['nnz']}] errors {errs}", flush=True)
+    fro = dict(H=rel_err_fro(got["H_act"], ref["H_act"]), Y=rel_err_fro(got["Y"], ref["Y"]),
+               dX=rel_err_fro(got["dX"], ref["dX"]))
+    print("   frobenius", fro, flush=True)
     for k, e in errs.items():
         assert e <= tol, (k, e, tol)
+        assert fro[k] <= FRO[c["dtype"]], (k, fro[k])
     assert np.isfinite(got["Y"]).all() and np.isfinite(got["dX"]).all()
     return got, ref
 
@@ -173,7 +179,7 @@ def test_config2_bf16_full_size_sampled_tiles(lx, oracle):
     c = inputs.config2_ffn()
     got = run_gpu(lx, c)
     assert got["nnz"] == int(c["mask"].sum())
-    rp = np.concatenate([[0], np.cumsum(c["mask"].sum(1))])
+    rp = np.concatenate([[0], np.cumsum(c["mask"].sum(1, dtype=np.int64))]).astype(np.int64)
     for i in (0, 17, 63):
         sl = slice(i * 64, (i + 1) * 64)
         sub = dict(c, X=c["X"][sl], dY=c["dY"][sl], mask=c["mask"][i:i + 1], T=64)
