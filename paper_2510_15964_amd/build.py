@@ -15,7 +15,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-shared", *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    cmd = [hipcc, *FLAGS, "-shared", "-Wl,--no-undefined", *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
     if verbose:
         cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -13,29 +13,45 @@ namespace lx {
 
 constexpr int kCompactThreads = 1024;
 constexpr int kCompactWaves = kCompactThreads / kWave;
-constexpr int kChunkRows = 4096;  // rows scanned per pass (4 per thread)
+constexpr int kChunkRows = 4096;    // rows scanned per pass (4 per thread)
+constexpr int kStageBytes = 32768;  // mask bytes staged in LDS per pass
 
+// The mask chunk is first copied into LDS with all loads in flight at once (strided or not),
+// because a wavefront that walks rows straight from global memory pays one full memory
+// latency per row; the ballots then run out of LDS.
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const uint8_t* __restrict__ mask, int batch, int rows, int cols, long long bstride,
     long long rstride, long long cstride, int* __restrict__ row_ptr, int* __restrict__ col_idx,
     int cap) {
   __shared__ int offs[kChunkRows];
   __shared__ int wave_tot[kCompactWaves];
+  __shared__ uint8_t stage[kStageBytes];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int total_rows = batch * rows;
+  const bool staged = cols <= kStageBytes;
+  const int chunk_rows = staged ? max(1, min(kChunkRows, kStageBytes / cols)) : 1;
   int carry = 0;
-  for (int chunk = 0; chunk < total_rows; chunk += kChunkRows) {
-    const int n = min(kChunkRows, total_rows - chunk);
+  for (int chunk = 0; chunk < total_rows; chunk += chunk_rows) {
+    const int n = min(chunk_rows, total_rows - chunk);
+    if (staged) {
+      for (int idx = tid; idx < n * cols; idx += kCompactThreads) {
+        const int r = idx / cols, c = idx - r * cols, gr = chunk + r;
+        stage[idx] = mask[(long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride +
+                          (long long)c * cstride];
+      }
+      __syncthreads();
+    }
+    auto is_on = [&](int r, int c) -> bool {
+      if (c >= cols) return false;
+      if (staged) return stage[r * cols + c] != 0;
+      const int gr = chunk + r;
+      return mask[(long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride +
+                  (long long)c * cstride] != 0;
+    };
     // 1. per-row counts
     for (int r = wave; r < n; r += kCompactWaves) {
-      const int gr = chunk + r;
-      const uint8_t* base = mask + (long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride;
       int cnt = 0;
-      for (int c0 = 0; c0 < cols; c0 += kWave) {
-        const int c = c0 + lane;
-        const bool on = c < cols && base[(long long)c * cstride] != 0;
-        cnt += __popcll(__ballot(on));
-      }
+      for (int c0 = 0; c0 < cols; c0 += kWave) cnt += __popcll(__ballot(is_on(r, c0 + lane)));
       if (lane == 0) offs[r] = cnt;
     }
     __syncthreads();
@@ -75,12 +91,10 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     __syncthreads();
     // 3. scatter the ascending column indices
     for (int r = wave; r < n; r += kCompactWaves) {
-      const int gr = chunk + r;
-      const uint8_t* base = mask + (long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride;
       int off = offs[r];
       for (int c0 = 0; c0 < cols; c0 += kWave) {
         const int c = c0 + lane;
-        const bool on = c < cols && base[(long long)c * cstride] != 0;
+        const bool on = is_on(r, c);
         const unsigned long long bits = __ballot(on);
         const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(bits >> 32),
                                                    __builtin_amdgcn_mbcnt_lo((unsigned)bits, 0));

@@ -62,18 +62,50 @@ __device__ __forceinline__ void mma_step(const uint16_t* lds, int wave, f32x16 (
   }
 }
 
+// Work items of the sdd kernel are (token tile, group of `per` consecutive list entries),
+// numbered in list order.  The launch grid is the host-known upper bound on their number;
+// every wavefront finds its item from row_ptr with a 64-wide scan, so that the active
+// workgroups are the FIRST ones of the grid and spread evenly over XCDs, shader engines and
+// CUs (a 2-D grid with early exits piles them onto a few CUs).  Returns false past the end.
+__device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int work,
+                                          int per, int& row, int& chunk) {
+  const int lane = threadIdx.x % kWave;
+  int running = 0;
+  for (int base = 0; base < rows; base += kWave) {
+    const int r = base + lane;
+    int c = 0;
+    if (r < rows) c = (row_ptr[r + 1] - row_ptr[r] + per - 1) / per;
+    int incl = c;
+#pragma unroll
+    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+      const int up = __shfl_up(incl, dlt);
+      if (lane >= dlt) incl += up;
+    }
+    const int total = __shfl(incl, kWave - 1);
+    if (work < running + total) {
+      const unsigned long long hit = __ballot(running + incl > work);
+      const int first = __ffsll((long long)hit) - 1;
+      row = base + first;
+      chunk = work - running - __shfl(incl - c, first);
+      return true;
+    }
+    running += total;
+  }
+  return false;
+}
+
 // MODE 0: out = bf16(max(acc + bias, 0));  MODE 1: out = gate > 0 ? bf16(acc) : 0.
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, int K, uint16_t* __restrict__ out_act,
+    const int* __restrict__ col_idx, int rows, int K, uint16_t* __restrict__ out_act,
     const uint16_t* __restrict__ gate_act) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[(kRowsA + kRowsB) * kPitch];
-  const int i = blockIdx.y;
+  int i, chunk;
+  if (!find_work(row_ptr, rows, blockIdx.x, 4, i, chunk)) return;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
-  const int first = blockIdx.x * 4;
-  if (first >= n_i) return;
+  const int first = chunk * 4;
   const int nb = min(4, n_i - first);
   const int p0 = rs + first;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -237,18 +269,19 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
 //                    act_gate = H_act, out = dX
 hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
-                           const uint16_t* b2, const int* row_ptr, const int* col_idx,
+                           const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st) {
-  const dim3 g1((Fb + 3) / 4, Tt);
+  (void)Fb;
+  const dim3 g1(nnz_cap / 4 + Tt);   // >= sum over rows of ceil(n_i / 4)
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
-      hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, d,
-                         act_out, (const uint16_t*)nullptr);
+      hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, Tt,
+                         d, act_out, (const uint16_t*)nullptr);
     else
       hipLaunchKernelGGL(ffn_sdd_bf16<1>, g1, dim3(kThreads), 0, st, A, W1,
-                         (const uint16_t*)nullptr, row_ptr, col_idx, d, act_out, act_gate);
+                         (const uint16_t*)nullptr, row_ptr, col_idx, Tt, d, act_out, act_gate);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

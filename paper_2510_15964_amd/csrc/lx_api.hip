@@ -185,7 +185,7 @@ lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_
   else
     e = launch_ffn_bf16(0, bl->rows, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
                         (const uint16_t*)b_up, (const uint16_t*)W_down, (const uint16_t*)b_down,
-                        bl->row_ptr, bl->col_idx, (uint16_t*)act, nullptr, (uint16_t*)Y,
+                        bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)act, nullptr, (uint16_t*)Y,
                         (hipStream_t)stream);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
@@ -228,7 +228,7 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
   else
     e = launch_ffn_bf16(1, bl->rows, bl->cols, d, F, (const uint16_t*)dY,
                         (const uint16_t*)W_down_t, nullptr, (const uint16_t*)W_up_t, nullptr,
-                        bl->row_ptr, bl->col_idx, (uint16_t*)dz, (const uint16_t*)H_act,
+                        bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)dz, (const uint16_t*)H_act,
                         (uint16_t*)dX, st);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }

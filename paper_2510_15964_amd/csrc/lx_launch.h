@@ -42,7 +42,7 @@ hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, cons
                           const float* act_gate, float* out, hipStream_t st);
 hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
-                           const uint16_t* b2, const int* row_ptr, const int* col_idx,
+                           const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);

@@ -38,6 +38,7 @@ def _check(lx, oracle, mask, transpose=False):
     ((32, 16, 16), 0.3), ((2, 32, 32, 32), 0.25), ((40, 32, 32), 0.5),
     ((9000, 5), 0.4),       # more rows than one scan pass holds
     ((4, 1100, 3), 0.7),
+    ((3, 40000), 0.01),     # a row longer than the LDS staging buffer
 ])
 @pytest.mark.parametrize("transpose", [False, True])
 def test_compact_bit_exact(lx, oracle, shape, density, transpose):
