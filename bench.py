@@ -138,8 +138,7 @@ class AttnJob:
 
     def run(self):
         lx, a = self.lx, self.a
-        lx.lx_mask_compact(self.mask, out=self.bl_r)
-        lx.lx_mask_compact(self.mask, transpose=True, out=self.bl_c)
+        lx.lx_mask_compact_pair(self.mask, out=(self.bl_r, self.bl_c))
         lx.lx_sparse_attn_fwd(self.Q, self.K, self.V, self.bl_r, a["scale"], a["causal"], self.O,
                               self.LSE, mask_batch=a["mask_batch"], head_active=self.ha)
         lx.lx_sparse_attn_bwd_dx(self.Q, self.K, self.V, self.O, self.LSE, self.dO, self.bl_r,
@@ -172,7 +171,7 @@ def kernel_model(lx, ffn_jobs, attn):
         lx.LX_K_ATTN_FWD: (1, attn.flops(2), 4 * u + stat),
         lx.LX_K_ATTN_BWD_DQ: (1, attn.flops(3), 6 * u + 2 * stat),
         lx.LX_K_ATTN_BWD_DKV: (1, attn.flops(4), 6 * u + 2 * stat),
-        lx.LX_K_COMPACT: (n + 2, 0.0, 0.0),
+        lx.LX_K_COMPACT: (n + 1, 0.0, 0.0),
     }
 
 

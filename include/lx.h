@@ -102,6 +102,18 @@ lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int3
                           int32_t* row_ptr, int32_t* col_idx, int32_t col_idx_cap, void* stream);
 
 /*
+ * The same compaction for the row-compressed AND the column-compressed list of
+ * the same masks in a single launch (the attention backward pass walks both).
+ * Row list: batch*rows rows of column indices into (row_ptr_r, col_idx_r);
+ * column list: batch*cols rows of row indices into (row_ptr_c, col_idx_c).
+ * col_idx_cap applies to each of the two index buffers.
+ */
+lx_status lx_mask_compact_pair(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
+                               int64_t batch_stride, int64_t row_stride, int64_t col_stride,
+                               int32_t* row_ptr_r, int32_t* col_idx_r, int32_t* row_ptr_c,
+                               int32_t* col_idx_c, int32_t col_idx_cap, void* stream);
+
+/*
  * One-time repack of the frozen weights (Sec. VI-B "memory coalescing": each
  * product reads its weights along the contiguous dimension).  Writes the
  * transposes W_up_t[d,F] = W_up[F,d]^T and W_down_t[F,d] = W_down[d,F]^T, which
@@ -190,7 +202,7 @@ lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int3
  *   bl_rows  the forward list;  bl_cols  the same mask column-compressed:
  *            rows = mask_batch*Hh*(S/64) ordered (batch, head, key block),
  *            entries = query blocks.
- *   workspace  >= lx_sparse_attn_bwd_workspace_bytes (holds Delta).
+ *   workspace  >= lx_sparse_attn_bwd_workspace_bytes (holds Delta and a rescaled LSE).
  */
 lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                                 float scale, int32_t causal, const void* Q, const void* K,

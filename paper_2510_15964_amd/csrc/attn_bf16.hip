@@ -9,94 +9,95 @@
 // rows and walks the block list of its row of the mask.  All products run on
 // the 32x32x16 bf16 MFMA with fp32 accumulators.
 //
-// Trick used throughout: the first product is computed transposed (S^T = K Q^T)
-// so that every lane holds scores of ONE query and the accumulator registers
-// can be fed straight back as the B operand of the second product; the MFMA's
-// k index may be permuted freely as long as both operands agree, so the A
-// operand (V^T, K^T, Q^T, dO^T from LDS) is read in the matching order
-// { 16s+4h .. +3, 16s+8+4h .. +3 }.  Operands needed "k-major" are written to
-// LDS transposed, two rows packed per 32-bit store.
+// Data movement: the [64 x D] tiles of the listed blocks go from global memory
+// straight into LDS (global_load_lds, 16 bytes per lane), double buffered: the
+// tiles of list entry it+1 are in flight while entry it is computed.  The two
+// stages are separate LDS arrays so that the compiler's LDS-DMA tracking does
+// not wait for the in-flight stage.  Tiles are row-major, unpadded, with the
+// 16-byte slots of a row XOR-swizzled by the row index (bank spreading).
+//
+// Two tricks keep everything in one LDS layout and out of cross-lane shuffles:
+//  * the first product is computed transposed (S^T = K Q^T), so every lane
+//    holds scores of ONE query and the accumulator registers are fed straight
+//    back as the B operand of the second product; the MFMA's k index may be
+//    permuted freely as long as both operands agree: { 16s+4h..+3, 16s+8+4h..+3 };
+//  * the operands that are needed k-major (V^T, K^T, Q^T, dO^T) are read from
+//    the same row-major tile with the transposing LDS read (ds_read_b64_tr_b16:
+//    within 16 lanes, lane j receives column c0+j of the four rows addressed by
+//    lanes 0-3, 4-7, 8-11, 12-15).
 #include "lx_dev.h"
 #include "lx_launch.h"
 
 namespace lx {
 
+#define LX_AS1 __attribute__((address_space(1)))
+#define LX_AS3 __attribute__((address_space(3)))
+
 constexpr int kAT = 128;                 // threads per workgroup
-constexpr int kTP = 68;                  // pitch (elements) of transposed tiles [D][64]
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+typedef short short4v __attribute__((ext_vector_type(4)));
+
 template <int D>
-struct Tile {                            // a [64 x D] bf16 tile held across the workgroup
-  static constexpr int kTasks = D / 32;  // per thread: (row pair, 8-column group) tasks
-  uint4 lo[kTasks], hi[kTasks];          // row 2rp and row 2rp+1
+__device__ __forceinline__ int tswz(int row) {
+  return D == 64 ? ((row ^ (row >> 3)) & 7) : (row & 15);
+}
+
+// Per-lane element offsets (relative to the tile's first row) of the DMA instructions this
+// wave issues for one [64 x D] tile.  One instruction moves 1 KiB = 64*16/(2D) rows.
+template <int D>
+struct TileDma {
+  static constexpr int kSlots = D / 8;            // 16-byte slots per row
+  static constexpr int kRowsPer = 64 / kSlots;    // rows per DMA instruction
+  static constexpr int kPerWave = 64 / kRowsPer / 2;
+  long long off[kPerWave];
+  __device__ __forceinline__ void init(long long ld) {
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const int g = wave + 2 * u;
+      const int row = kRowsPer * g + lane / kSlots;
+      const int slot = (lane % kSlots) ^ tswz<D>(row);
+      off[u] = (long long)row * ld + slot * 8;
+    }
+  }
+  __device__ __forceinline__ void issue(uint16_t* tile, const uint16_t* g0) const {
+    const int wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u)
+      __builtin_amdgcn_global_load_lds((const LX_AS1 void*)(g0 + off[u]),
+                                       (LX_AS3 void*)(tile + (wave + 2 * u) * 512), 16, 0, 0);
+  }
 };
 
+// acc[half] += R[rows 32*half + lane%32][:] . F^T   where R is a row-major tile in LDS and F the
+// per-lane register fragments (column index = lane%32).  Result register v of a lane is element
+// (row 32*half + 8*(v/4) + 4*(lane/32) + v%4, column lane%32).
 template <int D>
-__device__ __forceinline__ void tile_fetch(Tile<D>& t, const uint16_t* __restrict__ g,
-                                           long long ld) {
-#pragma unroll
-  for (int u = 0; u < Tile<D>::kTasks; ++u) {
-    const int task = threadIdx.x + kAT * u;
-    const int cg = task % (D / 8), rp = task / (D / 8);
-    t.lo[u] = *reinterpret_cast<const uint4*>(g + (long long)(2 * rp) * ld + cg * 8);
-    t.hi[u] = *reinterpret_cast<const uint4*>(g + (long long)(2 * rp + 1) * ld + cg * 8);
-  }
-}
-
-// row-major copy: lds[row][c], pitch D+8
-template <int D>
-__device__ __forceinline__ void tile_store_rows(const Tile<D>& t, uint16_t* lds) {
-#pragma unroll
-  for (int u = 0; u < Tile<D>::kTasks; ++u) {
-    const int task = threadIdx.x + kAT * u;
-    const int cg = task % (D / 8), rp = task / (D / 8);
-    *reinterpret_cast<uint4*>(lds + (2 * rp) * (D + 8) + cg * 8) = t.lo[u];
-    *reinterpret_cast<uint4*>(lds + (2 * rp + 1) * (D + 8) + cg * 8) = t.hi[u];
-  }
-}
-
-// transposed copy: lds[c][row], pitch kTP; rows 2rp, 2rp+1 share one 32-bit word
-template <int D>
-__device__ __forceinline__ void tile_store_transposed(const Tile<D>& t, uint16_t* lds) {
-  uint32_t* w = reinterpret_cast<uint32_t*>(lds);
-#pragma unroll
-  for (int u = 0; u < Tile<D>::kTasks; ++u) {
-    const int task = threadIdx.x + kAT * u;
-    const int cg = task % (D / 8), rp = task / (D / 8);
-    const uint32_t a[4] = {t.lo[u].x, t.lo[u].y, t.lo[u].z, t.lo[u].w};
-    const uint32_t b[4] = {t.hi[u].x, t.hi[u].y, t.hi[u].z, t.hi[u].w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int c = cg * 8 + 2 * e;
-      w[(c * kTP) / 2 + rp] = (a[e] & 0xFFFFu) | (b[e] << 16);
-      w[((c + 1) * kTP) / 2 + rp] = (a[e] >> 16) | (b[e] & 0xFFFF0000u);
-    }
-  }
-}
-
-// acc[half] += R[rows 32*half + lane%32][:] . F^T   where R is a row-major LDS tile and
-// F the per-lane register fragments (column index = lane%32).  Result register v of a lane is
-// element (row 32*half + 8*(v/4) + 4*(lane/32) + v%4, column lane%32).
-template <int D>
-__device__ __forceinline__ void mma_rows(const uint16_t* lds, const uint4 (&frag)[D / 16],
+__device__ __forceinline__ void mma_rows(const uint16_t* tile, const uint4 (&frag)[D / 16],
                                          f32x16 (&acc)[2]) {
-  const int lane = threadIdx.x % kWave, r = lane % 32, kq = (lane / 32) * 8;
+  const int lane = threadIdx.x % kWave, r = lane % 32, h2 = lane / 32;
 #pragma unroll
-  for (int half = 0; half < 2; ++half)
+  for (int half = 0; half < 2; ++half) {
+    const int row = 32 * half + r;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
-      const uint4 a = *reinterpret_cast<const uint4*>(lds + (32 * half + r) * (D + 8) + 16 * s + kq);
+      const uint4 a = *reinterpret_cast<const uint4*>(tile + row * D +
+                                                      (((2 * s + h2) ^ tswz<D>(row)) << 3));
       acc[half] = mfma32(a, frag[s], acc[half]);
     }
+  }
 }
 
-// out[ct] += T^T-tile . P   where lds holds the transposed tile [D][64] and p[half][v] are the
-// fp32 accumulator-layout values of the [64 x 32] factor (rounded to bf16 here).
+// out[ct] += T^T . P   where T is a row-major [64 x D] tile in LDS (read transposed) and
+// p[half][v] the accumulator-layout values of the [64 x 32] factor (rounded to bf16 here).
 template <int D>
-__device__ __forceinline__ void mma_transposed(const uint16_t* lds, const f32x16 (&p)[2],
+__device__ __forceinline__ void mma_transposed(const uint16_t* tile, const f32x16 (&p)[2],
                                                f32x16 (&out)[D / 32]) {
-  const int lane = threadIdx.x % kWave, r = lane % 32, h2 = lane / 32;
+  const int lane = threadIdx.x % kWave, h2 = lane / 32;
+  const int j = lane % 16, e = j / 4, q = j % 4;
+  const int cbase = 16 * ((lane / 16) % 2) + 4 * q;      // + 32*ct
 #pragma unroll
   for (int s2 = 0; s2 < 4; ++s2) {
     const int half = s2 / 2, g0 = 2 * (s2 % 2);
@@ -105,11 +106,16 @@ __device__ __forceinline__ void mma_transposed(const uint16_t* lds, const f32x16
     b.y = pack2bf(p[half][4 * g0 + 2], p[half][4 * g0 + 3]);
     b.z = pack2bf(p[half][4 * g0 + 4], p[half][4 * g0 + 5]);
     b.w = pack2bf(p[half][4 * g0 + 6], p[half][4 * g0 + 7]);
+    const int r_lo = 16 * s2 + 4 * h2 + e, r_hi = r_lo + 8;
 #pragma unroll
     for (int ct = 0; ct < D / 32; ++ct) {
-      const uint16_t* row = lds + (32 * ct + r) * kTP + 16 * s2 + 4 * h2;
-      const uint2 lo = *reinterpret_cast<const uint2*>(row);
-      const uint2 hi = *reinterpret_cast<const uint2*>(row + 8);
+      const int col = 32 * ct + cbase;
+      const uint16_t* p_lo = tile + r_lo * D + (((col >> 3) ^ tswz<D>(r_lo)) << 3) + (col & 7);
+      const uint16_t* p_hi = tile + r_hi * D + (((col >> 3) ^ tswz<D>(r_hi)) << 3) + (col & 7);
+      const uint2 lo = __builtin_bit_cast(
+          uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LX_AS3 short4v*)p_lo));
+      const uint2 hi = __builtin_bit_cast(
+          uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LX_AS3 short4v*)p_hi));
       out[ct] = mfma32(make_uint4(lo.x, lo.y, hi.x, hi.y), b, out[ct]);
     }
   }
@@ -139,15 +145,33 @@ __device__ __forceinline__ void store_acc(const f32x16 (&acc)[D / 32], float mul
     }
 }
 
+// Double-buffered walk over n list entries: issue0/issue1 start the DMA of an entry into
+// stage 0/1, comp0/comp1 consume it.  A wave first waits for its own DMA (vmcnt), the barrier
+// then makes the whole stage visible and retires the reads of the stage about to be refilled.
+template <class I0, class I1, class C0, class C1>
+__device__ __forceinline__ void walk2(int n, I0 issue0, I1 issue1, C0 comp0, C1 comp1) {
+  if (n > 0) issue0(0);
+  for (int it = 0; it < n; it += 2) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (it + 1 < n) issue1(it + 1);
+    comp0(it);
+    if (it + 1 < n) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      if (it + 2 < n) issue0(it + 2);
+      comp1(it + 1);
+    }
+  }
+}
 
 // ---------------------------------------------------------------------------
 // forward: O, LSE for one (batch, head, query block)
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT) void attn_fwd_bf16(const AttnArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  uint16_t* Ks = smem;                    // [64][D+8]
-  uint16_t* Vt = smem + 64 * (D + 8);     // [D][kTP]
+__global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_fwd_bf16(const AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint16_t st0[2 * 64 * D];   // K tile, V tile
+  __shared__ __attribute__((aligned(1024))) uint16_t st1[2 * 64 * D];
   const int nqb = a.S / 64;
   const int qb = nqb - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -164,58 +188,64 @@ __global__ __launch_bounds__(kAT) void attn_fwd_bf16(const AttnArgs a) {
   for (int s = 0; s < D / 16; ++s)
     qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
 
+  TileDma<D> dma;
+  dma.init(a.ss);
   f32x16 o_acc[D / 32];
   zero(o_acc);
   float m = -INFINITY, lsum = 0.f;
   const float sc = a.scale * kLog2e;
 
-  for (int it = 0; it < n; ++it) {
+  auto issue = [&](uint16_t* st, int it) {
+    const long long t0 = base + (long long)a.col_idx[rs + it] * 64 * a.ss;
+    dma.issue(st, a.K + t0);
+    dma.issue(st + 64 * D, a.V + t0);
+  };
+  auto comp = [&](const uint16_t* st, int it) {
     const int kb = a.col_idx[rs + it];
-    if (a.causal && kb > qb) continue;
-    Tile<D> tk, tv;
-    tile_fetch<D>(tk, a.K + base + (long long)kb * 64 * a.ss, a.ss);
-    tile_fetch<D>(tv, a.V + base + (long long)kb * 64 * a.ss, a.ss);
-    __syncthreads();
-    tile_store_rows<D>(tk, Ks);
-    tile_store_transposed<D>(tv, Vt);
-    __syncthreads();
-
     f32x16 s_acc[2];
     zero(s_acc);
-    mma_rows<D>(Ks, qf, s_acc);
-    const bool diag = a.causal && kb == qb;
+    mma_rows<D>(st, qf, s_acc);           // S^T[key][q]
     float mloc = -INFINITY;
+    if (a.causal && kb == qb) {           // diagonal block: keys after the query are excluded
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
+      for (int half = 0; half < 2; ++half)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float x = s_acc[half][v] * sc;
-        const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
-        if (diag && kl > ql) x = -INFINITY;
-        s_acc[half][v] = x;
-        mloc = fmaxf(mloc, x);
-      }
+        for (int v = 0; v < 16; ++v) {
+          const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
+          if (kl > ql) s_acc[half][v] = -INFINITY;
+          mloc = fmaxf(mloc, s_acc[half][v]);
+        }
+    } else {
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, s_acc[half][v]);
+    }
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    const float m_new = fmaxf(m, mloc);
+    const float m_new = fmaxf(m, mloc * sc);          // running max in scaled log2 units
     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
     float psum = 0.f;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(s_acc[half][v] - m_new);
+        const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -m_new));
         s_acc[half][v] = p;
         psum += p;
       }
     psum += __shfl_xor(psum, 32);
     lsum = lsum * alpha + psum;
     m = m_new;
+    if (__any(alpha != 1.f)) {            // the running maximum moved for some query
 #pragma unroll
-    for (int ct = 0; ct < D / 32; ++ct)
+      for (int ct = 0; ct < D / 32; ++ct)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o_acc[ct][v] *= alpha;
-    mma_transposed<D>(Vt, s_acc, o_acc);
-  }
+        for (int v = 0; v < 16; ++v) o_acc[ct][v] *= alpha;
+    }
+    mma_transposed<D>(st + 64 * D, s_acc, o_acc);   // O^T += V^T P^T
+  };
+  walk2(n, [&](int it) { issue(st0, it); }, [&](int it) { issue(st1, it); },
+        [&](int it) { comp(st0, it); }, [&](int it) { comp(st1, it); });
 
   const bool any = lsum > 0.f;
   const float inv = any ? 1.f / lsum : 0.f;
@@ -229,11 +259,9 @@ __global__ __launch_bounds__(kAT) void attn_fwd_bf16(const AttnArgs a) {
 // backward, query side: Delta and dQ for one (batch, head, query block)
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT) void attn_bwd_dq_bf16(const AttnArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  uint16_t* Ks = smem;                          // [64][D+8]
-  uint16_t* Vs = Ks + 64 * (D + 8);             // [64][D+8]
-  uint16_t* Kt = Vs + 64 * (D + 8);             // [D][kTP]
+__global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint16_t st0[2 * 64 * D];   // K tile, V tile
+  __shared__ __attribute__((aligned(1024))) uint16_t st1[2 * 64 * D];
   const int nqb = a.S / 64;
   const int qb = nqb - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -260,41 +288,52 @@ __global__ __launch_bounds__(kAT) void attn_bwd_dq_bf16(const AttnArgs a) {
       part += bf2f(x[e] & 0xFFFFu) * bf2f(y[e] & 0xFFFFu) + bf2f(x[e] >> 16) * bf2f(y[e] >> 16);
   }
   const float delta = part + __shfl_xor(part, 32);
-  if (h2 == 0) a.Delta[stat] = delta;
   const float lse2 = a.LSEin[stat] * kLog2e;
+  if (h2 == 0) {                     // for the key-side kernel: Delta and -LSE in log2 units
+    a.Delta[stat] = delta;
+    a.NegLse2[stat] = -lse2;
+  }
   const float sc = a.scale * kLog2e;
 
+  TileDma<D> dma;
+  dma.init(a.ss);
   f32x16 dq_acc[D / 32];
   zero(dq_acc);
-  for (int it = 0; it < n; ++it) {
-    const int kb = a.col_idx[rs + it];
-    if (a.causal && kb > qb) continue;
-    Tile<D> tk, tv;
-    tile_fetch<D>(tk, a.K + base + (long long)kb * 64 * a.ss, a.ss);
-    tile_fetch<D>(tv, a.V + base + (long long)kb * 64 * a.ss, a.ss);
-    __syncthreads();
-    tile_store_rows<D>(tk, Ks);
-    tile_store_transposed<D>(tk, Kt);
-    tile_store_rows<D>(tv, Vs);
-    __syncthreads();
 
+  auto issue = [&](uint16_t* st, int it) {
+    const long long t0 = base + (long long)a.col_idx[rs + it] * 64 * a.ss;
+    dma.issue(st, a.K + t0);
+    dma.issue(st + 64 * D, a.V + t0);
+  };
+  auto comp = [&](const uint16_t* st, int it) {
+    const int kb = a.col_idx[rs + it];
     f32x16 s_acc[2], dp_acc[2];
     zero(s_acc);
     zero(dp_acc);
-    mma_rows<D>(Ks, qf, s_acc);     // S^T[key][q]
-    mma_rows<D>(Vs, dof, dp_acc);   // dP^T[key][q]
-    const bool diag = a.causal && kb == qb;
+    mma_rows<D>(st, qf, s_acc);              // S^T[key][q]
+    mma_rows<D>(st + 64 * D, dof, dp_acc);   // dP^T[key][q]
+    if (a.causal && kb == qb) {
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
+      for (int half = 0; half < 2; ++half)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
-        float p = __builtin_amdgcn_exp2f(s_acc[half][v] * sc - lse2);
-        if (diag && kl > ql) p = 0.f;
-        s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
-      }
-    mma_transposed<D>(Kt, s_acc, dq_acc);
-  }
+        for (int v = 0; v < 16; ++v) {
+          const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
+          const float p = kl > ql ? 0.f : __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -lse2));
+          s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
+        }
+    } else {
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -lse2));
+          s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
+        }
+    }
+    mma_transposed<D>(st, s_acc, dq_acc);    // dQ^T += K^T dS^T
+  };
+  walk2(n, [&](int it) { issue(st0, it); }, [&](int it) { issue(st1, it); },
+        [&](int it) { comp(st0, it); }, [&](int it) { comp(st1, it); });
   store_acc<D>(dq_acc, a.scale, a.dQ + qoff);
 }
 
@@ -302,14 +341,11 @@ __global__ __launch_bounds__(kAT) void attn_bwd_dq_bf16(const AttnArgs a) {
 // backward, key side: dK and dV for one (batch, head, key block)
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT) void attn_bwd_dkv_bf16(const AttnArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  uint16_t* Qs = smem;                          // [64][D+8]
-  uint16_t* dOs = Qs + 64 * (D + 8);            // [64][D+8]
-  uint16_t* Qt = dOs + 64 * (D + 8);            // [D][kTP]
-  uint16_t* dOt = Qt + D * kTP;                 // [D][kTP]
-  float* lse_s = reinterpret_cast<float*>(dOt + D * kTP);  // [64] (log2 units)
-  float* del_s = lse_s + 64;                               // [64]
+__global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint16_t st0[2 * 64 * D];   // Q tile, dO tile
+  __shared__ __attribute__((aligned(1024))) uint16_t st1[2 * 64 * D];
+  __shared__ __attribute__((aligned(256))) float stat0[128];            // -LSE*log2e [64], Delta [64]
+  __shared__ __attribute__((aligned(256))) float stat1[128];
   const int nkb = a.S / 64;
   const int kb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -320,7 +356,7 @@ __global__ __launch_bounds__(kAT) void attn_bwd_dkv_bf16(const AttnArgs a) {
   if (a.head_active && !a.head_active[h]) n = 0;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long koff = base + (long long)(kb * 64 + kl) * a.ss;
-  const long long stat0 = ((long long)b * a.Hh + h) * a.S;
+  const long long stat_base = ((long long)b * a.Hh + h) * a.S;
 
   uint4 kf[D / 16], vf[D / 16];
 #pragma unroll
@@ -329,83 +365,73 @@ __global__ __launch_bounds__(kAT) void attn_bwd_dkv_bf16(const AttnArgs a) {
     vf[s] = *reinterpret_cast<const uint4*>(a.V + koff + 16 * s + 8 * h2);
   }
   const float sc = a.scale * kLog2e;
+  TileDma<D> dma;
+  dma.init(a.ss);
   f32x16 dk_acc[D / 32], dv_acc[D / 32];
   zero(dk_acc);
   zero(dv_acc);
+  const float* stat_src = wave == 0 ? a.NegLse2 : a.Delta;  // wave 0: -LSE*log2(e), wave 1: Delta
 
-  for (int it = 0; it < n; ++it) {
+  auto issue = [&](uint16_t* st, float* sstat, int it) {
     const int qb = a.ccol_idx[rs + it];
-    if (a.causal && qb < kb) continue;
-    Tile<D> tq, tdo;
-    tile_fetch<D>(tq, a.Q + base + (long long)qb * 64 * a.ss, a.ss);
-    tile_fetch<D>(tdo, a.dO + base + (long long)qb * 64 * a.ss, a.ss);
-    float stat_v = 0.f;
-    if (threadIdx.x < 64) stat_v = a.LSEin[stat0 + qb * 64 + threadIdx.x] * kLog2e;
-    else stat_v = a.Delta[stat0 + qb * 64 + threadIdx.x - 64];
-    __syncthreads();
-    tile_store_rows<D>(tq, Qs);
-    tile_store_transposed<D>(tq, Qt);
-    tile_store_rows<D>(tdo, dOs);
-    tile_store_transposed<D>(tdo, dOt);
-    lse_s[threadIdx.x] = stat_v;   // threads 64..127 land in del_s
-    __syncthreads();
-
+    const long long t0 = base + (long long)qb * 64 * a.ss;
+    dma.issue(st, a.Q + t0);
+    dma.issue(st + 64 * D, a.dO + t0);
+    __builtin_amdgcn_global_load_lds((const LX_AS1 void*)(stat_src + stat_base + qb * 64 + lane),
+                                     (LX_AS3 void*)(sstat + 64 * wave), 4, 0, 0);
+  };
+  auto comp = [&](const uint16_t* st, const float* sstat, int it) {
+    const int qb = a.ccol_idx[rs + it];
     f32x16 s_acc[2], dp_acc[2];
     zero(s_acc);
     zero(dp_acc);
-    mma_rows<D>(Qs, kf, s_acc);     // S[q][key]
-    mma_rows<D>(dOs, vf, dp_acc);   // dP[q][key]
+    mma_rows<D>(st, kf, s_acc);               // S[q][key]
+    mma_rows<D>(st + 64 * D, vf, dp_acc);     // dP[q][key]
     const bool diag = a.causal && kb == qb;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ql = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
-        float p = __builtin_amdgcn_exp2f(s_acc[half][v] * sc - lse_s[ql]);
-        if (diag && kl > ql) p = 0.f;
-        s_acc[half][v] = p;                                   // P
-        dp_acc[half][v] = p * (dp_acc[half][v] - del_s[ql]);  // dS
+      for (int g = 0; g < 4; ++g) {
+        const int q0 = 32 * half + 8 * g + 4 * h2;            // four consecutive queries
+        const float4 nl = *reinterpret_cast<const float4*>(sstat + q0);
+        const float4 dl = *reinterpret_cast<const float4*>(sstat + 64 + q0);
+        const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v = 4 * g + e;
+          float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, nls[e]));
+          if (diag && kl > q0 + e) p = 0.f;
+          s_acc[half][v] = p;                                   // P
+          dp_acc[half][v] = p * (dp_acc[half][v] - dls[e]);     // dS
+        }
       }
-    mma_transposed<D>(dOt, s_acc, dv_acc);
-    mma_transposed<D>(Qt, dp_acc, dk_acc);
-  }
+    mma_transposed<D>(st + 64 * D, s_acc, dv_acc);   // dV^T += dO^T P
+    mma_transposed<D>(st, dp_acc, dk_acc);           // dK^T += Q^T dS
+  };
+  walk2(n, [&](int it) { issue(st0, stat0, it); }, [&](int it) { issue(st1, stat1, it); },
+        [&](int it) { comp(st0, stat0, it); }, [&](int it) { comp(st1, stat1, it); });
   store_acc<D>(dv_acc, 1.f, a.dV + koff);
   store_acc<D>(dk_acc, a.scale, a.dK + koff);
 }
 
 template <int D>
-static size_t fwd_lds() { return (64 * (D + 8) + D * kTP) * 2; }
-template <int D>
-static size_t dq_lds() { return (2 * 64 * (D + 8) + D * kTP) * 2; }
-template <int D>
-static size_t dkv_lds() { return (2 * 64 * (D + 8) + 2 * D * kTP) * 2 + 128 * 4; }
-
-template <int D>
 static hipError_t launch_fwd(const AttnArgs& a, int B, hipStream_t st) {
   ProfScope ps(kKAttnFwd, st);
-  hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), fwd_lds<D>(), st, a);
+  hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), 0, st, a);
   return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_bwd(const AttnArgs& a, int B, hipStream_t st) {
-  static bool attr_set = false;   // raise the dynamic LDS limit once (above 64 KiB for D = 128)
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkv_bf16<D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)dkv_lds<D>());
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   {
     ProfScope ps(kKAttnDq, st);
-    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), dq_lds<D>(), st, a);
+    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   {
     ProfScope ps(kKAttnDkv, st);
-    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), dkv_lds<D>(), st, a);
+    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), 0, st, a);
   }
   return hipGetLastError();
 }

@@ -19,10 +19,25 @@ constexpr int kStageBytes = 32768;  // mask bytes staged in LDS per pass
 // The mask chunk is first copied into LDS with all loads in flight at once (strided or not),
 // because a wavefront that walks rows straight from global memory pays one full memory
 // latency per row; the ballots then run out of LDS.
-__global__ __launch_bounds__(kCompactThreads) void compact_kernel(
-    const uint8_t* __restrict__ mask, int batch, int rows, int cols, long long bstride,
-    long long rstride, long long cstride, int* __restrict__ row_ptr, int* __restrict__ col_idx,
-    int cap) {
+struct CompactJob {
+  const uint8_t* mask;
+  int batch, rows, cols;
+  long long bstride, rstride, cstride;
+  int* row_ptr;
+  int* col_idx;
+  int cap;
+};
+
+// One workgroup per job (blockIdx.x): a launch builds one list, or the row list and the
+// column list of the same masks side by side.
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJob job0,
+                                                                  const CompactJob job1) {
+  const CompactJob& job = blockIdx.x == 0 ? job0 : job1;
+  const uint8_t* __restrict__ mask = job.mask;
+  const int batch = job.batch, rows = job.rows, cols = job.cols, cap = job.cap;
+  const long long bstride = job.bstride, rstride = job.rstride, cstride = job.cstride;
+  int* __restrict__ row_ptr = job.row_ptr;
+  int* __restrict__ col_idx = job.col_idx;
   __shared__ int offs[kChunkRows];
   __shared__ int wave_tot[kCompactWaves];
   __shared__ uint8_t stage[kStageBytes];
@@ -30,6 +45,11 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
   const int total_rows = batch * rows;
   const bool staged = cols <= kStageBytes;
   const int chunk_rows = staged ? max(1, min(kChunkRows, kStageBytes / cols)) : 1;
+  int cp = kWave;                       // columns handled per wave pass (power of two)
+  while (cp > 1 && (cp >> 1) >= cols) cp >>= 1;
+  const int rpw = kWave / cp;           // rows per wave pass
+  const int sub = lane / cp, cl = lane % cp;
+  const unsigned long long field = cp == 64 ? ~0ull : ((1ull << cp) - 1ull);
   int carry = 0;
   for (int chunk = 0; chunk < total_rows; chunk += chunk_rows) {
     const int n = min(chunk_rows, total_rows - chunk);
@@ -48,11 +68,17 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
       return mask[(long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride +
                   (long long)c * cstride] != 0;
     };
-    // 1. per-row counts
-    for (int r = wave; r < n; r += kCompactWaves) {
+    // 1. per-row counts.  A wavefront covers `rpw` rows at once when rows are short
+    //    (cols <= 32): lane l looks at column l % cp of row l / cp, cp = cols rounded up to a
+    //    power of two; each row's bits are a cp-wide field of the 64-bit ballot.
+    for (int r0 = wave * rpw; r0 < n; r0 += kCompactWaves * rpw) {
+      const int r = r0 + sub;
       int cnt = 0;
-      for (int c0 = 0; c0 < cols; c0 += kWave) cnt += __popcll(__ballot(is_on(r, c0 + lane)));
-      if (lane == 0) offs[r] = cnt;
+      for (int c0 = 0; c0 < cols; c0 += cp) {
+        const unsigned long long bits = __ballot(r < n && is_on(r, c0 + cl));
+        cnt += __popcll((bits >> (sub * cp)) & field);
+      }
+      if (cl == 0 && r < n) offs[r] = cnt;
     }
     __syncthreads();
     // 2. exclusive scan of the counts (4 consecutive rows per thread)
@@ -90,16 +116,16 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     }
     __syncthreads();
     // 3. scatter the ascending column indices
-    for (int r = wave; r < n; r += kCompactWaves) {
-      int off = offs[r];
-      for (int c0 = 0; c0 < cols; c0 += kWave) {
-        const int c = c0 + lane;
-        const bool on = is_on(r, c);
-        const unsigned long long bits = __ballot(on);
-        const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(bits >> 32),
-                                                   __builtin_amdgcn_mbcnt_lo((unsigned)bits, 0));
+    for (int r0 = wave * rpw; r0 < n; r0 += kCompactWaves * rpw) {
+      const int r = r0 + sub;
+      int off = r < n ? offs[r] : 0;
+      for (int c0 = 0; c0 < cols; c0 += cp) {
+        const int c = c0 + cl;
+        const bool on = r < n && is_on(r, c);
+        const unsigned long long mine = (__ballot(on) >> (sub * cp)) & field;
+        const int rank = __popcll(mine & ((1ull << cl) - 1ull));
         if (on && off + rank < cap) col_idx[off + rank] = c;
-        off += __popcll(bits);
+        off += __popcll(mine);
       }
     }
     carry += chunk_total;
@@ -111,9 +137,19 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
 hipError_t launch_compact(const uint8_t* mask, int batch, int rows, int cols, long long bs,
                           long long rs, long long cs, int* row_ptr, int* col_idx, int cap,
                           hipStream_t stream) {
+  const CompactJob j = {mask, batch, rows, cols, bs, rs, cs, row_ptr, col_idx, cap};
   ProfScope ps(kKCompact, stream);
-  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kCompactThreads), 0, stream, mask, batch, rows,
-                     cols, bs, rs, cs, row_ptr, col_idx, cap);
+  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kCompactThreads), 0, stream, j, j);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_pair(const uint8_t* mask, int batch, int rows, int cols, long long bs,
+                               long long rs, long long cs, int* row_ptr_r, int* col_idx_r,
+                               int* row_ptr_c, int* col_idx_c, int cap, hipStream_t stream) {
+  const CompactJob jr = {mask, batch, rows, cols, bs, rs, cs, row_ptr_r, col_idx_r, cap};
+  const CompactJob jc = {mask, batch, cols, rows, bs, cs, rs, row_ptr_c, col_idx_c, cap};
+  ProfScope ps(kKCompact, stream);
+  hipLaunchKernelGGL(compact_kernel, dim3(2), dim3(kCompactThreads), 0, stream, jr, jc);
   return hipGetLastError();
 }
 

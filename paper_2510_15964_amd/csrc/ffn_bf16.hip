@@ -12,53 +12,101 @@
 //   dsd  out tile (i, 256 columns) = sum over listed j of Act_ij [64 x 64] .
 //        W[rows n0.., j-block columns]^T: the K loop walks the active list, one
 //        64-wide K-step per active block; inactive blocks are never touched.
-// Global -> register prefetch of K-step s+1 overlaps the MFMA work of step s.
+//
+// Data movement: global memory -> LDS directly (global_load_lds, 16 bytes per
+// lane, no registers in between), two 40 KiB stages; the loads of K-step s+1
+// are in flight while the MFMAs of step s run.  The stages are two separate
+// LDS arrays on purpose: the compiler tracks LDS-DMA writes per array and would
+// otherwise wait for the in-flight stage before every LDS read.
+// LDS rows are 128 bytes, unpadded (a DMA instruction writes 1 KiB = 8 rows
+// contiguously); the 16-byte slots of a row are XOR-swizzled with the row
+// index so that the MFMA operand reads of 16 consecutive rows hit distinct
+// banks.
 #include "lx_dev.h"
 #include "lx_launch.h"
 
 namespace lx {
 
+#define LX_AS1 __attribute__((address_space(1)))
+#define LX_AS3 __attribute__((address_space(3)))
+
 constexpr int kThreads = 256;
-constexpr int kBK = 64;           // K-chunk per step: 64 bf16 = 128 bytes per row
-constexpr int kPitch = kBK + 8;   // LDS row pitch in elements (144 B): conflict-free b128 reads
-constexpr int kRowsB = 64;        // shared operand (token rows)
-constexpr int kRowsA = 256;       // per-wave operand (4 x 64 weight rows)
-constexpr int kSlots = (kRowsA + kRowsB) * 8 / kThreads;  // 16-byte loads per thread per step = 10
+constexpr int kBK = 64;            // K-chunk per step: 64 bf16 = 128 bytes per row
+constexpr int kRowsB = 64;         // shared operand (token rows)
+constexpr int kRowsA = 256;        // per-wave operand (4 x 64 weight rows)
+constexpr int kStageRows = kRowsA + kRowsB;
+constexpr int kStageElems = kStageRows * kBK;                 // 20480 elements = 40 KiB
+constexpr int kIssues = kStageRows / 8 / (kThreads / kWave);  // DMA instructions per wave per stage
 
-struct Stage {
-  uint4 v[kSlots];
-};
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-// slot u of thread tid covers row (tid/8 + 32u) of the combined [B rows | A rows] tile,
-// 16-byte segment tid%8.
-__device__ __forceinline__ void store_stage(const Stage& st, uint16_t* lds) {
-  const int tid = threadIdx.x;
+// One stage = kIssues DMA instructions per wave.  Instruction u of wave w fills stage rows
+// 8g .. 8g+7 with g = w + 4u; lane l brings the 16-byte slot l%8 of row 8g + l/8.
+// src[u] already points at this lane's (row, swizzled segment); offB / offA are the element
+// offsets of the current K-step for the shared rows (u < 2) and the weight rows (u >= 2).
+__device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[kIssues],
+                                            long long offB, long long offA) {
+  const int wave = threadIdx.x / kWave;
 #pragma unroll
-  for (int u = 0; u < kSlots; ++u) {
-    const int row = tid / 8 + 32 * u;
-    *reinterpret_cast<uint4*>(lds + row * kPitch + (tid % 8) * 8) = st.v[u];
+  for (int u = 0; u < kIssues; ++u) {
+    const int g = wave + 4 * u;
+    __builtin_amdgcn_global_load_lds((const LX_AS1 void*)(src[u] + (u < 2 ? offB : offA)),
+                                     (LX_AS3 void*)(stage + g * 512), 16, 0, 0);
   }
 }
 
 // One 64-deep K-step from LDS: wave w multiplies its 64 A rows with the 64 shared B rows.
 // acc[ni][ti]: rows (A operand) 32ni.., columns (B operand) 32ti..
-__device__ __forceinline__ void mma_step(const uint16_t* lds, int wave, f32x16 (&acc)[2][2]) {
+__device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16 (&acc)[2][2]) {
   const int lane = threadIdx.x % kWave;
-  const int r = lane % 32, kq = (lane / 32) * 8;
-  const uint16_t* Bt = lds;
-  const uint16_t* At = lds + (kRowsB + 64 * wave) * kPitch;
+  const int r = lane % 32, h2 = lane / 32;
 #pragma unroll
-  for (int kk = 0; kk < kBK; kk += 16) {
+  for (int kk = 0; kk < 4; ++kk) {
+    const int seg = 2 * kk + h2;
     uint4 a[2], b[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      a[h] = *reinterpret_cast<const uint4*>(At + (32 * h + r) * kPitch + kk + kq);
-      b[h] = *reinterpret_cast<const uint4*>(Bt + (32 * h + r) * kPitch + kk + kq);
+      const int ra = kRowsB + 64 * wave + 32 * h + r, rb = 32 * h + r;
+      a[h] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+      b[h] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
     }
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32(a[ni], b[ti], acc[ni][ti]);
+  }
+}
+
+// Two-stage pipeline over nsteps K-steps.  offs(s, offB, offA) yields the element offsets of
+// step s.  Every wave waits for its own DMA (vmcnt), the barrier then guarantees that the whole
+// stage has landed and that nobody still reads the stage about to be refilled.
+template <class Offs>
+__device__ __forceinline__ void run_pipeline(int nsteps, bool wave_on,
+                                             const uint16_t* const (&src)[kIssues], Offs offs,
+                                             uint16_t* st0, uint16_t* st1, f32x16 (&acc)[2][2]) {
+  const int wave = threadIdx.x / kWave;
+  long long ob, oa;
+  if (nsteps > 0) {
+    offs(0, ob, oa);
+    issue_stage(st0, src, ob, oa);
+  }
+  for (int s = 0; s < nsteps; s += 2) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (s + 1 < nsteps) {
+      offs(s + 1, ob, oa);
+      issue_stage(st1, src, ob, oa);
+    }
+    if (wave_on) mma_step(st0, wave, acc);
+    if (s + 1 < nsteps) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      if (s + 2 < nsteps) {
+        offs(s + 2, ob, oa);
+        issue_stage(st0, src, ob, oa);
+      }
+      if (wave_on) mma_step(st1, wave, acc);
+    }
   }
 }
 
@@ -94,6 +142,15 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   return false;
 }
 
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+}
+
 // MODE 0: out = bf16(max(acc + bias, 0));  MODE 1: out = gate > 0 ? bf16(acc) : 0.
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
@@ -101,7 +158,8 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int rows, int K, uint16_t* __restrict__ out_act,
     const uint16_t* __restrict__ gate_act) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[(kRowsA + kRowsB) * kPitch];
+  __shared__ __attribute__((aligned(1024))) uint16_t st0[kStageElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t st1[kStageElems];
   int i, chunk;
   if (!find_work(row_ptr, rows, blockIdx.x, 4, i, chunk)) return;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
@@ -110,41 +168,26 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   const int p0 = rs + first;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
 
-  // per-slot row base pointers (slot -> block index is a compile-time function of u)
-  const uint16_t* src[kSlots];
+  // per-instruction source pointers of this lane (K offset added per step)
+  const uint16_t* src[kIssues];
 #pragma unroll
-  for (int u = 0; u < kSlots; ++u) {
-    const int row = tid / 8 + 32 * u;
+  for (int u = 0; u < kIssues; ++u) {
+    const int g = wave + 4 * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
     if (u < 2) {
-      src[u] = A + ((long long)i * 64 + row) * K + (tid % 8) * 8;
+      src[u] = A + ((long long)i * 64 + row) * K + seg * 8;
     } else {
       const int blk = (u - 2) / 2, r = row - kRowsB - 64 * blk;
-      src[u] = blk < nb ? W + ((long long)col_idx[p0 + blk] * 64 + r) * K + (tid % 8) * 8 : nullptr;
+      // blocks past the end of the list are filled from the first block (never used)
+      const int j = col_idx[p0 + (blk < nb ? blk : 0)];
+      src[u] = W + ((long long)j * 64 + r) * K + seg * 8;
     }
   }
-  Stage st;
-  auto fetch = [&](int k0) {
-#pragma unroll
-    for (int u = 0; u < kSlots; ++u)
-      st.v[u] = src[u] ? *reinterpret_cast<const uint4*>(src[u] + k0) : make_uint4(0, 0, 0, 0);
-  };
-
   f32x16 acc[2][2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-  fetch(0);
-  for (int k0 = 0; k0 < K; k0 += kBK) {
-    store_stage(st, lds);
-    __syncthreads();
-    if (k0 + kBK < K) fetch(k0 + kBK);
-    if (wave < nb) mma_step(lds, wave, acc);
-    __syncthreads();
-  }
+  zero_acc(acc);
+  run_pipeline(K / kBK, wave < nb, src,
+               [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; }, st0, st1,
+               acc);
   if (wave >= nb) return;
 
   const int p = p0 + wave;
@@ -188,56 +231,34 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int ncols_out, uint16_t* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[(kRowsA + kRowsB) * kPitch];
+  __shared__ __attribute__((aligned(1024))) uint16_t st0[kStageElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t st1[kStageElems];
   const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const bool wave_on = n0 + 64 * wave < ncols_out;
 
-  // slot bases without the per-step block offset
-  long long off[kSlots];
-  bool on[kSlots];
+  const uint16_t* src[kIssues];
 #pragma unroll
-  for (int u = 0; u < kSlots; ++u) {
-    const int row = tid / 8 + 32 * u;
+  for (int u = 0; u < kIssues; ++u) {
+    const int g = wave + 4 * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
     if (u < 2) {
-      off[u] = (long long)row * 64 + (tid % 8) * 8;  // inside the compact 64x64 activation block
-      on[u] = true;
+      src[u] = act + row * 64 + seg * 8;          // inside a compact 64x64 activation block
     } else {
-      const int n = n0 + row - kRowsB;
-      on[u] = n < ncols_out;
-      off[u] = (long long)n * ldw + (tid % 8) * 8;
+      const int n = min(n0 + row - kRowsB, ncols_out - 1);   // rows past the edge: re-read the last
+      src[u] = W + (long long)n * ldw + seg * 8;
     }
   }
-  Stage st;
-  auto fetch = [&](int s) {
-    const int p = rs + s;
-    const long long jcol = (long long)col_idx[p] * 64;
-#pragma unroll
-    for (int u = 0; u < kSlots; ++u) {
-      if (u < 2)
-        st.v[u] = *reinterpret_cast<const uint4*>(act + (long long)p * 4096 + off[u]);
-      else
-        st.v[u] = on[u] ? *reinterpret_cast<const uint4*>(W + off[u] + jcol) : make_uint4(0, 0, 0, 0);
-    }
-  };
-
   f32x16 acc[2][2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-  if (n_i > 0) fetch(0);
-  for (int s = 0; s < n_i; ++s) {
-    store_stage(st, lds);
-    __syncthreads();
-    if (s + 1 < n_i) fetch(s + 1);
-    if (wave_on) mma_step(lds, wave, acc);
-    __syncthreads();
-  }
+  zero_acc(acc);
+  run_pipeline(n_i, wave_on, src,
+               [&](int s, long long& ob, long long& oa) {
+                 const int p = rs + s;
+                 ob = (long long)p * 4096;
+                 oa = (long long)col_idx[p] * 64;
+               },
+               st0, st1, acc);
   if (!wave_on) return;
 
   const int tl = lane % 32, nq = (lane / 32) * 4;

@@ -128,6 +128,21 @@ lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int3
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
+lx_status lx_mask_compact_pair(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
+                               int64_t batch_stride, int64_t row_stride, int64_t col_stride,
+                               int32_t* row_ptr_r, int32_t* col_idx_r, int32_t* row_ptr_c,
+                               int32_t* col_idx_c, int32_t col_idx_cap, void* stream) {
+  if (!mask || !row_ptr_r || !col_idx_r || !row_ptr_c || !col_idx_c) return LX_ERR_INVALID_ARG;
+  if (batch <= 0 || rows <= 0 || cols <= 0 || col_idx_cap <= 0) return LX_ERR_INVALID_ARG;
+  if ((int64_t)batch * rows > (int64_t)1 << 30 || (int64_t)batch * cols > (int64_t)1 << 30)
+    return LX_ERR_INVALID_ARG;
+  if (batch_stride < 0 || row_stride < 0 || col_stride < 0) return LX_ERR_INVALID_ARG;
+  hipError_t e = launch_compact_pair(mask, batch, rows, cols, batch_stride, row_stride, col_stride,
+                                     row_ptr_r, col_idx_r, row_ptr_c, col_idx_c, col_idx_cap,
+                                     (hipStream_t)stream);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
 lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_up,
                               const void* W_down, void* W_up_t, void* W_down_t, void* stream) {
   if (dt != LX_F32 && dt != LX_BF16) return LX_ERR_UNSUPPORTED;
@@ -237,7 +252,7 @@ size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, in
                                           int32_t D) {
   (void)dt; (void)D;
   if (B <= 0 || Hh <= 0 || S <= 0) return 0;
-  return round256((size_t)B * Hh * S * sizeof(float));
+  return 2 * round256((size_t)B * Hh * S * sizeof(float));   // Delta and -LSE*log2(e)
 }
 
 static lx_status check_attn(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
@@ -299,6 +314,7 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
   a.O = (const uint16_t*)O; a.dO = (const uint16_t*)dO; a.LSEin = LSE;
   a.dQ = (uint16_t*)dQ; a.dK = (uint16_t*)dK; a.dV = (uint16_t*)dV;
   a.Delta = (float*)workspace;
+  a.NegLse2 = (float*)((char*)workspace + round256((size_t)B * Hh * S * sizeof(float)));
   a.sb = strides_bhs[0]; a.sh = strides_bhs[1]; a.ss = strides_bhs[2];
   a.row_ptr = bl_rows->row_ptr; a.col_idx = bl_rows->col_idx;
   a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx;

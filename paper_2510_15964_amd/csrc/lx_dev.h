@@ -17,8 +17,12 @@ __device__ __forceinline__ uint32_t f2bf(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return u >> 16;
 }
+// two floats -> packed bfloat16 pair (round to nearest even) in one v_cvt_pk_bf16_f32
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
-  return f2bf(lo) | (f2bf(hi) << 16);
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 __device__ __forceinline__ float bf2f(uint32_t bits16) {
   return __builtin_bit_cast(float, bits16 << 16);

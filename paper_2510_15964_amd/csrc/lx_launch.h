@@ -24,7 +24,7 @@ struct ProfScope {
 struct AttnArgs {
   const uint16_t *Q, *K, *V, *O, *dO;
   uint16_t *Out, *dQ, *dK, *dV;
-  float *LSE, *Delta;
+  float *LSE, *Delta, *NegLse2;
   const float* LSEin;
   long long sb, sh, ss;
   const int *row_ptr, *col_idx;
@@ -36,6 +36,8 @@ struct AttnArgs {
 
 hipError_t launch_compact(const uint8_t*, int, int, int, long long, long long, long long, int*, int*,
                           int, hipStream_t);
+hipError_t launch_compact_pair(const uint8_t*, int, int, int, long long, long long, long long, int*,
+                               int*, int*, int*, int, hipStream_t);
 hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, const float* A,
                           const float* W1, const float* b1, const float* W2, const float* b2,
                           const int* row_ptr, const int* col_idx, float* act_out,

@@ -27,7 +27,7 @@ LX_OK, LX_ERR_INVALID_ARG, LX_ERR_UNSUPPORTED, LX_ERR_WORKSPACE, LX_ERR_RUNTIME 
 LX_F32, LX_BF16 = 0, 1
 
 EXPORTS = (
-    "lx_status_string", "lx_mask_compact", "lx_ffn_pack_weights",
+    "lx_status_string", "lx_mask_compact", "lx_mask_compact_pair", "lx_ffn_pack_weights",
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
@@ -48,6 +48,8 @@ _blp = C.POINTER(lx_blocklist)
 _lib.lx_status_string.restype = C.c_char_p
 _lib.lx_status_string.argtypes = [C.c_int]
 _lib.lx_mask_compact.argtypes = [_vp, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp]
+_lib.lx_mask_compact_pair.argtypes = [_vp, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp,
+                                      _i32, _vp]
 _lib.lx_ffn_pack_weights.argtypes = [C.c_int, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
 for _n in ("lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes"):
     getattr(_lib, _n).restype = _sz
@@ -129,6 +131,24 @@ def lx_mask_compact(mask: torch.Tensor, transpose: bool = False, nnz_cap: int | 
     _check(_lib.lx_mask_compact(_ptr(mask), batch, rows, cols, R * Cc, rs, cs, _ptr(out.row_ptr),
                                 _ptr(out.col_idx), max(cap, 1), _stream()), "lx_mask_compact")
     return out
+
+
+def lx_mask_compact_pair(mask: torch.Tensor, out=None):
+    """Row list and column list of the same masks [..., R, C] in one launch."""
+    assert mask.dtype == torch.uint8 and mask.is_cuda and mask.is_contiguous() and mask.dim() >= 2
+    R, Cc = mask.shape[-2], mask.shape[-1]
+    batch = mask.numel() // (R * Cc)
+    cap = batch * R * Cc
+    if out is None:
+        mk = lambda rows, cols: BlockList(
+            batch * rows, cols, torch.empty(batch * rows + 1, dtype=torch.int32, device=mask.device),
+            torch.empty(cap, dtype=torch.int32, device=mask.device), cap)
+        out = (mk(R, Cc), mk(Cc, R))
+    blr, blc = out
+    _check(_lib.lx_mask_compact_pair(_ptr(mask), batch, R, Cc, R * Cc, Cc, 1, _ptr(blr.row_ptr),
+                                     _ptr(blr.col_idx), _ptr(blc.row_ptr), _ptr(blc.col_idx), cap,
+                                     _stream()), "lx_mask_compact_pair")
+    return blr, blc
 
 
 def lx_ffn_pack_weights(W_up: torch.Tensor, W_down: torch.Tensor):

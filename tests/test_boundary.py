@@ -49,6 +49,12 @@ def test_compact_rejects_bad_arguments(lxmod):
     assert f(FAKE, 1, 4, 4, 16, -4, 1, FAKE, FAKE, 16, None) == lxmod.LX_ERR_INVALID_ARG
 
 
+def test_compact_pair_rejects_bad_arguments(lxmod):
+    f = lxmod._lib.lx_mask_compact_pair
+    assert f(FAKE, 1, 4, 4, 16, 4, 1, FAKE, FAKE, FAKE, None, 16, None) == lxmod.LX_ERR_INVALID_ARG
+    assert f(FAKE, 1, 4, 0, 16, 4, 1, FAKE, FAKE, FAKE, FAKE, 16, None) == lxmod.LX_ERR_INVALID_ARG
+
+
 def _ffn_fwd(lxmod, dt, T, d, F, tt, bn, bl, X=FAKE, ws=None, ws_bytes=0, H=FAKE):
     return lxmod._lib.lx_sparse_ffn_fwd(dt, T, d, F, tt, bn, X, FAKE, None, FAKE, None,
                                         C.byref(bl) if bl is not None else None, FAKE, H, ws,

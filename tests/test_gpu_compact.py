@@ -63,3 +63,22 @@ def test_capacity_smaller_than_count_keeps_row_ptr_exact(lx, oracle):
     assert np.array_equal(row_ptr.cpu().numpy(), rp)
     c = col.cpu().numpy()
     assert np.array_equal(c[:10], ci[:10]) and np.all(c[10:] == -7)
+
+
+def test_pair_matches_single_lists(lx, oracle):
+    import torch
+    rng = np.random.default_rng(9)
+    mask = (rng.random((2, 5, 24, 24)) < 0.35).astype(np.uint8)
+    m = torch.from_numpy(mask).cuda()
+    blr, blc = lx.lx_mask_compact_pair(m)
+    a = lx.lx_mask_compact(m)
+    b = lx.lx_mask_compact(m, transpose=True)
+    torch.cuda.synchronize()
+    nnz = int(mask.sum())
+    for x, y in ((blr, a), (blc, b)):
+        assert torch.equal(x.row_ptr, y.row_ptr) and torch.equal(x.col_idx[:nnz], y.col_idx[:nnz])
+    rp, ci = oracle.mask_compact(mask[1, 3], transpose=True)
+    r0 = (1 * 5 + 3) * 24
+    got_rp = blc.row_ptr.cpu().numpy()[r0:r0 + 25]
+    assert np.array_equal(got_rp - got_rp[0], rp)
+    assert np.array_equal(blc.col_idx.cpu().numpy()[got_rp[0]:got_rp[-1]], ci)
