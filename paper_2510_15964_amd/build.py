@@ -22,6 +22,8 @@ def build(verbose: bool = False) -> str:
     err = "\n".join(l for l in r.stderr.splitlines()
                     if "not a recognized feature" not in l)
     if r.returncode != 0:
+        if os.path.exists(LIB):
+            os.remove(LIB)          # never leave a stale library behind a failed build
         raise RuntimeError("hipcc failed:\n" + err)
     if err.strip():
         sys.stderr.write(err + "\n")

@@ -14,8 +14,8 @@
 //        64-wide K-step per active block; inactive blocks are never touched.
 //
 // Data movement: global memory -> LDS directly (global_load_lds, 16 bytes per
-// lane, no registers in between), two 40 KiB stages; the loads of K-step s+1
-// are in flight while the MFMAs of step s run.  The stages are two separate
+// lane, no registers in between), three 40 KiB stages; the loads of K-steps s+1
+// and s+2 are in flight while the MFMAs of step s run.  The stages are separate
 // LDS arrays on purpose: the compiler tracks LDS-DMA writes per array and would
 // otherwise wait for the in-flight stage before every LDS read.
 // LDS rows are 128 bytes, unpadded (a DMA instruction writes 1 KiB = 8 rows
@@ -46,13 +46,9 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 // offsets of the current K-step for the shared rows (u < 2) and the weight rows (u >= 2).
 __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[kIssues],
                                             long long offB, long long offA) {
-  const int wave = threadIdx.x / kWave;
+  const uint32_t base = lds_addr(stage) + (threadIdx.x / kWave) * 1024;
 #pragma unroll
-  for (int u = 0; u < kIssues; ++u) {
-    const int g = wave + 4 * u;
-    __builtin_amdgcn_global_load_lds((const LX_AS1 void*)(src[u] + (u < 2 ? offB : offA)),
-                                     (LX_AS3 void*)(stage + g * 512), 16, 0, 0);
-  }
+  for (int u = 0; u < kIssues; ++u) dma16(src[u] + (u < 2 ? offB : offA), base + u * 4096);
 }
 
 // One 64-deep K-step from LDS: wave w multiplies its 64 A rows with the 64 shared B rows.
@@ -60,64 +56,120 @@ __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* con
 __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16 (&acc)[2][2]) {
   const int lane = threadIdx.x % kWave;
   const int r = lane % 32, h2 = lane / 32;
+  // all 16 operand reads of the step are issued first, so that their LDS latency overlaps
+  // the MFMAs instead of being paid once per k16 slice
+  uint4 a[4][2], b[4][2];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     const int seg = 2 * kk + h2;
-    uint4 a[2], b[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int ra = kRowsB + 64 * wave + 32 * h + r, rb = 32 * h + r;
-      a[h] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
-      b[h] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
+      a[kk][h] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+      b[kk][h] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
     }
+  }
+  __builtin_amdgcn_sched_barrier(0);   // keep the reads above: the scheduler would sink them
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32(a[ni], b[ti], acc[ni][ti]);
-  }
+      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32(a[kk][ni], b[kk][ti], acc[ni][ti]);
 }
 
-// Two-stage pipeline over nsteps K-steps.  offs(s, offB, offA) yields the element offsets of
-// step s.  Every wave waits for its own DMA (vmcnt), the barrier then guarantees that the whole
-// stage has landed and that nobody still reads the stage about to be refilled.
+// Three-stage pipeline over nsteps K-steps: while step s is multiplied, the DMA of steps s+1
+// and s+2 is in flight.  offs(s, offB, offA) yields the element offsets of step s.  A wave
+// first waits until its own DMA of step s has landed (its loads retire in order, so at most the
+// kIssues loads of step s+1 may still be outstanding), the barrier then guarantees that the
+// whole stage is there and that nobody still reads the stage about to be refilled.
+__device__ __forceinline__ void wait_stage(bool next_in_flight) {
+  if (next_in_flight)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kIssues);   // vmcnt(kIssues), kIssues < 16
+  else
+    __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0)
+  lds_barrier();
+}
+
 template <class Offs>
 __device__ __forceinline__ void run_pipeline(int nsteps, bool wave_on,
                                              const uint16_t* const (&src)[kIssues], Offs offs,
-                                             uint16_t* st0, uint16_t* st1, f32x16 (&acc)[2][2]) {
+                                             uint16_t* st0, uint16_t* st1, uint16_t* st2,
+                                             f32x16 (&acc)[2][2]) {
+  static_assert(kIssues < 16, "vmcnt immediate");
   const int wave = threadIdx.x / kWave;
   long long ob, oa;
-  if (nsteps > 0) {
-    offs(0, ob, oa);
-    issue_stage(st0, src, ob, oa);
-  }
-  for (int s = 0; s < nsteps; s += 2) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
-    if (s + 1 < nsteps) {
-      offs(s + 1, ob, oa);
-      issue_stage(st1, src, ob, oa);
-    }
+  auto issue = [&](uint16_t* st, int s) {
+    offs(s, ob, oa);
+    issue_stage(st, src, ob, oa);
+  };
+  if (nsteps > 0) issue(st0, 0);
+  if (nsteps > 1) issue(st1, 1);
+  for (int s = 0; s < nsteps; s += 3) {
+    wait_stage(s + 1 < nsteps);
+    if (s + 2 < nsteps) issue(st2, s + 2);
     if (wave_on) mma_step(st0, wave, acc);
     if (s + 1 < nsteps) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-      if (s + 2 < nsteps) {
-        offs(s + 2, ob, oa);
-        issue_stage(st0, src, ob, oa);
-      }
+      wait_stage(s + 2 < nsteps);
+      if (s + 3 < nsteps) issue(st0, s + 3);
+      if (wave_on) mma_step(st1, wave, acc);
+    }
+    if (s + 2 < nsteps) {
+      wait_stage(s + 3 < nsteps);
+      if (s + 4 < nsteps) issue(st1, s + 4);
+      if (wave_on) mma_step(st2, wave, acc);
+    }
+  }
+}
+
+// Two-stage variant (80 KiB of LDS, two workgroups per CU): used where the grid is large
+// enough that a second resident workgroup hides latency better than a third stage.
+template <class Offs>
+__device__ __forceinline__ void run_pipeline2(int nsteps, bool wave_on,
+                                              const uint16_t* const (&src)[kIssues], Offs offs,
+                                              uint16_t* st0, uint16_t* st1, f32x16 (&acc)[2][2]) {
+  const int wave = threadIdx.x / kWave;
+  long long ob, oa;
+  auto issue = [&](uint16_t* st, int s) {
+    offs(s, ob, oa);
+    issue_stage(st, src, ob, oa);
+  };
+  if (nsteps > 0) issue(st0, 0);
+  for (int s = 0; s < nsteps; s += 2) {
+    wait_stage(false);
+    if (s + 1 < nsteps) issue(st1, s + 1);
+    if (wave_on) mma_step(st0, wave, acc);
+    if (s + 1 < nsteps) {
+      wait_stage(false);
+      if (s + 2 < nsteps) issue(st0, s + 2);
       if (wave_on) mma_step(st1, wave, acc);
     }
   }
 }
 
 // Work items of the sdd kernel are (token tile, group of `per` consecutive list entries),
-// numbered in list order.  The launch grid is the host-known upper bound on their number;
-// every wavefront finds its item from row_ptr with a 64-wide scan, so that the active
-// workgroups are the FIRST ones of the grid and spread evenly over XCDs, shader engines and
-// CUs (a 2-D grid with early exits piles them onto a few CUs).  Returns false past the end.
-__device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int work,
+// numbered in list order.  The launch grid is the host-known upper bound on their number and
+// every wavefront finds its item from row_ptr with 64-wide scans, so the active workgroups are
+// the FIRST ones of the grid and spread evenly over shader engines and CUs (a 2-D grid with
+// early exits piles them onto a few CUs).  Workgroup w runs on XCD w % 8; it takes item
+// (w % 8) * L + w / 8 with L = ceil(total / 8), so each XCD owns a contiguous range of items,
+// i.e. of token tiles: a tile's activations are fetched into one L2 only, and the weight
+// blocks an XCD needs are those of one eighth of the tiles.  Returns false past the end.
+__device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int w,
                                           int per, int& row, int& chunk) {
   const int lane = threadIdx.x % kWave;
+  int total = 0;
+  for (int base = 0; base < rows; base += kWave) {
+    const int r = base + lane;
+    int c = 0;
+    if (r < rows) c = (row_ptr[r + 1] - row_ptr[r] + per - 1) / per;
+#pragma unroll
+    for (int dlt = 32; dlt > 0; dlt >>= 1) c += __shfl_xor(c, dlt);
+    total += c;
+  }
+  const int L = (total + 7) / 8;
+  const int slot = w / 8, work = (w % 8) * L + slot;
+  if (slot >= L || work >= total) return false;
   int running = 0;
   for (int base = 0; base < rows; base += kWave) {
     const int r = base + lane;
@@ -129,15 +181,15 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
       const int up = __shfl_up(incl, dlt);
       if (lane >= dlt) incl += up;
     }
-    const int total = __shfl(incl, kWave - 1);
-    if (work < running + total) {
+    const int seg = __shfl(incl, kWave - 1);
+    if (work < running + seg) {
       const unsigned long long hit = __ballot(running + incl > work);
       const int first = __ffsll((long long)hit) - 1;
       row = base + first;
       chunk = work - running - __shfl(incl - c, first);
       return true;
     }
-    running += total;
+    running += seg;
   }
   return false;
 }
@@ -160,6 +212,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ gate_act) {
   __shared__ __attribute__((aligned(1024))) uint16_t st0[kStageElems];
   __shared__ __attribute__((aligned(1024))) uint16_t st1[kStageElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t st2[kStageElems];
   int i, chunk;
   if (!find_work(row_ptr, rows, blockIdx.x, 4, i, chunk)) return;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
@@ -187,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   zero_acc(acc);
   run_pipeline(K / kBK, wave < nb, src,
                [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; }, st0, st1,
-               acc);
+               st2, acc);
   if (wave >= nb) return;
 
   const int p = p0 + wave;
@@ -252,7 +305,7 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   }
   f32x16 acc[2][2];
   zero_acc(acc);
-  run_pipeline(n_i, wave_on, src,
+  run_pipeline2(n_i, wave_on, src,
                [&](int s, long long& ob, long long& oa) {
                  const int p = rs + s;
                  ob = (long long)p * 4096;
@@ -294,7 +347,7 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st) {
   (void)Fb;
-  const dim3 g1(nnz_cap / 4 + Tt);   // >= sum over rows of ceil(n_i / 4)
+  const dim3 g1((nnz_cap / 4 + Tt + 7) / 8 * 8);   // >= 8 * ceil(sum_i ceil(n_i / 4) / 8)
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)

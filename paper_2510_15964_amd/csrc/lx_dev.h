@@ -36,4 +36,24 @@ __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// Asynchronous 16-byte-per-lane copy global -> LDS (global_load_lds_dwordx4): lane l of the
+// wave lands at lds_wave_base + 16*l; completion is counted by vmcnt.  Issued as assembly so
+// that the waits are entirely under the kernel's control: for DMA it knows about, the compiler
+// conservatively drains vmcnt before LDS reads and barriers, which defeats multi-stage
+// pipelining.  Callers pair it with explicit s_waitcnt vmcnt(N) + barrier before reading.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
+  const uint32_t l = __builtin_amdgcn_readfirstlane(lds_wave_base);   // must be a scalar register
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gptr)
+               : "memory");
+}
+// Byte address of an LDS object as a wave-uniform scalar (operand of dma16).
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p);
+}
+// LDS-only barrier: waits for this wave's LDS traffic, not for DMA still in flight.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 }  // namespace lx
