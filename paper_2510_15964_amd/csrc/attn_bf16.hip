@@ -38,6 +38,8 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 typedef short short4v __attribute__((ext_vector_type(4)));
+struct TrueTag { static constexpr bool value = true; };
+struct FalseTag { static constexpr bool value = false; };
 
 template <int D>
 __device__ __forceinline__ int tswz(int row) {
@@ -78,6 +80,7 @@ template <int D>
 __device__ __forceinline__ void mma_rows(const uint16_t* tile, const uint4 (&frag)[D / 16],
                                          f32x16 (&acc)[2]) {
   const int lane = threadIdx.x % kWave, r = lane % 32, h2 = lane / 32;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     const int row = 32 * half + r;
@@ -85,10 +88,33 @@ __device__ __forceinline__ void mma_rows(const uint16_t* tile, const uint4 (&fra
     for (int s = 0; s < D / 16; ++s) {
       const uint4 a = *reinterpret_cast<const uint4*>(tile + row * D +
                                                       (((2 * s + h2) ^ tswz<D>(row)) << 3));
-      acc[half] = mfma32(a, frag[s], acc[half]);
+      // the first product starts from a literal zero (no register clearing); acc is overwritten
+      acc[half] = mfma32(a, frag[s], s == 0 ? zero16 : acc[half]);
     }
   }
 }
+
+// One row of a block list, kept in a register (entry it of the row sits in lane it % 64), so the
+// walk over the list issues no memory loads: a load inside the pipelined loop would have to wait
+// on vmcnt and with it on the tile DMA that is deliberately left in flight.
+struct ListRow {
+  const int* p;
+  int n, chunk, cur;
+  __device__ __forceinline__ void init(const int* list, int n_) {
+    p = list;
+    n = n_;
+    chunk = -1;
+    cur = 0;
+  }
+  __device__ __forceinline__ int get(int it) {        // it is wave-uniform
+    if ((it >> 6) != chunk) {                         // only for rows longer than 64 entries
+      chunk = it >> 6;
+      const int i = chunk * 64 + (int)(threadIdx.x % kWave);
+      cur = i < n ? p[i] : 0;
+    }
+    return __builtin_amdgcn_readlane(cur, it & 63);
+  }
+};
 
 // out[ct] += T^T . P   where T is a row-major [64 x D] tile in LDS (read transposed) and
 // p[half][v] the accumulator-layout values of the [64 x 32] factor (rounded to bf16 here).
@@ -169,7 +195,7 @@ __device__ __forceinline__ void walk2(int n, I0 issue0, I1 issue1, C0 comp0, C1 
 // forward: O, LSE for one (batch, head, query block)
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_fwd_bf16(const AttnArgs a) {
+__global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t st0[2 * 64 * D];   // K tile, V tile
   __shared__ __attribute__((aligned(1024))) uint16_t st1[2 * 64 * D];
   const int nqb = a.S / 64;
@@ -195,32 +221,31 @@ __global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_fwd_bf16(const Attn
   float m = -INFINITY, lsum = 0.f;
   const float sc = a.scale * kLog2e;
 
+  ListRow list;
+  list.init(a.col_idx + rs, n);
   auto issue = [&](uint16_t* st, int it) {
-    const long long t0 = base + (long long)a.col_idx[rs + it] * 64 * a.ss;
+    const long long t0 = base + (long long)list.get(it) * 64 * a.ss;
     dma.issue(st, a.K + t0);
     dma.issue(st + 64 * D, a.V + t0);
   };
-  auto comp = [&](const uint16_t* st, int it) {
-    const int kb = a.col_idx[rs + it];
+  // DIAG: the diagonal block of a causal mask, where keys after the query are excluded.  Two
+  // separate instantiations (instead of a branch in the middle) keep the 32 score registers in
+  // place on both paths.
+  auto comp_body = [&](const uint16_t* st, auto diag_tag) {
+    constexpr bool DIAG = decltype(diag_tag)::value;
     f32x16 s_acc[2];
-    zero(s_acc);
     mma_rows<D>(st, qf, s_acc);           // S^T[key][q]
     float mloc = -INFINITY;
-    if (a.causal && kb == qb) {           // diagonal block: keys after the query are excluded
 #pragma unroll
-      for (int half = 0; half < 2; ++half)
+    for (int half = 0; half < 2; ++half)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
+      for (int v = 0; v < 16; ++v) {
+        if (DIAG) {
           const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
           if (kl > ql) s_acc[half][v] = -INFINITY;
-          mloc = fmaxf(mloc, s_acc[half][v]);
         }
-    } else {
-#pragma unroll
-      for (int half = 0; half < 2; ++half)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, s_acc[half][v]);
-    }
+        mloc = fmaxf(mloc, s_acc[half][v]);
+      }
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
     const float m_new = fmaxf(m, mloc * sc);          // running max in scaled log2 units
     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
@@ -243,6 +268,12 @@ __global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_fwd_bf16(const Attn
         for (int v = 0; v < 16; ++v) o_acc[ct][v] *= alpha;
     }
     mma_transposed<D>(st + 64 * D, s_acc, o_acc);   // O^T += V^T P^T
+  };
+  auto comp = [&](const uint16_t* st, int it) {
+    if (a.causal && list.get(it) == qb)
+      comp_body(st, TrueTag{});
+    else
+      comp_body(st, FalseTag{});
   };
   walk2(n, [&](int it) { issue(st0, it); }, [&](int it) { issue(st1, it); },
         [&](int it) { comp(st0, it); }, [&](int it) { comp(st1, it); });
@@ -300,37 +331,36 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const A
   f32x16 dq_acc[D / 32];
   zero(dq_acc);
 
+  ListRow list;
+  list.init(a.col_idx + rs, n);
   auto issue = [&](uint16_t* st, int it) {
-    const long long t0 = base + (long long)a.col_idx[rs + it] * 64 * a.ss;
+    const long long t0 = base + (long long)list.get(it) * 64 * a.ss;
     dma.issue(st, a.K + t0);
     dma.issue(st + 64 * D, a.V + t0);
   };
-  auto comp = [&](const uint16_t* st, int it) {
-    const int kb = a.col_idx[rs + it];
+  auto comp_body = [&](const uint16_t* st, auto diag_tag) {
+    constexpr bool DIAG = decltype(diag_tag)::value;
     f32x16 s_acc[2], dp_acc[2];
-    zero(s_acc);
-    zero(dp_acc);
     mma_rows<D>(st, qf, s_acc);              // S^T[key][q]
     mma_rows<D>(st + 64 * D, dof, dp_acc);   // dP^T[key][q]
-    if (a.causal && kb == qb) {
 #pragma unroll
-      for (int half = 0; half < 2; ++half)
+    for (int half = 0; half < 2; ++half)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
+      for (int v = 0; v < 16; ++v) {
+        float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -lse2));
+        if (DIAG) {
           const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
-          const float p = kl > ql ? 0.f : __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -lse2));
-          s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
+          if (kl > ql) p = 0.f;
         }
-    } else {
-#pragma unroll
-      for (int half = 0; half < 2; ++half)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -lse2));
-          s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
-        }
-    }
+        s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
+      }
     mma_transposed<D>(st, s_acc, dq_acc);    // dQ^T += K^T dS^T
+  };
+  auto comp = [&](const uint16_t* st, int it) {
+    if (a.causal && list.get(it) == qb)
+      comp_body(st, TrueTag{});
+    else
+      comp_body(st, FalseTag{});
   };
   walk2(n, [&](int it) { issue(st0, it); }, [&](int it) { issue(st1, it); },
         [&](int it) { comp(st0, it); }, [&](int it) { comp(st1, it); });
@@ -372,22 +402,21 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
   zero(dv_acc);
   const float* stat_src = wave == 0 ? a.NegLse2 : a.Delta;  // wave 0: -LSE*log2(e), wave 1: Delta
 
+  ListRow list;
+  list.init(a.ccol_idx + rs, n);
   auto issue = [&](uint16_t* st, float* sstat, int it) {
-    const int qb = a.ccol_idx[rs + it];
+    const int qb = list.get(it);
     const long long t0 = base + (long long)qb * 64 * a.ss;
     dma.issue(st, a.Q + t0);
     dma.issue(st + 64 * D, a.dO + t0);
     __builtin_amdgcn_global_load_lds((const LX_AS1 void*)(stat_src + stat_base + qb * 64 + lane),
                                      (LX_AS3 void*)(sstat + 64 * wave), 4, 0, 0);
   };
-  auto comp = [&](const uint16_t* st, const float* sstat, int it) {
-    const int qb = a.ccol_idx[rs + it];
+  auto comp_body = [&](const uint16_t* st, const float* sstat, auto diag_tag) {
+    constexpr bool DIAG = decltype(diag_tag)::value;
     f32x16 s_acc[2], dp_acc[2];
-    zero(s_acc);
-    zero(dp_acc);
     mma_rows<D>(st, kf, s_acc);               // S[q][key]
     mma_rows<D>(st + 64 * D, vf, dp_acc);     // dP[q][key]
-    const bool diag = a.causal && kb == qb;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -400,13 +429,19 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
         for (int e = 0; e < 4; ++e) {
           const int v = 4 * g + e;
           float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, nls[e]));
-          if (diag && kl > q0 + e) p = 0.f;
+          if (DIAG && kl > q0 + e) p = 0.f;
           s_acc[half][v] = p;                                   // P
           dp_acc[half][v] = p * (dp_acc[half][v] - dls[e]);     // dS
         }
       }
     mma_transposed<D>(st + 64 * D, s_acc, dv_acc);   // dV^T += dO^T P
     mma_transposed<D>(st, dp_acc, dk_acc);           // dK^T += Q^T dS
+  };
+  auto comp = [&](const uint16_t* st, const float* sstat, int it) {
+    if (a.causal && list.get(it) == kb)
+      comp_body(st, sstat, TrueTag{});
+    else
+      comp_body(st, sstat, FalseTag{});
   };
   walk2(n, [&](int it) { issue(st0, stat0, it); }, [&](int it) { issue(st1, stat1, it); },
         [&](int it) { comp(st0, stat0, it); }, [&](int it) { comp(st1, stat1, it); });
