@@ -208,6 +208,13 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const Attn
   if (a.head_active && !a.head_active[h]) n = 0;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long qoff = base + (long long)(qb * 64 + ql) * a.ss;
+  if (n == 0) {   // no listed block (or inactive head): O = 0, LSE = -inf, nothing to read
+    f32x16 z[D / 32];
+    zero(z);
+    store_acc<D>(z, 0.f, a.Out + qoff);
+    if (h2 == 0) a.LSE[((long long)b * a.Hh + h) * a.S + qb * 64 + ql] = -INFINITY;
+    return;
+  }
 
   uint4 qf[D / 16];
 #pragma unroll
@@ -304,6 +311,16 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const A
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long qoff = base + (long long)(qb * 64 + ql) * a.ss;
   const long long stat = ((long long)b * a.Hh + h) * a.S + qb * 64 + ql;
+  if (n == 0) {   // no listed block (or inactive head): O = 0, hence Delta = 0 and dQ = 0
+    f32x16 z[D / 32];
+    zero(z);
+    store_acc<D>(z, 0.f, a.dQ + qoff);
+    if (h2 == 0) {
+      a.Delta[stat] = 0.f;
+      a.NegLse2[stat] = INFINITY;
+    }
+    return;
+  }
 
   uint4 qf[D / 16], dof[D / 16];
   float part = 0.f;
@@ -387,6 +404,13 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long koff = base + (long long)(kb * 64 + kl) * a.ss;
   const long long stat_base = ((long long)b * a.Hh + h) * a.S;
+  if (n == 0) {   // key block used by no query block: zero gradients, nothing to read
+    f32x16 z[D / 32];
+    zero(z);
+    store_acc<D>(z, 0.f, a.dV + koff);
+    store_acc<D>(z, 0.f, a.dK + koff);
+    return;
+  }
 
   uint4 kf[D / 16], vf[D / 16];
 #pragma unroll

@@ -46,6 +46,18 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) 
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gptr)
                : "memory");
 }
+// Same with 4 bytes per lane (lane l lands at lds_wave_base + 4*l).
+__device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_wave_base) {
+  const uint32_t l = __builtin_amdgcn_readfirstlane(lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(l), "v"(gptr)
+               : "memory");
+}
+// s_waitcnt vmcnt(N) alone (expcnt / lgkmcnt left open); N < 64.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 // Byte address of an LDS object as a wave-uniform scalar (operand of dma16).
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return __builtin_amdgcn_readfirstlane(
