@@ -96,7 +96,6 @@ class FfnJob:
 
     def run(self):
         lx = self.lx
-        lx.lx_mask_compact(self.mask, out=self.bl)
         lx.lx_sparse_ffn_fwd(self.X, self.Wu, self.Wd, self.bl_run, 64, 64, self.Y, self.H_act)
         lx.lx_sparse_ffn_bwd_dx(self.dY, self.H_act, self.Wu, self.Wd, self.bl_run, 64, 64, self.dX,
                                 self.ws, W_up_t=self.Wut, W_down_t=self.Wdt)
@@ -138,7 +137,6 @@ class AttnJob:
 
     def run(self):
         lx, a = self.lx, self.a
-        lx.lx_mask_compact_pair(self.mask, out=(self.bl_r, self.bl_c))
         lx.lx_sparse_attn_fwd(self.Q, self.K, self.V, self.bl_r, a["scale"], a["causal"], self.O,
                               self.LSE, mask_batch=a["mask_batch"], head_active=self.ha)
         lx.lx_sparse_attn_bwd_dx(self.Q, self.K, self.V, self.O, self.LSE, self.dO, self.bl_r,
@@ -171,7 +169,7 @@ def kernel_model(lx, ffn_jobs, attn):
         lx.LX_K_ATTN_FWD: (1, attn.flops(2), 4 * u + stat),
         lx.LX_K_ATTN_BWD_DQ: (1, attn.flops(3), 6 * u + 2 * stat),
         lx.LX_K_ATTN_BWD_DKV: (1, attn.flops(4), 6 * u + 2 * stat),
-        lx.LX_K_COMPACT: (n + 1, 0.0, 0.0),
+        lx.LX_K_COMPACT: (1, 0.0, 0.0),
     }
 
 
@@ -228,7 +226,14 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     tokens = a["B"] * a["S"]
     assert tokens == f["T"], "FFN and attention halves cover the same tokens"
 
+    # all masks of the step (FFN token-tile masks, attention row and column lists): one launch
+    cb = lx.CompactBatch()
+    for j in ffn_jobs:
+        cb.add(j.mask, j.bl)
+    cb.add(attn.mask, attn.bl_r).add(attn.mask, attn.bl_c, transpose=True)
+
     def step():
+        lx.lx_mask_compact_batch(cb)
         for j in ffn_jobs:
             j.run()
         attn.run()

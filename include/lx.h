@@ -114,6 +114,22 @@ lx_status lx_mask_compact_pair(const uint8_t* mask, int32_t batch, int32_t rows,
                                int32_t* col_idx_c, int32_t col_idx_cap, void* stream);
 
 /*
+ * Several independent compactions in ONE launch (all masks of a layer step: the
+ * FFN token-tile masks and both attention lists), one workgroup per job.  Each
+ * job has the meaning of one lx_mask_compact call.  `jobs` is a HOST array of
+ * 1..8 entries holding DEVICE pointers; it is copied into the launch.
+ */
+typedef struct {
+  const uint8_t* mask;
+  int32_t batch, rows, cols;
+  int64_t batch_stride, row_stride, col_stride;
+  int32_t* row_ptr;
+  int32_t* col_idx;
+  int32_t col_idx_cap;
+} lx_compact_job;
+lx_status lx_mask_compact_batch(const lx_compact_job* jobs, int32_t n_jobs, void* stream);
+
+/*
  * One-time repack of the frozen weights (Sec. VI-B "memory coalescing": each
  * product reads its weights along the contiguous dimension).  Writes the
  * transposes W_up_t[d,F] = W_up[F,d]^T and W_down_t[F,d] = W_down[d,F]^T, which

@@ -19,20 +19,16 @@ constexpr int kStageBytes = 32768;  // mask bytes staged in LDS per pass
 // The mask chunk is first copied into LDS with all loads in flight at once (strided or not),
 // because a wavefront that walks rows straight from global memory pays one full memory
 // latency per row; the ballots then run out of LDS.
-struct CompactJob {
-  const uint8_t* mask;
-  int batch, rows, cols;
-  long long bstride, rstride, cstride;
-  int* row_ptr;
-  int* col_idx;
-  int cap;
+
+constexpr int kMaxJobs = 8;
+struct CompactJobs {
+  CompactJob j[kMaxJobs];
 };
 
-// One workgroup per job (blockIdx.x): a launch builds one list, or the row list and the
-// column list of the same masks side by side.
-__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJob job0,
-                                                                  const CompactJob job1) {
-  const CompactJob& job = blockIdx.x == 0 ? job0 : job1;
+// One workgroup per job (blockIdx.x): a launch builds one list, the row list and the column
+// list of the same masks, or the lists of several independent masks side by side.
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJobs jobs) {
+  const CompactJob& job = jobs.j[blockIdx.x];
   const uint8_t* __restrict__ mask = job.mask;
   const int batch = job.batch, rows = job.rows, cols = job.cols, cap = job.cap;
   const long long bstride = job.bstride, rstride = job.rstride, cstride = job.cstride;
@@ -134,23 +130,27 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   if (tid == 0) row_ptr[total_rows] = carry;
 }
 
+hipError_t launch_compact_jobs(const CompactJob* jobs, int n, hipStream_t stream) {
+  CompactJobs js = {};
+  for (int i = 0; i < n; ++i) js.j[i] = jobs[i];
+  ProfScope ps(kKCompact, stream);
+  hipLaunchKernelGGL(compact_kernel, dim3(n), dim3(kCompactThreads), 0, stream, js);
+  return hipGetLastError();
+}
+
 hipError_t launch_compact(const uint8_t* mask, int batch, int rows, int cols, long long bs,
                           long long rs, long long cs, int* row_ptr, int* col_idx, int cap,
                           hipStream_t stream) {
   const CompactJob j = {mask, batch, rows, cols, bs, rs, cs, row_ptr, col_idx, cap};
-  ProfScope ps(kKCompact, stream);
-  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kCompactThreads), 0, stream, j, j);
-  return hipGetLastError();
+  return launch_compact_jobs(&j, 1, stream);
 }
 
 hipError_t launch_compact_pair(const uint8_t* mask, int batch, int rows, int cols, long long bs,
                                long long rs, long long cs, int* row_ptr_r, int* col_idx_r,
                                int* row_ptr_c, int* col_idx_c, int cap, hipStream_t stream) {
-  const CompactJob jr = {mask, batch, rows, cols, bs, rs, cs, row_ptr_r, col_idx_r, cap};
-  const CompactJob jc = {mask, batch, cols, rows, bs, cs, rs, row_ptr_c, col_idx_c, cap};
-  ProfScope ps(kKCompact, stream);
-  hipLaunchKernelGGL(compact_kernel, dim3(2), dim3(kCompactThreads), 0, stream, jr, jc);
-  return hipGetLastError();
+  const CompactJob j[2] = {{mask, batch, rows, cols, bs, rs, cs, row_ptr_r, col_idx_r, cap},
+                           {mask, batch, cols, rows, bs, cs, rs, row_ptr_c, col_idx_c, cap}};
+  return launch_compact_jobs(j, 2, stream);
 }
 
 }  // namespace lx

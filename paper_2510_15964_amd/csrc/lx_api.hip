@@ -143,6 +143,21 @@ lx_status lx_mask_compact_pair(const uint8_t* mask, int32_t batch, int32_t rows,
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
+lx_status lx_mask_compact_batch(const lx_compact_job* jobs, int32_t n_jobs, void* stream) {
+  if (!jobs || n_jobs <= 0 || n_jobs > 8) return LX_ERR_INVALID_ARG;
+  CompactJob cj[8];
+  for (int i = 0; i < n_jobs; ++i) {
+    const lx_compact_job& j = jobs[i];
+    if (!j.mask || !j.row_ptr || !j.col_idx) return LX_ERR_INVALID_ARG;
+    if (j.batch <= 0 || j.rows <= 0 || j.cols <= 0 || j.col_idx_cap <= 0) return LX_ERR_INVALID_ARG;
+    if ((int64_t)j.batch * j.rows > (int64_t)1 << 30) return LX_ERR_INVALID_ARG;
+    if (j.batch_stride < 0 || j.row_stride < 0 || j.col_stride < 0) return LX_ERR_INVALID_ARG;
+    cj[i] = {j.mask, j.batch, j.rows, j.cols, j.batch_stride, j.row_stride, j.col_stride,
+             j.row_ptr, j.col_idx, j.col_idx_cap};
+  }
+  return launch_compact_jobs(cj, n_jobs, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
 lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_up,
                               const void* W_down, void* W_up_t, void* W_down_t, void* stream) {
   if (dt != LX_F32 && dt != LX_BF16) return LX_ERR_UNSUPPORTED;

@@ -36,6 +36,16 @@ struct AttnArgs {
 
 hipError_t launch_compact(const uint8_t*, int, int, int, long long, long long, long long, int*, int*,
                           int, hipStream_t);
+// One compaction job: `batch` masks of rows x cols bytes -> one list (see lx_mask_compact).
+struct CompactJob {
+  const uint8_t* mask;
+  int batch, rows, cols;
+  long long bstride, rstride, cstride;
+  int* row_ptr;
+  int* col_idx;
+  int cap;
+};
+hipError_t launch_compact_jobs(const CompactJob* jobs, int n, hipStream_t stream);
 hipError_t launch_compact_pair(const uint8_t*, int, int, int, long long, long long, long long, int*,
                                int*, int*, int*, int, hipStream_t);
 hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, const float* A,

@@ -27,7 +27,7 @@ LX_OK, LX_ERR_INVALID_ARG, LX_ERR_UNSUPPORTED, LX_ERR_WORKSPACE, LX_ERR_RUNTIME 
 LX_F32, LX_BF16 = 0, 1
 
 EXPORTS = (
-    "lx_status_string", "lx_mask_compact", "lx_mask_compact_pair", "lx_ffn_pack_weights",
+    "lx_status_string", "lx_mask_compact", "lx_mask_compact_pair", "lx_mask_compact_batch", "lx_ffn_pack_weights",
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
@@ -44,12 +44,20 @@ class lx_blocklist(C.Structure):
 
 
 _i32, _i64, _vp, _sz, _f = C.c_int32, C.c_int64, C.c_void_p, C.c_size_t, C.c_float
+
+
+class lx_compact_job(C.Structure):
+    _fields_ = [("mask", C.c_void_p), ("batch", C.c_int32), ("rows", C.c_int32),
+                ("cols", C.c_int32), ("batch_stride", C.c_int64), ("row_stride", C.c_int64),
+                ("col_stride", C.c_int64), ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p),
+                ("col_idx_cap", C.c_int32)]
 _blp = C.POINTER(lx_blocklist)
 _lib.lx_status_string.restype = C.c_char_p
 _lib.lx_status_string.argtypes = [C.c_int]
 _lib.lx_mask_compact.argtypes = [_vp, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp]
 _lib.lx_mask_compact_pair.argtypes = [_vp, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp,
                                       _i32, _vp]
+_lib.lx_mask_compact_batch.argtypes = [C.POINTER(lx_compact_job), _i32, _vp]
 _lib.lx_ffn_pack_weights.argtypes = [C.c_int, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
 for _n in ("lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes"):
     getattr(_lib, _n).restype = _sz
@@ -149,6 +157,33 @@ def lx_mask_compact_pair(mask: torch.Tensor, out=None):
                                      _ptr(blr.col_idx), _ptr(blc.row_ptr), _ptr(blc.col_idx), cap,
                                      _stream()), "lx_mask_compact_pair")
     return blr, blc
+
+
+class CompactBatch:
+    """Pre-marshalled set of compaction jobs (up to 8) that run in one launch.
+    add(mask, out, transpose) mirrors lx_mask_compact(mask, transpose, out=out)."""
+
+    def __init__(self):
+        self.jobs = []
+        self._keep = []
+
+    def add(self, mask: torch.Tensor, out: "BlockList", transpose: bool = False):
+        assert mask.dtype == torch.uint8 and mask.is_cuda and mask.is_contiguous()
+        R, Cc = mask.shape[-2], mask.shape[-1]
+        batch = mask.numel() // (R * Cc)
+        rows, cols, rs, cs = (Cc, R, 1, Cc) if transpose else (R, Cc, Cc, 1)
+        assert out.rows == batch * rows and out.cols == cols
+        self.jobs.append(lx_compact_job(mask.data_ptr(), batch, rows, cols, R * Cc, rs, cs,
+                                        out.row_ptr.data_ptr(), out.col_idx.data_ptr(),
+                                        out.col_idx.numel()))
+        self._keep.append((mask, out))
+        self._arr = (lx_compact_job * len(self.jobs))(*self.jobs)
+        return self
+
+
+def lx_mask_compact_batch(batch: CompactBatch):
+    _check(_lib.lx_mask_compact_batch(batch._arr, len(batch.jobs), _stream()),
+           "lx_mask_compact_batch")
 
 
 def lx_ffn_pack_weights(W_up: torch.Tensor, W_down: torch.Tensor):

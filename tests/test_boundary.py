@@ -55,6 +55,17 @@ def test_compact_pair_rejects_bad_arguments(lxmod):
     assert f(FAKE, 1, 4, 0, 16, 4, 1, FAKE, FAKE, FAKE, FAKE, 16, None) == lxmod.LX_ERR_INVALID_ARG
 
 
+def test_compact_batch_rejects_bad_arguments(lxmod):
+    f = lxmod._lib.lx_mask_compact_batch
+    J = lxmod.lx_compact_job
+    ok = J(0x1000, 1, 4, 4, 16, 4, 1, 0x1000, 0x1000, 16)
+    arr = (J * 2)(ok, J(0x1000, 1, 4, 4, 16, 4, 1, 0, 0x1000, 16))
+    assert f(arr, 2, None) == lxmod.LX_ERR_INVALID_ARG          # second job has a null row_ptr
+    assert f(arr, 0, None) == lxmod.LX_ERR_INVALID_ARG
+    assert f(arr, 9, None) == lxmod.LX_ERR_INVALID_ARG
+    assert f(None, 1, None) == lxmod.LX_ERR_INVALID_ARG
+
+
 def _ffn_fwd(lxmod, dt, T, d, F, tt, bn, bl, X=FAKE, ws=None, ws_bytes=0, H=FAKE):
     return lxmod._lib.lx_sparse_ffn_fwd(dt, T, d, F, tt, bn, X, FAKE, None, FAKE, None,
                                         C.byref(bl) if bl is not None else None, FAKE, H, ws,

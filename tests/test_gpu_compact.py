@@ -82,3 +82,24 @@ def test_pair_matches_single_lists(lx, oracle):
     got_rp = blc.row_ptr.cpu().numpy()[r0:r0 + 25]
     assert np.array_equal(got_rp - got_rp[0], rp)
     assert np.array_equal(blc.col_idx.cpu().numpy()[got_rp[0]:got_rp[-1]], ci)
+
+
+def test_batch_matches_single_lists(lx, oracle):
+    import torch
+    rng = np.random.default_rng(10)
+    m1 = (rng.random((64, 128)) < 0.1).astype(np.uint8)
+    m2 = (rng.random((3, 16, 16)) < 0.4).astype(np.uint8)
+    t1, t2 = torch.from_numpy(m1).cuda(), torch.from_numpy(m2).cuda()
+    ref = [lx.lx_mask_compact(t1), lx.lx_mask_compact(t2), lx.lx_mask_compact(t2, transpose=True)]
+    mk = lambda r: lx.BlockList(r.rows, r.cols, torch.zeros_like(r.row_ptr),
+                                torch.zeros_like(r.col_idx), r.nnz_cap)
+    outs = [mk(r) for r in ref]
+    cb = lx.CompactBatch().add(t1, outs[0]).add(t2, outs[1]).add(t2, outs[2], transpose=True)
+    lx.lx_mask_compact_batch(cb)
+    torch.cuda.synchronize()
+    for o, r, m in zip(outs, ref, (m1, m2, m2)):
+        nnz = int(m.sum())
+        assert torch.equal(o.row_ptr, r.row_ptr) and torch.equal(o.col_idx[:nnz], r.col_idx[:nnz])
+    rp, ci = oracle.mask_compact(m1)
+    assert np.array_equal(outs[0].row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(outs[0].col_idx.cpu().numpy()[:rp[-1]], ci)
