@@ -8,7 +8,7 @@
 //   sdd  out block (i, j) = A_i [64 x K] . W[j-block rows, :]^T, K = d
 //        one workgroup owns up to four consecutive entries of token tile i's
 //        list, so the A_i chunk staged in LDS is shared by four neuron blocks;
-//        wave w computes block w (64 x 64, four 32x32 accumulators).
+//        8 waves: wave w computes half w%2 (32 neurons) of block w/2 for all 64 tokens.
 //   dsd  out tile (i, 256 columns) = sum over listed j of Act_ij [64 x 64] .
 //        W[rows n0.., j-block columns]^T: the K loop walks the active list, one
 //        64-wide K-step per active block; inactive blocks are never touched.
@@ -30,7 +30,7 @@ namespace lx {
 #define LX_AS1 __attribute__((address_space(1)))
 #define LX_AS3 __attribute__((address_space(3)))
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;      // 8 wavefronts: two per SIMD, so one hides the other's LDS latency
 constexpr int kBK = 64;            // K-chunk per step: 64 bf16 = 128 bytes per row
 constexpr int kRowsB = 64;         // shared operand (token rows)
 constexpr int kRowsA = 256;        // per-wave operand (4 x 64 weight rows)
@@ -41,31 +41,33 @@ constexpr int kIssues = kStageRows / 8 / (kThreads / kWave);  // DMA instruction
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
 // One stage = kIssues DMA instructions per wave.  Instruction u of wave w fills stage rows
-// 8g .. 8g+7 with g = w + 4u; lane l brings the 16-byte slot l%8 of row 8g + l/8.
-// src[u] already points at this lane's (row, swizzled segment); offB / offA are the element
-// offsets of the current K-step for the shared rows (u < 2) and the weight rows (u >= 2).
+// 8g .. 8g+7 with g = w + 8u (u = 0: the 64 shared rows, u >= 1: weight block u-1); lane l brings
+// the 16-byte slot l%8 of row 8g + l/8.  src[u] already points at this lane's (row, swizzled
+// segment); offB / offA are the element offsets of the current K-step for the shared rows and
+// the weight rows.
 __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[kIssues],
                                             long long offB, long long offA) {
   const uint32_t base = lds_addr(stage) + (threadIdx.x / kWave) * 1024;
 #pragma unroll
-  for (int u = 0; u < kIssues; ++u) dma16(src[u] + (u < 2 ? offB : offA), base + u * 4096);
+  for (int u = 0; u < kIssues; ++u) dma16(src[u] + (u < 1 ? offB : offA), base + u * 8192);
 }
 
-// One 64-deep K-step from LDS: wave w multiplies its 64 A rows with the 64 shared B rows.
-// acc[ni][ti]: rows (A operand) 32ni.., columns (B operand) 32ti..
-__device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16 (&acc)[2][2]) {
+// One 64-deep K-step from LDS: wave w multiplies 32 weight rows (half w%2 of block w/2) with the
+// 64 shared rows.  acc[ti]: rows = the 32 weight rows, columns = shared rows 32ti..
+__device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16 (&acc)[2]) {
   const int lane = threadIdx.x % kWave;
   const int r = lane % 32, h2 = lane / 32;
-  // all 16 operand reads of the step are issued first, so that their LDS latency overlaps
+  const int ra = kRowsB + 32 * wave + r;
+  // all 12 operand reads of the step are issued first, so that their LDS latency overlaps
   // the MFMAs instead of being paid once per k16 slice
-  uint4 a[4][2], b[4][2];
+  uint4 a[4], b[4][2];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     const int seg = 2 * kk + h2;
+    a[kk] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int ra = kRowsB + 64 * wave + 32 * h + r, rb = 32 * h + r;
-      a[kk][h] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+      const int rb = 32 * h + r;
       b[kk][h] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
     }
   }
@@ -73,9 +75,7 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32(a[kk][ni], b[kk][ti], acc[ni][ti]);
+    for (int ti = 0; ti < 2; ++ti) acc[ti] = mfma32(a[kk], b[kk][ti], acc[ti]);
 }
 
 // Three-stage pipeline over nsteps K-steps: while step s is multiplied, the DMA of steps s+1
@@ -95,7 +95,7 @@ template <class Offs>
 __device__ __forceinline__ void run_pipeline(int nsteps, bool wave_on,
                                              const uint16_t* const (&src)[kIssues], Offs offs,
                                              uint16_t* st0, uint16_t* st1, uint16_t* st2,
-                                             f32x16 (&acc)[2][2]) {
+                                             f32x16 (&acc)[2]) {
   static_assert(kIssues < 16, "vmcnt immediate");
   const int wave = threadIdx.x / kWave;
   long long ob, oa;
@@ -127,7 +127,7 @@ __device__ __forceinline__ void run_pipeline(int nsteps, bool wave_on,
 template <class Offs>
 __device__ __forceinline__ void run_pipeline2(int nsteps, bool wave_on,
                                               const uint16_t* const (&src)[kIssues], Offs offs,
-                                              uint16_t* st0, uint16_t* st1, f32x16 (&acc)[2][2]) {
+                                              uint16_t* st0, uint16_t* st1, f32x16 (&acc)[2]) {
   const int wave = threadIdx.x / kWave;
   long long ob, oa;
   auto issue = [&](uint16_t* st, int s) {
@@ -194,13 +194,11 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   return false;
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[2]) {
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 }
 
 // MODE 0: out = bf16(max(acc + bias, 0));  MODE 1: out = gate > 0 ? bf16(acc) : 0.
@@ -225,29 +223,29 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   const uint16_t* src[kIssues];
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
-    const int g = wave + 4 * u, row = 8 * g + lane / 8;
+    const int g = wave + 8 * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 2) {
+    if (u < 1) {
       src[u] = A + ((long long)i * 64 + row) * K + seg * 8;
     } else {
-      const int blk = (u - 2) / 2, r = row - kRowsB - 64 * blk;
+      const int blk = u - 1, r = row - kRowsB - 64 * blk;
       // blocks past the end of the list are filled from the first block (never used)
       const int j = col_idx[p0 + (blk < nb ? blk : 0)];
       src[u] = W + ((long long)j * 64 + r) * K + seg * 8;
     }
   }
-  f32x16 acc[2][2];
+  f32x16 acc[2];
   zero_acc(acc);
-  run_pipeline(K / kBK, wave < nb, src,
+  run_pipeline(K / kBK, wave / 2 < nb, src,
                [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; }, st0, st1,
                st2, acc);
-  if (wave >= nb) return;
+  if (wave / 2 >= nb) return;
 
-  const int p = p0 + wave;
+  const int p = p0 + wave / 2;
   const int j = col_idx[p];
   const int tl = lane % 32, nq = (lane / 32) * 4;
-#pragma unroll
-  for (int ni = 0; ni < 2; ++ni)
+  {
+    const int ni = wave % 2;
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
@@ -256,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
         const long long o = (long long)p * 4096 + t * 64 + n;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
+        for (int e = 0; e < 4; ++e) v[e] = acc[ti][4 * g + e];
         if (MODE == 0) {
           if (bias) {
             const uint2 bb = *reinterpret_cast<const uint2*>(bias + j * 64 + n);
@@ -277,6 +275,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
         ov.y = pack2bf(v[2], v[3]);
         *reinterpret_cast<uint2*>(out_act + o) = ov;
       }
+  }
 }
 
 // out[i-tile rows, n0 .. n0+255] = sum_s act[p_s] [64 x 64] . W[n0.., j_s*64 ..]^T (+ bias)
@@ -289,21 +288,21 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  const bool wave_on = n0 + 64 * wave < ncols_out;
+  const bool wave_on = n0 + 64 * (wave / 2) < ncols_out;
 
   const uint16_t* src[kIssues];
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
-    const int g = wave + 4 * u, row = 8 * g + lane / 8;
+    const int g = wave + 8 * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 2) {
+    if (u < 1) {
       src[u] = act + row * 64 + seg * 8;          // inside a compact 64x64 activation block
     } else {
       const int n = min(n0 + row - kRowsB, ncols_out - 1);   // rows past the edge: re-read the last
       src[u] = W + (long long)n * ldw + seg * 8;
     }
   }
-  f32x16 acc[2][2];
+  f32x16 acc[2];
   zero_acc(acc);
   run_pipeline2(n_i, wave_on, src,
                [&](int s, long long& ob, long long& oa) {
@@ -315,17 +314,16 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   if (!wave_on) return;
 
   const int tl = lane % 32, nq = (lane / 32) * 4;
-#pragma unroll
-  for (int ni = 0; ni < 2; ++ni)
+  {
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int t = i * 64 + 32 * ti + tl;
-        const int n = n0 + 64 * wave + 32 * ni + 8 * g + nq;
+        const int n = n0 + 32 * wave + 8 * g + nq;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
+        for (int e = 0; e < 4; ++e) v[e] = acc[ti][4 * g + e];
         if (bias) {
           const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
           v[0] += bf2f(bb.x & 0xFFFFu); v[1] += bf2f(bb.x >> 16);
@@ -336,6 +334,7 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
         ov.y = pack2bf(v[2], v[3]);
         *reinterpret_cast<uint2*>(out + (long long)t * ncols_out + n) = ov;
       }
+  }
 }
 
 // pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
