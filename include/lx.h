@@ -241,6 +241,18 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
 lx_status lx_profile_begin(int32_t kernel, int32_t max_launches);
 lx_status lx_profile_end(float* total_ms, int32_t* launches);
 
+/*
+ * Tuning knob of the attention kernels (Sec. VI-A leaves the launch shape open).
+ * A workgroup walks the block lists of `rows` rows of the mask (query blocks in
+ * the forward and dQ kernels, key blocks in the dK/dV kernel) of one (batch,
+ * head) as one stream of blocks.  rows = 0 (the default) lets the library
+ * choose from the problem size; 1..4 fixes it for all later calls of this
+ * process.  Results do not depend on it beyond the order of fp32 additions
+ * inside a row, which it does not change.  Not thread-safe; returns
+ * LX_ERR_INVALID_ARG outside 0..4.
+ */
+lx_status lx_attn_set_rows_per_workgroup(int32_t rows);
+
 #ifdef __cplusplus
 }
 #endif

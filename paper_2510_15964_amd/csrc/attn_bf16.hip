@@ -5,16 +5,26 @@
 // heads with different patterns balanced (Sec. VI-A, online combination).
 //
 // Layout of one workgroup (128 threads = 2 wavefronts): a 64-row query block
-// (forward, dQ) or a 64-row key block (dK/dV); each wavefront owns 32 of the
-// rows and walks the block list of its row of the mask.  All products run on
-// the 32x32x16 bf16 MFMA with fp32 accumulators.
+// (forward, dQ) or a 64-row key block (dK/dV) at a time; each wavefront owns 32
+// of the rows and walks the block list of its row of the mask.  All products
+// run on the 32x32x16 bf16 MFMA with fp32 accumulators.
+//
+// At the block densities of the paper a row of the mask lists only a few
+// blocks, so a workgroup that handled one row would spend most of its life in
+// the chain of dependent loads that starts it (row pointer -> list -> tiles).
+// A workgroup therefore owns up to four rows of one (batch, head) and walks
+// their lists as ONE stream of blocks: the metadata of all its rows is read up
+// front, and the tile transfer of the next block -- of the same row or of the
+// next one -- is always in flight while the current block is computed.  The
+// rows are picked k, 2G-1-k, 2G+k, 4G-1-k (G = groups per head), which gives
+// every workgroup the same number of blocks under a causal mask.
 //
 // Data movement: the [64 x D] tiles of the listed blocks go from global memory
-// straight into LDS (global_load_lds, 16 bytes per lane), double buffered: the
-// tiles of list entry it+1 are in flight while entry it is computed.  The two
-// stages are separate LDS arrays so that the compiler's LDS-DMA tracking does
-// not wait for the in-flight stage.  Tiles are row-major, unpadded, with the
-// 16-byte slots of a row XOR-swizzled by the row index (bank spreading).
+// straight into LDS (global_load_lds, 16 bytes per lane), double buffered.  The
+// transfers are issued as assembly and waited for explicitly, so that no
+// compiler-inserted wait drains the stage in flight.  Tiles are row-major,
+// unpadded, with the 16-byte slots of a row XOR-swizzled by the row index
+// (bank spreading).
 //
 // Two tricks keep everything in one LDS layout and out of cross-lane shuffles:
 //  * the first product is computed transposed (S^T = K Q^T), so every lane
@@ -64,12 +74,11 @@ struct TileDma {
       off[u] = (long long)row * ld + slot * 8;
     }
   }
-  __device__ __forceinline__ void issue(uint16_t* tile, const uint16_t* g0) const {
+  // tile_addr: LDS byte address of the destination tile
+  __device__ __forceinline__ void issue(uint32_t tile_addr, const uint16_t* g0) const {
     const int wave = threadIdx.x / kWave;
 #pragma unroll
-    for (int u = 0; u < kPerWave; ++u)
-      __builtin_amdgcn_global_load_lds((const LX_AS1 void*)(g0 + off[u]),
-                                       (LX_AS3 void*)(tile + (wave + 2 * u) * 512), 16, 0, 0);
+    for (int u = 0; u < kPerWave; ++u) dma16(g0 + off[u], tile_addr + (wave + 2 * u) * 1024);
   }
 };
 
@@ -171,77 +180,165 @@ __device__ __forceinline__ void store_acc(const f32x16 (&acc)[D / 32], float mul
     }
 }
 
-// Double-buffered walk over n list entries: issue0/issue1 start the DMA of an entry into
-// stage 0/1, comp0/comp1 consume it.  A wave first waits for its own DMA (vmcnt), the barrier
-// then makes the whole stage visible and retires the reads of the stage about to be refilled.
-template <class I0, class I1, class C0, class C1>
-__device__ __forceinline__ void walk2(int n, I0 issue0, I1 issue1, C0 comp0, C1 comp1) {
-  if (n > 0) issue0(0);
-  for (int it = 0; it < n; it += 2) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
-    if (it + 1 < n) issue1(it + 1);
-    comp0(it);
-    if (it + 1 < n) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-      if (it + 2 < n) issue0(it + 2);
-      comp1(it + 1);
+// ---------------------------------------------------------------------------
+// rows of a workgroup and the walk over their blocks
+// ---------------------------------------------------------------------------
+constexpr int kRMax = 4;   // rows of the mask per workgroup, at most
+
+// Wave-uniform selection from a small array by a run-time index (stays in scalar registers).
+__device__ __forceinline__ int pick(const int (&v)[kRMax], int k) {
+  int r = v[0];
+#pragma unroll
+  for (int j = 1; j < kRMax; ++j) r = k == j ? v[j] : r;
+  return r;
+}
+
+// The rows (query blocks, or key blocks for dK/dV) of one (batch, head) that workgroup g of G
+// owns: slot j holds block j*G + g for even j and (j+1)*G - 1 - g for odd j.  All metadata is
+// fetched here, before the walk, so the walk itself issues no dependent metadata loads.
+struct RowSet {
+  int blk[kRMax];   // block index of the slot, -1 = slot not used
+  int n[kRMax];     // listed blocks of that row (0 for an inactive head)
+  ListRow list[kRMax];
+  __device__ __forceinline__ void init(const int* __restrict__ row_ptr,
+                                       const int* __restrict__ col_idx, int head_row0, int nblk,
+                                       int g, int G, int R, bool head_on) {
+    int rs[kRMax];
+#pragma unroll
+    for (int j = 0; j < kRMax; ++j) {
+      const int bj = (j & 1) ? (j + 1) * G - 1 - g : j * G + g;
+      const bool used = j < R && bj < nblk;
+      blk[j] = used ? bj : -1;
+      rs[j] = 0;
+      n[j] = 0;
+      if (used) {
+        rs[j] = row_ptr[head_row0 + bj];
+        n[j] = head_on ? row_ptr[head_row0 + bj + 1] - rs[j] : 0;
+      }
     }
+#pragma unroll
+    for (int j = 0; j < kRMax; ++j) {
+      list[j].init(col_idx + rs[j], n[j]);
+      if (n[j] > 0) list[j].get(0);   // fetch the first 64 entries now
+    }
+  }
+  // listed block `it` of slot k (both wave-uniform)
+  __device__ __forceinline__ int col(int k, int it) {
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < kRMax; ++j)
+      if (k == j) c = list[j].get(it);
+    return c;
+  }
+  // first slot >= k with a non-empty list, kRMax if none
+  __device__ __forceinline__ int next_row(int k) const {
+    int r = kRMax;
+#pragma unroll
+    for (int j = kRMax - 1; j >= 0; --j) r = (j >= k && n[j] > 0) ? j : r;
+    return r;
+  }
+};
+
+// Walk over all listed blocks of the row set as one double-buffered stream.  issue(stage, k, it)
+// starts the transfer of block `it` of slot k into stage 0/1; comp(stage, k, it) consumes it;
+// row_begin(k) / row_end(k) load and store the per-row state.  The transfer of the next block,
+// which may belong to the next row, is issued before the current one is computed.  A wave first
+// waits for its own transfers (vmcnt), the barrier then makes the whole stage visible and
+// retires the reads of the stage about to be refilled.  All control flow is workgroup-uniform.
+template <class RowBegin, class Issue, class Comp, class RowEnd>
+__device__ __forceinline__ void walk_rows(RowSet& rows, RowBegin row_begin, Issue issue, Comp comp,
+                                          RowEnd row_end) {
+  int ki = rows.next_row(0), iti = 0;
+  if (ki >= kRMax) return;
+  issue(0, ki, iti);
+  int kc = ki, itc = 0, nc = pick(rows.n, kc);
+  auto advance = [&]() {
+    if (++iti == pick(rows.n, ki)) {
+      ki = rows.next_row(ki + 1);
+      iti = 0;
+    }
+  };
+  advance();
+  row_begin(kc);
+  for (int t = 0;; ++t) {
+    wait_vmcnt<0>();
+    lds_barrier();
+    const bool more = ki < kRMax;
+    if (more) issue((t + 1) & 1, ki, iti);
+    comp(t & 1, kc, itc);
+    const bool last = itc + 1 == nc;
+    if (last) row_end(kc);
+    if (!more) break;
+    if (last) {
+      row_begin(ki);
+      nc = pick(rows.n, ki);
+    }
+    kc = ki;
+    itc = iti;
+    advance();
   }
 }
 
 // ---------------------------------------------------------------------------
-// forward: O, LSE for one (batch, head, query block)
+// forward: O, LSE for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st0[2 * 64 * D];   // K tile, V tile
-  __shared__ __attribute__((aligned(1024))) uint16_t st1[2 * 64 * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   const int nqb = a.S / 64;
-  const int qb = nqb - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int ql = 32 * wave + lane % 32, h2 = lane / 32;
-  const int row = ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb + qb;
-  const int rs = a.row_ptr[row];
-  int n = a.row_ptr[row + 1] - rs;
-  if (a.head_active && !a.head_active[h]) n = 0;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
-  const long long qoff = base + (long long)(qb * 64 + ql) * a.ss;
-  if (n == 0) {   // no listed block (or inactive head): O = 0, LSE = -inf, nothing to read
-    f32x16 z[D / 32];
-    zero(z);
-    store_acc<D>(z, 0.f, a.Out + qoff);
-    if (h2 == 0) a.LSE[((long long)b * a.Hh + h) * a.S + qb * 64 + ql] = -INFINITY;
-    return;
-  }
+  const long long stat_base = ((long long)b * a.Hh + h) * a.S;
+  const uint32_t st_addr = lds_addr(&st[0][0]);
 
-  uint4 qf[D / 16];
+  RowSet rows;
+  rows.init(a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
+            gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
+  // rows without a listed block (or of an inactive head): O = 0, LSE = -inf, nothing to read
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s)
-    qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
+  for (int j = 0; j < kRMax; ++j)
+    if (rows.blk[j] >= 0 && rows.n[j] == 0) {
+      f32x16 z[D / 32];
+      zero(z);
+      store_acc<D>(z, 0.f, a.Out + base + (long long)(rows.blk[j] * 64 + ql) * a.ss);
+      if (h2 == 0) a.LSE[stat_base + rows.blk[j] * 64 + ql] = -INFINITY;
+    }
 
   TileDma<D> dma;
   dma.init(a.ss);
-  f32x16 o_acc[D / 32];
-  zero(o_acc);
-  float m = -INFINITY, lsum = 0.f;
   const float sc = a.scale * kLog2e;
+  // state of the row being computed
+  int qb = 0;
+  long long qoff = 0;
+  uint4 qf[D / 16];
+  f32x16 o_acc[D / 32];
+  float m = -INFINITY, lsum = 0.f;
 
-  ListRow list;
-  list.init(a.col_idx + rs, n);
-  auto issue = [&](uint16_t* st, int it) {
-    const long long t0 = base + (long long)list.get(it) * 64 * a.ss;
-    dma.issue(st, a.K + t0);
-    dma.issue(st + 64 * D, a.V + t0);
+  auto row_begin = [&](int k) {
+    qb = pick(rows.blk, k);
+    qoff = base + (long long)(qb * 64 + ql) * a.ss;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+      qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
+    zero(o_acc);
+    m = -INFINITY;
+    lsum = 0.f;
+  };
+  auto issue = [&](int stage, int k, int it) {
+    const long long t0 = base + (long long)rows.col(k, it) * 64 * a.ss;
+    const uint32_t dst = st_addr + stage * (4 * 64 * D);
+    dma.issue(dst, a.K + t0);
+    dma.issue(dst + 2 * 64 * D, a.V + t0);
   };
   // DIAG: the diagonal block of a causal mask, where keys after the query are excluded.  Two
   // separate instantiations (instead of a branch in the middle) keep the 32 score registers in
   // place on both paths.
-  auto comp_body = [&](const uint16_t* st, auto diag_tag) {
+  auto comp_body = [&](const uint16_t* stg, auto diag_tag) {
     constexpr bool DIAG = decltype(diag_tag)::value;
     f32x16 s_acc[2];
-    mma_rows<D>(st, qf, s_acc);           // S^T[key][q]
+    mma_rows<D>(stg, qf, s_acc);           // S^T[key][q]
     float mloc = -INFINITY;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
@@ -274,92 +371,97 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const Attn
 #pragma unroll
         for (int v = 0; v < 16; ++v) o_acc[ct][v] *= alpha;
     }
-    mma_transposed<D>(st + 64 * D, s_acc, o_acc);   // O^T += V^T P^T
+    mma_transposed<D>(stg + 64 * D, s_acc, o_acc);   // O^T += V^T P^T
   };
-  auto comp = [&](const uint16_t* st, int it) {
-    if (a.causal && list.get(it) == qb)
-      comp_body(st, TrueTag{});
+  auto comp = [&](int stage, int k, int it) {
+    if (a.causal && rows.col(k, it) == qb)
+      comp_body(st[stage], TrueTag{});
     else
-      comp_body(st, FalseTag{});
+      comp_body(st[stage], FalseTag{});
   };
-  walk2(n, [&](int it) { issue(st0, it); }, [&](int it) { issue(st1, it); },
-        [&](int it) { comp(st0, it); }, [&](int it) { comp(st1, it); });
-
-  const bool any = lsum > 0.f;
-  const float inv = any ? 1.f / lsum : 0.f;
-  store_acc<D>(o_acc, inv, a.Out + qoff);
-  if (h2 == 0)
-    a.LSE[((long long)b * a.Hh + h) * a.S + qb * 64 + ql] =
-        any ? (m + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+  auto row_end = [&](int) {
+    const bool any = lsum > 0.f;
+    const float inv = any ? 1.f / lsum : 0.f;
+    store_acc<D>(o_acc, inv, a.Out + qoff);
+    if (h2 == 0)
+      a.LSE[stat_base + qb * 64 + ql] = any ? (m + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+  };
+  walk_rows(rows, row_begin, issue, comp, row_end);
 }
 
 // ---------------------------------------------------------------------------
-// backward, query side: Delta and dQ for one (batch, head, query block)
+// backward, query side: Delta and dQ for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st0[2 * 64 * D];   // K tile, V tile
-  __shared__ __attribute__((aligned(1024))) uint16_t st1[2 * 64 * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   const int nqb = a.S / 64;
-  const int qb = nqb - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int ql = 32 * wave + lane % 32, h2 = lane / 32;
-  const int row = ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb + qb;
-  const int rs = a.row_ptr[row];
-  int n = a.row_ptr[row + 1] - rs;
-  if (a.head_active && !a.head_active[h]) n = 0;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
-  const long long qoff = base + (long long)(qb * 64 + ql) * a.ss;
-  const long long stat = ((long long)b * a.Hh + h) * a.S + qb * 64 + ql;
-  if (n == 0) {   // no listed block (or inactive head): O = 0, hence Delta = 0 and dQ = 0
-    f32x16 z[D / 32];
-    zero(z);
-    store_acc<D>(z, 0.f, a.dQ + qoff);
-    if (h2 == 0) {
-      a.Delta[stat] = 0.f;
-      a.NegLse2[stat] = INFINITY;
-    }
-    return;
-  }
+  const long long stat_base = ((long long)b * a.Hh + h) * a.S;
+  const uint32_t st_addr = lds_addr(&st[0][0]);
 
-  uint4 qf[D / 16], dof[D / 16];
-  float part = 0.f;
+  RowSet rows;
+  rows.init(a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
+            gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
+  // rows without a listed block (or of an inactive head): O = 0, hence Delta = 0 and dQ = 0
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
-    dof[s] = *reinterpret_cast<const uint4*>(a.dO + qoff + 16 * s + 8 * h2);
-    const uint4 of = *reinterpret_cast<const uint4*>(a.O + qoff + 16 * s + 8 * h2);
-    const uint32_t x[4] = {dof[s].x, dof[s].y, dof[s].z, dof[s].w};
-    const uint32_t y[4] = {of.x, of.y, of.z, of.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      part += bf2f(x[e] & 0xFFFFu) * bf2f(y[e] & 0xFFFFu) + bf2f(x[e] >> 16) * bf2f(y[e] >> 16);
-  }
-  const float delta = part + __shfl_xor(part, 32);
-  const float lse2 = a.LSEin[stat] * kLog2e;
-  if (h2 == 0) {                     // for the key-side kernel: Delta and -LSE in log2 units
-    a.Delta[stat] = delta;
-    a.NegLse2[stat] = -lse2;
-  }
-  const float sc = a.scale * kLog2e;
+  for (int j = 0; j < kRMax; ++j)
+    if (rows.blk[j] >= 0 && rows.n[j] == 0) {
+      f32x16 z[D / 32];
+      zero(z);
+      store_acc<D>(z, 0.f, a.dQ + base + (long long)(rows.blk[j] * 64 + ql) * a.ss);
+      if (h2 == 0) {
+        a.Delta[stat_base + rows.blk[j] * 64 + ql] = 0.f;
+        a.NegLse2[stat_base + rows.blk[j] * 64 + ql] = INFINITY;
+      }
+    }
 
   TileDma<D> dma;
   dma.init(a.ss);
+  const float sc = a.scale * kLog2e;
+  int qb = 0;
+  long long qoff = 0;
+  uint4 qf[D / 16], dof[D / 16];
+  float delta = 0.f, lse2 = 0.f;
   f32x16 dq_acc[D / 32];
-  zero(dq_acc);
 
-  ListRow list;
-  list.init(a.col_idx + rs, n);
-  auto issue = [&](uint16_t* st, int it) {
-    const long long t0 = base + (long long)list.get(it) * 64 * a.ss;
-    dma.issue(st, a.K + t0);
-    dma.issue(st + 64 * D, a.V + t0);
+  auto row_begin = [&](int k) {
+    qb = pick(rows.blk, k);
+    qoff = base + (long long)(qb * 64 + ql) * a.ss;
+    float part = 0.f;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+      qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
+      dof[s] = *reinterpret_cast<const uint4*>(a.dO + qoff + 16 * s + 8 * h2);
+      const uint4 of = *reinterpret_cast<const uint4*>(a.O + qoff + 16 * s + 8 * h2);
+      const uint32_t x[4] = {dof[s].x, dof[s].y, dof[s].z, dof[s].w};
+      const uint32_t y[4] = {of.x, of.y, of.z, of.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        part += bf2f(x[e] & 0xFFFFu) * bf2f(y[e] & 0xFFFFu) + bf2f(x[e] >> 16) * bf2f(y[e] >> 16);
+    }
+    delta = part + __shfl_xor(part, 32);
+    lse2 = a.LSEin[stat_base + qb * 64 + ql] * kLog2e;
+    if (h2 == 0) {                     // for the key-side kernel: Delta and -LSE in log2 units
+      a.Delta[stat_base + qb * 64 + ql] = delta;
+      a.NegLse2[stat_base + qb * 64 + ql] = -lse2;
+    }
+    zero(dq_acc);
   };
-  auto comp_body = [&](const uint16_t* st, auto diag_tag) {
+  auto issue = [&](int stage, int k, int it) {
+    const long long t0 = base + (long long)rows.col(k, it) * 64 * a.ss;
+    const uint32_t dst = st_addr + stage * (4 * 64 * D);
+    dma.issue(dst, a.K + t0);
+    dma.issue(dst + 2 * 64 * D, a.V + t0);
+  };
+  auto comp_body = [&](const uint16_t* stg, auto diag_tag) {
     constexpr bool DIAG = decltype(diag_tag)::value;
     f32x16 s_acc[2], dp_acc[2];
-    mma_rows<D>(st, qf, s_acc);              // S^T[key][q]
-    mma_rows<D>(st + 64 * D, dof, dp_acc);   // dP^T[key][q]
+    mma_rows<D>(stg, qf, s_acc);              // S^T[key][q]
+    mma_rows<D>(stg + 64 * D, dof, dp_acc);   // dP^T[key][q]
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -371,83 +473,87 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const A
         }
         s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
       }
-    mma_transposed<D>(st, s_acc, dq_acc);    // dQ^T += K^T dS^T
+    mma_transposed<D>(stg, s_acc, dq_acc);    // dQ^T += K^T dS^T
   };
-  auto comp = [&](const uint16_t* st, int it) {
-    if (a.causal && list.get(it) == qb)
-      comp_body(st, TrueTag{});
+  auto comp = [&](int stage, int k, int it) {
+    if (a.causal && rows.col(k, it) == qb)
+      comp_body(st[stage], TrueTag{});
     else
-      comp_body(st, FalseTag{});
+      comp_body(st[stage], FalseTag{});
   };
-  walk2(n, [&](int it) { issue(st0, it); }, [&](int it) { issue(st1, it); },
-        [&](int it) { comp(st0, it); }, [&](int it) { comp(st1, it); });
-  store_acc<D>(dq_acc, a.scale, a.dQ + qoff);
+  auto row_end = [&](int) { store_acc<D>(dq_acc, a.scale, a.dQ + qoff); };
+  walk_rows(rows, row_begin, issue, comp, row_end);
 }
 
 // ---------------------------------------------------------------------------
-// backward, key side: dK and dV for one (batch, head, key block)
+// backward, key side: dK and dV for the key blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st0[2 * 64 * D];   // Q tile, dO tile
-  __shared__ __attribute__((aligned(1024))) uint16_t st1[2 * 64 * D];
-  __shared__ __attribute__((aligned(256))) float stat0[128];            // -LSE*log2e [64], Delta [64]
-  __shared__ __attribute__((aligned(256))) float stat1[128];
+  __shared__ __attribute__((aligned(1024))) uint16_t st[2][2 * 64 * D];   // stage: Q tile, dO tile
+  __shared__ __attribute__((aligned(256))) float sstat[2][128];   // stage: -LSE*log2e [64], Delta [64]
   const int nkb = a.S / 64;
-  const int kb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int kl = 32 * wave + lane % 32, h2 = lane / 32;
-  const int row = ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb + kb;
-  const int rs = a.crow_ptr[row];
-  int n = a.crow_ptr[row + 1] - rs;
-  if (a.head_active && !a.head_active[h]) n = 0;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
-  const long long koff = base + (long long)(kb * 64 + kl) * a.ss;
   const long long stat_base = ((long long)b * a.Hh + h) * a.S;
-  if (n == 0) {   // key block used by no query block: zero gradients, nothing to read
-    f32x16 z[D / 32];
-    zero(z);
-    store_acc<D>(z, 0.f, a.dV + koff);
-    store_acc<D>(z, 0.f, a.dK + koff);
-    return;
-  }
+  const uint32_t st_addr = lds_addr(&st[0][0]), sstat_addr = lds_addr(&sstat[0][0]);
 
-  uint4 kf[D / 16], vf[D / 16];
+  RowSet rows;
+  rows.init(a.crow_ptr, a.ccol_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
+            blockIdx.x, gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
+  // key blocks used by no query block: zero gradients, nothing to read
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    kf[s] = *reinterpret_cast<const uint4*>(a.K + koff + 16 * s + 8 * h2);
-    vf[s] = *reinterpret_cast<const uint4*>(a.V + koff + 16 * s + 8 * h2);
-  }
-  const float sc = a.scale * kLog2e;
+  for (int j = 0; j < kRMax; ++j)
+    if (rows.blk[j] >= 0 && rows.n[j] == 0) {
+      f32x16 z[D / 32];
+      zero(z);
+      const long long koff = base + (long long)(rows.blk[j] * 64 + kl) * a.ss;
+      store_acc<D>(z, 0.f, a.dV + koff);
+      store_acc<D>(z, 0.f, a.dK + koff);
+    }
+
   TileDma<D> dma;
   dma.init(a.ss);
-  f32x16 dk_acc[D / 32], dv_acc[D / 32];
-  zero(dk_acc);
-  zero(dv_acc);
+  const float sc = a.scale * kLog2e;
   const float* stat_src = wave == 0 ? a.NegLse2 : a.Delta;  // wave 0: -LSE*log2(e), wave 1: Delta
+  int kb = 0;
+  long long koff = 0;
+  uint4 kf[D / 16], vf[D / 16];
+  f32x16 dk_acc[D / 32], dv_acc[D / 32];
 
-  ListRow list;
-  list.init(a.ccol_idx + rs, n);
-  auto issue = [&](uint16_t* st, float* sstat, int it) {
-    const int qb = list.get(it);
-    const long long t0 = base + (long long)qb * 64 * a.ss;
-    dma.issue(st, a.Q + t0);
-    dma.issue(st + 64 * D, a.dO + t0);
-    __builtin_amdgcn_global_load_lds((const LX_AS1 void*)(stat_src + stat_base + qb * 64 + lane),
-                                     (LX_AS3 void*)(sstat + 64 * wave), 4, 0, 0);
+  auto row_begin = [&](int k) {
+    kb = pick(rows.blk, k);
+    koff = base + (long long)(kb * 64 + kl) * a.ss;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+      kf[s] = *reinterpret_cast<const uint4*>(a.K + koff + 16 * s + 8 * h2);
+      vf[s] = *reinterpret_cast<const uint4*>(a.V + koff + 16 * s + 8 * h2);
+    }
+    zero(dk_acc);
+    zero(dv_acc);
   };
-  auto comp_body = [&](const uint16_t* st, const float* sstat, auto diag_tag) {
+  auto issue = [&](int stage, int k, int it) {
+    const int qb = rows.col(k, it);
+    const long long t0 = base + (long long)qb * 64 * a.ss;
+    const uint32_t dst = st_addr + stage * (4 * 64 * D);
+    dma.issue(dst, a.Q + t0);
+    dma.issue(dst + 2 * 64 * D, a.dO + t0);
+    dma4(stat_src + stat_base + qb * 64 + lane, sstat_addr + stage * 512 + wave * 256);
+  };
+  auto comp_body = [&](const uint16_t* stg, const float* stt, auto diag_tag) {
     constexpr bool DIAG = decltype(diag_tag)::value;
     f32x16 s_acc[2], dp_acc[2];
-    mma_rows<D>(st, kf, s_acc);               // S[q][key]
-    mma_rows<D>(st + 64 * D, vf, dp_acc);     // dP[q][key]
+    mma_rows<D>(stg, kf, s_acc);               // S[q][key]
+    mma_rows<D>(stg + 64 * D, vf, dp_acc);     // dP[q][key]
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int q0 = 32 * half + 8 * g + 4 * h2;            // four consecutive queries
-        const float4 nl = *reinterpret_cast<const float4*>(sstat + q0);
-        const float4 dl = *reinterpret_cast<const float4*>(sstat + 64 + q0);
+        const float4 nl = *reinterpret_cast<const float4*>(stt + q0);
+        const float4 dl = *reinterpret_cast<const float4*>(stt + 64 + q0);
         const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -458,39 +564,61 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
           dp_acc[half][v] = p * (dp_acc[half][v] - dls[e]);     // dS
         }
       }
-    mma_transposed<D>(st + 64 * D, s_acc, dv_acc);   // dV^T += dO^T P
-    mma_transposed<D>(st, dp_acc, dk_acc);           // dK^T += Q^T dS
+    mma_transposed<D>(stg + 64 * D, s_acc, dv_acc);   // dV^T += dO^T P
+    mma_transposed<D>(stg, dp_acc, dk_acc);           // dK^T += Q^T dS
   };
-  auto comp = [&](const uint16_t* st, const float* sstat, int it) {
-    if (a.causal && list.get(it) == kb)
-      comp_body(st, sstat, TrueTag{});
+  auto comp = [&](int stage, int k, int it) {
+    if (a.causal && rows.col(k, it) == kb)
+      comp_body(st[stage], sstat[stage], TrueTag{});
     else
-      comp_body(st, sstat, FalseTag{});
+      comp_body(st[stage], sstat[stage], FalseTag{});
   };
-  walk2(n, [&](int it) { issue(st0, stat0, it); }, [&](int it) { issue(st1, stat1, it); },
-        [&](int it) { comp(st0, stat0, it); }, [&](int it) { comp(st1, stat1, it); });
-  store_acc<D>(dv_acc, 1.f, a.dV + koff);
-  store_acc<D>(dk_acc, a.scale, a.dK + koff);
+  auto row_end = [&](int) {
+    store_acc<D>(dv_acc, 1.f, a.dV + koff);
+    store_acc<D>(dk_acc, a.scale, a.dK + koff);
+  };
+  walk_rows(rows, row_begin, issue, comp, row_end);
+}
+
+// Rows per workgroup: as many (up to kRMax) as still leave enough workgroups to fill the chip,
+// unless the caller fixed the number.
+static int g_rows_per_wg = 0;
+hipError_t set_attn_rows_per_wg(int r) {
+  if (r < 0 || r > kRMax) return hipErrorInvalidValue;
+  g_rows_per_wg = r;
+  return hipSuccess;
+}
+static int rows_per_wg(int nblk, int heads, int B) {
+  const long long total = (long long)nblk * heads * B;
+  int r = g_rows_per_wg > 0 ? g_rows_per_wg : (int)(total / 1024);
+  r = r < 1 ? 1 : (r > kRMax ? kRMax : r);
+  return r > nblk ? nblk : r;
 }
 
 template <int D>
-static hipError_t launch_fwd(const AttnArgs& a, int B, hipStream_t st) {
+static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
   ProfScope ps(kKAttnFwd, st);
-  hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), 0, st, a);
+  const int nblk = a.S / 64;
+  a.rows_per_wg = rows_per_wg(nblk, a.Hh, B);
+  const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
+  hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
   return hipGetLastError();
 }
 
 template <int D>
-static hipError_t launch_bwd(const AttnArgs& a, int B, hipStream_t st) {
+static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
+  const int nblk = a.S / 64;
+  a.rows_per_wg = rows_per_wg(nblk, a.Hh, B);
+  const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
   {
     ProfScope ps(kKAttnDq, st);
-    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   {
     ProfScope ps(kKAttnDkv, st);
-    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(a.S / 64, a.Hh, B), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
   }
   return hipGetLastError();
 }

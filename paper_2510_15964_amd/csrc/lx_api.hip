@@ -116,6 +116,10 @@ lx_status lx_profile_end(float* total_ms, int32_t* launches) {
   return rc;
 }
 
+lx_status lx_attn_set_rows_per_workgroup(int32_t rows) {
+  return set_attn_rows_per_wg(rows) == hipSuccess ? LX_OK : LX_ERR_INVALID_ARG;
+}
+
 lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
                           int64_t batch_stride, int64_t row_stride, int64_t col_stride,
                           int32_t* row_ptr, int32_t* col_idx, int32_t col_idx_cap, void* stream) {

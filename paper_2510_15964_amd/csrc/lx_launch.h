@@ -32,6 +32,7 @@ struct AttnArgs {
   const uint8_t* head_active;
   int Hh, S, mask_batch, causal;
   float scale;
+  int rows_per_wg;   // rows of the mask per workgroup, set by the launcher
 };
 
 hipError_t launch_compact(const uint8_t*, int, int, int, long long, long long, long long, int*, int*,
@@ -60,5 +61,6 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);
 hipError_t launch_attn_fwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
+hipError_t set_attn_rows_per_wg(int r);   // 0 = automatic
 
 }  // namespace lx

@@ -31,6 +31,7 @@ EXPORTS = (
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
+    "lx_attn_set_rows_per_workgroup",
 )
 (LX_K_COMPACT, LX_K_FFN_UP, LX_K_FFN_DOWN, LX_K_FFN_DH, LX_K_FFN_DX, LX_K_ATTN_FWD,
  LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE) = range(9)
@@ -77,6 +78,7 @@ _lib.lx_sparse_attn_bwd_dx.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32
 
 _lib.lx_profile_begin.argtypes = [_i32, _i32]
 _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
+_lib.lx_attn_set_rows_per_workgroup.argtypes = [_i32]
 
 
 class LxError(RuntimeError):
@@ -232,6 +234,10 @@ def lx_sparse_ffn_bwd_dx(dY, H_act, W_up, W_down, bl: BlockList, tile_t: int, bl
 
 def lx_profile_begin(kernel: int, max_launches: int):
     _check(_lib.lx_profile_begin(kernel, max_launches), "lx_profile_begin")
+
+
+def lx_attn_set_rows_per_workgroup(rows: int):
+    _check(_lib.lx_attn_set_rows_per_workgroup(rows), "lx_attn_set_rows_per_workgroup")
 
 
 def lx_profile_end():

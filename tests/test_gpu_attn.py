@@ -88,6 +88,32 @@ def test_small_shapes(lx, oracle, kw, seed):
     check(run_gpu(lx, c), run_oracle(oracle, c), str(kw))
 
 
+@pytest.mark.parametrize("kw,seed", [
+    (dict(B=2, Hh=3, S=448, D=64, density=0.4), 31),            # 7 blocks: ragged last group
+    (dict(B=1, Hh=2, S=320, D=128, density=0.5), 32),
+    (dict(B=1, Hh=2, S=576, D=64, density=0.25, causal=False), 33),
+    (dict(B=2, Hh=2, S=256, D=64, density=0.3, head_keep=0.5), 34),
+])
+def test_rows_per_workgroup(lx, oracle, kw, seed):
+    """A workgroup that walks several rows of the mask as one stream of blocks gives the
+    same bits as one workgroup per row, and both match the oracle."""
+    c = inputs.attn_blocks(seed=seed, dtype="bf16", **kw)
+    ref = run_oracle(oracle, c)
+    try:
+        outs = {}
+        for r in (1, 2, 3, 4):
+            lx.lx_attn_set_rows_per_workgroup(r)
+            outs[r] = run_gpu(lx, c)
+            check(outs[r], ref, f"{kw} rows/wg={r}")
+        for r in (2, 3, 4):
+            for k in outs[1]:
+                assert np.array_equal(outs[r][k], outs[1][k], equal_nan=True), (r, k)
+    finally:
+        lx.lx_attn_set_rows_per_workgroup(0)
+    with pytest.raises(Exception):
+        lx.lx_attn_set_rows_per_workgroup(5)
+
+
 def test_strided_layout(lx, oracle):
     """[B,S,Hh,D] storage (heads interleaved) through the stride arguments."""
     c = inputs.attn_blocks(2, 3, 192, 64, 0.5, seed=21, dtype="bf16")
