@@ -90,16 +90,28 @@ __device__ __forceinline__ void mma_rows(const uint16_t* tile, const uint4 (&fra
                                          f32x16 (&acc)[2]) {
   const int lane = threadIdx.x % kWave, r = lane % 32, h2 = lane / 32;
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // The operand reads are issued ahead of the MFMAs that use them (all 2 * D/16 of them for
+  // D = 64, one half at a time for D = 128, where registers are short), so their LDS latency is
+  // paid once instead of once per k16 slice.
+  constexpr int kGroup = D == 64 ? 2 : 1;   // halves per group of reads
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const int row = 32 * half + r;
+  for (int h0 = 0; h0 < 2; h0 += kGroup) {
+    uint4 a[kGroup][D / 16];
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      const uint4 a = *reinterpret_cast<const uint4*>(tile + row * D +
-                                                      (((2 * s + h2) ^ tswz<D>(row)) << 3));
-      // the first product starts from a literal zero (no register clearing); acc is overwritten
-      acc[half] = mfma32(a, frag[s], s == 0 ? zero16 : acc[half]);
+    for (int hh = 0; hh < kGroup; ++hh) {
+      const int row = 32 * (h0 + hh) + r;
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s)
+        a[hh][s] =
+            *reinterpret_cast<const uint4*>(tile + row * D + (((2 * s + h2) ^ tswz<D>(row)) << 3));
     }
+    __builtin_amdgcn_sched_barrier(0);   // keep the reads above: the scheduler would sink them
+#pragma unroll
+    for (int hh = 0; hh < kGroup; ++hh)
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s)
+        // the first product starts from a literal zero (no register clearing)
+        acc[h0 + hh] = mfma32(a[hh][s], frag[s], s == 0 ? zero16 : acc[h0 + hh]);
   }
 }
 
@@ -125,23 +137,20 @@ struct ListRow {
   }
 };
 
-// out[ct] += T^T . P   where T is a row-major [64 x D] tile in LDS (read transposed) and
-// p[half][v] the accumulator-layout values of the [64 x 32] factor (rounded to bf16 here).
-template <int D>
-__device__ __forceinline__ void mma_transposed(const uint16_t* tile, const f32x16 (&p)[2],
-                                               f32x16 (&out)[D / 32]) {
+// Operands of out[ct] += T^T . P for the k-slices s2 = S0 .. S0+NS2-1 (16 rows of T each), read
+// from the row-major [64 x D] tile T in LDS with the transposing read.
+template <int D, int NS2>
+struct TrOps {
+  uint4 a[NS2][D / 32];
+};
+template <int D, int NS2>
+__device__ __forceinline__ void load_tr(const uint16_t* tile, int s2_0, TrOps<D, NS2>& t) {
   const int lane = threadIdx.x % kWave, h2 = lane / 32;
   const int j = lane % 16, e = j / 4, q = j % 4;
   const int cbase = 16 * ((lane / 16) % 2) + 4 * q;      // + 32*ct
 #pragma unroll
-  for (int s2 = 0; s2 < 4; ++s2) {
-    const int half = s2 / 2, g0 = 2 * (s2 % 2);
-    uint4 b;
-    b.x = pack2bf(p[half][4 * g0 + 0], p[half][4 * g0 + 1]);
-    b.y = pack2bf(p[half][4 * g0 + 2], p[half][4 * g0 + 3]);
-    b.z = pack2bf(p[half][4 * g0 + 4], p[half][4 * g0 + 5]);
-    b.w = pack2bf(p[half][4 * g0 + 6], p[half][4 * g0 + 7]);
-    const int r_lo = 16 * s2 + 4 * h2 + e, r_hi = r_lo + 8;
+  for (int i = 0; i < NS2; ++i) {
+    const int r_lo = 16 * (s2_0 + i) + 4 * h2 + e, r_hi = r_lo + 8;
 #pragma unroll
     for (int ct = 0; ct < D / 32; ++ct) {
       const int col = 32 * ct + cbase;
@@ -151,8 +160,36 @@ __device__ __forceinline__ void mma_transposed(const uint16_t* tile, const f32x1
           uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LX_AS3 short4v*)p_lo));
       const uint2 hi = __builtin_bit_cast(
           uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LX_AS3 short4v*)p_hi));
-      out[ct] = mfma32(make_uint4(lo.x, lo.y, hi.x, hi.y), b, out[ct]);
+      t.a[i][ct] = make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
+  }
+}
+// p[half][v]: accumulator-layout values of the [64 x 32] factor P (rounded to bf16 here).
+template <int D, int NS2>
+__device__ __forceinline__ void mma_tr(const TrOps<D, NS2>& t, int s2_0, const f32x16 (&p)[2],
+                                       f32x16 (&out)[D / 32]) {
+#pragma unroll
+  for (int i = 0; i < NS2; ++i) {
+    const int s2 = s2_0 + i, half = s2 / 2, g0 = 2 * (s2 % 2);
+    uint4 b;
+    b.x = pack2bf(p[half][4 * g0 + 0], p[half][4 * g0 + 1]);
+    b.y = pack2bf(p[half][4 * g0 + 2], p[half][4 * g0 + 3]);
+    b.z = pack2bf(p[half][4 * g0 + 4], p[half][4 * g0 + 5]);
+    b.w = pack2bf(p[half][4 * g0 + 6], p[half][4 * g0 + 7]);
+#pragma unroll
+    for (int ct = 0; ct < D / 32; ++ct) out[ct] = mfma32(t.a[i][ct], b, out[ct]);
+  }
+}
+// out[ct] += T^T . P with the reads of two k-slices grouped ahead of their MFMAs.
+template <int D>
+__device__ __forceinline__ void mma_transposed(const uint16_t* tile, const f32x16 (&p)[2],
+                                               f32x16 (&out)[D / 32]) {
+#pragma unroll
+  for (int s2 = 0; s2 < 4; s2 += 2) {
+    TrOps<D, 2> t;
+    load_tr<D, 2>(tile, s2, t);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_tr<D, 2>(t, s2, p, out);
   }
 }
 
@@ -215,6 +252,9 @@ struct RowSet {
         rs[j] = row_ptr[head_row0 + bj];
         n[j] = head_on ? row_ptr[head_row0 + bj + 1] - rs[j] : 0;
       }
+      // wave-uniform by construction; say so, to keep the walk's control flow scalar
+      rs[j] = __builtin_amdgcn_readfirstlane(rs[j]);
+      n[j] = __builtin_amdgcn_readfirstlane(n[j]);
     }
 #pragma unroll
     for (int j = 0; j < kRMax; ++j) {
@@ -248,13 +288,13 @@ struct RowSet {
 template <class RowBegin, class Issue, class Comp, class RowEnd>
 __device__ __forceinline__ void walk_rows(RowSet& rows, RowBegin row_begin, Issue issue, Comp comp,
                                           RowEnd row_end) {
-  int ki = rows.next_row(0), iti = 0;
+  int ki = __builtin_amdgcn_readfirstlane(rows.next_row(0)), iti = 0;
   if (ki >= kRMax) return;
   issue(0, ki, iti);
   int kc = ki, itc = 0, nc = pick(rows.n, kc);
   auto advance = [&]() {
     if (++iti == pick(rows.n, ki)) {
-      ki = rows.next_row(ki + 1);
+      ki = __builtin_amdgcn_readfirstlane(rows.next_row(ki + 1));
       iti = 0;
     }
   };
@@ -339,6 +379,13 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const Attn
     constexpr bool DIAG = decltype(diag_tag)::value;
     f32x16 s_acc[2];
     mma_rows<D>(stg, qf, s_acc);           // S^T[key][q]
+    // D = 64: the V^T operands do not depend on the scores; reading them now hides their LDS
+    // latency behind the softmax arithmetic
+    TrOps<D, D == 64 ? 4 : 1> vt;
+    if (D == 64) {
+      load_tr<D, D == 64 ? 4 : 1>(stg + 64 * D, 0, vt);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     float mloc = -INFINITY;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
@@ -371,7 +418,10 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const Attn
 #pragma unroll
         for (int v = 0; v < 16; ++v) o_acc[ct][v] *= alpha;
     }
-    mma_transposed<D>(stg + 64 * D, s_acc, o_acc);   // O^T += V^T P^T
+    if (D == 64)                                     // O^T += V^T P^T
+      mma_tr<D, D == 64 ? 4 : 1>(vt, 0, s_acc, o_acc);
+    else
+      mma_transposed<D>(stg + 64 * D, s_acc, o_acc);
   };
   auto comp = [&](int stage, int k, int it) {
     if (a.causal && rows.col(k, it) == qb)
