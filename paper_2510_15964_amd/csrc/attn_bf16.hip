@@ -4,10 +4,18 @@
 // only in registers; the unit of work is the listed block, which is what keeps
 // heads with different patterns balanced (Sec. VI-A, online combination).
 //
-// Layout of one workgroup (128 threads = 2 wavefronts): a 64-row query block
-// (forward, dQ) or a 64-row key block (dK/dV) at a time; each wavefront owns 32
-// of the rows and walks the block list of its row of the mask.  All products
-// run on the 32x32x16 bf16 MFMA with fp32 accumulators.
+// Layout of one workgroup (256 threads = 4 wavefronts): it works on a 64-row
+// query block (forward, dQ) or a 64-row key block (dK/dV) at a time -- its OWN
+// rows -- and streams the [64 x D] tiles of the blocks listed for that row of
+// the mask through LDS.  Wavefront w owns 32 of the own rows (w % 2) and works
+// on 32 of the 64 rows of every streamed tile (w / 2).  The two wavefronts that
+// share own rows keep separate partial results (running maximum, sum and
+// output in the forward pass; gradient sums in the backward pass) and combine
+// them once per row of the mask, through LDS; inside the walk over the blocks
+// they never communicate.  Splitting the streamed tile, rather than giving a
+// wavefront more own rows, halves the time one block takes on the critical
+// path of a row, which is what bounds a kernel whose rows list few blocks.
+// All products run on the 32x32x16 bf16 MFMA with fp32 accumulators.
 //
 // At the block densities of the paper a row of the mask lists only a few
 // blocks, so a workgroup that handled one row would spend most of its life in
@@ -40,16 +48,14 @@
 
 namespace lx {
 
-#define LX_AS1 __attribute__((address_space(1)))
 #define LX_AS3 __attribute__((address_space(3)))
 
-constexpr int kAT = 128;                 // threads per workgroup
+constexpr int kAT = 256;                 // threads per workgroup
+constexpr int kAW = kAT / kWave;         // wavefronts per workgroup
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 typedef short short4v __attribute__((ext_vector_type(4)));
-struct TrueTag { static constexpr bool value = true; };
-struct FalseTag { static constexpr bool value = false; };
 
 template <int D>
 __device__ __forceinline__ int tswz(int row) {
@@ -62,13 +68,13 @@ template <int D>
 struct TileDma {
   static constexpr int kSlots = D / 8;            // 16-byte slots per row
   static constexpr int kRowsPer = 64 / kSlots;    // rows per DMA instruction
-  static constexpr int kPerWave = 64 / kRowsPer / 2;
+  static constexpr int kPerWave = 64 / kRowsPer / kAW;
   long long off[kPerWave];
   __device__ __forceinline__ void init(long long ld) {
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const int g = wave + 2 * u;
+      const int g = wave + kAW * u;
       const int row = kRowsPer * g + lane / kSlots;
       const int slot = (lane % kSlots) ^ tswz<D>(row);
       off[u] = (long long)row * ld + slot * 8;
@@ -78,119 +84,112 @@ struct TileDma {
   __device__ __forceinline__ void issue(uint32_t tile_addr, const uint16_t* g0) const {
     const int wave = threadIdx.x / kWave;
 #pragma unroll
-    for (int u = 0; u < kPerWave; ++u) dma16(g0 + off[u], tile_addr + (wave + 2 * u) * 1024);
+    for (int u = 0; u < kPerWave; ++u) dma16(g0 + off[u], tile_addr + (wave + kAW * u) * 1024);
   }
 };
 
-// acc[half] += R[rows 32*half + lane%32][:] . F^T   where R is a row-major tile in LDS and F the
-// per-lane register fragments (column index = lane%32).  Result register v of a lane is element
-// (row 32*half + 8*(v/4) + 4*(lane/32) + v%4, column lane%32).
+// LDS byte offsets inside a [64 x D] tile.  Element (row, col) sits at
+// row*2D + (((col/8) ^ tswz(row)) << 4) + (col%8)*2.  tswz is linear over XOR and the row, slot
+// and in-slot parts occupy disjoint bits, so the offset of (r0 + dr, c0 + dc) is the offset of
+// (r0, c0) XOR a compile-time constant whenever r0/dr and c0/dc have disjoint bits.  The kernels
+// keep ONE per-lane offset per access pattern in a register and derive every address of the
+// pattern with an XOR by a constant (tile base addresses are multiples of the tile size, so they
+// combine with OR): this is what keeps the address arithmetic out of the register budget.
 template <int D>
-__device__ __forceinline__ void mma_rows(const uint16_t* tile, const uint4 (&frag)[D / 16],
-                                         f32x16 (&acc)[2]) {
-  const int lane = threadIdx.x % kWave, r = lane % 32, h2 = lane / 32;
-  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  // The operand reads are issued ahead of the MFMAs that use them (all 2 * D/16 of them for
-  // D = 64, one half at a time for D = 128, where registers are short), so their LDS latency is
-  // paid once instead of once per k16 slice.
-  constexpr int kGroup = D == 64 ? 2 : 1;   // halves per group of reads
-#pragma unroll
-  for (int h0 = 0; h0 < 2; h0 += kGroup) {
-    uint4 a[kGroup][D / 16];
-#pragma unroll
-    for (int hh = 0; hh < kGroup; ++hh) {
-      const int row = 32 * (h0 + hh) + r;
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s)
-        a[hh][s] =
-            *reinterpret_cast<const uint4*>(tile + row * D + (((2 * s + h2) ^ tswz<D>(row)) << 3));
-    }
-    __builtin_amdgcn_sched_barrier(0);   // keep the reads above: the scheduler would sink them
-#pragma unroll
-    for (int hh = 0; hh < kGroup; ++hh)
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s)
-        // the first product starts from a literal zero (no register clearing)
-        acc[h0 + hh] = mfma32(a[hh][s], frag[s], s == 0 ? zero16 : acc[h0 + hh]);
-  }
+__device__ __forceinline__ constexpr uint32_t tile_off(int row, int col) {
+  return (uint32_t)(row * 2 * D + ((((col >> 3) ^ tswz<D>(row)) << 4)) + (col & 7) * 2);
+}
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
+  return __builtin_bit_cast(uint4, *reinterpret_cast<const LX_AS3 u32x4*>((uintptr_t)addr));
+}
+__device__ __forceinline__ uint2 lds_read8_tr(uint32_t addr) {
+  return __builtin_bit_cast(
+      uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LX_AS3 short4v*>((uintptr_t)addr)));
 }
 
-// One row of a block list, kept in a register (entry it of the row sits in lane it % 64), so the
-// walk over the list issues no memory loads: a load inside the pipelined loop would have to wait
-// on vmcnt and with it on the tile DMA that is deliberately left in flight.
-struct ListRow {
-  const int* p;
-  int n, chunk, cur;
-  __device__ __forceinline__ void init(const int* list, int n_) {
-    p = list;
-    n = n_;
-    chunk = -1;
-    cur = 0;
-  }
-  __device__ __forceinline__ int get(int it) {        // it is wave-uniform
-    if ((it >> 6) != chunk) {                         // only for rows longer than 64 entries
-      chunk = it >> 6;
-      const int i = chunk * 64 + (int)(threadIdx.x % kWave);
-      cur = i < n ? p[i] : 0;
-    }
-    return __builtin_amdgcn_readlane(cur, it & 63);
+// Per-lane offsets of the two access patterns of a wavefront that works on rows 32*half..+31
+// of the streamed tiles.
+template <int D>
+struct LaneOff {
+  uint32_t rows;   // mma_rows: element (32*half + lane%32, 8*(lane/32))
+  uint32_t tr;     // load_tr: element (32*half + 4*(lane/32) + (lane%16)/4, 16*((lane/16)%2) + 4*(lane%4))
+  __device__ __forceinline__ void init(int half) {
+    const int lane = threadIdx.x % kWave, h2 = lane / 32, j = lane % 16;
+    rows = tile_off<D>(32 * half + lane % 32, 8 * h2);
+    tr = tile_off<D>(32 * half + 4 * h2 + j / 4, 16 * ((lane / 16) % 2) + 4 * (j % 4));
   }
 };
 
-// Operands of out[ct] += T^T . P for the k-slices s2 = S0 .. S0+NS2-1 (16 rows of T each), read
-// from the row-major [64 x D] tile T in LDS with the transposing read.
-template <int D, int NS2>
-struct TrOps {
-  uint4 a[NS2][D / 32];
-};
-template <int D, int NS2>
-__device__ __forceinline__ void load_tr(const uint16_t* tile, int s2_0, TrOps<D, NS2>& t) {
-  const int lane = threadIdx.x % kWave, h2 = lane / 32;
-  const int j = lane % 16, e = j / 4, q = j % 4;
-  const int cbase = 16 * ((lane / 16) % 2) + 4 * q;      // + 32*ct
+// acc = R[rows 32*half + lane%32][:] . F^T   where R is a row-major tile in LDS (byte address
+// `tile`) and F the per-lane register fragments (column index = lane%32).  Result register v of
+// a lane is element (row 32*half + 8*(v/4) + 4*(lane/32) + v%4, column lane%32).  The operand
+// reads are issued ahead of the MFMAs, so their LDS latency is paid once, not once per k16 slice.
+template <int D>
+__device__ __forceinline__ void mma_rows(uint32_t tile, const LaneOff<D>& lo,
+                                         const uint4 (&frag)[D / 16], f32x16& acc) {
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const uint32_t a0 = tile | lo.rows;
+  uint4 a[D / 16];
 #pragma unroll
-  for (int i = 0; i < NS2; ++i) {
-    const int r_lo = 16 * (s2_0 + i) + 4 * h2 + e, r_hi = r_lo + 8;
+  for (int s = 0; s < D / 16; ++s) a[s] = lds_read16(a0 ^ tile_off<D>(0, 16 * s));
+  __builtin_amdgcn_sched_barrier(0);   // keep the reads above: the scheduler would sink them
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s)
+    // the first product starts from a literal zero (no register clearing)
+    acc = mfma32(a[s], frag[s], s == 0 ? zero16 : acc);
+}
+
+// Operands of out[ct] += T[rows 32*half ..+31][:]^T . P (two k-slices of 16 rows of T), read from
+// the row-major [64 x D] tile T in LDS (byte address `tile`) with the transposing read.
+template <int D>
+struct TrOps {
+  uint4 a[2][D / 32];
+};
+template <int D>
+__device__ __forceinline__ void load_tr(uint32_t tile, const LaneOff<D>& lo, TrOps<D>& t) {
+  const uint32_t a0 = tile | lo.tr;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int ct = 0; ct < D / 32; ++ct) {
-      const int col = 32 * ct + cbase;
-      const uint16_t* p_lo = tile + r_lo * D + (((col >> 3) ^ tswz<D>(r_lo)) << 3) + (col & 7);
-      const uint16_t* p_hi = tile + r_hi * D + (((col >> 3) ^ tswz<D>(r_hi)) << 3) + (col & 7);
-      const uint2 lo = __builtin_bit_cast(
-          uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LX_AS3 short4v*)p_lo));
-      const uint2 hi = __builtin_bit_cast(
-          uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LX_AS3 short4v*)p_hi));
-      t.a[i][ct] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      const uint2 l = lds_read8_tr(a0 ^ tile_off<D>(16 * i, 32 * ct));
+      const uint2 h = lds_read8_tr(a0 ^ tile_off<D>(16 * i + 8, 32 * ct));
+      t.a[i][ct] = make_uint4(l.x, l.y, h.x, h.y);
     }
-  }
 }
-// p[half][v]: accumulator-layout values of the [64 x 32] factor P (rounded to bf16 here).
-template <int D, int NS2>
-__device__ __forceinline__ void mma_tr(const TrOps<D, NS2>& t, int s2_0, const f32x16 (&p)[2],
-                                       f32x16 (&out)[D / 32]) {
+// p[v]: accumulator-layout values of the [32 x 32] factor P (rounded to bf16 here).
+template <int D>
+__device__ __forceinline__ void mma_tr(const TrOps<D>& t, const f32x16& p, f32x16 (&out)[D / 32]) {
 #pragma unroll
-  for (int i = 0; i < NS2; ++i) {
-    const int s2 = s2_0 + i, half = s2 / 2, g0 = 2 * (s2 % 2);
+  for (int i = 0; i < 2; ++i) {
     uint4 b;
-    b.x = pack2bf(p[half][4 * g0 + 0], p[half][4 * g0 + 1]);
-    b.y = pack2bf(p[half][4 * g0 + 2], p[half][4 * g0 + 3]);
-    b.z = pack2bf(p[half][4 * g0 + 4], p[half][4 * g0 + 5]);
-    b.w = pack2bf(p[half][4 * g0 + 6], p[half][4 * g0 + 7]);
+    b.x = pack2bf(p[8 * i + 0], p[8 * i + 1]);
+    b.y = pack2bf(p[8 * i + 2], p[8 * i + 3]);
+    b.z = pack2bf(p[8 * i + 4], p[8 * i + 5]);
+    b.w = pack2bf(p[8 * i + 6], p[8 * i + 7]);
 #pragma unroll
     for (int ct = 0; ct < D / 32; ++ct) out[ct] = mfma32(t.a[i][ct], b, out[ct]);
   }
 }
-// out[ct] += T^T . P with the reads of two k-slices grouped ahead of their MFMAs.
-template <int D>
-__device__ __forceinline__ void mma_transposed(const uint16_t* tile, const f32x16 (&p)[2],
-                                               f32x16 (&out)[D / 32]) {
+
+// Diagonal block of a causal mask, scores in accumulator layout with the streamed rows (index
+// 32*part + 8*(v/4) + 4*(lane/32) + v%4) being KEYS and the lane (32*own + lane%32) the QUERY:
+// keys after the query get -inf.  mask_diag_t: the same with the roles exchanged (rows are
+// queries, the lane is the key).
+__device__ __forceinline__ void mask_diag(f32x16& s, int own, int part) {
+  const int lane = threadIdx.x % kWave;
+  const int x = lane % 32 + 32 * (own - part) - 4 * (lane / 32);   // key 8*(v/4) + v%4 > x: excluded
 #pragma unroll
-  for (int s2 = 0; s2 < 4; s2 += 2) {
-    TrOps<D, 2> t;
-    load_tr<D, 2>(tile, s2, t);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_tr<D, 2>(t, s2, p, out);
-  }
+  for (int v = 0; v < 16; ++v)
+    if (8 * (v / 4) + v % 4 > x) s[v] = -INFINITY;
+}
+__device__ __forceinline__ void mask_diag_t(f32x16& s, int own, int part) {
+  const int lane = threadIdx.x % kWave;
+  const int x = lane % 32 + 32 * (own - part) - 4 * (lane / 32);   // query 8*(v/4) + v%4 < x: excluded
+#pragma unroll
+  for (int v = 0; v < 16; ++v)
+    if (8 * (v / 4) + v % 4 < x) s[v] = -INFINITY;
 }
 
 template <int N>
@@ -217,86 +216,105 @@ __device__ __forceinline__ void store_acc(const f32x16 (&acc)[D / 32], float mul
     }
 }
 
+// Exchange of accumulators between the two wavefronts that share own rows, through an LDS area
+// of 2 * (D/2) * 64 floats (exactly one stage of tiles): [own][register][lane], so that a
+// wavefront's 64 lanes write and read consecutive words.
+template <int D>
+__device__ __forceinline__ void put_acc(float* area, int own, const f32x16 (&acc)[D / 32]) {
+  float* p = area + own * (D / 2) * 64 + threadIdx.x % kWave;
+#pragma unroll
+  for (int ct = 0; ct < D / 32; ++ct)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) p[(16 * ct + v) * 64] = acc[ct][v];
+}
+// acc = acc * mine + other * theirs
+template <int D>
+__device__ __forceinline__ void merge_acc(const float* area, int own, float mine, float theirs,
+                                          f32x16 (&acc)[D / 32]) {
+  const float* p = area + own * (D / 2) * 64 + threadIdx.x % kWave;
+#pragma unroll
+  for (int ct = 0; ct < D / 32; ++ct)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[ct][v] = acc[ct][v] * mine + p[(16 * ct + v) * 64] * theirs;
+}
+
 // ---------------------------------------------------------------------------
 // rows of a workgroup and the walk over their blocks
 // ---------------------------------------------------------------------------
 constexpr int kRMax = 4;   // rows of the mask per workgroup, at most
 
-// Wave-uniform selection from a small array by a run-time index (stays in scalar registers).
-__device__ __forceinline__ int pick(const int (&v)[kRMax], int k) {
-  int r = v[0];
-#pragma unroll
-  for (int j = 1; j < kRMax; ++j) r = k == j ? v[j] : r;
-  return r;
-}
+typedef const __attribute__((address_space(4))) int* ScalarIntPtr;   // loads become scalar loads
 
 // The rows (query blocks, or key blocks for dK/dV) of one (batch, head) that workgroup g of G
-// owns: slot j holds block j*G + g for even j and (j+1)*G - 1 - g for odd j.  All metadata is
-// fetched here, before the walk, so the walk itself issues no dependent metadata loads.
+// owns: slot j holds block j*G + g for even j and (j+1)*G - 1 - g for odd j.  The row pointers
+// of all slots are fetched once, before the walk, and kept in a small LDS table; the walk reads
+// the table and the list entries with LDS reads and scalar loads, which are counted apart from
+// the vector-memory counter that the tile transfers are waited on.
 struct RowSet {
-  int blk[kRMax];   // block index of the slot, -1 = slot not used
-  int n[kRMax];     // listed blocks of that row (0 for an inactive head)
-  ListRow list[kRMax];
-  __device__ __forceinline__ void init(const int* __restrict__ row_ptr,
-                                       const int* __restrict__ col_idx, int head_row0, int nblk,
+  ScalarIntPtr col_idx;
+  const int* tab;   // LDS: blk[kRMax] (-1 = slot not used), rs[kRMax], n[kRMax]
+  // tab_lds: 3 * kRMax ints of LDS; contains a barrier: call from uniform control flow
+  __device__ __forceinline__ void init(int* tab_lds, const int* __restrict__ row_ptr,
+                                       const int* __restrict__ col_idx_, int head_row0, int nblk,
                                        int g, int G, int R, bool head_on) {
-    int rs[kRMax];
-#pragma unroll
-    for (int j = 0; j < kRMax; ++j) {
+    col_idx = (ScalarIntPtr)col_idx_;
+    tab = tab_lds;
+    const int j = threadIdx.x;
+    if (j < kRMax) {
       const int bj = (j & 1) ? (j + 1) * G - 1 - g : j * G + g;
       const bool used = j < R && bj < nblk;
-      blk[j] = used ? bj : -1;
-      rs[j] = 0;
-      n[j] = 0;
+      int rs = 0, n = 0;
       if (used) {
-        rs[j] = row_ptr[head_row0 + bj];
-        n[j] = head_on ? row_ptr[head_row0 + bj + 1] - rs[j] : 0;
+        rs = row_ptr[head_row0 + bj];
+        n = head_on ? row_ptr[head_row0 + bj + 1] - rs : 0;
       }
-      // wave-uniform by construction; say so, to keep the walk's control flow scalar
-      rs[j] = __builtin_amdgcn_readfirstlane(rs[j]);
-      n[j] = __builtin_amdgcn_readfirstlane(n[j]);
+      tab_lds[j] = used ? bj : -1;
+      tab_lds[kRMax + j] = rs;
+      tab_lds[2 * kRMax + j] = n;
     }
-#pragma unroll
-    for (int j = 0; j < kRMax; ++j) {
-      list[j].init(col_idx + rs[j], n[j]);
-      if (n[j] > 0) list[j].get(0);   // fetch the first 64 entries now
-    }
+    __syncthreads();
   }
-  // listed block `it` of slot k (both wave-uniform)
-  __device__ __forceinline__ int col(int k, int it) {
-    int c = 0;
-#pragma unroll
-    for (int j = 0; j < kRMax; ++j)
-      if (k == j) c = list[j].get(it);
-    return c;
+  // k is wave-uniform; so are the results, and they are made scalar registers
+  __device__ __forceinline__ int blk(int k) const { return __builtin_amdgcn_readfirstlane(tab[k]); }
+  __device__ __forceinline__ int rs(int k) const {
+    return __builtin_amdgcn_readfirstlane(tab[kRMax + k]);
   }
+  __device__ __forceinline__ int n(int k) const {
+    return __builtin_amdgcn_readfirstlane(tab[2 * kRMax + k]);
+  }
+  // listed block `it` of slot k (both wave-uniform, it < n(k))
+  __device__ __forceinline__ int col(int k, int it) const { return col_idx[rs(k) + it]; }
   // first slot >= k with a non-empty list, kRMax if none
   __device__ __forceinline__ int next_row(int k) const {
-    int r = kRMax;
-#pragma unroll
-    for (int j = kRMax - 1; j >= 0; --j) r = (j >= k && n[j] > 0) ? j : r;
-    return r;
+    while (k < kRMax && n(k) == 0) ++k;
+    return k;
   }
 };
 
-// Walk over all listed blocks of the row set as one double-buffered stream.  issue(stage, k, it)
-// starts the transfer of block `it` of slot k into stage 0/1; comp(stage, k, it) consumes it;
-// row_begin(k) / row_end(k) load and store the per-row state.  The transfer of the next block,
-// which may belong to the next row, is issued before the current one is computed.  A wave first
-// waits for its own transfers (vmcnt), the barrier then makes the whole stage visible and
-// retires the reads of the stage about to be refilled.  All control flow is workgroup-uniform.
+// Walk over all listed blocks of the row set as one double-buffered stream.  issue(stage, col)
+// starts the transfer of the tiles of block `col` into stage 0/1; comp(stage, col) consumes
+// them; row_begin(k) loads the per-row state, row_end(k, stage) combines and stores it and may
+// use the LDS of `stage` (the one just consumed) after a barrier of its own.  The transfer of
+// the next block, which may belong to the next row, is issued before the current one is
+// computed, and the list entry after that one is fetched at the same time.  A wave first waits
+// for its own transfers (vmcnt), the barrier then makes the whole stage visible and retires the
+// reads of the stage about to be refilled.  All control flow is workgroup-uniform.
 template <class RowBegin, class Issue, class Comp, class RowEnd>
-__device__ __forceinline__ void walk_rows(RowSet& rows, RowBegin row_begin, Issue issue, Comp comp,
-                                          RowEnd row_end) {
-  int ki = __builtin_amdgcn_readfirstlane(rows.next_row(0)), iti = 0;
+__device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin, Issue issue,
+                                          Comp comp, RowEnd row_end) {
+  int ki = rows.next_row(0), iti = 0;
   if (ki >= kRMax) return;
-  issue(0, ki, iti);
-  int kc = ki, itc = 0, nc = pick(rows.n, kc);
+  int ni = rows.n(ki);                 // length of the list the issue side is in
+  int coli = rows.col(ki, 0);          // block whose transfer is issued next
+  issue(0, coli);
+  int kc = ki, itc = 0, colc = coli, nc = ni;
   auto advance = [&]() {
-    if (++iti == pick(rows.n, ki)) {
-      ki = __builtin_amdgcn_readfirstlane(rows.next_row(ki + 1));
+    if (++iti == ni) {
+      ki = rows.next_row(ki + 1);
       iti = 0;
+      if (ki < kRMax) ni = rows.n(ki);
     }
+    if (ki < kRMax) coli = rows.col(ki, iti);
   };
   advance();
   row_begin(kc);
@@ -304,17 +322,18 @@ __device__ __forceinline__ void walk_rows(RowSet& rows, RowBegin row_begin, Issu
     wait_vmcnt<0>();
     lds_barrier();
     const bool more = ki < kRMax;
-    if (more) issue((t + 1) & 1, ki, iti);
-    comp(t & 1, kc, itc);
+    if (more) issue((t + 1) & 1, coli);
+    comp(t & 1, colc);
     const bool last = itc + 1 == nc;
-    if (last) row_end(kc);
+    if (last) row_end(kc, t & 1);
     if (!more) break;
     if (last) {
       row_begin(ki);
-      nc = pick(rows.n, ki);
+      nc = ni;
     }
     kc = ki;
     itc = iti;
+    colc = coli;
     advance();
   }
 }
@@ -323,41 +342,47 @@ __device__ __forceinline__ void walk_rows(RowSet& rows, RowBegin row_begin, Issu
 // forward: O, LSE for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
+__global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_fwd_bf16(const AttnArgs a) {
+  __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
+  __shared__ float xstat[2][2][64];   // [own][max, sum][lane] of the wavefronts with part 1
+  __shared__ int rowtab[3 * kRMax];
   const int nqb = a.S / 64;
   const int h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int ql = 32 * wave + lane % 32, h2 = lane / 32;
+  const int own = wave % 2, part = wave / 2;   // own query half, key half of every block
+  const int ql = 32 * own + lane % 32, h2 = lane / 32;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long stat_base = ((long long)b * a.Hh + h) * a.S;
   const uint32_t st_addr = lds_addr(&st[0][0]);
 
   RowSet rows;
-  rows.init(a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
+  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
             gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
   // rows without a listed block (or of an inactive head): O = 0, LSE = -inf, nothing to read
-#pragma unroll
-  for (int j = 0; j < kRMax; ++j)
-    if (rows.blk[j] >= 0 && rows.n[j] == 0) {
-      f32x16 z[D / 32];
-      zero(z);
-      store_acc<D>(z, 0.f, a.Out + base + (long long)(rows.blk[j] * 64 + ql) * a.ss);
-      if (h2 == 0) a.LSE[stat_base + rows.blk[j] * 64 + ql] = -INFINITY;
-    }
+  if (part == 0) {
+    for (int j = 0; j < kRMax; ++j)
+      if (rows.blk(j) >= 0 && rows.n(j) == 0) {
+        f32x16 z[D / 32];
+        zero(z);
+        store_acc<D>(z, 0.f, a.Out + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
+        if (h2 == 0) a.LSE[stat_base + rows.blk(j) * 64 + ql] = -INFINITY;
+      }
+  }
 
   TileDma<D> dma;
   dma.init(a.ss);
+  LaneOff<D> lo;
+  lo.init(part);
   const float sc = a.scale * kLog2e;
-  // state of the row being computed
+  // state of the row being computed (this wavefront's part of it)
   int qb = 0;
   long long qoff = 0;
   uint4 qf[D / 16];
   f32x16 o_acc[D / 32];
-  float m = -INFINITY, lsum = 0.f;
+  float m = -INFINITY, lsum = 0.f;   // running maximum (scaled log2 units) and sum
 
   auto row_begin = [&](int k) {
-    qb = pick(rows.blk, k);
+    qb = rows.blk(k);
     qoff = base + (long long)(qb * 64 + ql) * a.ss;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
@@ -366,75 +391,76 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const Attn
     m = -INFINITY;
     lsum = 0.f;
   };
-  auto issue = [&](int stage, int k, int it) {
-    const long long t0 = base + (long long)rows.col(k, it) * 64 * a.ss;
+  auto issue = [&](int stage, int col) {
+    const long long t0 = base + (long long)col * 64 * a.ss;
     const uint32_t dst = st_addr + stage * (4 * 64 * D);
     dma.issue(dst, a.K + t0);
     dma.issue(dst + 2 * 64 * D, a.V + t0);
   };
-  // DIAG: the diagonal block of a causal mask, where keys after the query are excluded.  Two
-  // separate instantiations (instead of a branch in the middle) keep the 32 score registers in
-  // place on both paths.
-  auto comp_body = [&](const uint16_t* stg, auto diag_tag) {
-    constexpr bool DIAG = decltype(diag_tag)::value;
-    f32x16 s_acc[2];
-    mma_rows<D>(stg, qf, s_acc);           // S^T[key][q]
-    // D = 64: the V^T operands do not depend on the scores; reading them now hides their LDS
-    // latency behind the softmax arithmetic
-    TrOps<D, D == 64 ? 4 : 1> vt;
-    if (D == 64) {
-      load_tr<D, D == 64 ? 4 : 1>(stg + 64 * D, 0, vt);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    float mloc = -INFINITY;
+  // diag: the diagonal block of a causal mask, where keys after the query are excluded.  Only
+  // the scores are touched inside that branch, so the accumulators have one definition on
+  // every path and stay in place.
+  auto comp = [&](int stage, int col) {
+    const uint32_t stg = st_addr + stage * (4 * 64 * D);
+    f32x16 s_acc;
+    mma_rows<D>(stg, lo, qf, s_acc);       // S^T[key][q]
+    // the V^T operands do not depend on the scores; reading them now hides their LDS latency
+    // behind the softmax arithmetic
+    TrOps<D> vt;
+    load_tr<D>(stg + 2 * 64 * D, lo, vt);
+    __builtin_amdgcn_sched_barrier(0);
+    if (a.causal && col == qb) mask_diag(s_acc, own, part);
+    float mloc = s_acc[0];
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        if (DIAG) {
-          const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
-          if (kl > ql) s_acc[half][v] = -INFINITY;
-        }
-        mloc = fmaxf(mloc, s_acc[half][v]);
-      }
+    for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, s_acc[v]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    const float m_new = fmaxf(m, mloc * sc);          // running max in scaled log2 units
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    const float m_new = fmaxf(m, mloc * sc);
+    // a query none of whose keys so far is allowed keeps m = -inf; subtracting 0 instead keeps
+    // the exponentials below at exp2(-inf) = 0 rather than exp2(-inf + inf)
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
     float psum = 0.f;
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -m_new));
-        s_acc[half][v] = p;
-        psum += p;
-      }
+    for (int v = 0; v < 16; ++v) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[v], sc, -m_use));
+      s_acc[v] = p;
+      psum += p;
+    }
     psum += __shfl_xor(psum, 32);
     lsum = lsum * alpha + psum;
     m = m_new;
-    if (__any(alpha != 1.f)) {            // the running maximum moved for some query
+    if (alpha != 1.f) {   // the running maximum moved for this query (lane-wise: the
+                          // accumulators are rescaled in place under the execution mask)
 #pragma unroll
       for (int ct = 0; ct < D / 32; ++ct)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o_acc[ct][v] *= alpha;
     }
-    if (D == 64)                                     // O^T += V^T P^T
-      mma_tr<D, D == 64 ? 4 : 1>(vt, 0, s_acc, o_acc);
-    else
-      mma_transposed<D>(stg + 64 * D, s_acc, o_acc);
+    mma_tr<D>(vt, s_acc, o_acc);          // O^T += V^T P^T
   };
-  auto comp = [&](int stage, int k, int it) {
-    if (a.causal && rows.col(k, it) == qb)
-      comp_body(st[stage], TrueTag{});
-    else
-      comp_body(st[stage], FalseTag{});
-  };
-  auto row_end = [&](int) {
-    const bool any = lsum > 0.f;
-    const float inv = any ? 1.f / lsum : 0.f;
-    store_acc<D>(o_acc, inv, a.Out + qoff);
-    if (h2 == 0)
-      a.LSE[stat_base + qb * 64 + ql] = any ? (m + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+  // combine the two key halves: (m, l, O) = (m0, l0, O0) (+) (m1, l1, O1)
+  auto row_end = [&](int, int stage) {
+    float* area = reinterpret_cast<float*>(st[stage]);
+    lds_barrier();                       // every wavefront is done with the tiles of this stage
+    if (part == 1) {
+      put_acc<D>(area, own, o_acc);
+      xstat[own][0][lane] = m;
+      xstat[own][1][lane] = lsum;
+    }
+    lds_barrier();
+    if (part == 0) {
+      const float m1 = xstat[own][0][lane], l1 = xstat[own][1][lane];
+      const float mt = fmaxf(m, m1);
+      const float mu = mt == -INFINITY ? 0.f : mt;
+      const float a0 = __builtin_amdgcn_exp2f(m - mu), a1 = __builtin_amdgcn_exp2f(m1 - mu);
+      const float l = lsum * a0 + l1 * a1;
+      const bool any = l > 0.f;
+      const float inv = any ? 1.f / l : 0.f;
+      merge_acc<D>(area, own, a0 * inv, a1 * inv, o_acc);
+      store_acc<D>(o_acc, 1.f, a.Out + qoff);
+      if (h2 == 0)
+        a.LSE[stat_base + qb * 64 + ql] = any ? (mt + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    }
   };
   walk_rows(rows, row_begin, issue, comp, row_end);
 }
@@ -443,34 +469,39 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_fwd_bf16(const Attn
 // backward, query side: Delta and dQ for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
+__global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_bwd_dq_bf16(const AttnArgs a) {
+  __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
+  __shared__ int rowtab[3 * kRMax];
   const int nqb = a.S / 64;
   const int h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int ql = 32 * wave + lane % 32, h2 = lane / 32;
+  const int own = wave % 2, part = wave / 2;   // own query half, key half of every block
+  const int ql = 32 * own + lane % 32, h2 = lane / 32;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long stat_base = ((long long)b * a.Hh + h) * a.S;
   const uint32_t st_addr = lds_addr(&st[0][0]);
 
   RowSet rows;
-  rows.init(a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
+  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
             gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
   // rows without a listed block (or of an inactive head): O = 0, hence Delta = 0 and dQ = 0
-#pragma unroll
-  for (int j = 0; j < kRMax; ++j)
-    if (rows.blk[j] >= 0 && rows.n[j] == 0) {
-      f32x16 z[D / 32];
-      zero(z);
-      store_acc<D>(z, 0.f, a.dQ + base + (long long)(rows.blk[j] * 64 + ql) * a.ss);
-      if (h2 == 0) {
-        a.Delta[stat_base + rows.blk[j] * 64 + ql] = 0.f;
-        a.NegLse2[stat_base + rows.blk[j] * 64 + ql] = INFINITY;
+  if (part == 0) {
+    for (int j = 0; j < kRMax; ++j)
+      if (rows.blk(j) >= 0 && rows.n(j) == 0) {
+        f32x16 z[D / 32];
+        zero(z);
+        store_acc<D>(z, 0.f, a.dQ + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
+        if (h2 == 0) {
+          a.Delta[stat_base + rows.blk(j) * 64 + ql] = 0.f;
+          a.NegLse2[stat_base + rows.blk(j) * 64 + ql] = INFINITY;
+        }
       }
-    }
+  }
 
   TileDma<D> dma;
   dma.init(a.ss);
+  LaneOff<D> lo;
+  lo.init(part);
   const float sc = a.scale * kLog2e;
   int qb = 0;
   long long qoff = 0;
@@ -479,9 +510,9 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const A
   f32x16 dq_acc[D / 32];
 
   auto row_begin = [&](int k) {
-    qb = pick(rows.blk, k);
+    qb = rows.blk(k);
     qoff = base + (long long)(qb * 64 + ql) * a.ss;
-    float part = 0.f;
+    float sum = 0.f;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
       qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
@@ -491,47 +522,48 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const A
       const uint32_t y[4] = {of.x, of.y, of.z, of.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        part += bf2f(x[e] & 0xFFFFu) * bf2f(y[e] & 0xFFFFu) + bf2f(x[e] >> 16) * bf2f(y[e] >> 16);
+        sum += bf2f(x[e] & 0xFFFFu) * bf2f(y[e] & 0xFFFFu) + bf2f(x[e] >> 16) * bf2f(y[e] >> 16);
     }
-    delta = part + __shfl_xor(part, 32);
+    delta = sum + __shfl_xor(sum, 32);
     lse2 = a.LSEin[stat_base + qb * 64 + ql] * kLog2e;
-    if (h2 == 0) {                     // for the key-side kernel: Delta and -LSE in log2 units
+    if (part == 0 && h2 == 0) {        // for the key-side kernel: Delta and -LSE in log2 units
       a.Delta[stat_base + qb * 64 + ql] = delta;
       a.NegLse2[stat_base + qb * 64 + ql] = -lse2;
     }
     zero(dq_acc);
   };
-  auto issue = [&](int stage, int k, int it) {
-    const long long t0 = base + (long long)rows.col(k, it) * 64 * a.ss;
+  auto issue = [&](int stage, int col) {
+    const long long t0 = base + (long long)col * 64 * a.ss;
     const uint32_t dst = st_addr + stage * (4 * 64 * D);
     dma.issue(dst, a.K + t0);
     dma.issue(dst + 2 * 64 * D, a.V + t0);
   };
-  auto comp_body = [&](const uint16_t* stg, auto diag_tag) {
-    constexpr bool DIAG = decltype(diag_tag)::value;
-    f32x16 s_acc[2], dp_acc[2];
-    mma_rows<D>(stg, qf, s_acc);              // S^T[key][q]
-    mma_rows<D>(stg + 64 * D, dof, dp_acc);   // dP^T[key][q]
+  auto comp = [&](int stage, int col) {
+    const uint32_t stg = st_addr + stage * (4 * 64 * D);
+    f32x16 s_acc, dp_acc;
+    mma_rows<D>(stg, lo, qf, s_acc);                    // S^T[key][q]
+    mma_rows<D>(stg + 2 * 64 * D, lo, dof, dp_acc);     // dP^T[key][q]
+    TrOps<D> kt;                                        // K^T operands: independent of the scores
+    load_tr<D>(stg, lo, kt);
+    __builtin_amdgcn_sched_barrier(0);
+    if (a.causal && col == qb) mask_diag(s_acc, own, part);   // excluded keys: P = exp2(-inf) = 0
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, -lse2));
-        if (DIAG) {
-          const int kl = 32 * half + 8 * (v / 4) + 4 * h2 + v % 4;
-          if (kl > ql) p = 0.f;
-        }
-        s_acc[half][v] = p * (dp_acc[half][v] - delta);   // dS^T
-      }
-    mma_transposed<D>(stg, s_acc, dq_acc);    // dQ^T += K^T dS^T
+    for (int v = 0; v < 16; ++v) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[v], sc, -lse2));
+      s_acc[v] = p * (dp_acc[v] - delta);   // dS^T
+    }
+    mma_tr<D>(kt, s_acc, dq_acc);           // dQ^T += K^T dS^T
   };
-  auto comp = [&](int stage, int k, int it) {
-    if (a.causal && rows.col(k, it) == qb)
-      comp_body(st[stage], TrueTag{});
-    else
-      comp_body(st[stage], FalseTag{});
+  auto row_end = [&](int, int stage) {     // dQ = sum over the two key halves
+    float* area = reinterpret_cast<float*>(st[stage]);
+    lds_barrier();
+    if (part == 1) put_acc<D>(area, own, dq_acc);
+    lds_barrier();
+    if (part == 0) {
+      merge_acc<D>(area, own, 1.f, 1.f, dq_acc);
+      store_acc<D>(dq_acc, a.scale, a.dQ + qoff);
+    }
   };
-  auto row_end = [&](int) { store_acc<D>(dq_acc, a.scale, a.dQ + qoff); };
   walk_rows(rows, row_begin, issue, comp, row_end);
 }
 
@@ -540,32 +572,37 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dq_bf16(const A
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st[2][2 * 64 * D];   // stage: Q tile, dO tile
+  __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: Q tile, dO tile
   __shared__ __attribute__((aligned(256))) float sstat[2][128];   // stage: -LSE*log2e [64], Delta [64]
+  __shared__ int rowtab[3 * kRMax];
   const int nkb = a.S / 64;
   const int h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int kl = 32 * wave + lane % 32, h2 = lane / 32;
+  const int own = wave % 2, part = wave / 2;   // own key half, query half of every block
+  const int kl = 32 * own + lane % 32, h2 = lane / 32;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long stat_base = ((long long)b * a.Hh + h) * a.S;
   const uint32_t st_addr = lds_addr(&st[0][0]), sstat_addr = lds_addr(&sstat[0][0]);
 
   RowSet rows;
-  rows.init(a.crow_ptr, a.ccol_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
+  rows.init(rowtab, a.crow_ptr, a.ccol_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
             blockIdx.x, gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
   // key blocks used by no query block: zero gradients, nothing to read
-#pragma unroll
-  for (int j = 0; j < kRMax; ++j)
-    if (rows.blk[j] >= 0 && rows.n[j] == 0) {
-      f32x16 z[D / 32];
-      zero(z);
-      const long long koff = base + (long long)(rows.blk[j] * 64 + kl) * a.ss;
-      store_acc<D>(z, 0.f, a.dV + koff);
-      store_acc<D>(z, 0.f, a.dK + koff);
-    }
+  if (part == 0) {
+    for (int j = 0; j < kRMax; ++j)
+      if (rows.blk(j) >= 0 && rows.n(j) == 0) {
+        f32x16 z[D / 32];
+        zero(z);
+        const long long koff = base + (long long)(rows.blk(j) * 64 + kl) * a.ss;
+        store_acc<D>(z, 0.f, a.dV + koff);
+        store_acc<D>(z, 0.f, a.dK + koff);
+      }
+  }
 
   TileDma<D> dma;
   dma.init(a.ss);
+  LaneOff<D> lo;
+  lo.init(part);
   const float sc = a.scale * kLog2e;
   const float* stat_src = wave == 0 ? a.NegLse2 : a.Delta;  // wave 0: -LSE*log2(e), wave 1: Delta
   int kb = 0;
@@ -574,7 +611,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
   f32x16 dk_acc[D / 32], dv_acc[D / 32];
 
   auto row_begin = [&](int k) {
-    kb = pick(rows.blk, k);
+    kb = rows.blk(k);
     koff = base + (long long)(kb * 64 + kl) * a.ss;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
@@ -584,48 +621,60 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
     zero(dk_acc);
     zero(dv_acc);
   };
-  auto issue = [&](int stage, int k, int it) {
-    const int qb = rows.col(k, it);
+  auto issue = [&](int stage, int qb) {
     const long long t0 = base + (long long)qb * 64 * a.ss;
     const uint32_t dst = st_addr + stage * (4 * 64 * D);
     dma.issue(dst, a.Q + t0);
     dma.issue(dst + 2 * 64 * D, a.dO + t0);
-    dma4(stat_src + stat_base + qb * 64 + lane, sstat_addr + stage * 512 + wave * 256);
+    if (wave < 2) dma4(stat_src + stat_base + qb * 64 + lane, sstat_addr + stage * 512 + wave * 256);
   };
-  auto comp_body = [&](const uint16_t* stg, const float* stt, auto diag_tag) {
-    constexpr bool DIAG = decltype(diag_tag)::value;
-    f32x16 s_acc[2], dp_acc[2];
-    mma_rows<D>(stg, kf, s_acc);               // S[q][key]
-    mma_rows<D>(stg + 64 * D, vf, dp_acc);     // dP[q][key]
+  auto comp = [&](int stage, int col) {
+    const uint32_t stg = st_addr + stage * (4 * 64 * D);
+    const float* stt = sstat[stage];
+    f32x16 s_acc, dp_acc;
+    mma_rows<D>(stg, lo, kf, s_acc);                   // S[q][key]
+    mma_rows<D>(stg + 2 * 64 * D, lo, vf, dp_acc);     // dP[q][key]
+    TrOps<D> dot;                                      // dO^T operands: independent of the scores
+    load_tr<D>(stg + 2 * 64 * D, lo, dot);
+    __builtin_amdgcn_sched_barrier(0);
+    // diagonal block: here the rows of the score tile are queries and the lane is the key
+    if (a.causal && col == kb) mask_diag_t(s_acc, own, part);
 #pragma unroll
-    for (int half = 0; half < 2; ++half)
+    for (int g = 0; g < 4; ++g) {
+      const int q0 = 8 * g + 4 * h2;                 // four consecutive queries of this half
+      const float4 nl = *reinterpret_cast<const float4*>(stt + 32 * part + q0);
+      const float4 dl = *reinterpret_cast<const float4*>(stt + 64 + 32 * part + q0);
+      const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int q0 = 32 * half + 8 * g + 4 * h2;            // four consecutive queries
-        const float4 nl = *reinterpret_cast<const float4*>(stt + q0);
-        const float4 dl = *reinterpret_cast<const float4*>(stt + 64 + q0);
-        const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int v = 4 * g + e;
-          float p = __builtin_amdgcn_exp2f(fmaf(s_acc[half][v], sc, nls[e]));
-          if (DIAG && kl > q0 + e) p = 0.f;
-          s_acc[half][v] = p;                                   // P
-          dp_acc[half][v] = p * (dp_acc[half][v] - dls[e]);     // dS
-        }
+      for (int e = 0; e < 4; ++e) {
+        const int v = 4 * g + e;
+        const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[v], sc, nls[e]));
+        s_acc[v] = p;                             // P
+        dp_acc[v] = p * (dp_acc[v] - dls[e]);     // dS
       }
-    mma_transposed<D>(stg + 64 * D, s_acc, dv_acc);   // dV^T += dO^T P
-    mma_transposed<D>(stg, dp_acc, dk_acc);           // dK^T += Q^T dS
+    }
+    mma_tr<D>(dot, s_acc, dv_acc);            // dV^T += dO^T P
+    TrOps<D> qt;
+    load_tr<D>(stg, lo, qt);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_tr<D>(qt, dp_acc, dk_acc);            // dK^T += Q^T dS
   };
-  auto comp = [&](int stage, int k, int it) {
-    if (a.causal && rows.col(k, it) == kb)
-      comp_body(st[stage], sstat[stage], TrueTag{});
-    else
-      comp_body(st[stage], sstat[stage], FalseTag{});
-  };
-  auto row_end = [&](int) {
-    store_acc<D>(dv_acc, 1.f, a.dV + koff);
-    store_acc<D>(dk_acc, a.scale, a.dK + koff);
+  // dV and dK = sums over the two query halves, exchanged one after the other through the
+  // same LDS area
+  auto row_end = [&](int, int stage) {
+    float* area = reinterpret_cast<float*>(st[stage]);
+    lds_barrier();
+    if (part == 1) put_acc<D>(area, own, dv_acc);
+    lds_barrier();
+    if (part == 0) merge_acc<D>(area, own, 1.f, 1.f, dv_acc);
+    lds_barrier();
+    if (part == 1) put_acc<D>(area, own, dk_acc);
+    lds_barrier();
+    if (part == 0) {
+      merge_acc<D>(area, own, 1.f, 1.f, dk_acc);
+      store_acc<D>(dv_acc, 1.f, a.dV + koff);
+      store_acc<D>(dk_acc, a.scale, a.dK + koff);
+    }
   };
   walk_rows(rows, row_begin, issue, comp, row_end);
 }
