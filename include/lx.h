@@ -246,10 +246,10 @@ lx_status lx_profile_end(float* total_ms, int32_t* launches);
  * A workgroup walks the block lists of `rows` rows of the mask (query blocks in
  * the forward and dQ kernels, key blocks in the dK/dV kernel) of one (batch,
  * head) as one stream of blocks.  rows = 0 (the default) lets the library
- * choose from the problem size; 1..4 fixes it for all later calls of this
- * process.  Results do not depend on it beyond the order of fp32 additions
- * inside a row, which it does not change.  Not thread-safe; returns
- * LX_ERR_INVALID_ARG outside 0..4.
+ * choose from the problem size; 1..8 fixes it for all later calls of this
+ * process.  Results do not depend on it: it changes neither the arithmetic of
+ * a row nor its order.  Not thread-safe; returns LX_ERR_INVALID_ARG outside
+ * 0..8.
  */
 lx_status lx_attn_set_rows_per_workgroup(int32_t rows);
 

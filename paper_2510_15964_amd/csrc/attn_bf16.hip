@@ -52,6 +52,8 @@ namespace lx {
 
 constexpr int kAT = 256;                 // threads per workgroup
 constexpr int kAW = kAT / kWave;         // wavefronts per workgroup
+// resident workgroups per CU (= wavefronts per SIMD) the D = 64 kernels are compiled for
+constexpr int kFwdOcc64 = 4, kDqOcc64 = 4, kDkvOcc64 = 2;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -241,7 +243,7 @@ __device__ __forceinline__ void merge_acc(const float* area, int own, float mine
 // ---------------------------------------------------------------------------
 // rows of a workgroup and the walk over their blocks
 // ---------------------------------------------------------------------------
-constexpr int kRMax = 4;   // rows of the mask per workgroup, at most
+constexpr int kRMax = 8;   // rows of the mask per workgroup, at most
 
 typedef const __attribute__((address_space(4))) int* ScalarIntPtr;   // loads become scalar loads
 
@@ -342,7 +344,7 @@ __device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin
 // forward: O, LSE for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_fwd_bf16(const AttnArgs a) {
+__global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   __shared__ float xstat[2][2][64];   // [own][max, sum][lane] of the wavefronts with part 1
   __shared__ int rowtab[3 * kRMax];
@@ -469,7 +471,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_fwd_bf16(const Attn
 // backward, query side: Delta and dQ for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_bwd_dq_bf16(const AttnArgs a) {
+__global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   __shared__ int rowtab[3 * kRMax];
   const int nqb = a.S / 64;
@@ -543,15 +545,17 @@ __global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_bwd_dq_bf16(const A
     f32x16 s_acc, dp_acc;
     mma_rows<D>(stg, lo, qf, s_acc);                    // S^T[key][q]
     mma_rows<D>(stg + 2 * 64 * D, lo, dof, dp_acc);     // dP^T[key][q]
-    TrOps<D> kt;                                        // K^T operands: independent of the scores
-    load_tr<D>(stg, lo, kt);
-    __builtin_amdgcn_sched_barrier(0);
     if (a.causal && col == qb) mask_diag(s_acc, own, part);   // excluded keys: P = exp2(-inf) = 0
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[v], sc, -lse2));
       s_acc[v] = p * (dp_acc[v] - delta);   // dS^T
     }
+    // registers are what limits the number of resident wavefronts here, so the K^T operands
+    // are read only now; the other wavefronts of the SIMD cover the latency
+    __builtin_amdgcn_sched_barrier(0);
+    TrOps<D> kt;
+    load_tr<D>(stg, lo, kt);
     mma_tr<D>(kt, s_acc, dq_acc);           // dQ^T += K^T dS^T
   };
   auto row_end = [&](int, int stage) {     // dQ = sum over the two key halves
@@ -571,7 +575,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? 3 : 2) void attn_bwd_dq_bf16(const A
 // backward, key side: dK and dV for the key blocks of one workgroup
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
+__global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: Q tile, dO tile
   __shared__ __attribute__((aligned(256))) float sstat[2][128];   // stage: -LSE*log2e [64], Delta [64]
   __shared__ int rowtab[3 * kRMax];
@@ -634,9 +638,6 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
     f32x16 s_acc, dp_acc;
     mma_rows<D>(stg, lo, kf, s_acc);                   // S[q][key]
     mma_rows<D>(stg + 2 * 64 * D, lo, vf, dp_acc);     // dP[q][key]
-    TrOps<D> dot;                                      // dO^T operands: independent of the scores
-    load_tr<D>(stg + 2 * 64 * D, lo, dot);
-    __builtin_amdgcn_sched_barrier(0);
     // diagonal block: here the rows of the score tile are queries and the lane is the key
     if (a.causal && col == kb) mask_diag_t(s_acc, own, part);
 #pragma unroll
@@ -653,6 +654,11 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
         dp_acc[v] = p * (dp_acc[v] - dls[e]);     // dS
       }
     }
+    // registers are what limits the number of resident wavefronts here, so the transposed
+    // operands are read only when they are needed
+    __builtin_amdgcn_sched_barrier(0);
+    TrOps<D> dot;
+    load_tr<D>(stg + 2 * 64 * D, lo, dot);
     mma_tr<D>(dot, s_acc, dv_acc);            // dV^T += dO^T P
     TrOps<D> qt;
     load_tr<D>(stg, lo, qt);
@@ -679,26 +685,29 @@ __global__ __launch_bounds__(kAT, D == 64 ? 2 : 1) void attn_bwd_dkv_bf16(const 
   walk_rows(rows, row_begin, issue, comp, row_end);
 }
 
-// Rows per workgroup: as many (up to kRMax) as still leave enough workgroups to fill the chip,
-// unless the caller fixed the number.
+// Rows per workgroup: the smallest of 1, 2, 4, 8 (even counts keep the groups of a causal mask
+// balanced) with which all workgroups of the launch are resident at once on the chip's `slots`
+// workgroup slots, unless the caller fixed the number.
 static int g_rows_per_wg = 0;
 hipError_t set_attn_rows_per_wg(int r) {
   if (r < 0 || r > kRMax) return hipErrorInvalidValue;
   g_rows_per_wg = r;
   return hipSuccess;
 }
-static int rows_per_wg(int nblk, int heads, int B) {
+static int rows_per_wg(int nblk, int heads, int B, int slots) {
   const long long total = (long long)nblk * heads * B;
-  int r = g_rows_per_wg > 0 ? g_rows_per_wg : (int)(total / 1024);
-  r = r < 1 ? 1 : (r > kRMax ? kRMax : r);
+  int r = 1;
+  while (r < kRMax && total > (long long)slots * r) r *= 2;
+  if (g_rows_per_wg > 0) r = g_rows_per_wg;
   return r > nblk ? nblk : r;
 }
+constexpr int kCUs = 256;   // compute units of the chip: slots = kCUs * resident workgroups per CU
 
 template <int D>
 static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
   ProfScope ps(kKAttnFwd, st);
   const int nblk = a.S / 64;
-  a.rows_per_wg = rows_per_wg(nblk, a.Hh, B);
+  a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kFwdOcc64 : 2));
   const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
   hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
   return hipGetLastError();
@@ -707,16 +716,18 @@ static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
 template <int D>
 static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
   const int nblk = a.S / 64;
-  a.rows_per_wg = rows_per_wg(nblk, a.Hh, B);
-  const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
   {
     ProfScope ps(kKAttnDq, st);
+    a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDqOcc64 : 2));
+    const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
     hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   {
     ProfScope ps(kKAttnDkv, st);
+    a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDkvOcc64 : 1));
+    const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
     hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
   }
   return hipGetLastError();

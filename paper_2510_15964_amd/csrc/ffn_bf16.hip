@@ -37,6 +37,10 @@ constexpr int kRowsA = 256;        // per-wave operand (4 x 64 weight rows)
 constexpr int kStageRows = kRowsA + kRowsB;
 constexpr int kStageElems = kStageRows * kBK;                 // 20480 elements = 40 KiB
 constexpr int kIssues = kStageRows / 8 / (kThreads / kWave);  // DMA instructions per wave per stage
+// Ring depths.  Measured on the 11 %-dense FFN of the benchmark: a fourth stage (all 160 KiB of
+// LDS) does not help the sdd kernels, and the dsd kernel is faster with two resident
+// workgroups of two stages each than with one workgroup of three or four.
+constexpr int kSddStages = 3, kDsdStages = 2;
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
@@ -78,72 +82,40 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
     for (int ti = 0; ti < 2; ++ti) acc[ti] = mfma32(a[kk], b[kk][ti], acc[ti]);
 }
 
-// Three-stage pipeline over nsteps K-steps: while step s is multiplied, the DMA of steps s+1
-// and s+2 is in flight.  offs(s, offB, offA) yields the element offsets of step s.  A wave
-// first waits until its own DMA of step s has landed (its loads retire in order, so at most the
-// kIssues loads of step s+1 may still be outstanding), the barrier then guarantees that the
-// whole stage is there and that nobody still reads the stage about to be refilled.
-__device__ __forceinline__ void wait_stage(bool next_in_flight) {
-  if (next_in_flight)
-    __builtin_amdgcn_s_waitcnt(0x0F70 | kIssues);   // vmcnt(kIssues), kIssues < 16
-  else
-    __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0)
-  lds_barrier();
-}
-
-template <class Offs>
-__device__ __forceinline__ void run_pipeline(int nsteps, bool wave_on,
-                                             const uint16_t* const (&src)[kIssues], Offs offs,
-                                             uint16_t* st0, uint16_t* st1, uint16_t* st2,
-                                             f32x16 (&acc)[2]) {
-  static_assert(kIssues < 16, "vmcnt immediate");
+// Pipeline over nsteps K-steps through a ring of NST stages: while step s is multiplied, the
+// DMA of steps s+1 .. s+NST-1 is in flight (what bounds these kernels is how many bytes a CU
+// keeps in flight towards memory, so the ring is as deep as LDS allows).  offs(s, offB, offA)
+// yields the element offsets of step s.  A wave first waits until its own DMA of step s has
+// landed (its loads retire in order, so the loads of the younger steps may stay outstanding),
+// the barrier then guarantees that the whole stage is there and that nobody still reads the
+// stage about to be refilled.
+template <int NST, class Offs>
+__device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
+                                         const uint16_t* const (&src)[kIssues], Offs offs,
+                                         uint16_t* ring, f32x16 (&acc)[2]) {
+  static_assert(NST >= 2 && NST <= 4 && kIssues * (NST - 2) < 64, "ring depth");
   const int wave = threadIdx.x / kWave;
   long long ob, oa;
-  auto issue = [&](uint16_t* st, int s) {
+  auto issue = [&](int s, int stage) {
     offs(s, ob, oa);
-    issue_stage(st, src, ob, oa);
+    issue_stage(ring + stage * kStageElems, src, ob, oa);
   };
-  if (nsteps > 0) issue(st0, 0);
-  if (nsteps > 1) issue(st1, 1);
-  for (int s = 0; s < nsteps; s += 3) {
-    wait_stage(s + 1 < nsteps);
-    if (s + 2 < nsteps) issue(st2, s + 2);
-    if (wave_on) mma_step(st0, wave, acc);
-    if (s + 1 < nsteps) {
-      wait_stage(s + 2 < nsteps);
-      if (s + 3 < nsteps) issue(st0, s + 3);
-      if (wave_on) mma_step(st1, wave, acc);
-    }
-    if (s + 2 < nsteps) {
-      wait_stage(s + 3 < nsteps);
-      if (s + 4 < nsteps) issue(st1, s + 4);
-      if (wave_on) mma_step(st2, wave, acc);
-    }
-  }
-}
-
-// Two-stage variant (80 KiB of LDS, two workgroups per CU): used where the grid is large
-// enough that a second resident workgroup hides latency better than a third stage.
-template <class Offs>
-__device__ __forceinline__ void run_pipeline2(int nsteps, bool wave_on,
-                                              const uint16_t* const (&src)[kIssues], Offs offs,
-                                              uint16_t* st0, uint16_t* st1, f32x16 (&acc)[2]) {
-  const int wave = threadIdx.x / kWave;
-  long long ob, oa;
-  auto issue = [&](uint16_t* st, int s) {
-    offs(s, ob, oa);
-    issue_stage(st, src, ob, oa);
-  };
-  if (nsteps > 0) issue(st0, 0);
-  for (int s = 0; s < nsteps; s += 2) {
-    wait_stage(false);
-    if (s + 1 < nsteps) issue(st1, s + 1);
-    if (wave_on) mma_step(st0, wave, acc);
-    if (s + 1 < nsteps) {
-      wait_stage(false);
-      if (s + 2 < nsteps) issue(st0, s + 2);
-      if (wave_on) mma_step(st1, wave, acc);
-    }
+#pragma unroll
+  for (int p = 0; p < NST - 1; ++p)
+    if (p < nsteps) issue(p, p);
+  int stage = 0;
+  for (int s = 0; s < nsteps; ++s) {
+    const int younger = nsteps - 1 - s;   // steps after s whose DMA has been issued: min(., NST-2)
+    if (younger >= NST - 2)
+      wait_vmcnt<kIssues * (NST - 2)>();
+    else if (NST == 4 && younger == 1)
+      wait_vmcnt<kIssues>();
+    else
+      wait_vmcnt<0>();
+    lds_barrier();
+    if (s + NST - 1 < nsteps) issue(s + NST - 1, stage == 0 ? NST - 1 : stage - 1);
+    if (wave_on) mma_step(ring + stage * kStageElems, wave, acc);
+    stage = stage + 1 == NST ? 0 : stage + 1;
   }
 }
 
@@ -208,9 +180,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int rows, int K, uint16_t* __restrict__ out_act,
     const uint16_t* __restrict__ gate_act) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st0[kStageElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t st1[kStageElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t st2[kStageElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
   int i, chunk;
   if (!find_work(row_ptr, rows, blockIdx.x, 4, i, chunk)) return;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
@@ -236,9 +206,9 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   }
   f32x16 acc[2];
   zero_acc(acc);
-  run_pipeline(K / kBK, wave / 2 < nb, src,
-               [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; }, st0, st1,
-               st2, acc);
+  run_ring<kSddStages>(K / kBK, wave / 2 < nb, src,
+               [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; }, ring,
+                       acc);
   if (wave / 2 >= nb) return;
 
   const int p = p0 + wave / 2;
@@ -283,8 +253,7 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int ncols_out, uint16_t* __restrict__ out) {
-  __shared__ __attribute__((aligned(1024))) uint16_t st0[kStageElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t st1[kStageElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[kDsdStages * kStageElems];
   const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -304,13 +273,13 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   }
   f32x16 acc[2];
   zero_acc(acc);
-  run_pipeline2(n_i, wave_on, src,
+  run_ring<kDsdStages>(n_i, wave_on, src,
                [&](int s, long long& ob, long long& oa) {
                  const int p = rs + s;
                  ob = (long long)p * 4096;
                  oa = (long long)col_idx[p] * 64;
                },
-               st0, st1, acc);
+                       ring, acc);
   if (!wave_on) return;
 
   const int tl = lane % 32, nq = (lane / 32) * 4;

@@ -101,17 +101,17 @@ def test_rows_per_workgroup(lx, oracle, kw, seed):
     ref = run_oracle(oracle, c)
     try:
         outs = {}
-        for r in (1, 2, 3, 4):
+        for r in (1, 2, 3, 4, 8):
             lx.lx_attn_set_rows_per_workgroup(r)
             outs[r] = run_gpu(lx, c)
             check(outs[r], ref, f"{kw} rows/wg={r}")
-        for r in (2, 3, 4):
+        for r in (2, 3, 4, 8):
             for k in outs[1]:
                 assert np.array_equal(outs[r][k], outs[1][k], equal_nan=True), (r, k)
     finally:
         lx.lx_attn_set_rows_per_workgroup(0)
     with pytest.raises(Exception):
-        lx.lx_attn_set_rows_per_workgroup(5)
+        lx.lx_attn_set_rows_per_workgroup(9)
 
 
 def test_strided_layout(lx, oracle):
