@@ -248,7 +248,11 @@ constexpr int kRMax = 8;   // rows of the mask per workgroup, at most
 typedef const __attribute__((address_space(4))) int* ScalarIntPtr;   // loads become scalar loads
 
 // The rows (query blocks, or key blocks for dK/dV) of one (batch, head) that workgroup g of G
-// owns: slot j holds block j*G + g for even j and (j+1)*G - 1 - g for odd j.  The row pointers
+// owns: slot j holds block j*G + g for even j and (j+1)*G - 1 - g for odd j (counted from the
+// last block if `mirror`).  The group index is the slowest grid dimension and a causal mask
+// lists most blocks for the last query blocks and for the first key blocks, so with `mirror`
+// set for the query-side kernels the workgroups with the longest rows are dispatched first
+// whenever a launch takes more than one round of workgroups.  The row pointers
 // of all slots are fetched once, before the walk, and kept in a small LDS table; the walk reads
 // the table and the list entries with LDS reads and scalar loads, which are counted apart from
 // the vector-memory counter that the tile transfers are waited on.
@@ -258,13 +262,14 @@ struct RowSet {
   // tab_lds: 3 * kRMax ints of LDS; contains a barrier: call from uniform control flow
   __device__ __forceinline__ void init(int* tab_lds, const int* __restrict__ row_ptr,
                                        const int* __restrict__ col_idx_, int head_row0, int nblk,
-                                       int g, int G, int R, bool head_on) {
+                                       int g, int G, int R, bool mirror, bool head_on) {
     col_idx = (ScalarIntPtr)col_idx_;
     tab = tab_lds;
     const int j = threadIdx.x;
     if (j < kRMax) {
-      const int bj = (j & 1) ? (j + 1) * G - 1 - g : j * G + g;
+      int bj = (j & 1) ? (j + 1) * G - 1 - g : j * G + g;
       const bool used = j < R && bj < nblk;
+      if (mirror) bj = nblk - 1 - bj;
       int rs = 0, n = 0;
       if (used) {
         rs = row_ptr[head_row0 + bj];
@@ -349,7 +354,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
   __shared__ float xstat[2][2][64];   // [own][max, sum][lane] of the wavefronts with part 1
   __shared__ int rowtab[3 * kRMax];
   const int nqb = a.S / 64;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, b = blockIdx.y;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int own = wave % 2, part = wave / 2;   // own query half, key half of every block
   const int ql = 32 * own + lane % 32, h2 = lane / 32;
@@ -358,8 +363,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
   const uint32_t st_addr = lds_addr(&st[0][0]);
 
   RowSet rows;
-  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
-            gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
+  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
+            gridDim.z, a.rows_per_wg, true, !(a.head_active && !a.head_active[h]));
   // rows without a listed block (or of an inactive head): O = 0, LSE = -inf, nothing to read
   if (part == 0) {
     for (int j = 0; j < kRMax; ++j)
@@ -475,7 +480,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   __shared__ int rowtab[3 * kRMax];
   const int nqb = a.S / 64;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, b = blockIdx.y;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int own = wave % 2, part = wave / 2;   // own query half, key half of every block
   const int ql = 32 * own + lane % 32, h2 = lane / 32;
@@ -484,8 +489,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   const uint32_t st_addr = lds_addr(&st[0][0]);
 
   RowSet rows;
-  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.x,
-            gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
+  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
+            gridDim.z, a.rows_per_wg, true, !(a.head_active && !a.head_active[h]));
   // rows without a listed block (or of an inactive head): O = 0, hence Delta = 0 and dQ = 0
   if (part == 0) {
     for (int j = 0; j < kRMax; ++j)
@@ -580,7 +585,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   __shared__ __attribute__((aligned(256))) float sstat[2][128];   // stage: -LSE*log2e [64], Delta [64]
   __shared__ int rowtab[3 * kRMax];
   const int nkb = a.S / 64;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, b = blockIdx.y;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int own = wave % 2, part = wave / 2;   // own key half, query half of every block
   const int kl = 32 * own + lane % 32, h2 = lane / 32;
@@ -590,7 +595,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
 
   RowSet rows;
   rows.init(rowtab, a.crow_ptr, a.ccol_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
-            blockIdx.x, gridDim.x, a.rows_per_wg, !(a.head_active && !a.head_active[h]));
+            blockIdx.z, gridDim.z, a.rows_per_wg, false, !(a.head_active && !a.head_active[h]));
   // key blocks used by no query block: zero gradients, nothing to read
   if (part == 0) {
     for (int j = 0; j < kRMax; ++j)
@@ -709,7 +714,7 @@ static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
   const int nblk = a.S / 64;
   a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kFwdOcc64 : 2));
   const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-  hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
+  hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
   return hipGetLastError();
 }
 
@@ -720,7 +725,7 @@ static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
     ProfScope ps(kKAttnDq, st);
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDqOcc64 : 2));
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -728,7 +733,7 @@ static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
     ProfScope ps(kKAttnDkv, st);
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDkvOcc64 : 1));
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(G, a.Hh, B), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
   }
   return hipGetLastError();
 }
