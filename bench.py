@@ -154,6 +154,23 @@ class AttnJob:
 # algorithmic work per kernel launch (what the method must do)
 # ----------------------------------------------------------------------------
 
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` as measured with rocprofv3's FETCH_SIZE / WRITE_SIZE
+    counters (two --pmc runs of this script, scaled as the table's header explains); read from
+    the committed summary profiles/hbm_traffic_<workload>.txt, None if there is no entry."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                c = line.split()
+                if len(c) >= 5 and not line.startswith("#") and kernel in c[0].split("+"):
+                    return (float(c[1]) * float(c[2]) + float(c[3]) * float(c[4])) * 1024.0
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def kernel_model(lx, ffn_jobs, attn):
     """kernel id -> (launches per step, flops per launch, bytes per launch)."""
     fj = ffn_jobs[0]
@@ -276,7 +293,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
         roof = {"bound": "hbm", "achieved": by / dom_avg_s / 1e9, "peak": PEAK_HBM / 1e9,
                 "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(workload, lx.KERNEL_NAMES[dom])
     roof["kernel"] = lx.KERNEL_NAMES[dom]
     roof["avg_launch_us"] = dom_avg_s * 1e6
     roof["launches_timed"] = dom_n
