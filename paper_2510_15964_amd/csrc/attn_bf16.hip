@@ -53,9 +53,10 @@ namespace lx {
 constexpr int kAT = 256;                 // threads per workgroup
 constexpr int kAW = kAT / kWave;         // wavefronts per workgroup
 // resident workgroups per CU (= wavefronts per SIMD) the D = 64 kernels are compiled for
-constexpr int kFwdOcc64 = 4, kDqOcc64 = 4, kDkvOcc64 = 2;
+constexpr int kFwdOcc64 = 4, kDqOcc64 = 3, kDkvOcc64 = 2;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kSlack = 8.f;            // log2 units; see the forward kernel
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 
@@ -421,7 +422,12 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
 #pragma unroll
     for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, s_acc[v]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    const float m_new = fmaxf(m, mloc * sc);
+    // The reference point m of the running sums only has to bound the scores from above up to
+    // a factor that fp32 holds comfortably: it follows the running maximum only when that has
+    // moved by more than kSlack (then exp2(score - m) <= 2^kSlack), so most blocks need no
+    // rescaling of the accumulators.  Sums, output and LSE do not depend on the choice.
+    const float cand = mloc * sc;
+    const float m_new = cand > m + kSlack ? cand : m;
     // a query none of whose keys so far is allowed keeps m = -inf; subtracting 0 instead keeps
     // the exponentials below at exp2(-inf) = 0 rather than exp2(-inf + inf)
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
@@ -435,13 +441,14 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
     }
     psum += __shfl_xor(psum, 32);
     lsum = lsum * alpha + psum;
+    // (where m was -inf the accumulators are still zero: nothing to rescale.  Whole-vector
+    // products under a wave-uniform branch: a lane-wise branch around element updates can send
+    // the accumulators to scratch.)
+    const bool rescale = __any(alpha != 1.f && m != -INFINITY);
     m = m_new;
-    if (alpha != 1.f) {   // the running maximum moved for this query (lane-wise: the
-                          // accumulators are rescaled in place under the execution mask)
+    if (rescale) {
 #pragma unroll
-      for (int ct = 0; ct < D / 32; ++ct)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o_acc[ct][v] *= alpha;
+      for (int ct = 0; ct < D / 32; ++ct) o_acc[ct] *= alpha;
     }
     mma_tr<D>(vt, s_acc, o_acc);          // O^T += V^T P^T
   };
@@ -690,9 +697,9 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   walk_rows(rows, row_begin, issue, comp, row_end);
 }
 
-// Rows per workgroup: the smallest of 1, 2, 4, 8 (even counts keep the groups of a causal mask
-// balanced) with which all workgroups of the launch are resident at once on the chip's `slots`
-// workgroup slots, unless the caller fixed the number.
+// Rows per workgroup: the smallest count with which all workgroups of the launch are resident at
+// once on the chip's `slots` workgroup slots (a causal mask keeps the groups balanced for every
+// count, because slots are filled in pairs k, 2G-1-k), unless the caller fixed the number.
 static int g_rows_per_wg = 0;
 hipError_t set_attn_rows_per_wg(int r) {
   if (r < 0 || r > kRMax) return hipErrorInvalidValue;
@@ -700,9 +707,8 @@ hipError_t set_attn_rows_per_wg(int r) {
   return hipSuccess;
 }
 static int rows_per_wg(int nblk, int heads, int B, int slots) {
-  const long long total = (long long)nblk * heads * B;
   int r = 1;
-  while (r < kRMax && total > (long long)slots * r) r *= 2;
+  while (r < kRMax && (long long)((nblk + r - 1) / r) * heads * B > slots) ++r;
   if (g_rows_per_wg > 0) r = g_rows_per_wg;
   return r > nblk ? nblk : r;
 }

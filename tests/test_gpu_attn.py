@@ -53,8 +53,11 @@ def run_oracle(oracle, c):
     return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV)
 
 
-def check(got, ref, label=""):
+def check(got, ref, label="", fro_grad=None):
     tol = TOL["bf16"]
+    fro_gate = {k: FRO["bf16"] for k in ("O", "dQ", "dK", "dV")}
+    if fro_grad is not None:
+        fro_gate.update(dQ=fro_grad, dK=fro_grad, dV=fro_grad)
     ninf = np.isneginf(ref["LSE"])
     assert np.array_equal(np.isneginf(got["LSE"]), ninf), "rows without keys must give LSE = -inf"
     errs = {k: rel_err_max(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
@@ -66,7 +69,7 @@ def check(got, ref, label=""):
     for k in ("O", "dQ", "dK", "dV"):
         assert np.isfinite(got[k]).all(), k
         assert errs[k] <= tol, (k, errs[k])
-        assert fro[k] <= FRO["bf16"], (k, fro[k])
+        assert fro[k] <= fro_gate[k], (k, fro[k])
     assert errs["LSE"] <= 2e-2       # absolute, natural-log units
     # rows with no allowed key: exact zeros
     assert not got["O"][ninf].any() and not got["dQ"][ninf].any()
@@ -112,6 +115,18 @@ def test_rows_per_workgroup(lx, oracle, kw, seed):
         lx.lx_attn_set_rows_per_workgroup(0)
     with pytest.raises(Exception):
         lx.lx_attn_set_rows_per_workgroup(9)
+
+
+def test_large_score_range(lx, oracle):
+    """Scores spread over tens of log2 units: the running reference point of the online softmax
+    has to move repeatedly and the accumulators are rescaled (the forward kernel rescales only
+    when the maximum has moved by more than a slack, which N(0,1) scores rarely do)."""
+    c = inputs.attn_blocks(2, 2, 512, 64, 0.5, seed=41, dtype="bf16")
+    c["Q"] = c["Q"] * np.float32(8.0)          # exact in bf16
+    # With near-one-hot probabilities dS = P (dP - Delta) cancels strongly, so the one bf16
+    # rounding of dS weighs more in the gradients' Frobenius error (measured 5.5e-3) than the
+    # two-roundoff gate derived for ordinary scores allows; the forward outputs keep that gate.
+    check(run_gpu(lx, c), run_oracle(oracle, c), "large score range", fro_grad=1e-2)
 
 
 def test_strided_layout(lx, oracle):
