@@ -57,7 +57,10 @@ typedef enum { LX_F32 = 0, LX_BF16 = 1 } lx_dtype;
  *               column list used by the backward pass)
  * nnz_cap is a host-known upper bound on the number of active blocks (rows*cols
  * if nothing better is known); it sizes H_act and bounds launch grids, because
- * the true count lives only on the device.
+ * the true count lives only on the device.  If row_ptr counts more entries
+ * than nnz_cap (a bound that was too small), every call ignores the entries
+ * after the first nnz_cap in list order: the results are those of the
+ * truncated list and nothing outside the stated buffers is read or written.
  */
 typedef struct {
   int32_t rows;

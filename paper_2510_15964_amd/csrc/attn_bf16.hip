@@ -262,8 +262,8 @@ struct RowSet {
   const int* tab;   // LDS: blk[kRMax] (-1 = slot not used), rs[kRMax], n[kRMax]
   // tab_lds: 3 * kRMax ints of LDS; contains a barrier: call from uniform control flow
   __device__ __forceinline__ void init(int* tab_lds, const int* __restrict__ row_ptr,
-                                       const int* __restrict__ col_idx_, int head_row0, int nblk,
-                                       int g, int G, int R, bool mirror, bool head_on) {
+                                       const int* __restrict__ col_idx_, int cap, int head_row0,
+                                       int nblk, int g, int G, int R, bool mirror, bool head_on) {
     col_idx = (ScalarIntPtr)col_idx_;
     tab = tab_lds;
     const int j = threadIdx.x;
@@ -274,7 +274,8 @@ struct RowSet {
       int rs = 0, n = 0;
       if (used) {
         rs = row_ptr[head_row0 + bj];
-        n = head_on ? row_ptr[head_row0 + bj + 1] - rs : 0;
+        // entries beyond the capacity of the index buffer are ignored
+        n = head_on ? max(min(row_ptr[head_row0 + bj + 1], cap) - rs, 0) : 0;
       }
       tab_lds[j] = used ? bj : -1;
       tab_lds[kRMax + j] = rs;
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
   const uint32_t st_addr = lds_addr(&st[0][0]);
 
   RowSet rows;
-  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
+  rows.init(rowtab, a.row_ptr, a.col_idx, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
             gridDim.z, a.rows_per_wg, true, !(a.head_active && !a.head_active[h]));
   // rows without a listed block (or of an inactive head): O = 0, LSE = -inf, nothing to read
   if (part == 0) {
@@ -496,7 +497,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   const uint32_t st_addr = lds_addr(&st[0][0]);
 
   RowSet rows;
-  rows.init(rowtab, a.row_ptr, a.col_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
+  rows.init(rowtab, a.row_ptr, a.col_idx, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
             gridDim.z, a.rows_per_wg, true, !(a.head_active && !a.head_active[h]));
   // rows without a listed block (or of an inactive head): O = 0, hence Delta = 0 and dQ = 0
   if (part == 0) {
@@ -601,7 +602,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   const uint32_t st_addr = lds_addr(&st[0][0]), sstat_addr = lds_addr(&sstat[0][0]);
 
   RowSet rows;
-  rows.init(rowtab, a.crow_ptr, a.ccol_idx, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
+  rows.init(rowtab, a.crow_ptr, a.ccol_idx, a.cnnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
             blockIdx.z, gridDim.z, a.rows_per_wg, false, !(a.head_active && !a.head_active[h]));
   // key blocks used by no query block: zero gradients, nothing to read
   if (part == 0) {

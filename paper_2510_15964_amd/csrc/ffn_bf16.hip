@@ -178,15 +178,16 @@ template <int MODE>
 __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, int rows, int K, uint16_t* __restrict__ out_act,
-    const uint16_t* __restrict__ gate_act) {
+    const int* __restrict__ col_idx, int rows, int K, int nnz_cap,
+    uint16_t* __restrict__ out_act, const uint16_t* __restrict__ gate_act) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
   int i, chunk;
   if (!find_work(row_ptr, rows, blockIdx.x, 4, i, chunk)) return;
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
   const int first = chunk * 4;
-  const int nb = min(4, n_i - first);
   const int p0 = rs + first;
+  if (p0 >= nnz_cap) return;       // entries beyond the capacity of the list buffers are ignored
+  const int nb = min(min(4, n_i - first), nnz_cap - p0);
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
 
   // per-instruction source pointers of this lane (K offset added per step)
@@ -252,10 +253,11 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
 __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, int ncols_out, uint16_t* __restrict__ out) {
+    const int* __restrict__ col_idx, int ncols_out, int nnz_cap, uint16_t* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kDsdStages * kStageElems];
   const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
-  const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
+  const int rs = row_ptr[i];
+  const int n_i = min(row_ptr[i + 1], nnz_cap) - rs;   // <= 0: nothing listed within the capacity
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const bool wave_on = n0 + 64 * (wave / 2) < ncols_out;
 
@@ -320,16 +322,16 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
       hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, Tt,
-                         d, act_out, (const uint16_t*)nullptr);
+                         d, nnz_cap, act_out, (const uint16_t*)nullptr);
     else
       hipLaunchKernelGGL(ffn_sdd_bf16<1>, g1, dim3(kThreads), 0, st, A, W1,
-                         (const uint16_t*)nullptr, row_ptr, col_idx, Tt, d, act_out, act_gate);
+                         (const uint16_t*)nullptr, row_ptr, col_idx, Tt, d, nnz_cap, act_out, act_gate);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   hipLaunchKernelGGL(ffn_dsd_bf16, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
-                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, out);
+                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, nnz_cap, out);
   return hipGetLastError();
 }
 

@@ -54,7 +54,7 @@ __device__ __forceinline__ void gemm_nt_f32(const float* __restrict__ A, long lo
 template <int TT, int BN, int MODE>
 __global__ __launch_bounds__(kF32Threads) void ffn_sdd_f32(
     const float* __restrict__ A, const float* __restrict__ W, const float* __restrict__ bias,
-    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, int K,
+    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, int K, int nnz_cap,
     float* __restrict__ out_act, const float* __restrict__ gate_act) {
   __shared__ float As[TT * (kF32BK + 1)];
   __shared__ float Bs[BN * (kF32BK + 1)];
@@ -62,6 +62,7 @@ __global__ __launch_bounds__(kF32Threads) void ffn_sdd_f32(
   const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
   if ((int)blockIdx.x >= n_i) return;
   const int p = rs + blockIdx.x;
+  if (p >= nnz_cap) return;        // entries beyond the capacity of the list buffers are ignored
   const int j = col_idx[p];
   float acc[TT / 16][BN / 16] = {};
   gemm_nt_f32<TT, BN>(A + (long long)i * TT * K, K, W + (long long)j * BN * K, K, K, acc, As, Bs);
@@ -88,12 +89,12 @@ template <int TT, int BN>
 __global__ __launch_bounds__(kF32Threads) void ffn_dsd_f32(
     const float* __restrict__ act, const float* __restrict__ W, long long ldw,
     const float* __restrict__ bias, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, int ncols_out, float* __restrict__ out) {
+    const int* __restrict__ col_idx, int ncols_out, int nnz_cap, float* __restrict__ out) {
   constexpr int CT = 32;
   __shared__ float As[TT * (kF32BK + 1)];
   __shared__ float Bs[CT * (kF32BK + 1)];
   const int i = blockIdx.y, n0 = blockIdx.x * CT;
-  const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
+  const int rs = row_ptr[i], n_i = min(row_ptr[i + 1], nnz_cap) - rs;
   float acc[TT / 16][CT / 16] = {};
   for (int s = 0; s < n_i; ++s) {
     const int p = rs + s;
@@ -114,23 +115,23 @@ __global__ __launch_bounds__(kF32Threads) void ffn_dsd_f32(
 template <int TT, int BN>
 static hipError_t launch_f32(int pass, int Tt, int Fb, int d, int F, const float* A, const float* W1,
                              const float* b1, const float* W2, const float* b2, const int* row_ptr,
-                             const int* col_idx, float* act_out, const float* act_gate, float* out,
-                             hipStream_t st) {
+                             const int* col_idx, int nnz_cap, float* act_out,
+                             const float* act_gate, float* out, hipStream_t st) {
   // W1: [F, d] rows = neurons (contraction over d).  W2: [d, F] (contraction over active f).
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
       hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 0>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1,
-                         b1, row_ptr, col_idx, d, act_out, (const float*)nullptr);
+                         b1, row_ptr, col_idx, d, nnz_cap, act_out, (const float*)nullptr);
     else
       hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 1>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1,
-                         (const float*)nullptr, row_ptr, col_idx, d, act_out, act_gate);
+                         (const float*)nullptr, row_ptr, col_idx, d, nnz_cap, act_out, act_gate);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   hipLaunchKernelGGL((ffn_dsd_f32<TT, BN>), dim3(d / 32, Tt), dim3(kF32Threads), 0, st,
-                     (const float*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, out);
+                     (const float*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, nnz_cap, out);
   return hipGetLastError();
 }
 
@@ -139,13 +140,13 @@ static hipError_t launch_f32(int pass, int Tt, int Fb, int d, int F, const float
 //                    act_gate = H_act, out = dX
 hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, const float* A,
                           const float* W1, const float* b1, const float* W2, const float* b2,
-                          const int* row_ptr, const int* col_idx, float* act_out,
+                          const int* row_ptr, const int* col_idx, int nnz_cap, float* act_out,
                           const float* act_gate, float* out, hipStream_t st) {
   if (tile == 32)
-    return launch_f32<32, 32>(pass, Tt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, act_out,
-                              act_gate, out, st);
-  return launch_f32<64, 64>(pass, Tt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, act_out,
-                            act_gate, out, st);
+    return launch_f32<32, 32>(pass, Tt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap,
+                              act_out, act_gate, out, st);
+  return launch_f32<64, 64>(pass, Tt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap,
+                            act_out, act_gate, out, st);
 }
 
 // ---------------------------------------------------------------------------

@@ -215,7 +215,7 @@ lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_
   if (dt == LX_F32)
     e = launch_ffn_f32(0, tile_t, bl->rows, bl->cols, d, F, (const float*)X, (const float*)W_up,
                        (const float*)b_up, (const float*)W_down, (const float*)b_down, bl->row_ptr,
-                       bl->col_idx, (float*)act, nullptr, (float*)Y, (hipStream_t)stream);
+                       bl->col_idx, bl->nnz_cap, (float*)act, nullptr, (float*)Y, (hipStream_t)stream);
   else
     e = launch_ffn_bf16(0, bl->rows, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
                         (const uint16_t*)b_up, (const uint16_t*)W_down, (const uint16_t*)b_down,
@@ -258,7 +258,7 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
   if (dt == LX_F32)
     e = launch_ffn_f32(1, tile_t, bl->rows, bl->cols, d, F, (const float*)dY,
                        (const float*)W_down_t, nullptr, (const float*)W_up_t, nullptr, bl->row_ptr,
-                       bl->col_idx, (float*)dz, (const float*)H_act, (float*)dX, st);
+                       bl->col_idx, bl->nnz_cap, (float*)dz, (const float*)H_act, (float*)dX, st);
   else
     e = launch_ffn_bf16(1, bl->rows, bl->cols, d, F, (const uint16_t*)dY,
                         (const uint16_t*)W_down_t, nullptr, (const uint16_t*)W_up_t, nullptr,
@@ -305,7 +305,7 @@ lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int3
   a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
   a.Out = (uint16_t*)O; a.LSE = LSE;
   a.sb = strides_bhs[0]; a.sh = strides_bhs[1]; a.ss = strides_bhs[2];
-  a.row_ptr = bl->row_ptr; a.col_idx = bl->col_idx;
+  a.row_ptr = bl->row_ptr; a.col_idx = bl->col_idx; a.nnz_cap = bl->nnz_cap;
   a.head_active = head_active;
   a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
   return launch_attn_fwd_bf16(D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
@@ -335,8 +335,8 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
   a.Delta = (float*)workspace;
   a.NegLse2 = (float*)((char*)workspace + round256((size_t)B * Hh * S * sizeof(float)));
   a.sb = strides_bhs[0]; a.sh = strides_bhs[1]; a.ss = strides_bhs[2];
-  a.row_ptr = bl_rows->row_ptr; a.col_idx = bl_rows->col_idx;
-  a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx;
+  a.row_ptr = bl_rows->row_ptr; a.col_idx = bl_rows->col_idx; a.nnz_cap = bl_rows->nnz_cap;
+  a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx; a.cnnz_cap = bl_cols->nnz_cap;
   a.head_active = head_active;
   a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
   return launch_attn_bwd_bf16(D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;

@@ -29,6 +29,7 @@ struct AttnArgs {
   long long sb, sh, ss;
   const int *row_ptr, *col_idx;
   const int *crow_ptr, *ccol_idx;
+  int nnz_cap, cnnz_cap;   // capacities of col_idx / ccol_idx: entries beyond them are ignored
   const uint8_t* head_active;
   int Hh, S, mask_batch, causal;
   float scale;
@@ -51,7 +52,7 @@ hipError_t launch_compact_pair(const uint8_t*, int, int, int, long long, long lo
                                int*, int*, int*, int, hipStream_t);
 hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, const float* A,
                           const float* W1, const float* b1, const float* W2, const float* b2,
-                          const int* row_ptr, const int* col_idx, float* act_out,
+                          const int* row_ptr, const int* col_idx, int nnz_cap, float* act_out,
                           const float* act_gate, float* out, hipStream_t st);
 hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,

@@ -181,3 +181,30 @@ def test_config4_shape_sampled_heads(lx, oracle):
         sub = dict(c, Hh=1, mask=c["mask"][:, h:h + 1], head_active=np.ones(1, np.uint8),
                    **{k: c[k][:, h:h + 1] for k in ("Q", "K", "V", "dO")})
         check({k: v[:, h:h + 1] for k, v in got.items()}, run_oracle(oracle, sub), f"config4 h={h}")
+
+
+def test_list_longer_than_its_capacity_is_truncated(lx):
+    """Row list with a capacity bound that was too small: the forward pass ignores the entries
+    after the first nnz_cap and gives the bits of the truncated mask."""
+    import torch
+    c = inputs.attn_blocks(1, 2, 384, 64, 0.6, seed=51, dtype="bf16")
+    mask = c["mask"]                                   # [1, Hh, nb, nb]
+    nnz = int(mask.sum())
+    cap = nnz - 4
+    trunc = mask.copy()
+    idx = np.argwhere(mask.reshape(-1, mask.shape[-1]))   # (row, col) in list order
+    for r, col in idx[cap:]:
+        trunc.reshape(-1, mask.shape[-1])[r, col] = 0
+    Q, K, V = (dev(c[k], "bf16") for k in ("Q", "K", "V"))
+
+    def run(m):
+        bl = lx.lx_mask_compact(torch.from_numpy(np.ascontiguousarray(m)).cuda(), nnz_cap=cap)
+        O = torch.full_like(Q, float("nan"))
+        LSE = torch.full((c["B"], c["Hh"], c["S"]), float("nan"), dtype=torch.float32, device="cuda")
+        lx.lx_sparse_attn_fwd(Q, K, V, bl, c["scale"], c["causal"], O, LSE, mask_batch=1)
+        torch.cuda.synchronize()
+        return host(O), host(LSE)
+
+    a, b = run(mask), run(trunc)
+    assert np.isfinite(a[0]).all()
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])

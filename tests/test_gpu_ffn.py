@@ -200,3 +200,41 @@ def test_config2_bf16_full_size_sampled_tiles(lx, oracle):
     # tiles with no active block are exactly zero
     for i in np.nonzero(c["mask"].sum(1) == 0)[0]:
         assert not got["Y"][i * 64:(i + 1) * 64].any()
+
+
+@pytest.mark.parametrize("dtype,tile", [("f32", 32), ("bf16", 64)])
+def test_list_longer_than_its_capacity_is_truncated(lx, dtype, tile):
+    """A capacity bound that was too small: the entries after the first nnz_cap (list order)
+    are ignored by every call, nothing past the buffers is written, and the results are
+    bit-identical to those of the truncated mask."""
+    import torch
+    c = inputs.ffn_bernoulli(4 * tile, 256, 8 * tile, tile, tile, 0.4, seed=77, dtype=dtype)
+    mask = c["mask"]
+    nnz = int(mask.sum())
+    drop = 5
+    cap = nnz - drop
+    trunc = mask.copy()
+    rr, cc = np.nonzero(mask)                         # row-major = list order
+    trunc[rr[cap:], cc[cap:]] = 0
+    X, Wu, Wd, dY = (dev(c[k], dtype) for k in ("X", "W_up", "W_down", "dY"))
+
+    def run(m, nnz_cap):
+        bl = lx.lx_mask_compact(torch.from_numpy(m).cuda(), nnz_cap=nnz_cap)
+        H = torch.full((nnz_cap * tile * tile + 4096,), float("nan"), dtype=X.dtype, device="cuda")
+        Y = torch.full_like(X, float("nan"))
+        lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, tile, tile, Y, H)
+        assert torch.isnan(H[nnz_cap * tile * tile:]).all(), "wrote past the H_act buffer"
+        dtc = lx.LX_F32 if dtype == "f32" else lx.LX_BF16
+        ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(dtc, c["T"], c["d"], c["F"], tile,
+                                                              tile, nnz_cap, 0) + 256,
+                         dtype=torch.uint8, device="cuda")
+        dX = torch.full_like(X, float("nan"))
+        lx.lx_sparse_ffn_bwd_dx(dY, H, Wu, Wd, bl, tile, tile, dX, ws)
+        torch.cuda.synchronize()
+        return host(Y), host(dX), host(H[:nnz_cap * tile * tile])
+
+    a = run(mask, cap)        # true list longer than the capacity
+    b = run(trunc, cap)       # the truncated mask, exactly at capacity
+    for x, y in zip(a, b):
+        assert np.isfinite(x).all()
+        assert np.array_equal(x, y)
