@@ -20,12 +20,14 @@
 // At the block densities of the paper a row of the mask lists only a few
 // blocks, so a workgroup that handled one row would spend most of its life in
 // the chain of dependent loads that starts it (row pointer -> list -> tiles).
-// A workgroup therefore owns up to four rows of one (batch, head) and walks
+// A workgroup therefore owns up to eight rows of one (batch, head) and walks
 // their lists as ONE stream of blocks: the metadata of all its rows is read up
 // front, and the tile transfer of the next block -- of the same row or of the
 // next one -- is always in flight while the current block is computed.  The
-// rows are picked k, 2G-1-k, 2G+k, 4G-1-k (G = groups per head), which gives
-// every workgroup the same number of blocks under a causal mask.
+// rows of a head are ranked by the length of their lists and dealt to the
+// head's workgroups in a snake over the ranks, which evens out the number of
+// blocks per workgroup for any mask (all workgroups of a launch are resident at
+// once, so the launch lasts as long as its longest workgroup).
 //
 // Data movement: the [64 x D] tiles of the listed blocks go from global memory
 // straight into LDS (global_load_lds, 16 bytes per lane), double buffered.  The
@@ -249,11 +251,10 @@ constexpr int kRMax = 8;   // rows of the mask per workgroup, at most
 typedef const __attribute__((address_space(4))) int* ScalarIntPtr;   // loads become scalar loads
 
 // The rows (query blocks, or key blocks for dK/dV) of one (batch, head) that workgroup g of G
-// owns: slot j holds block j*G + g for even j and (j+1)*G - 1 - g for odd j (counted from the
-// last block if `mirror`).  The group index is the slowest grid dimension and a causal mask
-// lists most blocks for the last query blocks and for the first key blocks, so with `mirror`
-// set for the query-side kernels the workgroups with the longest rows are dispatched first
-// whenever a launch takes more than one round of workgroups.  The row pointers
+// owns (see init for how they are chosen; with more than 64 blocks per head: slot j holds block
+// j*G + g for even j and (j+1)*G - 1 - g for odd j, counted from the last block if `mirror`, so
+// that with the group index as the slowest grid dimension the longest rows of a causal mask are
+// dispatched first).  The row pointers
 // of all slots are fetched once, before the walk, and kept in a small LDS table; the walk reads
 // the table and the list entries with LDS reads and scalar loads, which are counted apart from
 // the vector-memory counter that the tile transfers are waited on.
@@ -266,15 +267,50 @@ struct RowSet {
                                        int nblk, int g, int G, int R, bool mirror, bool head_on) {
     col_idx = (ScalarIntPtr)col_idx_;
     tab = tab_lds;
-    const int j = threadIdx.x;
-    if (j < kRMax) {
+    const int tid = threadIdx.x;
+    if (nblk <= kWave) {
+      // Groups balanced by the actual lengths of the lists: the rows of the head are ranked by
+      // length (longest first, ties by index) and dealt to the G workgroups in a snake over the
+      // ranks, rank k going to slot k / G of workgroup k % G or G - 1 - k % G.  Every workgroup
+      // of the head computes the same ranking, one row per lane of its first wavefront.
+      if (tid < kWave) {
+        const bool valid = tid < nblk;
+        int rs = 0, n = -1;
+        if (valid) {
+          rs = row_ptr[head_row0 + tid];
+          // entries beyond the capacity of the index buffer are ignored
+          n = head_on ? max(min(row_ptr[head_row0 + tid + 1], cap) - rs, 0) : 0;
+        }
+        int rank = 0;
+        for (int q = 0; q < nblk; ++q) {
+          const int nq = __builtin_amdgcn_readlane(n, q);
+          rank += (nq > n || (nq == n && q < tid)) ? 1 : 0;
+        }
+        const int j = rank / G, pos = rank - j * G;
+        if (valid && ((j & 1) ? G - 1 - pos : pos) == g) {
+          tab_lds[j] = tid;
+          tab_lds[kRMax + j] = rs;
+          tab_lds[2 * kRMax + j] = n;
+        }
+      } else if (tid < kWave + kRMax) {
+        // slots whose rank does not exist (the head has fewer rows than G * kRMax)
+        const int j = tid - kWave;
+        const int rank = j * G + ((j & 1) ? G - 1 - g : g);
+        if (j >= R || rank >= nblk) {
+          tab_lds[j] = -1;
+          tab_lds[kRMax + j] = 0;
+          tab_lds[2 * kRMax + j] = 0;
+        }
+      }
+    } else if (tid < kRMax) {
+      // more rows than lanes: fixed snake over the block index (balanced under a causal mask)
+      const int j = tid;
       int bj = (j & 1) ? (j + 1) * G - 1 - g : j * G + g;
       const bool used = j < R && bj < nblk;
       if (mirror) bj = nblk - 1 - bj;
       int rs = 0, n = 0;
       if (used) {
         rs = row_ptr[head_row0 + bj];
-        // entries beyond the capacity of the index buffer are ignored
         n = head_on ? max(min(row_ptr[head_row0 + bj + 1], cap) - rs, 0) : 0;
       }
       tab_lds[j] = used ? bj : -1;
