@@ -8,7 +8,7 @@
 //   sdd  out block (i, j) = A_i [64 x K] . W[j-block rows, :]^T, K = d
 //        one workgroup owns up to four consecutive entries of token tile i's
 //        list, so the A_i chunk staged in LDS is shared by four neuron blocks;
-//        8 waves: wave w computes half w%2 (32 neurons) of block w/2 for all 64 tokens.
+//        wave w computes block w (64 neurons) for all 64 tokens.
 //   dsd  out tile (i, 256 columns) = sum over listed j of Act_ij [64 x 64] .
 //        W[rows n0.., j-block columns]^T: the K loop walks the active list, one
 //        64-wide K-step per active block; inactive blocks are never touched.
@@ -30,7 +30,9 @@ namespace lx {
 #define LX_AS1 __attribute__((address_space(1)))
 #define LX_AS3 __attribute__((address_space(3)))
 
-constexpr int kThreads = 512;      // 8 wavefronts: two per SIMD, so one hides the other's LDS latency
+constexpr int kFW = 8;             // wavefronts per workgroup
+constexpr int kNI = 8 / kFW;       // 32-row groups of the 256 weight rows per wavefront
+constexpr int kThreads = kFW * kWave;
 constexpr int kBK = 64;            // K-chunk per step: 64 bf16 = 128 bytes per row
 constexpr int kRowsB = 64;         // shared operand (token rows)
 constexpr int kRowsA = 256;        // per-wave operand (4 x 64 weight rows)
@@ -45,30 +47,35 @@ constexpr int kSddStages = 3, kDsdStages = 2;
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
 // One stage = kIssues DMA instructions per wave.  Instruction u of wave w fills stage rows
-// 8g .. 8g+7 with g = w + 8u (u = 0: the 64 shared rows, u >= 1: weight block u-1); lane l brings
-// the 16-byte slot l%8 of row 8g + l/8.  src[u] already points at this lane's (row, swizzled
-// segment); offB / offA are the element offsets of the current K-step for the shared rows and
-// the weight rows.
+// 8g .. 8g+7 with g = w + kFW*u (g < 8: the 64 shared rows, then the weight blocks); lane l
+// brings the 16-byte slot l%8 of row 8g + l/8.  src[u] already points at this lane's (row,
+// swizzled segment); offB / offA are the element offsets of the current K-step for the shared
+// rows and the weight rows.
 __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[kIssues],
                                             long long offB, long long offA) {
   const uint32_t base = lds_addr(stage) + (threadIdx.x / kWave) * 1024;
 #pragma unroll
-  for (int u = 0; u < kIssues; ++u) dma16(src[u] + (u < 1 ? offB : offA), base + u * 8192);
+  for (int u = 0; u < kIssues; ++u)
+    dma16(src[u] + (u < 8 / kFW ? offB : offA), base + u * (kFW * 1024));
 }
 
-// One 64-deep K-step from LDS: wave w multiplies 32 weight rows (half w%2 of block w/2) with the
-// 64 shared rows.  acc[ti]: rows = the 32 weight rows, columns = shared rows 32ti..
-__device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16 (&acc)[2]) {
+// One 64-deep K-step from LDS: wave w multiplies its 32*kNI weight rows (row groups kNI*w ..)
+// with the 64 shared rows.  acc[ni][ti]: rows = weight rows 32*(kNI*w + ni).., columns = shared
+// rows 32ti..
+__device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16 (&acc)[kNI][2]) {
   const int lane = threadIdx.x % kWave;
   const int r = lane % 32, h2 = lane / 32;
-  const int ra = kRowsB + 32 * wave + r;
-  // all 12 operand reads of the step are issued first, so that their LDS latency overlaps
-  // the MFMAs instead of being paid once per k16 slice
-  uint4 a[4], b[4][2];
+  // all operand reads of the step are issued first, so that their LDS latency overlaps the
+  // MFMAs instead of being paid once per k16 slice
+  uint4 a[4][kNI], b[4][2];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     const int seg = 2 * kk + h2;
-    a[kk] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+#pragma unroll
+    for (int ni = 0; ni < kNI; ++ni) {
+      const int ra = kRowsB + 32 * (kNI * wave + ni) + r;
+      a[kk][ni] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int rb = 32 * h + r;
@@ -79,7 +86,9 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti) acc[ti] = mfma32(a[kk], b[kk][ti], acc[ti]);
+    for (int ni = 0; ni < kNI; ++ni)
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32(a[kk][ni], b[kk][ti], acc[ni][ti]);
 }
 
 // Pipeline over nsteps K-steps through a ring of NST stages: while step s is multiplied, the
@@ -92,7 +101,7 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
 template <int NST, class Offs>
 __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
                                          const uint16_t* const (&src)[kIssues], Offs offs,
-                                         uint16_t* ring, f32x16 (&acc)[2]) {
+                                         uint16_t* ring, f32x16 (&acc)[kNI][2]) {
   static_assert(NST >= 2 && NST <= 4 && kIssues * (NST - 2) < 64, "ring depth");
   const int wave = threadIdx.x / kWave;
   long long ob, oa;
@@ -124,9 +133,10 @@ __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
 // every wavefront finds its item from row_ptr with 64-wide scans, so the active workgroups are
 // the FIRST ones of the grid and spread evenly over shader engines and CUs (a 2-D grid with
 // early exits piles them onto a few CUs).  Workgroup w runs on XCD w % 8; it takes item
-// (w % 8) * L + w / 8 with L = ceil(total / 8), so each XCD owns a contiguous range of items,
-// i.e. of token tiles: a tile's activations are fetched into one L2 only, and the weight
-// blocks an XCD needs are those of one eighth of the tiles.  Returns false past the end.
+// of the range (w % 8) * L .. + L - 1 with L = ceil(total / 8), so each XCD owns a contiguous
+// range of items, i.e. of token tiles: a tile's activations are fetched into one L2 only, and
+// the weight blocks an XCD needs are those of one eighth of the tiles.  Returns false past the
+// end.
 __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int w,
                                           int per, int& row, int& chunk) {
   const int lane = threadIdx.x % kWave;
@@ -140,8 +150,13 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
     total += c;
   }
   const int L = (total + 7) / 8;
-  const int slot = w / 8, work = (w % 8) * L + slot;
-  if (slot >= L || work >= total) return false;
+  // Inside an XCD's range consecutive workgroups are an eighth of the range apart, so the
+  // workgroups that run at the same time come from different token tiles and, the lists being
+  // sorted, from the same region of the neuron axis: the weight blocks that several tiles of
+  // the XCD use are then fetched into its L2 once (with all blocks listed: once per eight tiles).
+  const int q = (L + 7) / 8, slot = w / 8;
+  const int pos = (slot % 8) * q + slot / 8, work = (w % 8) * L + pos;
+  if (slot >= 8 * q || pos >= L || work >= total) return false;
   int running = 0;
   for (int base = 0; base < rows; base += kWave) {
     const int r = base + lane;
@@ -166,11 +181,13 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   return false;
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[2]) {
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[kNI][2]) {
 #pragma unroll
-  for (int b = 0; b < 2; ++b)
+  for (int a = 0; a < kNI; ++a)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 }
 
 // MODE 0: out = bf16(max(acc + bias, 0));  MODE 1: out = gate > 0 ? bf16(acc) : 0.
@@ -194,38 +211,40 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   const uint16_t* src[kIssues];
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
-    const int g = wave + 8 * u, row = 8 * g + lane / 8;
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 1) {
+    if (u < 8 / kFW) {
       src[u] = A + ((long long)i * 64 + row) * K + seg * 8;
     } else {
-      const int blk = u - 1, r = row - kRowsB - 64 * blk;
+      const int blk = g / 8 - 1, r = row - kRowsB - 64 * blk;
       // blocks past the end of the list are filled from the first block (never used)
       const int j = col_idx[p0 + (blk < nb ? blk : 0)];
       src[u] = W + ((long long)j * 64 + r) * K + seg * 8;
     }
   }
-  f32x16 acc[2];
+  f32x16 acc[kNI][2];
   zero_acc(acc);
-  run_ring<kSddStages>(K / kBK, wave / 2 < nb, src,
-               [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; }, ring,
-                       acc);
-  if (wave / 2 >= nb) return;
+  const int blk_w = kNI * wave / 2;          // list entry (of the four) this wave works on
+  run_ring<kSddStages>(K / kBK, blk_w < nb, src,
+                       [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; },
+                       ring, acc);
+  if (blk_w >= nb) return;
 
-  const int p = p0 + wave / 2;
+  const int p = p0 + blk_w;
   const int j = col_idx[p];
   const int tl = lane % 32, nq = (lane / 32) * 4;
-  {
-    const int ni = wave % 2;
+#pragma unroll
+  for (int ni = 0; ni < kNI; ++ni) {
+    const int nh = (kNI * wave + ni) % 2;    // which 32 neurons of the block
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int t = 32 * ti + tl, n = 32 * ni + 8 * g + nq;
+        const int t = 32 * ti + tl, n = 32 * nh + 8 * g + nq;
         const long long o = (long long)p * 4096 + t * 64 + n;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[ti][4 * g + e];
+        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
         if (MODE == 0) {
           if (bias) {
             const uint2 bb = *reinterpret_cast<const uint2*>(bias + j * 64 + n);
@@ -259,21 +278,21 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   const int rs = row_ptr[i];
   const int n_i = min(row_ptr[i + 1], nnz_cap) - rs;   // <= 0: nothing listed within the capacity
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  const bool wave_on = n0 + 64 * (wave / 2) < ncols_out;
+  const bool wave_on = n0 + 32 * kNI * wave < ncols_out;
 
   const uint16_t* src[kIssues];
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
-    const int g = wave + 8 * u, row = 8 * g + lane / 8;
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 1) {
+    if (u < 8 / kFW) {
       src[u] = act + row * 64 + seg * 8;          // inside a compact 64x64 activation block
     } else {
       const int n = min(n0 + row - kRowsB, ncols_out - 1);   // rows past the edge: re-read the last
       src[u] = W + (long long)n * ldw + seg * 8;
     }
   }
-  f32x16 acc[2];
+  f32x16 acc[kNI][2];
   zero_acc(acc);
   run_ring<kDsdStages>(n_i, wave_on, src,
                [&](int s, long long& ob, long long& oa) {
@@ -285,16 +304,17 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   if (!wave_on) return;
 
   const int tl = lane % 32, nq = (lane / 32) * 4;
-  {
+#pragma unroll
+  for (int ni = 0; ni < kNI; ++ni) {
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int t = i * 64 + 32 * ti + tl;
-        const int n = n0 + 32 * wave + 8 * g + nq;
+        const int n = n0 + 32 * (kNI * wave + ni) + 8 * g + nq;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[ti][4 * g + e];
+        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
         if (bias) {
           const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
           v[0] += bf2f(bb.x & 0xFFFFu); v[1] += bf2f(bb.x >> 16);
@@ -317,7 +337,9 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st) {
   (void)Fb;
-  const dim3 g1((nnz_cap / 4 + Tt + 7) / 8 * 8);   // >= 8 * ceil(sum_i ceil(n_i / 4) / 8)
+  // items <= nnz_cap / 4 + Tt; per XCD L = ceil(items / 8) of them in 8 * ceil(L / 8) slots
+  const int Lub = (nnz_cap / 4 + Tt + 7) / 8;
+  const dim3 g1(8 * 8 * ((Lub + 7) / 8));
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
