@@ -19,7 +19,9 @@
 // library matmul / softmax attention, exact ReLU-support equivalence, empty
 // mask, brute-force element-wise masks on tiny shapes, finite differences and
 // autograd for the backward passes, closed forms, NaN poisoning of inactive
-// blocks, and popcount / scatter-back for the compaction.
+// blocks, popcount / scatter-back for the compaction, and for the MLP
+// predictor brute force, the max-over-tokens closed form of the reduction and
+// the threshold limits.
 
 #include <cmath>
 #include <cstdint>
@@ -252,6 +254,33 @@ void lxo_attn_bwd(int32_t B, int32_t Hh, int32_t S, int32_t D, double scale,
           }
         }
       }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// MLP predictor, inference side (Sec. V-A, "MLP Block"): approximate block
+// scores S = X Wa with Wa [d, n_blk], binarised with a threshold (a block whose
+// score exceeds it is kept), then reduced over the tokens of a group: a block
+// is active for the group if it is active for any of its tokens (the final
+// pattern must cover every token that needs the block; the paper reduces over
+// batch and sequence, i.e. one group holding all tokens).
+//   S[t,j]    = sum_k X[t,k] Wa[k,j]
+//   M[g,j]    = OR over t in group g of (S[t,j] > thr)
+// X [T,d], Wa [d,nblk] row-major; group_rows divides T.  Outputs: S [T,nblk]
+// fp64 (may be null), M [T/group_rows][nblk] bytes (0/1).
+// ---------------------------------------------------------------------------
+void lxo_mlp_predict(int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
+                     const float* X, const float* Wa, double thr, double* S,
+                     uint8_t* M) {
+  for (int32_t g = 0; g < T / group_rows; ++g)
+    for (int32_t j = 0; j < nblk; ++j) M[(int64_t)g * nblk + j] = 0;
+  for (int32_t t = 0; t < T; ++t)
+    for (int32_t j = 0; j < nblk; ++j) {
+      double s = 0.0;
+      for (int32_t k = 0; k < d; ++k)
+        s += (double)X[(int64_t)t * d + k] * (double)Wa[(int64_t)k * nblk + j];
+      if (S) S[(int64_t)t * nblk + j] = s;
+      if (s > thr) M[(int64_t)(t / group_rows) * nblk + j] = 1;
     }
 }
 

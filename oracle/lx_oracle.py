@@ -147,3 +147,21 @@ def attn_bwd(Q, K, V, dO, mask, scale, causal, head_active=None, blk=64):
                        pdO, C.c_int32(blk), pM, C.c_int32(mb), pHa, pdQ, pdK,
                        pdV)
     return dQ, dK, dV
+
+
+def mlp_predict(X, Wa, thr, group_rows=None):
+    """MLP predictor of Sec. V-A: scores S = X Wa [T, nblk] (float64) and the
+    block mask [T/group_rows, nblk] (uint8) = OR over the tokens of a group of
+    (S > thr).  group_rows=None: one group holding all tokens."""
+    T, d = X.shape
+    nblk = Wa.shape[1]
+    assert Wa.shape == (d, nblk)
+    g = T if group_rows is None else group_rows
+    assert T % g == 0
+    X, pX = _f32(X)
+    Wa, pW = _f32(Wa)
+    S, pS = _f64_out((T, nblk))
+    M = np.empty((T // g, nblk), dtype=np.uint8)
+    lib().lxo_mlp_predict(C.c_int32(T), C.c_int32(d), C.c_int32(nblk), C.c_int32(g), pX, pW,
+                          C.c_double(thr), pS, M.ctypes.data_as(C.POINTER(C.c_uint8)))
+    return S, M
