@@ -51,7 +51,11 @@ typedef enum { LX_F32 = 0, LX_BF16 = 1 } lx_dtype;
  * Row-compressed active-block list: the "list of data block indices" of
  * Sec. VI-A and the "indices of activated neuron blocks" of Sec. VI-B.
  * Row r owns col_idx[row_ptr[r] .. row_ptr[r+1]), ascending, no duplicates.
- *   FFN:        rows = T / tile_t (token tiles),      cols = F / blk_n (neuron blocks)
+ *   FFN:        rows = T / tile_t (token tiles),      cols = F / blk_n (neuron blocks);
+ *               rows may also be any divisor of T / tile_t: row r is then the
+ *               list of the (T/tile_t)/rows consecutive token tiles of group r.
+ *               rows = 1 is the paper's own case, one list reduced over batch
+ *               and sequence (Sec. V-A) and shared by all tokens.
  *   attention:  rows = mask_batch * Hh * (S/64),      cols = S / 64
  *               (query-block rows for the row list; key-block rows for the
  *               column list used by the backward pass)
@@ -80,7 +84,8 @@ typedef enum {
   LX_K_ATTN_FWD = 5,     /* fused SDD + softmax + DSD */
   LX_K_ATTN_BWD_DQ = 6,  /* Delta and dQ, query side */
   LX_K_ATTN_BWD_DKV = 7, /* dK and dV, key side */
-  LX_K_TRANSPOSE = 8     /* weight repack */
+  LX_K_TRANSPOSE = 8,    /* weight repack */
+  LX_K_PREDICT = 9       /* MLP predictor scores + threshold + OR over a token tile */
 } lx_kernel;
 
 /* Human-readable name of a status code (HOST string, static storage). */
@@ -142,6 +147,9 @@ lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_u
                               const void* W_down, void* W_up_t, void* W_down_t, void* stream);
 
 /* Workspace (bytes) for lx_sparse_ffn_fwd / lx_sparse_ffn_bwd_dx.
+ * nnz_cap: capacity of the activation buffers in blocks, i.e. bl->nnz_cap times
+ *   the number of token tiles per list row ((T/tile_t)/bl->rows, 1 for a list
+ *   row per tile).
  * have_h_act: the caller passes an H_act buffer to the forward call.
  * have_packed: the caller passes W_up_t and W_down_t to the backward call. */
 size_t lx_sparse_ffn_fwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t F,
@@ -159,8 +167,12 @@ size_t lx_sparse_ffn_bwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int3
  *   X      [T,d]   W_up [F,d]   W_down [d,F]   b_up [F] / b_down [d] nullable
  *   bl     rows = T/tile_t, cols = F/blk_n
  *   Y      out [T,d]
- *   H_act  out, compact activations [nnz_cap][tile_t][blk_n] in list order,
- *          needed by the backward call; NULL keeps them in the workspace only.
+ *   H_act  out, compact activations, needed by the backward call; NULL keeps
+ *          them in the workspace only.  With gt = (T/tile_t)/bl->rows token
+ *          tiles per list row, the block of (tile i, entry k of its row r =
+ *          i/gt) is block number row_ptr[r]*gt + k*gt + i%gt of tile_t x blk_n
+ *          elements; the buffer holds nnz_cap*gt blocks (gt = 1: [nnz_cap]
+ *          blocks in list order).
  * Supported: LX_F32 with (tile_t, blk_n) in {(32,32),(64,64)}, d % 32 == 0;
  *            LX_BF16 with (64,64), d % 64 == 0.
  */
@@ -183,6 +195,29 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
                                const void* W_up, const void* W_down, const void* W_up_t,
                                const void* W_down_t, const lx_blocklist* bl, void* dX,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * MLP predictor, inference side (Sec. V-A, "MLP Block"): block scores
+ * S = X Wa [T, nblk], binarised with a threshold and reduced over the tokens of
+ * a group: mask[g][n] = 1 if S[t][n] > thr for any token t of group g, else 0.
+ * group_rows = T gives the paper's single mask reduced over batch and sequence;
+ * group_rows = 64 one mask row per token tile.  The mask is what
+ * lx_mask_compact takes (rows = T/group_rows, cols = nblk).
+ *   X      [T,d]
+ *   Wa_t   [nblk,d]: the predictor matrix of the paper ([d, nblk]) transposed,
+ *          so that it is read along its contiguous dimension like the weights
+ *   mask   out, uint8 [T/group_rows][nblk]
+ *   workspace  >= lx_mlp_predict_workspace_bytes (per-tile masks before the
+ *          reduction; none needed for group_rows = 64)
+ * The comparison is made on fp32 sums of bf16 products; a score within rounding
+ * distance of thr may fall on either side.
+ * Supported: LX_BF16, d % 64 == 0, nblk % 64 == 0, T % 64 == 0, group_rows a
+ * multiple of 64 that divides T.
+ */
+size_t lx_mlp_predict_workspace_bytes(int32_t T, int32_t nblk, int32_t group_rows);
+lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
+                              const void* X, const void* Wa_t, float thr, uint8_t* mask,
+                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* Workspace (bytes) for lx_sparse_attn_bwd_dx (the forward call needs none). */
 size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, int32_t S,

@@ -129,7 +129,8 @@ __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
 }
 
 // Work items of the sdd kernel are (token tile, group of `per` consecutive list entries),
-// numbered in list order.  The launch grid is the host-known upper bound on their number and
+// numbered in list order; `rows` counts token tiles, and gt consecutive tiles share one row of
+// the list (gt = 1: a list row per tile).  The launch grid is the host-known upper bound on their number and
 // every wavefront finds its item from row_ptr with 64-wide scans, so the active workgroups are
 // the FIRST ones of the grid and spread evenly over shader engines and CUs (a 2-D grid with
 // early exits piles them onto a few CUs).  Workgroup w runs on XCD w % 8; it takes item
@@ -137,14 +138,14 @@ __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
 // range of items, i.e. of token tiles: a tile's activations are fetched into one L2 only, and
 // the weight blocks an XCD needs are those of one eighth of the tiles.  Returns false past the
 // end.
-__device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int w,
+__device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int gt, int w,
                                           int per, int& row, int& chunk) {
   const int lane = threadIdx.x % kWave;
   int total = 0;
   for (int base = 0; base < rows; base += kWave) {
     const int r = base + lane;
     int c = 0;
-    if (r < rows) c = (row_ptr[r + 1] - row_ptr[r] + per - 1) / per;
+    if (r < rows) c = (row_ptr[r / gt + 1] - row_ptr[r / gt] + per - 1) / per;
 #pragma unroll
     for (int dlt = 32; dlt > 0; dlt >>= 1) c += __shfl_xor(c, dlt);
     total += c;
@@ -161,7 +162,7 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   for (int base = 0; base < rows; base += kWave) {
     const int r = base + lane;
     int c = 0;
-    if (r < rows) c = (row_ptr[r + 1] - row_ptr[r] + per - 1) / per;
+    if (r < rows) c = (row_ptr[r / gt + 1] - row_ptr[r / gt] + per - 1) / per;
     int incl = c;
 #pragma unroll
     for (int dlt = 1; dlt < kWave; dlt <<= 1) {
@@ -195,12 +196,12 @@ template <int MODE>
 __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, int rows, int K, int nnz_cap,
+    const int* __restrict__ col_idx, int rows, int gt, int K, int nnz_cap,
     uint16_t* __restrict__ out_act, const uint16_t* __restrict__ gate_act) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
   int i, chunk;
-  if (!find_work(row_ptr, rows, blockIdx.x, 4, i, chunk)) return;
-  const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
+  if (!find_work(row_ptr, rows, gt, blockIdx.x, 4, i, chunk)) return;
+  const int rs = row_ptr[i / gt], n_i = row_ptr[i / gt + 1] - rs;
   const int first = chunk * 4;
   const int p0 = rs + first;
   if (p0 >= nnz_cap) return;       // entries beyond the capacity of the list buffers are ignored
@@ -230,8 +231,10 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
                        ring, acc);
   if (blk_w >= nb) return;
 
-  const int p = p0 + blk_w;
-  const int j = col_idx[p];
+  const int j = col_idx[p0 + blk_w];
+  // compact activation block of (tile i, list entry): the entries of a list row are stored as
+  // [entry][tile within the row's group of gt tiles]
+  const long long p = (long long)rs * gt + (long long)(first + blk_w) * gt + i % gt;
   const int tl = lane % 32, nq = (lane / 32) * 4;
 #pragma unroll
   for (int ni = 0; ni < kNI; ++ni) {
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int t = 32 * ti + tl, n = 32 * nh + 8 * g + nq;
-        const long long o = (long long)p * 4096 + t * 64 + n;
+        const long long o = p * 4096 + t * 64 + n;
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
@@ -272,11 +275,12 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
 __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, int ncols_out, int nnz_cap, uint16_t* __restrict__ out) {
+    const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
+    uint16_t* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kDsdStages * kStageElems];
   const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
-  const int rs = row_ptr[i];
-  const int n_i = min(row_ptr[i + 1], nnz_cap) - rs;   // <= 0: nothing listed within the capacity
+  const int rs = row_ptr[i / gt];
+  const int n_i = min(row_ptr[i / gt + 1], nnz_cap) - rs;   // <= 0: nothing within the capacity
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const bool wave_on = n0 + 32 * kNI * wave < ncols_out;
 
@@ -296,9 +300,8 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   zero_acc(acc);
   run_ring<kDsdStages>(n_i, wave_on, src,
                [&](int s, long long& ob, long long& oa) {
-                 const int p = rs + s;
-                 ob = (long long)p * 4096;
-                 oa = (long long)col_idx[p] * 64;
+                 ob = ((long long)(rs + s) * gt + i % gt) * 4096;
+                 oa = (long long)col_idx[rs + s] * 64;
                },
                        ring, acc);
   if (!wave_on) return;
@@ -328,32 +331,109 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   }
 }
 
+// MLP predictor (Sec. V-A): scores S = X Wa for one 64-token tile and up to 256 neuron blocks
+// (rows of Wa_t [nblk, K], 64 per "weight block" of the pipeline), thresholded and OR-reduced
+// over the tile's tokens: tile_mask[i][n] = any token t of tile i has S[t][n] > thr.  Same
+// pipeline and MFMA core as the sdd kernel; only the epilogue differs.
+__global__ __launch_bounds__(kThreads) void predict_bf16(
+    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wa_t, int K, int nblk, float thr,
+    uint8_t* __restrict__ tile_mask) {
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
+  const int i = blockIdx.y, chunk = blockIdx.x;
+  const int nb = min(4, nblk / 64 - chunk * 4);      // 64-row groups of Wa_t in this workgroup
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const uint16_t* src[kIssues];
+#pragma unroll
+  for (int u = 0; u < kIssues; ++u) {
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 8 / kFW) {
+      src[u] = X + ((long long)i * 64 + row) * K + seg * 8;
+    } else {
+      const int blk = g / 8 - 1, r = row - kRowsB - 64 * blk;
+      const int j = chunk * 4 + (blk < nb ? blk : 0);   // groups past the end: re-read the first
+      src[u] = Wa_t + ((long long)j * 64 + r) * K + seg * 8;
+    }
+  }
+  f32x16 acc[kNI][2];
+  zero_acc(acc);
+  const int blk_w = kNI * wave / 2;
+  run_ring<kSddStages>(K / kBK, blk_w < nb, src,
+                       [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; },
+                       ring, acc);
+  if (blk_w >= nb) return;
+  uint8_t* out = tile_mask + (long long)i * nblk + (chunk * 4 + blk_w) * 64;
+#pragma unroll
+  for (int ni = 0; ni < kNI; ++ni) {
+    const int nh = (kNI * wave + ni) % 2;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      // register v of a lane: block 32*nh + 8*(v/4) + 4*(lane/32) + v%4, tokens lane%32 and +32
+      const unsigned long long hit = __ballot(acc[ni][0][v] > thr || acc[ni][1][v] > thr);
+      const int n = 32 * nh + 8 * (v / 4) + v % 4;
+      if (lane == 0) out[n] = (uint32_t)hit != 0u;
+      if (lane == 32) out[n + 4] = (hit >> 32) != 0ull;
+    }
+  }
+}
+
+// group_mask[g][n] = OR over the tiles_per_group tile masks of group g
+__global__ void or_rows_kernel(const uint8_t* __restrict__ tile_mask, int tiles_per_group, int nblk,
+                               int total, uint8_t* __restrict__ group_mask) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int g = idx / nblk, n = idx - g * nblk;
+  uint8_t any = 0;
+  for (int t = 0; t < tiles_per_group; ++t) any |= tile_mask[((long long)g * tiles_per_group + t) * nblk + n];
+  group_mask[idx] = any != 0;
+}
+
+// tile_mask: [T/64][nblk] bytes (the result itself when tiles_per_group == 1)
+hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
+                               const uint16_t* Wa_t, float thr, uint8_t* tile_mask,
+                               uint8_t* group_mask, hipStream_t st) {
+  const int Tt = T / 64;
+  {
+    ProfScope ps(kKPredict, st);
+    hipLaunchKernelGGL(predict_bf16, dim3((nblk / 64 + 3) / 4, Tt), dim3(kThreads), 0, st, X, Wa_t,
+                       d, nblk, thr, tile_mask);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || tiles_per_group == 1) return e;
+  const int total = Tt / tiles_per_group * nblk;
+  hipLaunchKernelGGL(or_rows_kernel, dim3((total + 255) / 256), dim3(256), 0, st,
+                     (const uint8_t*)tile_mask, tiles_per_group, nblk, total, group_mask);
+  return hipGetLastError();
+}
+
 // pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
 // pass 1 (backward): A = dY, W1 = W_down_t [F,d], W2 = W_up_t [d,F], act_out = dZ_act,
 //                    act_gate = H_act, out = dX
-hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_t* A,
+hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st) {
   (void)Fb;
   // items <= nnz_cap / 4 + Tt; per XCD L = ceil(items / 8) of them in 8 * ceil(L / 8) slots
-  const int Lub = (nnz_cap / 4 + Tt + 7) / 8;
+  const long long items = ((long long)nnz_cap * gt + 3) / 4 + Tt;
+  if (items > (1ll << 30)) return hipErrorInvalidValue;
+  const int Lub = (int)((items + 7) / 8);
   const dim3 g1(8 * 8 * ((Lub + 7) / 8));
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
       hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, Tt,
-                         d, nnz_cap, act_out, (const uint16_t*)nullptr);
+                         gt, d, nnz_cap, act_out, (const uint16_t*)nullptr);
     else
       hipLaunchKernelGGL(ffn_sdd_bf16<1>, g1, dim3(kThreads), 0, st, A, W1,
-                         (const uint16_t*)nullptr, row_ptr, col_idx, Tt, d, nnz_cap, act_out, act_gate);
+                         (const uint16_t*)nullptr, row_ptr, col_idx, Tt, gt, d, nnz_cap, act_out, act_gate);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   hipLaunchKernelGGL(ffn_dsd_bf16, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
-                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, nnz_cap, out);
+                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap, out);
   return hipGetLastError();
 }
 

@@ -54,16 +54,19 @@ __device__ __forceinline__ void gemm_nt_f32(const float* __restrict__ A, long lo
 template <int TT, int BN, int MODE>
 __global__ __launch_bounds__(kF32Threads) void ffn_sdd_f32(
     const float* __restrict__ A, const float* __restrict__ W, const float* __restrict__ bias,
-    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, int K, int nnz_cap,
+    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, int gt, int K, int nnz_cap,
     float* __restrict__ out_act, const float* __restrict__ gate_act) {
   __shared__ float As[TT * (kF32BK + 1)];
   __shared__ float Bs[BN * (kF32BK + 1)];
   const int i = blockIdx.y;
-  const int rs = row_ptr[i], n_i = row_ptr[i + 1] - rs;
+  // gt consecutive token tiles share row i / gt of the list; the activation blocks of a list
+  // row are stored as [entry][tile within the group]
+  const int rs = row_ptr[i / gt], n_i = row_ptr[i / gt + 1] - rs;
   if ((int)blockIdx.x >= n_i) return;
-  const int p = rs + blockIdx.x;
-  if (p >= nnz_cap) return;        // entries beyond the capacity of the list buffers are ignored
-  const int j = col_idx[p];
+  const int lp = rs + blockIdx.x;
+  if (lp >= nnz_cap) return;       // entries beyond the capacity of the list buffers are ignored
+  const int j = col_idx[lp];
+  const long long p = (long long)lp * gt + i % gt;
   float acc[TT / 16][BN / 16] = {};
   gemm_nt_f32<TT, BN>(A + (long long)i * TT * K, K, W + (long long)j * BN * K, K, K, acc, As, Bs);
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
@@ -89,17 +92,18 @@ template <int TT, int BN>
 __global__ __launch_bounds__(kF32Threads) void ffn_dsd_f32(
     const float* __restrict__ act, const float* __restrict__ W, long long ldw,
     const float* __restrict__ bias, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, int ncols_out, int nnz_cap, float* __restrict__ out) {
+    const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
+    float* __restrict__ out) {
   constexpr int CT = 32;
   __shared__ float As[TT * (kF32BK + 1)];
   __shared__ float Bs[CT * (kF32BK + 1)];
   const int i = blockIdx.y, n0 = blockIdx.x * CT;
-  const int rs = row_ptr[i], n_i = min(row_ptr[i + 1], nnz_cap) - rs;
+  const int rs = row_ptr[i / gt], n_i = min(row_ptr[i / gt + 1], nnz_cap) - rs;
   float acc[TT / 16][CT / 16] = {};
   for (int s = 0; s < n_i; ++s) {
     const int p = rs + s;
     const int j = col_idx[p];
-    gemm_nt_f32<TT, CT>(act + (long long)p * TT * BN, BN, W + (long long)n0 * ldw + (long long)j * BN,
+    gemm_nt_f32<TT, CT>(act + ((long long)p * gt + i % gt) * TT * BN, BN, W + (long long)n0 * ldw + (long long)j * BN,
                         ldw, BN, acc, As, Bs);
   }
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
@@ -113,7 +117,7 @@ __global__ __launch_bounds__(kF32Threads) void ffn_dsd_f32(
 }
 
 template <int TT, int BN>
-static hipError_t launch_f32(int pass, int Tt, int Fb, int d, int F, const float* A, const float* W1,
+static hipError_t launch_f32(int pass, int Tt, int gt, int Fb, int d, int F, const float* A, const float* W1,
                              const float* b1, const float* W2, const float* b2, const int* row_ptr,
                              const int* col_idx, int nnz_cap, float* act_out,
                              const float* act_gate, float* out, hipStream_t st) {
@@ -122,30 +126,30 @@ static hipError_t launch_f32(int pass, int Tt, int Fb, int d, int F, const float
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
       hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 0>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1,
-                         b1, row_ptr, col_idx, d, nnz_cap, act_out, (const float*)nullptr);
+                         b1, row_ptr, col_idx, gt, d, nnz_cap, act_out, (const float*)nullptr);
     else
       hipLaunchKernelGGL((ffn_sdd_f32<TT, BN, 1>), dim3(Fb, Tt), dim3(kF32Threads), 0, st, A, W1,
-                         (const float*)nullptr, row_ptr, col_idx, d, nnz_cap, act_out, act_gate);
+                         (const float*)nullptr, row_ptr, col_idx, gt, d, nnz_cap, act_out, act_gate);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   hipLaunchKernelGGL((ffn_dsd_f32<TT, BN>), dim3(d / 32, Tt), dim3(kF32Threads), 0, st,
-                     (const float*)act_out, W2, (long long)F, b2, row_ptr, col_idx, d, nnz_cap, out);
+                     (const float*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap, out);
   return hipGetLastError();
 }
 
 // pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
 // pass 1 (backward): A = dY, W1 = W_down_t [F,d], W2 = W_up_t [d,F], act_out = dZ_act,
 //                    act_gate = H_act, out = dX
-hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, const float* A,
+hipError_t launch_ffn_f32(int pass, int tile, int Tt, int gt, int Fb, int d, int F, const float* A,
                           const float* W1, const float* b1, const float* W2, const float* b2,
                           const int* row_ptr, const int* col_idx, int nnz_cap, float* act_out,
                           const float* act_gate, float* out, hipStream_t st) {
   if (tile == 32)
-    return launch_f32<32, 32>(pass, Tt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap,
+    return launch_f32<32, 32>(pass, Tt, gt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap,
                               act_out, act_gate, out, st);
-  return launch_f32<64, 64>(pass, Tt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap,
+  return launch_f32<64, 64>(pass, Tt, gt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap,
                             act_out, act_gate, out, st);
 }
 

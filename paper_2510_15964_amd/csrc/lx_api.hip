@@ -52,7 +52,8 @@ static lx_status check_ffn(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t
   }
   if (T % tile_t != 0 || F % blk_n != 0) return LX_ERR_UNSUPPORTED;
   if (!bl || !bl->row_ptr || !bl->col_idx) return LX_ERR_INVALID_ARG;
-  if (bl->rows != T / tile_t || bl->cols != F / blk_n) return LX_ERR_INVALID_ARG;
+  if (bl->rows <= 0 || (T / tile_t) % bl->rows != 0 || bl->cols != F / blk_n)
+    return LX_ERR_INVALID_ARG;
   if (bl->nnz_cap < 0 || (int64_t)bl->nnz_cap > (int64_t)bl->rows * bl->cols) return LX_ERR_INVALID_ARG;
   return LX_OK;
 }
@@ -205,19 +206,21 @@ lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_
   if (!aligned16(X) || !aligned16(W_up) || !aligned16(W_down) || !aligned16(Y) ||
       !aligned16(H_act) || !aligned16(workspace) || !aligned16(b_up) || !aligned16(b_down))
     return LX_ERR_INVALID_ARG;
+  const int gt = (T / tile_t) / bl->rows;     // token tiles per list row
+  if ((int64_t)bl->nnz_cap * gt > (int64_t)1 << 30) return LX_ERR_INVALID_ARG;
   void* act = H_act;
   if (!act) {
-    const size_t need = lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, bl->nnz_cap, 0);
+    const size_t need = lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, bl->nnz_cap * gt, 0);
     if (!workspace || workspace_bytes < need) return LX_ERR_WORKSPACE;
     act = workspace;
   }
   hipError_t e;
   if (dt == LX_F32)
-    e = launch_ffn_f32(0, tile_t, bl->rows, bl->cols, d, F, (const float*)X, (const float*)W_up,
+    e = launch_ffn_f32(0, tile_t, T / tile_t, gt, bl->cols, d, F, (const float*)X, (const float*)W_up,
                        (const float*)b_up, (const float*)W_down, (const float*)b_down, bl->row_ptr,
                        bl->col_idx, bl->nnz_cap, (float*)act, nullptr, (float*)Y, (hipStream_t)stream);
   else
-    e = launch_ffn_bf16(0, bl->rows, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
+    e = launch_ffn_bf16(0, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
                         (const uint16_t*)b_up, (const uint16_t*)W_down, (const uint16_t*)b_down,
                         bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)act, nullptr, (uint16_t*)Y,
                         (hipStream_t)stream);
@@ -238,12 +241,14 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
   if (!aligned16(dY) || !aligned16(H_act) || !aligned16(dX) || !aligned16(W_up) ||
       !aligned16(W_down) || !aligned16(W_up_t) || !aligned16(W_down_t) || !aligned16(workspace))
     return LX_ERR_INVALID_ARG;
-  const size_t need =
-      lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, bl->nnz_cap, packed ? 1 : 0);
+  const int gt = (T / tile_t) / bl->rows;     // token tiles per list row
+  if ((int64_t)bl->nnz_cap * gt > (int64_t)1 << 30) return LX_ERR_INVALID_ARG;
+  const size_t need = lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n,
+                                                        bl->nnz_cap * gt, packed ? 1 : 0);
   if (!workspace || workspace_bytes < need) return LX_ERR_WORKSPACE;
   char* ws = (char*)workspace;
   void* dz = ws;
-  ws += act_bytes(dt, tile_t, blk_n, bl->nnz_cap);
+  ws += act_bytes(dt, tile_t, blk_n, bl->nnz_cap * gt);
   hipStream_t st = (hipStream_t)stream;
   if (!packed) {
     void* wut = ws;
@@ -256,15 +261,44 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
   }
   hipError_t e;
   if (dt == LX_F32)
-    e = launch_ffn_f32(1, tile_t, bl->rows, bl->cols, d, F, (const float*)dY,
+    e = launch_ffn_f32(1, tile_t, T / tile_t, gt, bl->cols, d, F, (const float*)dY,
                        (const float*)W_down_t, nullptr, (const float*)W_up_t, nullptr, bl->row_ptr,
                        bl->col_idx, bl->nnz_cap, (float*)dz, (const float*)H_act, (float*)dX, st);
   else
-    e = launch_ffn_bf16(1, bl->rows, bl->cols, d, F, (const uint16_t*)dY,
+    e = launch_ffn_bf16(1, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)dY,
                         (const uint16_t*)W_down_t, nullptr, (const uint16_t*)W_up_t, nullptr,
                         bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)dz, (const uint16_t*)H_act,
                         (uint16_t*)dX, st);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+size_t lx_mlp_predict_workspace_bytes(int32_t T, int32_t nblk, int32_t group_rows) {
+  if (T <= 0 || nblk <= 0 || group_rows <= 64) return 0;
+  return round256((size_t)(T / 64) * nblk);
+}
+
+lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
+                              const void* X, const void* Wa_t, float thr, uint8_t* mask,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (T <= 0 || d <= 0 || nblk <= 0 || group_rows <= 0) return LX_ERR_INVALID_ARG;
+  if (T % 64 != 0 || d % 64 != 0 || nblk % 64 != 0) return LX_ERR_UNSUPPORTED;
+  if (group_rows % 64 != 0 || T % group_rows != 0) return LX_ERR_INVALID_ARG;
+  if (!X || !Wa_t || !mask || !aligned16(X) || !aligned16(Wa_t)) return LX_ERR_INVALID_ARG;
+  if (thr != thr) return LX_ERR_INVALID_ARG;   // NaN
+  if (2ll * nblk * d >= (1ll << 31) || (int64_t)(T / 64) * nblk >= (1ll << 31))
+    return LX_ERR_INVALID_ARG;
+  const int tpg = group_rows / 64;
+  uint8_t* tile_mask = mask;
+  if (tpg > 1) {
+    if (!workspace || workspace_bytes < lx_mlp_predict_workspace_bytes(T, nblk, group_rows))
+      return LX_ERR_WORKSPACE;
+    tile_mask = (uint8_t*)workspace;
+  }
+  return launch_predict_bf16(T, d, nblk, tpg, (const uint16_t*)X, (const uint16_t*)Wa_t, thr,
+                             tile_mask, mask, (hipStream_t)stream) == hipSuccess
+             ? LX_OK
+             : LX_ERR_RUNTIME;
 }
 
 size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, int32_t S,

@@ -8,7 +8,7 @@ namespace lx {
 // Kernel ids of the profiling aid (values are part of the C ABI: lx_kernel in lx.h).
 enum KernelId {
   kKCompact = 0, kKFfnUp = 1, kKFfnDown = 2, kKFfnDh = 3, kKFfnDx = 4,
-  kKAttnFwd = 5, kKAttnDq = 6, kKAttnDkv = 7, kKTranspose = 8, kKCount = 9
+  kKAttnFwd = 5, kKAttnDq = 6, kKAttnDkv = 7, kKTranspose = 8, kKPredict = 9, kKCount = 10
 };
 void prof_pre(int id, hipStream_t st);
 void prof_post(int id, hipStream_t st);
@@ -50,15 +50,18 @@ struct CompactJob {
 hipError_t launch_compact_jobs(const CompactJob* jobs, int n, hipStream_t stream);
 hipError_t launch_compact_pair(const uint8_t*, int, int, int, long long, long long, long long, int*,
                                int*, int*, int*, int, hipStream_t);
-hipError_t launch_ffn_f32(int pass, int tile, int Tt, int Fb, int d, int F, const float* A,
+hipError_t launch_ffn_f32(int pass, int tile, int Tt, int gt, int Fb, int d, int F, const float* A,
                           const float* W1, const float* b1, const float* W2, const float* b2,
                           const int* row_ptr, const int* col_idx, int nnz_cap, float* act_out,
                           const float* act_gate, float* out, hipStream_t st);
-hipError_t launch_ffn_bf16(int pass, int Tt, int Fb, int d, int F, const uint16_t* A,
+hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st);
+hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
+                               const uint16_t* Wa_t, float thr, uint8_t* tile_mask,
+                               uint8_t* group_mask, hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);
 hipError_t launch_attn_fwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);

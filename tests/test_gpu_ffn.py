@@ -238,3 +238,76 @@ def test_list_longer_than_its_capacity_is_truncated(lx, dtype, tile):
     for x, y in zip(a, b):
         assert np.isfinite(x).all()
         assert np.array_equal(x, y)
+
+
+def _grouped_compact(dense, rows_mask, gt, tt, bn):
+    """Dense [T,F] -> compact blocks in the order of a list whose row r covers the gt token
+    tiles of group r: [row r][entry k][tile within the group]."""
+    G, Fb = rows_mask.shape
+    v = dense.reshape(G, gt, tt, Fb, bn)
+    out = []
+    for r in range(G):
+        for j in np.nonzero(rows_mask[r])[0]:
+            for g in range(gt):
+                out.append(v[r, g, :, j, :])
+    return np.stack(out) if out else np.zeros((0, tt, bn), dtype=dense.dtype)
+
+
+@pytest.mark.parametrize("dtype,tile,T,d,F,G,density,seed", [
+    ("bf16", 64, 512, 256, 1024, 1, 0.3, 81),     # one list for all tokens (the paper's case)
+    ("bf16", 64, 512, 192, 704, 2, 0.4, 82),      # two groups of four tiles
+    ("bf16", 64, 256, 128, 512, 1, 1.0, 83),      # shared and dense
+    ("bf16", 64, 256, 128, 256, 1, 0.0, 84),      # shared and empty
+    ("f32", 32, 256, 96, 384, 1, 0.3, 85),
+    ("f32", 64, 256, 128, 512, 2, 0.5, 86),
+])
+def test_list_rows_shared_by_groups_of_token_tiles(lx, oracle, dtype, tile, T, d, F, G, density,
+                                                   seed):
+    """A list with fewer rows than token tiles: row r is the list of the tiles of group r.  The
+    oracle sees the same thing as a dense mask with repeated rows."""
+    import torch
+    c = inputs.ffn_bernoulli(T, d, F, tile, tile, density, seed, dtype=dtype, w_std=0.05)
+    Tt, Fb = T // tile, F // tile
+    gt = Tt // G
+    rows_mask = np.ascontiguousarray(c["mask"][:G])             # G independent rows
+    full = np.repeat(rows_mask, gt, axis=0)
+    H, Y = oracle.ffn_fwd(c["X"], c["W_up"], c["W_down"], full, tile, tile)
+    Hq = round_to(H, dtype)
+    _, dX = oracle.ffn_bwd_dx(c["dY"], c["W_up"], c["W_down"], full, Hq > 0, tile, tile)
+
+    X, Wu, Wd, dY = (dev(c[k], dtype) for k in ("X", "W_up", "W_down", "dY"))
+    bl = lx.lx_mask_compact(torch.from_numpy(rows_mask).cuda())
+    assert bl.rows == G
+    nblocks = bl.nnz_cap * gt
+    Hd = torch.full((nblocks * tile * tile + 4096,), float("nan"), dtype=X.dtype, device="cuda")
+    Yd = torch.full_like(X, float("nan"))
+    lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, tile, tile, Yd, Hd)
+    assert torch.isnan(Hd[nblocks * tile * tile:]).all(), "wrote past the H_act buffer"
+    nnz = int(rows_mask.sum()) * gt
+    got_H = host(Hd[:nnz * tile * tile]).reshape(nnz, tile, tile)
+    ref_H = _grouped_compact(H, rows_mask, gt, tile, tile)
+    H_in = torch.zeros_like(Hd)
+    H_in[:nnz * tile * tile] = dev(_grouped_compact(Hq, rows_mask, gt, tile, tile).reshape(-1), dtype)
+    dtc = lx.LX_F32 if dtype == "f32" else lx.LX_BF16
+    ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(dtc, T, d, F, tile, tile, nblocks, 0) + 256,
+                     dtype=torch.uint8, device="cuda")
+    dXd = torch.full_like(X, float("nan"))
+    lx.lx_sparse_ffn_bwd_dx(dY, H_in, Wu, Wd, bl, tile, tile, dXd, ws)
+    torch.cuda.synchronize()
+    pairs = dict(Y=(host(Yd), Y), dX=(host(dXd), dX))
+    if nnz:
+        pairs["H"] = (got_H, ref_H)
+    for k, (g, r) in pairs.items():
+        assert np.isfinite(g).all(), k
+        if not r.any():
+            assert not g.any(), k
+            continue
+        assert rel_err_max(g, r) <= TOL[dtype], (k, rel_err_max(g, r))
+        assert rel_err_fro(g, r) <= FRO[dtype], (k, rel_err_fro(g, r))
+    # the same problem with one list row per tile gives the same bits
+    bl_full = lx.lx_mask_compact(torch.from_numpy(np.ascontiguousarray(full)).cuda())
+    Y2 = torch.full_like(X, float("nan"))
+    H2 = torch.empty(max(bl_full.nnz_cap, 1) * tile * tile, dtype=X.dtype, device="cuda")
+    lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl_full, tile, tile, Y2, H2)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Y2), host(Yd))

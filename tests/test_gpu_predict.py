@@ -1,0 +1,91 @@
+"""GPU parity: MLP predictor (Sec. V-A) -- block scores, threshold, OR over token groups --
+against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2510_15964_amd import inputs
+from util import dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lx():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2510_15964_amd import lx
+    return lx
+
+
+def _case(T, d, nblk, seed):
+    rng = np.random.default_rng(seed)
+    X = inputs.bf16_round(rng.standard_normal((T, d)).astype(np.float32))
+    Wa_t = inputs.bf16_round((rng.standard_normal((nblk, d)) / np.sqrt(d)).astype(np.float32))
+    return X, Wa_t
+
+
+def _check(lx, oracle, X, Wa_t, thr, group):
+    """The decision is made on fp32 sums of bf16 products on the GPU and in fp64 in the oracle:
+    both must agree wherever the oracle's scores of a (group, block) are not within rounding
+    distance of the threshold; inside that band either value is valid."""
+    import torch
+    T, d = X.shape
+    nblk = Wa_t.shape[0]
+    S, M = oracle.mlp_predict(X, np.ascontiguousarray(Wa_t.T), thr, group_rows=group)
+    got = host(lx.lx_mlp_predict_mask(dev(X, "bf16"), dev(Wa_t, "bf16"), float(thr), group))
+    assert got.shape == M.shape and set(np.unique(got)) <= {0, 1}
+    # fp32 accumulation of d products of magnitude |x||w|: a few ulp of the running sum
+    band = 4 * np.finfo(np.float32).eps * np.sqrt(d) * (np.abs(X).astype(np.float64) @ np.abs(Wa_t.T).astype(np.float64)).max()
+    G = T // group
+    Sg = S.reshape(G, group, nblk)
+    near = (np.abs(Sg - thr) <= band).any(axis=1)            # some token of the group is ambiguous
+    clear = ~near | (Sg > thr + band).any(axis=1)            # ...unless another token decides it anyway
+    assert np.array_equal(got[clear], M[clear])
+    assert clear.mean() > 0.99
+    return got, M
+
+
+@pytest.mark.parametrize("T,d,nblk,group,thr,seed", [
+    (256, 128, 64, 64, 2.5, 1),          # one mask row per token tile
+    (512, 256, 128, 512, 3.1, 2),        # one row for all tokens (the paper's reduction)
+    (512, 192, 320, 128, 2.5, 3),        # nblk = 5 groups of 64: a ragged last chunk of the pipeline
+    (64, 64, 64, 64, 2.2, 4),            # smallest shape
+])
+def test_predict_matches_oracle(lx, oracle, T, d, nblk, group, thr, seed):
+    X, Wa_t = _case(T, d, nblk, seed)
+    got, M = _check(lx, oracle, X, Wa_t, thr, group)
+    assert 0.02 < M.mean() < 0.98                             # the case is not degenerate
+
+
+def test_threshold_limits(lx, oracle):
+    import torch
+    X, Wa_t = _case(256, 128, 128, 5)
+    lo = host(lx.lx_mlp_predict_mask(dev(X, "bf16"), dev(Wa_t, "bf16"), -1e30, 256))
+    hi = host(lx.lx_mlp_predict_mask(dev(X, "bf16"), dev(Wa_t, "bf16"), 1e30, 256))
+    assert lo.all() and not hi.any()
+
+
+def test_predicted_mask_feeds_the_sparse_ffn(lx, oracle):
+    """Predictor -> compaction -> sparse FFN with one list shared by all tokens: the chain the
+    paper runs per layer; checked against the oracle run on the oracle's own mask."""
+    import torch
+    from util import FRO, TOL, rel_err_fro, rel_err_max
+    T, d, F = 512, 256, 4096
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, 0.5, 91, dtype="bf16", w_std=0.05)
+    nblk = F // 64
+    rng = np.random.default_rng(92)
+    Wa_t = inputs.bf16_round((rng.standard_normal((nblk, d)) / np.sqrt(d)).astype(np.float32))
+    thr = 3.1
+    S, M = oracle.mlp_predict(c["X"], np.ascontiguousarray(Wa_t.T), thr)
+    assert 0 < M.sum() < nblk
+    assert np.abs(S - thr).min() > 1e-3                       # no score near the threshold here
+    X, Wu, Wd = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down"))
+    mask = lx.lx_mlp_predict_mask(X, dev(Wa_t, "bf16"), thr, T)
+    assert np.array_equal(host(mask), M)
+    bl = lx.lx_mask_compact(mask)
+    Y = torch.full_like(X, float("nan"))
+    H = torch.empty(bl.nnz_cap * (T // 64) * 4096, dtype=X.dtype, device="cuda")
+    lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, 64, 64, Y, H)
+    torch.cuda.synchronize()
+    _, Yref = oracle.ffn_fwd(c["X"], c["W_up"], c["W_down"], np.repeat(M, T // 64, axis=0), 64, 64)
+    assert rel_err_max(host(Y), Yref) <= TOL["bf16"] and rel_err_fro(host(Y), Yref) <= FRO["bf16"]
