@@ -51,6 +51,15 @@ def make_workload(name: str):
         f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
         a = inputs.config3_attn()
         ffn_calls = 2
+    elif name == "opt1.3b_layer_shared":
+        # the paper's own operating point (Sec. V-A): per FFN call ONE list of active neuron
+        # blocks, predicted on the device from the call's tokens (scores, threshold, OR over
+        # all tokens) and shared by all its token tiles; same shapes and density otherwise
+        f = inputs.ffn_bernoulli(8192, 2048, 8192, 64, 64, 0.11, seed=2100, dtype="bf16")
+        f["predictor"] = inputs.predictor_planted(2048, 128, 0.11, seed=2100)
+        f["mask"] = np.repeat(f["predictor"]["hot"][None].astype(np.uint8), 128, axis=0)
+        a = inputs.config3_attn()
+        ffn_calls = 2
     elif name == "config4":
         f = inputs.config4_ffn()
         a = inputs.config4_attn()
@@ -75,17 +84,26 @@ class FfnJob:
         self.X = dev(f["X"][sl], "bf16")
         self.dY = dev(f["dY"][sl], "bf16")
         self.mask_h = np.ascontiguousarray(f["mask"][rows[0]:rows[1]])
-        self.mask = torch.from_numpy(self.mask_h).cuda()
         self.Wu, self.Wd, self.Wut, self.Wdt = Wu, Wd, Wut, Wdt
         self.T, self.d = self.X.shape
         self.F = Wu.shape[0]
         Tt, Fb = self.mask_h.shape
-        self.nnz = int(self.mask_h.sum())
-        self.cap = Tt * Fb
-        self.bl = lx.BlockList(Tt, Fb, torch.empty(Tt + 1, dtype=torch.int32, device="cuda"),
+        self.nnz = int(self.mask_h.sum())          # active (tile, block) pairs
+        self.pred = f.get("predictor")
+        if self.pred is None:                      # mask rows are inputs, one per token tile
+            self.mask = torch.from_numpy(self.mask_h).cuda()
+            lrows, lnnz = Tt, self.nnz
+        else:                                      # one row, written by the predictor every step
+            self.Wa_t = dev(self.pred["Wa_t"], "bf16")
+            self.mask = torch.zeros((1, Fb), dtype=torch.uint8, device="cuda")
+            self.pws = torch.empty(lx.lx_mlp_predict_workspace_bytes(self.T, Fb, self.T),
+                                   dtype=torch.uint8, device="cuda")
+            lrows, lnnz = 1, int(self.pred["hot"].sum())
+        self.cap = lrows * Fb
+        self.bl = lx.BlockList(lrows, Fb, torch.empty(lrows + 1, dtype=torch.int32, device="cuda"),
                                torch.empty(self.cap, dtype=torch.int32, device="cuda"), self.cap)
         # H_act sized by the host-known active count (the mask is a host-generated input)
-        self.bl_run = lx.BlockList(Tt, Fb, self.bl.row_ptr, self.bl.col_idx, max(self.nnz, 1))
+        self.bl_run = lx.BlockList(lrows, Fb, self.bl.row_ptr, self.bl.col_idx, max(lnnz, 1))
         self.H_act = torch.empty(max(self.nnz, 1) * 4096, dtype=torch.bfloat16, device="cuda")
         self.Y = torch.empty_like(self.X)
         self.dX = torch.empty_like(self.X)
@@ -93,6 +111,11 @@ class FfnJob:
                                                   max(self.nnz, 1), 1)
         self.ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
         self.used = float((self.mask_h.sum(0) > 0).mean())     # fraction of neuron blocks touched
+
+    def predict(self):
+        if self.pred is not None:
+            self.lx.lx_mlp_predict_mask(self.X, self.Wa_t, self.pred["thr"], self.T, mask=self.mask,
+                                        workspace=self.pws)
 
     def run(self):
         lx = self.lx
@@ -187,6 +210,9 @@ def kernel_model(lx, ffn_jobs, attn):
         lx.LX_K_ATTN_BWD_DQ: (1, attn.flops(3), 6 * u + 2 * stat),
         lx.LX_K_ATTN_BWD_DKV: (1, attn.flops(4), 6 * u + 2 * stat),
         lx.LX_K_COMPACT: (1, 0.0, 0.0),
+        **({lx.LX_K_PREDICT: (n, 2.0 * fj.T * fj.d * fj.mask_h.shape[1],
+                              2.0 * (fj.T * fj.d + fj.mask_h.shape[1] * fj.d))}
+           if fj.pred is not None else {}),
     }
 
 
@@ -250,6 +276,8 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     cb.add(attn.mask, attn.bl_r).add(attn.mask, attn.bl_c, transpose=True)
 
     def step():
+        for j in ffn_jobs:
+            j.predict()
         lx.lx_mask_compact_batch(cb)
         for j in ffn_jobs:
             j.run()
@@ -258,6 +286,9 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     for _ in range(max(warmup, 1)):
         step()
     torch.cuda.synchronize()
+    for j in ffn_jobs:        # the predicted mask is the planted one (accounting relies on it)
+        if j.pred is not None:
+            assert np.array_equal(j.mask.cpu().numpy()[0].astype(bool), j.pred["hot"])
 
     # per-kernel breakdown (untimed pre-pass, 3 steps per kernel)
     model = kernel_model(lx, ffn_jobs, attn)

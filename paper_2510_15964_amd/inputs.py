@@ -211,6 +211,20 @@ def config4_attn(seed=4000):
     return attn_blocks(4, 32, 2048, 128, 0.25, seed)
 
 
+def predictor_planted(d, nblk, density, seed, hot_scale=4.0, thr=6.5):
+    """Predictor matrix Wa_t [nblk, d] (bf16-representable) whose block scores X Wa_t^T, for
+    X ~ N(0,1), are N(0,1) for cold blocks and N(0, hot_scale^2) for a planted set of
+    round(density * nblk) hot blocks.  Over thousands of tokens the largest score of a cold
+    block stays below `thr` and that of a hot block far above it, so the mask reduced over the
+    tokens is the planted set, with a wide margin around the threshold."""
+    rng = _rng(seed, 20)
+    hot = np.zeros(nblk, dtype=bool)
+    hot[rng.permutation(nblk)[:int(round(density * nblk))]] = True
+    W = rng.standard_normal((nblk, d)).astype(np.float32) / np.float32(np.sqrt(d))
+    W[hot] *= np.float32(hot_scale)
+    return dict(Wa_t=bf16_round(W), thr=float(thr), hot=hot)
+
+
 def config5_ffn(density, seed=5000):
     """OPT-13B-shaped FFN, iid Bernoulli(density) blocks."""
     return ffn_bernoulli(4096, 5120, 20480, 64, 64, density,

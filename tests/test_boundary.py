@@ -140,3 +140,36 @@ def test_attn_validation(lxmod):
     r = g(L.LX_BF16, 2, 32, 256, 64, 0.125, 1, FAKE, FAKE, FAKE, FAKE, None, FAKE, st, C.byref(bl),
           C.byref(bl), 1, None, FAKE, FAKE, FAKE, FAKE, need, None)
     assert r == L.LX_ERR_INVALID_ARG
+
+
+def test_ffn_list_rows_must_divide_the_token_tiles(lxmod):
+    L = lxmod
+    # 8 token tiles: lists with 1, 2, 4, 8 rows are accepted by the validation (the H_act-less
+    # call then fails on the workspace, after the list has been accepted), 3 rows are not
+    for rows in (1, 2, 4, 8):
+        assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, _bl(L, rows, 16), H=None) == \
+            L.LX_ERR_WORKSPACE
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, _bl(L, 3, 16)) == L.LX_ERR_INVALID_ARG
+    assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, _bl(L, 16, 16)) == L.LX_ERR_INVALID_ARG
+
+
+def test_mlp_predict_validation(lxmod):
+    L = lxmod
+    f = L._lib.lx_mlp_predict_mask
+    args = lambda **k: [k.get("dt", L.LX_BF16), k.get("T", 512), k.get("d", 128), k.get("nblk", 128),
+                        k.get("g", 512), k.get("X", FAKE), FAKE, k.get("thr", 1.0),
+                        k.get("mask", FAKE), k.get("ws", FAKE), k.get("wsb", 1 << 20), None]
+    assert f(*args(dt=L.LX_F32)) == L.LX_ERR_UNSUPPORTED
+    assert f(*args(T=500)) == L.LX_ERR_UNSUPPORTED
+    assert f(*args(d=100)) == L.LX_ERR_UNSUPPORTED
+    assert f(*args(nblk=100)) == L.LX_ERR_UNSUPPORTED
+    assert f(*args(g=96)) == L.LX_ERR_INVALID_ARG              # not a multiple of 64
+    assert f(*args(g=192)) == L.LX_ERR_INVALID_ARG             # does not divide T
+    assert f(*args(X=None)) == L.LX_ERR_INVALID_ARG
+    assert f(*args(mask=None)) == L.LX_ERR_INVALID_ARG
+    assert f(*args(thr=float("nan"))) == L.LX_ERR_INVALID_ARG
+    assert f(*args(ws=None)) == L.LX_ERR_WORKSPACE
+    need = L.lx_mlp_predict_workspace_bytes(512, 128, 512)
+    assert need >= 8 * 128
+    assert f(*args(wsb=need - 1)) == L.LX_ERR_WORKSPACE
+    assert L.lx_mlp_predict_workspace_bytes(512, 128, 64) == 0
