@@ -96,8 +96,6 @@ class FfnJob:
         else:                                      # one row, written by the predictor every step
             self.Wa_t = dev(self.pred["Wa_t"], "bf16")
             self.mask = torch.zeros((1, Fb), dtype=torch.uint8, device="cuda")
-            self.pws = torch.empty(lx.lx_mlp_predict_workspace_bytes(self.T, Fb, self.T),
-                                   dtype=torch.uint8, device="cuda")
             lrows, lnnz = 1, int(self.pred["hot"].sum())
         self.cap = lrows * Fb
         self.bl = lx.BlockList(lrows, Fb, torch.empty(lrows + 1, dtype=torch.int32, device="cuda"),
@@ -114,8 +112,7 @@ class FfnJob:
 
     def predict(self):
         if self.pred is not None:
-            self.lx.lx_mlp_predict_mask(self.X, self.Wa_t, self.pred["thr"], self.T, mask=self.mask,
-                                        workspace=self.pws)
+            self.lx.lx_mlp_predict_mask(self.X, self.Wa_t, self.pred["thr"], self.T, mask=self.mask)
 
     def run(self):
         lx = self.lx

@@ -85,7 +85,7 @@ typedef enum {
   LX_K_ATTN_BWD_DQ = 6,  /* Delta and dQ, query side */
   LX_K_ATTN_BWD_DKV = 7, /* dK and dV, key side */
   LX_K_TRANSPOSE = 8,    /* weight repack */
-  LX_K_PREDICT = 9       /* MLP predictor scores + threshold + OR over a token tile */
+  LX_K_PREDICT = 9       /* MLP predictor: scores + threshold + OR over the tokens */
 } lx_kernel;
 
 /* Human-readable name of a status code (HOST string, static storage). */
@@ -206,18 +206,16 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
  *   X      [T,d]
  *   Wa_t   [nblk,d]: the predictor matrix of the paper ([d, nblk]) transposed,
  *          so that it is read along its contiguous dimension like the weights
- *   mask   out, uint8 [T/group_rows][nblk]
- *   workspace  >= lx_mlp_predict_workspace_bytes (per-tile masks before the
- *          reduction; none needed for group_rows = 64)
+ *   mask   out, uint8 [T/group_rows][nblk] (cleared and filled by the call,
+ *          no workspace)
  * The comparison is made on fp32 sums of bf16 products; a score within rounding
  * distance of thr may fall on either side.
  * Supported: LX_BF16, d % 64 == 0, nblk % 64 == 0, T % 64 == 0, group_rows a
  * multiple of 64 that divides T.
  */
-size_t lx_mlp_predict_workspace_bytes(int32_t T, int32_t nblk, int32_t group_rows);
 lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
                               const void* X, const void* Wa_t, float thr, uint8_t* mask,
-                              void* workspace, size_t workspace_bytes, void* stream);
+                              void* stream);
 
 /* Workspace (bytes) for lx_sparse_attn_bwd_dx (the forward call needs none). */
 size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, int32_t S,

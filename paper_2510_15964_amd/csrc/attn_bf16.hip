@@ -749,7 +749,6 @@ static int rows_per_wg(int nblk, int heads, int B, int slots) {
   if (g_rows_per_wg > 0) r = g_rows_per_wg;
   return r > nblk ? nblk : r;
 }
-constexpr int kCUs = 256;   // compute units of the chip: slots = kCUs * resident workgroups per CU
 
 template <int D>
 static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {

@@ -46,16 +46,17 @@ constexpr int kSddStages = 3, kDsdStages = 2;
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-// One stage = kIssues DMA instructions per wave.  Instruction u of wave w fills stage rows
-// 8g .. 8g+7 with g = w + kFW*u (g < 8: the 64 shared rows, then the weight blocks); lane l
-// brings the 16-byte slot l%8 of row 8g + l/8.  src[u] already points at this lane's (row,
-// swizzled segment); offB / offA are the element offsets of the current K-step for the shared
-// rows and the weight rows.
-__device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[kIssues],
+// One stage = NISS DMA instructions per wave (kIssues for the 64 + 256 rows of the FFN kernels).
+// Instruction u of wave w fills stage rows 8g .. 8g+7 with g = w + kFW*u (g < 8: the 64 shared
+// rows, then the weight blocks); lane l brings the 16-byte slot l%8 of row 8g + l/8.  src[u]
+// already points at this lane's (row, swizzled segment); offB / offA are the element offsets of
+// the current K-step for the shared rows and the weight rows.
+template <int NISS>
+__device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[NISS],
                                             long long offB, long long offA) {
   const uint32_t base = lds_addr(stage) + (threadIdx.x / kWave) * 1024;
 #pragma unroll
-  for (int u = 0; u < kIssues; ++u)
+  for (int u = 0; u < NISS; ++u)
     dma16(src[u] + (u < 8 / kFW ? offB : offA), base + u * (kFW * 1024));
 }
 
@@ -98,16 +99,29 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
 // landed (its loads retire in order, so the loads of the younger steps may stay outstanding),
 // the barrier then guarantees that the whole stage is there and that nobody still reads the
 // stage about to be refilled.
-template <int NST, class Offs>
-__device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
-                                         const uint16_t* const (&src)[kIssues], Offs offs,
-                                         uint16_t* ring, f32x16 (&acc)[kNI][2]) {
-  static_assert(NST >= 2 && NST <= 4 && kIssues * (NST - 2) < 64, "ring depth");
-  const int wave = threadIdx.x / kWave;
+// Wait until at most NISS * y DMA instructions are outstanding, for a run-time y <= M (the last
+// steps of a ring, when fewer stages than its depth are in flight).
+template <int NISS, int M>
+__device__ __forceinline__ void wait_tail(int y) {
+  if constexpr (M <= 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (y == M)
+      wait_vmcnt<NISS * M>();
+    else
+      wait_tail<NISS, M - 1>(y);
+  }
+}
+
+// step(stage pointer) is the multiplication of one landed stage; a stage holds SE elements.
+template <int NST, int NISS, int SE, class Offs, class Step>
+__device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&src)[NISS], Offs offs,
+                                            uint16_t* ring, Step step) {
+  static_assert(NST >= 2 && NISS * (NST - 2) < 64, "ring depth");
   long long ob, oa;
   auto issue = [&](int s, int stage) {
     offs(s, ob, oa);
-    issue_stage(ring + stage * kStageElems, src, ob, oa);
+    issue_stage<NISS>(ring + stage * SE, src, ob, oa);
   };
 #pragma unroll
   for (int p = 0; p < NST - 1; ++p)
@@ -116,16 +130,24 @@ __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
   for (int s = 0; s < nsteps; ++s) {
     const int younger = nsteps - 1 - s;   // steps after s whose DMA has been issued: min(., NST-2)
     if (younger >= NST - 2)
-      wait_vmcnt<kIssues * (NST - 2)>();
-    else if (NST == 4 && younger == 1)
-      wait_vmcnt<kIssues>();
+      wait_vmcnt<NISS * (NST - 2)>();
     else
-      wait_vmcnt<0>();
+      wait_tail<NISS, NST - 3>(younger);
     lds_barrier();
     if (s + NST - 1 < nsteps) issue(s + NST - 1, stage == 0 ? NST - 1 : stage - 1);
-    if (wave_on) mma_step(ring + stage * kStageElems, wave, acc);
+    step(ring + stage * SE);
     stage = stage + 1 == NST ? 0 : stage + 1;
   }
+}
+
+template <int NST, class Offs>
+__device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
+                                         const uint16_t* const (&src)[kIssues], Offs offs,
+                                         uint16_t* ring, f32x16 (&acc)[kNI][2]) {
+  const int wave = threadIdx.x / kWave;
+  run_ring_of<NST, kIssues, kStageElems>(nsteps, src, offs, ring, [&](const uint16_t* stage) {
+    if (wave_on) mma_step(stage, wave, acc);
+  });
 }
 
 // Work items of the sdd kernel are (token tile, group of `per` consecutive list entries),
@@ -331,78 +353,112 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   }
 }
 
-// MLP predictor (Sec. V-A): scores S = X Wa for one 64-token tile and up to 256 neuron blocks
-// (rows of Wa_t [nblk, K], 64 per "weight block" of the pipeline), thresholded and OR-reduced
-// over the tile's tokens: tile_mask[i][n] = any token t of tile i has S[t][n] > thr.  Same
-// pipeline and MFMA core as the sdd kernel; only the epilogue differs.
+// MLP predictor (Sec. V-A): scores S = X Wa for one 64-token tile and NB groups of 64 neuron
+// blocks (rows of Wa_t [nblk, K]), thresholded and OR-reduced over the tokens of a group of
+// tiles_per_group tiles: mask[i / tiles_per_group][n] = 1 if any token t of tile i has
+// S[t][n] > thr.  The mask has been zeroed before; workgroups only ever store ones, so the
+// stores of the tiles of a group to the same byte need no ordering.  Same DMA ring as the sdd
+// kernel with 64 + 64*NB rows per stage; the 4*NB accumulator tiles (32 blocks x 32 tokens)
+// are dealt to the eight wavefronts (two each for NB = 4, else one; NB = 1 leaves four
+// wavefronts with the transfers only).  NB is chosen by the host so that the grid fills the
+// chip when nblk is small.
+template <int NB>
 __global__ __launch_bounds__(kThreads) void predict_bf16(
-    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wa_t, int K, int nblk, float thr,
-    uint8_t* __restrict__ tile_mask) {
-  __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
-  const int i = blockIdx.y, chunk = blockIdx.x;
-  const int nb = min(4, nblk / 64 - chunk * 4);      // 64-row groups of Wa_t in this workgroup
+    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wa_t, int tiles, int K, int nblk,
+    int tiles_per_group, float thr, uint8_t* __restrict__ mask) {
+  constexpr int kSE = (kRowsB + 64 * NB) * kBK;   // stage elements
+  constexpr int kNIss = 1 + NB;                   // DMA instructions per wave and stage
+  constexpr int kTPW = NB == 4 ? 2 : 1;           // accumulator tiles per wavefront
+  // few workgroups, each with little arithmetic per byte: what bounds the small variants is the
+  // number of bytes in flight, so their rings take most of the LDS
+  constexpr int kNSt = NB == 1 ? 8 : NB == 2 ? 6 : kSddStages;
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[kNSt * kSE];
+  // Workgroup w runs on XCD w % 8: the workgroups of one token tile (one per chunk of NB groups
+  // of rows of Wa_t) are given the same XCD, so the tile's tokens reach one L2 only.
+  const int nchunk = nblk / (64 * NB), slot = blockIdx.x / 8;
+  const int i = (slot / nchunk) * 8 + blockIdx.x % 8;   // token tile
+  const int c0 = (slot % nchunk) * NB;                  // first group of 64 rows of Wa_t
+  if (i >= tiles) return;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  const uint16_t* src[kIssues];
+  const uint16_t* src[kNIss];
 #pragma unroll
-  for (int u = 0; u < kIssues; ++u) {
+  for (int u = 0; u < kNIss; ++u) {
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 8 / kFW) {
+    if (u == 0)
       src[u] = X + ((long long)i * 64 + row) * K + seg * 8;
-    } else {
-      const int blk = g / 8 - 1, r = row - kRowsB - 64 * blk;
-      const int j = chunk * 4 + (blk < nb ? blk : 0);   // groups past the end: re-read the first
-      src[u] = Wa_t + ((long long)j * 64 + r) * K + seg * 8;
-    }
+    else
+      src[u] = Wa_t + ((long long)c0 * 64 + row - kRowsB) * K + seg * 8;
   }
-  f32x16 acc[kNI][2];
-  zero_acc(acc);
-  const int blk_w = kNI * wave / 2;
-  run_ring<kSddStages>(K / kBK, blk_w < nb, src,
-                       [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; },
-                       ring, acc);
-  if (blk_w >= nb) return;
-  uint8_t* out = tile_mask + (long long)i * nblk + (chunk * 4 + blk_w) * 64;
+  // tile idx of the workgroup: 32 rows of Wa_t (idx / 2) x 32 tokens (idx % 2)
+  const int idx0 = wave * kTPW;
+  const bool on = idx0 < 4 * NB;
+  const int rgrp = idx0 / 2, r = lane % 32, h2 = lane / 32;
+  f32x16 acc[kTPW];
 #pragma unroll
-  for (int ni = 0; ni < kNI; ++ni) {
-    const int nh = (kNI * wave + ni) % 2;
+  for (int t = 0; t < kTPW; ++t)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      // register v of a lane: block 32*nh + 8*(v/4) + 4*(lane/32) + v%4, tokens lane%32 and +32
-      const unsigned long long hit = __ballot(acc[ni][0][v] > thr || acc[ni][1][v] > thr);
-      const int n = 32 * nh + 8 * (v / 4) + v % 4;
-      if (lane == 0) out[n] = (uint32_t)hit != 0u;
-      if (lane == 32) out[n + 4] = (hit >> 32) != 0ull;
-    }
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  run_ring_of<kNSt, kNIss, kSE>(
+      K / kBK, src, [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; },
+      ring,
+      [&](const uint16_t* stage) {
+        if (!on) return;
+        uint4 a[4], b[4][kTPW];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const int seg = 2 * kk + h2, ra = kRowsB + 32 * rgrp + r;
+          a[kk] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+#pragma unroll
+          for (int t = 0; t < kTPW; ++t) {
+            const int rb = 32 * ((idx0 + t) % 2) + r;
+            b[kk][t] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+          for (int t = 0; t < kTPW; ++t) acc[t] = mfma32(a[kk], b[kk][t], acc[t]);
+      });
+  if (!on) return;
+  uint8_t* out = mask + (long long)(i / tiles_per_group) * nblk + c0 * 64 + 32 * rgrp;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    // register v of a lane: block 8*(v/4) + 4*(lane/32) + v%4 of the 32, token lane%32
+    bool mine = acc[0][v] > thr;
+    if (kTPW == 2) mine = mine || acc[kTPW - 1][v] > thr;
+    const unsigned long long hit = __ballot(mine);
+    const int n = 8 * (v / 4) + v % 4;
+    if (lane == 0 && (uint32_t)hit != 0u) out[n] = 1;
+    if (lane == 32 && (hit >> 32) != 0ull) out[n + 4] = 1;
   }
 }
 
-// group_mask[g][n] = OR over the tiles_per_group tile masks of group g
-__global__ void or_rows_kernel(const uint8_t* __restrict__ tile_mask, int tiles_per_group, int nblk,
-                               int total, uint8_t* __restrict__ group_mask) {
+__global__ void zero_bytes_kernel(uint8_t* __restrict__ p, int n) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int g = idx / nblk, n = idx - g * nblk;
-  uint8_t any = 0;
-  for (int t = 0; t < tiles_per_group; ++t) any |= tile_mask[((long long)g * tiles_per_group + t) * nblk + n];
-  group_mask[idx] = any != 0;
+  if (idx < n) p[idx] = 0;
 }
 
-// tile_mask: [T/64][nblk] bytes (the result itself when tiles_per_group == 1)
+// mask: [T/64/tiles_per_group][nblk] bytes
 hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
-                               const uint16_t* Wa_t, float thr, uint8_t* tile_mask,
-                               uint8_t* group_mask, hipStream_t st) {
-  const int Tt = T / 64;
-  {
-    ProfScope ps(kKPredict, st);
-    hipLaunchKernelGGL(predict_bf16, dim3((nblk / 64 + 3) / 4, Tt), dim3(kThreads), 0, st, X, Wa_t,
-                       d, nblk, thr, tile_mask);
-  }
+                               const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st) {
+  const int Tt = T / 64, total = Tt / tiles_per_group * nblk, ng = nblk / 64;
+  hipLaunchKernelGGL(zero_bytes_kernel, dim3((total + 255) / 256), dim3(256), 0, st, mask, total);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || tiles_per_group == 1) return e;
-  const int total = Tt / tiles_per_group * nblk;
-  hipLaunchKernelGGL(or_rows_kernel, dim3((total + 255) / 256), dim3(256), 0, st,
-                     (const uint8_t*)tile_mask, tiles_per_group, nblk, total, group_mask);
+  if (e != hipSuccess) return e;
+  // the widest workgroup (least re-reading of X) that still gives every CU a workgroup
+  ProfScope ps(kKPredict, st);
+  const int T8 = (Tt + 7) / 8 * 8;   // grid: 8 XCDs x chunks x ceil(Tt / 8) tiles
+  if (ng % 4 == 0 && (long long)ng / 4 * Tt >= kCUs)
+    hipLaunchKernelGGL(predict_bf16<4>, dim3(ng / 4 * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
+                       nblk, tiles_per_group, thr, mask);
+  else if (ng % 2 == 0 && (long long)ng / 2 * Tt >= kCUs)
+    hipLaunchKernelGGL(predict_bf16<2>, dim3(ng / 2 * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
+                       nblk, tiles_per_group, thr, mask);
+  else
+    hipLaunchKernelGGL(predict_bf16<1>, dim3(ng * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d, nblk,
+                       tiles_per_group, thr, mask);
   return hipGetLastError();
 }
 

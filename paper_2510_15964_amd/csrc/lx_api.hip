@@ -272,14 +272,9 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
-size_t lx_mlp_predict_workspace_bytes(int32_t T, int32_t nblk, int32_t group_rows) {
-  if (T <= 0 || nblk <= 0 || group_rows <= 64) return 0;
-  return round256((size_t)(T / 64) * nblk);
-}
-
 lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
                               const void* X, const void* Wa_t, float thr, uint8_t* mask,
-                              void* workspace, size_t workspace_bytes, void* stream) {
+                              void* stream) {
   if (dt != LX_BF16) return LX_ERR_UNSUPPORTED;
   if (T <= 0 || d <= 0 || nblk <= 0 || group_rows <= 0) return LX_ERR_INVALID_ARG;
   if (T % 64 != 0 || d % 64 != 0 || nblk % 64 != 0) return LX_ERR_UNSUPPORTED;
@@ -288,15 +283,8 @@ lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, i
   if (thr != thr) return LX_ERR_INVALID_ARG;   // NaN
   if (2ll * nblk * d >= (1ll << 31) || (int64_t)(T / 64) * nblk >= (1ll << 31))
     return LX_ERR_INVALID_ARG;
-  const int tpg = group_rows / 64;
-  uint8_t* tile_mask = mask;
-  if (tpg > 1) {
-    if (!workspace || workspace_bytes < lx_mlp_predict_workspace_bytes(T, nblk, group_rows))
-      return LX_ERR_WORKSPACE;
-    tile_mask = (uint8_t*)workspace;
-  }
-  return launch_predict_bf16(T, d, nblk, tpg, (const uint16_t*)X, (const uint16_t*)Wa_t, thr,
-                             tile_mask, mask, (hipStream_t)stream) == hipSuccess
+  return launch_predict_bf16(T, d, nblk, group_rows / 64, (const uint16_t*)X, (const uint16_t*)Wa_t,
+                             thr, mask, (hipStream_t)stream) == hipSuccess
              ? LX_OK
              : LX_ERR_RUNTIME;
 }

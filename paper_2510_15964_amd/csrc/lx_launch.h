@@ -5,6 +5,8 @@
 
 namespace lx {
 
+constexpr int kCUs = 256;   // compute units of the chip
+
 // Kernel ids of the profiling aid (values are part of the C ABI: lx_kernel in lx.h).
 enum KernelId {
   kKCompact = 0, kKFfnUp = 1, kKFfnDown = 2, kKFfnDh = 3, kKFfnDx = 4,
@@ -60,8 +62,7 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st);
 hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
-                               const uint16_t* Wa_t, float thr, uint8_t* tile_mask,
-                               uint8_t* group_mask, hipStream_t st);
+                               const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);
 hipError_t launch_attn_fwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);

@@ -31,7 +31,7 @@ EXPORTS = (
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
-    "lx_attn_set_rows_per_workgroup", "lx_mlp_predict_workspace_bytes", "lx_mlp_predict_mask",
+    "lx_attn_set_rows_per_workgroup", "lx_mlp_predict_mask",
 )
 (LX_K_COMPACT, LX_K_FFN_UP, LX_K_FFN_DOWN, LX_K_FFN_DH, LX_K_FFN_DX, LX_K_ATTN_FWD,
  LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE, LX_K_PREDICT) = range(10)
@@ -79,10 +79,7 @@ _lib.lx_sparse_attn_bwd_dx.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32
 _lib.lx_profile_begin.argtypes = [_i32, _i32]
 _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.lx_attn_set_rows_per_workgroup.argtypes = [_i32]
-_lib.lx_mlp_predict_workspace_bytes.restype = _sz
-_lib.lx_mlp_predict_workspace_bytes.argtypes = [_i32, _i32, _i32]
-_lib.lx_mlp_predict_mask.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _vp, _vp, _f, _vp, _vp, _sz,
-                                     _vp]
+_lib.lx_mlp_predict_mask.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _vp, _vp, _f, _vp, _vp]
 
 
 class LxError(RuntimeError):
@@ -209,24 +206,16 @@ def lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_
     return _lib.lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed)
 
 
-def lx_mlp_predict_workspace_bytes(T, nblk, group_rows) -> int:
-    return _lib.lx_mlp_predict_workspace_bytes(T, nblk, group_rows)
-
-
 def lx_mlp_predict_mask(X: torch.Tensor, Wa_t: torch.Tensor, thr: float, group_rows: int,
-                        mask: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+                        mask: torch.Tensor | None = None):
     """mask [T/group_rows, nblk] uint8 = OR over the tokens of a group of (X Wa_t^T > thr)."""
     T, d = X.shape
     nblk = Wa_t.shape[0]
     assert Wa_t.shape == (nblk, d) and X.is_contiguous() and Wa_t.is_contiguous()
     if mask is None:
         mask = torch.empty((T // group_rows, nblk), dtype=torch.uint8, device=X.device)
-    need = lx_mlp_predict_workspace_bytes(T, nblk, group_rows)
-    if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     _check(_lib.lx_mlp_predict_mask(_dt(X), T, d, nblk, group_rows, _ptr(X), _ptr(Wa_t), thr,
-                                    _ptr(mask), _ptr(workspace),
-                                    0 if workspace is None else workspace.numel(), _stream()),
+                                    _ptr(mask), _stream()),
            "lx_mlp_predict_mask")
     return mask
 

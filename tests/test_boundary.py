@@ -158,7 +158,7 @@ def test_mlp_predict_validation(lxmod):
     f = L._lib.lx_mlp_predict_mask
     args = lambda **k: [k.get("dt", L.LX_BF16), k.get("T", 512), k.get("d", 128), k.get("nblk", 128),
                         k.get("g", 512), k.get("X", FAKE), FAKE, k.get("thr", 1.0),
-                        k.get("mask", FAKE), k.get("ws", FAKE), k.get("wsb", 1 << 20), None]
+                        k.get("mask", FAKE), None]
     assert f(*args(dt=L.LX_F32)) == L.LX_ERR_UNSUPPORTED
     assert f(*args(T=500)) == L.LX_ERR_UNSUPPORTED
     assert f(*args(d=100)) == L.LX_ERR_UNSUPPORTED
@@ -168,8 +168,3 @@ def test_mlp_predict_validation(lxmod):
     assert f(*args(X=None)) == L.LX_ERR_INVALID_ARG
     assert f(*args(mask=None)) == L.LX_ERR_INVALID_ARG
     assert f(*args(thr=float("nan"))) == L.LX_ERR_INVALID_ARG
-    assert f(*args(ws=None)) == L.LX_ERR_WORKSPACE
-    need = L.lx_mlp_predict_workspace_bytes(512, 128, 512)
-    assert need >= 8 * 128
-    assert f(*args(wsb=need - 1)) == L.LX_ERR_WORKSPACE
-    assert L.lx_mlp_predict_workspace_bytes(512, 128, 64) == 0

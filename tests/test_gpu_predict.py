@@ -50,6 +50,8 @@ def _check(lx, oracle, X, Wa_t, thr, group):
     (512, 256, 128, 512, 3.1, 2),        # one row for all tokens (the paper's reduction)
     (512, 192, 320, 128, 2.5, 3),        # nblk = 5 groups of 64: a ragged last chunk of the pipeline
     (64, 64, 64, 64, 2.2, 4),            # smallest shape
+    (2048, 128, 2048, 256, 2.8, 6),      # enough work for workgroups of four 64-row groups of Wa_t
+    (8192, 64, 384, 1024, 3.2, 7),       # ... of two (6 groups of rows, 128 token tiles)
 ])
 def test_predict_matches_oracle(lx, oracle, T, d, nblk, group, thr, seed):
     X, Wa_t = _case(T, d, nblk, seed)
