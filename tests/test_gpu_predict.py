@@ -91,3 +91,50 @@ def test_predicted_mask_feeds_the_sparse_ffn(lx, oracle):
     torch.cuda.synchronize()
     _, Yref = oracle.ffn_fwd(c["X"], c["W_up"], c["W_down"], np.repeat(M, T // 64, axis=0), 64, 64)
     assert rel_err_max(host(Y), Yref) <= TOL["bf16"] and rel_err_fro(host(Y), Yref) <= FRO["bf16"]
+
+
+def test_shared_list_full_size_sampled_tiles(lx, oracle):
+    """The benchmark's workload at the paper's operating point (T = 4096, d = 2048, F = 8192, one
+    predicted list of 11 % of the blocks for all tokens) in the launch configuration bench.py times:
+    mask bit-exact against the oracle's predictor, forward and input gradient on sampled token tiles
+    (tiles are independent given the list)."""
+    import torch
+    from util import FRO, TOL, compact_blocks, rel_err_fro, rel_err_max
+    T, d, F, Tt = 4096, 2048, 8192, 64
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, 0.11, seed=2100, dtype="bf16")
+    p = inputs.predictor_planted(d, F // 64, 0.11, seed=2100)
+    S, M = oracle.mlp_predict(c["X"], np.ascontiguousarray(p["Wa_t"].T), p["thr"])
+    assert np.array_equal(M[0].astype(bool), p["hot"])
+    band = 4 * np.finfo(np.float32).eps * np.sqrt(d) * (np.abs(c["X"]).astype(np.float64) @ np.abs(p["Wa_t"].T).astype(np.float64)).max()
+    hi = S.max(axis=0)                                        # the token that decides each block
+    assert (np.abs(hi - p["thr"]) > band).all()               # no block is decided inside the rounding band
+    X, Wu, Wd, dY = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down", "dY"))
+    mask = lx.lx_mlp_predict_mask(X, dev(p["Wa_t"], "bf16"), p["thr"], T)
+    assert np.array_equal(host(mask), M)
+    bl = lx.lx_mask_compact(mask)
+    n = int(M.sum())
+    assert bl.rows == 1 and int(bl.row_ptr[-1].item()) == n
+    H = torch.full((bl.nnz_cap * Tt * 4096,), float("nan"), dtype=X.dtype, device="cuda")
+    Y = torch.full_like(X, float("nan"))
+    lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, 64, 64, Y, H)
+    Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+    ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(lx.LX_BF16, T, d, F, 64, 64, bl.nnz_cap * Tt, 1),
+                     dtype=torch.uint8, device="cuda")
+    dX = torch.full_like(X, float("nan"))
+    lx.lx_sparse_ffn_bwd_dx(dY, H, Wu, Wd, bl, 64, 64, dX, ws, W_up_t=Wut, W_down_t=Wdt)
+    torch.cuda.synchronize()
+    Hh = host(H[:n * Tt * 4096]).reshape(n, Tt, 64, 64)       # [entry][tile][token][neuron]
+    Yh, dXh = host(Y), host(dX)
+    assert np.isfinite(Hh).all() and np.isfinite(Yh).all() and np.isfinite(dXh).all()
+    cols = np.nonzero(M[0])[0]
+    for i in (0, 29, 63):
+        sl = slice(i * 64, (i + 1) * 64)
+        Href, Yref = oracle.ffn_fwd(c["X"][sl], c["W_up"], c["W_down"], M, 64, 64)
+        gate = np.zeros((64, F), dtype=bool)                  # the stored activations decide the gate
+        for k, j in enumerate(cols):
+            gate[:, j * 64:(j + 1) * 64] = Hh[k, i] > 0
+        _, dXref = oracle.ffn_bwd_dx(c["dY"][sl], c["W_up"], c["W_down"], M, gate, 64, 64)
+        prs = ((Hh[:, i], compact_blocks(Href, M, 64, 64)), (Yh[sl], Yref), (dXh[sl], dXref))
+        errs, fro = [rel_err_max(*q) for q in prs], [rel_err_fro(*q) for q in prs]
+        print(f"shared list, tile {i}: max-rel {errs} fro {fro}", flush=True)
+        assert max(errs) <= TOL["bf16"] and max(fro) <= FRO["bf16"]
