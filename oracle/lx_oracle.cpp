@@ -284,4 +284,26 @@ void lxo_mlp_predict(int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
     }
 }
 
+// ---------------------------------------------------------------------------
+// Online pattern combination for multi-head attention (Sec. VI-A; the head's
+// pattern is the pre-defined mask its predicted mask was categorised into,
+// Sec. V-A).  pool: P dense block masks [nblk][nblk] (the atomic patterns whose
+// layouts are pre-computed offline).  Head h of the Hm heads is assigned
+// pattern head_pattern[h]; a negative value assigns no block at all.  The
+// overall pattern of the multi-head attention is the per-head patterns side by
+// side: out [Hm][nblk][nblk].  The block list the operator consumes is the
+// compaction (lxo_mask_compact) of `out` viewed as Hm*nblk rows.
+// ---------------------------------------------------------------------------
+void lxo_attn_combine_patterns(int32_t P, int32_t nblk, const uint8_t* pool, int32_t Hm,
+                               const int32_t* head_pattern, uint8_t* out) {
+  const int64_t nn = (int64_t)nblk * nblk;
+  for (int32_t h = 0; h < Hm; ++h) {
+    const int32_t p = head_pattern[h];
+    for (int32_t q = 0; q < nblk; ++q)
+      for (int32_t k = 0; k < nblk; ++k)
+        out[h * nn + (int64_t)q * nblk + k] =
+            (p >= 0 && p < P && pool[p * nn + (int64_t)q * nblk + k] != 0) ? 1 : 0;
+  }
+}
+
 }  // extern "C"

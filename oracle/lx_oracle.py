@@ -165,3 +165,18 @@ def mlp_predict(X, Wa, thr, group_rows=None):
     lib().lxo_mlp_predict(C.c_int32(T), C.c_int32(d), C.c_int32(nblk), C.c_int32(g), pX, pW,
                           C.c_double(thr), pS, M.ctypes.data_as(C.POINTER(C.c_uint8)))
     return S, M
+
+
+def combine_patterns(pool, head_pattern):
+    """Dense multi-head block mask [Hm, nblk, nblk]: head h carries pool[head_pattern[h]]
+    (no block for a negative entry).  pool: [P, nblk, nblk] bytes."""
+    pool = np.ascontiguousarray(pool, dtype=np.uint8)
+    P, nblk, n2 = pool.shape
+    assert nblk == n2
+    hp = np.ascontiguousarray(head_pattern, dtype=np.int32)
+    out = np.empty((hp.shape[0], nblk, nblk), dtype=np.uint8)
+    lib().lxo_attn_combine_patterns(
+        C.c_int32(P), C.c_int32(nblk), pool.ctypes.data_as(C.POINTER(C.c_uint8)),
+        C.c_int32(hp.shape[0]), hp.ctypes.data_as(C.POINTER(C.c_int32)),
+        out.ctypes.data_as(C.POINTER(C.c_uint8)))
+    return out

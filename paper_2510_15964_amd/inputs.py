@@ -211,6 +211,64 @@ def config4_attn(seed=4000):
     return attn_blocks(4, 32, 2048, 128, 0.25, seed)
 
 
+# ----------------------------------------------------------------------------
+# attention patterns: the pool of Sec. VI-A is fed with dense block masks; these
+# are the usual building blocks of the sparse-attention literature the paper
+# cites (sliding window, global tokens, strided, random), as data
+# ----------------------------------------------------------------------------
+
+def pattern_local(nblk, w, causal=True):
+    """Blocks within w block-diagonals of the diagonal (behind it only when causal)."""
+    q, k = np.arange(nblk)[:, None], np.arange(nblk)[None, :]
+    m = (q - k < w) & (q - k >= 0) if causal else (np.abs(q - k) < w)
+    return m.astype(np.uint8)
+
+
+def pattern_global(nblk, g, causal=True):
+    """The first g key blocks are seen by every query block and the first g query blocks see
+    every key block (up to the diagonal when causal)."""
+    q, k = np.arange(nblk)[:, None], np.arange(nblk)[None, :]
+    m = (k < g) | (q < g)
+    if causal:
+        m &= k <= q
+    return m.astype(np.uint8)
+
+
+def pattern_strided(nblk, s, causal=True):
+    """Every s-th block diagonal."""
+    q, k = np.arange(nblk)[:, None], np.arange(nblk)[None, :]
+    m = (q - k) % s == 0
+    if causal:
+        m &= k <= q
+    return m.astype(np.uint8)
+
+
+def pattern_random(nblk, density, seed, causal=True):
+    q, k = np.arange(nblk)[:, None], np.arange(nblk)[None, :]
+    m = _rng(seed, 40).random((nblk, nblk)) < density
+    if causal:
+        m &= k <= q
+    return m.astype(np.uint8)
+
+
+def pattern_pool(nblk, seed=0, causal=True):
+    """Eight patterns built from the atoms above: window, window + global (two widths each),
+    window + strided, window + global + random, global + random, dense (causal)."""
+    L, G, St, R = pattern_local, pattern_global, pattern_strided, pattern_random
+    c = causal
+    pool = [
+        L(nblk, 2, c),
+        L(nblk, 4, c),
+        L(nblk, 2, c) | G(nblk, 1, c),
+        L(nblk, 3, c) | G(nblk, 2, c),
+        L(nblk, 2, c) | St(nblk, 4, c),
+        L(nblk, 2, c) | G(nblk, 1, c) | R(nblk, 0.10, seed, c),
+        L(nblk, 1, c) | G(nblk, 1, c) | R(nblk, 0.25, seed + 1, c),
+        L(nblk, nblk, c),
+    ]
+    return np.stack(pool).astype(np.uint8)
+
+
 def predictor_planted(d, nblk, density, seed, hot_scale=4.0, thr=6.5):
     """Predictor matrix Wa_t [nblk, d] (bf16-representable) whose block scores X Wa_t^T, for
     X ~ N(0,1), are N(0,1) for cold blocks and N(0, hot_scale^2) for a planted set of
