@@ -85,7 +85,8 @@ typedef enum {
   LX_K_ATTN_BWD_DQ = 6,  /* Delta and dQ, query side */
   LX_K_ATTN_BWD_DKV = 7, /* dK and dV, key side */
   LX_K_TRANSPOSE = 8,    /* weight repack */
-  LX_K_PREDICT = 9       /* MLP predictor: scores + threshold + OR over the tokens */
+  LX_K_PREDICT = 9,      /* MLP predictor: scores + threshold + OR over the tokens */
+  LX_K_COMBINE = 10      /* per-head pattern layouts -> multi-head block list */
 } lx_kernel;
 
 /* Human-readable name of a status code (HOST string, static storage). */
@@ -136,6 +137,31 @@ typedef struct {
   int32_t col_idx_cap;
 } lx_compact_job;
 lx_status lx_mask_compact_batch(const lx_compact_job* jobs, int32_t n_jobs, void* stream);
+
+/*
+ * Online pattern combination for multi-head attention (Sec. VI-A).  Offline, the
+ * pool: the layouts of n_patterns block patterns [nblk][nblk], i.e. the lists
+ * lx_mask_compact builds from their dense masks with batch = n_patterns (pool_r,
+ * rows = n_patterns*nblk, cols = nblk) and, for the backward pass, the
+ * column-compressed lists of the same masks (pool_c, may be NULL together with
+ * row_ptr_c and col_idx_c).  Online, per step: head h (of n_heads = mask_batch *
+ * heads) is assigned pattern head_pattern[h] (DEVICE int32[n_heads]; a value
+ * outside 0..n_patterns-1 assigns no block), and the call writes the list of
+ * the whole attention, rows ordered (head, block row): the layout of each
+ * head's pattern shifted by the number of blocks of the heads before it.  The
+ * result equals lx_mask_compact on the dense mask [n_heads][nblk][nblk] whose
+ * head h is a copy of its pattern; no mask is read or written.
+ *   row_ptr_r / row_ptr_c  out, int32[n_heads*nblk + 1]
+ *   col_idx_r / col_idx_c  out, int32[col_idx_cap] (entries beyond the capacity,
+ *                          or beyond the pool's, are dropped; row_ptr stays exact)
+ * Errors: INVALID_ARG for null pointers, non-positive sizes, or a pool whose
+ * rows / cols do not match n_patterns and nblk.
+ */
+lx_status lx_attn_combine_patterns(const lx_blocklist* pool_r, const lx_blocklist* pool_c,
+                                   int32_t n_patterns, int32_t nblk, const int32_t* head_pattern,
+                                   int32_t n_heads, int32_t* row_ptr_r, int32_t* col_idx_r,
+                                   int32_t* row_ptr_c, int32_t* col_idx_c, int32_t col_idx_cap,
+                                   void* stream);
 
 /*
  * One-time repack of the frozen weights (Sec. VI-B "memory coalescing": each

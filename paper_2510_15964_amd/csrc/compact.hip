@@ -153,4 +153,57 @@ hipError_t launch_compact_pair(const uint8_t* mask, int batch, int rows, int col
   return launch_compact_jobs(j, 2, stream);
 }
 
+// ---------------------------------------------------------------------------
+// Online pattern combination (Sec. VI-A): the list of a multi-head attention
+// whose head h carries pattern head_pattern[h] of a pool whose layouts
+// (row-compressed lists, the "lookup tables") were computed beforehand.  The
+// layout of a head is the layout of its pattern plus an offset: the number of
+// blocks of the heads before it.  No mask is read.
+// Workgroup (h, list): sums the lengths of the heads before h, then copies row
+// pointers (+ offset) and block indices.  Pattern ids outside 0..P-1 give a head
+// without blocks.  Entries beyond the capacity of the pool's or the output's
+// index buffer are dropped; row_ptr stays exact.
+// ---------------------------------------------------------------------------
+struct CombineLists {
+  CombineList l[2];
+};
+constexpr int kCombineThreads = 256;
+
+__global__ __launch_bounds__(kCombineThreads) void combine_patterns_kernel(
+    const CombineLists lists, const int* __restrict__ head_pattern, int P, int nblk, int n_heads) {
+  __shared__ int part[kCombineThreads / kWave];
+  const CombineList L = lists.l[blockIdx.y];
+  const int h = blockIdx.x, tid = threadIdx.x, lane = tid % kWave;
+  auto length = [&](int p) { return p >= 0 && p < P ? L.pool_row_ptr[(p + 1) * nblk] - L.pool_row_ptr[p * nblk] : 0; };
+  int off = 0;
+  for (int g = tid; g < h; g += kCombineThreads) off += length(head_pattern[g]);
+#pragma unroll
+  for (int dlt = 32; dlt > 0; dlt >>= 1) off += __shfl_xor(off, dlt);
+  if (lane == 0) part[tid / kWave] = off;
+  __syncthreads();
+  off = 0;
+#pragma unroll
+  for (int w = 0; w < kCombineThreads / kWave; ++w) off += part[w];
+
+  const int p = head_pattern[h];
+  const bool valid = p >= 0 && p < P;
+  const int start = valid ? L.pool_row_ptr[p * nblk] : 0;
+  const int len = length(p);
+  for (int r = tid; r < nblk; r += kCombineThreads)
+    L.row_ptr[h * nblk + r] = off + (valid ? L.pool_row_ptr[p * nblk + r] - start : 0);
+  if (h == n_heads - 1 && tid == 0) L.row_ptr[n_heads * nblk] = off + len;
+  for (int k = tid; k < len; k += kCombineThreads)
+    if (off + k < L.cap && start + k < L.pool_cap) L.col_idx[off + k] = L.pool_col_idx[start + k];
+}
+
+hipError_t launch_combine_patterns(const CombineList* lists, int n_lists, const int* head_pattern,
+                                   int P, int nblk, int n_heads, hipStream_t stream) {
+  CombineLists ls = {};
+  for (int i = 0; i < n_lists; ++i) ls.l[i] = lists[i];
+  ProfScope ps(kKCombine, stream);
+  hipLaunchKernelGGL(combine_patterns_kernel, dim3(n_heads, n_lists), dim3(kCombineThreads), 0,
+                     stream, ls, head_pattern, P, nblk, n_heads);
+  return hipGetLastError();
+}
+
 }  // namespace lx

@@ -163,6 +163,34 @@ lx_status lx_mask_compact_batch(const lx_compact_job* jobs, int32_t n_jobs, void
   return launch_compact_jobs(cj, n_jobs, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
+lx_status lx_attn_combine_patterns(const lx_blocklist* pool_r, const lx_blocklist* pool_c,
+                                   int32_t n_patterns, int32_t nblk, const int32_t* head_pattern,
+                                   int32_t n_heads, int32_t* row_ptr_r, int32_t* col_idx_r,
+                                   int32_t* row_ptr_c, int32_t* col_idx_c, int32_t col_idx_cap,
+                                   void* stream) {
+  if (!pool_r || !head_pattern || !row_ptr_r || !col_idx_r) return LX_ERR_INVALID_ARG;
+  if (n_patterns <= 0 || nblk <= 0 || n_heads <= 0 || col_idx_cap <= 0) return LX_ERR_INVALID_ARG;
+  if ((int64_t)n_patterns * nblk > (int64_t)1 << 30 || (int64_t)n_heads * nblk > (int64_t)1 << 30)
+    return LX_ERR_INVALID_ARG;
+  const bool with_c = pool_c || row_ptr_c || col_idx_c;
+  if (with_c && (!pool_c || !row_ptr_c || !col_idx_c)) return LX_ERR_INVALID_ARG;
+  const lx_blocklist* pools[2] = {pool_r, pool_c};
+  int32_t* rps[2] = {row_ptr_r, row_ptr_c};
+  int32_t* cis[2] = {col_idx_r, col_idx_c};
+  CombineList cl[2];
+  const int n_lists = with_c ? 2 : 1;
+  for (int i = 0; i < n_lists; ++i) {
+    const lx_blocklist* pl = pools[i];
+    if (!pl->row_ptr || !pl->col_idx || pl->nnz_cap <= 0) return LX_ERR_INVALID_ARG;
+    if (pl->rows != n_patterns * nblk || pl->cols != nblk) return LX_ERR_INVALID_ARG;
+    cl[i] = {pl->row_ptr, pl->col_idx, pl->nnz_cap, rps[i], cis[i], col_idx_cap};
+  }
+  return launch_combine_patterns(cl, n_lists, head_pattern, n_patterns, nblk, n_heads,
+                                 (hipStream_t)stream) == hipSuccess
+             ? LX_OK
+             : LX_ERR_RUNTIME;
+}
+
 lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_up,
                               const void* W_down, void* W_up_t, void* W_down_t, void* stream) {
   if (dt != LX_F32 && dt != LX_BF16) return LX_ERR_UNSUPPORTED;

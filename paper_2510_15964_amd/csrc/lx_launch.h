@@ -10,7 +10,7 @@ constexpr int kCUs = 256;   // compute units of the chip
 // Kernel ids of the profiling aid (values are part of the C ABI: lx_kernel in lx.h).
 enum KernelId {
   kKCompact = 0, kKFfnUp = 1, kKFfnDown = 2, kKFfnDh = 3, kKFfnDx = 4,
-  kKAttnFwd = 5, kKAttnDq = 6, kKAttnDkv = 7, kKTranspose = 8, kKPredict = 9, kKCount = 10
+  kKAttnFwd = 5, kKAttnDq = 6, kKAttnDkv = 7, kKTranspose = 8, kKPredict = 9, kKCombine = 10, kKCount = 11
 };
 void prof_pre(int id, hipStream_t st);
 void prof_post(int id, hipStream_t st);
@@ -50,6 +50,17 @@ struct CompactJob {
   int cap;
 };
 hipError_t launch_compact_jobs(const CompactJob* jobs, int n, hipStream_t stream);
+// One list built by the pattern combination: pool layout in, per-head layout out.
+struct CombineList {
+  const int* pool_row_ptr;   // [P*nblk + 1]
+  const int* pool_col_idx;
+  int pool_cap;
+  int* row_ptr;              // [n_heads*nblk + 1]
+  int* col_idx;
+  int cap;
+};
+hipError_t launch_combine_patterns(const CombineList* lists, int n_lists, const int* head_pattern,
+                                   int P, int nblk, int n_heads, hipStream_t stream);
 hipError_t launch_compact_pair(const uint8_t*, int, int, int, long long, long long, long long, int*,
                                int*, int*, int*, int, hipStream_t);
 hipError_t launch_ffn_f32(int pass, int tile, int Tt, int gt, int Fb, int d, int F, const float* A,

@@ -269,6 +269,27 @@ def pattern_pool(nblk, seed=0, causal=True):
     return np.stack(pool).astype(np.uint8)
 
 
+def attn_patterns(B, Hh, S, D, seed, dtype="bf16", causal=True, probs=None, head_keep=1.0,
+                  mask_batch=1):
+    """Attention inputs whose block masks come from a pool: tensors as in attn_blocks, the pool
+    of pattern_pool, and a seeded pattern id per (mask batch, head); heads dropped by head_keep
+    get id -1 (no block).  The dense mask itself is not formed here."""
+    c = attn_blocks(B, Hh, S, D, 1.0, seed, dtype=dtype, causal=causal, mask_batch=mask_batch)
+    del c["mask"]
+    pool = pattern_pool(S // 64, seed, causal)
+    hp = _rng(seed, 41).choice(pool.shape[0], size=mask_batch * Hh, p=probs).astype(np.int32)
+    if head_keep < 1.0:
+        hp[_rng(seed, 42).random(mask_batch * Hh) >= head_keep] = -1
+    c.update(pool=pool, head_pattern=hp)
+    return c
+
+
+def config3_patterns(seed=3100):
+    """configs[2]'s shape with per-head patterns drawn so that the mean density inside the
+    causal region is about 30 %, as in configs[2]."""
+    return attn_patterns(8, 32, 1024, 64, seed, probs=(0.5, 0.08, 0.27, 0.03, 0.05, 0.05, 0.02, 0.0))
+
+
 def predictor_planted(d, nblk, density, seed, hot_scale=4.0, thr=6.5):
     """Predictor matrix Wa_t [nblk, d] (bf16-representable) whose block scores X Wa_t^T, for
     X ~ N(0,1), are N(0,1) for cold blocks and N(0, hot_scale^2) for a planted set of

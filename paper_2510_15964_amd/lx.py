@@ -31,12 +31,12 @@ EXPORTS = (
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
-    "lx_attn_set_rows_per_workgroup", "lx_mlp_predict_mask",
+    "lx_attn_set_rows_per_workgroup", "lx_mlp_predict_mask", "lx_attn_combine_patterns",
 )
 (LX_K_COMPACT, LX_K_FFN_UP, LX_K_FFN_DOWN, LX_K_FFN_DH, LX_K_FFN_DX, LX_K_ATTN_FWD,
- LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE, LX_K_PREDICT) = range(10)
+ LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE, LX_K_PREDICT, LX_K_COMBINE) = range(11)
 KERNEL_NAMES = ("compact", "ffn_up", "ffn_down", "ffn_dh", "ffn_dx", "attn_fwd", "attn_bwd_dq",
-                "attn_bwd_dkv", "transpose", "predict")
+                "attn_bwd_dkv", "transpose", "predict", "combine")
 
 
 class lx_blocklist(C.Structure):
@@ -80,6 +80,8 @@ _lib.lx_profile_begin.argtypes = [_i32, _i32]
 _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.lx_attn_set_rows_per_workgroup.argtypes = [_i32]
 _lib.lx_mlp_predict_mask.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _vp, _vp, _f, _vp, _vp]
+_lib.lx_attn_combine_patterns.argtypes = [_blp, _blp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
+                                          _vp]
 
 
 class LxError(RuntimeError):
@@ -187,6 +189,28 @@ class CompactBatch:
 def lx_mask_compact_batch(batch: CompactBatch):
     _check(_lib.lx_mask_compact_batch(batch._arr, len(batch.jobs), _stream()),
            "lx_mask_compact_batch")
+
+
+def lx_attn_combine_patterns(pool_r: BlockList, pool_c: BlockList | None, nblk: int,
+                             head_pattern: torch.Tensor, nnz_cap: int | None = None, out=None):
+    """Multi-head list(s) from the pool layouts and the pattern id of every head.  Returns
+    (row list, column list or None)."""
+    assert head_pattern.dtype == torch.int32 and head_pattern.is_cuda and head_pattern.is_contiguous()
+    Hm = head_pattern.numel()
+    P = pool_r.rows // nblk
+    cap = Hm * nblk * nblk if nnz_cap is None else nnz_cap
+    if out is None:
+        mk = lambda: BlockList(Hm * nblk, nblk,
+                               torch.empty(Hm * nblk + 1, dtype=torch.int32, device=head_pattern.device),
+                               torch.empty(max(cap, 1), dtype=torch.int32, device=head_pattern.device), cap)
+        out = (mk(), mk() if pool_c is not None else None)
+    blr, blc = out
+    _check(_lib.lx_attn_combine_patterns(
+        C.byref(pool_r.c), C.byref(pool_c.c) if pool_c is not None else None, P, nblk,
+        _ptr(head_pattern), Hm, _ptr(blr.row_ptr), _ptr(blr.col_idx),
+        _ptr(blc.row_ptr) if blc is not None else None, _ptr(blc.col_idx) if blc is not None else None,
+        max(cap, 1), _stream()), "lx_attn_combine_patterns")
+    return blr, blc
 
 
 def lx_ffn_pack_weights(W_up: torch.Tensor, W_down: torch.Tensor):

@@ -168,3 +168,25 @@ def test_mlp_predict_validation(lxmod):
     assert f(*args(X=None)) == L.LX_ERR_INVALID_ARG
     assert f(*args(mask=None)) == L.LX_ERR_INVALID_ARG
     assert f(*args(thr=float("nan"))) == L.LX_ERR_INVALID_ARG
+
+
+def test_attn_combine_patterns_validation(lxmod):
+    L = lxmod
+    f = L._lib.lx_attn_combine_patterns
+    pool = _bl(L, 8 * 16, 16)
+    ok = lambda **k: [C.byref(k.get("pr", pool)) if k.get("pr", pool) is not None else None,
+                      C.byref(k["pc"]) if k.get("pc") is not None else None,
+                      k.get("P", 8), k.get("nblk", 16), k.get("hp", FAKE), k.get("H", 32),
+                      k.get("rp", FAKE), k.get("ci", FAKE), k.get("rpc"), k.get("cic"),
+                      k.get("cap", 1024), None]
+    assert f(*ok(pr=None)) == L.LX_ERR_INVALID_ARG
+    assert f(*ok(hp=None)) == L.LX_ERR_INVALID_ARG
+    assert f(*ok(rp=None)) == L.LX_ERR_INVALID_ARG
+    assert f(*ok(ci=None)) == L.LX_ERR_INVALID_ARG
+    assert f(*ok(P=0)) == L.LX_ERR_INVALID_ARG
+    assert f(*ok(H=0)) == L.LX_ERR_INVALID_ARG
+    assert f(*ok(cap=0)) == L.LX_ERR_INVALID_ARG
+    assert f(*ok(P=7)) == L.LX_ERR_INVALID_ARG                 # pool rows != P * nblk
+    assert f(*ok(nblk=8)) == L.LX_ERR_INVALID_ARG              # pool cols != nblk
+    assert f(*ok(pc=pool)) == L.LX_ERR_INVALID_ARG             # column pool without column outputs
+    assert f(*ok(rpc=FAKE, cic=FAKE)) == L.LX_ERR_INVALID_ARG  # column outputs without a pool
