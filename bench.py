@@ -60,6 +60,13 @@ def make_workload(name: str):
         f["mask"] = np.repeat(f["predictor"]["hot"][None].astype(np.uint8), 128, axis=0)
         a = inputs.config3_attn()
         ffn_calls = 2
+    elif name == "opt1.3b_layer_patterns":
+        # attention masks the way the paper forms them (Sec. VI-A): every head is assigned one
+        # pattern of a pool whose layouts were computed beforehand; the step combines them into
+        # the multi-head list on the device instead of compacting dense masks
+        f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
+        a = inputs.config3_patterns()
+        ffn_calls = 2
     elif name == "config4":
         f = inputs.config4_ffn()
         a = inputs.config4_attn()
@@ -135,12 +142,20 @@ class AttnJob:
         from util import dev
         self.lx, self.torch, self.a = lx, torch, a
         self.Q, self.K, self.V, self.dO = (dev(a[k], "bf16") for k in ("Q", "K", "V", "dO"))
-        self.mask = torch.from_numpy(a["mask"]).cuda()
         self.ha = torch.from_numpy(a["head_active"]).cuda()
         B, Hh, S, D = self.Q.shape
         self.B, self.Hh, self.S, self.D = B, Hh, S, D
         nb = S // 64
         mb = a["mask_batch"]
+        self.pool = a.get("pool")
+        if self.pool is None:                      # dense masks, compacted every step
+            self.mask = torch.from_numpy(a["mask"]).cuda()
+            blocks_per_head = a["mask"].sum(axis=(2, 3))                  # [mb, Hh]
+        else:                                      # offline: the layouts of the pool's patterns
+            self.pool_r, self.pool_c = lx.lx_mask_compact_pair(torch.from_numpy(self.pool).cuda())
+            self.hp = torch.from_numpy(a["head_pattern"]).cuda()
+            hp = a["head_pattern"].reshape(mb, Hh)
+            blocks_per_head = np.where(hp >= 0, self.pool.sum(axis=(1, 2))[np.maximum(hp, 0)], 0)
         rows = mb * Hh * nb
         mk = lambda: lx.BlockList(rows, nb, torch.empty(rows + 1, dtype=torch.int32, device="cuda"),
                                   torch.empty(rows * nb, dtype=torch.int32, device="cuda"), rows * nb)
@@ -152,8 +167,14 @@ class AttnJob:
                               dtype=torch.uint8, device="cuda")
         act = a["head_active"].astype(bool)
         self.h_act = int(act.sum())
-        per_batch = a["mask"][:, act].sum(axis=(1, 2, 3))      # blocks per mask batch entry
+        per_batch = blocks_per_head[:, act].sum(axis=1)        # blocks per mask batch entry
         self.nblk = float(per_batch.sum() * (B if mb == 1 else 1))
+        self.density = float(blocks_per_head.sum() / (mb * Hh * nb * (nb + 1) / 2))   # over all heads
+
+    def combine(self):
+        if self.pool is not None:
+            self.lx.lx_attn_combine_patterns(self.pool_r, self.pool_c, self.S // 64, self.hp,
+                                             out=(self.bl_r, self.bl_c))
 
     def run(self):
         lx, a = self.lx, self.a
@@ -207,6 +228,7 @@ def kernel_model(lx, ffn_jobs, attn):
         lx.LX_K_ATTN_BWD_DQ: (1, attn.flops(3), 6 * u + 2 * stat),
         lx.LX_K_ATTN_BWD_DKV: (1, attn.flops(4), 6 * u + 2 * stat),
         lx.LX_K_COMPACT: (1, 0.0, 0.0),
+        **({lx.LX_K_COMBINE: (1, 0.0, 0.0)} if attn.pool is not None else {}),
         **({lx.LX_K_PREDICT: (n, 2.0 * fj.T * fj.d * fj.mask_h.shape[1],
                               2.0 * (fj.T * fj.d + fj.mask_h.shape[1] * fj.d))}
            if fj.pred is not None else {}),
@@ -229,7 +251,12 @@ def cpu_baseline(f, a, ffn_tiles=3, attn_heads=24):
     t_ffn = time.perf_counter() - t0
     heads = np.nonzero(a["head_active"])[0][:attn_heads]
     sub = {k: np.ascontiguousarray(a[k][0:1, heads]) for k in ("Q", "K", "V", "dO")}
-    mk = np.ascontiguousarray(a["mask"][0:1, heads])
+    if "pool" in a:
+        nb = a["S"] // 64
+        dense = oracle.combine_patterns(a["pool"], a["head_pattern"]).reshape(-1, a["Hh"], nb, nb)
+    else:
+        dense = a["mask"]
+    mk = np.ascontiguousarray(dense[0:1, heads])
     t0 = time.perf_counter()
     oracle.attn_fwd(sub["Q"], sub["K"], sub["V"], mk, a["scale"], a["causal"], None, a["blk"])
     oracle.attn_bwd(sub["Q"], sub["K"], sub["V"], sub["dO"], mk, a["scale"], a["causal"], None,
@@ -270,12 +297,14 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     cb = lx.CompactBatch()
     for j in ffn_jobs:
         cb.add(j.mask, j.bl)
-    cb.add(attn.mask, attn.bl_r).add(attn.mask, attn.bl_c, transpose=True)
+    if attn.pool is None:
+        cb.add(attn.mask, attn.bl_r).add(attn.mask, attn.bl_c, transpose=True)
 
     def step():
         for j in ffn_jobs:
             j.predict()
         lx.lx_mask_compact_batch(cb)
+        attn.combine()
         for j in ffn_jobs:
             j.run()
         attn.run()
@@ -297,7 +326,8 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
         torch.cuda.synchronize()
         ms, n = lx.lx_profile_end()
         per_kernel[kid] = (ms / 3.0, ms / max(n, 1))      # ms per step, ms per launch
-    dom = max((k for k in per_kernel if k != lx.LX_K_COMPACT), key=lambda k: per_kernel[k][0])
+    dom = max((k for k in per_kernel if k not in (lx.LX_K_COMPACT, lx.LX_K_COMBINE)),
+              key=lambda k: per_kernel[k][0])
 
     # timed region: exactly `steps` steps, dominant kernel bracketed by events
     lx.lx_profile_begin(dom, steps * model[dom][0])
@@ -344,10 +374,10 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
                     "active_blocks": int(f["mask"].sum())},
             "attn": {"B": a["B"], "heads": a["Hh"], "active_heads": attn.h_act, "S": a["S"],
                      "D": a["D"], "causal": bool(a["causal"]),
-                     "block_density_in_causal_region": float(
-                         a["mask"].sum() / (a["mask"].shape[0] * a["Hh"] * (a["S"] // 64) *
-                                            (a["S"] // 64 + 1) / 2)),
-                     "active_blocks": attn.nblk},
+                     "block_density_in_causal_region": attn.density,
+                     "active_blocks": attn.nblk,
+                     **({"mask_source": "pattern pool, combined on the device every step"}
+                        if attn.pool is not None else {})},
         },
         "active_tflops": flops_step / (elapsed / steps) / 1e12,
         "mfma_util_active_flops": flops_step / (elapsed / steps) / PEAK_MFMA_BF16,

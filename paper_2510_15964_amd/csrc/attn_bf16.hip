@@ -205,13 +205,14 @@ __device__ __forceinline__ void zero(f32x16 (&a)[N]) {
     for (int v = 0; v < 16; ++v) a[i][v] = 0.f;
 }
 
-// accumulator layout [c-tile][v] (c = 32ct + 8(v/4) + 4(lane/32) + v%4, row = lane%32) -> global
-template <int D>
+// accumulator layout [c-tile][v] (c = 32ct + 8(v/4) + 4(lane/32) + v%4, row = lane%32) -> global;
+// c-tiles C0 .. C0+N-1 only
+template <int D, int C0 = 0, int N = D / 32>
 __device__ __forceinline__ void store_acc(const f32x16 (&acc)[D / 32], float mul,
                                           uint16_t* __restrict__ dst_row) {
   const int h2 = (threadIdx.x % kWave) / 32;
 #pragma unroll
-  for (int ct = 0; ct < D / 32; ++ct)
+  for (int ct = C0; ct < C0 + N; ++ct)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       uint2 o;
@@ -221,26 +222,31 @@ __device__ __forceinline__ void store_acc(const f32x16 (&acc)[D / 32], float mul
     }
 }
 
-// Exchange of accumulators between the two wavefronts that share own rows, through an LDS area
-// of 2 * (D/2) * 64 floats (exactly one stage of tiles): [own][register][lane], so that a
-// wavefront's 64 lanes write and read consecutive words.
-template <int D>
-__device__ __forceinline__ void put_acc(float* area, int own, const f32x16 (&acc)[D / 32]) {
-  float* p = area + own * (D / 2) * 64 + threadIdx.x % kWave;
+// Exchange of accumulators between the two wavefronts that share own rows (parts 0 and 1),
+// through an LDS area of 4 * (D/4) * 64 floats (exactly one stage of tiles).  Each of the two
+// finishes one half of the c-tiles: part p keeps tiles p*D/64 .. and hands the other half to its
+// partner, so both halves of the pair share the combination and the stores.  Layout
+// [writer's part][own][register][lane]: a wavefront's 64 lanes write and read consecutive words.
+template <int D, int PART>
+__device__ __forceinline__ void put_half(float* area, int own, const f32x16 (&acc)[D / 32]) {
+  constexpr int kN = D / 64, kC0 = (1 - PART) * kN;   // the partner's tiles
+  float* p = area + (PART * 2 + own) * (16 * kN) * 64 + threadIdx.x % kWave;
 #pragma unroll
-  for (int ct = 0; ct < D / 32; ++ct)
+  for (int ct = 0; ct < kN; ++ct)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) p[(16 * ct + v) * 64] = acc[ct][v];
+    for (int v = 0; v < 16; ++v) p[(16 * ct + v) * 64] = acc[kC0 + ct][v];
 }
-// acc = acc * mine + other * theirs
-template <int D>
-__device__ __forceinline__ void merge_acc(const float* area, int own, float mine, float theirs,
-                                          f32x16 (&acc)[D / 32]) {
-  const float* p = area + own * (D / 2) * 64 + threadIdx.x % kWave;
+// own tiles: acc = acc * mine + partner's * theirs
+template <int D, int PART>
+__device__ __forceinline__ void merge_half(const float* area, int own, float mine, float theirs,
+                                           f32x16 (&acc)[D / 32]) {
+  constexpr int kN = D / 64, kC0 = PART * kN;
+  const float* p = area + ((1 - PART) * 2 + own) * (16 * kN) * 64 + threadIdx.x % kWave;
 #pragma unroll
-  for (int ct = 0; ct < D / 32; ++ct)
+  for (int ct = 0; ct < kN; ++ct)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[ct][v] = acc[ct][v] * mine + p[(16 * ct + v) * 64] * theirs;
+    for (int v = 0; v < 16; ++v)
+      acc[kC0 + ct][v] = acc[kC0 + ct][v] * mine + p[(16 * ct + v) * 64] * theirs;
 }
 
 // ---------------------------------------------------------------------------
@@ -389,7 +395,7 @@ __device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin
 template <int D>
 __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
-  __shared__ float xstat[2][2][64];   // [own][max, sum][lane] of the wavefronts with part 1
+  __shared__ float xstat[2][2][2][64];   // [part][own][max, sum][lane]
   __shared__ int rowtab[3 * kRMax];
   const int nqb = a.S / 64;
   const int h = blockIdx.x, b = blockIdx.y;
@@ -493,24 +499,28 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
   auto row_end = [&](int, int stage) {
     float* area = reinterpret_cast<float*>(st[stage]);
     lds_barrier();                       // every wavefront is done with the tiles of this stage
-    if (part == 1) {
-      put_acc<D>(area, own, o_acc);
-      xstat[own][0][lane] = m;
-      xstat[own][1][lane] = lsum;
-    }
+    if (part == 0)
+      put_half<D, 0>(area, own, o_acc);
+    else
+      put_half<D, 1>(area, own, o_acc);
+    xstat[part][own][0][lane] = m;
+    xstat[part][own][1][lane] = lsum;
     lds_barrier();
+    const float m1 = xstat[1 - part][own][0][lane], l1 = xstat[1 - part][own][1][lane];
+    const float mt = fmaxf(m, m1);
+    const float mu = mt == -INFINITY ? 0.f : mt;
+    const float a0 = __builtin_amdgcn_exp2f(m - mu), a1 = __builtin_amdgcn_exp2f(m1 - mu);
+    const float l = lsum * a0 + l1 * a1;
+    const bool any = l > 0.f;
+    const float inv = any ? 1.f / l : 0.f;
     if (part == 0) {
-      const float m1 = xstat[own][0][lane], l1 = xstat[own][1][lane];
-      const float mt = fmaxf(m, m1);
-      const float mu = mt == -INFINITY ? 0.f : mt;
-      const float a0 = __builtin_amdgcn_exp2f(m - mu), a1 = __builtin_amdgcn_exp2f(m1 - mu);
-      const float l = lsum * a0 + l1 * a1;
-      const bool any = l > 0.f;
-      const float inv = any ? 1.f / l : 0.f;
-      merge_acc<D>(area, own, a0 * inv, a1 * inv, o_acc);
-      store_acc<D>(o_acc, 1.f, a.Out + qoff);
+      merge_half<D, 0>(area, own, a0 * inv, a1 * inv, o_acc);
+      store_acc<D, 0, D / 64>(o_acc, 1.f, a.Out + qoff);
       if (h2 == 0)
         a.LSE[stat_base + qb * 64 + ql] = any ? (mt + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    } else {
+      merge_half<D, 1>(area, own, a0 * inv, a1 * inv, o_acc);
+      store_acc<D, D / 64, D / 64>(o_acc, 1.f, a.Out + qoff);
     }
   };
   walk_rows(rows, row_begin, issue, comp, row_end);
@@ -610,11 +620,17 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   auto row_end = [&](int, int stage) {     // dQ = sum over the two key halves
     float* area = reinterpret_cast<float*>(st[stage]);
     lds_barrier();
-    if (part == 1) put_acc<D>(area, own, dq_acc);
+    if (part == 0)
+      put_half<D, 0>(area, own, dq_acc);
+    else
+      put_half<D, 1>(area, own, dq_acc);
     lds_barrier();
     if (part == 0) {
-      merge_acc<D>(area, own, 1.f, 1.f, dq_acc);
-      store_acc<D>(dq_acc, a.scale, a.dQ + qoff);
+      merge_half<D, 0>(area, own, 1.f, 1.f, dq_acc);
+      store_acc<D, 0, D / 64>(dq_acc, a.scale, a.dQ + qoff);
+    } else {
+      merge_half<D, 1>(area, own, 1.f, 1.f, dq_acc);
+      store_acc<D, D / 64, D / 64>(dq_acc, a.scale, a.dQ + qoff);
     }
   };
   walk_rows(rows, row_begin, issue, comp, row_end);
@@ -719,16 +735,29 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   auto row_end = [&](int, int stage) {
     float* area = reinterpret_cast<float*>(st[stage]);
     lds_barrier();
-    if (part == 1) put_acc<D>(area, own, dv_acc);
+    if (part == 0)
+      put_half<D, 0>(area, own, dv_acc);
+    else
+      put_half<D, 1>(area, own, dv_acc);
     lds_barrier();
-    if (part == 0) merge_acc<D>(area, own, 1.f, 1.f, dv_acc);
+    if (part == 0)
+      merge_half<D, 0>(area, own, 1.f, 1.f, dv_acc);
+    else
+      merge_half<D, 1>(area, own, 1.f, 1.f, dv_acc);
     lds_barrier();
-    if (part == 1) put_acc<D>(area, own, dk_acc);
+    if (part == 0)
+      put_half<D, 0>(area, own, dk_acc);
+    else
+      put_half<D, 1>(area, own, dk_acc);
     lds_barrier();
     if (part == 0) {
-      merge_acc<D>(area, own, 1.f, 1.f, dk_acc);
-      store_acc<D>(dv_acc, 1.f, a.dV + koff);
-      store_acc<D>(dk_acc, a.scale, a.dK + koff);
+      merge_half<D, 0>(area, own, 1.f, 1.f, dk_acc);
+      store_acc<D, 0, D / 64>(dv_acc, 1.f, a.dV + koff);
+      store_acc<D, 0, D / 64>(dk_acc, a.scale, a.dK + koff);
+    } else {
+      merge_half<D, 1>(area, own, 1.f, 1.f, dk_acc);
+      store_acc<D, D / 64, D / 64>(dv_acc, 1.f, a.dV + koff);
+      store_acc<D, D / 64, D / 64>(dk_acc, a.scale, a.dK + koff);
     }
   };
   walk_rows(rows, row_begin, issue, comp, row_end);
