@@ -249,6 +249,26 @@ __device__ __forceinline__ void merge_half(const float* area, int own, float min
       acc[kC0 + ct][v] = acc[kC0 + ct][v] * mine + p[(16 * ct + v) * 64] * theirs;
 }
 
+// One-sided variant (the wavefront with part 1 hands over all its tiles, part 0 finishes them),
+// area layout [own][register][lane]: used where the symmetric exchange does not fit the
+// register budget.
+template <int D>
+__device__ __forceinline__ void put_all(float* area, int own, const f32x16 (&acc)[D / 32]) {
+  float* p = area + own * (D / 2) * 64 + threadIdx.x % kWave;
+#pragma unroll
+  for (int ct = 0; ct < D / 32; ++ct)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) p[(16 * ct + v) * 64] = acc[ct][v];
+}
+template <int D>
+__device__ __forceinline__ void merge_all(const float* area, int own, f32x16 (&acc)[D / 32]) {
+  const float* p = area + own * (D / 2) * 64 + threadIdx.x % kWave;
+#pragma unroll
+  for (int ct = 0; ct < D / 32; ++ct)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[ct][v] += p[(16 * ct + v) * 64];
+}
+
 // ---------------------------------------------------------------------------
 // rows of a workgroup and the walk over their blocks
 // ---------------------------------------------------------------------------
@@ -350,9 +370,14 @@ struct RowSet {
 // computed, and the list entry after that one is fetched at the same time.  A wave first waits
 // for its own transfers (vmcnt), the barrier then makes the whole stage visible and retires the
 // reads of the stage about to be refilled.  All control flow is workgroup-uniform.
-template <class RowBegin, class Issue, class Comp, class RowEnd>
-__device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin, Issue issue,
-                                          Comp comp, RowEnd row_end) {
+// With OWN_PF the per-row state comes from tiles that prefetch(k) transfers into an LDS area of
+// the kernel's own (one row ahead: right after the barrier that follows row_begin of the
+// current row, when no wavefront reads the area any more), so row_begin reads LDS instead of
+// waiting for global memory at every row; a row of a single block, whose successor's tiles were
+// requested in the same step, waits for them before it hands over.
+template <bool OWN_PF, class RowBegin, class Prefetch, class Issue, class Comp, class RowEnd>
+__device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin, Prefetch prefetch,
+                                          Issue issue, Comp comp, RowEnd row_end) {
   int ki = rows.next_row(0), iti = 0;
   if (ki >= kRMax) return;
   int ni = rows.n(ki);                 // length of the list the issue side is in
@@ -368,18 +393,38 @@ __device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin
     if (ki < kRMax) coli = rows.col(ki, iti);
   };
   advance();
+  if (OWN_PF) {
+    prefetch(kc);
+    wait_vmcnt<0>();
+    lds_barrier();
+  }
   row_begin(kc);
+  bool want_pf = OWN_PF;               // the row after kc still has to be requested
+  int t_pf = -1;                       // step in which the last request was made
   for (int t = 0;; ++t) {
     wait_vmcnt<0>();
     lds_barrier();
     const bool more = ki < kRMax;
+    if (OWN_PF && want_pf) {
+      const int kn = rows.next_row(kc + 1);
+      if (kn < kRMax) {
+        prefetch(kn);
+        t_pf = t;
+      }
+      want_pf = false;
+    }
     if (more) issue((t + 1) & 1, coli);
     comp(t & 1, colc);
     const bool last = itc + 1 == nc;
     if (last) row_end(kc, t & 1);
     if (!more) break;
     if (last) {
+      if (OWN_PF && t_pf == t) {
+        wait_vmcnt<0>();
+        lds_barrier();
+      }
       row_begin(ki);
+      want_pf = OWN_PF;
       nc = ni;
     }
     kc = ki;
@@ -523,7 +568,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
       store_acc<D, D / 64, D / 64>(o_acc, 1.f, a.Out + qoff);
     }
   };
-  walk_rows(rows, row_begin, issue, comp, row_end);
+  walk_rows<false>(rows, row_begin, [](int) {}, issue, comp, row_end);
 }
 
 // ---------------------------------------------------------------------------
@@ -532,6 +577,10 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
 template <int D>
 __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
+  // Q and dO tiles of a row, brought in one row ahead (head size 64 only: with 128 the area would
+  // halve the number of resident workgroups)
+  constexpr bool kOwnPf = D == 64;
+  __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t ownt[kOwnPf ? 2 : 1][kOwnPf ? 64 * D : 8];
   __shared__ int rowtab[3 * kRMax];
   const int nqb = a.S / 64;
   const int h = blockIdx.x, b = blockIdx.y;
@@ -540,7 +589,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   const int ql = 32 * own + lane % 32, h2 = lane / 32;
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long stat_base = ((long long)b * a.Hh + h) * a.S;
-  const uint32_t st_addr = lds_addr(&st[0][0]);
+  const uint32_t st_addr = lds_addr(&st[0][0]), own_addr = lds_addr(&ownt[0][0]);
+  const uint32_t own_off = tile_off<D>(ql, 8 * h2);   // this lane's fragments inside an own tile
 
   RowSet rows;
   rows.init(rowtab, a.row_ptr, a.col_idx, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
@@ -570,15 +620,31 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   float delta = 0.f, lse2 = 0.f;
   f32x16 dq_acc[D / 32];
 
+  // the row's Q and dO tiles have been brought into LDS (prefetch below) or are read from
+  // global memory; O is only needed for Delta and always comes straight from global memory
+  // (computing Delta for all rows of the workgroup up front was measured slower)
   auto row_begin = [&](int k) {
     qb = rows.blk(k);
     qoff = base + (long long)(qb * 64 + ql) * a.ss;
+    uint4 ofr[D / 16];
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+      ofr[s] = *reinterpret_cast<const uint4*>(a.O + qoff + 16 * s + 8 * h2);
+    lse2 = a.LSEin[stat_base + qb * 64 + ql] * kLog2e;
     float sum = 0.f;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
-      qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
-      dof[s] = *reinterpret_cast<const uint4*>(a.dO + qoff + 16 * s + 8 * h2);
-      const uint4 of = *reinterpret_cast<const uint4*>(a.O + qoff + 16 * s + 8 * h2);
+      if (kOwnPf) {
+        qf[s] = lds_read16((own_addr | own_off) ^ tile_off<D>(0, 16 * s));
+        dof[s] = lds_read16((own_addr + 2 * 64 * D) | (own_off ^ tile_off<D>(0, 16 * s)));
+      } else {
+        qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
+        dof[s] = *reinterpret_cast<const uint4*>(a.dO + qoff + 16 * s + 8 * h2);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+      const uint4 of = ofr[s];
       const uint32_t x[4] = {dof[s].x, dof[s].y, dof[s].z, dof[s].w};
       const uint32_t y[4] = {of.x, of.y, of.z, of.w};
 #pragma unroll
@@ -586,12 +652,16 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
         sum += bf2f(x[e] & 0xFFFFu) * bf2f(y[e] & 0xFFFFu) + bf2f(x[e] >> 16) * bf2f(y[e] >> 16);
     }
     delta = sum + __shfl_xor(sum, 32);
-    lse2 = a.LSEin[stat_base + qb * 64 + ql] * kLog2e;
     if (part == 0 && h2 == 0) {        // for the key-side kernel: Delta and -LSE in log2 units
       a.Delta[stat_base + qb * 64 + ql] = delta;
       a.NegLse2[stat_base + qb * 64 + ql] = -lse2;
     }
     zero(dq_acc);
+  };
+  auto prefetch = [&](int k) {
+    const long long t0 = base + (long long)rows.blk(k) * 64 * a.ss;
+    dma.issue(own_addr, a.Q + t0);
+    dma.issue(own_addr + 2 * 64 * D, a.dO + t0);
   };
   auto issue = [&](int stage, int col) {
     const long long t0 = base + (long long)col * 64 * a.ss;
@@ -633,7 +703,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
       store_acc<D, D / 64, D / 64>(dq_acc, a.scale, a.dQ + qoff);
     }
   };
-  walk_rows(rows, row_begin, issue, comp, row_end);
+  walk_rows<kOwnPf>(rows, row_begin, prefetch, issue, comp, row_end);
 }
 
 // ---------------------------------------------------------------------------
@@ -642,6 +712,10 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
 template <int D>
 __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: Q tile, dO tile
+  // K and V tiles of a row, brought in one row ahead (head size 64 only: with 128 the kernel is
+  // at its register limit and the extra addressing spills)
+  constexpr bool kOwnPf = D == 64;
+  __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t ownt[kOwnPf ? 2 : 1][kOwnPf ? 64 * D : 8];
   __shared__ __attribute__((aligned(256))) float sstat[2][128];   // stage: -LSE*log2e [64], Delta [64]
   __shared__ int rowtab[3 * kRMax];
   const int nkb = a.S / 64;
@@ -652,6 +726,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   const long long base = (long long)b * a.sb + (long long)h * a.sh;
   const long long stat_base = ((long long)b * a.Hh + h) * a.S;
   const uint32_t st_addr = lds_addr(&st[0][0]), sstat_addr = lds_addr(&sstat[0][0]);
+  const uint32_t own_addr = lds_addr(&ownt[0][0]);
+  const uint32_t own_off = tile_off<D>(kl, 8 * h2);   // this lane's fragments inside an own tile
 
   RowSet rows;
   rows.init(rowtab, a.crow_ptr, a.ccol_idx, a.cnnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
@@ -679,16 +755,26 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   uint4 kf[D / 16], vf[D / 16];
   f32x16 dk_acc[D / 32], dv_acc[D / 32];
 
-  auto row_begin = [&](int k) {
+  auto row_begin = [&](int k) {       // the row's K and V tiles are in LDS (prefetch below) or read directly
     kb = rows.blk(k);
     koff = base + (long long)(kb * 64 + kl) * a.ss;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
-      kf[s] = *reinterpret_cast<const uint4*>(a.K + koff + 16 * s + 8 * h2);
-      vf[s] = *reinterpret_cast<const uint4*>(a.V + koff + 16 * s + 8 * h2);
+      if (kOwnPf) {
+        kf[s] = lds_read16((own_addr | own_off) ^ tile_off<D>(0, 16 * s));
+        vf[s] = lds_read16((own_addr + 2 * 64 * D) | (own_off ^ tile_off<D>(0, 16 * s)));
+      } else {
+        kf[s] = *reinterpret_cast<const uint4*>(a.K + koff + 16 * s + 8 * h2);
+        vf[s] = *reinterpret_cast<const uint4*>(a.V + koff + 16 * s + 8 * h2);
+      }
     }
     zero(dk_acc);
     zero(dv_acc);
+  };
+  auto prefetch = [&](int k) {
+    const long long t0 = base + (long long)rows.blk(k) * 64 * a.ss;
+    dma.issue(own_addr, a.K + t0);
+    dma.issue(own_addr + 2 * 64 * D, a.V + t0);
   };
   auto issue = [&](int stage, int qb) {
     const long long t0 = base + (long long)qb * 64 * a.ss;
@@ -734,6 +820,21 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   // same LDS area
   auto row_end = [&](int, int stage) {
     float* area = reinterpret_cast<float*>(st[stage]);
+    if (D == 128) {      // 254 registers without it: the symmetric exchange would spill
+      lds_barrier();
+      if (part == 1) put_all<D>(area, own, dv_acc);
+      lds_barrier();
+      if (part == 0) merge_all<D>(area, own, dv_acc);
+      lds_barrier();
+      if (part == 1) put_all<D>(area, own, dk_acc);
+      lds_barrier();
+      if (part == 0) {
+        merge_all<D>(area, own, dk_acc);
+        store_acc<D>(dv_acc, 1.f, a.dV + koff);
+        store_acc<D>(dk_acc, a.scale, a.dK + koff);
+      }
+      return;
+    }
     lds_barrier();
     if (part == 0)
       put_half<D, 0>(area, own, dv_acc);
@@ -760,7 +861,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
       store_acc<D, D / 64, D / 64>(dk_acc, a.scale, a.dK + koff);
     }
   };
-  walk_rows(rows, row_begin, issue, comp, row_end);
+  walk_rows<kOwnPf>(rows, row_begin, prefetch, issue, comp, row_end);
 }
 
 // Rows per workgroup: the smallest count with which all workgroups of the launch are resident at
