@@ -7,16 +7,22 @@ forward + backward.  Inputs (activations, frozen weights, dense byte masks) are
 resident in HBM before the timed region; the frozen weights are repacked once,
 outside it.
 
-Workloads (see the design doc for the recipes):
+Workloads (recipes in paper_2510_15964_amd/inputs.py):
   opt1.3b_layer   default.  An OPT-1.3B-shaped layer over 8 x 1024 tokens:
                   attention = configs[2] (30 % of causal blocks), FFN =
                   configs[1] (planted ReLU support, ~10 % blocks) applied to the
                   8192 tokens as two X[4096,2048] calls that share the weights.
+  opt1.3b_layer_shared    the same layer with the FFN masks predicted on the
+                  device every step (MLP predictor, one list for all tokens of
+                  a call: the paper's operating point, Sec. V-A).
+  opt1.3b_layer_patterns  the same layer with per-head attention patterns from
+                  a pool, combined into the block lists on the device every
+                  step (Sec. VI-A).
   config4         OPT-6.7B-shaped layer (configs[3]).
   config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]).
 
-Prints ONE JSON line.  `--sweep` additionally runs the configs[4] density sweep
-and writes one line per density to gpurun_out/sweep.jsonl.
+Prints ONE JSON line.  `--sweep FILE` additionally runs the configs[4] density
+sweep and writes one JSON line per density to FILE.
 """
 from __future__ import annotations
 
@@ -192,7 +198,7 @@ class AttnJob:
 
 
 # ----------------------------------------------------------------------------
-# algorithmic work per kernel launch (what the method must do; DESIGN.md)
+# algorithmic work per kernel launch (what the method must do)
 # ----------------------------------------------------------------------------
 
 def measured_traffic(workload: str, kernel: str):
@@ -401,12 +407,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="opt1.3b_layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also run the configs[4] density sweep into gpurun_out/sweep.jsonl")
+    ap.add_argument("--sweep", metavar="FILE", default=None,
+                    help="also run the configs[4] density sweep, one JSON line per density into FILE")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build is single-GPU; run with --gpus 1 "
-                         "(the path shards without communication, see DESIGN.md)")
+                         "(token tiles and (batch, head) pairs are independent: the path "
+                         "shards without communication)")
     if not os.path.exists(os.path.join(ROOT, "paper_2510_15964_amd", "liblx_sparse.so")):
         import __graft_entry__
         __graft_entry__.build()
@@ -415,8 +422,8 @@ def main():
     res = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
     if args.sweep:
         from paper_2510_15964_amd.inputs import DENSITY_SWEEP
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "sweep.jsonl"), "w") as fh:
+        os.makedirs(os.path.dirname(os.path.abspath(args.sweep)), exist_ok=True)
+        with open(args.sweep, "w") as fh:
             for rho in DENSITY_SWEEP:
                 r = run(f"config5:{rho}", max(args.steps // 5, 5), 2, False)
                 log(f"config5 rho={rho}: {r['ms_per_step']:.3f} ms/step, "
