@@ -25,8 +25,20 @@ struct CompactJobs {
   CompactJob j[kMaxJobs];
 };
 
-// One workgroup per job (blockIdx.x): a launch builds one list, the row list and the column
-// list of the same masks, or the lists of several independent masks side by side.
+// Workgroups (blockIdx.x = job, blockIdx.y = part of the job's rows): a launch builds one list,
+// the row list and the column list of the same masks, or the lists of several independent masks
+// side by side.  A mask of more than kSplitBytes is divided by rows among up to kMaxSplit
+// workgroups; a workgroup that does not start at row 0 first counts the active entries of all
+// rows before its own (a plain count over bytes it would otherwise wait for another workgroup to
+// scan), so the parts need no communication.
+constexpr int kSplitBytes = 4096, kMaxSplit = 16;
+__host__ __device__ inline int compact_parts(long long total_rows, int cols) {
+  long long p = (total_rows * cols + kSplitBytes - 1) / kSplitBytes;
+  if (p > kMaxSplit) p = kMaxSplit;
+  if (p > total_rows) p = total_rows;
+  return p < 1 ? 1 : (int)p;
+}
+
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJobs jobs) {
   const CompactJob& job = jobs.j[blockIdx.x];
   const uint8_t* __restrict__ mask = job.mask;
@@ -39,6 +51,10 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   __shared__ uint8_t stage[kStageBytes];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int total_rows = batch * rows;
+  const int parts = compact_parts(total_rows, cols), part = blockIdx.y;
+  if (part >= parts) return;
+  const int per_part = (total_rows + parts - 1) / parts;
+  const int row_lo = min(part * per_part, total_rows), row_hi = min(row_lo + per_part, total_rows);
   const bool staged = cols <= kStageBytes;
   const int chunk_rows = staged ? max(1, min(kChunkRows, kStageBytes / cols)) : 1;
   int cp = kWave;                       // columns handled per wave pass (power of two)
@@ -47,8 +63,35 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   const int sub = lane / cp, cl = lane % cp;
   const unsigned long long field = cp == 64 ? ~0ull : ((1ull << cp) - 1ull);
   int carry = 0;
-  for (int chunk = 0; chunk < total_rows; chunk += chunk_rows) {
-    const int n = min(chunk_rows, total_rows - chunk);
+  if (row_lo > 0) {      // active entries of the rows before this part
+    const long long before = (long long)row_lo * cols;
+    int cnt = 0;
+    constexpr int kBatch = 8;
+    for (long long i0 = tid; i0 < before; i0 += (long long)kCompactThreads * kBatch) {
+      uint8_t v[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const long long idx = i0 + (long long)u * kCompactThreads;
+        v[u] = 0;
+        if (idx < before) {
+          const int gr = (int)(idx / cols), c = (int)(idx - (long long)gr * cols);
+          v[u] = mask[(long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride +
+                      (long long)c * cstride];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) cnt += v[u] != 0;
+    }
+#pragma unroll
+    for (int dlt = 32; dlt > 0; dlt >>= 1) cnt += __shfl_xor(cnt, dlt);
+    if (lane == 0) wave_tot[wave] = cnt;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kCompactWaves; ++w) carry += wave_tot[w];
+    __syncthreads();
+  }
+  for (int chunk = row_lo; chunk < row_hi; chunk += chunk_rows) {
+    const int n = min(chunk_rows, row_hi - chunk);
     if (staged) {
       for (int idx = tid; idx < n * cols; idx += kCompactThreads) {
         const int r = idx / cols, c = idx - r * cols, gr = chunk + r;
@@ -127,14 +170,19 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
     carry += chunk_total;
     __syncthreads();
   }
-  if (tid == 0) row_ptr[total_rows] = carry;
+  if (part == parts - 1 && tid == 0) row_ptr[total_rows] = carry;
 }
 
 hipError_t launch_compact_jobs(const CompactJob* jobs, int n, hipStream_t stream) {
   CompactJobs js = {};
-  for (int i = 0; i < n; ++i) js.j[i] = jobs[i];
+  int parts = 1;
+  for (int i = 0; i < n; ++i) {
+    js.j[i] = jobs[i];
+    const int p = compact_parts((long long)jobs[i].batch * jobs[i].rows, jobs[i].cols);
+    parts = p > parts ? p : parts;
+  }
   ProfScope ps(kKCompact, stream);
-  hipLaunchKernelGGL(compact_kernel, dim3(n), dim3(kCompactThreads), 0, stream, js);
+  hipLaunchKernelGGL(compact_kernel, dim3(n, parts), dim3(kCompactThreads), 0, stream, js);
   return hipGetLastError();
 }
 
