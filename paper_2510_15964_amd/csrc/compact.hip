@@ -2,8 +2,9 @@
 // neuron-block index list of Sec. VI-B).
 //
 // The masks of one layer are tiny (tens of thousands of bytes), so the whole
-// job is latency-bound: one 1024-thread workgroup does count -> scan -> scatter
-// in a single launch with no host round trip.  One wavefront owns a mask row at
+// job is latency-bound: a 1024-thread workgroup does count -> scan -> scatter
+// for a list (or for a part of its rows) in a single launch with no host
+// round trip.  One wavefront owns a mask row at
 // a time: a 64-wide ballot gives the row's bit pattern, popcount its total and
 // mbcnt the rank of every set lane, so columns come out ascending.
 #include "lx_dev.h"
