@@ -208,3 +208,22 @@ def test_list_longer_than_its_capacity_is_truncated(lx):
     a, b = run(mask), run(trunc)
     assert np.isfinite(a[0]).all()
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("r", [0, 1, 8])
+def test_rows_of_one_and_two_blocks(lx, oracle, r):
+    """Every row of the mask lists one block (the diagonal) or two (diagonal and the block
+    before): the shortest rows there are, where a row hands over to the next one in the very step
+    in which the next row's own tiles were requested."""
+    for width in (1, 2):
+        c = inputs.attn_blocks(2, 3, 512, 64, 1.0, seed=40 + width, dtype="bf16")
+        nb = 512 // 64
+        q, k = np.arange(nb)[:, None], np.arange(nb)[None, :]
+        c["mask"] = np.broadcast_to(((q - k >= 0) & (q - k < width)).astype(np.uint8),
+                                    c["mask"].shape).copy()
+        lx.lx_attn_set_rows_per_workgroup(r)
+        try:
+            got = run_gpu(lx, c)
+        finally:
+            lx.lx_attn_set_rows_per_workgroup(0)
+        check(got, run_oracle(oracle, c), f"band of {width}, rows per workgroup {r}")
