@@ -435,6 +435,78 @@ __global__ __launch_bounds__(kThreads) void predict_bf16(
   }
 }
 
+// Finer variant for so few neuron blocks that even one group of 64 rows of Wa_t per workgroup
+// leaves CUs idle: a workgroup takes 32 rows of Wa_t, and a step covers two 64-wide chunks of K
+// (64 + 64 token-rows and 32 + 32 rows of Wa_t per stage: three DMA instructions per wave).  The
+// 2 x 8 products of a step (token half x k16 slice) are dealt to the eight wavefronts, which sum
+// over disjoint parts of K; the four partial sums of a token half are added in a fixed order
+// through LDS before the threshold.  Requires K % 128 == 0.
+__global__ __launch_bounds__(kThreads) void predict_half_bf16(
+    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wa_t, int tiles, int K, int nblk,
+    int tiles_per_group, float thr, uint8_t* __restrict__ mask) {
+  constexpr int kSE = 192 * kBK, kNIss = 3, kNSt = 6;
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[kNSt * kSE];
+  const int nchunk = nblk / 32, slot = blockIdx.x / 8;
+  const int i = (slot / nchunk) * 8 + blockIdx.x % 8;   // token tile; its workgroups share an XCD
+  const int r0 = (slot % nchunk) * 32;                  // first row of Wa_t
+  if (i >= tiles) return;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const uint16_t* src[kNIss];
+#pragma unroll
+  for (int u = 0; u < kNIss; ++u) {
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;   // stage row 0 .. 191
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 2) {
+      src[u] = X + ((long long)i * 64 + row - 64 * u) * K + 64 * u + seg * 8;
+    } else {
+      const int wr = row - 128;                              // 0 .. 63: chunk wr / 32, row wr % 32
+      src[u] = Wa_t + ((long long)r0 + wr % 32) * K + 64 * (wr / 32) + seg * 8;
+    }
+  }
+  const int ti = wave % 2, chunk = (wave / 2) % 2, kh = wave / 4;
+  const int r = lane % 32, h2 = lane / 32;
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  run_ring_of<kNSt, kNIss, kSE>(
+      K / (2 * kBK), src,
+      [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * (2 * kBK); }, ring,
+      [&](const uint16_t* stage) {
+        uint4 a[2], b[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int seg = 2 * (2 * kh + e) + h2;
+          const int ra = 128 + 32 * chunk + r, rb = 64 * chunk + 32 * ti + r;
+          a[e] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+          b[e] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) acc = mfma32(a[e], b[e], acc);
+      });
+  // partial sums of wavefronts 2 .. 7 -> LDS; wavefronts 0, 1 add those of their token half
+  float* red = reinterpret_cast<float*>(ring);
+  lds_barrier();
+  if (wave >= 2) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * kWave + lane] = acc[v];
+  }
+  lds_barrier();
+  if (wave >= 2) return;
+#pragma unroll
+  for (int p = 1; p < 4; ++p)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] += red[((wave + 2 * p) * 16 + v) * kWave + lane];
+  uint8_t* out = mask + (long long)(i / tiles_per_group) * nblk + r0;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    // register v of a lane: row 8*(v/4) + 4*(lane/32) + v%4 of the 32, token 32*ti + lane%32
+    const unsigned long long hit = __ballot(acc[v] > thr);
+    const int n = 8 * (v / 4) + v % 4;
+    if (lane == 0 && (uint32_t)hit != 0u) out[n] = 1;
+    if (lane == 32 && (hit >> 32) != 0ull) out[n + 4] = 1;
+  }
+}
+
 __global__ void zero_bytes_kernel(uint8_t* __restrict__ p, int n) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < n) p[idx] = 0;
@@ -455,6 +527,9 @@ hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, cons
                        nblk, tiles_per_group, thr, mask);
   else if (ng % 2 == 0 && (long long)ng / 2 * Tt >= kCUs)
     hipLaunchKernelGGL(predict_bf16<2>, dim3(ng / 2 * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
+                       nblk, tiles_per_group, thr, mask);
+  else if ((long long)ng * Tt < kCUs && d % 128 == 0)
+    hipLaunchKernelGGL(predict_half_bf16, dim3(2 * ng * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
                        nblk, tiles_per_group, thr, mask);
   else
     hipLaunchKernelGGL(predict_bf16<1>, dim3(ng * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d, nblk,
