@@ -124,6 +124,97 @@ void lxo_ffn_bwd_dx(int32_t T, int32_t d, int32_t F, int32_t tile_t,
 }
 
 // ---------------------------------------------------------------------------
+// Masked FFN with a LoRA branch on the up-projection (Sec. II-C: z = W x + B A x,
+// a = sigma(z); Sec. II-D: the gradients of the trainable A and B, and the rule
+// that a neuron which is inactive in the forward pass takes no part in the
+// backward pass).  A [r,d], B [F,r].
+//   U[t,q] = sum_k X[t,k] A[q,k]
+//   Z[t,f] = sum_k X[t,k] W_up[f,k] + sum_q U[t,q] B[f,q]     where M
+//   H = M ? max(Z,0) : 0;   Y[t,n] = sum_f H[t,f] W_down[n,f]
+// Outputs: U [T,r], H [T,F], Y [T,d] in fp64.
+// ---------------------------------------------------------------------------
+void lxo_ffn_lora_fwd(int32_t T, int32_t d, int32_t F, int32_t r, int32_t tile_t, int32_t blk_n,
+                      const float* X, const float* W_up, const float* A, const float* B,
+                      const float* W_down, const uint8_t* M, double* U, double* H, double* Y) {
+  const int32_t Fb = F / blk_n;
+  for (int32_t t = 0; t < T; ++t) {
+    const uint8_t* Mrow = M + (int64_t)(t / tile_t) * Fb;
+    for (int32_t q = 0; q < r; ++q) {
+      double u = 0.0;
+      for (int32_t k = 0; k < d; ++k) u += (double)X[(int64_t)t * d + k] * (double)A[(int64_t)q * d + k];
+      U[(int64_t)t * r + q] = u;
+    }
+    for (int32_t f = 0; f < F; ++f) {
+      double h = 0.0;
+      if (Mrow[f / blk_n]) {
+        double z = 0.0;
+        for (int32_t k = 0; k < d; ++k)
+          z += (double)X[(int64_t)t * d + k] * (double)W_up[(int64_t)f * d + k];
+        for (int32_t q = 0; q < r; ++q) z += U[(int64_t)t * r + q] * (double)B[(int64_t)f * r + q];
+        h = z > 0.0 ? z : 0.0;
+      }
+      H[(int64_t)t * F + f] = h;
+    }
+    for (int32_t n = 0; n < d; ++n) {
+      double y = 0.0;
+      for (int32_t f = 0; f < F; ++f) {
+        if (!Mrow[f / blk_n]) continue;
+        y += H[(int64_t)t * F + f] * (double)W_down[(int64_t)n * F + f];
+      }
+      Y[(int64_t)t * d + n] = y;
+    }
+  }
+}
+
+// Backward of the above for the input and the trainable matrices.  Uin [T,r] is
+// the forward's U as stored (the caller may have rounded it to the run dtype),
+// act [T,F] the activation map [Z > 0].
+//   dZ[t,f] = (M and act) ? sum_n dY[t,n] W_down[n,f] : 0
+//   G[t,q]  = sum_f dZ[t,f] B[f,q]
+//   dX[t,k] = sum_f dZ[t,f] W_up[f,k] + sum_q G[t,q] A[q,k]
+//   dB[f,q] = sum_t dZ[t,f] Uin[t,q]        dA[q,k] = sum_t G[t,q] X[t,k]
+// Outputs in fp64: dZ [T,F], G [T,r], dX [T,d], dA [r,d], dB [F,r].
+void lxo_ffn_lora_bwd(int32_t T, int32_t d, int32_t F, int32_t r, int32_t tile_t, int32_t blk_n,
+                      const float* X, const float* dY, const float* W_up, const float* A,
+                      const float* B, const float* W_down, const uint8_t* M, const uint8_t* act,
+                      const double* Uin, double* dZ, double* G, double* dX, double* dA,
+                      double* dB) {
+  const int32_t Fb = F / blk_n;
+  for (int64_t i = 0; i < (int64_t)r * d; ++i) dA[i] = 0.0;
+  for (int64_t i = 0; i < (int64_t)F * r; ++i) dB[i] = 0.0;
+  for (int32_t t = 0; t < T; ++t) {
+    const uint8_t* Mrow = M + (int64_t)(t / tile_t) * Fb;
+    for (int32_t f = 0; f < F; ++f) {
+      double g = 0.0;
+      if (Mrow[f / blk_n] && act[(int64_t)t * F + f]) {
+        for (int32_t n = 0; n < d; ++n)
+          g += (double)dY[(int64_t)t * d + n] * (double)W_down[(int64_t)n * F + f];
+      }
+      dZ[(int64_t)t * F + f] = g;
+    }
+    for (int32_t q = 0; q < r; ++q) {
+      double g = 0.0;
+      for (int32_t f = 0; f < F; ++f) g += dZ[(int64_t)t * F + f] * (double)B[(int64_t)f * r + q];
+      G[(int64_t)t * r + q] = g;
+    }
+    for (int32_t k = 0; k < d; ++k) {
+      double x = 0.0;
+      for (int32_t f = 0; f < F; ++f) x += dZ[(int64_t)t * F + f] * (double)W_up[(int64_t)f * d + k];
+      for (int32_t q = 0; q < r; ++q) x += G[(int64_t)t * r + q] * (double)A[(int64_t)q * d + k];
+      dX[(int64_t)t * d + k] = x;
+    }
+    for (int32_t f = 0; f < F; ++f) {
+      const double z = dZ[(int64_t)t * F + f];
+      if (z == 0.0) continue;
+      for (int32_t q = 0; q < r; ++q) dB[(int64_t)f * r + q] += z * Uin[(int64_t)t * r + q];
+    }
+    for (int32_t q = 0; q < r; ++q)
+      for (int32_t k = 0; k < d; ++k)
+        dA[(int64_t)q * d + k] += G[(int64_t)t * r + q] * (double)X[(int64_t)t * d + k];
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Block-masked attention forward, written as SDD -> softmax -> DSD (Sec. VI-A).
 // Q,K,V are contiguous [B,Hh,S,D].  Mblk is [mask_batch][Hh][S/blk][S/blk]
 // bytes with mask_batch 1 (shared over the batch, Sec. V-A) or B.

@@ -180,3 +180,50 @@ def combine_patterns(pool, head_pattern):
         C.c_int32(hp.shape[0]), hp.ctypes.data_as(C.POINTER(C.c_int32)),
         out.ctypes.data_as(C.POINTER(C.c_uint8)))
     return out
+
+
+def ffn_lora_fwd(X, W_up, A, B, W_down, mask, tile_t, blk_n):
+    """LoRA branch on the up-projection.  A [r,d], B [F,r].  Returns (U [T,r], H [T,F], Y [T,d])
+    in float64."""
+    T, d = X.shape
+    F, r = B.shape
+    assert W_up.shape == (F, d) and W_down.shape == (d, F) and A.shape == (r, d)
+    assert mask.shape == (T // tile_t, F // blk_n)
+    X, pX = _f32(X)
+    W_up, pU = _f32(W_up)
+    A, pA = _f32(A)
+    B, pB = _f32(B)
+    W_down, pD = _f32(W_down)
+    mask, pM = _u8(mask)
+    U, pu = _f64_out((T, r))
+    H, pH = _f64_out((T, F))
+    Y, pY = _f64_out((T, d))
+    lib().lxo_ffn_lora_fwd(C.c_int32(T), C.c_int32(d), C.c_int32(F), C.c_int32(r), C.c_int32(tile_t),
+                           C.c_int32(blk_n), pX, pU, pA, pB, pD, pM, pu, pH, pY)
+    return U, H, Y
+
+
+def ffn_lora_bwd(X, dY, W_up, A, B, W_down, mask, act, U, tile_t, blk_n):
+    """Returns dict(dZ [T,F], G [T,r], dX [T,d], dA [r,d], dB [F,r]) in float64; U is the stored
+    forward U (float64 array, possibly rounded by the caller), act the map [Z > 0]."""
+    T, d = X.shape
+    F, r = B.shape
+    X, pX = _f32(X)
+    dY, pdY = _f32(dY)
+    W_up, pU = _f32(W_up)
+    A, pA = _f32(A)
+    B, pB = _f32(B)
+    W_down, pD = _f32(W_down)
+    mask, pM = _u8(mask)
+    act, pact = _u8(act)
+    U = np.ascontiguousarray(U, dtype=np.float64)
+    assert act.shape == (T, F) and U.shape == (T, r)
+    dZ, pdZ = _f64_out((T, F))
+    G, pG = _f64_out((T, r))
+    dX, pdX = _f64_out((T, d))
+    dA, pdA = _f64_out((r, d))
+    dB, pdB = _f64_out((F, r))
+    lib().lxo_ffn_lora_bwd(C.c_int32(T), C.c_int32(d), C.c_int32(F), C.c_int32(r), C.c_int32(tile_t),
+                           C.c_int32(blk_n), pX, pdY, pU, pA, pB, pD, pM, pact,
+                           U.ctypes.data_as(C.POINTER(C.c_double)), pdZ, pG, pdX, pdA, pdB)
+    return dict(dZ=dZ, G=G, dX=dX, dA=dA, dB=dB)
