@@ -86,7 +86,8 @@ typedef enum {
   LX_K_ATTN_BWD_DKV = 7, /* dK and dV, key side */
   LX_K_TRANSPOSE = 8,    /* weight repack */
   LX_K_PREDICT = 9,      /* MLP predictor: scores + threshold + OR over the tokens */
-  LX_K_COMBINE = 10      /* per-head pattern layouts -> multi-head block list */
+  LX_K_COMBINE = 10,     /* per-head pattern layouts -> multi-head block list */
+  LX_K_LORA = 11         /* LoRA branch: U = X A^T, G = dZ B, dB, dA (the fused steps run in the FFN kernels) */
 } lx_kernel;
 
 /* Human-readable name of a status code (HOST string, static storage). */
@@ -221,6 +222,44 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
                                const void* W_up, const void* W_down, const void* W_up_t,
                                const void* W_down_t, const lx_blocklist* bl, void* dX,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sparse FFN with a LoRA branch on the up-projection (Sec. II-C: z = W x + B A x,
+ * a = ReLU(z); Sec. II-D: gradients of the trainable matrices, and no part in the
+ * backward pass for what was inactive in the forward pass).  A [r,d] and B [F,r]
+ * are handed over zero-padded to rank 64: A_pad [64,d] (rows r.. zero), B_pad
+ * [F,64] (columns r.. zero); the padding costs nothing in accuracy and its
+ * gradients come out zero.  LX_BF16, 64 x 64 blocks only.
+ *
+ * Forward, for every listed (i, j):
+ *   U = X A_pad^T [T,64];  H_ij = ReLU(X_i W_up_j^T + U_i B_pad_j^T);  Y_i = sum_j H_ij W_down_j^T
+ *   U      out [T,64], needed by the backward call
+ *   H_act  out, compact activations as in lx_sparse_ffn_fwd (required)
+ *   workspace  >= lx_sparse_ffn_lora_fwd_workspace_bytes()
+ * Backward:
+ *   dZ_ij = (dY_i W_down[:, j]) (.) [H_ij > 0];   G = sum_j dZ_ij B_pad_j  [T,64]
+ *   dX_i = sum_j dZ_ij W_up_j + G_i A_pad
+ *   dB[j-th 64 rows] = sum_i dZ_ij^T U_i  (fp32 [F,64]; rows of blocks no tile lists are zero)
+ *   dA = G^T X  (fp32 [64,d])
+ *   W_up_t, W_down_t: outputs of lx_ffn_pack_weights (required here)
+ *   workspace  >= lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, nnz_cap) with
+ *              nnz_cap counted in activation blocks as for lx_sparse_ffn_bwd_workspace_bytes
+ * dA is summed over eight token ranges in a fixed order, dB per block over the
+ * token tiles in ascending order: results are bit-reproducible.
+ */
+size_t lx_sparse_ffn_lora_fwd_workspace_bytes(void);
+size_t lx_sparse_ffn_lora_bwd_workspace_bytes(int32_t T, int32_t d, int32_t F, int32_t nnz_cap);
+lx_status lx_sparse_ffn_lora_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                                 int32_t blk_n, const void* X, const void* W_up, const void* A_pad,
+                                 const void* B_pad, const void* W_down, const lx_blocklist* bl,
+                                 void* Y, void* H_act, void* U, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                                 int32_t blk_n, const void* X, const void* dY, const void* H_act,
+                                 const void* U, const void* W_up_t, const void* W_down_t,
+                                 const void* A_pad, const void* B_pad, const lx_blocklist* bl,
+                                 void* dX, float* dA, float* dB, void* workspace,
+                                 size_t workspace_bytes, void* stream);
 
 /*
  * MLP predictor, inference side (Sec. V-A, "MLP Block"): block scores

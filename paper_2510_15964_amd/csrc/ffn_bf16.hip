@@ -51,13 +51,16 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 // rows, then the weight blocks); lane l brings the 16-byte slot l%8 of row 8g + l/8.  src[u]
 // already points at this lane's (row, swizzled segment); offB / offA are the element offsets of
 // the current K-step for the shared rows and the weight rows.
+// With `alt` (wave-uniform) the pointers of alt_src are used instead: a step whose operands
+// live in other buffers with another row stride (the LoRA branch).
 template <int NISS>
 __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[NISS],
+                                            const uint16_t* const (&alt_src)[NISS], bool alt,
                                             long long offB, long long offA) {
   const uint32_t base = lds_addr(stage) + (threadIdx.x / kWave) * 1024;
 #pragma unroll
   for (int u = 0; u < NISS; ++u)
-    dma16(src[u] + (u < 8 / kFW ? offB : offA), base + u * (kFW * 1024));
+    dma16((alt ? alt_src[u] : src[u]) + (u < 8 / kFW ? offB : offA), base + u * (kFW * 1024));
 }
 
 // One 64-deep K-step from LDS: wave w multiplies its 32*kNI weight rows (row groups kNI*w ..)
@@ -114,14 +117,17 @@ __device__ __forceinline__ void wait_tail(int y) {
 }
 
 // step(stage pointer) is the multiplication of one landed stage; a stage holds SE elements.
+// offs(s, offB, offA) yields the element offsets of step s and returns whether the step takes
+// its operands from alt_src.
 template <int NST, int NISS, int SE, class Offs, class Step>
-__device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&src)[NISS], Offs offs,
+__device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&src)[NISS],
+                                            const uint16_t* const (&alt_src)[NISS], Offs offs,
                                             uint16_t* ring, Step step) {
   static_assert(NST >= 2 && NISS * (NST - 2) < 64, "ring depth");
   long long ob, oa;
   auto issue = [&](int s, int stage) {
-    offs(s, ob, oa);
-    issue_stage<NISS>(ring + stage * SE, src, ob, oa);
+    const bool alt = offs(s, ob, oa);
+    issue_stage<NISS>(ring + stage * SE, src, alt_src, alt, ob, oa);
   };
 #pragma unroll
   for (int p = 0; p < NST - 1; ++p)
@@ -142,12 +148,14 @@ __device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&
 
 template <int NST, class Offs>
 __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
-                                         const uint16_t* const (&src)[kIssues], Offs offs,
+                                         const uint16_t* const (&src)[kIssues],
+                                         const uint16_t* const (&alt_src)[kIssues], Offs offs,
                                          uint16_t* ring, f32x16 (&acc)[kNI][2]) {
   const int wave = threadIdx.x / kWave;
-  run_ring_of<NST, kIssues, kStageElems>(nsteps, src, offs, ring, [&](const uint16_t* stage) {
-    if (wave_on) mma_step(stage, wave, acc);
-  });
+  run_ring_of<NST, kIssues, kStageElems>(nsteps, src, alt_src, offs, ring,
+                                         [&](const uint16_t* stage) {
+                                           if (wave_on) mma_step(stage, wave, acc);
+                                         });
 }
 
 // Work items of the sdd kernel are (token tile, group of `per` consecutive list entries),
@@ -213,13 +221,19 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[kNI][2]) {
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 }
 
-// MODE 0: out = bf16(max(acc + bias, 0));  MODE 1: out = gate > 0 ? bf16(acc) : 0.
-template <int MODE>
+// MODE 0: out = bf16(max(acc + bias, 0));  MODE 1: out = gate > 0 ? bf16(acc) : 0;
+// MODE 2: out = bf16(acc).
+// LORA: one more 64-deep step after the K loop with the operands A2 [T,64] (rows of the token
+// tile) and W2 [F,64] (rows of the listed blocks): acc += A2_i W2_j^T, the low-rank branch
+// z = W x + B (A x) of Sec. II-C with A2 = X A^T computed beforehand and W2 = B, both padded to
+// rank 64.
+template <int MODE, bool LORA>
 __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int rows, int gt, int K, int nnz_cap,
-    uint16_t* __restrict__ out_act, const uint16_t* __restrict__ gate_act) {
+    uint16_t* __restrict__ out_act, const uint16_t* __restrict__ gate_act,
+    const uint16_t* __restrict__ A2, const uint16_t* __restrict__ W2) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
   int i, chunk;
   if (!find_work(row_ptr, rows, gt, blockIdx.x, 4, i, chunk)) return;
@@ -232,24 +246,32 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
 
   // per-instruction source pointers of this lane (K offset added per step)
   const uint16_t* src[kIssues];
+  const uint16_t* src2[kIssues];             // the same for the low-rank step
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
     if (u < 8 / kFW) {
       src[u] = A + ((long long)i * 64 + row) * K + seg * 8;
+      src2[u] = LORA ? A2 + ((long long)i * 64 + row) * 64 + seg * 8 : src[u];
     } else {
       const int blk = g / 8 - 1, r = row - kRowsB - 64 * blk;
       // blocks past the end of the list are filled from the first block (never used)
       const int j = col_idx[p0 + (blk < nb ? blk : 0)];
       src[u] = W + ((long long)j * 64 + r) * K + seg * 8;
+      src2[u] = LORA ? W2 + ((long long)j * 64 + r) * 64 + seg * 8 : src[u];
     }
   }
   f32x16 acc[kNI][2];
   zero_acc(acc);
   const int blk_w = kNI * wave / 2;          // list entry (of the four) this wave works on
-  run_ring<kSddStages>(K / kBK, blk_w < nb, src,
-                       [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; },
+  const int ksteps = K / kBK;
+  run_ring<kSddStages>(ksteps + (LORA ? 1 : 0), blk_w < nb, src, src2,
+                       [=](int s, long long& ob, long long& oa) {
+                         const bool alt = LORA && s == ksteps;
+                         ob = oa = alt ? 0 : (long long)s * kBK;
+                         return alt;
+                       },
                        ring, acc);
   if (blk_w >= nb) return;
 
@@ -270,7 +292,8 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
-        if (MODE == 0) {
+        if (MODE == 2) {
+        } else if (MODE == 0) {
           if (bias) {
             const uint2 bb = *reinterpret_cast<const uint2*>(bias + j * 64 + n);
             v[0] += bf2f(bb.x & 0xFFFFu); v[1] += bf2f(bb.x >> 16);
@@ -294,11 +317,15 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
 }
 
 // out[i-tile rows, n0 .. n0+255] = sum_s act[p_s] [64 x 64] . W[n0.., j_s*64 ..]^T (+ bias)
+// LORA: one more step with the operands act2 [T,64] (the token tile's 64 x 64 block) and
+// W2 [ncols_out, 64]: out += act2_i W2[n0..]^T, the low-rank part (dZ B) A of the input gradient.
+template <bool LORA>
 __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
-    uint16_t* __restrict__ out) {
+    uint16_t* __restrict__ out, const uint16_t* __restrict__ act2,
+    const uint16_t* __restrict__ W2) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kDsdStages * kStageElems];
   const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i / gt];
@@ -307,23 +334,29 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   const bool wave_on = n0 + 32 * kNI * wave < ncols_out;
 
   const uint16_t* src[kIssues];
+  const uint16_t* src2[kIssues];
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
     if (u < 8 / kFW) {
       src[u] = act + row * 64 + seg * 8;          // inside a compact 64x64 activation block
+      src2[u] = LORA ? act2 + ((long long)i * 64 + row) * 64 + seg * 8 : src[u];
     } else {
       const int n = min(n0 + row - kRowsB, ncols_out - 1);   // rows past the edge: re-read the last
       src[u] = W + (long long)n * ldw + seg * 8;
+      src2[u] = LORA ? W2 + (long long)n * 64 + seg * 8 : src[u];
     }
   }
   f32x16 acc[kNI][2];
   zero_acc(acc);
-  run_ring<kDsdStages>(n_i, wave_on, src,
+  const int lsteps = n_i > 0 ? n_i : 0;
+  run_ring<kDsdStages>(lsteps + (LORA ? 1 : 0), wave_on, src, src2,
                [&](int s, long long& ob, long long& oa) {
-                 ob = ((long long)(rs + s) * gt + i % gt) * 4096;
-                 oa = (long long)col_idx[rs + s] * 64;
+                 const bool alt = LORA && s == lsteps;
+                 ob = alt ? 0 : ((long long)(rs + s) * gt + i % gt) * 4096;
+                 oa = alt ? 0 : (long long)col_idx[rs + s] * 64;
+                 return alt;
                },
                        ring, acc);
   if (!wave_on) return;
@@ -400,7 +433,11 @@ __global__ __launch_bounds__(kThreads) void predict_bf16(
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
   run_ring_of<kNSt, kNIss, kSE>(
-      K / kBK, src, [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * kBK; },
+      K / kBK, src, src,
+      [](int s, long long& ob, long long& oa) {
+        ob = oa = (long long)s * kBK;
+        return false;
+      },
       ring,
       [&](const uint16_t* stage) {
         if (!on) return;
@@ -469,8 +506,12 @@ __global__ __launch_bounds__(kThreads) void predict_half_bf16(
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   run_ring_of<kNSt, kNIss, kSE>(
-      K / (2 * kBK), src,
-      [](int s, long long& ob, long long& oa) { ob = oa = (long long)s * (2 * kBK); }, ring,
+      K / (2 * kBK), src, src,
+      [](int s, long long& ob, long long& oa) {
+        ob = oa = (long long)s * (2 * kBK);
+        return false;
+      },
+      ring,
       [&](const uint16_t* stage) {
         uint4 a[2], b[2];
 #pragma unroll
@@ -540,31 +581,256 @@ hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, cons
 // pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
 // pass 1 (backward): A = dY, W1 = W_down_t [F,d], W2 = W_up_t [d,F], act_out = dZ_act,
 //                    act_gate = H_act, out = dX
+static dim3 sdd_grid(int Tt, int gt, int nnz_cap) {
+  // items <= nnz_cap / 4 + Tt; per XCD L = ceil(items / 8) of them in 8 * ceil(L / 8) slots
+  const long long items = ((long long)nnz_cap * gt + 3) / 4 + Tt;
+  const int Lub = (int)((items + 7) / 8);
+  return dim3(8 * 8 * ((Lub + 7) / 8));
+}
+
 hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st) {
   (void)Fb;
-  // items <= nnz_cap / 4 + Tt; per XCD L = ceil(items / 8) of them in 8 * ceil(L / 8) slots
-  const long long items = ((long long)nnz_cap * gt + 3) / 4 + Tt;
-  if (items > (1ll << 30)) return hipErrorInvalidValue;
-  const int Lub = (int)((items + 7) / 8);
-  const dim3 g1(8 * 8 * ((Lub + 7) / 8));
+  if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
+  const dim3 g1 = sdd_grid(Tt, gt, nnz_cap);
+  const uint16_t* none = nullptr;
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
-      hipLaunchKernelGGL(ffn_sdd_bf16<0>, g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr, col_idx, Tt,
-                         gt, d, nnz_cap, act_out, (const uint16_t*)nullptr);
+      hipLaunchKernelGGL((ffn_sdd_bf16<0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
     else
-      hipLaunchKernelGGL(ffn_sdd_bf16<1>, g1, dim3(kThreads), 0, st, A, W1,
-                         (const uint16_t*)nullptr, row_ptr, col_idx, Tt, gt, d, nnz_cap, act_out, act_gate);
+      hipLaunchKernelGGL((ffn_sdd_bf16<1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
+                         col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
-  hipLaunchKernelGGL(ffn_dsd_bf16, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
-                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap, out);
+  hipLaunchKernelGGL(ffn_dsd_bf16<false>, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap,
+                     out, none, none);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// LoRA branch on the up-projection (Sec. II-C: z = W x + B A x; Sec. II-D: its gradients).
+// A_pad [64, d] and B_pad [F, 64] hold A [r, d] and B [F, r] zero-padded to rank 64.
+// ---------------------------------------------------------------------------
+
+// A list of one row with the single entry 0: with it the sdd kernel multiplies every token
+// tile with the 64 rows of one matrix (U = X A_pad^T).
+__global__ void one_entry_list_kernel(int* __restrict__ list) {
+  if (threadIdx.x == 0) {
+    list[0] = 0;   // row_ptr[0]
+    list[1] = 1;   // row_ptr[1]
+    list[2] = 0;   // col_idx[0]
+  }
+}
+
+// forward: U = X A_pad^T [T,64];  H_act = ReLU(X W_up^T + U B_pad^T) on the listed blocks;
+// Y = H W_down^T.  mini: 3 ints of scratch.
+hipError_t launch_ffn_lora_fwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+                                    const uint16_t* W_up, const uint16_t* A_pad,
+                                    const uint16_t* B_pad, const uint16_t* W_down,
+                                    const int* row_ptr, const int* col_idx, int nnz_cap,
+                                    uint16_t* U, uint16_t* H_act, uint16_t* Y, int* mini,
+                                    hipStream_t st) {
+  if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
+  const uint16_t* none = nullptr;
+  {
+    ProfScope ps(kKLora, st);
+    hipLaunchKernelGGL(one_entry_list_kernel, dim3(1), dim3(64), 0, st, mini);
+    hipLaunchKernelGGL((ffn_sdd_bf16<2, false>), sdd_grid(Tt, Tt, 1), dim3(kThreads), 0, st, X, A_pad,
+                       none, (const int*)mini, (const int*)(mini + 2), Tt, Tt, d, 1, U, none, none, none);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ProfScope ps(kKFfnUp, st);
+    hipLaunchKernelGGL((ffn_sdd_bf16<0, true>), sdd_grid(Tt, gt, nnz_cap), dim3(kThreads), 0, st, X,
+                       W_up, none, row_ptr, col_idx, Tt, gt, d, nnz_cap, H_act, none,
+                       (const uint16_t*)U, B_pad);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  ProfScope ps(kKFfnDown, st);
+  hipLaunchKernelGGL(ffn_dsd_bf16<false>, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+                     (const uint16_t*)H_act, W_down, (long long)F, none, row_ptr, col_idx, gt, d,
+                     nnz_cap, Y, none, none);
+  return hipGetLastError();
+}
+
+// dB[j*64 + n][q] = sum over the token tiles i whose list row holds block j of
+// sum_t dZ_ij[t][n] U[i*64 + t][q]: one workgroup per neuron block; thread (n, 16 values of q).
+// The position of block j in every tile's (sorted) list row is found first, one tile per
+// thread, by bisection.  Plain fp32 arithmetic: 0.5 MFLOP per listed block.
+constexpr int kLoraThreads = 256;
+__global__ __launch_bounds__(kLoraThreads) void lora_db_kernel(
+    const uint16_t* __restrict__ dZ, const uint16_t* __restrict__ U,
+    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, int Tt, int gt, int nnz_cap,
+    float* __restrict__ dB) {
+  __shared__ float sz[64][65], su[64][64];
+  __shared__ int pos[kLoraThreads];
+  const int j = blockIdx.x, tid = threadIdx.x;
+  const int n = tid / 4, q0 = (tid % 4) * 16;
+  float acc[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+  for (int i0 = 0; i0 < Tt; i0 += kLoraThreads) {
+    {
+      const int i = i0 + tid;
+      int p = -1;
+      if (i < Tt) {
+        const int rs = row_ptr[i / gt];
+        int lo = 0, hi = min(row_ptr[i / gt + 1], nnz_cap) - rs;   // entries beyond the capacity are ignored
+        while (lo < hi) {
+          const int mid = (lo + hi) / 2, c = col_idx[rs + mid];
+          if (c == j) {
+            p = rs + mid;
+            break;
+          }
+          if (c < j) lo = mid + 1; else hi = mid;
+        }
+      }
+      pos[tid] = p;
+    }
+    __syncthreads();
+    for (int t = 0; t < min(kLoraThreads, Tt - i0); ++t) {
+      const int p = pos[t];
+      if (p < 0) continue;                       // uniform: the table is shared
+      const int i = i0 + t;
+      const int rs = row_ptr[i / gt];
+      const long long blk = (long long)rs * gt + (long long)(p - rs) * gt + i % gt;
+      // 64 x 64 bf16 each: 512 pieces of 16 bytes, two per thread
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int piece = tid + h * kLoraThreads, r = piece / 8, c8 = (piece % 8) * 8;
+        const uint4 z = *reinterpret_cast<const uint4*>(dZ + blk * 4096 + r * 64 + c8);
+        const uint4 u = *reinterpret_cast<const uint4*>(U + ((long long)i * 64 + r) * 64 + c8);
+        const uint32_t zz[4] = {z.x, z.y, z.z, z.w}, uu[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          sz[r][c8 + 2 * e] = bf2f(zz[e] & 0xFFFFu);
+          sz[r][c8 + 2 * e + 1] = bf2f(zz[e] >> 16);
+          su[r][c8 + 2 * e] = bf2f(uu[e] & 0xFFFFu);
+          su[r][c8 + 2 * e + 1] = bf2f(uu[e] >> 16);
+        }
+      }
+      __syncthreads();
+      for (int tt = 0; tt < 64; ++tt) {
+        const float z = sz[tt][n];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc[k] += z * su[tt][q0 + k];
+      }
+      __syncthreads();
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int k = 0; k < 16; ++k) dB[((long long)j * 64 + n) * 64 + q0 + k] = acc[k];
+}
+
+// Partial sums of dA[q][c] = sum_t G[t][q] X[t][c] over the token range of blockIdx.y:
+// part[y][q][c]; thread (q, 16 columns of the workgroup's 64).
+__global__ __launch_bounds__(kLoraThreads) void lora_da_kernel(
+    const uint16_t* __restrict__ G, const uint16_t* __restrict__ X, int Tt, int d,
+    float* __restrict__ part) {
+  __shared__ float sg[64][65], sx[64][64];
+  const int c0 = blockIdx.x * 64, tid = threadIdx.x;
+  const int q = tid / 4, k0 = (tid % 4) * 16;
+  const int per = (Tt + gridDim.y - 1) / gridDim.y;
+  const int i_lo = blockIdx.y * per, i_hi = min(Tt, i_lo + per);
+  float acc[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+  for (int i = i_lo; i < i_hi; ++i) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int piece = tid + h * kLoraThreads, r = piece / 8, c8 = (piece % 8) * 8;
+      const uint4 g = *reinterpret_cast<const uint4*>(G + ((long long)i * 64 + r) * 64 + c8);
+      const uint4 x = *reinterpret_cast<const uint4*>(X + ((long long)i * 64 + r) * d + c0 + c8);
+      const uint32_t gg[4] = {g.x, g.y, g.z, g.w}, xx[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sg[r][c8 + 2 * e] = bf2f(gg[e] & 0xFFFFu);
+        sg[r][c8 + 2 * e + 1] = bf2f(gg[e] >> 16);
+        sx[r][c8 + 2 * e] = bf2f(xx[e] & 0xFFFFu);
+        sx[r][c8 + 2 * e + 1] = bf2f(xx[e] >> 16);
+      }
+    }
+    __syncthreads();
+    for (int tt = 0; tt < 64; ++tt) {
+      const float g = sg[tt][q];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) acc[k] += g * sx[tt][k0 + k];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int k = 0; k < 16; ++k)
+    part[((long long)blockIdx.y * 64 + q) * d + c0 + k0 + k] = acc[k];
+}
+// dA = sum of the parts, in order
+__global__ void lora_da_reduce_kernel(const float* __restrict__ part, int parts, int n,
+                                      float* __restrict__ dA) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  float s = 0.f;
+  for (int p = 0; p < parts; ++p) s += part[(long long)p * n + idx];
+  dA[idx] = s;
+}
+
+// backward: dZ = (dY W_down) (.) [H > 0] on the listed blocks;  G = dZ B_pad [T,64];
+// dX = dZ W_up + G A_pad;  dB = dZ^T U;  dA = G^T X.
+// B_t [64,F], A_t [d,64], G [T,64] and da_part [kLoraSplit][64][d] are scratch.
+hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+                                    const uint16_t* dY, const uint16_t* H_act, const uint16_t* U,
+                                    const uint16_t* W_down_t, const uint16_t* W_up_t,
+                                    const uint16_t* A_pad, const uint16_t* B_pad,
+                                    const int* row_ptr, const int* col_idx, int nnz_cap,
+                                    uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
+                                    float* da_part, uint16_t* dX, float* dA, float* dB,
+                                    hipStream_t st) {
+  if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
+  const uint16_t* none = nullptr;
+  hipError_t e = launch_transpose(2, B_pad, F, 64, B_t, st);
+  if (e != hipSuccess) return e;
+  e = launch_transpose(2, A_pad, 64, d, A_t, st);
+  if (e != hipSuccess) return e;
+  {
+    ProfScope ps(kKFfnDh, st);
+    hipLaunchKernelGGL((ffn_sdd_bf16<1, false>), sdd_grid(Tt, gt, nnz_cap), dim3(kThreads), 0, st, dY,
+                       W_down_t, none, row_ptr, col_idx, Tt, gt, d, nnz_cap, dZ, H_act, none, none);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ProfScope ps(kKLora, st);
+    hipLaunchKernelGGL(ffn_dsd_bf16<false>, dim3(1, Tt), dim3(kThreads), 0, st, (const uint16_t*)dZ,
+                       (const uint16_t*)B_t, (long long)F, none, row_ptr, col_idx, gt, 64, nnz_cap, G,
+                       none, none);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ProfScope ps(kKFfnDx, st);
+    hipLaunchKernelGGL(ffn_dsd_bf16<true>, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+                       (const uint16_t*)dZ, W_up_t, (long long)F, none, row_ptr, col_idx, gt, d,
+                       nnz_cap, dX, (const uint16_t*)G, (const uint16_t*)A_t);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  ProfScope ps(kKLora, st);
+  hipLaunchKernelGGL(lora_db_kernel, dim3(F / 64), dim3(kLoraThreads), 0, st, (const uint16_t*)dZ, U,
+                     row_ptr, col_idx, Tt, gt, nnz_cap, dB);
+  const int split = Tt < kLoraSplit ? Tt : kLoraSplit;
+  hipLaunchKernelGGL(lora_da_kernel, dim3(d / 64, split), dim3(kLoraThreads), 0, st,
+                     (const uint16_t*)G, X, Tt, d, da_part);
+  hipLaunchKernelGGL(lora_da_reduce_kernel, dim3((64 * d + 255) / 256), dim3(256), 0, st,
+                     (const float*)da_part, split, 64 * d, dA);
   return hipGetLastError();
 }
 

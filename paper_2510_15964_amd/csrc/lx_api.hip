@@ -300,6 +300,80 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
+size_t lx_sparse_ffn_lora_fwd_workspace_bytes(void) { return 256; }
+
+size_t lx_sparse_ffn_lora_bwd_workspace_bytes(int32_t T, int32_t d, int32_t F, int32_t nnz_cap) {
+  if (T <= 0 || d <= 0 || F <= 0) return 0;
+  return act_bytes(LX_BF16, 64, 64, nnz_cap) + round256((size_t)64 * F * 2) +
+         round256((size_t)d * 64 * 2) + round256((size_t)T * 64 * 2) +
+         round256((size_t)kLoraSplit * 64 * d * 4);
+}
+
+static lx_status check_lora(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                            int32_t blk_n, const lx_blocklist* bl) {
+  if (dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  lx_status s = check_ffn(dt, T, d, F, tile_t, blk_n, bl);
+  if (s != LX_OK) return s;
+  if ((int64_t)bl->nnz_cap * ((T / tile_t) / bl->rows) > (int64_t)1 << 30) return LX_ERR_INVALID_ARG;
+  return LX_OK;
+}
+
+lx_status lx_sparse_ffn_lora_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                                 int32_t blk_n, const void* X, const void* W_up, const void* A_pad,
+                                 const void* B_pad, const void* W_down, const lx_blocklist* bl,
+                                 void* Y, void* H_act, void* U, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  lx_status s = check_lora(dt, T, d, F, tile_t, blk_n, bl);
+  if (s != LX_OK) return s;
+  if (!X || !W_up || !A_pad || !B_pad || !W_down || !Y || !H_act || !U) return LX_ERR_INVALID_ARG;
+  if (!aligned16(X) || !aligned16(W_up) || !aligned16(A_pad) || !aligned16(B_pad) ||
+      !aligned16(W_down) || !aligned16(Y) || !aligned16(H_act) || !aligned16(U) ||
+      !aligned16(workspace))
+    return LX_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < lx_sparse_ffn_lora_fwd_workspace_bytes()) return LX_ERR_WORKSPACE;
+  const int gt = (T / tile_t) / bl->rows;
+  hipError_t e = launch_ffn_lora_fwd_bf16(
+      T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)W_up, (const uint16_t*)A_pad,
+      (const uint16_t*)B_pad, (const uint16_t*)W_down, bl->row_ptr, bl->col_idx, bl->nnz_cap,
+      (uint16_t*)U, (uint16_t*)H_act, (uint16_t*)Y, (int*)workspace, (hipStream_t)stream);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+                                 int32_t blk_n, const void* X, const void* dY, const void* H_act,
+                                 const void* U, const void* W_up_t, const void* W_down_t,
+                                 const void* A_pad, const void* B_pad, const lx_blocklist* bl,
+                                 void* dX, float* dA, float* dB, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  lx_status s = check_lora(dt, T, d, F, tile_t, blk_n, bl);
+  if (s != LX_OK) return s;
+  if (!X || !dY || !H_act || !U || !W_up_t || !W_down_t || !A_pad || !B_pad || !dX || !dA || !dB)
+    return LX_ERR_INVALID_ARG;
+  if (!aligned16(X) || !aligned16(dY) || !aligned16(H_act) || !aligned16(U) || !aligned16(W_up_t) ||
+      !aligned16(W_down_t) || !aligned16(A_pad) || !aligned16(B_pad) || !aligned16(dX) ||
+      !aligned16(dA) || !aligned16(dB) || !aligned16(workspace))
+    return LX_ERR_INVALID_ARG;
+  const int gt = (T / tile_t) / bl->rows;
+  const size_t need = lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, bl->nnz_cap * gt);
+  if (!workspace || workspace_bytes < need) return LX_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  uint16_t* dz = (uint16_t*)ws;
+  ws += act_bytes(LX_BF16, 64, 64, bl->nnz_cap * gt);
+  uint16_t* bt = (uint16_t*)ws;
+  ws += round256((size_t)64 * F * 2);
+  uint16_t* at = (uint16_t*)ws;
+  ws += round256((size_t)d * 64 * 2);
+  uint16_t* g = (uint16_t*)ws;
+  ws += round256((size_t)T * 64 * 2);
+  float* part = (float*)ws;
+  hipError_t e = launch_ffn_lora_bwd_bf16(
+      T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)dY, (const uint16_t*)H_act,
+      (const uint16_t*)U, (const uint16_t*)W_down_t, (const uint16_t*)W_up_t,
+      (const uint16_t*)A_pad, (const uint16_t*)B_pad, bl->row_ptr, bl->col_idx, bl->nnz_cap, dz, bt,
+      at, g, part, (uint16_t*)dX, dA, dB, (hipStream_t)stream);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
 lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
                               const void* X, const void* Wa_t, float thr, uint8_t* mask,
                               void* stream) {

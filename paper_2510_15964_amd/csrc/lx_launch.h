@@ -10,7 +10,7 @@ constexpr int kCUs = 256;   // compute units of the chip
 // Kernel ids of the profiling aid (values are part of the C ABI: lx_kernel in lx.h).
 enum KernelId {
   kKCompact = 0, kKFfnUp = 1, kKFfnDown = 2, kKFfnDh = 3, kKFfnDx = 4,
-  kKAttnFwd = 5, kKAttnDq = 6, kKAttnDkv = 7, kKTranspose = 8, kKPredict = 9, kKCombine = 10, kKCount = 11
+  kKAttnFwd = 5, kKAttnDq = 6, kKAttnDkv = 7, kKTranspose = 8, kKPredict = 9, kKCombine = 10, kKLora = 11, kKCount = 12
 };
 void prof_pre(int id, hipStream_t st);
 void prof_post(int id, hipStream_t st);
@@ -72,6 +72,21 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st);
+constexpr int kLoraSplit = 8;   // token ranges whose partial sums of dA are added at the end
+hipError_t launch_ffn_lora_fwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+                                    const uint16_t* W_up, const uint16_t* A_pad,
+                                    const uint16_t* B_pad, const uint16_t* W_down,
+                                    const int* row_ptr, const int* col_idx, int nnz_cap,
+                                    uint16_t* U, uint16_t* H_act, uint16_t* Y, int* mini,
+                                    hipStream_t st);
+hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+                                    const uint16_t* dY, const uint16_t* H_act, const uint16_t* U,
+                                    const uint16_t* W_down_t, const uint16_t* W_up_t,
+                                    const uint16_t* A_pad, const uint16_t* B_pad,
+                                    const int* row_ptr, const int* col_idx, int nnz_cap,
+                                    uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
+                                    float* da_part, uint16_t* dX, float* dA, float* dB,
+                                    hipStream_t st);
 hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
                                const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);

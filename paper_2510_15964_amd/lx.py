@@ -32,11 +32,14 @@ EXPORTS = (
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
     "lx_attn_set_rows_per_workgroup", "lx_mlp_predict_mask", "lx_attn_combine_patterns",
+    "lx_sparse_ffn_lora_fwd_workspace_bytes", "lx_sparse_ffn_lora_bwd_workspace_bytes",
+    "lx_sparse_ffn_lora_fwd", "lx_sparse_ffn_lora_bwd",
 )
 (LX_K_COMPACT, LX_K_FFN_UP, LX_K_FFN_DOWN, LX_K_FFN_DH, LX_K_FFN_DX, LX_K_ATTN_FWD,
- LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE, LX_K_PREDICT, LX_K_COMBINE) = range(11)
+ LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE, LX_K_PREDICT, LX_K_COMBINE,
+ LX_K_LORA) = range(12)
 KERNEL_NAMES = ("compact", "ffn_up", "ffn_down", "ffn_dh", "ffn_dx", "attn_fwd", "attn_bwd_dq",
-                "attn_bwd_dkv", "transpose", "predict", "combine")
+                "attn_bwd_dkv", "transpose", "predict", "combine", "lora")
 
 
 class lx_blocklist(C.Structure):
@@ -80,6 +83,14 @@ _lib.lx_profile_begin.argtypes = [_i32, _i32]
 _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.lx_attn_set_rows_per_workgroup.argtypes = [_i32]
 _lib.lx_mlp_predict_mask.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _vp, _vp, _f, _vp, _vp]
+_lib.lx_sparse_ffn_lora_fwd_workspace_bytes.restype = _sz
+_lib.lx_sparse_ffn_lora_fwd_workspace_bytes.argtypes = []
+_lib.lx_sparse_ffn_lora_bwd_workspace_bytes.restype = _sz
+_lib.lx_sparse_ffn_lora_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
+_lib.lx_sparse_ffn_lora_fwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
+                                        _blp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.lx_sparse_ffn_lora_bwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
+                                        _vp, _vp, _vp, _blp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.lx_attn_combine_patterns.argtypes = [_blp, _blp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
                                           _vp]
 
@@ -228,6 +239,37 @@ def lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_
 
 def lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed) -> int:
     return _lib.lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed)
+
+
+def lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, nnz_cap) -> int:
+    return _lib.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, nnz_cap)
+
+
+def lx_sparse_ffn_lora_fwd(X, W_up, A_pad, B_pad, W_down, bl: BlockList, Y, H_act, U, workspace=None):
+    """U = X A_pad^T, H = ReLU(X W_up^T + U B_pad^T) on the listed blocks, Y = H W_down^T."""
+    T, d = X.shape
+    F = W_up.shape[0]
+    assert A_pad.shape == (64, d) and B_pad.shape == (F, 64) and U.shape == (T, 64)
+    if workspace is None:
+        workspace = torch.empty(_lib.lx_sparse_ffn_lora_fwd_workspace_bytes(), dtype=torch.uint8,
+                                device=X.device)
+    _check(_lib.lx_sparse_ffn_lora_fwd(_dt(X), T, d, F, 64, 64, _ptr(X), _ptr(W_up), _ptr(A_pad),
+                                       _ptr(B_pad), _ptr(W_down), C.byref(bl.c), _ptr(Y), _ptr(H_act),
+                                       _ptr(U), _ptr(workspace), workspace.numel(), _stream()),
+           "lx_sparse_ffn_lora_fwd")
+
+
+def lx_sparse_ffn_lora_bwd(X, dY, H_act, U, W_up_t, W_down_t, A_pad, B_pad, bl: BlockList, dX, dA, dB,
+                           workspace):
+    """dX, dA (fp32 [64,d]) and dB (fp32 [F,64]) of the LoRA-branch FFN."""
+    T, d = X.shape
+    F = W_down_t.shape[0]
+    assert dA.dtype == torch.float32 and dA.shape == (64, d) and dB.dtype == torch.float32
+    assert dB.shape == (F, 64) and W_up_t.shape == (d, F) and W_down_t.shape == (F, d)
+    _check(_lib.lx_sparse_ffn_lora_bwd(_dt(X), T, d, F, 64, 64, _ptr(X), _ptr(dY), _ptr(H_act), _ptr(U),
+                                       _ptr(W_up_t), _ptr(W_down_t), _ptr(A_pad), _ptr(B_pad),
+                                       C.byref(bl.c), _ptr(dX), _ptr(dA), _ptr(dB), _ptr(workspace),
+                                       workspace.numel(), _stream()), "lx_sparse_ffn_lora_bwd")
 
 
 def lx_mlp_predict_mask(X: torch.Tensor, Wa_t: torch.Tensor, thr: float, group_rows: int,

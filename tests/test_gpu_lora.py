@@ -1,0 +1,146 @@
+"""GPU parity: sparse FFN with a LoRA branch on the up-projection (Sec. II-C / II-D) -- forward,
+input gradient and the gradients of the trainable A and B -- against the CPU oracle."""
+import numpy as np
+import pytest
+
+from paper_2510_15964_amd import inputs
+from util import FRO, TOL, compact_blocks, dev, host, rel_err_fro, rel_err_max, round_to
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lx():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2510_15964_amd import lx
+    return lx
+
+
+def make_case(T, d, F, r, density, seed, rows=None):
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, density, seed, dtype="bf16", w_std=0.05)
+    rng = np.random.default_rng(seed + 17)
+    A = np.zeros((64, d), np.float32)
+    B = np.zeros((F, 64), np.float32)
+    A[:r] = inputs.bf16_round((rng.standard_normal((r, d)) / np.sqrt(d)).astype(np.float32))
+    B[:, :r] = inputs.bf16_round((rng.standard_normal((F, r)) * 0.05).astype(np.float32))
+    c.update(A_pad=A, B_pad=B, r=r)
+    if rows is not None:                      # list rows shared by groups of token tiles
+        m = c["mask"][:rows]
+        c["list_mask"] = np.ascontiguousarray(m)
+        c["mask"] = np.repeat(m, (T // 64) // rows, axis=0)
+    return c
+
+
+def grouped_compact(a, mask_rows, gt):
+    """[T,F] -> compact blocks in the layout of shared list rows: [entry][tile of the group]."""
+    out = []
+    for r in range(mask_rows.shape[0]):
+        for j in np.nonzero(mask_rows[r])[0]:
+            for g in range(gt):
+                i = r * gt + g
+                out.append(a[i * 64:(i + 1) * 64, j * 64:(j + 1) * 64])
+    return np.stack(out) if out else np.zeros((0, 64, 64), a.dtype)
+
+
+def run_both(lx, oracle, c):
+    import torch
+    T, d, F, r = c["T"], c["d"], c["F"], c["r"]
+    lm = c.get("list_mask", c["mask"])
+    gt = (T // 64) // lm.shape[0]
+    X, Wu, Wd, dY, Ap, Bp = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down", "dY", "A_pad", "B_pad"))
+    bl = lx.lx_mask_compact(torch.from_numpy(lm).cuda())
+    nblk = max(bl.nnz_cap * gt, 1)
+    H_act = torch.full((nblk * 4096 + 4096,), float("nan"), dtype=X.dtype, device="cuda")
+    Y = torch.full_like(X, float("nan"))
+    U = torch.full((T, 64), float("nan"), dtype=X.dtype, device="cuda")
+    lx.lx_sparse_ffn_lora_fwd(X, Wu, Ap, Bp, Wd, bl, Y, H_act, U)
+    Uo, Ho, Yo = oracle.ffn_lora_fwd(c["X"], c["W_up"], c["A_pad"][:r], c["B_pad"][:, :r], c["W_down"],
+                                     c["mask"], 64, 64)
+    nnz = int(lm.sum())
+    got = dict(U=host(U), Y=host(Y), H=host(H_act[:nnz * gt * 4096]).reshape(-1, 64, 64))
+    assert torch.isnan(H_act[nblk * 4096:]).all()
+    ref = dict(U=np.pad(Uo, ((0, 0), (0, 64 - r))), Y=Yo, H=grouped_compact(Ho, lm, gt))
+    # backward: both sides take the oracle's stored activations and U, rounded to the run dtype
+    Hq, Uq = round_to(Ho, "bf16"), round_to(ref["U"], "bf16")
+    H_in = torch.zeros_like(H_act)
+    H_in[:nnz * gt * 4096] = dev(grouped_compact(Hq, lm, gt).reshape(-1), "bf16")
+    Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+    ws = torch.empty(lx.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, bl.nnz_cap * gt), dtype=torch.uint8,
+                     device="cuda")
+    dX = torch.full_like(X, float("nan"))
+    dA = torch.full((64, d), float("nan"), dtype=torch.float32, device="cuda")
+    dB = torch.full((F, 64), float("nan"), dtype=torch.float32, device="cuda")
+    lx.lx_sparse_ffn_lora_bwd(X, dY, H_in, dev(Uq, "bf16"), Wut, Wdt, Ap, Bp, bl, dX, dA, dB, ws)
+    torch.cuda.synchronize()
+    g = oracle.ffn_lora_bwd(c["X"], c["dY"], c["W_up"], c["A_pad"][:r], c["B_pad"][:, :r], c["W_down"],
+                            c["mask"], Hq > 0, Uq[:, :r], 64, 64)
+    got.update(dX=host(dX), dA=host(dA), dB=host(dB))
+    ref.update(dX=g["dX"], dA=np.pad(g["dA"], ((0, 64 - r), (0, 0))), dB=np.pad(g["dB"], ((0, 0), (0, 64 - r))))
+    return got, ref
+
+
+def check(got, ref, label):
+    errs, fro = {}, {}
+    for k in ("U", "H", "Y", "dX", "dA", "dB"):
+        assert np.isfinite(got[k]).all(), k
+        if not ref[k].any():
+            assert not got[k].any(), k
+            continue
+        errs[k], fro[k] = rel_err_max(got[k], ref[k]), rel_err_fro(got[k], ref[k])
+    print(f"[lora {label}] max-rel {errs} fro {fro}", flush=True)
+    for k in errs:
+        assert errs[k] <= TOL["bf16"], (k, errs[k])
+        assert fro[k] <= FRO["bf16"], (k, fro[k])
+
+
+@pytest.mark.parametrize("T,d,F,r,density,seed", [
+    (256, 128, 512, 16, 0.4, 1),
+    (512, 256, 1024, 64, 0.2, 2),
+    (128, 64, 384, 8, 1.0, 3),
+    (320, 192, 640, 1, 0.5, 4),
+])
+def test_lora_matches_oracle(lx, oracle, T, d, F, r, density, seed):
+    c = make_case(T, d, F, r, density, seed)
+    got, ref = run_both(lx, oracle, c)
+    check(got, ref, f"T={T} d={d} F={F} r={r}")
+    assert not got["dA"][r:].any() and not got["dB"][:, r:].any() and not got["U"][:, r:].any()
+
+
+def test_lora_shared_list_rows(lx, oracle):
+    c = make_case(512, 128, 768, 16, 0.4, 5, rows=2)
+    got, ref = run_both(lx, oracle, c)
+    check(got, ref, "two list rows for eight tiles")
+
+
+def test_lora_empty_mask_and_unlisted_blocks(lx, oracle):
+    c = make_case(256, 128, 512, 16, 0.0, 6)
+    got, ref = run_both(lx, oracle, c)
+    assert not got["Y"].any() and not got["dX"].any() and not got["dA"].any() and not got["dB"].any()
+    c = make_case(256, 128, 512, 16, 0.5, 7)
+    c["mask"][:, 3] = 0                                    # a neuron block no tile lists
+    got, ref = run_both(lx, oracle, c)
+    check(got, ref, "block 3 unlisted")
+    assert not got["dB"][3 * 64:4 * 64].any()
+
+
+def test_zero_branch_equals_the_plain_ffn_bit_for_bit(lx, oracle):
+    """B = 0: the extra step adds exact zeros, so Y and H equal the plain kernels' output."""
+    import torch
+    c = make_case(256, 128, 512, 16, 0.4, 8)
+    c["B_pad"][:] = 0
+    got, _ = run_both(lx, oracle, c)
+    X, Wu, Wd = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down"))
+    bl = lx.lx_mask_compact(torch.from_numpy(c["mask"]).cuda())
+    H = torch.zeros(bl.nnz_cap * 4096, dtype=X.dtype, device="cuda")
+    Y = torch.empty_like(X)
+    lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, 64, 64, Y, H)
+    assert np.array_equal(host(Y), got["Y"])
+    assert np.array_equal(host(H[:got["H"].size]).reshape(got["H"].shape), got["H"])
+
+
+def test_lora_bench_shape_reduced_tokens(lx, oracle):
+XX
+    c = make_case(512, 2048, 8192, 16, 0.11, 9)
+    got, ref = run_both(lx, oracle, c)
+    check(got, ref, "d=2048 F=8192")
