@@ -140,7 +140,7 @@ def test_zero_branch_equals_the_plain_ffn_bit_for_bit(lx, oracle):
 
 
 def test_lora_bench_shape_reduced_tokens(lx, oracle):
-XX
+    """OPT-1.3B FFN widths with 512 tokens (the oracle's fp64 loops set the size), rank 16."""
     c = make_case(512, 2048, 8192, 16, 0.11, 9)
     got, ref = run_both(lx, oracle, c)
     check(got, ref, "d=2048 F=8192")
