@@ -15,6 +15,8 @@ Workloads (recipes in paper_2510_15964_amd/inputs.py):
   opt1.3b_layer_shared    the same layer with the FFN masks predicted on the
                   device every step (MLP predictor, one list for all tokens of
                   a call: the paper's operating point, Sec. V-A).
+  opt1.3b_layer_lora      the same layer with a LoRA branch (rank 16) on the FFN
+                  up-projection, including the gradients of A and B (Sec. II-C/D).
   opt1.3b_layer_patterns  the same layer with per-head attention patterns from
                   a pool, combined into the block lists on the device every
                   step (Sec. VI-A).
@@ -64,6 +66,13 @@ def make_workload(name: str):
         f = inputs.ffn_bernoulli(8192, 2048, 8192, 64, 64, 0.11, seed=2100, dtype="bf16")
         f["predictor"] = inputs.predictor_planted(2048, 128, 0.11, seed=2100)
         f["mask"] = np.repeat(f["predictor"]["hot"][None].astype(np.uint8), 128, axis=0)
+        a = inputs.config3_attn()
+        ffn_calls = 2
+    elif name == "opt1.3b_layer_lora":
+        # the default layer with a LoRA branch (rank 16) on the FFN up-projection: forward, input
+        # gradient and the gradients of the trainable A and B under the mask (Sec. II-C / II-D)
+        f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
+        f["lora"] = inputs.lora_matrices(2048, 8192, 16, seed=2200)
         a = inputs.config3_attn()
         ffn_calls = 2
     elif name == "opt1.3b_layer_patterns":
@@ -122,6 +131,16 @@ class FfnJob:
                                                   max(self.nnz, 1), 1)
         self.ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
         self.used = float((self.mask_h.sum(0) > 0).mean())     # fraction of neuron blocks touched
+        self.lora = f.get("lora")
+        if self.lora is not None:
+            self.A_pad, self.B_pad = dev(self.lora["A_pad"], "bf16"), dev(self.lora["B_pad"], "bf16")
+            self.U = torch.empty((self.T, 64), dtype=torch.bfloat16, device="cuda")
+            self.dA = torch.empty((64, self.d), dtype=torch.float32, device="cuda")
+            self.dB = torch.empty((self.F, 64), dtype=torch.float32, device="cuda")
+            self.ws = torch.empty(lx.lx_sparse_ffn_lora_bwd_workspace_bytes(self.T, self.d, self.F,
+                                                                            max(self.nnz, 1)),
+                                  dtype=torch.uint8, device="cuda")
+            self.ws_f = torch.empty(256, dtype=torch.uint8, device="cuda")
 
     def predict(self):
         if self.pred is not None:
@@ -129,6 +148,13 @@ class FfnJob:
 
     def run(self):
         lx = self.lx
+        if self.lora is not None:
+            lx.lx_sparse_ffn_lora_fwd(self.X, self.Wu, self.A_pad, self.B_pad, self.Wd, self.bl_run,
+                                      self.Y, self.H_act, self.U, self.ws_f)
+            lx.lx_sparse_ffn_lora_bwd(self.X, self.dY, self.H_act, self.U, self.Wut, self.Wdt,
+                                      self.A_pad, self.B_pad, self.bl_run, self.dX, self.dA, self.dB,
+                                      self.ws)
+            return
         lx.lx_sparse_ffn_fwd(self.X, self.Wu, self.Wd, self.bl_run, 64, 64, self.Y, self.H_act)
         lx.lx_sparse_ffn_bwd_dx(self.dY, self.H_act, self.Wu, self.Wd, self.bl_run, 64, 64, self.dX,
                                 self.ws, W_up_t=self.Wut, W_down_t=self.Wdt)
@@ -235,6 +261,8 @@ def kernel_model(lx, ffn_jobs, attn):
         lx.LX_K_ATTN_BWD_DKV: (1, attn.flops(4), 6 * u + 2 * stat),
         lx.LX_K_COMPACT: (1, 0.0, 0.0),
         **({lx.LX_K_COMBINE: (1, 0.0, 0.0)} if attn.pool is not None else {}),
+        # three bracketed groups per call: U = X A^T; G = dZ B; dB, dA
+        **({lx.LX_K_LORA: (3 * n, 0.0, 0.0)} if fj.lora is not None else {}),
         **({lx.LX_K_PREDICT: (n, 2.0 * fj.T * fj.d * fj.mask_h.shape[1],
                               2.0 * (fj.T * fj.d + fj.mask_h.shape[1] * fj.d))}
            if fj.pred is not None else {}),
@@ -252,8 +280,14 @@ def cpu_baseline(f, a, ffn_tiles=3, attn_heads=24):
     sl = slice(0, ffn_tiles * 64)
     m = np.ascontiguousarray(f["mask"][:ffn_tiles])
     t0 = time.perf_counter()
-    H, _ = oracle.ffn_fwd(f["X"][sl], f["W_up"], f["W_down"], m, 64, 64)
-    oracle.ffn_bwd_dx(f["dY"][sl], f["W_up"], f["W_down"], m, round_to(H, "bf16") > 0, 64, 64)
+    if "lora" in f:
+        r, Ap, Bp = f["lora"]["r"], f["lora"]["A_pad"], f["lora"]["B_pad"]
+        U, H, _ = oracle.ffn_lora_fwd(f["X"][sl], f["W_up"], Ap[:r], Bp[:, :r], f["W_down"], m, 64, 64)
+        oracle.ffn_lora_bwd(f["X"][sl], f["dY"][sl], f["W_up"], Ap[:r], Bp[:, :r], f["W_down"], m,
+                            round_to(H, "bf16") > 0, U, 64, 64)
+    else:
+        H, _ = oracle.ffn_fwd(f["X"][sl], f["W_up"], f["W_down"], m, 64, 64)
+        oracle.ffn_bwd_dx(f["dY"][sl], f["W_up"], f["W_down"], m, round_to(H, "bf16") > 0, 64, 64)
     t_ffn = time.perf_counter() - t0
     heads = np.nonzero(a["head_active"])[0][:attn_heads]
     sub = {k: np.ascontiguousarray(a[k][0:1, heads]) for k in ("Q", "K", "V", "dO")}
@@ -332,7 +366,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
         torch.cuda.synchronize()
         ms, n = lx.lx_profile_end()
         per_kernel[kid] = (ms / 3.0, ms / max(n, 1))      # ms per step, ms per launch
-    dom = max((k for k in per_kernel if k not in (lx.LX_K_COMPACT, lx.LX_K_COMBINE)),
+    dom = max((k for k in per_kernel if k not in (lx.LX_K_COMPACT, lx.LX_K_COMBINE, lx.LX_K_LORA)),
               key=lambda k: per_kernel[k][0])
 
     # timed region: exactly `steps` steps, dominant kernel bracketed by events

@@ -51,17 +51,26 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 // rows, then the weight blocks); lane l brings the 16-byte slot l%8 of row 8g + l/8.  src[u]
 // already points at this lane's (row, swizzled segment); offB / offA are the element offsets of
 // the current K-step for the shared rows and the weight rows.
-// With `alt` (wave-uniform) the pointers of alt_src are used instead: a step whose operands
-// live in other buffers with another row stride (the LoRA branch).
-template <int NISS>
+// With `alt` (wave-uniform) the source of instruction u is alt_ptr(u) instead: a step whose
+// operands live in other buffers with another row stride (the LoRA branch).  alt_ptr is
+// evaluated only then, so such a step costs no registers in the steady state.
+template <int NISS, class AltPtr>
 __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[NISS],
-                                            const uint16_t* const (&alt_src)[NISS], bool alt,
-                                            long long offB, long long offA) {
+                                            AltPtr alt_ptr, bool alt, long long offB,
+                                            long long offA) {
   const uint32_t base = lds_addr(stage) + (threadIdx.x / kWave) * 1024;
+  if (alt) {
 #pragma unroll
-  for (int u = 0; u < NISS; ++u)
-    dma16((alt ? alt_src[u] : src[u]) + (u < 8 / kFW ? offB : offA), base + u * (kFW * 1024));
+    for (int u = 0; u < NISS; ++u) dma16(alt_ptr(u), base + u * (kFW * 1024));
+  } else {
+#pragma unroll
+    for (int u = 0; u < NISS; ++u)
+      dma16(src[u] + (u < 8 / kFW ? offB : offA), base + u * (kFW * 1024));
+  }
 }
+struct NoAlt {
+  __device__ __forceinline__ const uint16_t* operator()(int) const { return nullptr; }
+};
 
 // One 64-deep K-step from LDS: wave w multiplies its 32*kNI weight rows (row groups kNI*w ..)
 // with the 64 shared rows.  acc[ni][ti]: rows = weight rows 32*(kNI*w + ni).., columns = shared
@@ -118,16 +127,15 @@ __device__ __forceinline__ void wait_tail(int y) {
 
 // step(stage pointer) is the multiplication of one landed stage; a stage holds SE elements.
 // offs(s, offB, offA) yields the element offsets of step s and returns whether the step takes
-// its operands from alt_src.
-template <int NST, int NISS, int SE, class Offs, class Step>
+// its operands from alt_ptr(u).
+template <int NST, int NISS, int SE, class AltPtr, class Offs, class Step>
 __device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&src)[NISS],
-                                            const uint16_t* const (&alt_src)[NISS], Offs offs,
-                                            uint16_t* ring, Step step) {
+                                            AltPtr alt_ptr, Offs offs, uint16_t* ring, Step step) {
   static_assert(NST >= 2 && NISS * (NST - 2) < 64, "ring depth");
   long long ob, oa;
   auto issue = [&](int s, int stage) {
     const bool alt = offs(s, ob, oa);
-    issue_stage<NISS>(ring + stage * SE, src, alt_src, alt, ob, oa);
+    issue_stage<NISS>(ring + stage * SE, src, alt_ptr, alt, ob, oa);
   };
 #pragma unroll
   for (int p = 0; p < NST - 1; ++p)
@@ -146,13 +154,12 @@ __device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&
   }
 }
 
-template <int NST, class Offs>
+template <int NST, class AltPtr, class Offs>
 __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
-                                         const uint16_t* const (&src)[kIssues],
-                                         const uint16_t* const (&alt_src)[kIssues], Offs offs,
-                                         uint16_t* ring, f32x16 (&acc)[kNI][2]) {
+                                         const uint16_t* const (&src)[kIssues], AltPtr alt_ptr,
+                                         Offs offs, uint16_t* ring, f32x16 (&acc)[kNI][2]) {
   const int wave = threadIdx.x / kWave;
-  run_ring_of<NST, kIssues, kStageElems>(nsteps, src, alt_src, offs, ring,
+  run_ring_of<NST, kIssues, kStageElems>(nsteps, src, alt_ptr, offs, ring,
                                          [&](const uint16_t* stage) {
                                            if (wave_on) mma_step(stage, wave, acc);
                                          });
@@ -246,22 +253,28 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
 
   // per-instruction source pointers of this lane (K offset added per step)
   const uint16_t* src[kIssues];
-  const uint16_t* src2[kIssues];             // the same for the low-rank step
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
     if (u < 8 / kFW) {
       src[u] = A + ((long long)i * 64 + row) * K + seg * 8;
-      src2[u] = LORA ? A2 + ((long long)i * 64 + row) * 64 + seg * 8 : src[u];
     } else {
       const int blk = g / 8 - 1, r = row - kRowsB - 64 * blk;
       // blocks past the end of the list are filled from the first block (never used)
       const int j = col_idx[p0 + (blk < nb ? blk : 0)];
       src[u] = W + ((long long)j * 64 + r) * K + seg * 8;
-      src2[u] = LORA ? W2 + ((long long)j * 64 + r) * 64 + seg * 8 : src[u];
     }
   }
+  // the same for the low-rank step (rows of 64 elements), computed when that step is issued
+  auto src2 = [&](int u) -> const uint16_t* {
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 8 / kFW) return A2 + ((long long)i * 64 + row) * 64 + seg * 8;
+    const int blk = g / 8 - 1, r = row - kRowsB - 64 * blk;
+    const int j = col_idx[p0 + (blk < nb ? blk : 0)];
+    return W2 + ((long long)j * 64 + r) * 64 + seg * 8;
+  };
   f32x16 acc[kNI][2];
   zero_acc(acc);
   const int blk_w = kNI * wave / 2;          // list entry (of the four) this wave works on
@@ -334,20 +347,24 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   const bool wave_on = n0 + 32 * kNI * wave < ncols_out;
 
   const uint16_t* src[kIssues];
-  const uint16_t* src2[kIssues];
 #pragma unroll
   for (int u = 0; u < kIssues; ++u) {
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
     if (u < 8 / kFW) {
       src[u] = act + row * 64 + seg * 8;          // inside a compact 64x64 activation block
-      src2[u] = LORA ? act2 + ((long long)i * 64 + row) * 64 + seg * 8 : src[u];
     } else {
       const int n = min(n0 + row - kRowsB, ncols_out - 1);   // rows past the edge: re-read the last
       src[u] = W + (long long)n * ldw + seg * 8;
-      src2[u] = LORA ? W2 + (long long)n * 64 + seg * 8 : src[u];
     }
   }
+  auto src2 = [&](int u) -> const uint16_t* {     // the low-rank step, computed when it is issued
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 8 / kFW) return act2 + ((long long)i * 64 + row) * 64 + seg * 8;
+    const int n = min(n0 + row - kRowsB, ncols_out - 1);
+    return W2 + (long long)n * 64 + seg * 8;
+  };
   f32x16 acc[kNI][2];
   zero_acc(acc);
   const int lsteps = n_i > 0 ? n_i : 0;
@@ -433,7 +450,7 @@ __global__ __launch_bounds__(kThreads) void predict_bf16(
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
   run_ring_of<kNSt, kNIss, kSE>(
-      K / kBK, src, src,
+      K / kBK, src, NoAlt(),
       [](int s, long long& ob, long long& oa) {
         ob = oa = (long long)s * kBK;
         return false;
@@ -506,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void predict_half_bf16(
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   run_ring_of<kNSt, kNIss, kSE>(
-      K / (2 * kBK), src, src,
+      K / (2 * kBK), src, NoAlt(),
       [](int s, long long& ob, long long& oa) {
         ob = oa = (long long)s * (2 * kBK);
         return false;

@@ -290,6 +290,17 @@ def config3_patterns(seed=3100):
     return attn_patterns(8, 32, 1024, 64, seed, probs=(0.5, 0.08, 0.27, 0.03, 0.05, 0.05, 0.02, 0.0))
 
 
+def lora_matrices(d, F, r, seed, b_std=0.02):
+    """LoRA matrices A [r,d] ~ N(0, 1/d), B [F,r] ~ N(0, b_std^2) (a branch in mid-training: B is
+    zero only at initialisation), bf16-representable, zero-padded to rank 64: A_pad [64,d],
+    B_pad [F,64]."""
+    A = np.zeros((64, d), np.float32)
+    B = np.zeros((F, 64), np.float32)
+    A[:r] = bf16_round((_rng(seed, 50).standard_normal((r, d)) / np.sqrt(d)).astype(np.float32))
+    B[:, :r] = bf16_round((_rng(seed, 51).standard_normal((F, r)) * b_std).astype(np.float32))
+    return dict(A_pad=A, B_pad=B, r=r)
+
+
 def predictor_planted(d, nblk, density, seed, hot_scale=4.0, thr=6.5):
     """Predictor matrix Wa_t [nblk, d] (bf16-representable) whose block scores X Wa_t^T, for
     X ~ N(0,1), are N(0,1) for cold blocks and N(0, hot_scale^2) for a planted set of
