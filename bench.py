@@ -140,7 +140,8 @@ class FfnJob:
             self.ws = torch.empty(lx.lx_sparse_ffn_lora_bwd_workspace_bytes(self.T, self.d, self.F,
                                                                             max(self.nnz, 1)),
                                   dtype=torch.uint8, device="cuda")
-            self.ws_f = torch.empty(256, dtype=torch.uint8, device="cuda")
+            self.ws_f = torch.empty(lx.lx_sparse_ffn_lora_fwd_workspace_bytes(self.T, self.d), dtype=torch.uint8,
+                                    device="cuda")
 
     def predict(self):
         if self.pred is not None:

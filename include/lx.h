@@ -235,7 +235,8 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
  *   U = X A_pad^T [T,64];  H_ij = ReLU(X_i W_up_j^T + U_i B_pad_j^T);  Y_i = sum_j H_ij W_down_j^T
  *   U      out [T,64], needed by the backward call
  *   H_act  out, compact activations as in lx_sparse_ffn_fwd (required)
- *   workspace  >= lx_sparse_ffn_lora_fwd_workspace_bytes()
+ *   workspace  >= lx_sparse_ffn_lora_fwd_workspace_bytes(T, d): fp32 partial sums of U when the
+ *              product is split over K to fill the chip (few token tiles)
  * Backward:
  *   dZ_ij = (dY_i W_down[:, j]) (.) [H_ij > 0];   G = sum_j dZ_ij B_pad_j  [T,64]
  *   dX_i = sum_j dZ_ij W_up_j + G_i A_pad
@@ -244,10 +245,11 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
  *   W_up_t, W_down_t: outputs of lx_ffn_pack_weights (required here)
  *   workspace  >= lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, nnz_cap) with
  *              nnz_cap counted in activation blocks as for lx_sparse_ffn_bwd_workspace_bytes
- * dA is summed over eight token ranges in a fixed order, dB per block over the
- * token tiles in ascending order: results are bit-reproducible.
+ * U, dA and dB are summed over a number of ranges (of K, of token tiles) that depends
+ * on the shape only, each range in ascending order and the ranges in a fixed order:
+ * results are bit-reproducible.
  */
-size_t lx_sparse_ffn_lora_fwd_workspace_bytes(void);
+size_t lx_sparse_ffn_lora_fwd_workspace_bytes(int32_t T, int32_t d);
 size_t lx_sparse_ffn_lora_bwd_workspace_bytes(int32_t T, int32_t d, int32_t F, int32_t nnz_cap);
 lx_status lx_sparse_ffn_lora_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
                                  int32_t blk_n, const void* X, const void* W_up, const void* A_pad,

@@ -50,8 +50,6 @@
 
 namespace lx {
 
-#define LX_AS3 __attribute__((address_space(3)))
-
 constexpr int kAT = 256;                 // threads per workgroup
 constexpr int kAW = kAT / kWave;         // wavefronts per workgroup
 // resident workgroups per CU (= wavefronts per SIMD) the D = 64 kernels are compiled for
@@ -59,8 +57,6 @@ constexpr int kFwdOcc64 = 4, kDqOcc64 = 3, kDkvOcc64 = 2;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 8.f;            // log2 units; see the forward kernel
-
-typedef short short4v __attribute__((ext_vector_type(4)));
 
 template <int D>
 __device__ __forceinline__ int tswz(int row) {
@@ -103,14 +99,6 @@ struct TileDma {
 template <int D>
 __device__ __forceinline__ constexpr uint32_t tile_off(int row, int col) {
   return (uint32_t)(row * 2 * D + ((((col >> 3) ^ tswz<D>(row)) << 4)) + (col & 7) * 2);
-}
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
-  return __builtin_bit_cast(uint4, *reinterpret_cast<const LX_AS3 u32x4*>((uintptr_t)addr));
-}
-__device__ __forceinline__ uint2 lds_read8_tr(uint32_t addr) {
-  return __builtin_bit_cast(
-      uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LX_AS3 short4v*>((uintptr_t)addr)));
 }
 
 // Per-lane offsets of the two access patterns of a wavefront that works on rows 32*half..+31

@@ -300,13 +300,19 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
-size_t lx_sparse_ffn_lora_fwd_workspace_bytes(void) { return 256; }
+size_t lx_sparse_ffn_lora_fwd_workspace_bytes(int32_t T, int32_t d) {
+  if (T < 64 || d < 64) return 256;
+  const int split = lora_u_split(T / 64, d);
+  return 256 + (split > 1 ? round256((size_t)split * T * 64 * 4) : 0);
+}
 
 size_t lx_sparse_ffn_lora_bwd_workspace_bytes(int32_t T, int32_t d, int32_t F, int32_t nnz_cap) {
-  if (T <= 0 || d <= 0 || F <= 0) return 0;
+  if (T < 64 || d < 64 || F < 64) return 0;
+  const int sa = lora_da_split(T / 64, d), sb = lora_db_split(T / 64, F);
   return act_bytes(LX_BF16, 64, 64, nnz_cap) + round256((size_t)64 * F * 2) +
          round256((size_t)d * 64 * 2) + round256((size_t)T * 64 * 2) +
-         round256((size_t)kLoraSplit * 64 * d * 4);
+         (sa > 1 ? round256((size_t)sa * 64 * d * 4) : 0) +
+         (sb > 1 ? round256((size_t)sb * F * 64 * 4) : 0);
 }
 
 static lx_status check_lora(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
@@ -330,12 +336,12 @@ lx_status lx_sparse_ffn_lora_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
       !aligned16(W_down) || !aligned16(Y) || !aligned16(H_act) || !aligned16(U) ||
       !aligned16(workspace))
     return LX_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < lx_sparse_ffn_lora_fwd_workspace_bytes()) return LX_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < lx_sparse_ffn_lora_fwd_workspace_bytes(T, d)) return LX_ERR_WORKSPACE;
   const int gt = (T / tile_t) / bl->rows;
   hipError_t e = launch_ffn_lora_fwd_bf16(
       T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)W_up, (const uint16_t*)A_pad,
       (const uint16_t*)B_pad, (const uint16_t*)W_down, bl->row_ptr, bl->col_idx, bl->nnz_cap,
-      (uint16_t*)U, (uint16_t*)H_act, (uint16_t*)Y, (int*)workspace, (hipStream_t)stream);
+      (uint16_t*)U, (uint16_t*)H_act, (uint16_t*)Y, (float*)workspace, (hipStream_t)stream);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
@@ -365,12 +371,15 @@ lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
   ws += round256((size_t)d * 64 * 2);
   uint16_t* g = (uint16_t*)ws;
   ws += round256((size_t)T * 64 * 2);
-  float* part = (float*)ws;
+  float* part_a = (float*)ws;
+  const int sa = lora_da_split(T / 64, d);
+  if (sa > 1) ws += round256((size_t)sa * 64 * d * 4);
+  float* part_b = (float*)ws;
   hipError_t e = launch_ffn_lora_bwd_bf16(
       T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)dY, (const uint16_t*)H_act,
       (const uint16_t*)U, (const uint16_t*)W_down_t, (const uint16_t*)W_up_t,
       (const uint16_t*)A_pad, (const uint16_t*)B_pad, bl->row_ptr, bl->col_idx, bl->nnz_cap, dz, bt,
-      at, g, part, (uint16_t*)dX, dA, dB, (hipStream_t)stream);
+      at, g, part_a, part_b, (uint16_t*)dX, dA, dB, (hipStream_t)stream);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 

@@ -68,4 +68,20 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+#define LX_AS1 __attribute__((address_space(1)))
+#define LX_AS3 __attribute__((address_space(3)))
+
+// LDS reads by byte address.  lds_read8_tr is the transposing read (ds_read_b64_tr_b16): within
+// 16 lanes, lane j receives element j of the four 16-element rows whose 8-byte quarters are
+// addressed by lanes 0-3, 4-7, 8-11 and 12-15.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
+  return __builtin_bit_cast(uint4, *reinterpret_cast<const LX_AS3 u32x4*>((uintptr_t)addr));
+}
+__device__ __forceinline__ uint2 lds_read8_tr(uint32_t addr) {
+  return __builtin_bit_cast(
+      uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LX_AS3 short4v*>((uintptr_t)addr)));
+}
+
 }  // namespace lx

@@ -72,12 +72,27 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
                            hipStream_t st);
-constexpr int kLoraSplit = 8;   // token ranges whose partial sums of dA are added at the end
+// Splits of the low-rank products of the LoRA branch over workgroups so that they fill the chip;
+// the partial sums are added in a fixed order.  U = X A^T: over K; dB: over ranges of token
+// tiles per neuron block; dA: over ranges of token tiles per 64-column chunk.
+inline int lora_clamp(int s, int hi) { return s < 1 ? 1 : (s > hi ? (hi < 1 ? 1 : hi) : s); }
+inline int lora_u_split(int Tt, int d) {
+  const int by_k = d / 64 / 4;   // at least four K-steps per workgroup
+  return lora_clamp((kCUs + Tt - 1) / Tt, by_k < 8 ? by_k : 8);
+}
+inline int lora_db_split(int Tt, int F) {
+  const int s = lora_clamp((2 * kCUs + F / 64 - 1) / (F / 64), Tt < 16 ? Tt : 16);
+  const int need = (Tt + 511) / 512;   // the kernel searches one tile of its range per thread
+  return s > need ? s : need;
+}
+inline int lora_da_split(int Tt, int d) {
+  return lora_clamp((kCUs + d / 64 - 1) / (d / 64), Tt < 32 ? Tt : 32);
+}
 hipError_t launch_ffn_lora_fwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* W_up, const uint16_t* A_pad,
                                     const uint16_t* B_pad, const uint16_t* W_down,
                                     const int* row_ptr, const int* col_idx, int nnz_cap,
-                                    uint16_t* U, uint16_t* H_act, uint16_t* Y, int* mini,
+                                    uint16_t* U, uint16_t* H_act, uint16_t* Y, float* u_part,
                                     hipStream_t st);
 hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* dY, const uint16_t* H_act, const uint16_t* U,
@@ -85,8 +100,8 @@ hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t
                                     const uint16_t* A_pad, const uint16_t* B_pad,
                                     const int* row_ptr, const int* col_idx, int nnz_cap,
                                     uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
-                                    float* da_part, uint16_t* dX, float* dA, float* dB,
-                                    hipStream_t st);
+                                    float* da_part, float* db_part, uint16_t* dX, float* dA,
+                                    float* dB, hipStream_t st);
 hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
                                const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);

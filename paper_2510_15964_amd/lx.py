@@ -84,7 +84,7 @@ _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.lx_attn_set_rows_per_workgroup.argtypes = [_i32]
 _lib.lx_mlp_predict_mask.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _vp, _vp, _f, _vp, _vp]
 _lib.lx_sparse_ffn_lora_fwd_workspace_bytes.restype = _sz
-_lib.lx_sparse_ffn_lora_fwd_workspace_bytes.argtypes = []
+_lib.lx_sparse_ffn_lora_fwd_workspace_bytes.argtypes = [_i32, _i32]
 _lib.lx_sparse_ffn_lora_bwd_workspace_bytes.restype = _sz
 _lib.lx_sparse_ffn_lora_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32]
 _lib.lx_sparse_ffn_lora_fwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
@@ -241,6 +241,10 @@ def lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_
     return _lib.lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed)
 
 
+def lx_sparse_ffn_lora_fwd_workspace_bytes(T, d) -> int:
+    return _lib.lx_sparse_ffn_lora_fwd_workspace_bytes(T, d)
+
+
 def lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, nnz_cap) -> int:
     return _lib.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, nnz_cap)
 
@@ -251,7 +255,7 @@ def lx_sparse_ffn_lora_fwd(X, W_up, A_pad, B_pad, W_down, bl: BlockList, Y, H_ac
     F = W_up.shape[0]
     assert A_pad.shape == (64, d) and B_pad.shape == (F, 64) and U.shape == (T, 64)
     if workspace is None:
-        workspace = torch.empty(_lib.lx_sparse_ffn_lora_fwd_workspace_bytes(), dtype=torch.uint8,
+        workspace = torch.empty(_lib.lx_sparse_ffn_lora_fwd_workspace_bytes(T, d), dtype=torch.uint8,
                                 device=X.device)
     _check(_lib.lx_sparse_ffn_lora_fwd(_dt(X), T, d, F, 64, 64, _ptr(X), _ptr(W_up), _ptr(A_pad),
                                        _ptr(B_pad), _ptr(W_down), C.byref(bl.c), _ptr(Y), _ptr(H_act),
