@@ -190,3 +190,52 @@ def test_attn_combine_patterns_validation(lxmod):
     assert f(*ok(nblk=8)) == L.LX_ERR_INVALID_ARG              # pool cols != nblk
     assert f(*ok(pc=pool)) == L.LX_ERR_INVALID_ARG             # column pool without column outputs
     assert f(*ok(rpc=FAKE, cic=FAKE)) == L.LX_ERR_INVALID_ARG  # column outputs without a pool
+
+
+def test_ffn_lora_validation(lxmod):
+    L = lxmod
+    bl = _bl(L, 8, 16)
+    T, d, F = 512, 128, 1024
+
+    def fwd(**k):
+        need = L.lx_sparse_ffn_lora_fwd_workspace_bytes(k.get("T", T), k.get("d", d))
+        b = k.get("bl", bl)
+        return L._lib.lx_sparse_ffn_lora_fwd(
+            k.get("dt", L.LX_BF16), k.get("T", T), k.get("d", d), k.get("F", F), k.get("tt", 64), 64,
+            k.get("X", FAKE), FAKE, k.get("A", FAKE), FAKE, FAKE, C.byref(b) if b is not None else None,
+            FAKE, k.get("H", FAKE), k.get("U", FAKE), k.get("ws", FAKE), k.get("wsb", need), None)
+
+    def bwd(**k):
+        need = L.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, bl.nnz_cap)
+        b = k.get("bl", bl)
+        return L._lib.lx_sparse_ffn_lora_bwd(
+            k.get("dt", L.LX_BF16), k.get("T", T), d, F, 64, 64, k.get("X", FAKE), FAKE, FAKE,
+            k.get("U", FAKE), k.get("Wut", FAKE), FAKE, FAKE, FAKE,
+            C.byref(b) if b is not None else None, FAKE, k.get("dA", FAKE), k.get("dB", FAKE),
+            k.get("ws", FAKE), k.get("wsb", need), None)
+
+    for f in (fwd, bwd):
+        assert f(dt=L.LX_F32) == L.LX_ERR_UNSUPPORTED            # bf16 only
+        assert f(T=500) == L.LX_ERR_UNSUPPORTED
+        assert f(X=None) == L.LX_ERR_INVALID_ARG
+        assert f(U=None) == L.LX_ERR_INVALID_ARG
+        assert f(bl=None) == L.LX_ERR_INVALID_ARG
+        assert f(bl=_bl(L, 8, 15)) == L.LX_ERR_INVALID_ARG
+        assert f(bl=_bl(L, 3, 16)) == L.LX_ERR_INVALID_ARG       # 8 tiles, 3 list rows
+        assert f(ws=None) == L.LX_ERR_WORKSPACE
+        assert f(X=C.c_void_p(0x1004)) == L.LX_ERR_INVALID_ARG
+    assert fwd(tt=32) == L.LX_ERR_UNSUPPORTED
+    assert fwd(d=100) == L.LX_ERR_UNSUPPORTED
+    assert fwd(A=None) == L.LX_ERR_INVALID_ARG
+    assert fwd(H=None) == L.LX_ERR_INVALID_ARG                   # the backward call needs it
+    assert fwd(wsb=L.lx_sparse_ffn_lora_fwd_workspace_bytes(T, d) - 1) == L.LX_ERR_WORKSPACE
+    assert bwd(Wut=None) == L.LX_ERR_INVALID_ARG                 # packed transposes are required
+    assert bwd(dA=None) == L.LX_ERR_INVALID_ARG
+    assert bwd(dB=None) == L.LX_ERR_INVALID_ARG
+    assert bwd(wsb=L.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, bl.nnz_cap) - 1) == L.LX_ERR_WORKSPACE
+    # sizes: the K split of U needs T*64 floats per range; degenerate shapes give the fixed minimum
+    assert L.lx_sparse_ffn_lora_fwd_workspace_bytes(4096, 2048) >= 4 * 4096 * 64 * 4
+    assert L.lx_sparse_ffn_lora_fwd_workspace_bytes(0, 0) == 256
+    assert L.lx_sparse_ffn_lora_bwd_workspace_bytes(0, 128, 1024, 16) == 0
+    assert (L.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, 128)
+            >= 128 * 8192 + 64 * F * 2 + d * 64 * 2 + T * 64 * 2)
