@@ -326,6 +326,37 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   }
 }
 
+// Which token tile the workgroups of grid row `slot` work on.  A workgroup of the dsd kernel
+// lasts as long as its tile's list is long, and a launch of few tiles lasts as long as its
+// slowest CU.  Up to kBalTiles tiles are therefore ranked by list length (ties by index; every
+// workgroup computes the same ranking, so the assignment is a permutation): grid rows are
+// dispatched in order, so the longest lists start first; and when the whole launch is resident
+// at once, two workgroups per CU, rows s and s + Tt/2, which the round robin of the dispatcher
+// places on the same CU, get ranks s and Tt - 1 - s, a long list next to a short one.
+constexpr int kBalTiles = 128;
+__device__ __forceinline__ int balanced_tile(const int* __restrict__ row_ptr, int Tt, int gt,
+                                             int nnz_cap, int slot, bool resident, int* lens) {
+  if (Tt > kBalTiles || Tt < 3) return slot;
+  const int tid = threadIdx.x;
+  if (tid < Tt) lens[tid] = min(row_ptr[tid / gt + 1], nnz_cap) - row_ptr[tid / gt];
+  __syncthreads();
+  const int half = (Tt + 1) / 2;
+  const int want = resident && slot >= half ? Tt - 1 - (slot - half) : slot;
+  if (tid < Tt) {
+    const int n = lens[tid];
+    int rank = 0;
+    for (int u = 0; u < Tt; ++u) {
+      const int m = lens[u];
+      rank += (m > n || (m == n && u < tid)) ? 1 : 0;
+    }
+    if (rank == want) lens[kBalTiles] = tid;
+  }
+  __syncthreads();
+  const int tile = __builtin_amdgcn_readfirstlane(lens[kBalTiles]);
+  __syncthreads();   // lens is memory the caller reuses
+  return tile;
+}
+
 // out[i-tile rows, n0 .. n0+255] = sum_s act[p_s] [64 x 64] . W[n0.., j_s*64 ..]^T (+ bias)
 // LORA: one more step with the operands act2 [T,64] (the token tile's 64 x 64 block) and
 // W2 [ncols_out, 64]: out += act2_i W2[n0..]^T, the low-rank part (dZ B) A of the input gradient.
@@ -337,7 +368,9 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     uint16_t* __restrict__ out, const uint16_t* __restrict__ act2,
     const uint16_t* __restrict__ W2) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kDsdStages * kStageElems];
-  const int i = blockIdx.y, n0 = blockIdx.x * kRowsA;
+  const int i = balanced_tile(row_ptr, gridDim.y, gt, nnz_cap, blockIdx.y,
+                              gridDim.x * gridDim.y <= 2 * kCUs, reinterpret_cast<int*>(ring));
+  const int n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i / gt];
   const int n_i = min(row_ptr[i / gt + 1], nnz_cap) - rs;   // <= 0: nothing within the capacity
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;

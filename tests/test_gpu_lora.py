@@ -139,8 +139,127 @@ def test_zero_branch_equals_the_plain_ffn_bit_for_bit(lx, oracle):
     assert np.array_equal(host(H[:got["H"].size]).reshape(got["H"].shape), got["H"])
 
 
-def test_lora_bench_shape_reduced_tokens(lx, oracle):
+def test_lora_bench_widths_reduced_tokens(lx, oracle):
     """OPT-1.3B FFN widths with 512 tokens (the oracle's fp64 loops set the size), rank 16."""
     c = make_case(512, 2048, 8192, 16, 0.11, 9)
     got, ref = run_both(lx, oracle, c)
     check(got, ref, "d=2048 F=8192")
+
+
+def test_lora_bench_shape_full_size_sampled(lx, oracle):
+    """The benchmark's LoRA FFN call (4096 tokens, OPT-1.3B widths, its planted-support mask and
+    seeded LoRA matrices) in the launch configuration the benchmark times.  The oracle checks
+    what it can compute piece by piece: U for all tokens; H, Y and dX of sampled token tiles
+    (tiles are independent); the rows of dB of sampled neuron blocks, from the problem sliced to
+    that block (dB of a block needs only that block's weights); and dA and dB in full from a
+    second backward call whose dY is zero outside the sampled tiles (the sums then run over
+    those tiles only).  The backward calls take the oracle's rounded U and, wherever an output
+    is compared, the oracle's rounded activations, so both sides use the same ReLU gate."""
+    import torch
+    T, d, F, r = 4096, 2048, 8192, 16
+    f = inputs.ffn_planted_support(8192, d, F, 64, 64, 0.5, 4.0, seed=2000)
+    lo = inputs.lora_matrices(d, F, r, seed=2200)
+    X, dYh, mask = f["X"][:T], f["dY"][:T], np.ascontiguousarray(f["mask"][:T // 64])
+    A, B = lo["A_pad"][:r], np.ascontiguousarray(lo["B_pad"][:, :r])
+    tiles = (0, 29, 63)
+    blocks = [int(np.argmax(mask.sum(0))), int(np.argsort(mask.sum(0))[len(mask[0]) // 2]),
+              int(np.argmin(mask.sum(0)))]
+    rp = np.concatenate([[0], np.cumsum(mask.sum(1, dtype=np.int64))])
+    pos = lambda i, j: int(rp[i] + mask[i, :j].sum())          # compact block of (tile i, block j)
+
+    Xd, Wu, Wd, Ap, Bp = (dev(a, "bf16") for a in (X, f["W_up"], f["W_down"], lo["A_pad"], lo["B_pad"]))
+    bl = lx.lx_mask_compact(torch.from_numpy(mask).cuda())
+    nnz = int(mask.sum())
+    assert bl.nnz_cap >= nnz
+    H_act = torch.zeros((bl.nnz_cap * 4096,), dtype=Xd.dtype, device="cuda")
+    Y = torch.empty_like(Xd)
+    U = torch.empty((T, 64), dtype=Xd.dtype, device="cuda")
+    lx.lx_sparse_ffn_lora_fwd(Xd, Wu, Ap, Bp, Wd, bl, Y, H_act, U)
+    torch.cuda.synchronize()
+    Yg, Ug, Hg = host(Y), host(U), host(H_act).reshape(-1, 64, 64)
+
+    def gate(name, g, ref):
+        e, fr = rel_err_max(g, ref), rel_err_fro(g, ref)
+        print(f"[lora full size] {name}: max-rel {e:.2e} fro {fr:.2e}", flush=True)
+        assert e <= TOL["bf16"] and fr <= FRO["bf16"], (name, e, fr)
+
+    # forward, per sampled tile; the oracle's U of every token comes from the block-sliced calls
+    H_in = Hg.copy()
+    tile_ref = {}
+    for i in tiles:
+        sl = slice(i * 64, (i + 1) * 64)
+        Uo, Ho, Yo = oracle.ffn_lora_fwd(X[sl], f["W_up"], A, B, f["W_down"], mask[i:i + 1], 64, 64)
+        gate(f"U tile {i}", Ug[sl, :r], Uo)
+        gate(f"Y tile {i}", Yg[sl], Yo)
+        js = np.nonzero(mask[i])[0]
+        Hc = np.stack([Ho[:, j * 64:(j + 1) * 64] for j in js])
+        gate(f"H tile {i}", Hg[rp[i]:rp[i + 1]], Hc)
+        Hq = round_to(Ho, "bf16")
+        for j in js:
+            H_in[pos(i, j)] = Hq[:, j * 64:(j + 1) * 64]
+        tile_ref[i] = (Hq, round_to(Uo, "bf16"))
+    assert not Ug[:, r:].any()
+    blk_ref = {}
+    U_all = None
+    for j in blocks:
+        jb = slice(j * 64, (j + 1) * 64)
+        Wu_j, B_j = f["W_up"][jb], B[jb]
+        Wd_j = np.ascontiguousarray(f["W_down"][:, jb])
+        m_j = np.ascontiguousarray(mask[:, j:j + 1])
+        Uo, Ho, _ = oracle.ffn_lora_fwd(X, Wu_j, A, B_j, Wd_j, m_j, 64, 64)
+        U_all = Uo
+        Hq = round_to(Ho, "bf16")
+        for i in np.nonzero(mask[:, j])[0]:
+            H_in[pos(i, j)] = Hq[i * 64:(i + 1) * 64]
+        blk_ref[j] = (Wu_j, B_j, Wd_j, m_j, Hq)
+    gate("U all tokens", Ug[:, :r], U_all)
+    Uq = round_to(U_all, "bf16")
+    U_in = dev(np.pad(Uq, ((0, 0), (0, 64 - r))), "bf16")
+    H_in_d = dev(H_in.reshape(-1), "bf16")
+
+    Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+    ws = torch.empty(lx.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, bl.nnz_cap), dtype=torch.uint8,
+                     device="cuda")
+
+    def backward(dY_host):
+        dX = torch.full_like(Xd, float("nan"))
+        dA = torch.full((64, d), float("nan"), dtype=torch.float32, device="cuda")
+        dB = torch.full((F, 64), float("nan"), dtype=torch.float32, device="cuda")
+        lx.lx_sparse_ffn_lora_bwd(Xd, dev(dY_host, "bf16"), H_in_d, U_in, Wut, Wdt, Ap, Bp, bl, dX, dA, dB, ws)
+        torch.cuda.synchronize()
+        out = host(dX), host(dA), host(dB)
+        assert all(np.isfinite(o).all() for o in out)
+        return out
+
+    # first call: the benchmark's dY
+    dXg, dAg, dBg = backward(dYh)
+    assert not dAg[r:].any() and not dBg[:, r:].any()
+    sum_dA, sum_dB = np.zeros((r, d)), np.zeros((F, r))
+    for i in tiles:
+        sl = slice(i * 64, (i + 1) * 64)
+        Hq, Uq_i = tile_ref[i]
+        g = oracle.ffn_lora_bwd(X[sl], dYh[sl], f["W_up"], A, B, f["W_down"], mask[i:i + 1], Hq > 0, Uq_i,
+                                64, 64)
+        gate(f"dX tile {i}", dXg[sl], g["dX"])
+        sum_dA += g["dA"]
+        sum_dB += g["dB"]
+    for j in blocks:
+        Wu_j, B_j, Wd_j, m_j, Hq = blk_ref[j]
+        g = oracle.ffn_lora_bwd(X, dYh, Wu_j, A, B_j, Wd_j, m_j, Hq > 0, Uq, 64, 64)
+        rows = dBg[j * 64:(j + 1) * 64, :r]
+        if m_j.any():
+            gate(f"dB block {j} ({int(m_j.sum())} tiles)", rows, g["dB"])
+        else:
+            assert not rows.any()
+    # second call: dY zero outside the sampled tiles
+    dY2 = np.zeros_like(dYh)
+    for i in tiles:
+        dY2[i * 64:(i + 1) * 64] = dYh[i * 64:(i + 1) * 64]
+    dX2, dA2, dB2 = backward(dY2)
+    gate("dA (sampled tiles)", dA2[:r], sum_dA)
+    gate("dB (sampled tiles)", dB2[:, :r], sum_dB)
+    untouched = np.ones(T // 64, bool)
+    untouched[list(tiles)] = False
+    assert not dX2.reshape(T // 64, 64, d)[untouched].any()
+    listed = mask[list(tiles)].any(0)
+    assert not dB2.reshape(F // 64, 64, 64)[~listed].any()
