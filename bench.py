@@ -41,7 +41,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 METRIC = "sparse FFN+attn fwd+bwd-dX tokens/s and active-FLOP MFMA util @10/30% density"
-PEAK_MFMA_BF16 = 2.5e15     # FLOP/s, dense bf16 MFMA, MI355X
+PEAK_MFMA_BF16 = 2.5e15     # FLOP/s, dense MFMA on 16-bit operands (bf16 and fp16 alike), MI355X
 PEAK_HBM = 8.0e12           # B/s
 
 
@@ -75,6 +75,12 @@ def make_workload(name: str):
         f["lora"] = inputs.lora_matrices(2048, 8192, 16, seed=2200)
         a = inputs.config3_attn()
         ffn_calls = 2
+    elif name == "opt1.3b_layer_f16":
+        # the default layer in IEEE half precision (fp16 operands, fp32 accumulation): the
+        # parameter precision of the paper's own runs (Sec. VII-A); same recipes and seeds
+        f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000, dtype="f16")
+        a = inputs.config3_attn(dtype="f16")
+        ffn_calls = 2
     elif name == "opt1.3b_layer_patterns":
         # attention masks the way the paper forms them (Sec. VI-A): every head is assigned one
         # pattern of a pool whose layouts were computed beforehand; the step combines them into
@@ -100,11 +106,12 @@ class FfnJob:
     """One lx_sparse_ffn_fwd + lx_sparse_ffn_bwd_dx call pair on T tokens."""
 
     def __init__(self, lx, torch, f, rows, Wu, Wd, Wut, Wdt):
-        from util import dev
+        from util import dev, lx_dtype
         self.lx, self.torch = lx, torch
         sl = slice(rows[0] * 64, rows[1] * 64)
-        self.X = dev(f["X"][sl], "bf16")
-        self.dY = dev(f["dY"][sl], "bf16")
+        self.dt = f["dtype"]
+        self.X = dev(f["X"][sl], self.dt)
+        self.dY = dev(f["dY"][sl], self.dt)
         self.mask_h = np.ascontiguousarray(f["mask"][rows[0]:rows[1]])
         self.Wu, self.Wd, self.Wut, self.Wdt = Wu, Wd, Wut, Wdt
         self.T, self.d = self.X.shape
@@ -116,7 +123,7 @@ class FfnJob:
             self.mask = torch.from_numpy(self.mask_h).cuda()
             lrows, lnnz = Tt, self.nnz
         else:                                      # one row, written by the predictor every step
-            self.Wa_t = dev(self.pred["Wa_t"], "bf16")
+            self.Wa_t = dev(self.pred["Wa_t"], self.dt)
             self.mask = torch.zeros((1, Fb), dtype=torch.uint8, device="cuda")
             lrows, lnnz = 1, int(self.pred["hot"].sum())
         self.cap = lrows * Fb
@@ -124,17 +131,17 @@ class FfnJob:
                                torch.empty(self.cap, dtype=torch.int32, device="cuda"), self.cap)
         # H_act sized by the host-known active count (the mask is a host-generated input)
         self.bl_run = lx.BlockList(lrows, Fb, self.bl.row_ptr, self.bl.col_idx, max(lnnz, 1))
-        self.H_act = torch.empty(max(self.nnz, 1) * 4096, dtype=torch.bfloat16, device="cuda")
+        self.H_act = torch.empty(max(self.nnz, 1) * 4096, dtype=self.X.dtype, device="cuda")
         self.Y = torch.empty_like(self.X)
         self.dX = torch.empty_like(self.X)
-        nb = lx.lx_sparse_ffn_bwd_workspace_bytes(lx.LX_BF16, self.T, self.d, self.F, 64, 64,
+        nb = lx.lx_sparse_ffn_bwd_workspace_bytes(lx_dtype(lx, self.dt), self.T, self.d, self.F, 64, 64,
                                                   max(self.nnz, 1), 1)
         self.ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
         self.used = float((self.mask_h.sum(0) > 0).mean())     # fraction of neuron blocks touched
         self.lora = f.get("lora")
         if self.lora is not None:
-            self.A_pad, self.B_pad = dev(self.lora["A_pad"], "bf16"), dev(self.lora["B_pad"], "bf16")
-            self.U = torch.empty((self.T, 64), dtype=torch.bfloat16, device="cuda")
+            self.A_pad, self.B_pad = dev(self.lora["A_pad"], self.dt), dev(self.lora["B_pad"], self.dt)
+            self.U = torch.empty((self.T, 64), dtype=self.X.dtype, device="cuda")
             self.dA = torch.empty((64, self.d), dtype=torch.float32, device="cuda")
             self.dB = torch.empty((self.F, 64), dtype=torch.float32, device="cuda")
             self.ws = torch.empty(lx.lx_sparse_ffn_lora_bwd_workspace_bytes(self.T, self.d, self.F,
@@ -172,9 +179,9 @@ class FfnJob:
 
 class AttnJob:
     def __init__(self, lx, torch, a):
-        from util import dev
+        from util import dev, lx_dtype
         self.lx, self.torch, self.a = lx, torch, a
-        self.Q, self.K, self.V, self.dO = (dev(a[k], "bf16") for k in ("Q", "K", "V", "dO"))
+        self.Q, self.K, self.V, self.dO = (dev(a[k], a["dtype"]) for k in ("Q", "K", "V", "dO"))
         self.ha = torch.from_numpy(a["head_active"]).cuda()
         B, Hh, S, D = self.Q.shape
         self.B, self.Hh, self.S, self.D = B, Hh, S, D
@@ -196,7 +203,7 @@ class AttnJob:
         self.O = torch.empty_like(self.Q)
         self.LSE = torch.empty((B, Hh, S), dtype=torch.float32, device="cuda")
         self.dQ, self.dK, self.dV = (torch.empty_like(self.Q) for _ in range(3))
-        self.ws = torch.empty(lx.lx_sparse_attn_bwd_workspace_bytes(lx.LX_BF16, B, Hh, S, D),
+        self.ws = torch.empty(lx.lx_sparse_attn_bwd_workspace_bytes(lx_dtype(lx, a["dtype"]), B, Hh, S, D),
                               dtype=torch.uint8, device="cuda")
         act = a["head_active"].astype(bool)
         self.h_act = int(act.sum())
@@ -285,10 +292,10 @@ def cpu_baseline(f, a, ffn_tiles=3, attn_heads=24):
         r, Ap, Bp = f["lora"]["r"], f["lora"]["A_pad"], f["lora"]["B_pad"]
         U, H, _ = oracle.ffn_lora_fwd(f["X"][sl], f["W_up"], Ap[:r], Bp[:, :r], f["W_down"], m, 64, 64)
         oracle.ffn_lora_bwd(f["X"][sl], f["dY"][sl], f["W_up"], Ap[:r], Bp[:, :r], f["W_down"], m,
-                            round_to(H, "bf16") > 0, U, 64, 64)
+                            round_to(H, f["dtype"]) > 0, U, 64, 64)
     else:
         H, _ = oracle.ffn_fwd(f["X"][sl], f["W_up"], f["W_down"], m, 64, 64)
-        oracle.ffn_bwd_dx(f["dY"][sl], f["W_up"], f["W_down"], m, round_to(H, "bf16") > 0, 64, 64)
+        oracle.ffn_bwd_dx(f["dY"][sl], f["W_up"], f["W_down"], m, round_to(H, f["dtype"]) > 0, 64, 64)
     t_ffn = time.perf_counter() - t0
     heads = np.nonzero(a["head_active"])[0][:attn_heads]
     sub = {k: np.ascontiguousarray(a[k][0:1, heads]) for k in ("Q", "K", "V", "dO")}
@@ -324,7 +331,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     assert torch.cuda.is_available(), "bench.py needs a GPU (no fallback path)"
     torch.cuda.set_device(0)
     f, a, ffn_calls = make_workload(workload)
-    Wu, Wd = dev(f["W_up"], "bf16"), dev(f["W_down"], "bf16")
+    Wu, Wd = dev(f["W_up"], f["dtype"]), dev(f["W_down"], f["dtype"])
     Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)            # one-time repack of frozen weights
     Tt = f["mask"].shape[0]
     per = Tt // ffn_calls
@@ -407,7 +414,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     out = {
         "metric": METRIC, "value": tokens * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": f["dtype"], "data": "synthetic",
         "config": {
             "workload": workload, "tokens_per_step": tokens,
             "ffn": {"T_per_call": ffn_jobs[0].T, "calls": ffn_calls, "d": f["d"], "F": f["F"],

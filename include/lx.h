@@ -45,7 +45,7 @@ typedef enum {
   LX_ERR_RUNTIME = 4      /* a HIP launch reported an error */
 } lx_status;
 
-typedef enum { LX_F32 = 0, LX_BF16 = 1 } lx_dtype;
+typedef enum { LX_F32 = 0, LX_BF16 = 1, LX_F16 = 2 } lx_dtype;
 
 /*
  * Row-compressed active-block list: the "list of data block indices" of

@@ -118,7 +118,7 @@ struct LaneOff {
 // `tile`) and F the per-lane register fragments (column index = lane%32).  Result register v of
 // a lane is element (row 32*half + 8*(v/4) + 4*(lane/32) + v%4, column lane%32).  The operand
 // reads are issued ahead of the MFMAs, so their LDS latency is paid once, not once per k16 slice.
-template <int D>
+template <int D, int DT>
 __device__ __forceinline__ void mma_rows(uint32_t tile, const LaneOff<D>& lo,
                                          const uint4 (&frag)[D / 16], f32x16& acc) {
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -130,7 +130,7 @@ __device__ __forceinline__ void mma_rows(uint32_t tile, const LaneOff<D>& lo,
 #pragma unroll
   for (int s = 0; s < D / 16; ++s)
     // the first product starts from a literal zero (no register clearing)
-    acc = mfma32(a[s], frag[s], s == 0 ? zero16 : acc);
+    acc = mfma32<DT>(a[s], frag[s], s == 0 ? zero16 : acc);
 }
 
 // Operands of out[ct] += T[rows 32*half ..+31][:]^T . P (two k-slices of 16 rows of T), read from
@@ -152,17 +152,17 @@ __device__ __forceinline__ void load_tr(uint32_t tile, const LaneOff<D>& lo, TrO
     }
 }
 // p[v]: accumulator-layout values of the [32 x 32] factor P (rounded to bf16 here).
-template <int D>
+template <int D, int DT>
 __device__ __forceinline__ void mma_tr(const TrOps<D>& t, const f32x16& p, f32x16 (&out)[D / 32]) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     uint4 b;
-    b.x = pack2bf(p[8 * i + 0], p[8 * i + 1]);
-    b.y = pack2bf(p[8 * i + 2], p[8 * i + 3]);
-    b.z = pack2bf(p[8 * i + 4], p[8 * i + 5]);
-    b.w = pack2bf(p[8 * i + 6], p[8 * i + 7]);
+    b.x = pack2<DT>(p[8 * i + 0], p[8 * i + 1]);
+    b.y = pack2<DT>(p[8 * i + 2], p[8 * i + 3]);
+    b.z = pack2<DT>(p[8 * i + 4], p[8 * i + 5]);
+    b.w = pack2<DT>(p[8 * i + 6], p[8 * i + 7]);
 #pragma unroll
-    for (int ct = 0; ct < D / 32; ++ct) out[ct] = mfma32(t.a[i][ct], b, out[ct]);
+    for (int ct = 0; ct < D / 32; ++ct) out[ct] = mfma32<DT>(t.a[i][ct], b, out[ct]);
   }
 }
 
@@ -195,7 +195,7 @@ __device__ __forceinline__ void zero(f32x16 (&a)[N]) {
 
 // accumulator layout [c-tile][v] (c = 32ct + 8(v/4) + 4(lane/32) + v%4, row = lane%32) -> global;
 // c-tiles C0 .. C0+N-1 only
-template <int D, int C0 = 0, int N = D / 32>
+template <int D, int DT, int C0 = 0, int N = D / 32>
 __device__ __forceinline__ void store_acc(const f32x16 (&acc)[D / 32], float mul,
                                           uint16_t* __restrict__ dst_row) {
   const int h2 = (threadIdx.x % kWave) / 32;
@@ -204,8 +204,8 @@ __device__ __forceinline__ void store_acc(const f32x16 (&acc)[D / 32], float mul
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       uint2 o;
-      o.x = pack2bf(acc[ct][4 * g] * mul, acc[ct][4 * g + 1] * mul);
-      o.y = pack2bf(acc[ct][4 * g + 2] * mul, acc[ct][4 * g + 3] * mul);
+      o.x = pack2<DT>(acc[ct][4 * g] * mul, acc[ct][4 * g + 1] * mul);
+      o.y = pack2<DT>(acc[ct][4 * g + 2] * mul, acc[ct][4 * g + 3] * mul);
       *reinterpret_cast<uint2*>(dst_row + 32 * ct + 8 * g + 4 * h2) = o;
     }
 }
@@ -425,7 +425,7 @@ __device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin
 // ---------------------------------------------------------------------------
 // forward: O, LSE for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, int DT>
 __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   __shared__ float xstat[2][2][2][64];   // [part][own][max, sum][lane]
@@ -448,7 +448,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
       if (rows.blk(j) >= 0 && rows.n(j) == 0) {
         f32x16 z[D / 32];
         zero(z);
-        store_acc<D>(z, 0.f, a.Out + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
+        store_acc<D, DT>(z, 0.f, a.Out + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
         if (h2 == 0) a.LSE[stat_base + rows.blk(j) * 64 + ql] = -INFINITY;
       }
   }
@@ -487,7 +487,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
   auto comp = [&](int stage, int col) {
     const uint32_t stg = st_addr + stage * (4 * 64 * D);
     f32x16 s_acc;
-    mma_rows<D>(stg, lo, qf, s_acc);       // S^T[key][q]
+    mma_rows<D, DT>(stg, lo, qf, s_acc);       // S^T[key][q]
     // the V^T operands do not depend on the scores; reading them now hides their LDS latency
     // behind the softmax arithmetic
     TrOps<D> vt;
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
 #pragma unroll
       for (int ct = 0; ct < D / 32; ++ct) o_acc[ct] *= alpha;
     }
-    mma_tr<D>(vt, s_acc, o_acc);          // O^T += V^T P^T
+    mma_tr<D, DT>(vt, s_acc, o_acc);          // O^T += V^T P^T
   };
   // combine the two key halves: (m, l, O) = (m0, l0, O0) (+) (m1, l1, O1)
   auto row_end = [&](int, int stage) {
@@ -548,12 +548,12 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
     const float inv = any ? 1.f / l : 0.f;
     if (part == 0) {
       merge_half<D, 0>(area, own, a0 * inv, a1 * inv, o_acc);
-      store_acc<D, 0, D / 64>(o_acc, 1.f, a.Out + qoff);
+      store_acc<D, DT, 0, D / 64>(o_acc, 1.f, a.Out + qoff);
       if (h2 == 0)
         a.LSE[stat_base + qb * 64 + ql] = any ? (mt + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
     } else {
       merge_half<D, 1>(area, own, a0 * inv, a1 * inv, o_acc);
-      store_acc<D, D / 64, D / 64>(o_acc, 1.f, a.Out + qoff);
+      store_acc<D, DT, D / 64, D / 64>(o_acc, 1.f, a.Out + qoff);
     }
   };
   walk_rows<false>(rows, row_begin, [](int) {}, issue, comp, row_end);
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
 // ---------------------------------------------------------------------------
 // backward, query side: Delta and dQ for the query blocks of one workgroup
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, int DT>
 __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   // Q and dO tiles of a row, brought in one row ahead (head size 64 only: with 128 the area would
@@ -589,7 +589,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
       if (rows.blk(j) >= 0 && rows.n(j) == 0) {
         f32x16 z[D / 32];
         zero(z);
-        store_acc<D>(z, 0.f, a.dQ + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
+        store_acc<D, DT>(z, 0.f, a.dQ + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
         if (h2 == 0) {
           a.Delta[stat_base + rows.blk(j) * 64 + ql] = 0.f;
           a.NegLse2[stat_base + rows.blk(j) * 64 + ql] = INFINITY;
@@ -637,7 +637,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
       const uint32_t y[4] = {of.x, of.y, of.z, of.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        sum += bf2f(x[e] & 0xFFFFu) * bf2f(y[e] & 0xFFFFu) + bf2f(x[e] >> 16) * bf2f(y[e] >> 16);
+        sum += to_f32<DT>(x[e] & 0xFFFFu) * to_f32<DT>(y[e] & 0xFFFFu) + to_f32<DT>(x[e] >> 16) * to_f32<DT>(y[e] >> 16);
     }
     delta = sum + __shfl_xor(sum, 32);
     if (part == 0 && h2 == 0) {        // for the key-side kernel: Delta and -LSE in log2 units
@@ -660,8 +660,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   auto comp = [&](int stage, int col) {
     const uint32_t stg = st_addr + stage * (4 * 64 * D);
     f32x16 s_acc, dp_acc;
-    mma_rows<D>(stg, lo, qf, s_acc);                    // S^T[key][q]
-    mma_rows<D>(stg + 2 * 64 * D, lo, dof, dp_acc);     // dP^T[key][q]
+    mma_rows<D, DT>(stg, lo, qf, s_acc);                    // S^T[key][q]
+    mma_rows<D, DT>(stg + 2 * 64 * D, lo, dof, dp_acc);     // dP^T[key][q]
     if (a.causal && col == qb) mask_diag(s_acc, own, part);   // excluded keys: P = exp2(-inf) = 0
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -673,7 +673,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
     __builtin_amdgcn_sched_barrier(0);
     TrOps<D> kt;
     load_tr<D>(stg, lo, kt);
-    mma_tr<D>(kt, s_acc, dq_acc);           // dQ^T += K^T dS^T
+    mma_tr<D, DT>(kt, s_acc, dq_acc);           // dQ^T += K^T dS^T
   };
   auto row_end = [&](int, int stage) {     // dQ = sum over the two key halves
     float* area = reinterpret_cast<float*>(st[stage]);
@@ -685,10 +685,10 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
     lds_barrier();
     if (part == 0) {
       merge_half<D, 0>(area, own, 1.f, 1.f, dq_acc);
-      store_acc<D, 0, D / 64>(dq_acc, a.scale, a.dQ + qoff);
+      store_acc<D, DT, 0, D / 64>(dq_acc, a.scale, a.dQ + qoff);
     } else {
       merge_half<D, 1>(area, own, 1.f, 1.f, dq_acc);
-      store_acc<D, D / 64, D / 64>(dq_acc, a.scale, a.dQ + qoff);
+      store_acc<D, DT, D / 64, D / 64>(dq_acc, a.scale, a.dQ + qoff);
     }
   };
   walk_rows<kOwnPf>(rows, row_begin, prefetch, issue, comp, row_end);
@@ -697,7 +697,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
 // ---------------------------------------------------------------------------
 // backward, key side: dK and dV for the key blocks of one workgroup
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, int DT>
 __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: Q tile, dO tile
   // K and V tiles of a row, brought in one row ahead (head size 64 only: with 128 the kernel is
@@ -727,8 +727,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
         f32x16 z[D / 32];
         zero(z);
         const long long koff = base + (long long)(rows.blk(j) * 64 + kl) * a.ss;
-        store_acc<D>(z, 0.f, a.dV + koff);
-        store_acc<D>(z, 0.f, a.dK + koff);
+        store_acc<D, DT>(z, 0.f, a.dV + koff);
+        store_acc<D, DT>(z, 0.f, a.dK + koff);
       }
   }
 
@@ -775,8 +775,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
     const uint32_t stg = st_addr + stage * (4 * 64 * D);
     const float* stt = sstat[stage];
     f32x16 s_acc, dp_acc;
-    mma_rows<D>(stg, lo, kf, s_acc);                   // S[q][key]
-    mma_rows<D>(stg + 2 * 64 * D, lo, vf, dp_acc);     // dP[q][key]
+    mma_rows<D, DT>(stg, lo, kf, s_acc);                   // S[q][key]
+    mma_rows<D, DT>(stg + 2 * 64 * D, lo, vf, dp_acc);     // dP[q][key]
     // diagonal block: here the rows of the score tile are queries and the lane is the key
     if (a.causal && col == kb) mask_diag_t(s_acc, own, part);
 #pragma unroll
@@ -798,11 +798,11 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
     __builtin_amdgcn_sched_barrier(0);
     TrOps<D> dot;
     load_tr<D>(stg + 2 * 64 * D, lo, dot);
-    mma_tr<D>(dot, s_acc, dv_acc);            // dV^T += dO^T P
+    mma_tr<D, DT>(dot, s_acc, dv_acc);            // dV^T += dO^T P
     TrOps<D> qt;
     load_tr<D>(stg, lo, qt);
     __builtin_amdgcn_sched_barrier(0);
-    mma_tr<D>(qt, dp_acc, dk_acc);            // dK^T += Q^T dS
+    mma_tr<D, DT>(qt, dp_acc, dk_acc);            // dK^T += Q^T dS
   };
   // dV and dK = sums over the two query halves, exchanged one after the other through the
   // same LDS area
@@ -818,8 +818,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
       lds_barrier();
       if (part == 0) {
         merge_all<D>(area, own, dk_acc);
-        store_acc<D>(dv_acc, 1.f, a.dV + koff);
-        store_acc<D>(dk_acc, a.scale, a.dK + koff);
+        store_acc<D, DT>(dv_acc, 1.f, a.dV + koff);
+        store_acc<D, DT>(dk_acc, a.scale, a.dK + koff);
       }
       return;
     }
@@ -841,12 +841,12 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
     lds_barrier();
     if (part == 0) {
       merge_half<D, 0>(area, own, 1.f, 1.f, dk_acc);
-      store_acc<D, 0, D / 64>(dv_acc, 1.f, a.dV + koff);
-      store_acc<D, 0, D / 64>(dk_acc, a.scale, a.dK + koff);
+      store_acc<D, DT, 0, D / 64>(dv_acc, 1.f, a.dV + koff);
+      store_acc<D, DT, 0, D / 64>(dk_acc, a.scale, a.dK + koff);
     } else {
       merge_half<D, 1>(area, own, 1.f, 1.f, dk_acc);
-      store_acc<D, D / 64, D / 64>(dv_acc, 1.f, a.dV + koff);
-      store_acc<D, D / 64, D / 64>(dk_acc, a.scale, a.dK + koff);
+      store_acc<D, DT, D / 64, D / 64>(dv_acc, 1.f, a.dV + koff);
+      store_acc<D, DT, D / 64, D / 64>(dk_acc, a.scale, a.dK + koff);
     }
   };
   walk_rows<kOwnPf>(rows, row_begin, prefetch, issue, comp, row_end);
@@ -868,24 +868,24 @@ static int rows_per_wg(int nblk, int heads, int B, int slots) {
   return r > nblk ? nblk : r;
 }
 
-template <int D>
+template <int D, int DT>
 static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
   ProfScope ps(kKAttnFwd, st);
   const int nblk = a.S / 64;
   a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kFwdOcc64 : 2));
   const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-  hipLaunchKernelGGL(attn_fwd_bf16<D>, dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
+  hipLaunchKernelGGL((attn_fwd_bf16<D, DT>), dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
   return hipGetLastError();
 }
 
-template <int D>
+template <int D, int DT>
 static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
   const int nblk = a.S / 64;
   {
     ProfScope ps(kKAttnDq, st);
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDqOcc64 : 2));
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL(attn_bwd_dq_bf16<D>, dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL((attn_bwd_dq_bf16<D, DT>), dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -893,16 +893,19 @@ static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
     ProfScope ps(kKAttnDkv, st);
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDkvOcc64 : 1));
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL(attn_bwd_dkv_bf16<D>, dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT>), dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_attn_fwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st) {
-  return D == 64 ? launch_fwd<64>(a, B, st) : launch_fwd<128>(a, B, st);
+// dt: element type (kBf16 or kF16)
+hipError_t launch_attn_fwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st) {
+  if (dt == kF16) return D == 64 ? launch_fwd<64, kF16>(a, B, st) : launch_fwd<128, kF16>(a, B, st);
+  return D == 64 ? launch_fwd<64, kBf16>(a, B, st) : launch_fwd<128, kBf16>(a, B, st);
 }
-hipError_t launch_attn_bwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st) {
-  return D == 64 ? launch_bwd<64>(a, B, st) : launch_bwd<128>(a, B, st);
+hipError_t launch_attn_bwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st) {
+  if (dt == kF16) return D == 64 ? launch_bwd<64, kF16>(a, B, st) : launch_bwd<128, kF16>(a, B, st);
+  return D == 64 ? launch_bwd<64, kBf16>(a, B, st) : launch_bwd<128, kBf16>(a, B, st);
 }
 
 }  // namespace lx

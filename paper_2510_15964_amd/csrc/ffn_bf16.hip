@@ -1,6 +1,8 @@
 // bf16 sparse FFN kernels for gfx950 (Sec. VI-B: neuron-centric tiled matrix
 // products that take the list of active neuron blocks and load / compute only
-// those).  fp32 accumulation on the 32x32x16 bf16 MFMA.
+// those).  fp32 accumulation on the 32x32x16 MFMA for 16-bit operands.  The kernels are
+// templates over the element type DT (bfloat16 or IEEE half, same layouts and data movement);
+// "bf16" in their names dates from the first of the two.
 //
 // Both products of a pass are "NT" contractions whose operands are read along
 // their contiguous dimension in 128-byte segments (one 64-element bf16 K-chunk
@@ -72,6 +74,7 @@ struct NoAlt {
 // One 64-deep K-step from LDS: wave w multiplies its 32*kNI weight rows (row groups kNI*w ..)
 // with the 64 shared rows.  acc[ni][ti]: rows = weight rows 32*(kNI*w + ni).., columns = shared
 // rows 32ti..
+template <int DT>
 __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16 (&acc)[kNI][2]) {
   const int lane = threadIdx.x % kWave;
   const int r = lane % 32, h2 = lane / 32;
@@ -98,7 +101,7 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
 #pragma unroll
     for (int ni = 0; ni < kNI; ++ni)
 #pragma unroll
-      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32(a[kk][ni], b[kk][ti], acc[ni][ti]);
+      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32<DT>(a[kk][ni], b[kk][ti], acc[ni][ti]);
 }
 
 // Pipeline over nsteps K-steps through a ring of NST stages: while step s is multiplied, the
@@ -151,14 +154,14 @@ __device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&
   }
 }
 
-template <int NST, class AltPtr, class Offs>
+template <int DT, int NST, class AltPtr, class Offs>
 __device__ __forceinline__ void run_ring(int nsteps, bool wave_on,
                                          const uint16_t* const (&src)[kIssues], AltPtr alt_ptr,
                                          Offs offs, uint16_t* ring, f32x16 (&acc)[kNI][2]) {
   const int wave = threadIdx.x / kWave;
   run_ring_of<NST, kIssues, kStageElems>(nsteps, src, alt_ptr, offs, ring,
                                          [&](const uint16_t* stage) {
-                                           if (wave_on) mma_step(stage, wave, acc);
+                                           if (wave_on) mma_step<DT>(stage, wave, acc);
                                          });
 }
 
@@ -231,7 +234,7 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[kNI][2]) {
 // tile) and W2 [F,64] (rows of the listed blocks): acc += A2_i W2_j^T, the low-rank branch
 // z = W x + B (A x) of Sec. II-C with A2 = X A^T computed beforehand and W2 = B, both padded to
 // rank 64.
-template <int MODE, bool LORA>
+template <int DT, int MODE, bool LORA>
 __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   zero_acc(acc);
   const int blk_w = kNI * wave / 2;          // list entry (of the four) this wave works on
   const int ksteps = K / kBK;
-  run_ring<kSddStages>(ksteps + (LORA ? 1 : 0), blk_w < nb, src, src2,
+  run_ring<DT, kSddStages>(ksteps + (LORA ? 1 : 0), blk_w < nb, src, src2,
                        [=](int s, long long& ob, long long& oa) {
                          const bool alt = LORA && s == ksteps;
                          ob = oa = alt ? 0 : (long long)s * kBK;
@@ -306,21 +309,21 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
         } else if (MODE == 0) {
           if (bias) {
             const uint2 bb = *reinterpret_cast<const uint2*>(bias + j * 64 + n);
-            v[0] += bf2f(bb.x & 0xFFFFu); v[1] += bf2f(bb.x >> 16);
-            v[2] += bf2f(bb.y & 0xFFFFu); v[3] += bf2f(bb.y >> 16);
+            v[0] += to_f32<DT>(bb.x & 0xFFFFu); v[1] += to_f32<DT>(bb.x >> 16);
+            v[2] += to_f32<DT>(bb.y & 0xFFFFu); v[3] += to_f32<DT>(bb.y >> 16);
           }
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
         } else {
           const uint2 gg = *reinterpret_cast<const uint2*>(gate_act + o);
-          if (!(bf2f(gg.x & 0xFFFFu) > 0.f)) v[0] = 0.f;
-          if (!(bf2f(gg.x >> 16) > 0.f)) v[1] = 0.f;
-          if (!(bf2f(gg.y & 0xFFFFu) > 0.f)) v[2] = 0.f;
-          if (!(bf2f(gg.y >> 16) > 0.f)) v[3] = 0.f;
+          if (!(to_f32<DT>(gg.x & 0xFFFFu) > 0.f)) v[0] = 0.f;
+          if (!(to_f32<DT>(gg.x >> 16) > 0.f)) v[1] = 0.f;
+          if (!(to_f32<DT>(gg.y & 0xFFFFu) > 0.f)) v[2] = 0.f;
+          if (!(to_f32<DT>(gg.y >> 16) > 0.f)) v[3] = 0.f;
         }
         uint2 ov;
-        ov.x = pack2bf(v[0], v[1]);
-        ov.y = pack2bf(v[2], v[3]);
+        ov.x = pack2<DT>(v[0], v[1]);
+        ov.y = pack2<DT>(v[2], v[3]);
         *reinterpret_cast<uint2*>(out_act + o) = ov;
       }
   }
@@ -360,7 +363,7 @@ __device__ __forceinline__ int balanced_tile(const int* __restrict__ row_ptr, in
 // out[i-tile rows, n0 .. n0+255] = sum_s act[p_s] [64 x 64] . W[n0.., j_s*64 ..]^T (+ bias)
 // LORA: one more step with the operands act2 [T,64] (the token tile's 64 x 64 block) and
 // W2 [ncols_out, 64]: out += act2_i W2[n0..]^T, the low-rank part (dZ B) A of the input gradient.
-template <bool LORA>
+template <int DT, bool LORA>
 __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
@@ -398,7 +401,7 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   f32x16 acc[kNI][2];
   zero_acc(acc);
   const int lsteps = n_i > 0 ? n_i : 0;
-  run_ring<kDsdStages>(lsteps + (LORA ? 1 : 0), wave_on, src, src2,
+  run_ring<DT, kDsdStages>(lsteps + (LORA ? 1 : 0), wave_on, src, src2,
                [&](int s, long long& ob, long long& oa) {
                  const bool alt = LORA && s == lsteps;
                  ob = alt ? 0 : ((long long)(rs + s) * gt + i % gt) * 4096;
@@ -422,12 +425,12 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
         for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
         if (bias) {
           const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
-          v[0] += bf2f(bb.x & 0xFFFFu); v[1] += bf2f(bb.x >> 16);
-          v[2] += bf2f(bb.y & 0xFFFFu); v[3] += bf2f(bb.y >> 16);
+          v[0] += to_f32<DT>(bb.x & 0xFFFFu); v[1] += to_f32<DT>(bb.x >> 16);
+          v[2] += to_f32<DT>(bb.y & 0xFFFFu); v[3] += to_f32<DT>(bb.y >> 16);
         }
         uint2 ov;
-        ov.x = pack2bf(v[0], v[1]);
-        ov.y = pack2bf(v[2], v[3]);
+        ov.x = pack2<DT>(v[0], v[1]);
+        ov.y = pack2<DT>(v[2], v[3]);
         *reinterpret_cast<uint2*>(out + (long long)t * ncols_out + n) = ov;
       }
   }
@@ -442,7 +445,7 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
 // are dealt to the eight wavefronts (two each for NB = 4, else one; NB = 1 leaves four
 // wavefronts with the transfers only).  NB is chosen by the host so that the grid fills the
 // chip when nblk is small.
-template <int NB>
+template <int DT, int NB>
 __global__ __launch_bounds__(kThreads) void predict_bf16(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wa_t, int tiles, int K, int nblk,
     int tiles_per_group, float thr, uint8_t* __restrict__ mask) {
@@ -503,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void predict_bf16(
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-          for (int t = 0; t < kTPW; ++t) acc[t] = mfma32(a[kk], b[kk][t], acc[t]);
+          for (int t = 0; t < kTPW; ++t) acc[t] = mfma32<DT>(a[kk], b[kk][t], acc[t]);
       });
   if (!on) return;
   uint8_t* out = mask + (long long)(i / tiles_per_group) * nblk + c0 * 64 + 32 * rgrp;
@@ -525,6 +528,7 @@ __global__ __launch_bounds__(kThreads) void predict_bf16(
 // 2 x 8 products of a step (token half x k16 slice) are dealt to the eight wavefronts, which sum
 // over disjoint parts of K; the four partial sums of a token half are added in a fixed order
 // through LDS before the threshold.  Requires K % 128 == 0.
+template <int DT>
 __global__ __launch_bounds__(kThreads) void predict_half_bf16(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Wa_t, int tiles, int K, int nblk,
     int tiles_per_group, float thr, uint8_t* __restrict__ mask) {
@@ -569,7 +573,7 @@ __global__ __launch_bounds__(kThreads) void predict_half_bf16(
           b[e] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
         }
 #pragma unroll
-        for (int e = 0; e < 2; ++e) acc = mfma32(a[e], b[e], acc);
+        for (int e = 0; e < 2; ++e) acc = mfma32<DT>(a[e], b[e], acc);
       });
   // partial sums of wavefronts 2 .. 7 -> LDS; wavefronts 0, 1 add those of their token half
   float* red = reinterpret_cast<float*>(ring);
@@ -601,7 +605,8 @@ __global__ void zero_bytes_kernel(uint8_t* __restrict__ p, int n) {
 }
 
 // mask: [T/64/tiles_per_group][nblk] bytes
-hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
+template <int DT>
+static hipError_t launch_predict_bf16_t(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
                                const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st) {
   const int Tt = T / 64, total = Tt / tiles_per_group * nblk, ng = nblk / 64;
   hipLaunchKernelGGL(zero_bytes_kernel, dim3((total + 255) / 256), dim3(256), 0, st, mask, total);
@@ -611,16 +616,16 @@ hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, cons
   ProfScope ps(kKPredict, st);
   const int T8 = (Tt + 7) / 8 * 8;   // grid: 8 XCDs x chunks x ceil(Tt / 8) tiles
   if (ng % 4 == 0 && (long long)ng / 4 * Tt >= kCUs)
-    hipLaunchKernelGGL(predict_bf16<4>, dim3(ng / 4 * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
+    hipLaunchKernelGGL((predict_bf16<DT, 4>), dim3(ng / 4 * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
                        nblk, tiles_per_group, thr, mask);
   else if (ng % 2 == 0 && (long long)ng / 2 * Tt >= kCUs)
-    hipLaunchKernelGGL(predict_bf16<2>, dim3(ng / 2 * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
+    hipLaunchKernelGGL((predict_bf16<DT, 2>), dim3(ng / 2 * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
                        nblk, tiles_per_group, thr, mask);
   else if ((long long)ng * Tt < kCUs && d % 128 == 0)
-    hipLaunchKernelGGL(predict_half_bf16, dim3(2 * ng * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
+    hipLaunchKernelGGL(predict_half_bf16<DT>, dim3(2 * ng * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d,
                        nblk, tiles_per_group, thr, mask);
   else
-    hipLaunchKernelGGL(predict_bf16<1>, dim3(ng * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d, nblk,
+    hipLaunchKernelGGL((predict_bf16<DT, 1>), dim3(ng * T8), dim3(kThreads), 0, st, X, Wa_t, Tt, d, nblk,
                        tiles_per_group, thr, mask);
   return hipGetLastError();
 }
@@ -635,7 +640,8 @@ static dim3 sdd_grid(int Tt, int gt, int nnz_cap) {
   return dim3(8 * 8 * ((Lub + 7) / 8));
 }
 
-hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
+template <int DT>
+static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
@@ -647,16 +653,16 @@ hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0)
-      hipLaunchKernelGGL((ffn_sdd_bf16<0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
     else
-      hipLaunchKernelGGL((ffn_sdd_bf16<1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
+      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
-  hipLaunchKernelGGL(ffn_dsd_bf16<false>, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+  hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
                      (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap,
                      out, none, none);
   return hipGetLastError();
@@ -709,6 +715,7 @@ __device__ __forceinline__ bool fold_khalves(float* area, f32x16& acc) {
 // U = X A_pad^T (Sec. II-C: the inner factor A x of the branch) for token tile blockIdx.x over
 // the range of K-steps of blockIdx.y.  gridDim.y == 1: U [T,64] is stored as bf16; otherwise
 // fp32 partial sums part[y][T][64], which lora_u_reduce_kernel adds.
+template <int DT>
 __global__ __launch_bounds__(kThreads) void lora_u_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ A_pad, int K,
     uint16_t* __restrict__ U, float* __restrict__ part, long long part_stride) {
@@ -741,7 +748,7 @@ __global__ __launch_bounds__(kThreads) void lora_u_kernel(
           b[e] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
         }
 #pragma unroll
-        for (int e = 0; e < 2; ++e) acc = mfma32(a[e], b[e], acc);
+        for (int e = 0; e < 2; ++e) acc = mfma32<DT>(a[e], b[e], acc);
       });
   if (!fold_khalves(reinterpret_cast<float*>(ring), acc)) return;
   // register v: rank index 32*qh + 8*(v/4) + 4*h2 + v%4, token 32*th + lane%32
@@ -750,8 +757,8 @@ __global__ __launch_bounds__(kThreads) void lora_u_kernel(
   for (int g = 0; g < 4; ++g) {
     if (gridDim.y == 1) {
       uint2 ov;
-      ov.x = pack2bf(acc[4 * g], acc[4 * g + 1]);
-      ov.y = pack2bf(acc[4 * g + 2], acc[4 * g + 3]);
+      ov.x = pack2<DT>(acc[4 * g], acc[4 * g + 1]);
+      ov.y = pack2<DT>(acc[4 * g + 2], acc[4 * g + 3]);
       *reinterpret_cast<uint2*>(U + o + 8 * g) = ov;
     } else {
       const float4 ov = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
@@ -760,6 +767,7 @@ __global__ __launch_bounds__(kThreads) void lora_u_kernel(
   }
 }
 // U = bf16(sum of the parts, in order); n4 = number of groups of four elements
+template <int DT>
 __global__ void lora_u_reduce_kernel(const float* __restrict__ part, int parts, long long n4,
                                      uint16_t* __restrict__ U) {
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -770,14 +778,15 @@ __global__ void lora_u_reduce_kernel(const float* __restrict__ part, int parts, 
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   uint2 ov;
-  ov.x = pack2bf(s.x, s.y);
-  ov.y = pack2bf(s.z, s.w);
+  ov.x = pack2<DT>(s.x, s.y);
+  ov.y = pack2<DT>(s.z, s.w);
   *reinterpret_cast<uint2*>(U + idx * 4) = ov;
 }
 
 // forward: U = X A_pad^T [T,64];  H_act = ReLU(X W_up^T + U B_pad^T) on the listed blocks;
 // Y = H W_down^T.  u_part: lora_u_split(Tt, d) * T * 64 floats of scratch (unused for a split of 1).
-hipError_t launch_ffn_lora_fwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+template <int DT>
+static hipError_t launch_ffn_lora_fwd_bf16_t(int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* W_up, const uint16_t* A_pad,
                                     const uint16_t* B_pad, const uint16_t* W_down,
                                     const int* row_ptr, const int* col_idx, int nnz_cap,
@@ -789,24 +798,24 @@ hipError_t launch_ffn_lora_fwd_bf16(int Tt, int gt, int d, int F, const uint16_t
     ProfScope ps(kKLora, st);
     const int split = lora_u_split(Tt, d);
     const long long n = (long long)Tt * 4096;
-    hipLaunchKernelGGL(lora_u_kernel, dim3(Tt, split), dim3(kThreads), 0, st, X, A_pad, d, U, u_part,
+    hipLaunchKernelGGL(lora_u_kernel<DT>, dim3(Tt, split), dim3(kThreads), 0, st, X, A_pad, d, U, u_part,
                        n);
     if (split > 1)
-      hipLaunchKernelGGL(lora_u_reduce_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st,
+      hipLaunchKernelGGL(lora_u_reduce_kernel<DT>, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st,
                          (const float*)u_part, split, n / 4, U);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   {
     ProfScope ps(kKFfnUp, st);
-    hipLaunchKernelGGL((ffn_sdd_bf16<0, true>), sdd_grid(Tt, gt, nnz_cap), dim3(kThreads), 0, st, X,
+    hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, true>), sdd_grid(Tt, gt, nnz_cap), dim3(kThreads), 0, st, X,
                        W_up, none, row_ptr, col_idx, Tt, gt, d, nnz_cap, H_act, none,
                        (const uint16_t*)U, B_pad);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(kKFfnDown, st);
-  hipLaunchKernelGGL(ffn_dsd_bf16<false>, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+  hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
                      (const uint16_t*)H_act, W_down, (long long)F, none, row_ptr, col_idx, gt, d,
                      nnz_cap, Y, none, none);
   return hipGetLastError();
@@ -832,6 +841,7 @@ struct TnLane {
       }
   }
 };
+template <int DT>
 __device__ __forceinline__ void tn_step(uint32_t stage, const TnLane& lo, f32x16& acc) {
   uint4 a[2], b[2];
 #pragma unroll
@@ -842,7 +852,7 @@ __device__ __forceinline__ void tn_step(uint32_t stage, const TnLane& lo, f32x16
     b[i] = make_uint4(bl.x, bl.y, bh.x, bh.y);
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) acc = mfma32(a[i], b[i], acc);
+  for (int i = 0; i < 2; ++i) acc = mfma32<DT>(a[i], b[i], acc);
 }
 
 // Gradients of the two LoRA matrices (Sec. II-D), fp32, as sums of 64 x 64 products
@@ -855,7 +865,7 @@ __device__ __forceinline__ void tn_step(uint32_t stage, const TnLane& lo, f32x16
 //   P = G_i, Q = X_i[:, 64c ..]; out = columns 64c .. of dA [64,d].
 // The sums over the gridDim.y tile ranges go to part[y] (part_stride elements apart; with one
 // range, part is the result itself) and are added by lora_grad_reduce_kernel.
-template <int MODE>
+template <int DT, int MODE>
 __global__ __launch_bounds__(kThreads) void lora_tn_kernel(
     const uint16_t* __restrict__ P, const uint16_t* __restrict__ Q, long long ldq,
     const int* __restrict__ row_ptr, const int* __restrict__ col_idx, int Tt, int gt, int nnz_cap,
@@ -874,7 +884,7 @@ __global__ __launch_bounds__(kThreads) void lora_tn_kernel(
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-  auto step = [&](const uint16_t* stage) { tn_step(lds_addr(stage), lo, acc); };
+  auto step = [&](const uint16_t* stage) { tn_step<DT>(lds_addr(stage), lo, acc); };
   if (MODE == 1) {
     run_ring_of<kPairStages, 2, kPairElems>(
         i_hi - i_lo, src, NoAlt(),
@@ -993,7 +1003,8 @@ __global__ __launch_bounds__(256) void lora_transpose_kernel(
 // dX = dZ W_up + G A_pad;  dB = dZ^T U;  dA = G^T X.
 // Scratch: B_t [64,F], A_t [d,64], G [T,64], da_part [lora_da_split][64][d] and
 // db_part [lora_db_split][F][64] (each unused for a split of 1).
-hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+template <int DT>
+static hipError_t launch_ffn_lora_bwd_bf16_t(int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* dY, const uint16_t* H_act, const uint16_t* U,
                                     const uint16_t* W_down_t, const uint16_t* W_up_t,
                                     const uint16_t* A_pad, const uint16_t* B_pad,
@@ -1005,7 +1016,7 @@ hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t
   const uint16_t* none = nullptr;
   {
     ProfScope ps(kKFfnDh, st);
-    hipLaunchKernelGGL((ffn_sdd_bf16<1, false>), sdd_grid(Tt, gt, nnz_cap), dim3(kThreads), 0, st, dY,
+    hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false>), sdd_grid(Tt, gt, nnz_cap), dim3(kThreads), 0, st, dY,
                        W_down_t, none, row_ptr, col_idx, Tt, gt, d, nnz_cap, dZ, H_act, none, none);
   }
   hipError_t e = hipGetLastError();
@@ -1014,7 +1025,7 @@ hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t
     ProfScope ps(kKLora, st);
     hipLaunchKernelGGL(lora_transpose_kernel, dim3(d / 64 + F / 64), dim3(256), 0, st, A_pad, d, A_t,
                        B_pad, F, B_t);
-    hipLaunchKernelGGL(ffn_dsd_bf16<false>, dim3(1, Tt), dim3(kThreads), 0, st, (const uint16_t*)dZ,
+    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3(1, Tt), dim3(kThreads), 0, st, (const uint16_t*)dZ,
                        (const uint16_t*)B_t, (long long)F, none, row_ptr, col_idx, gt, 64, nnz_cap, G,
                        none, none);
   }
@@ -1022,7 +1033,7 @@ hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t
   if (e != hipSuccess) return e;
   {
     ProfScope ps(kKFfnDx, st);
-    hipLaunchKernelGGL(ffn_dsd_bf16<true>, dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+    hipLaunchKernelGGL((ffn_dsd_bf16<DT, true>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
                        (const uint16_t*)dZ, W_up_t, (long long)F, none, row_ptr, col_idx, gt, d,
                        nnz_cap, dX, (const uint16_t*)G, (const uint16_t*)A_t);
   }
@@ -1031,9 +1042,9 @@ hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t
   ProfScope ps(kKLora, st);
   const int sb = lora_db_split(Tt, F), sa = lora_da_split(Tt, d);
   const long long nb = (long long)F * 64, na = (long long)64 * d;
-  hipLaunchKernelGGL(lora_tn_kernel<0>, dim3(F / 64, sb), dim3(kThreads), 0, st, (const uint16_t*)dZ, U,
+  hipLaunchKernelGGL((lora_tn_kernel<DT, 0>), dim3(F / 64, sb), dim3(kThreads), 0, st, (const uint16_t*)dZ, U,
                      64ll, row_ptr, col_idx, Tt, gt, nnz_cap, sb > 1 ? db_part : dB, nb, 64);
-  hipLaunchKernelGGL(lora_tn_kernel<1>, dim3(d / 64, sa), dim3(kThreads), 0, st, (const uint16_t*)G, X,
+  hipLaunchKernelGGL((lora_tn_kernel<DT, 1>), dim3(d / 64, sa), dim3(kThreads), 0, st, (const uint16_t*)G, X,
                      (long long)d, row_ptr, col_idx, Tt, gt, nnz_cap, sa > 1 ? da_part : dA, na, d);
   const long long n4b = sb > 1 ? nb / 4 : 0, n4a = sa > 1 ? na / 4 : 0;
   if (n4b + n4a > 0)
@@ -1041,5 +1052,42 @@ hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t
                        st, (const float*)db_part, sb, n4b, dB, (const float*)da_part, sa, n4a, dA);
   return hipGetLastError();
 }
+
+// Entry points of this file: dt selects the element type (kBf16 or kF16).
+#define LX_BY_DT(fn, ...) (dt == kF16 ? fn<kF16>(__VA_ARGS__) : fn<kBf16>(__VA_ARGS__))
+hipError_t launch_predict_bf16(int dt, int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
+                               const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st) {
+  return LX_BY_DT(launch_predict_bf16_t, T, d, nblk, tiles_per_group, X, Wa_t, thr, mask, st);
+}
+hipError_t launch_ffn_bf16(int dt, int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
+                           const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
+                           const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
+                           uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
+                           hipStream_t st) {
+  return LX_BY_DT(launch_ffn_bf16_t, pass, Tt, gt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx,
+                  nnz_cap, act_out, act_gate, out, st);
+}
+hipError_t launch_ffn_lora_fwd_bf16(int dt, int Tt, int gt, int d, int F, const uint16_t* X,
+                                    const uint16_t* W_up, const uint16_t* A_pad,
+                                    const uint16_t* B_pad, const uint16_t* W_down,
+                                    const int* row_ptr, const int* col_idx, int nnz_cap,
+                                    uint16_t* U, uint16_t* H_act, uint16_t* Y, float* u_part,
+                                    hipStream_t st) {
+  return LX_BY_DT(launch_ffn_lora_fwd_bf16_t, Tt, gt, d, F, X, W_up, A_pad, B_pad, W_down, row_ptr,
+                  col_idx, nnz_cap, U, H_act, Y, u_part, st);
+}
+hipError_t launch_ffn_lora_bwd_bf16(int dt, int Tt, int gt, int d, int F, const uint16_t* X,
+                                    const uint16_t* dY, const uint16_t* H_act, const uint16_t* U,
+                                    const uint16_t* W_down_t, const uint16_t* W_up_t,
+                                    const uint16_t* A_pad, const uint16_t* B_pad,
+                                    const int* row_ptr, const int* col_idx, int nnz_cap,
+                                    uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
+                                    float* da_part, float* db_part, uint16_t* dX, float* dA,
+                                    float* dB, hipStream_t st) {
+  return LX_BY_DT(launch_ffn_lora_bwd_bf16_t, Tt, gt, d, F, X, dY, H_act, U, W_down_t, W_up_t,
+                  A_pad, B_pad, row_ptr, col_idx, nnz_cap, dZ, B_t, A_t, G, da_part, db_part, dX,
+                  dA, dB, st);
+}
+#undef LX_BY_DT
 
 }  // namespace lx

@@ -38,10 +38,12 @@ static void prof_clear() {
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline size_t esize(lx_dtype dt) { return dt == LX_F32 ? 4 : 2; }
+static inline bool is16(lx_dtype dt) { return dt == LX_BF16 || dt == LX_F16; }
+static inline int dt16(lx_dtype dt) { return dt == LX_F16 ? kF16 : kBf16; }   // element type of the 16-bit kernels
 
 static lx_status check_ffn(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
                            int32_t blk_n, const lx_blocklist* bl) {
-  if (dt != LX_F32 && dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (dt != LX_F32 && !is16(dt)) return LX_ERR_UNSUPPORTED;
   if (T <= 0 || d <= 0 || F <= 0 || tile_t <= 0 || blk_n <= 0) return LX_ERR_INVALID_ARG;
   if (dt == LX_F32) {
     if (!((tile_t == 32 && blk_n == 32) || (tile_t == 64 && blk_n == 64))) return LX_ERR_UNSUPPORTED;
@@ -193,7 +195,7 @@ lx_status lx_attn_combine_patterns(const lx_blocklist* pool_r, const lx_blocklis
 
 lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_up,
                               const void* W_down, void* W_up_t, void* W_down_t, void* stream) {
-  if (dt != LX_F32 && dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (dt != LX_F32 && !is16(dt)) return LX_ERR_UNSUPPORTED;
   if (d <= 0 || F <= 0) return LX_ERR_INVALID_ARG;
   if ((W_up_t && !W_up) || (W_down_t && !W_down)) return LX_ERR_INVALID_ARG;
   if (W_up_t) {
@@ -248,7 +250,7 @@ lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_
                        (const float*)b_up, (const float*)W_down, (const float*)b_down, bl->row_ptr,
                        bl->col_idx, bl->nnz_cap, (float*)act, nullptr, (float*)Y, (hipStream_t)stream);
   else
-    e = launch_ffn_bf16(0, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
+    e = launch_ffn_bf16(dt16(dt), 0, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
                         (const uint16_t*)b_up, (const uint16_t*)W_down, (const uint16_t*)b_down,
                         bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)act, nullptr, (uint16_t*)Y,
                         (hipStream_t)stream);
@@ -293,7 +295,7 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
                        (const float*)W_down_t, nullptr, (const float*)W_up_t, nullptr, bl->row_ptr,
                        bl->col_idx, bl->nnz_cap, (float*)dz, (const float*)H_act, (float*)dX, st);
   else
-    e = launch_ffn_bf16(1, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)dY,
+    e = launch_ffn_bf16(dt16(dt), 1, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)dY,
                         (const uint16_t*)W_down_t, nullptr, (const uint16_t*)W_up_t, nullptr,
                         bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)dz, (const uint16_t*)H_act,
                         (uint16_t*)dX, st);
@@ -317,7 +319,7 @@ size_t lx_sparse_ffn_lora_bwd_workspace_bytes(int32_t T, int32_t d, int32_t F, i
 
 static lx_status check_lora(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
                             int32_t blk_n, const lx_blocklist* bl) {
-  if (dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (!is16(dt)) return LX_ERR_UNSUPPORTED;
   lx_status s = check_ffn(dt, T, d, F, tile_t, blk_n, bl);
   if (s != LX_OK) return s;
   if ((int64_t)bl->nnz_cap * ((T / tile_t) / bl->rows) > (int64_t)1 << 30) return LX_ERR_INVALID_ARG;
@@ -339,7 +341,7 @@ lx_status lx_sparse_ffn_lora_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
   if (!workspace || workspace_bytes < lx_sparse_ffn_lora_fwd_workspace_bytes(T, d)) return LX_ERR_WORKSPACE;
   const int gt = (T / tile_t) / bl->rows;
   hipError_t e = launch_ffn_lora_fwd_bf16(
-      T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)W_up, (const uint16_t*)A_pad,
+      dt16(dt), T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)W_up, (const uint16_t*)A_pad,
       (const uint16_t*)B_pad, (const uint16_t*)W_down, bl->row_ptr, bl->col_idx, bl->nnz_cap,
       (uint16_t*)U, (uint16_t*)H_act, (uint16_t*)Y, (float*)workspace, (hipStream_t)stream);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
@@ -376,7 +378,7 @@ lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
   if (sa > 1) ws += round256((size_t)sa * 64 * d * 4);
   float* part_b = (float*)ws;
   hipError_t e = launch_ffn_lora_bwd_bf16(
-      T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)dY, (const uint16_t*)H_act,
+      dt16(dt), T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)dY, (const uint16_t*)H_act,
       (const uint16_t*)U, (const uint16_t*)W_down_t, (const uint16_t*)W_up_t,
       (const uint16_t*)A_pad, (const uint16_t*)B_pad, bl->row_ptr, bl->col_idx, bl->nnz_cap, dz, bt,
       at, g, part_a, part_b, (uint16_t*)dX, dA, dB, (hipStream_t)stream);
@@ -386,7 +388,7 @@ lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
 lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
                               const void* X, const void* Wa_t, float thr, uint8_t* mask,
                               void* stream) {
-  if (dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (!is16(dt)) return LX_ERR_UNSUPPORTED;
   if (T <= 0 || d <= 0 || nblk <= 0 || group_rows <= 0) return LX_ERR_INVALID_ARG;
   if (T % 64 != 0 || d % 64 != 0 || nblk % 64 != 0) return LX_ERR_UNSUPPORTED;
   if (group_rows % 64 != 0 || T % group_rows != 0) return LX_ERR_INVALID_ARG;
@@ -394,7 +396,7 @@ lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, i
   if (thr != thr) return LX_ERR_INVALID_ARG;   // NaN
   if (2ll * nblk * d >= (1ll << 31) || (int64_t)(T / 64) * nblk >= (1ll << 31))
     return LX_ERR_INVALID_ARG;
-  return launch_predict_bf16(T, d, nblk, group_rows / 64, (const uint16_t*)X, (const uint16_t*)Wa_t,
+  return launch_predict_bf16(dt16(dt), T, d, nblk, group_rows / 64, (const uint16_t*)X, (const uint16_t*)Wa_t,
                              thr, mask, (hipStream_t)stream) == hipSuccess
              ? LX_OK
              : LX_ERR_RUNTIME;
@@ -409,7 +411,7 @@ size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, in
 
 static lx_status check_attn(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                             const int64_t strides[3], const lx_blocklist* bl, int32_t mask_batch) {
-  if (dt != LX_BF16) return LX_ERR_UNSUPPORTED;
+  if (!is16(dt)) return LX_ERR_UNSUPPORTED;
   if (B <= 0 || Hh <= 0 || S <= 0 || D <= 0) return LX_ERR_INVALID_ARG;
   if (D != 64 && D != 128) return LX_ERR_UNSUPPORTED;
   if (S % 64 != 0) return LX_ERR_UNSUPPORTED;
@@ -441,7 +443,7 @@ lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int3
   a.row_ptr = bl->row_ptr; a.col_idx = bl->col_idx; a.nnz_cap = bl->nnz_cap;
   a.head_active = head_active;
   a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
-  return launch_attn_fwd_bf16(D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+  return launch_attn_fwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
 lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
@@ -472,7 +474,7 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
   a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx; a.cnnz_cap = bl_cols->nnz_cap;
   a.head_active = head_active;
   a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
-  return launch_attn_bwd_bf16(D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+  return launch_attn_bwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
 }  // extern "C"

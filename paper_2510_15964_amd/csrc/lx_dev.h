@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "lx_launch.h"   // kBf16 / kF16
+
 namespace lx {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -11,29 +13,41 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 
-// float -> bfloat16 bits, round to nearest even (inputs are finite).
-__device__ __forceinline__ uint32_t f2bf(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-// two floats -> packed bfloat16 pair (round to nearest even) in one v_cvt_pk_bf16_f32
+// The 16-bit kernels are templates over the element type of their operands: DT = kBf16
+// (bfloat16) or kF16 (IEEE half).  Storage is uint16_t either way; products accumulate in fp32.
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+// two floats -> packed pair of 16-bit elements, round to nearest even
+template <int DT>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  if constexpr (DT == kF16)
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+  else
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
-__device__ __forceinline__ float bf2f(uint32_t bits16) {
-  return __builtin_bit_cast(float, bits16 << 16);
+// 16-bit element (in the low half of the argument) -> float
+template <int DT>
+__device__ __forceinline__ float to_f32(uint32_t bits16) {
+  if constexpr (DT == kF16)
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+  else
+    return __builtin_bit_cast(float, bits16 << 16);
 }
 
-// 32x32x16 bf16 MFMA.  Operand a: lane l holds row (l % 32), k = 8*(l/32)..+7.
+// 32x32x16 MFMA on 16-bit operands.  Operand a: lane l holds row (l % 32), k = 8*(l/32)..+7.
 // Operand b: lane l holds column (l % 32), same k.  Accumulator register v of
 // lane l is C[8*(v/4) + 4*(l/32) + v%4][l % 32].
+template <int DT>
 __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  if constexpr (DT == kF16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
 // Asynchronous 16-byte-per-lane copy global -> LDS (global_load_lds_dwordx4): lane l of the

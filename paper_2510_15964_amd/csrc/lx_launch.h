@@ -6,6 +6,8 @@
 namespace lx {
 
 constexpr int kCUs = 256;   // compute units of the chip
+// element types of the 16-bit kernels (the `dt` argument of their launchers)
+constexpr int kBf16 = 0, kF16 = 1;
 
 // Kernel ids of the profiling aid (values are part of the C ABI: lx_kernel in lx.h).
 enum KernelId {
@@ -67,7 +69,7 @@ hipError_t launch_ffn_f32(int pass, int tile, int Tt, int gt, int Fb, int d, int
                           const float* W1, const float* b1, const float* W2, const float* b2,
                           const int* row_ptr, const int* col_idx, int nnz_cap, float* act_out,
                           const float* act_gate, float* out, hipStream_t st);
-hipError_t launch_ffn_bf16(int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
+hipError_t launch_ffn_bf16(int dt, int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
@@ -88,13 +90,13 @@ inline int lora_db_split(int Tt, int F) {
 inline int lora_da_split(int Tt, int d) {
   return lora_clamp((kCUs + d / 64 - 1) / (d / 64), Tt < 32 ? Tt : 32);
 }
-hipError_t launch_ffn_lora_fwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+hipError_t launch_ffn_lora_fwd_bf16(int dt, int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* W_up, const uint16_t* A_pad,
                                     const uint16_t* B_pad, const uint16_t* W_down,
                                     const int* row_ptr, const int* col_idx, int nnz_cap,
                                     uint16_t* U, uint16_t* H_act, uint16_t* Y, float* u_part,
                                     hipStream_t st);
-hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t* X,
+hipError_t launch_ffn_lora_bwd_bf16(int dt, int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* dY, const uint16_t* H_act, const uint16_t* U,
                                     const uint16_t* W_down_t, const uint16_t* W_up_t,
                                     const uint16_t* A_pad, const uint16_t* B_pad,
@@ -102,11 +104,11 @@ hipError_t launch_ffn_lora_bwd_bf16(int Tt, int gt, int d, int F, const uint16_t
                                     uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
                                     float* da_part, float* db_part, uint16_t* dX, float* dA,
                                     float* dB, hipStream_t st);
-hipError_t launch_predict_bf16(int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
+hipError_t launch_predict_bf16(int dt, int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
                                const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);
-hipError_t launch_attn_fwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
-hipError_t launch_attn_bwd_bf16(int D, int B, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_fwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_bwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t set_attn_rows_per_wg(int r);   // 0 = automatic
 
 }  // namespace lx

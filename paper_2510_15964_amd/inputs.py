@@ -11,9 +11,9 @@ sparsity with strongly skewed per-neuron activity, and head-specific block
 masks for attention.  They stand in for OPT weights and the E2E / Alpaca
 activations used in Sec. VII, which are not available here.
 
-All arrays are numpy float32.  For dtype "bf16" every value is rounded to the
-nearest bfloat16 (ties to even) and then widened again, so that a bf16 device
-tensor and the float32 array given to the oracle hold identical numbers.
+All arrays are numpy float32.  For dtype "bf16" (or "f16") every value is rounded
+to the nearest bfloat16 (IEEE half; ties to even) and then widened again, so that a
+16-bit device tensor and the float32 array given to the oracle hold identical numbers.
 """
 from __future__ import annotations
 
@@ -38,13 +38,20 @@ def bf16_round(x: np.ndarray) -> np.ndarray:
     return b.view(np.float32).reshape(np.shape(x))
 
 
+def f16_round(x: np.ndarray) -> np.ndarray:
+    """float32 -> nearest IEEE half (ties to even), returned widened to float32."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
 def _store(x: np.ndarray, dtype: str) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.float32)
     if dtype == "bf16":
         return bf16_round(x)
+    if dtype == "f16":
+        return f16_round(x)
     if dtype == "f32":
         return x
-    raise ValueError(f"dtype must be 'f32' or 'bf16', got {dtype!r}")
+    raise ValueError(f"dtype must be 'f32', 'bf16' or 'f16', got {dtype!r}")
 
 
 def _rng(seed: int, stream: int) -> np.random.Generator:
@@ -117,8 +124,7 @@ def ffn_planted_support(T, d, F, tile_t, blk_n, beta_a, beta_b, seed,
 
     sigma_c = w_std * np.sqrt(float(d - G))
     gamma = np.float32(4.0)
-    beta = bf16_round(np.float32(12.0 * sigma_c / gamma)) if dtype == "bf16" \
-        else np.float32(12.0 * sigma_c / gamma)
+    beta = _store(np.array([12.0 * sigma_c / gamma], np.float32), dtype)[0]
     X[:, d - G:] = 0.0
     tile_of_token = np.arange(T) // tile_t
     X[np.arange(T), d - G + tile_of_token] = gamma
@@ -194,10 +200,10 @@ def config2_ffn(seed=2000):
     return ffn_planted_support(4096, 2048, 8192, 64, 64, 0.5, 4.0, seed)
 
 
-def config3_attn(seed=3000, force_diagonal=False):
+def config3_attn(seed=3000, force_diagonal=False, dtype="bf16"):
     """OPT-1.3B-shaped causal attention, bf16, 30 % of causal 64x64 blocks,
     heads kept with probability 7/8."""
-    return attn_blocks(8, 32, 1024, 64, 0.30, seed, head_keep=0.875,
+    return attn_blocks(8, 32, 1024, 64, 0.30, seed, dtype=dtype, head_keep=0.875,
                        force_diagonal=force_diagonal)
 
 

@@ -24,7 +24,7 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 LX_OK, LX_ERR_INVALID_ARG, LX_ERR_UNSUPPORTED, LX_ERR_WORKSPACE, LX_ERR_RUNTIME = range(5)
-LX_F32, LX_BF16 = 0, 1
+LX_F32, LX_BF16, LX_F16 = 0, 1, 2
 
 EXPORTS = (
     "lx_status_string", "lx_mask_compact", "lx_mask_compact_pair", "lx_mask_compact_batch", "lx_ffn_pack_weights",
@@ -123,6 +123,8 @@ def _dt(t: torch.Tensor) -> int:
         return LX_F32
     if t.dtype == torch.bfloat16:
         return LX_BF16
+    if t.dtype == torch.float16:
+        return LX_F16
     raise LxError(LX_ERR_UNSUPPORTED, f"dtype {t.dtype}")
 
 

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2510_15964_amd import inputs
-from util import FRO, TOL, dev, host, rel_err, rel_err_fro, rel_err_max
+from util import FRO, TOL, dev, host, rel_err, rel_err_fro, rel_err_max, lx_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +22,7 @@ def run_gpu(lx, c, layout="bhsd"):
     B, Hh, S, D = c["B"], c["Hh"], c["S"], c["D"]
 
     def place(a):
-        t = dev(a, "bf16")
+        t = dev(a, c.get("dtype", "bf16"))
         if layout == "bshd":                      # [B,S,Hh,D] storage viewed as [B,Hh,S,D]
             t = t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
         return t
@@ -37,7 +37,7 @@ def run_gpu(lx, c, layout="bhsd"):
     lx.lx_sparse_attn_fwd(Q, K, V, bl_r, c["scale"], c["causal"], O, LSE,
                           mask_batch=c["mask_batch"], head_active=ha)
     dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
-    ws = torch.empty(lx.lx_sparse_attn_bwd_workspace_bytes(lx.LX_BF16, B, Hh, S, D),
+    ws = torch.empty(lx.lx_sparse_attn_bwd_workspace_bytes(lx_dtype(lx, c.get("dtype", "bf16")), B, Hh, S, D),
                      dtype=torch.uint8, device="cuda")
     lx.lx_sparse_attn_bwd_dx(Q, K, V, O, LSE, dO, bl_r, bl_c, c["scale"], c["causal"], dQ, dK, dV,
                              ws, mask_batch=c["mask_batch"], head_active=ha)
@@ -53,9 +53,9 @@ def run_oracle(oracle, c):
     return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV)
 
 
-def check(got, ref, label="", fro_grad=None):
-    tol = TOL["bf16"]
-    fro_gate = {k: FRO["bf16"] for k in ("O", "dQ", "dK", "dV")}
+def check(got, ref, label="", fro_grad=None, dtype="bf16"):
+    tol = TOL[dtype]
+    fro_gate = {k: FRO[dtype] for k in ("O", "dQ", "dK", "dV")}
     if fro_grad is not None:
         fro_gate.update(dQ=fro_grad, dK=fro_grad, dV=fro_grad)
     ninf = np.isneginf(ref["LSE"])
@@ -70,7 +70,7 @@ def check(got, ref, label="", fro_grad=None):
         assert np.isfinite(got[k]).all(), k
         assert errs[k] <= tol, (k, errs[k])
         assert fro[k] <= fro_gate[k], (k, fro[k])
-    assert errs["LSE"] <= 2e-2       # absolute, natural-log units
+    assert errs["LSE"] <= tol        # absolute, natural-log units
     # rows with no allowed key: exact zeros
     assert not got["O"][ninf].any() and not got["dQ"][ninf].any()
 

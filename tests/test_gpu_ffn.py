@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2510_15964_amd import inputs
-from util import FRO, TOL, compact_blocks, dev, host, rel_err, rel_err_fro, rel_err_max, round_to
+from util import FRO, TOL, compact_blocks, dev, host, rel_err, rel_err_fro, rel_err_max, round_to, lx_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -42,7 +42,7 @@ def run_gpu(lx, c, mask=None, packed=True, bias=False, h_from=None):
         H_in[:nnz * tt * bn] = dev(h_from.reshape(-1), dt)
     else:
         H_in = H_act
-    dtc = lx.LX_F32 if dt == "f32" else lx.LX_BF16
+    dtc = lx_dtype(lx, dt)
     ws_bytes = lx.lx_sparse_ffn_bwd_workspace_bytes(dtc, T, d, F, tt, bn, cap, 1 if packed else 0)
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
     dX = torch.full((T, d), float("nan"), dtype=tdt, device="cuda")
@@ -224,7 +224,7 @@ def test_list_longer_than_its_capacity_is_truncated(lx, dtype, tile):
         Y = torch.full_like(X, float("nan"))
         lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, tile, tile, Y, H)
         assert torch.isnan(H[nnz_cap * tile * tile:]).all(), "wrote past the H_act buffer"
-        dtc = lx.LX_F32 if dtype == "f32" else lx.LX_BF16
+        dtc = lx_dtype(lx, dtype)
         ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(dtc, c["T"], c["d"], c["F"], tile,
                                                               tile, nnz_cap, 0) + 256,
                          dtype=torch.uint8, device="cuda")
@@ -288,7 +288,7 @@ def test_list_rows_shared_by_groups_of_token_tiles(lx, oracle, dtype, tile, T, d
     ref_H = _grouped_compact(H, rows_mask, gt, tile, tile)
     H_in = torch.zeros_like(Hd)
     H_in[:nnz * tile * tile] = dev(_grouped_compact(Hq, rows_mask, gt, tile, tile).reshape(-1), dtype)
-    dtc = lx.LX_F32 if dtype == "f32" else lx.LX_BF16
+    dtc = lx_dtype(lx, dtype)
     ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(dtc, T, d, F, tile, tile, nblocks, 0) + 256,
                      dtype=torch.uint8, device="cuda")
     dXd = torch.full_like(X, float("nan"))

@@ -17,13 +17,13 @@ def lx():
     return lx
 
 
-def make_case(T, d, F, r, density, seed, rows=None):
-    c = inputs.ffn_bernoulli(T, d, F, 64, 64, density, seed, dtype="bf16", w_std=0.05)
+def make_case(T, d, F, r, density, seed, rows=None, dtype="bf16"):
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, density, seed, dtype=dtype, w_std=0.05)
     rng = np.random.default_rng(seed + 17)
     A = np.zeros((64, d), np.float32)
     B = np.zeros((F, 64), np.float32)
-    A[:r] = inputs.bf16_round((rng.standard_normal((r, d)) / np.sqrt(d)).astype(np.float32))
-    B[:, :r] = inputs.bf16_round((rng.standard_normal((F, r)) * 0.05).astype(np.float32))
+    A[:r] = round_to(rng.standard_normal((r, d)) / np.sqrt(d), dtype)
+    B[:, :r] = round_to(rng.standard_normal((F, r)) * 0.05, dtype)
     c.update(A_pad=A, B_pad=B, r=r)
     if rows is not None:                      # list rows shared by groups of token tiles
         m = c["mask"][:rows]
@@ -45,10 +45,10 @@ def grouped_compact(a, mask_rows, gt):
 
 def run_both(lx, oracle, c):
     import torch
-    T, d, F, r = c["T"], c["d"], c["F"], c["r"]
+    T, d, F, r, dt = c["T"], c["d"], c["F"], c["r"], c["dtype"]
     lm = c.get("list_mask", c["mask"])
     gt = (T // 64) // lm.shape[0]
-    X, Wu, Wd, dY, Ap, Bp = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down", "dY", "A_pad", "B_pad"))
+    X, Wu, Wd, dY, Ap, Bp = (dev(c[k], dt) for k in ("X", "W_up", "W_down", "dY", "A_pad", "B_pad"))
     bl = lx.lx_mask_compact(torch.from_numpy(lm).cuda())
     nblk = max(bl.nnz_cap * gt, 1)
     H_act = torch.full((nblk * 4096 + 4096,), float("nan"), dtype=X.dtype, device="cuda")
@@ -62,16 +62,16 @@ def run_both(lx, oracle, c):
     assert torch.isnan(H_act[nblk * 4096:]).all()
     ref = dict(U=np.pad(Uo, ((0, 0), (0, 64 - r))), Y=Yo, H=grouped_compact(Ho, lm, gt))
     # backward: both sides take the oracle's stored activations and U, rounded to the run dtype
-    Hq, Uq = round_to(Ho, "bf16"), round_to(ref["U"], "bf16")
+    Hq, Uq = round_to(Ho, dt), round_to(ref["U"], dt)
     H_in = torch.zeros_like(H_act)
-    H_in[:nnz * gt * 4096] = dev(grouped_compact(Hq, lm, gt).reshape(-1), "bf16")
+    H_in[:nnz * gt * 4096] = dev(grouped_compact(Hq, lm, gt).reshape(-1), dt)
     Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
     ws = torch.empty(lx.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, bl.nnz_cap * gt), dtype=torch.uint8,
                      device="cuda")
     dX = torch.full_like(X, float("nan"))
     dA = torch.full((64, d), float("nan"), dtype=torch.float32, device="cuda")
     dB = torch.full((F, 64), float("nan"), dtype=torch.float32, device="cuda")
-    lx.lx_sparse_ffn_lora_bwd(X, dY, H_in, dev(Uq, "bf16"), Wut, Wdt, Ap, Bp, bl, dX, dA, dB, ws)
+    lx.lx_sparse_ffn_lora_bwd(X, dY, H_in, dev(Uq, dt), Wut, Wdt, Ap, Bp, bl, dX, dA, dB, ws)
     torch.cuda.synchronize()
     g = oracle.ffn_lora_bwd(c["X"], c["dY"], c["W_up"], c["A_pad"][:r], c["B_pad"][:, :r], c["W_down"],
                             c["mask"], Hq > 0, Uq[:, :r], 64, 64)
@@ -80,7 +80,7 @@ def run_both(lx, oracle, c):
     return got, ref
 
 
-def check(got, ref, label):
+def check(got, ref, label, dtype="bf16"):
     errs, fro = {}, {}
     for k in ("U", "H", "Y", "dX", "dA", "dB"):
         assert np.isfinite(got[k]).all(), k
@@ -90,8 +90,8 @@ def check(got, ref, label):
         errs[k], fro[k] = rel_err_max(got[k], ref[k]), rel_err_fro(got[k], ref[k])
     print(f"[lora {label}] max-rel {errs} fro {fro}", flush=True)
     for k in errs:
-        assert errs[k] <= TOL["bf16"], (k, errs[k])
-        assert fro[k] <= FRO["bf16"], (k, fro[k])
+        assert errs[k] <= TOL[dtype], (k, errs[k])
+        assert fro[k] <= FRO[dtype], (k, fro[k])
 
 
 @pytest.mark.parametrize("T,d,F,r,density,seed", [

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2510_15964_amd import inputs
-from util import dev, host
+from util import dev, host, round_to
 
 pytestmark = pytest.mark.gpu
 
@@ -17,14 +17,14 @@ def lx():
     return lx
 
 
-def _case(T, d, nblk, seed):
+def _case(T, d, nblk, seed, dtype="bf16"):
     rng = np.random.default_rng(seed)
-    X = inputs.bf16_round(rng.standard_normal((T, d)).astype(np.float32))
-    Wa_t = inputs.bf16_round((rng.standard_normal((nblk, d)) / np.sqrt(d)).astype(np.float32))
+    X = round_to(rng.standard_normal((T, d)), dtype)
+    Wa_t = round_to(rng.standard_normal((nblk, d)) / np.sqrt(d), dtype)
     return X, Wa_t
 
 
-def _check(lx, oracle, X, Wa_t, thr, group):
+def _check(lx, oracle, X, Wa_t, thr, group, dtype="bf16"):
     """The decision is made on fp32 sums of bf16 products on the GPU and in fp64 in the oracle:
     both must agree wherever the oracle's scores of a (group, block) are not within rounding
     distance of the threshold; inside that band either value is valid."""
@@ -32,7 +32,7 @@ def _check(lx, oracle, X, Wa_t, thr, group):
     T, d = X.shape
     nblk = Wa_t.shape[0]
     S, M = oracle.mlp_predict(X, np.ascontiguousarray(Wa_t.T), thr, group_rows=group)
-    got = host(lx.lx_mlp_predict_mask(dev(X, "bf16"), dev(Wa_t, "bf16"), float(thr), group))
+    got = host(lx.lx_mlp_predict_mask(dev(X, dtype), dev(Wa_t, dtype), float(thr), group))
     assert got.shape == M.shape and set(np.unique(got)) <= {0, 1}
     # fp32 accumulation of d products of magnitude |x||w|: a few ulp of the running sum
     band = 4 * np.finfo(np.float32).eps * np.sqrt(d) * (np.abs(X).astype(np.float64) @ np.abs(Wa_t.T).astype(np.float64)).max()

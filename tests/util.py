@@ -14,8 +14,10 @@ import numpy as np
 # in scale by an order of magnitude (a query with one allowed key vs. hundreds;
 # the gate channels of the planted-support FFN input) read 0.03-0.06 on it even
 # for an ideal pipeline that is exact apart from rounding P / dS / dZ to bf16.
-TOL = {"f32": 1e-5, "bf16": 2e-2}
-FRO = {"f32": 2e-6, "bf16": 5e-3}
+# IEEE half ("f16") carries three more significand bits than bfloat16: its gates are an
+# eighth of bfloat16's.
+TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2.5e-3}
+FRO = {"f32": 2e-6, "bf16": 5e-3, "f16": 6.25e-4}
 
 
 def rel_err(got, ref) -> float:
@@ -53,7 +55,12 @@ def rel_err_fro(got, ref) -> float:
 
 def torch_dtype(name):
     import torch
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[name]
+
+
+def lx_dtype(lx, name):
+    """The library's dtype code of a run dtype name."""
+    return {"f32": lx.LX_F32, "bf16": lx.LX_BF16, "f16": lx.LX_F16}[name]
 
 
 def dev(a, dtype="f32"):
@@ -69,9 +76,9 @@ def host(t):
 
 def round_to(a, dtype):
     """Round an fp64/fp32 array to the run dtype, returned as float32."""
-    from paper_2510_15964_amd.inputs import bf16_round
+    from paper_2510_15964_amd.inputs import bf16_round, f16_round
     a32 = np.asarray(a, dtype=np.float32)
-    return bf16_round(a32) if dtype == "bf16" else a32
+    return bf16_round(a32) if dtype == "bf16" else f16_round(a32) if dtype == "f16" else a32
 
 
 def compact_blocks(dense, mask, tile_t, blk_n):
