@@ -45,6 +45,12 @@ typedef enum {
   LX_ERR_RUNTIME = 4      /* a HIP launch reported an error */
 } lx_status;
 
+/*
+ * Element type of the tensors of a call.  LX_BF16 and LX_F16 (IEEE half, the parameter
+ * precision of Sec. VII-A) run the same kernels: 16-bit operands, products accumulated in
+ * fp32, outputs rounded to nearest even; softmax statistics and the gradients of the LoRA
+ * matrices are fp32 for both.  LX_F32 is the correctness configuration of the FFN.
+ */
 typedef enum { LX_F32 = 0, LX_BF16 = 1, LX_F16 = 2 } lx_dtype;
 
 /*
@@ -201,7 +207,7 @@ size_t lx_sparse_ffn_bwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int3
  *          elements; the buffer holds nnz_cap*gt blocks (gt = 1: [nnz_cap]
  *          blocks in list order).
  * Supported: LX_F32 with (tile_t, blk_n) in {(32,32),(64,64)}, d % 32 == 0;
- *            LX_BF16 with (64,64), d % 64 == 0.
+ *            LX_BF16 / LX_F16 with (64,64), d % 64 == 0.
  */
 lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
                             int32_t blk_n, const void* X, const void* W_up, const void* b_up,
@@ -229,7 +235,7 @@ lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int
  * backward pass for what was inactive in the forward pass).  A [r,d] and B [F,r]
  * are handed over zero-padded to rank 64: A_pad [64,d] (rows r.. zero), B_pad
  * [F,64] (columns r.. zero); the padding costs nothing in accuracy and its
- * gradients come out zero.  LX_BF16, 64 x 64 blocks only.
+ * gradients come out zero.  LX_BF16 / LX_F16, 64 x 64 blocks only.
  *
  * Forward, for every listed (i, j):
  *   U = X A_pad^T [T,64];  H_ij = ReLU(X_i W_up_j^T + U_i B_pad_j^T);  Y_i = sum_j H_ij W_down_j^T
@@ -277,7 +283,7 @@ lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
  *          no workspace)
  * The comparison is made on fp32 sums of bf16 products; a score within rounding
  * distance of thr may fall on either side.
- * Supported: LX_BF16, d % 64 == 0, nblk % 64 == 0, T % 64 == 0, group_rows a
+ * Supported: LX_BF16 / LX_F16, d % 64 == 0, nblk % 64 == 0, T % 64 == 0, group_rows a
  * multiple of 64 that divides T.
  */
 lx_status lx_mlp_predict_mask(lx_dtype dt, int32_t T, int32_t d, int32_t nblk, int32_t group_rows,
@@ -305,7 +311,7 @@ size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, in
  *            mask_batch is 1 (mask shared over the batch, Sec. V-A) or B.
  *   head_active  uint8[Hh] or NULL (all heads active)
  *   LSE      out float32 [B,Hh,S] contiguous
- * Supported: LX_BF16, D in {64, 128}, S % 64 == 0.
+ * Supported: LX_BF16 / LX_F16, D in {64, 128}, S % 64 == 0.
  */
 lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                              float scale, int32_t causal, const void* Q, const void* K,

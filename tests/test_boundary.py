@@ -239,3 +239,22 @@ def test_ffn_lora_validation(lxmod):
     assert L.lx_sparse_ffn_lora_bwd_workspace_bytes(0, 128, 1024, 16) == 0
     assert (L.lx_sparse_ffn_lora_bwd_workspace_bytes(T, d, F, 128)
             >= 128 * 8192 + 64 * F * 2 + d * 64 * 2 + T * 64 * 2)
+
+
+def test_half_precision_is_accepted_where_bfloat16_is(lxmod):
+    """LX_F16 passes the dtype check of every 16-bit entry point (the next check then fails on
+    the deliberately bad argument); unknown dtype codes and fp32 where it is not built do not."""
+    L = lxmod
+    bl = _bl(L, 8, 16)
+    for dt in (L.LX_BF16, L.LX_F16):
+        assert _ffn_fwd(L, dt, 512, 128, 1024, 64, 64, bl, X=None) == L.LX_ERR_INVALID_ARG
+        assert _ffn_fwd(L, dt, 512, 128, 1024, 32, 32, _bl(L, 16, 32)) == L.LX_ERR_UNSUPPORTED
+        assert L._lib.lx_mlp_predict_mask(dt, 512, 128, 128, 512, None, FAKE, 1.0, FAKE,
+                                          None) == L.LX_ERR_INVALID_ARG
+        assert L._lib.lx_sparse_ffn_lora_fwd(dt, 512, 128, 1024, 64, 64, None, FAKE, FAKE, FAKE, FAKE,
+                                             C.byref(bl), FAKE, FAKE, FAKE, FAKE, 1 << 30,
+                                             None) == L.LX_ERR_INVALID_ARG
+        assert L.lx_sparse_ffn_bwd_workspace_bytes(dt, 512, 128, 1024, 64, 64, 128, 1) == 128 * 8192
+    assert _ffn_fwd(L, 3, 512, 128, 1024, 64, 64, bl) == L.LX_ERR_UNSUPPORTED
+    assert L._lib.lx_mlp_predict_mask(L.LX_F32, 512, 128, 128, 512, FAKE, FAKE, 1.0, FAKE,
+                                      None) == L.LX_ERR_UNSUPPORTED
