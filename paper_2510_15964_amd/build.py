@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblx_sparse.so")
-SOURCES = ["lx_api.hip", "compact.hip", "ffn_f32.hip", "ffn_bf16.hip", "attn_bf16.hip"]
+SOURCES = ["lx_api.hip", "compact.hip", "ffn_f32.hip", "ffn_bf16.hip", "predict_bf16.hip", "lora_bf16.hip",
+           "attn_bf16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -90,6 +90,15 @@ inline int lora_db_split(int Tt, int F) {
 inline int lora_da_split(int Tt, int d) {
   return lora_clamp((kCUs + d / 64 - 1) / (d / 64), Tt < 32 ? Tt : 32);
 }
+// the small products of the LoRA branch (lora_bf16.hip); dt = kBf16 or kF16
+hipError_t launch_lora_u(int dt, int Tt, int d, const uint16_t* X, const uint16_t* A_pad, uint16_t* U,
+                         float* u_part, hipStream_t st);
+hipError_t launch_lora_transposes(int d, int F, const uint16_t* A_pad, uint16_t* A_t,
+                                  const uint16_t* B_pad, uint16_t* B_t, hipStream_t st);
+hipError_t launch_lora_grads(int dt, int Tt, int gt, int d, int F, const uint16_t* dZ,
+                             const uint16_t* U, const uint16_t* G, const uint16_t* X,
+                             const int* row_ptr, const int* col_idx, int nnz_cap, float* da_part,
+                             float* db_part, float* dA, float* dB, hipStream_t st);
 hipError_t launch_ffn_lora_fwd_bf16(int dt, int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* W_up, const uint16_t* A_pad,
                                     const uint16_t* B_pad, const uint16_t* W_down,
