@@ -374,7 +374,7 @@ static hipError_t launch_ffn_lora_fwd_bf16_t(int Tt, int gt, int d, int F, const
 
 // backward: dZ = (dY W_down) (.) [H > 0] on the listed blocks;  G = dZ B_pad [T,64];
 // dX = dZ W_up + G A_pad;  dB = dZ^T U;  dA = G^T X.
-// Scratch: B_t [64,F], A_t [d,64], G [T,64], da_part [lora_da_split][64][d] and
+// Scratch: B_t [64,F], A_t [d,64], G [T,64], g_part [lora_g_split][T][64], da_part [lora_da_split][64][d] and
 // db_part [lora_db_split][F][64] (each unused for a split of 1).
 template <int DT>
 static hipError_t launch_ffn_lora_bwd_bf16_t(int Tt, int gt, int d, int F, const uint16_t* X,
@@ -383,8 +383,8 @@ static hipError_t launch_ffn_lora_bwd_bf16_t(int Tt, int gt, int d, int F, const
                                     const uint16_t* A_pad, const uint16_t* B_pad,
                                     const int* row_ptr, const int* col_idx, int nnz_cap,
                                     uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
-                                    float* da_part, float* db_part, uint16_t* dX, float* dA,
-                                    float* dB, hipStream_t st) {
+                                    float* g_part, float* da_part, float* db_part, uint16_t* dX,
+                                    float* dA, float* dB, hipStream_t st) {
   if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
   const uint16_t* none = nullptr;
   {
@@ -398,9 +398,8 @@ static hipError_t launch_ffn_lora_bwd_bf16_t(int Tt, int gt, int d, int F, const
     ProfScope ps(kKLora, st);
     const hipError_t et = launch_lora_transposes(d, F, A_pad, A_t, B_pad, B_t, st);
     if (et != hipSuccess) return et;
-    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3(1, Tt), dim3(kThreads), 0, st, (const uint16_t*)dZ,
-                       (const uint16_t*)B_t, (long long)F, none, row_ptr, col_idx, gt, 64, nnz_cap, G,
-                       none, none);
+    const hipError_t eg = launch_lora_g(DT, Tt, gt, F, dZ, B_t, row_ptr, col_idx, nnz_cap, G, g_part, st);
+    if (eg != hipSuccess) return eg;
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -441,10 +440,10 @@ hipError_t launch_ffn_lora_bwd_bf16(int dt, int Tt, int gt, int d, int F, const 
                                     const uint16_t* A_pad, const uint16_t* B_pad,
                                     const int* row_ptr, const int* col_idx, int nnz_cap,
                                     uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
-                                    float* da_part, float* db_part, uint16_t* dX, float* dA,
-                                    float* dB, hipStream_t st) {
+                                    float* g_part, float* da_part, float* db_part, uint16_t* dX,
+                                    float* dA, float* dB, hipStream_t st) {
   return LX_BY_DT(launch_ffn_lora_bwd_bf16_t, Tt, gt, d, F, X, dY, H_act, U, W_down_t, W_up_t,
-                  A_pad, B_pad, row_ptr, col_idx, nnz_cap, dZ, B_t, A_t, G, da_part, db_part, dX,
+                  A_pad, B_pad, row_ptr, col_idx, nnz_cap, dZ, B_t, A_t, G, g_part, da_part, db_part, dX,
                   dA, dB, st);
 }
 

@@ -46,29 +46,50 @@ __device__ __forceinline__ bool fold_khalves(float* area, f32x16& acc) {
   return true;
 }
 
-// U = X A_pad^T (Sec. II-C: the inner factor A x of the branch) for token tile blockIdx.x over
-// the range of K-steps of blockIdx.y.  gridDim.y == 1: U [T,64] is stored as bf16; otherwise
-// fp32 partial sums part[y][T][64], which lora_u_reduce_kernel adds.
-template <int DT>
-__global__ __launch_bounds__(kThreads) void lora_u_kernel(
-    const uint16_t* __restrict__ X, const uint16_t* __restrict__ A_pad, int K,
+// out[t][q] = sum over steps of sum_k P_s[t][k] Q_s[q][k] for token tile blockIdx.x ([64 x 64], both
+// operands read along their rows) over the range of steps of blockIdx.y.
+// MODE 0, U = X A_pad^T (Sec. II-C: the inner factor A x of the branch): P = X, Q = A_pad, row
+//   stride ld of both; the steps are the ld / 64 chunks of K.
+// MODE 1, G = dZ B_pad (Sec. II-D: the gradient that reaches A x): P = the compact blocks dZ_ij of
+//   the tile's list, Q = B_t [64, ld]; the steps are the list entries, step s takes the columns
+//   64 j_s .. of B_t.
+// gridDim.y == 1: out [T,64] is stored in the element type; otherwise fp32 partial sums
+// part[y][T][64], which lora_u_reduce_kernel adds.
+template <int DT, int MODE>
+__global__ __launch_bounds__(kThreads) void lora_nt_kernel(
+    const uint16_t* __restrict__ P, const uint16_t* __restrict__ Q, int ld,
+    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, int gt, int nnz_cap,
     uint16_t* __restrict__ U, float* __restrict__ part, long long part_stride) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kPairStages * kPairElems];
-  const int i = blockIdx.x, ksteps = K / kBK;
-  const int per = (ksteps + gridDim.y - 1) / gridDim.y;
-  const int s_lo = blockIdx.y * per, s_hi = min(ksteps, s_lo + per);
+  const int i = blockIdx.x;
+  int rs = 0, nsteps = ld / kBK;
+  if (MODE == 1) {
+    rs = row_ptr[i / gt];
+    nsteps = max(min(row_ptr[i / gt + 1], nnz_cap) - rs, 0);   // entries beyond the capacity are ignored
+  }
+  const int per = (nsteps + gridDim.y - 1) / gridDim.y;
+  const int s_lo = blockIdx.y * per, s_hi = min(nsteps, s_lo + per);
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int th = wave % 2, qh = (wave / 2) % 2, kh = wave / 4;
   const int r = lane % 32, h2 = lane / 32;
   const uint16_t* src[2];
-  pair_src(X + (long long)i * 64 * K, K, A_pad, K, src);
+  if (MODE == 0)
+    pair_src(P + (long long)i * 64 * ld, ld, Q, ld, src);
+  else
+    pair_src(P, 64, Q, ld, src);
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   run_ring_of<kPairStages, 2, kPairElems>(
       s_hi - s_lo, src, NoAlt(),
       [=](int s, long long& ob, long long& oa) {
-        ob = oa = (long long)(s_lo + s) * kBK;
+        if (MODE == 0) {
+          ob = oa = (long long)(s_lo + s) * kBK;
+        } else {
+          const int e = rs + s_lo + s;
+          ob = ((long long)e * gt + i % gt) * 4096;
+          oa = (long long)col_idx[e] * 64;
+        }
         return false;
       },
       ring,
@@ -100,7 +121,8 @@ __global__ __launch_bounds__(kThreads) void lora_u_kernel(
     }
   }
 }
-// U = bf16(sum of the parts, in order); n4 = number of groups of four elements
+// U (or G) = the sum of the parts, in order, rounded to the element type; n4 = number of groups
+// of four elements
 template <int DT>
 __global__ void lora_u_reduce_kernel(const float* __restrict__ part, int parts, long long n4,
                                      uint16_t* __restrict__ U) {
@@ -302,8 +324,9 @@ static hipError_t launch_lora_u_t(int Tt, int d, const uint16_t* X, const uint16
                                   float* u_part, hipStream_t st) {
   const int split = lora_u_split(Tt, d);
   const long long n = (long long)Tt * 4096;
-  hipLaunchKernelGGL(lora_u_kernel<DT>, dim3(Tt, split), dim3(kThreads), 0, st, X, A_pad, d, U, u_part,
-                     n);
+  const int* none = nullptr;
+  hipLaunchKernelGGL((lora_nt_kernel<DT, 0>), dim3(Tt, split), dim3(kThreads), 0, st, X, A_pad, d, none,
+                     none, 1, 0, U, u_part, n);
   if (split > 1)
     hipLaunchKernelGGL(lora_u_reduce_kernel<DT>, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st,
                        (const float*)u_part, split, n / 4, U);
@@ -312,6 +335,27 @@ static hipError_t launch_lora_u_t(int Tt, int d, const uint16_t* X, const uint16
 hipError_t launch_lora_u(int dt, int Tt, int d, const uint16_t* X, const uint16_t* A_pad, uint16_t* U,
                          float* u_part, hipStream_t st) {
   return LX_BY_DT(launch_lora_u_t, Tt, d, X, A_pad, U, u_part, st);
+}
+
+// G = dZ B_pad [T,64] from the compact blocks dZ and B_t [64,F].  g_part: lora_g_split(Tt) * T * 64
+// floats of scratch (unused for a split of 1).
+template <int DT>
+static hipError_t launch_lora_g_t(int Tt, int gt, int F, const uint16_t* dZ, const uint16_t* B_t,
+                                  const int* row_ptr, const int* col_idx, int nnz_cap, uint16_t* G,
+                                  float* g_part, hipStream_t st) {
+  const int split = lora_g_split(Tt);
+  const long long n = (long long)Tt * 4096;
+  hipLaunchKernelGGL((lora_nt_kernel<DT, 1>), dim3(Tt, split), dim3(kThreads), 0, st, dZ, B_t, F, row_ptr,
+                     col_idx, gt, nnz_cap, G, g_part, n);
+  if (split > 1)
+    hipLaunchKernelGGL(lora_u_reduce_kernel<DT>, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st,
+                       (const float*)g_part, split, n / 4, G);
+  return hipGetLastError();
+}
+hipError_t launch_lora_g(int dt, int Tt, int gt, int F, const uint16_t* dZ, const uint16_t* B_t,
+                         const int* row_ptr, const int* col_idx, int nnz_cap, uint16_t* G,
+                         float* g_part, hipStream_t st) {
+  return LX_BY_DT(launch_lora_g_t, Tt, gt, F, dZ, B_t, row_ptr, col_idx, nnz_cap, G, g_part, st);
 }
 
 hipError_t launch_lora_transposes(int d, int F, const uint16_t* A_pad, uint16_t* A_t,

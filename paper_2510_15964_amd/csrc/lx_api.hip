@@ -310,9 +310,10 @@ size_t lx_sparse_ffn_lora_fwd_workspace_bytes(int32_t T, int32_t d) {
 
 size_t lx_sparse_ffn_lora_bwd_workspace_bytes(int32_t T, int32_t d, int32_t F, int32_t nnz_cap) {
   if (T < 64 || d < 64 || F < 64) return 0;
-  const int sa = lora_da_split(T / 64, d), sb = lora_db_split(T / 64, F);
+  const int sa = lora_da_split(T / 64, d), sb = lora_db_split(T / 64, F), sg = lora_g_split(T / 64);
   return act_bytes(LX_BF16, 64, 64, nnz_cap) + round256((size_t)64 * F * 2) +
          round256((size_t)d * 64 * 2) + round256((size_t)T * 64 * 2) +
+         (sg > 1 ? round256((size_t)sg * T * 64 * 4) : 0) +
          (sa > 1 ? round256((size_t)sa * 64 * d * 4) : 0) +
          (sb > 1 ? round256((size_t)sb * F * 64 * 4) : 0);
 }
@@ -373,6 +374,9 @@ lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
   ws += round256((size_t)d * 64 * 2);
   uint16_t* g = (uint16_t*)ws;
   ws += round256((size_t)T * 64 * 2);
+  float* part_g = (float*)ws;
+  const int sg = lora_g_split(T / 64);
+  if (sg > 1) ws += round256((size_t)sg * T * 64 * 4);
   float* part_a = (float*)ws;
   const int sa = lora_da_split(T / 64, d);
   if (sa > 1) ws += round256((size_t)sa * 64 * d * 4);
@@ -381,7 +385,7 @@ lx_status lx_sparse_ffn_lora_bwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
       dt16(dt), T / 64, gt, d, F, (const uint16_t*)X, (const uint16_t*)dY, (const uint16_t*)H_act,
       (const uint16_t*)U, (const uint16_t*)W_down_t, (const uint16_t*)W_up_t,
       (const uint16_t*)A_pad, (const uint16_t*)B_pad, bl->row_ptr, bl->col_idx, bl->nnz_cap, dz, bt,
-      at, g, part_a, part_b, (uint16_t*)dX, dA, dB, (hipStream_t)stream);
+      at, g, part_g, part_a, part_b, (uint16_t*)dX, dA, dB, (hipStream_t)stream);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 

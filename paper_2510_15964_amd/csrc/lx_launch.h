@@ -82,6 +82,7 @@ inline int lora_u_split(int Tt, int d) {
   const int by_k = d / 64 / 4;   // at least four K-steps per workgroup
   return lora_clamp((kCUs + Tt - 1) / Tt, by_k < 8 ? by_k : 8);
 }
+inline int lora_g_split(int Tt) { return lora_clamp((kCUs + Tt - 1) / Tt, 4); }   // over list entries
 inline int lora_db_split(int Tt, int F) {
   const int s = lora_clamp((2 * kCUs + F / 64 - 1) / (F / 64), Tt < 16 ? Tt : 16);
   const int need = (Tt + 511) / 512;   // the kernel searches one tile of its range per thread
@@ -93,6 +94,9 @@ inline int lora_da_split(int Tt, int d) {
 // the small products of the LoRA branch (lora_bf16.hip); dt = kBf16 or kF16
 hipError_t launch_lora_u(int dt, int Tt, int d, const uint16_t* X, const uint16_t* A_pad, uint16_t* U,
                          float* u_part, hipStream_t st);
+hipError_t launch_lora_g(int dt, int Tt, int gt, int F, const uint16_t* dZ, const uint16_t* B_t,
+                         const int* row_ptr, const int* col_idx, int nnz_cap, uint16_t* G,
+                         float* g_part, hipStream_t st);
 hipError_t launch_lora_transposes(int d, int F, const uint16_t* A_pad, uint16_t* A_t,
                                   const uint16_t* B_pad, uint16_t* B_t, hipStream_t st);
 hipError_t launch_lora_grads(int dt, int Tt, int gt, int d, int F, const uint16_t* dZ,
@@ -111,8 +115,8 @@ hipError_t launch_ffn_lora_bwd_bf16(int dt, int Tt, int gt, int d, int F, const 
                                     const uint16_t* A_pad, const uint16_t* B_pad,
                                     const int* row_ptr, const int* col_idx, int nnz_cap,
                                     uint16_t* dZ, uint16_t* B_t, uint16_t* A_t, uint16_t* G,
-                                    float* da_part, float* db_part, uint16_t* dX, float* dA,
-                                    float* dB, hipStream_t st);
+                                    float* g_part, float* da_part, float* db_part, uint16_t* dX,
+                                    float* dA, float* dB, hipStream_t st);
 hipError_t launch_predict_bf16(int dt, int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
                                const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);
