@@ -17,6 +17,8 @@ Workloads (recipes in paper_2510_15964_amd/inputs.py):
                   a call: the paper's operating point, Sec. V-A).
   opt1.3b_layer_lora      the same layer with a LoRA branch (rank 16) on the FFN
                   up-projection, including the gradients of A and B (Sec. II-C/D).
+  opt1.3b_layer_f16       the same layer in IEEE half precision (fp16 operands,
+                  fp32 accumulation; the paper's parameter precision, Sec. VII-A).
   opt1.3b_layer_patterns  the same layer with per-head attention patterns from
                   a pool, combined into the block lists on the device every
                   step (Sec. VI-A).
@@ -447,7 +449,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="opt1.3b_layer")
+    ap.add_argument("--workload", default="opt1.3b_layer",
+                    help="opt1.3b_layer (default) | opt1.3b_layer_shared | opt1.3b_layer_patterns | "
+                         "opt1.3b_layer_lora | opt1.3b_layer_f16 | config4 | config5:RHO")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", metavar="FILE", default=None,
                     help="also run the configs[4] density sweep, one JSON line per density into FILE")
