@@ -40,6 +40,45 @@ __host__ __device__ inline int compact_parts(long long total_rows, int cols) {
   return p < 1 ? 1 : (int)p;
 }
 
+// Walks the flattened (batch, row, column) index space of a job in steps of kCompactThreads
+// elements without dividing per element (a 32-bit division costs some forty vector instructions,
+// three of them per byte were most of this kernel's time): the position is kept as (batch entry,
+// row, column) and advanced with carries.
+struct MaskCursor {
+  int bi, ri, c;          // batch entry, row inside it, column
+  int dbi, dri, dc;       // the step, decomposed the same way
+  int rows, cols;
+  __device__ __forceinline__ void init(long long first, int rows_, int cols_) {
+    rows = rows_;
+    cols = cols_;
+    const long long gr = first / cols;
+    c = (int)(first - gr * cols);
+    bi = (int)(gr / rows);
+    ri = (int)(gr - (long long)bi * rows);
+    const int dr = kCompactThreads / cols;
+    dc = kCompactThreads - dr * cols;
+    dbi = dr / rows;
+    dri = dr - dbi * rows;
+  }
+  __device__ __forceinline__ void advance() {
+    c += dc;
+    ri += dri;
+    bi += dbi;
+    if (c >= cols) {
+      c -= cols;
+      ++ri;
+    }
+    if (ri >= rows) {
+      ri -= rows;
+      ++bi;
+    }
+  }
+  __device__ __forceinline__ long long offset(long long bstride, long long rstride,
+                                              long long cstride) const {
+    return (long long)bi * bstride + (long long)ri * rstride + (long long)c * cstride;
+  }
+};
+
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJobs jobs) {
   const CompactJob& job = jobs.j[blockIdx.x];
   const uint8_t* __restrict__ mask = job.mask;
@@ -68,17 +107,15 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
     const long long before = (long long)row_lo * cols;
     int cnt = 0;
     constexpr int kBatch = 8;
+    MaskCursor cur;
+    cur.init(tid, rows, cols);
     for (long long i0 = tid; i0 < before; i0 += (long long)kCompactThreads * kBatch) {
       uint8_t v[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const long long idx = i0 + (long long)u * kCompactThreads;
-        v[u] = 0;
-        if (idx < before) {
-          const int gr = (int)(idx / cols), c = (int)(idx - (long long)gr * cols);
-          v[u] = mask[(long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride +
-                      (long long)c * cstride];
-        }
+        v[u] = idx < before ? mask[cur.offset(bstride, rstride, cstride)] : (uint8_t)0;
+        cur.advance();
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) cnt += v[u] != 0;
@@ -94,10 +131,11 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   for (int chunk = row_lo; chunk < row_hi; chunk += chunk_rows) {
     const int n = min(chunk_rows, row_hi - chunk);
     if (staged) {
+      MaskCursor cur;
+      cur.init((long long)chunk * cols + tid, rows, cols);
       for (int idx = tid; idx < n * cols; idx += kCompactThreads) {
-        const int r = idx / cols, c = idx - r * cols, gr = chunk + r;
-        stage[idx] = mask[(long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride +
-                          (long long)c * cstride];
+        stage[idx] = mask[cur.offset(bstride, rstride, cstride)];
+        cur.advance();
       }
       __syncthreads();
     }
