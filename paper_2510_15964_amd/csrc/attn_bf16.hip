@@ -274,14 +274,20 @@ typedef const __attribute__((address_space(4))) int* ScalarIntPtr;   // loads be
 // the vector-memory counter that the tile transfers are waited on.
 struct RowSet {
   ScalarIntPtr col_idx;
-  const int* tab;   // LDS: blk[kRMax] (-1 = slot not used), rs[kRMax], n[kRMax]
-  // tab_lds: 3 * kRMax ints of LDS; contains a barrier: call from uniform control flow
+  const int* tab;   // LDS: blk[kRMax] (-1 = slot not used), rs[kRMax], n[kRMax], head[kRMax]
+  // The rows are those of `heads` consecutive heads, h0 .. (nb1 blocks each, their list rows one
+  // after the other from head_row0), ranked and dealt together: heads whose lists differ in
+  // length then share their workgroups instead of each keeping G of its own.
+  // tab_lds: 4 * kRMax ints of LDS; contains a barrier: call from uniform control flow
   __device__ __forceinline__ void init(int* tab_lds, const int* __restrict__ row_ptr,
                                        const int* __restrict__ col_idx_, int cap, int head_row0,
-                                       int nblk, int g, int G, int R, bool mirror, bool head_on) {
+                                       int nb1, int heads, int h0,
+                                       const uint8_t* __restrict__ head_active, int g, int G, int R,
+                                       bool mirror) {
     col_idx = (ScalarIntPtr)col_idx_;
     tab = tab_lds;
     const int tid = threadIdx.x;
+    const int nblk = nb1 * heads;
     if (nblk <= kWave) {
       // Groups balanced by the actual lengths of the lists: the rows of the head are ranked by
       // length (longest first, ties by index) and dealt to the G workgroups in a snake over the
@@ -289,8 +295,10 @@ struct RowSet {
       // of the head computes the same ranking, one row per lane of its first wavefront.
       if (tid < kWave) {
         const bool valid = tid < nblk;
+        const int hh = valid ? tid / nb1 : 0;       // head of this lane's row, relative to h0
         int rs = 0, n = -1;
         if (valid) {
+          const bool head_on = !head_active || head_active[h0 + hh] != 0;
           rs = row_ptr[head_row0 + tid];
           // entries beyond the capacity of the index buffer are ignored
           n = head_on ? max(min(row_ptr[head_row0 + tid + 1], cap) - rs, 0) : 0;
@@ -302,9 +310,10 @@ struct RowSet {
         }
         const int j = rank / G, pos = rank - j * G;
         if (valid && ((j & 1) ? G - 1 - pos : pos) == g) {
-          tab_lds[j] = tid;
+          tab_lds[j] = tid - hh * nb1;
           tab_lds[kRMax + j] = rs;
           tab_lds[2 * kRMax + j] = n;
+          tab_lds[3 * kRMax + j] = h0 + hh;
         }
       } else if (tid < kWave + kRMax) {
         // slots whose rank does not exist (the head has fewer rows than G * kRMax)
@@ -314,14 +323,16 @@ struct RowSet {
           tab_lds[j] = -1;
           tab_lds[kRMax + j] = 0;
           tab_lds[2 * kRMax + j] = 0;
+          tab_lds[3 * kRMax + j] = h0;
         }
       }
     } else if (tid < kRMax) {
       // more rows than lanes: fixed snake over the block index (balanced under a causal mask)
-      const int j = tid;
-      int bj = (j & 1) ? (j + 1) * G - 1 - g : j * G + g;
+      const int j = tid;                       // (heads == 1 here: the launcher groups heads only
+      int bj = (j & 1) ? (j + 1) * G - 1 - g : j * G + g;   //  when their rows fit one wavefront)
       const bool used = j < R && bj < nblk;
       if (mirror) bj = nblk - 1 - bj;
+      const bool head_on = !head_active || head_active[h0] != 0;
       int rs = 0, n = 0;
       if (used) {
         rs = row_ptr[head_row0 + bj];
@@ -330,6 +341,7 @@ struct RowSet {
       tab_lds[j] = used ? bj : -1;
       tab_lds[kRMax + j] = rs;
       tab_lds[2 * kRMax + j] = n;
+      tab_lds[3 * kRMax + j] = h0;
     }
     __syncthreads();
   }
@@ -341,6 +353,9 @@ struct RowSet {
   __device__ __forceinline__ int n(int k) const {
     return __builtin_amdgcn_readfirstlane(tab[2 * kRMax + k]);
   }
+  __device__ __forceinline__ int head(int k) const {
+    return __builtin_amdgcn_readfirstlane(tab[3 * kRMax + k]);
+  }
   // listed block `it` of slot k (both wave-uniform, it < n(k))
   __device__ __forceinline__ int col(int k, int it) const { return col_idx[rs(k) + it]; }
   // first slot >= k with a non-empty list, kRMax if none
@@ -350,8 +365,8 @@ struct RowSet {
   }
 };
 
-// Walk over all listed blocks of the row set as one double-buffered stream.  issue(stage, col)
-// starts the transfer of the tiles of block `col` into stage 0/1; comp(stage, col) consumes
+// Walk over all listed blocks of the row set as one double-buffered stream.  issue(stage, k, col)
+// starts the transfer of the tiles of block `col` of the row in slot k into stage 0/1; comp(stage, col) consumes
 // them; row_begin(k) loads the per-row state, row_end(k, stage) combines and stores it and may
 // use the LDS of `stage` (the one just consumed) after a barrier of its own.  The transfer of
 // the next block, which may belong to the next row, is issued before the current one is
@@ -370,7 +385,7 @@ __device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin
   if (ki >= kRMax) return;
   int ni = rows.n(ki);                 // length of the list the issue side is in
   int coli = rows.col(ki, 0);          // block whose transfer is issued next
-  issue(0, coli);
+  issue(0, ki, coli);
   int kc = ki, itc = 0, colc = coli, nc = ni;
   auto advance = [&]() {
     if (++iti == ni) {
@@ -401,7 +416,7 @@ __device__ __forceinline__ void walk_rows(const RowSet& rows, RowBegin row_begin
       }
       want_pf = false;
     }
-    if (more) issue((t + 1) & 1, coli);
+    if (more) issue((t + 1) & 1, ki, coli);
     comp(t & 1, colc);
     const bool last = itc + 1 == nc;
     if (last) row_end(kc, t & 1);
@@ -429,27 +444,29 @@ template <int D, int DT>
 __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(const AttnArgs a) {
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: K tile, V tile
   __shared__ float xstat[2][2][2][64];   // [part][own][max, sum][lane]
-  __shared__ int rowtab[3 * kRMax];
+  __shared__ int rowtab[4 * kRMax];
   const int nqb = a.S / 64;
-  const int h = blockIdx.x, b = blockIdx.y;
+  const int h0 = blockIdx.x * a.vheads, b = blockIdx.y;   // first head of the group, batch entry
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int own = wave % 2, part = wave / 2;   // own query half, key half of every block
   const int ql = 32 * own + lane % 32, h2 = lane / 32;
-  const long long base = (long long)b * a.sb + (long long)h * a.sh;
-  const long long stat_base = ((long long)b * a.Hh + h) * a.S;
+  // element offset of head hh's tensors, and of its per-row statistics
+  auto base_of = [&](int hh) { return (long long)b * a.sb + (long long)hh * a.sh; };
+  auto stat_of = [&](int hh) { return ((long long)b * a.Hh + hh) * a.S; };
   const uint32_t st_addr = lds_addr(&st[0][0]);
 
   RowSet rows;
-  rows.init(rowtab, a.row_ptr, a.col_idx, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
-            gridDim.z, a.rows_per_wg, true, !(a.head_active && !a.head_active[h]));
+  rows.init(rowtab, a.row_ptr, a.col_idx, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h0) * nqb, nqb,
+            a.vheads, h0, a.head_active, blockIdx.z, gridDim.z, a.rows_per_wg, true);
   // rows without a listed block (or of an inactive head): O = 0, LSE = -inf, nothing to read
   if (part == 0) {
     for (int j = 0; j < kRMax; ++j)
       if (rows.blk(j) >= 0 && rows.n(j) == 0) {
         f32x16 z[D / 32];
         zero(z);
-        store_acc<D, DT>(z, 0.f, a.Out + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
-        if (h2 == 0) a.LSE[stat_base + rows.blk(j) * 64 + ql] = -INFINITY;
+        const int hh = rows.head(j);
+        store_acc<D, DT>(z, 0.f, a.Out + base_of(hh) + (long long)(rows.blk(j) * 64 + ql) * a.ss);
+        if (h2 == 0) a.LSE[stat_of(hh) + rows.blk(j) * 64 + ql] = -INFINITY;
       }
   }
 
@@ -460,14 +477,16 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
   const float sc = a.scale * kLog2e;
   // state of the row being computed (this wavefront's part of it)
   int qb = 0;
-  long long qoff = 0;
+  long long qoff = 0, soff = 0;      // this lane's row of Q / O, and of the statistics
   uint4 qf[D / 16];
   f32x16 o_acc[D / 32];
   float m = -INFINITY, lsum = 0.f;   // running maximum (scaled log2 units) and sum
 
   auto row_begin = [&](int k) {
     qb = rows.blk(k);
-    qoff = base + (long long)(qb * 64 + ql) * a.ss;
+    const int hh = rows.head(k);
+    qoff = base_of(hh) + (long long)(qb * 64 + ql) * a.ss;
+    soff = stat_of(hh) + qb * 64 + ql;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       qf[s] = *reinterpret_cast<const uint4*>(a.Q + qoff + 16 * s + 8 * h2);
@@ -475,8 +494,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
     m = -INFINITY;
     lsum = 0.f;
   };
-  auto issue = [&](int stage, int col) {
-    const long long t0 = base + (long long)col * 64 * a.ss;
+  auto issue = [&](int stage, int k, int col) {
+    const long long t0 = base_of(rows.head(k)) + (long long)col * 64 * a.ss;
     const uint32_t dst = st_addr + stage * (4 * 64 * D);
     dma.issue(dst, a.K + t0);
     dma.issue(dst + 2 * 64 * D, a.V + t0);
@@ -550,7 +569,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
       merge_half<D, 0>(area, own, a0 * inv, a1 * inv, o_acc);
       store_acc<D, DT, 0, D / 64>(o_acc, 1.f, a.Out + qoff);
       if (h2 == 0)
-        a.LSE[stat_base + qb * 64 + ql] = any ? (mt + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+        a.LSE[soff] = any ? (mt + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
     } else {
       merge_half<D, 1>(area, own, a0 * inv, a1 * inv, o_acc);
       store_acc<D, DT, D / 64, D / 64>(o_acc, 1.f, a.Out + qoff);
@@ -569,30 +588,31 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   // halve the number of resident workgroups)
   constexpr bool kOwnPf = D == 64;
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t ownt[kOwnPf ? 2 : 1][kOwnPf ? 64 * D : 8];
-  __shared__ int rowtab[3 * kRMax];
+  __shared__ int rowtab[4 * kRMax];
   const int nqb = a.S / 64;
-  const int h = blockIdx.x, b = blockIdx.y;
+  const int h0 = blockIdx.x * a.vheads, b = blockIdx.y;   // first head of the group, batch entry
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int own = wave % 2, part = wave / 2;   // own query half, key half of every block
   const int ql = 32 * own + lane % 32, h2 = lane / 32;
-  const long long base = (long long)b * a.sb + (long long)h * a.sh;
-  const long long stat_base = ((long long)b * a.Hh + h) * a.S;
+  auto base_of = [&](int hh) { return (long long)b * a.sb + (long long)hh * a.sh; };
+  auto stat_of = [&](int hh) { return ((long long)b * a.Hh + hh) * a.S; };
   const uint32_t st_addr = lds_addr(&st[0][0]), own_addr = lds_addr(&ownt[0][0]);
   const uint32_t own_off = tile_off<D>(ql, 8 * h2);   // this lane's fragments inside an own tile
 
   RowSet rows;
-  rows.init(rowtab, a.row_ptr, a.col_idx, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nqb, nqb, blockIdx.z,
-            gridDim.z, a.rows_per_wg, true, !(a.head_active && !a.head_active[h]));
+  rows.init(rowtab, a.row_ptr, a.col_idx, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h0) * nqb, nqb,
+            a.vheads, h0, a.head_active, blockIdx.z, gridDim.z, a.rows_per_wg, true);
   // rows without a listed block (or of an inactive head): O = 0, hence Delta = 0 and dQ = 0
   if (part == 0) {
     for (int j = 0; j < kRMax; ++j)
       if (rows.blk(j) >= 0 && rows.n(j) == 0) {
         f32x16 z[D / 32];
         zero(z);
-        store_acc<D, DT>(z, 0.f, a.dQ + base + (long long)(rows.blk(j) * 64 + ql) * a.ss);
+        const int hh = rows.head(j);
+        store_acc<D, DT>(z, 0.f, a.dQ + base_of(hh) + (long long)(rows.blk(j) * 64 + ql) * a.ss);
         if (h2 == 0) {
-          a.Delta[stat_base + rows.blk(j) * 64 + ql] = 0.f;
-          a.NegLse2[stat_base + rows.blk(j) * 64 + ql] = INFINITY;
+          a.Delta[stat_of(hh) + rows.blk(j) * 64 + ql] = 0.f;
+          a.NegLse2[stat_of(hh) + rows.blk(j) * 64 + ql] = INFINITY;
         }
       }
   }
@@ -603,7 +623,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   lo.init(part);
   const float sc = a.scale * kLog2e;
   int qb = 0;
-  long long qoff = 0;
+  long long qoff = 0, soff = 0;      // this lane's row of Q / O / dO / dQ, and of the statistics
   uint4 qf[D / 16], dof[D / 16];
   float delta = 0.f, lse2 = 0.f;
   f32x16 dq_acc[D / 32];
@@ -613,12 +633,14 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
   // (computing Delta for all rows of the workgroup up front was measured slower)
   auto row_begin = [&](int k) {
     qb = rows.blk(k);
-    qoff = base + (long long)(qb * 64 + ql) * a.ss;
+    const int hh = rows.head(k);
+    qoff = base_of(hh) + (long long)(qb * 64 + ql) * a.ss;
+    soff = stat_of(hh) + qb * 64 + ql;
     uint4 ofr[D / 16];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       ofr[s] = *reinterpret_cast<const uint4*>(a.O + qoff + 16 * s + 8 * h2);
-    lse2 = a.LSEin[stat_base + qb * 64 + ql] * kLog2e;
+    lse2 = a.LSEin[soff] * kLog2e;
     float sum = 0.f;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
@@ -641,18 +663,18 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
     }
     delta = sum + __shfl_xor(sum, 32);
     if (part == 0 && h2 == 0) {        // for the key-side kernel: Delta and -LSE in log2 units
-      a.Delta[stat_base + qb * 64 + ql] = delta;
-      a.NegLse2[stat_base + qb * 64 + ql] = -lse2;
+      a.Delta[soff] = delta;
+      a.NegLse2[soff] = -lse2;
     }
     zero(dq_acc);
   };
   auto prefetch = [&](int k) {
-    const long long t0 = base + (long long)rows.blk(k) * 64 * a.ss;
+    const long long t0 = base_of(rows.head(k)) + (long long)rows.blk(k) * 64 * a.ss;
     dma.issue(own_addr, a.Q + t0);
     dma.issue(own_addr + 2 * 64 * D, a.dO + t0);
   };
-  auto issue = [&](int stage, int col) {
-    const long long t0 = base + (long long)col * 64 * a.ss;
+  auto issue = [&](int stage, int k, int col) {
+    const long long t0 = base_of(rows.head(k)) + (long long)col * 64 * a.ss;
     const uint32_t dst = st_addr + stage * (4 * 64 * D);
     dma.issue(dst, a.K + t0);
     dma.issue(dst + 2 * 64 * D, a.V + t0);
@@ -705,28 +727,28 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
   constexpr bool kOwnPf = D == 64;
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t ownt[kOwnPf ? 2 : 1][kOwnPf ? 64 * D : 8];
   __shared__ __attribute__((aligned(256))) float sstat[2][128];   // stage: -LSE*log2e [64], Delta [64]
-  __shared__ int rowtab[3 * kRMax];
+  __shared__ int rowtab[4 * kRMax];
   const int nkb = a.S / 64;
-  const int h = blockIdx.x, b = blockIdx.y;
+  const int h0 = blockIdx.x * a.vheads, b = blockIdx.y;   // first head of the group, batch entry
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int own = wave % 2, part = wave / 2;   // own key half, query half of every block
   const int kl = 32 * own + lane % 32, h2 = lane / 32;
-  const long long base = (long long)b * a.sb + (long long)h * a.sh;
-  const long long stat_base = ((long long)b * a.Hh + h) * a.S;
+  auto base_of = [&](int hh) { return (long long)b * a.sb + (long long)hh * a.sh; };
+  auto stat_of = [&](int hh) { return ((long long)b * a.Hh + hh) * a.S; };
   const uint32_t st_addr = lds_addr(&st[0][0]), sstat_addr = lds_addr(&sstat[0][0]);
   const uint32_t own_addr = lds_addr(&ownt[0][0]);
   const uint32_t own_off = tile_off<D>(kl, 8 * h2);   // this lane's fragments inside an own tile
 
   RowSet rows;
-  rows.init(rowtab, a.crow_ptr, a.ccol_idx, a.cnnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h) * nkb, nkb,
-            blockIdx.z, gridDim.z, a.rows_per_wg, false, !(a.head_active && !a.head_active[h]));
+  rows.init(rowtab, a.crow_ptr, a.ccol_idx, a.cnnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h0) * nkb, nkb,
+            a.vheads, h0, a.head_active, blockIdx.z, gridDim.z, a.rows_per_wg, false);
   // key blocks used by no query block: zero gradients, nothing to read
   if (part == 0) {
     for (int j = 0; j < kRMax; ++j)
       if (rows.blk(j) >= 0 && rows.n(j) == 0) {
         f32x16 z[D / 32];
         zero(z);
-        const long long koff = base + (long long)(rows.blk(j) * 64 + kl) * a.ss;
+        const long long koff = base_of(rows.head(j)) + (long long)(rows.blk(j) * 64 + kl) * a.ss;
         store_acc<D, DT>(z, 0.f, a.dV + koff);
         store_acc<D, DT>(z, 0.f, a.dK + koff);
       }
@@ -745,7 +767,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
 
   auto row_begin = [&](int k) {       // the row's K and V tiles are in LDS (prefetch below) or read directly
     kb = rows.blk(k);
-    koff = base + (long long)(kb * 64 + kl) * a.ss;
+    koff = base_of(rows.head(k)) + (long long)(kb * 64 + kl) * a.ss;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
       if (kOwnPf) {
@@ -760,16 +782,17 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
     zero(dv_acc);
   };
   auto prefetch = [&](int k) {
-    const long long t0 = base + (long long)rows.blk(k) * 64 * a.ss;
+    const long long t0 = base_of(rows.head(k)) + (long long)rows.blk(k) * 64 * a.ss;
     dma.issue(own_addr, a.K + t0);
     dma.issue(own_addr + 2 * 64 * D, a.V + t0);
   };
-  auto issue = [&](int stage, int qb) {
-    const long long t0 = base + (long long)qb * 64 * a.ss;
+  auto issue = [&](int stage, int k, int qb) {
+    const int hh = rows.head(k);
+    const long long t0 = base_of(hh) + (long long)qb * 64 * a.ss;
     const uint32_t dst = st_addr + stage * (4 * 64 * D);
     dma.issue(dst, a.Q + t0);
     dma.issue(dst + 2 * 64 * D, a.dO + t0);
-    if (wave < 2) dma4(stat_src + stat_base + qb * 64 + lane, sstat_addr + stage * 512 + wave * 256);
+    if (wave < 2) dma4(stat_src + stat_of(hh) + qb * 64 + lane, sstat_addr + stage * 512 + wave * 256);
   };
   auto comp = [&](int stage, int col) {
     const uint32_t stg = st_addr + stage * (4 * 64 * D);
@@ -861,6 +884,14 @@ hipError_t set_attn_rows_per_wg(int r) {
   g_rows_per_wg = r;
   return hipSuccess;
 }
+// Heads per group of workgroups: as many consecutive heads (4, 2 or 1) as divide the head count
+// and whose rows one wavefront can rank (64 lanes).  The rows of the group are dealt to its
+// workgroups together, so heads with long and with short lists even each other out.
+static int heads_per_group(int nblk, int heads) {
+  for (int v = 4; v > 1; v /= 2)
+    if (heads % v == 0 && v * nblk <= kWave) return v;
+  return 1;
+}
 static int rows_per_wg(int nblk, int heads, int B, int slots) {
   int r = 1;
   while (r < kRMax && (long long)((nblk + r - 1) / r) * heads * B > slots) ++r;
@@ -872,20 +903,22 @@ template <int D, int DT>
 static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
   ProfScope ps(kKAttnFwd, st);
   const int nblk = a.S / 64;
+  a.vheads = heads_per_group(nblk, a.Hh);
   a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kFwdOcc64 : 2));
   const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-  hipLaunchKernelGGL((attn_fwd_bf16<D, DT>), dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
+  hipLaunchKernelGGL((attn_fwd_bf16<D, DT>), dim3(a.Hh / a.vheads, B, G * a.vheads), dim3(kAT), 0, st, a);
   return hipGetLastError();
 }
 
 template <int D, int DT>
 static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
   const int nblk = a.S / 64;
+  a.vheads = heads_per_group(nblk, a.Hh);
   {
     ProfScope ps(kKAttnDq, st);
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDqOcc64 : 2));
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL((attn_bwd_dq_bf16<D, DT>), dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL((attn_bwd_dq_bf16<D, DT>), dim3(a.Hh / a.vheads, B, G * a.vheads), dim3(kAT), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -893,7 +926,7 @@ static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
     ProfScope ps(kKAttnDkv, st);
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDkvOcc64 : 1));
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT>), dim3(a.Hh, B, G), dim3(kAT), 0, st, a);
+    hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT>), dim3(a.Hh / a.vheads, B, G * a.vheads), dim3(kAT), 0, st, a);
   }
   return hipGetLastError();
 }

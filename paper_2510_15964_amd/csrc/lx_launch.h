@@ -38,6 +38,7 @@ struct AttnArgs {
   int Hh, S, mask_batch, causal;
   float scale;
   int rows_per_wg;   // rows of the mask per workgroup, set by the launcher
+  int vheads;        // consecutive heads whose rows one group of workgroups shares, set by the launcher
 };
 
 hipError_t launch_compact(const uint8_t*, int, int, int, long long, long long, long long, int*, int*,
