@@ -20,13 +20,14 @@
 // At the block densities of the paper a row of the mask lists only a few
 // blocks, so a workgroup that handled one row would spend most of its life in
 // the chain of dependent loads that starts it (row pointer -> list -> tiles).
-// A workgroup therefore owns up to eight rows of one (batch, head) and walks
+// A workgroup therefore owns up to eight rows of one batch entry and walks
 // their lists as ONE stream of blocks: the metadata of all its rows is read up
 // front, and the tile transfer of the next block -- of the same row or of the
 // next one -- is always in flight while the current block is computed.  The
-// rows of a head are ranked by the length of their lists and dealt to the
-// head's workgroups in a snake over the ranks, which evens out the number of
-// blocks per workgroup for any mask (all workgroups of a launch are resident at
+// rows of a group of up to four consecutive heads are ranked by the length of
+// their lists and dealt to the group's workgroups in a snake over the ranks,
+// which evens out the number of blocks per workgroup for any mask and between
+// heads with long and short lists (all workgroups of a launch are resident at
 // once, so the launch lasts as long as its longest workgroup).
 //
 // Data movement: the [64 x D] tiles of the listed blocks go from global memory
