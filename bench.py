@@ -23,7 +23,9 @@ Workloads (recipes in paper_2510_15964_amd/inputs.py):
                   a pool, combined into the block lists on the device every
                   step (Sec. VI-A).
   config4         OPT-6.7B-shaped layer (configs[3]).
-  config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]).
+  config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]);
+                  config5:<rho>:shared2 = the same with one FFN list for all token tiles
+                  and two token tiles per FFN workgroup (the dense path at rho = 1).
 
 Prints ONE JSON line.  `--sweep FILE` additionally runs the configs[4] density
 sweep and writes one JSON line per density to FILE.
@@ -95,10 +97,16 @@ def make_workload(name: str):
         a = inputs.config4_attn()
         ffn_calls = 1
     elif name.startswith("config5:"):
-        rho = float(name.split(":")[1])
+        parts = name.split(":")
+        rho = float(parts[1])
         f = inputs.config5_ffn(rho)
         a = inputs.config5_attn(rho)
         ffn_calls = 1
+        if len(parts) > 2 and parts[2] == "shared2":
+            # the same layer with ONE list row for all token tiles (row 0 of the mask, repeated)
+            # and two token tiles per FFN workgroup: the dense path at rho = 1
+            f["mask"] = np.repeat(f["mask"][:1], f["mask"].shape[0], axis=0)
+            f["shared_list"], f["tiles_per_wg"] = True, 2
     else:
         raise SystemExit(f"unknown workload {name!r}")
     return f, a, ffn_calls
@@ -121,7 +129,11 @@ class FfnJob:
         Tt, Fb = self.mask_h.shape
         self.nnz = int(self.mask_h.sum())          # active (tile, block) pairs
         self.pred = f.get("predictor")
-        if self.pred is None:                      # mask rows are inputs, one per token tile
+        if self.pred is None and f.get("shared_list"):   # one input row for all token tiles
+            assert (self.mask_h == self.mask_h[:1]).all()
+            self.mask = torch.from_numpy(np.ascontiguousarray(self.mask_h[:1])).cuda()
+            lrows, lnnz = 1, int(self.mask_h[0].sum())
+        elif self.pred is None:                    # mask rows are inputs, one per token tile
             self.mask = torch.from_numpy(self.mask_h).cuda()
             lrows, lnnz = Tt, self.nnz
         else:                                      # one row, written by the predictor every step
@@ -333,6 +345,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     assert torch.cuda.is_available(), "bench.py needs a GPU (no fallback path)"
     torch.cuda.set_device(0)
     f, a, ffn_calls = make_workload(workload)
+    lx.lx_ffn_set_token_tiles_per_workgroup(f.get("tiles_per_wg", 0))   # 0 = the library chooses
     Wu, Wd = dev(f["W_up"], f["dtype"]), dev(f["W_down"], f["dtype"])
     Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)            # one-time repack of frozen weights
     Tt = f["mask"].shape[0]
@@ -421,7 +434,9 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
             "workload": workload, "tokens_per_step": tokens,
             "ffn": {"T_per_call": ffn_jobs[0].T, "calls": ffn_calls, "d": f["d"], "F": f["F"],
                     "block": "64x64", "block_density": float(f["mask"].mean()),
-                    "active_blocks": int(f["mask"].sum())},
+                    "active_blocks": int(f["mask"].sum()),
+                    "list_rows_per_call": ffn_jobs[0].bl.rows,
+                    "token_tiles_per_workgroup": f.get("tiles_per_wg", 0) or "auto"},
             "attn": {"B": a["B"], "heads": a["Hh"], "active_heads": attn.h_act, "S": a["S"],
                      "D": a["D"], "causal": bool(a["causal"]),
                      "block_density_in_causal_region": attn.density,
@@ -441,6 +456,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     }
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(f, a)
+    lx.lx_ffn_set_token_tiles_per_workgroup(0)
     return out
 
 
@@ -470,8 +486,9 @@ def main():
         from paper_2510_15964_amd.inputs import DENSITY_SWEEP
         os.makedirs(os.path.dirname(os.path.abspath(args.sweep)), exist_ok=True)
         with open(args.sweep, "w") as fh:
-            for rho in DENSITY_SWEEP:
-                r = run(f"config5:{rho}", max(args.steps // 5, 5), 2, False)
+            for wl in [f"config5:{rho}" for rho in DENSITY_SWEEP] + ["config5:1.0:shared2"]:
+                rho = wl.split(":", 1)[1]
+                r = run(wl, max(args.steps // 5, 5), 2, False)
                 log(f"config5 rho={rho}: {r['ms_per_step']:.3f} ms/step, "
                     f"{r['active_tflops']:.1f} active TFLOP/s")
                 fh.write(json.dumps(r) + "\n")

@@ -296,6 +296,194 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
   }
 }
 
+// ---------------------------------------------------------------------------
+// Two token tiles per workgroup.  When an even number of consecutive token tiles shares a list
+// row (the paper's reduced mask, or a dense layer), two of them can be multiplied with the same
+// weight rows: 128 token rows + 256 weight rows per stage (48 KiB, a ring of three, one
+// workgroup per CU) and a wave tile of 64 x 64, i.e. 0.6 times the transferred and half the
+// LDS-read bytes per product of the kernels above.  Every output element sees the same
+// products in the same order, so the results are bit-identical to the one-tile kernels'.
+// It pays when the launch still fills the chip with half as many workgroups (large or dense
+// layers); the host chooses (launch_ffn_bf16).
+// ---------------------------------------------------------------------------
+constexpr int kPairRingStages = 3;
+
+// Epilogue of a 64 x 64 wave tile: acc[ni][ti] -> rows t0 + 32*ti + lane%32 (stride ld elements)
+// and columns n0 + 32*ni + 8*g + 4*(lane/32) + e of `out`; bias over the columns, gate with the
+// same indexing (both may be null).
+template <int DT, int MODE>
+__device__ __forceinline__ void store_tile64(const f32x16 (&acc)[2][2], uint16_t* __restrict__ out,
+                                             long long ld, const uint16_t* __restrict__ bias,
+                                             const uint16_t* __restrict__ gate) {
+  const int lane = threadIdx.x % kWave, tl = lane % 32, nq = (lane / 32) * 4;
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = 32 * ni + 8 * g + nq;
+        const long long o = (long long)(32 * ti + tl) * ld + n;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
+        if (bias) {
+          const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
+          v[0] += to_f32<DT>(bb.x & 0xFFFFu); v[1] += to_f32<DT>(bb.x >> 16);
+          v[2] += to_f32<DT>(bb.y & 0xFFFFu); v[3] += to_f32<DT>(bb.y >> 16);
+        }
+        if (MODE == 0) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+        } else if (MODE == 1) {
+          const uint2 gg = *reinterpret_cast<const uint2*>(gate + o);
+          if (!(to_f32<DT>(gg.x & 0xFFFFu) > 0.f)) v[0] = 0.f;
+          if (!(to_f32<DT>(gg.x >> 16) > 0.f)) v[1] = 0.f;
+          if (!(to_f32<DT>(gg.y & 0xFFFFu) > 0.f)) v[2] = 0.f;
+          if (!(to_f32<DT>(gg.y >> 16) > 0.f)) v[3] = 0.f;
+        }
+        uint2 ov;
+        ov.x = pack2<DT>(v[0], v[1]);
+        ov.y = pack2<DT>(v[2], v[3]);
+        *reinterpret_cast<uint2*>(out + o) = ov;
+      }
+}
+
+// sdd for pairs of token tiles: work item = (pair of consecutive tiles of one list row, up to four
+// consecutive list entries); wave w multiplies entry w % 4 with tile w / 4 of the pair.
+// `rows` counts token tiles (even), gt tiles share a list row (even).  MODE / LORA as above.
+template <int DT, int MODE, bool LORA>
+__global__ __launch_bounds__(kThreads) void ffn_sdd2_bf16(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+    const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, int rows, int gt, int K, int nnz_cap,
+    uint16_t* __restrict__ out_act, const uint16_t* __restrict__ gate_act,
+    const uint16_t* __restrict__ A2, const uint16_t* __restrict__ W2) {
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[kPairRingStages * kStageElems2];
+  int pair, chunk;
+  if (!find_work(row_ptr, rows / 2, gt / 2, blockIdx.x, 4, pair, chunk)) return;
+  const int i0 = 2 * pair;                       // first tile of the pair
+  const int rs = row_ptr[i0 / gt], n_i = row_ptr[i0 / gt + 1] - rs;
+  const int first = chunk * 4;
+  const int p0 = rs + first;
+  if (p0 >= nnz_cap) return;       // entries beyond the capacity of the list buffers are ignored
+  const int nb = min(min(4, n_i - first), nnz_cap - p0);
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+
+  const uint16_t* src[kIssues2];
+#pragma unroll
+  for (int u = 0; u < kIssues2; ++u) {
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 2) {
+      src[u] = A + ((long long)i0 * 64 + row) * K + seg * 8;      // 128 consecutive token rows
+    } else {
+      const int blk = (row - kRowsB2) / 64, r = (row - kRowsB2) % 64;
+      // blocks past the end of the list are filled from the first block (never used)
+      const int j = col_idx[p0 + (blk < nb ? blk : 0)];
+      src[u] = W + ((long long)j * 64 + r) * K + seg * 8;
+    }
+  }
+  auto src2 = [&](int u) -> const uint16_t* {    // the low-rank step, computed when it is issued
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 2) return A2 + ((long long)i0 * 64 + row) * 64 + seg * 8;
+    const int blk = (row - kRowsB2) / 64, r = (row - kRowsB2) % 64;
+    const int j = col_idx[p0 + (blk < nb ? blk : 0)];
+    return W2 + ((long long)j * 64 + r) * 64 + seg * 8;
+  };
+  const int rg = wave % 4, th = wave / 4;        // list entry of the four, tile of the pair
+  const bool wave_on = rg < nb;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+  const int ksteps = K / kBK;
+  run_ring_of<kPairRingStages, kIssues2, kStageElems2, 2>(
+      ksteps + (LORA ? 1 : 0), src, src2,
+      [=](int s, long long& ob, long long& oa) {
+        const bool alt = LORA && s == ksteps;
+        ob = oa = alt ? 0 : (long long)s * kBK;
+        return alt;
+      },
+      ring, [&](const uint16_t* stage) {
+        if (wave_on) mma_step64<DT>(stage, rg, th, acc);
+      });
+  if (!wave_on) return;
+  const int j = col_idx[p0 + rg], i = i0 + th;
+  // compact activation block of (tile i, list entry): [entry][tile within the row's group]
+  const long long p = (long long)rs * gt + (long long)(first + rg) * gt + i % gt;
+  store_tile64<DT, MODE>(acc, out_act + p * 4096, 64, MODE == 0 && bias ? bias + j * 64 : nullptr,
+                         MODE == 1 ? gate_act + p * 4096 : nullptr);
+}
+
+// dsd for pairs of token tiles: the workgroup of grid row y works on tiles 2y, 2y + 1 (one list
+// row) and 256 output columns; wave w multiplies columns 64 * (w % 4) .. with tile w / 4.
+template <int DT, bool LORA>
+__global__ __launch_bounds__(kThreads) void ffn_dsd2_bf16(
+    const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
+    const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
+    uint16_t* __restrict__ out, const uint16_t* __restrict__ act2,
+    const uint16_t* __restrict__ W2) {
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[kPairRingStages * kStageElems2];
+  const int i0 = 2 * balanced_tile(row_ptr, gridDim.y, gt / 2, nnz_cap, blockIdx.y, false,
+                                   reinterpret_cast<int*>(ring));
+  const int n0 = blockIdx.x * kRowsA;
+  const int rs = row_ptr[i0 / gt];
+  const int n_i = min(row_ptr[i0 / gt + 1], nnz_cap) - rs;   // <= 0: nothing within the capacity
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int rg = wave % 4, th = wave / 4;        // 64 output columns of the 256, tile of the pair
+  const bool wave_on = n0 + 64 * rg < ncols_out;
+
+  const uint16_t* src[kIssues2];
+#pragma unroll
+  for (int u = 0; u < kIssues2; ++u) {
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 2) {
+      src[u] = act + row * 64 + seg * 8;          // the two tiles' blocks of an entry are adjacent
+    } else {
+      const int n = min(n0 + row - kRowsB2, ncols_out - 1);   // rows past the edge: re-read the last
+      src[u] = W + (long long)n * ldw + seg * 8;
+    }
+  }
+  auto src2 = [&](int u) -> const uint16_t* {     // the low-rank step, computed when it is issued
+    const int g = wave + kFW * u, row = 8 * g + lane / 8;
+    const int seg = (lane % 8) ^ swz(row);
+    if (u < 2) return act2 + ((long long)i0 * 64 + row) * 64 + seg * 8;
+    const int n = min(n0 + row - kRowsB2, ncols_out - 1);
+    return W2 + (long long)n * 64 + seg * 8;
+  };
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+  const int lsteps = n_i > 0 ? n_i : 0;
+  run_ring_of<kPairRingStages, kIssues2, kStageElems2, 2>(
+      lsteps + (LORA ? 1 : 0), src, src2,
+      [&](int s, long long& ob, long long& oa) {
+        const bool alt = LORA && s == lsteps;
+        ob = alt ? 0 : ((long long)(rs + s) * gt + i0 % gt) * 4096;
+        oa = alt ? 0 : (long long)col_idx[rs + s] * 64;
+        return alt;
+      },
+      ring, [&](const uint16_t* stage) {
+        if (wave_on) mma_step64<DT>(stage, rg, th, acc);
+      });
+  if (!wave_on) return;
+  // ncols_out is a multiple of 64 (the host checks d % 64 == 0): a wave's 64 columns are all inside
+  const int n = n0 + 64 * rg;
+  store_tile64<DT, 2>(acc, out + (long long)(i0 + th) * 64 * ncols_out + n, ncols_out,
+                      bias ? bias + n : nullptr, nullptr);
+}
+
 // pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
 // pass 1 (backward): A = dY, W1 = W_down_t [F,d], W2 = W_up_t [d,F], act_out = dZ_act,
 //                    act_gate = H_act, out = dX
@@ -306,6 +494,21 @@ static dim3 sdd_grid(int Tt, int gt, int nnz_cap) {
   return dim3(8 * 8 * ((Lub + 7) / 8));
 }
 
+// Token tiles per workgroup: 0 = chosen here, 1 or 2 = fixed by the caller.
+static int g_ffn_tiles_per_wg = 0;
+hipError_t set_ffn_tiles_per_wg(int n) {
+  if (n < 0 || n > 2) return hipErrorInvalidValue;
+  g_ffn_tiles_per_wg = n;
+  return hipSuccess;
+}
+// Pairs of tiles need list rows shared by an even number of tiles; left to itself the library
+// takes them only when the pairs alone outnumber the CUs (the number of list entries, which
+// decides whether fewer, larger workgroups still fill the chip, is known on the device only).
+static bool use_tile_pairs(int Tt, int gt) {
+  if (gt % 2 != 0 || g_ffn_tiles_per_wg == 1) return false;
+  return g_ffn_tiles_per_wg == 2 || Tt / 2 >= kCUs;
+}
+
 template <int DT>
 static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int F, const uint16_t* A,
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
@@ -314,13 +517,20 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
                            hipStream_t st) {
   (void)Fb;
   if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
-  const dim3 g1 = sdd_grid(Tt, gt, nnz_cap);
+  const bool pairs = use_tile_pairs(Tt, gt);
+  const dim3 g1 = pairs ? sdd_grid(Tt / 2, gt / 2, nnz_cap) : sdd_grid(Tt, gt, nnz_cap);
   const uint16_t* none = nullptr;
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
-    if (pass == 0)
+    if (pass == 0 && pairs)
+      hipLaunchKernelGGL((ffn_sdd2_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+    else if (pass == 0)
       hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+    else if (pairs)
+      hipLaunchKernelGGL((ffn_sdd2_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
+                         col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
     else
       hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
@@ -328,9 +538,14 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
-  hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
-                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap,
-                     out, none, none);
+  if (pairs)
+    hipLaunchKernelGGL((ffn_dsd2_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt / 2), dim3(kThreads),
+                       0, st, (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       nnz_cap, out, none, none);
+  else
+    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0,
+                       st, (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       nnz_cap, out, none, none);
   return hipGetLastError();
 }
 

@@ -32,11 +32,12 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 // Instruction u of wave w fills stage rows 8g .. 8g+7 with g = w + kFW*u (g < 8: the 64 shared
 // rows, then the weight blocks); lane l brings the 16-byte slot l%8 of row 8g + l/8.  src[u]
 // already points at this lane's (row, swizzled segment); offB / offA are the element offsets of
-// the current K-step for the shared rows and the weight rows.
+// the current K-step for the shared rows (the first NSH instructions of a wave) and the weight
+// rows.
 // With `alt` (wave-uniform) the source of instruction u is alt_ptr(u) instead: a step whose
 // operands live in other buffers with another row stride (the LoRA branch).  alt_ptr is
 // evaluated only then, so such a step costs no registers in the steady state.
-template <int NISS, class AltPtr>
+template <int NISS, int NSH, class AltPtr>
 __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* const (&src)[NISS],
                                             AltPtr alt_ptr, bool alt, long long offB,
                                             long long offA) {
@@ -47,7 +48,7 @@ __device__ __forceinline__ void issue_stage(uint16_t* stage, const uint16_t* con
   } else {
 #pragma unroll
     for (int u = 0; u < NISS; ++u)
-      dma16(src[u] + (u < 8 / kFW ? offB : offA), base + u * (kFW * 1024));
+      dma16(src[u] + (u < NSH ? offB : offA), base + u * (kFW * 1024));
   }
 }
 struct NoAlt {
@@ -87,6 +88,41 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
       for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32<DT>(a[kk][ni], b[kk][ti], acc[ni][ti]);
 }
 
+// The same for a stage of 128 shared rows (two token tiles) + 256 weight rows and a wave tile of
+// 64 weight rows (group rg of four) x 64 shared rows (half th): half the LDS bytes per product
+// of the 32 x 64 tile above.  acc[ni][ti]: weight rows 64*rg + 32*ni.., shared rows 64*th + 32*ti..
+constexpr int kRowsB2 = 2 * kRowsB;
+constexpr int kStageElems2 = (kRowsB2 + kRowsA) * kBK;   // 48 KiB
+constexpr int kIssues2 = (kRowsB2 + kRowsA) / 8 / kFW;    // 6 DMA instructions per wave and stage
+template <int DT>
+__device__ __forceinline__ void mma_step64(const uint16_t* stage, int rg, int th,
+                                           f32x16 (&acc)[2][2]) {
+  const int lane = threadIdx.x % kWave;
+  const int r = lane % 32, h2 = lane / 32;
+  uint4 a[4][2], b[4][2];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int seg = 2 * kk + h2;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+      const int ra = kRowsB2 + 64 * rg + 32 * ni + r;
+      a[kk][ni] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+    }
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+      const int rb = 64 * th + 32 * ti + r;
+      b[kk][ti] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);   // keep the reads above: the scheduler would sink them
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32<DT>(a[kk][ni], b[kk][ti], acc[ni][ti]);
+}
+
 // Pipeline over nsteps K-steps through a ring of NST stages: while step s is multiplied, the
 // DMA of steps s+1 .. s+NST-1 is in flight (what bounds these kernels is how many bytes a CU
 // keeps in flight towards memory, so the ring is as deep as LDS allows).  offs(s, offB, offA)
@@ -111,14 +147,14 @@ __device__ __forceinline__ void wait_tail(int y) {
 // step(stage pointer) is the multiplication of one landed stage; a stage holds SE elements.
 // offs(s, offB, offA) yields the element offsets of step s and returns whether the step takes
 // its operands from alt_ptr(u).
-template <int NST, int NISS, int SE, class AltPtr, class Offs, class Step>
+template <int NST, int NISS, int SE, int NSH = 1, class AltPtr, class Offs, class Step>
 __device__ __forceinline__ void run_ring_of(int nsteps, const uint16_t* const (&src)[NISS],
                                             AltPtr alt_ptr, Offs offs, uint16_t* ring, Step step) {
   static_assert(NST >= 2 && NISS * (NST - 2) < 64, "ring depth");
   long long ob, oa;
   auto issue = [&](int s, int stage) {
     const bool alt = offs(s, ob, oa);
-    issue_stage<NISS>(ring + stage * SE, src, alt_ptr, alt, ob, oa);
+    issue_stage<NISS, NSH>(ring + stage * SE, src, alt_ptr, alt, ob, oa);
   };
 #pragma unroll
   for (int p = 0; p < NST - 1; ++p)

@@ -123,6 +123,10 @@ lx_status lx_attn_set_rows_per_workgroup(int32_t rows) {
   return set_attn_rows_per_wg(rows) == hipSuccess ? LX_OK : LX_ERR_INVALID_ARG;
 }
 
+lx_status lx_ffn_set_token_tiles_per_workgroup(int32_t tiles) {
+  return set_ffn_tiles_per_wg(tiles) == hipSuccess ? LX_OK : LX_ERR_INVALID_ARG;
+}
+
 lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
                           int64_t batch_stride, int64_t row_stride, int64_t col_stride,
                           int32_t* row_ptr, int32_t* col_idx, int32_t col_idx_cap, void* stream) {

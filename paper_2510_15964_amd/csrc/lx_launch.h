@@ -124,5 +124,6 @@ hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void*
 hipError_t launch_attn_fwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t set_attn_rows_per_wg(int r);   // 0 = automatic
+hipError_t set_ffn_tiles_per_wg(int n);   // 0 = automatic, 1, 2
 
 }  // namespace lx

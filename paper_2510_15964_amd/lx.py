@@ -31,7 +31,7 @@ EXPORTS = (
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
-    "lx_attn_set_rows_per_workgroup", "lx_mlp_predict_mask", "lx_attn_combine_patterns",
+    "lx_attn_set_rows_per_workgroup", "lx_ffn_set_token_tiles_per_workgroup", "lx_mlp_predict_mask", "lx_attn_combine_patterns",
     "lx_sparse_ffn_lora_fwd_workspace_bytes", "lx_sparse_ffn_lora_bwd_workspace_bytes",
     "lx_sparse_ffn_lora_fwd", "lx_sparse_ffn_lora_bwd",
 )
@@ -82,6 +82,7 @@ _lib.lx_sparse_attn_bwd_dx.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32
 _lib.lx_profile_begin.argtypes = [_i32, _i32]
 _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.lx_attn_set_rows_per_workgroup.argtypes = [_i32]
+_lib.lx_ffn_set_token_tiles_per_workgroup.argtypes = [_i32]
 _lib.lx_mlp_predict_mask.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _vp, _vp, _f, _vp, _vp]
 _lib.lx_sparse_ffn_lora_fwd_workspace_bytes.restype = _sz
 _lib.lx_sparse_ffn_lora_fwd_workspace_bytes.argtypes = [_i32, _i32]
@@ -325,6 +326,10 @@ def lx_profile_begin(kernel: int, max_launches: int):
 
 def lx_attn_set_rows_per_workgroup(rows: int):
     _check(_lib.lx_attn_set_rows_per_workgroup(rows), "lx_attn_set_rows_per_workgroup")
+
+
+def lx_ffn_set_token_tiles_per_workgroup(tiles: int):
+    _check(_lib.lx_ffn_set_token_tiles_per_workgroup(tiles), "lx_ffn_set_token_tiles_per_workgroup")
 
 
 def lx_profile_end():

@@ -258,3 +258,13 @@ def test_half_precision_is_accepted_where_bfloat16_is(lxmod):
     assert _ffn_fwd(L, 3, 512, 128, 1024, 64, 64, bl) == L.LX_ERR_UNSUPPORTED
     assert L._lib.lx_mlp_predict_mask(L.LX_F32, 512, 128, 128, 512, FAKE, FAKE, 1.0, FAKE,
                                       None) == L.LX_ERR_UNSUPPORTED
+
+
+def test_tuning_knobs_reject_values_outside_their_range(lxmod):
+    L = lxmod
+    assert L._lib.lx_ffn_set_token_tiles_per_workgroup(3) == L.LX_ERR_INVALID_ARG
+    assert L._lib.lx_ffn_set_token_tiles_per_workgroup(-1) == L.LX_ERR_INVALID_ARG
+    for v in (2, 1, 0):
+        assert L._lib.lx_ffn_set_token_tiles_per_workgroup(v) == L.LX_OK
+    assert L._lib.lx_attn_set_rows_per_workgroup(9) == L.LX_ERR_INVALID_ARG
+    assert L._lib.lx_attn_set_rows_per_workgroup(0) == L.LX_OK

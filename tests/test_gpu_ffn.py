@@ -311,3 +311,68 @@ def test_list_rows_shared_by_groups_of_token_tiles(lx, oracle, dtype, tile, T, d
     lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl_full, tile, tile, Y2, H2)
     torch.cuda.synchronize()
     assert np.array_equal(host(Y2), host(Yd))
+
+
+@pytest.mark.parametrize("dtype,T,d,F,G,density,seed,bias", [
+    ("bf16", 512, 192, 704, 2, 0.45, 181, False),   # two list rows, four tiles each; 11 blocks: ragged chunks of four
+    ("bf16", 256, 128, 512, 1, 1.0, 182, True),     # one list for all tokens, dense, biases
+    ("f16", 384, 320, 320, 3, 0.3, 183, False),     # three rows of two tiles; d not a multiple of 256
+    ("bf16", 256, 128, 256, 1, 0.0, 184, False),    # empty list
+    ("bf16", 1024, 128, 2048, 2, 0.2, 185, False),  # several workgroups per XCD range
+])
+def test_two_token_tiles_per_workgroup(lx, oracle, dtype, T, d, F, G, density, seed, bias):
+    """Lists shared by an even number of tiles, run with two token tiles per workgroup (the
+    tuning knob set to 2): the results match the oracle and equal, bit for bit, those of the
+    one-tile kernels -- every output element sees the same products in the same order."""
+    import torch
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, density, seed, dtype=dtype, w_std=0.05)
+    Tt = T // 64
+    gt = Tt // G
+    assert gt % 2 == 0
+    rows_mask = np.ascontiguousarray(c["mask"][:G])
+    full = np.repeat(rows_mask, gt, axis=0)
+    rng = np.random.default_rng(seed)
+    b_up = round_to(rng.standard_normal(F) * 0.1, dtype) if bias else None
+    b_down = round_to(rng.standard_normal(d), dtype) if bias else None
+    H, Y = oracle.ffn_fwd(c["X"], c["W_up"], c["W_down"], full, 64, 64, b_up, b_down)
+    Hq = round_to(H, dtype)
+    _, dX = oracle.ffn_bwd_dx(c["dY"], c["W_up"], c["W_down"], full, Hq > 0, 64, 64)
+
+    X, Wu, Wd, dY = (dev(c[k], dtype) for k in ("X", "W_up", "W_down", "dY"))
+    bu = dev(b_up, dtype) if bias else None
+    bd = dev(b_down, dtype) if bias else None
+    bl = lx.lx_mask_compact(torch.from_numpy(rows_mask).cuda())
+    nblocks = max(bl.nnz_cap * gt, 1)
+    nnz = int(rows_mask.sum()) * gt
+    Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+    ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(lx_dtype(lx, dtype), T, d, F, 64, 64, nblocks, 1)
+                     + 256, dtype=torch.uint8, device="cuda")
+    H_in = torch.zeros((nblocks * 4096,), dtype=X.dtype, device="cuda")
+    H_in[:nnz * 4096] = dev(_grouped_compact(Hq, rows_mask, gt, 64, 64).reshape(-1), dtype)
+
+    def run(tiles):
+        lx.lx_ffn_set_token_tiles_per_workgroup(tiles)
+        try:
+            Hd = torch.full((nblocks * 4096 + 4096,), float("nan"), dtype=X.dtype, device="cuda")
+            Yd = torch.full_like(X, float("nan"))
+            lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, 64, 64, Yd, Hd, b_up=bu, b_down=bd)
+            assert torch.isnan(Hd[nblocks * 4096:]).all(), "wrote past the H_act buffer"
+            dXd = torch.full_like(X, float("nan"))
+            lx.lx_sparse_ffn_bwd_dx(dY, H_in, Wu, Wd, bl, 64, 64, dXd, ws, W_up_t=Wut, W_down_t=Wdt)
+            torch.cuda.synchronize()
+        finally:
+            lx.lx_ffn_set_token_tiles_per_workgroup(0)
+        return host(Yd), host(Hd[:nnz * 4096]).reshape(nnz, 64, 64), host(dXd)
+
+    two, one = run(2), run(1)
+    for name, a, b in zip(("Y", "H", "dX"), two, one):
+        assert np.isfinite(a).all(), name
+        assert np.array_equal(a, b), name
+    refs = dict(Y=Y, H=_grouped_compact(H, rows_mask, gt, 64, 64), dX=dX)
+    for name, g in zip(("Y", "H", "dX"), two):
+        r = refs[name]
+        if not r.any():
+            assert not g.any(), name
+            continue
+        assert rel_err_max(g, r) <= TOL[dtype], (name, rel_err_max(g, r))
+        assert rel_err_fro(g, r) <= FRO[dtype], (name, rel_err_fro(g, r))
