@@ -24,8 +24,8 @@ Workloads (recipes in paper_2510_15964_amd/inputs.py):
                   step (Sec. VI-A).
   config4         OPT-6.7B-shaped layer (configs[3]).
   config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]);
-                  config5:<rho>:shared2 = the same with one FFN list for all token tiles
-                  and two token tiles per FFN workgroup (the dense path at rho = 1).
+                  config5:<rho>:shared = the same with one FFN list for all token tiles
+                  and four token tiles per FFN workgroup (the dense path at rho = 1).
 
 Prints ONE JSON line.  `--sweep FILE` additionally runs the configs[4] density
 sweep and writes one JSON line per density to FILE.
@@ -102,11 +102,11 @@ def make_workload(name: str):
         f = inputs.config5_ffn(rho)
         a = inputs.config5_attn(rho)
         ffn_calls = 1
-        if len(parts) > 2 and parts[2] == "shared2":
+        if len(parts) > 2 and parts[2] == "shared":
             # the same layer with ONE list row for all token tiles (row 0 of the mask, repeated)
-            # and two token tiles per FFN workgroup: the dense path at rho = 1
+            # and up to four token tiles per FFN workgroup: the dense path at rho = 1
             f["mask"] = np.repeat(f["mask"][:1], f["mask"].shape[0], axis=0)
-            f["shared_list"], f["tiles_per_wg"] = True, 2
+            f["shared_list"], f["tiles_per_wg"] = True, 4
     else:
         raise SystemExit(f"unknown workload {name!r}")
     return f, a, ffn_calls
@@ -486,7 +486,7 @@ def main():
         from paper_2510_15964_amd.inputs import DENSITY_SWEEP
         os.makedirs(os.path.dirname(os.path.abspath(args.sweep)), exist_ok=True)
         with open(args.sweep, "w") as fh:
-            for wl in [f"config5:{rho}" for rho in DENSITY_SWEEP] + ["config5:1.0:shared2"]:
+            for wl in [f"config5:{rho}" for rho in DENSITY_SWEEP] + ["config5:1.0:shared"]:
                 rho = wl.split(":", 1)[1]
                 r = run(wl, max(args.steps // 5, 5), 2, False)
                 log(f"config5 rho={rho}: {r['ms_per_step']:.3f} ms/step, "

@@ -364,16 +364,17 @@ lx_status lx_attn_set_rows_per_workgroup(int32_t rows);
 
 /*
  * Tuning knob of the 16-bit FFN calls: how many token tiles one workgroup
- * multiplies with the weight rows it has staged.  Two tiles (possible when an
- * even number of consecutive tiles shares a list row, bl->rows dividing the
- * tile count accordingly) halve the weight bytes moved per product but also the
- * number of workgroups, so they pay for dense or large layers and lose where
- * one tile per workgroup just fills the chip.  tiles = 0 (the default) lets the
- * library choose (two only when the pairs alone outnumber the CUs); 1 or 2
- * fixes it for all later calls of this process (2 still falls back to 1 where
- * list rows are not shared by an even number of tiles, and in the LoRA calls).
- * Results are bit-identical for every value.  Not thread-safe; returns
- * LX_ERR_INVALID_ARG outside 0..2.
+ * multiplies with the weight rows it has staged.  Two or four tiles (possible
+ * when list rows are shared by a multiple of that many consecutive tiles) cut
+ * the weight bytes moved per product to 0.6 / 0.4 but also the number of
+ * workgroups to a half / a quarter, so they pay for dense or large layers and
+ * lose where one tile per workgroup just fills the chip.  tiles = 0 (the
+ * default) lets the library choose (more than one only when the groups alone
+ * outnumber the CUs); 1, 2 or 4 asks for at most that many for all later calls
+ * of this process (the library falls back to 2 or 1 where the list rows are not
+ * shared accordingly, and always uses 1 in the LoRA calls).  Results are
+ * bit-identical for every value.  Not thread-safe; returns LX_ERR_INVALID_ARG
+ * for other values.
  */
 lx_status lx_ffn_set_token_tiles_per_workgroup(int32_t tiles);
 

@@ -297,23 +297,24 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
 }
 
 // ---------------------------------------------------------------------------
-// Two token tiles per workgroup.  When an even number of consecutive token tiles shares a list
-// row (the paper's reduced mask, or a dense layer), two of them can be multiplied with the same
-// weight rows: 128 token rows + 256 weight rows per stage (48 KiB, a ring of three, one
-// workgroup per CU) and a wave tile of 64 x 64, i.e. 0.6 times the transferred and half the
-// LDS-read bytes per product of the kernels above.  Every output element sees the same
-// products in the same order, so the results are bit-identical to the one-tile kernels'.
-// It pays when the launch still fills the chip with half as many workgroups (large or dense
-// layers); the host chooses (launch_ffn_bf16).
+// Several token tiles per workgroup.  When TT = 2 or 4 consecutive token tiles share a list row
+// (the paper's reduced mask, or a dense layer), they can be multiplied with the same weight
+// rows: 64*TT token rows + 256 weight rows per stage (48 KiB in a ring of three, or 64 KiB in a
+// ring of two; one workgroup per CU) and a wave tile of 64 x 32*TT, i.e. 0.6 / 0.4 times the
+// transferred and a half / three eighths of the LDS-read bytes per product of the kernels above.
+// Every output element sees the same products in the same order, so the results are
+// bit-identical to the one-tile kernels'.  It pays when the launch still fills the chip with
+// a half or a quarter as many workgroups (large or dense layers); the host chooses
+// (launch_ffn_bf16).
 // ---------------------------------------------------------------------------
-constexpr int kPairRingStages = 3;
 
-// Epilogue of a 64 x 64 wave tile: acc[ni][ti] -> rows t0 + 32*ti + lane%32 (stride ld elements)
-// and columns n0 + 32*ni + 8*g + 4*(lane/32) + e of `out`; bias over the columns, gate with the
-// same indexing (both may be null).
-template <int DT, int MODE>
-__device__ __forceinline__ void store_tile64(const f32x16 (&acc)[2][2], uint16_t* __restrict__ out,
-                                             long long ld, const uint16_t* __restrict__ bias,
+// Epilogue of one 64 x 64 token tile of a wave tile: acc[ni][2*tile + ti] -> rows 32*ti + lane%32
+// (stride ld elements) and columns 32*ni + 8*g + 4*(lane/32) + e of `out`; bias over the
+// columns, gate with the same indexing (both may be null).
+template <int DT, int MODE, int TT>
+__device__ __forceinline__ void store_tile64(const f32x16 (&acc)[2][TT], int tile,
+                                             uint16_t* __restrict__ out, long long ld,
+                                             const uint16_t* __restrict__ bias,
                                              const uint16_t* __restrict__ gate) {
   const int lane = threadIdx.x % kWave, tl = lane % 32, nq = (lane / 32) * 4;
 #pragma unroll
@@ -326,7 +327,7 @@ __device__ __forceinline__ void store_tile64(const f32x16 (&acc)[2][2], uint16_t
         const long long o = (long long)(32 * ti + tl) * ld + n;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[ni][ti][4 * g + e];
+        for (int e = 0; e < 4; ++e) v[e] = acc[ni][2 * tile + ti][4 * g + e];
         if (bias) {
           const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
           v[0] += to_f32<DT>(bb.x & 0xFFFFu); v[1] += to_f32<DT>(bb.x >> 16);
@@ -349,20 +350,22 @@ __device__ __forceinline__ void store_tile64(const f32x16 (&acc)[2][2], uint16_t
       }
 }
 
-// sdd for pairs of token tiles: work item = (pair of consecutive tiles of one list row, up to four
-// consecutive list entries); wave w multiplies entry w % 4 with tile w / 4 of the pair.
-// `rows` counts token tiles (even), gt tiles share a list row (even).  MODE / LORA as above.
-template <int DT, int MODE, bool LORA>
-__global__ __launch_bounds__(kThreads) void ffn_sdd2_bf16(
+// sdd for groups of TT token tiles: work item = (TT consecutive tiles of one list row, up to four
+// consecutive list entries); wave w multiplies entry w % 4 with half w / 4 of the group's tiles.
+// `rows` counts token tiles, gt of which share a list row (both multiples of TT).  MODE / LORA as
+// above.
+template <int DT, int MODE, bool LORA, int TT>
+__global__ __launch_bounds__(kThreads) void ffn_sddn_bf16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int rows, int gt, int K, int nnz_cap,
     uint16_t* __restrict__ out_act, const uint16_t* __restrict__ gate_act,
     const uint16_t* __restrict__ A2, const uint16_t* __restrict__ W2) {
-  __shared__ __attribute__((aligned(1024))) uint16_t ring[kPairRingStages * kStageElems2];
-  int pair, chunk;
-  if (!find_work(row_ptr, rows / 2, gt / 2, blockIdx.x, 4, pair, chunk)) return;
-  const int i0 = 2 * pair;                       // first tile of the pair
+  using St = MultiStage<TT>;
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[St::kStages * St::kElems];
+  int grp, chunk;
+  if (!find_work(row_ptr, rows / TT, gt / TT, blockIdx.x, 4, grp, chunk)) return;
+  const int i0 = TT * grp;                       // first tile of the group
   const int rs = row_ptr[i0 / gt], n_i = row_ptr[i0 / gt + 1] - rs;
   const int first = chunk * 4;
   const int p0 = rs + first;
@@ -370,15 +373,15 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd2_bf16(
   const int nb = min(min(4, n_i - first), nnz_cap - p0);
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
 
-  const uint16_t* src[kIssues2];
+  const uint16_t* src[St::kIss];
 #pragma unroll
-  for (int u = 0; u < kIssues2; ++u) {
+  for (int u = 0; u < St::kIss; ++u) {
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 2) {
-      src[u] = A + ((long long)i0 * 64 + row) * K + seg * 8;      // 128 consecutive token rows
+    if (u < TT) {
+      src[u] = A + ((long long)i0 * 64 + row) * K + seg * 8;      // 64*TT consecutive token rows
     } else {
-      const int blk = (row - kRowsB2) / 64, r = (row - kRowsB2) % 64;
+      const int blk = (row - St::kShared) / 64, r = (row - St::kShared) % 64;
       // blocks past the end of the list are filled from the first block (never used)
       const int j = col_idx[p0 + (blk < nb ? blk : 0)];
       src[u] = W + ((long long)j * 64 + r) * K + seg * 8;
@@ -387,22 +390,22 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd2_bf16(
   auto src2 = [&](int u) -> const uint16_t* {    // the low-rank step, computed when it is issued
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 2) return A2 + ((long long)i0 * 64 + row) * 64 + seg * 8;
-    const int blk = (row - kRowsB2) / 64, r = (row - kRowsB2) % 64;
+    if (u < TT) return A2 + ((long long)i0 * 64 + row) * 64 + seg * 8;
+    const int blk = (row - St::kShared) / 64, r = (row - St::kShared) % 64;
     const int j = col_idx[p0 + (blk < nb ? blk : 0)];
     return W2 + ((long long)j * 64 + r) * 64 + seg * 8;
   };
-  const int rg = wave % 4, th = wave / 4;        // list entry of the four, tile of the pair
+  const int rg = wave % 4, th = wave / 4;        // list entry of the four, half of the group's tiles
   const bool wave_on = rg < nb;
-  f32x16 acc[2][2];
+  f32x16 acc[2][TT];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < TT; ++y)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
   const int ksteps = K / kBK;
-  run_ring_of<kPairRingStages, kIssues2, kStageElems2, 2>(
+  run_ring_of<St::kStages, St::kIss, St::kElems, TT>(
       ksteps + (LORA ? 1 : 0), src, src2,
       [=](int s, long long& ob, long long& oa) {
         const bool alt = LORA && s == ksteps;
@@ -410,63 +413,70 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd2_bf16(
         return alt;
       },
       ring, [&](const uint16_t* stage) {
-        if (wave_on) mma_step64<DT>(stage, rg, th, acc);
+        if (wave_on) mma_step64<DT, TT>(stage, rg, th, acc);
       });
   if (!wave_on) return;
-  const int j = col_idx[p0 + rg], i = i0 + th;
-  // compact activation block of (tile i, list entry): [entry][tile within the row's group]
-  const long long p = (long long)rs * gt + (long long)(first + rg) * gt + i % gt;
-  store_tile64<DT, MODE>(acc, out_act + p * 4096, 64, MODE == 0 && bias ? bias + j * 64 : nullptr,
-                         MODE == 1 ? gate_act + p * 4096 : nullptr);
+  const int j = col_idx[p0 + rg];
+#pragma unroll
+  for (int t = 0; t < TT / 2; ++t) {
+    const int i = i0 + (TT / 2) * th + t;
+    // compact activation block of (tile i, list entry): [entry][tile within the row's group]
+    const long long p = (long long)rs * gt + (long long)(first + rg) * gt + i % gt;
+    store_tile64<DT, MODE, TT>(acc, t, out_act + p * 4096, 64,
+                               MODE == 0 && bias ? bias + j * 64 : nullptr,
+                               MODE == 1 ? gate_act + p * 4096 : nullptr);
+  }
 }
 
-// dsd for pairs of token tiles: the workgroup of grid row y works on tiles 2y, 2y + 1 (one list
-// row) and 256 output columns; wave w multiplies columns 64 * (w % 4) .. with tile w / 4.
-template <int DT, bool LORA>
-__global__ __launch_bounds__(kThreads) void ffn_dsd2_bf16(
+// dsd for groups of TT token tiles: the workgroup of grid row y works on tiles TT*y .. (one list
+// row) and 256 output columns; wave w multiplies columns 64 * (w % 4) .. with half w / 4 of the
+// group's tiles.
+template <int DT, bool LORA, int TT>
+__global__ __launch_bounds__(kThreads) void ffn_dsdn_bf16(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ W, long long ldw,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
     uint16_t* __restrict__ out, const uint16_t* __restrict__ act2,
     const uint16_t* __restrict__ W2) {
-  __shared__ __attribute__((aligned(1024))) uint16_t ring[kPairRingStages * kStageElems2];
-  const int i0 = 2 * balanced_tile(row_ptr, gridDim.y, gt / 2, nnz_cap, blockIdx.y, false,
-                                   reinterpret_cast<int*>(ring));
+  using St = MultiStage<TT>;
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[St::kStages * St::kElems];
+  const int i0 = TT * balanced_tile(row_ptr, gridDim.y, gt / TT, nnz_cap, blockIdx.y, false,
+                                    reinterpret_cast<int*>(ring));
   const int n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i0 / gt];
   const int n_i = min(row_ptr[i0 / gt + 1], nnz_cap) - rs;   // <= 0: nothing within the capacity
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  const int rg = wave % 4, th = wave / 4;        // 64 output columns of the 256, tile of the pair
+  const int rg = wave % 4, th = wave / 4;        // 64 output columns of the 256, half of the tiles
   const bool wave_on = n0 + 64 * rg < ncols_out;
 
-  const uint16_t* src[kIssues2];
+  const uint16_t* src[St::kIss];
 #pragma unroll
-  for (int u = 0; u < kIssues2; ++u) {
+  for (int u = 0; u < St::kIss; ++u) {
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 2) {
-      src[u] = act + row * 64 + seg * 8;          // the two tiles' blocks of an entry are adjacent
+    if (u < TT) {
+      src[u] = act + row * 64 + seg * 8;          // the tiles' blocks of an entry are adjacent
     } else {
-      const int n = min(n0 + row - kRowsB2, ncols_out - 1);   // rows past the edge: re-read the last
+      const int n = min(n0 + row - St::kShared, ncols_out - 1);   // rows past the edge: re-read the last
       src[u] = W + (long long)n * ldw + seg * 8;
     }
   }
   auto src2 = [&](int u) -> const uint16_t* {     // the low-rank step, computed when it is issued
     const int g = wave + kFW * u, row = 8 * g + lane / 8;
     const int seg = (lane % 8) ^ swz(row);
-    if (u < 2) return act2 + ((long long)i0 * 64 + row) * 64 + seg * 8;
-    const int n = min(n0 + row - kRowsB2, ncols_out - 1);
+    if (u < TT) return act2 + ((long long)i0 * 64 + row) * 64 + seg * 8;
+    const int n = min(n0 + row - St::kShared, ncols_out - 1);
     return W2 + (long long)n * 64 + seg * 8;
   };
-  f32x16 acc[2][2];
+  f32x16 acc[2][TT];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < TT; ++y)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
   const int lsteps = n_i > 0 ? n_i : 0;
-  run_ring_of<kPairRingStages, kIssues2, kStageElems2, 2>(
+  run_ring_of<St::kStages, St::kIss, St::kElems, TT>(
       lsteps + (LORA ? 1 : 0), src, src2,
       [&](int s, long long& ob, long long& oa) {
         const bool alt = LORA && s == lsteps;
@@ -475,13 +485,15 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd2_bf16(
         return alt;
       },
       ring, [&](const uint16_t* stage) {
-        if (wave_on) mma_step64<DT>(stage, rg, th, acc);
+        if (wave_on) mma_step64<DT, TT>(stage, rg, th, acc);
       });
   if (!wave_on) return;
   // ncols_out is a multiple of 64 (the host checks d % 64 == 0): a wave's 64 columns are all inside
   const int n = n0 + 64 * rg;
-  store_tile64<DT, 2>(acc, out + (long long)(i0 + th) * 64 * ncols_out + n, ncols_out,
-                      bias ? bias + n : nullptr, nullptr);
+#pragma unroll
+  for (int t = 0; t < TT / 2; ++t)
+    store_tile64<DT, 2, TT>(acc, t, out + (long long)(i0 + (TT / 2) * th + t) * 64 * ncols_out + n,
+                            ncols_out, bias ? bias + n : nullptr, nullptr);
 }
 
 // pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
@@ -494,19 +506,46 @@ static dim3 sdd_grid(int Tt, int gt, int nnz_cap) {
   return dim3(8 * 8 * ((Lub + 7) / 8));
 }
 
-// Token tiles per workgroup: 0 = chosen here, 1 or 2 = fixed by the caller.
+// Token tiles per workgroup: 0 = chosen here; 1, 2 or 4 = asked for by the caller.
 static int g_ffn_tiles_per_wg = 0;
 hipError_t set_ffn_tiles_per_wg(int n) {
-  if (n < 0 || n > 2) return hipErrorInvalidValue;
+  if (n != 0 && n != 1 && n != 2 && n != 4) return hipErrorInvalidValue;
   g_ffn_tiles_per_wg = n;
   return hipSuccess;
 }
-// Pairs of tiles need list rows shared by an even number of tiles; left to itself the library
-// takes them only when the pairs alone outnumber the CUs (the number of list entries, which
-// decides whether fewer, larger workgroups still fill the chip, is known on the device only).
-static bool use_tile_pairs(int Tt, int gt) {
-  if (gt % 2 != 0 || g_ffn_tiles_per_wg == 1) return false;
-  return g_ffn_tiles_per_wg == 2 || Tt / 2 >= kCUs;
+// Groups of tiles need list rows shared by a multiple of that many tiles; left to itself the
+// library takes them only when the groups alone outnumber the CUs (the number of list entries,
+// which decides whether fewer, larger workgroups still fill the chip, is known on the device
+// only).
+static int tiles_per_wg(int Tt, int gt) {
+  const int want = g_ffn_tiles_per_wg;
+  if (want == 1) return 1;
+  for (int tt = 4; tt > 1; tt /= 2)
+    if (gt % tt == 0 && (want == 0 ? Tt / tt >= kCUs : want >= tt)) return tt;
+  return 1;
+}
+
+template <int DT, int TT>
+static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t* A, const uint16_t* W1,
+                         const uint16_t* b1, const uint16_t* W2, const uint16_t* b2,
+                         const int* row_ptr, const int* col_idx, int nnz_cap, uint16_t* act_out,
+                         const uint16_t* act_gate, uint16_t* out, hipStream_t st) {
+  const uint16_t* none = nullptr;
+  const dim3 g1 = sdd_grid(Tt / TT, gt / TT, nnz_cap);
+  {
+    ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
+    if (pass == 0)
+      hipLaunchKernelGGL((ffn_sddn_bf16<DT, 0, false, TT>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+    else
+      hipLaunchKernelGGL((ffn_sddn_bf16<DT, 1, false, TT>), g1, dim3(kThreads), 0, st, A, W1, none,
+                         row_ptr, col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
+  }
+  if (hipPeekAtLastError() != hipSuccess) return;
+  ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
+  hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3((d + kRowsA - 1) / kRowsA, Tt / TT),
+                     dim3(kThreads), 0, st, (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr,
+                     col_idx, gt, d, nnz_cap, out, none, none);
 }
 
 template <int DT>
@@ -517,20 +556,24 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
                            hipStream_t st) {
   (void)Fb;
   if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
-  const bool pairs = use_tile_pairs(Tt, gt);
-  const dim3 g1 = pairs ? sdd_grid(Tt / 2, gt / 2, nnz_cap) : sdd_grid(Tt, gt, nnz_cap);
+  const int tt = tiles_per_wg(Tt, gt);
+  if (tt == 4) {
+    launch_multi<DT, 4>(pass, Tt, gt, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap, act_out,
+                        act_gate, out, st);
+    return hipGetLastError();
+  }
+  if (tt == 2) {
+    launch_multi<DT, 2>(pass, Tt, gt, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap, act_out,
+                        act_gate, out, st);
+    return hipGetLastError();
+  }
+  const dim3 g1 = sdd_grid(Tt, gt, nnz_cap);
   const uint16_t* none = nullptr;
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
-    if (pass == 0 && pairs)
-      hipLaunchKernelGGL((ffn_sdd2_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
-                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
-    else if (pass == 0)
+    if (pass == 0)
       hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
-    else if (pairs)
-      hipLaunchKernelGGL((ffn_sdd2_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
-                         col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
     else
       hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
@@ -538,14 +581,9 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
-  if (pairs)
-    hipLaunchKernelGGL((ffn_dsd2_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt / 2), dim3(kThreads),
-                       0, st, (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
-                       nnz_cap, out, none, none);
-  else
-    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0,
-                       st, (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
-                       nnz_cap, out, none, none);
+  hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap,
+                     out, none, none);
   return hipGetLastError();
 }
 

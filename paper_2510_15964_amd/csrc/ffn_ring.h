@@ -88,39 +88,48 @@ __device__ __forceinline__ void mma_step(const uint16_t* stage, int wave, f32x16
       for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32<DT>(a[kk][ni], b[kk][ti], acc[ni][ti]);
 }
 
-// The same for a stage of 128 shared rows (two token tiles) + 256 weight rows and a wave tile of
-// 64 weight rows (group rg of four) x 64 shared rows (half th): half the LDS bytes per product
-// of the 32 x 64 tile above.  acc[ni][ti]: weight rows 64*rg + 32*ni.., shared rows 64*th + 32*ti..
-constexpr int kRowsB2 = 2 * kRowsB;
-constexpr int kStageElems2 = (kRowsB2 + kRowsA) * kBK;   // 48 KiB
-constexpr int kIssues2 = (kRowsB2 + kRowsA) / 8 / kFW;    // 6 DMA instructions per wave and stage
-template <int DT>
+// The same for a stage of 64*TT shared rows (TT = 2 or 4 token tiles) + 256 weight rows and a
+// wave tile of 64 weight rows (group rg of four) x 32*TT shared rows (half th of them): half
+// (TT = 2) or three eighths (TT = 4) of the LDS bytes per product of the 32 x 64 tile above.
+// acc[ni][ti]: weight rows 64*rg + 32*ni.., shared rows 32*TT*th + 32*ti..
+template <int TT>
+struct MultiStage {
+  static constexpr int kShared = kRowsB * TT;
+  static constexpr int kElems = (kShared + kRowsA) * kBK;   // 48 / 64 KiB
+  static constexpr int kIss = (kShared + kRowsA) / 8 / kFW; // DMA instructions per wave and stage
+  static constexpr int kStages = TT == 2 ? 3 : 2;           // what fits 160 KiB of LDS
+};
+template <int DT, int TT>
 __device__ __forceinline__ void mma_step64(const uint16_t* stage, int rg, int th,
-                                           f32x16 (&acc)[2][2]) {
+                                           f32x16 (&acc)[2][TT]) {
   const int lane = threadIdx.x % kWave;
   const int r = lane % 32, h2 = lane / 32;
-  uint4 a[4][2], b[4][2];
+  // operands of two k16 slices at a time: 8 + 4*TT registers of reads in flight
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const int seg = 2 * kk + h2;
+  for (int k2 = 0; k2 < 2; ++k2) {
+    uint4 a[2][2], b[2][TT];
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-      const int ra = kRowsB2 + 64 * rg + 32 * ni + r;
-      a[kk][ni] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+    for (int e = 0; e < 2; ++e) {
+      const int seg = 2 * (2 * k2 + e) + h2;
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int ra = MultiStage<TT>::kShared + 64 * rg + 32 * ni + r;
+        a[e][ni] = *reinterpret_cast<const uint4*>(stage + ra * kBK + ((seg ^ swz(ra)) << 3));
+      }
+#pragma unroll
+      for (int ti = 0; ti < TT; ++ti) {
+        const int rb = 32 * TT * th + 32 * ti + r;
+        b[e][ti] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
+      }
     }
+    __builtin_amdgcn_sched_barrier(0);   // keep the reads above: the scheduler would sink them
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti) {
-      const int rb = 64 * th + 32 * ti + r;
-      b[kk][ti] = *reinterpret_cast<const uint4*>(stage + rb * kBK + ((seg ^ swz(rb)) << 3));
-    }
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mfma32<DT>(a[e][ni], b[e][ti], acc[ni][ti]);
   }
-  __builtin_amdgcn_sched_barrier(0);   // keep the reads above: the scheduler would sink them
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int ti = 0; ti < 2; ++ti) acc[ni][ti] = mfma32<DT>(a[kk][ni], b[kk][ti], acc[ni][ti]);
 }
 
 // Pipeline over nsteps K-steps through a ring of NST stages: while step s is multiplied, the

@@ -262,9 +262,9 @@ def test_half_precision_is_accepted_where_bfloat16_is(lxmod):
 
 def test_tuning_knobs_reject_values_outside_their_range(lxmod):
     L = lxmod
-    assert L._lib.lx_ffn_set_token_tiles_per_workgroup(3) == L.LX_ERR_INVALID_ARG
-    assert L._lib.lx_ffn_set_token_tiles_per_workgroup(-1) == L.LX_ERR_INVALID_ARG
-    for v in (2, 1, 0):
+    for v in (3, 5, 8, -1):
+        assert L._lib.lx_ffn_set_token_tiles_per_workgroup(v) == L.LX_ERR_INVALID_ARG
+    for v in (4, 2, 1, 0):
         assert L._lib.lx_ffn_set_token_tiles_per_workgroup(v) == L.LX_OK
     assert L._lib.lx_attn_set_rows_per_workgroup(9) == L.LX_ERR_INVALID_ARG
     assert L._lib.lx_attn_set_rows_per_workgroup(0) == L.LX_OK

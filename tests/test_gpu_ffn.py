@@ -320,10 +320,10 @@ def test_list_rows_shared_by_groups_of_token_tiles(lx, oracle, dtype, tile, T, d
     ("bf16", 256, 128, 256, 1, 0.0, 184, False),    # empty list
     ("bf16", 1024, 128, 2048, 2, 0.2, 185, False),  # several workgroups per XCD range
 ])
-def test_two_token_tiles_per_workgroup(lx, oracle, dtype, T, d, F, G, density, seed, bias):
-    """Lists shared by an even number of tiles, run with two token tiles per workgroup (the
-    tuning knob set to 2): the results match the oracle and equal, bit for bit, those of the
-    one-tile kernels -- every output element sees the same products in the same order."""
+def test_several_token_tiles_per_workgroup(lx, oracle, dtype, T, d, F, G, density, seed, bias):
+    """Lists shared by an even number of tiles, run with two and with four token tiles per
+    workgroup (the tuning knob): the results match the oracle and equal, bit for bit, those of
+    the one-tile kernels -- every output element sees the same products in the same order."""
     import torch
     c = inputs.ffn_bernoulli(T, d, F, 64, 64, density, seed, dtype=dtype, w_std=0.05)
     Tt = T // 64
@@ -364,10 +364,11 @@ def test_two_token_tiles_per_workgroup(lx, oracle, dtype, T, d, F, G, density, s
             lx.lx_ffn_set_token_tiles_per_workgroup(0)
         return host(Yd), host(Hd[:nnz * 4096]).reshape(nnz, 64, 64), host(dXd)
 
-    two, one = run(2), run(1)
-    for name, a, b in zip(("Y", "H", "dX"), two, one):
-        assert np.isfinite(a).all(), name
-        assert np.array_equal(a, b), name
+    four, two, one = run(4), run(2), run(1)     # (4 falls back to 2 where gt is not a multiple of 4)
+    for multi in (four, two):
+        for name, a, b in zip(("Y", "H", "dX"), multi, one):
+            assert np.isfinite(a).all(), name
+            assert np.array_equal(a, b), name
     refs = dict(Y=Y, H=_grouped_compact(H, rows_mask, gt, 64, 64), dX=dX)
     for name, g in zip(("Y", "H", "dX"), two):
         r = refs[name]
