@@ -197,11 +197,16 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
 // at once, two workgroups per CU, rows s and s + Tt/2, which the round robin of the dispatcher
 // places on the same CU, get ranks s and Tt - 1 - s, a long list next to a short one.
 constexpr int kBalTiles = 128;
-__device__ __forceinline__ int balanced_tile(const int* __restrict__ row_ptr, int Tt, int gt,
-                                             int nnz_cap, int slot, bool resident, int* lens) {
-  if (Tt > kBalTiles || Tt < 3) return slot;
+// The launch covers the Tt tiles first .. first + Tt - 1; the result is a tile of that range.
+__device__ __forceinline__ int balanced_tile(const int* __restrict__ row_ptr, int first, int Tt,
+                                             int gt, int nnz_cap, int slot, bool resident,
+                                             int* lens) {
+  if (Tt > kBalTiles || Tt < 3) return first + slot;
   const int tid = threadIdx.x;
-  if (tid < Tt) lens[tid] = min(row_ptr[tid / gt + 1], nnz_cap) - row_ptr[tid / gt];
+  if (tid < Tt) {
+    const int r = (first + tid) / gt;
+    lens[tid] = min(row_ptr[r + 1], nnz_cap) - row_ptr[r];
+  }
   __syncthreads();
   const int half = (Tt + 1) / 2;
   const int want = resident && slot >= half ? Tt - 1 - (slot - half) : slot;
@@ -217,7 +222,7 @@ __device__ __forceinline__ int balanced_tile(const int* __restrict__ row_ptr, in
   __syncthreads();
   const int tile = __builtin_amdgcn_readfirstlane(lens[kBalTiles]);
   __syncthreads();   // lens is memory the caller reuses
-  return tile;
+  return first + tile;
 }
 
 // out[i-tile rows, n0 .. n0+255] = sum_s act[p_s] [64 x 64] . W[n0.., j_s*64 ..]^T (+ bias)
@@ -229,9 +234,10 @@ __global__ __launch_bounds__(kThreads) void ffn_dsd_bf16(
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
     uint16_t* __restrict__ out, const uint16_t* __restrict__ act2,
-    const uint16_t* __restrict__ W2) {
+    const uint16_t* __restrict__ W2, int tile0) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kDsdStages * kStageElems];
-  const int i = balanced_tile(row_ptr, gridDim.y, gt, nnz_cap, blockIdx.y,
+  // the launch covers the token tiles tile0 .. tile0 + gridDim.y - 1
+  const int i = balanced_tile(row_ptr, tile0, gridDim.y, gt, nnz_cap, blockIdx.y,
                               gridDim.x * gridDim.y <= 2 * kCUs, reinterpret_cast<int*>(ring));
   const int n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i / gt];
@@ -440,7 +446,7 @@ __global__ __launch_bounds__(kThreads) void ffn_dsdn_bf16(
     const uint16_t* __restrict__ W2) {
   using St = MultiStage<TT>;
   __shared__ __attribute__((aligned(1024))) uint16_t ring[St::kStages * St::kElems];
-  const int i0 = TT * balanced_tile(row_ptr, gridDim.y, gt / TT, nnz_cap, blockIdx.y, false,
+  const int i0 = TT * balanced_tile(row_ptr, 0, gridDim.y, gt / TT, nnz_cap, blockIdx.y, false,
                                     reinterpret_cast<int*>(ring));
   const int n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i0 / gt];
@@ -543,9 +549,22 @@ static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t*
   }
   if (hipPeekAtLastError() != hipSuccess) return;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
-  hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3((d + kRowsA - 1) / kRowsA, Tt / TT),
-                     dim3(kThreads), 0, st, (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr,
-                     col_idx, gt, d, nnz_cap, out, none, none);
+  // The dsd launch has (column chunks) x (tile groups) workgroups, one per CU, all about equally
+  // long.  When they make whole rounds plus a small rest, that rest would keep the launch alive
+  // for a full round on a fraction of the chip: the tile groups of whole rounds go to this
+  // kernel, the remaining tiles to the one-tile kernel (two workgroups per CU, shorter rounds).
+  const int chunks = (d + kRowsA - 1) / kRowsA;
+  int groups = Tt / TT;
+  const long long wgs = (long long)chunks * groups, rest = wgs % kCUs;
+  if (wgs > kCUs && rest > 0 && rest * 5 < kCUs * 3) groups = (int)((wgs - rest) / chunks);
+  if (groups > 0)
+    hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3(chunks, groups), dim3(kThreads), 0, st,
+                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       nnz_cap, out, none, none);
+  if (groups * TT < Tt)
+    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3(chunks, Tt - groups * TT), dim3(kThreads), 0, st,
+                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       nnz_cap, out, none, none, groups * TT);
 }
 
 template <int DT>
@@ -583,7 +602,7 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
                      (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap,
-                     out, none, none);
+                     out, none, none, 0);
   return hipGetLastError();
 }
 
@@ -621,7 +640,7 @@ static hipError_t launch_ffn_lora_fwd_bf16_t(int Tt, int gt, int d, int F, const
   ProfScope ps(kKFfnDown, st);
   hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
                      (const uint16_t*)H_act, W_down, (long long)F, none, row_ptr, col_idx, gt, d,
-                     nnz_cap, Y, none, none);
+                     nnz_cap, Y, none, none, 0);
   return hipGetLastError();
 }
 
@@ -660,7 +679,7 @@ static hipError_t launch_ffn_lora_bwd_bf16_t(int Tt, int gt, int d, int F, const
     ProfScope ps(kKFfnDx, st);
     hipLaunchKernelGGL((ffn_dsd_bf16<DT, true>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
                        (const uint16_t*)dZ, W_up_t, (long long)F, none, row_ptr, col_idx, gt, d,
-                       nnz_cap, dX, (const uint16_t*)G, (const uint16_t*)A_t);
+                       nnz_cap, dX, (const uint16_t*)G, (const uint16_t*)A_t, 0);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -377,3 +377,43 @@ def test_several_token_tiles_per_workgroup(lx, oracle, dtype, T, d, F, G, densit
             continue
         assert rel_err_max(g, r) <= TOL[dtype], (name, rel_err_max(g, r))
         assert rel_err_fro(g, r) <= FRO[dtype], (name, rel_err_fro(g, r))
+
+
+def test_several_token_tiles_dsd_round_split(lx, oracle):
+    """A shape whose four-tile dsd launch is whole rounds of workgroups plus a small rest
+    (3 column chunks x 90 tile groups = 270 for 256 CUs): the rest goes to the one-tile kernel.
+    The results equal those of one tile per workgroup bit for bit, and sampled tiles of both
+    regions match the oracle."""
+    import torch
+    T, d, F = 360 * 64, 768, 256
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, 0.75, 191, dtype="bf16", w_std=0.05)
+    row = np.ascontiguousarray(c["mask"][:1])
+    row[0, 0] = 1
+    X, Wu, Wd, dY = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down", "dY"))
+    bl = lx.lx_mask_compact(torch.from_numpy(row).cuda())
+    gt, nnz = T // 64, int(row.sum())
+    nblocks = bl.nnz_cap * gt
+    Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+    ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(lx.LX_BF16, T, d, F, 64, 64, nblocks, 1) + 256,
+                     dtype=torch.uint8, device="cuda")
+
+    def run(tiles):
+        lx.lx_ffn_set_token_tiles_per_workgroup(tiles)
+        try:
+            Hd = torch.zeros((nblocks * 4096,), dtype=X.dtype, device="cuda")
+            Yd = torch.full_like(X, float("nan"))
+            lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, 64, 64, Yd, Hd)
+            dXd = torch.full_like(X, float("nan"))
+            lx.lx_sparse_ffn_bwd_dx(dY, Hd, Wu, Wd, bl, 64, 64, dXd, ws, W_up_t=Wut, W_down_t=Wdt)
+            torch.cuda.synchronize()
+        finally:
+            lx.lx_ffn_set_token_tiles_per_workgroup(0)
+        return host(Yd), host(dXd)
+
+    (Y4, dX4), (Y1, dX1) = run(4), run(1)
+    assert np.isfinite(Y4).all() and np.isfinite(dX4).all()
+    assert np.array_equal(Y4, Y1) and np.array_equal(dX4, dX1)
+    for i in (3, 355):                        # a tile of the four-tile launch, one of the remainder
+        sl = slice(i * 64, (i + 1) * 64)
+        H, Y = oracle.ffn_fwd(c["X"][sl], c["W_up"], c["W_down"], row, 64, 64)
+        assert rel_err_max(Y4[sl], Y) <= TOL["bf16"] and rel_err_fro(Y4[sl], Y) <= FRO["bf16"]
