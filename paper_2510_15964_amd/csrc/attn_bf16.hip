@@ -720,8 +720,15 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
 // ---------------------------------------------------------------------------
 // backward, key side: dK and dV for the key blocks of one workgroup
 // ---------------------------------------------------------------------------
-template <int D, int DT>
-__global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf16(const AttnArgs a) {
+// WHICH = 0: dK and dV in one walk (head size 64).  At head size 128 the two gradients together need
+// 406 registers, i.e. one workgroup per CU and nothing to hide a wavefront's latency behind, so the
+// launcher runs the kernel twice there: WHICH = 1 computes dV only (S, P, dV += dO^T P), WHICH = 2
+// dK only (S, dP, dS, dK += Q^T dS), each with two workgroups per CU; the tiles of a block are
+// transferred and its scores computed twice, which costs less than the idle SIMDs did.
+template <int D, int DT, int WHICH>
+__global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : (WHICH == 0 ? 1 : 2)) void attn_bwd_dkv_bf16(
+    const AttnArgs a) {
+  constexpr bool kDV = WHICH != 2, kDK = WHICH != 1;
   __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[2][2 * 64 * D];   // stage: Q tile, dO tile
   // K and V tiles of a row, brought in one row ahead (head size 64 only: with 128 the kernel is
   // at its register limit and the extra addressing spills)
@@ -750,8 +757,8 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
         f32x16 z[D / 32];
         zero(z);
         const long long koff = base_of(rows.head(j)) + (long long)(rows.blk(j) * 64 + kl) * a.ss;
-        store_acc<D, DT>(z, 0.f, a.dV + koff);
-        store_acc<D, DT>(z, 0.f, a.dK + koff);
+        if (kDV) store_acc<D, DT>(z, 0.f, a.dV + koff);
+        if (kDK) store_acc<D, DT>(z, 0.f, a.dK + koff);
       }
   }
 
@@ -776,11 +783,11 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
         vf[s] = lds_read16((own_addr + 2 * 64 * D) | (own_off ^ tile_off<D>(0, 16 * s)));
       } else {
         kf[s] = *reinterpret_cast<const uint4*>(a.K + koff + 16 * s + 8 * h2);
-        vf[s] = *reinterpret_cast<const uint4*>(a.V + koff + 16 * s + 8 * h2);
+        if (kDK) vf[s] = *reinterpret_cast<const uint4*>(a.V + koff + 16 * s + 8 * h2);
       }
     }
-    zero(dk_acc);
-    zero(dv_acc);
+    if (kDK) zero(dk_acc);
+    if (kDV) zero(dv_acc);
   };
   auto prefetch = [&](int k) {
     const long long t0 = base_of(rows.head(k)) + (long long)rows.blk(k) * 64 * a.ss;
@@ -800,50 +807,64 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : 1) void attn_bwd_dkv_bf1
     const float* stt = sstat[stage];
     f32x16 s_acc, dp_acc;
     mma_rows<D, DT>(stg, lo, kf, s_acc);                   // S[q][key]
-    mma_rows<D, DT>(stg + 2 * 64 * D, lo, vf, dp_acc);     // dP[q][key]
+    if (kDK) mma_rows<D, DT>(stg + 2 * 64 * D, lo, vf, dp_acc);     // dP[q][key]
     // diagonal block: here the rows of the score tile are queries and the lane is the key
     if (a.causal && col == kb) mask_diag_t(s_acc, own, part);
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int q0 = 8 * g + 4 * h2;                 // four consecutive queries of this half
       const float4 nl = *reinterpret_cast<const float4*>(stt + 32 * part + q0);
-      const float4 dl = *reinterpret_cast<const float4*>(stt + 64 + 32 * part + q0);
-      const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
+      const float nls[4] = {nl.x, nl.y, nl.z, nl.w};
+      float dls[4] = {0.f, 0.f, 0.f, 0.f};
+      if (kDK) {
+        const float4 dl = *reinterpret_cast<const float4*>(stt + 64 + 32 * part + q0);
+        dls[0] = dl.x; dls[1] = dl.y; dls[2] = dl.z; dls[3] = dl.w;
+      }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int v = 4 * g + e;
         const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[v], sc, nls[e]));
-        s_acc[v] = p;                             // P
-        dp_acc[v] = p * (dp_acc[v] - dls[e]);     // dS
+        s_acc[v] = p;                                         // P
+        if (kDK) dp_acc[v] = p * (dp_acc[v] - dls[e]);        // dS
       }
     }
     // registers are what limits the number of resident wavefronts here, so the transposed
     // operands are read only when they are needed
     __builtin_amdgcn_sched_barrier(0);
-    TrOps<D> dot;
-    load_tr<D>(stg + 2 * 64 * D, lo, dot);
-    mma_tr<D, DT>(dot, s_acc, dv_acc);            // dV^T += dO^T P
-    TrOps<D> qt;
-    load_tr<D>(stg, lo, qt);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_tr<D, DT>(qt, dp_acc, dk_acc);            // dK^T += Q^T dS
+    if (kDV) {
+      TrOps<D> dot;
+      load_tr<D>(stg + 2 * 64 * D, lo, dot);
+      mma_tr<D, DT>(dot, s_acc, dv_acc);            // dV^T += dO^T P
+    }
+    if (kDK) {
+      TrOps<D> qt;
+      load_tr<D>(stg, lo, qt);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_tr<D, DT>(qt, dp_acc, dk_acc);            // dK^T += Q^T dS
+    }
   };
   // dV and dK = sums over the two query halves, exchanged one after the other through the
   // same LDS area
   auto row_end = [&](int, int stage) {
     float* area = reinterpret_cast<float*>(st[stage]);
-    if (D == 128) {      // 254 registers without it: the symmetric exchange would spill
-      lds_barrier();
-      if (part == 1) put_all<D>(area, own, dv_acc);
-      lds_barrier();
-      if (part == 0) merge_all<D>(area, own, dv_acc);
-      lds_barrier();
-      if (part == 1) put_all<D>(area, own, dk_acc);
-      lds_barrier();
-      if (part == 0) {
-        merge_all<D>(area, own, dk_acc);
-        store_acc<D, DT>(dv_acc, 1.f, a.dV + koff);
-        store_acc<D, DT>(dk_acc, a.scale, a.dK + koff);
+    if (D == 128) {      // the one-sided exchange (the symmetric one costs registers this size lacks)
+      if (kDV) {
+        lds_barrier();
+        if (part == 1) put_all<D>(area, own, dv_acc);
+        lds_barrier();
+        if (part == 0) {
+          merge_all<D>(area, own, dv_acc);
+          store_acc<D, DT>(dv_acc, 1.f, a.dV + koff);
+        }
+      }
+      if (kDK) {
+        lds_barrier();
+        if (part == 1) put_all<D>(area, own, dk_acc);
+        lds_barrier();
+        if (part == 0) {
+          merge_all<D>(area, own, dk_acc);
+          store_acc<D, DT>(dk_acc, a.scale, a.dK + koff);
+        }
       }
       return;
     }
@@ -925,9 +946,15 @@ static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
   if (e != hipSuccess) return e;
   {
     ProfScope ps(kKAttnDkv, st);
-    a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDkvOcc64 : 1));
+    a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * (D == 64 ? kDkvOcc64 : 2));
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT>), dim3(a.Hh / a.vheads, B, G * a.vheads), dim3(kAT), 0, st, a);
+    const dim3 grid(a.Hh / a.vheads, B, G * a.vheads);
+    if constexpr (D == 64) {
+      hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT, 0>), grid, dim3(kAT), 0, st, a);
+    } else {      // head size 128: dV and dK in a launch each (see the kernel)
+      hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT, 1>), grid, dim3(kAT), 0, st, a);
+      hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT, 2>), grid, dim3(kAT), 0, st, a);
+    }
   }
   return hipGetLastError();
 }
