@@ -79,6 +79,12 @@ struct MaskCursor {
   }
 };
 
+// number of non-zero bytes of a 32-bit word
+__device__ __forceinline__ int nonzero_bytes(uint32_t w) {
+  const uint32_t t = ((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w;   // bit 7 of a byte set <=> byte != 0
+  return __popc(t & 0x80808080u);
+}
+
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJobs jobs) {
   const CompactJob& job = jobs.j[blockIdx.x];
   const uint8_t* __restrict__ mask = job.mask;
@@ -106,10 +112,40 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   if (row_lo > 0) {      // active entries of the rows before this part
     const long long before = (long long)row_lo * cols;
     int cnt = 0;
+    // Whole masks before this part whose rows * cols bytes are one contiguous range (either
+    // orientation) are counted 16 bytes per load; the rows of the mask the part starts in, and
+    // masks with other strides, byte by byte below.
+    long long done = 0;
+    const bool dense = bstride == (long long)rows * cols &&
+                       ((cstride == 1 && rstride == cols) || (rstride == 1 && cstride == rows));
+    if (dense && row_lo >= rows) {
+      const long long nbytes = (long long)(row_lo / rows) * rows * cols;
+      long long head = (16 - (long long)(reinterpret_cast<uintptr_t>(mask) & 15)) & 15;
+      head = head < nbytes ? head : nbytes;
+      if (tid < head) cnt += mask[tid] != 0;
+      const long long nvec = (nbytes - head) / 16;
+      const uint4* __restrict__ vp = reinterpret_cast<const uint4*>(mask + head);
+      constexpr int kVec = 4;
+      for (long long i0 = tid; i0 < nvec; i0 += (long long)kCompactThreads * kVec) {
+        uint4 q[kVec];
+#pragma unroll
+        for (int u = 0; u < kVec; ++u) {
+          const long long i = i0 + (long long)u * kCompactThreads;
+          q[u] = i < nvec ? vp[i] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kVec; ++u)
+          cnt += nonzero_bytes(q[u].x) + nonzero_bytes(q[u].y) + nonzero_bytes(q[u].z) +
+                 nonzero_bytes(q[u].w);
+      }
+      const long long tail = head + nvec * 16;   // fewer than 16 bytes remain
+      if (tail + tid < nbytes) cnt += mask[tail + tid] != 0;
+      done = nbytes;
+    }
     constexpr int kBatch = 8;
     MaskCursor cur;
-    cur.init(tid, rows, cols);
-    for (long long i0 = tid; i0 < before; i0 += (long long)kCompactThreads * kBatch) {
+    cur.init(done + tid, rows, cols);
+    for (long long i0 = done + tid; i0 < before; i0 += (long long)kCompactThreads * kBatch) {
       uint8_t v[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {

@@ -13,9 +13,15 @@ def lx():
     return lx
 
 
-def _check(lx, oracle, mask, transpose=False):
+def _check(lx, oracle, mask, transpose=False, offset=0):
     import torch
-    m = torch.from_numpy(mask).cuda()
+    if offset:   # the same bytes at an address that is `offset` past an aligned one
+        buf = torch.empty(mask.size + offset, dtype=torch.uint8, device="cuda")
+        m = buf[offset:].view(mask.shape)
+        m.copy_(torch.from_numpy(mask))
+        assert m.data_ptr() % 16 == offset % 16
+    else:
+        m = torch.from_numpy(mask).cuda()
     bl = lx.lx_mask_compact(m, transpose=transpose)
     torch.cuda.synchronize()
     flat = mask.reshape(-1, mask.shape[-2], mask.shape[-1])
@@ -46,6 +52,19 @@ def test_compact_bit_exact(lx, oracle, shape, density, transpose):
     mask = (rng.random(shape) < density).astype(np.uint8)
     mask[mask > 0] = rng.integers(1, 256, size=int(mask.sum()), dtype=np.uint8)
     _check(lx, oracle, mask, transpose)
+
+
+@pytest.mark.parametrize("shape", [(7, 24, 40), (40, 32, 32), (33, 16, 16), (5, 61, 67)])
+@pytest.mark.parametrize("offset", [1, 5, 15, 16])
+@pytest.mark.parametrize("transpose", [False, True])
+def test_compact_masks_at_any_address_and_parts_inside_a_mask(lx, oracle, shape, offset, transpose):
+    """Masks large enough to be divided among workgroups: the rows before a part are counted
+    16 bytes per load where whole masks precede it (at any alignment of the mask's address) and
+    byte by byte inside the mask the part starts in."""
+    rng = np.random.default_rng(1000 * offset + shape[0])
+    mask = (rng.random(shape) < 0.4).astype(np.uint8)
+    mask[mask > 0] = rng.integers(1, 256, size=int(mask.sum()), dtype=np.uint8)
+    _check(lx, oracle, mask, transpose, offset)
 
 
 def test_capacity_smaller_than_count_keeps_row_ptr_exact(lx, oracle):
