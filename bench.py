@@ -22,6 +22,8 @@ Workloads (recipes in paper_2510_15964_amd/inputs.py):
   opt1.3b_layer_patterns  the same layer with per-head attention patterns from
                   a pool, combined into the block lists on the device every
                   step (Sec. VI-A).
+  opt1.3b_layer_onecall   the same layer with the FFN applied to all 8192 tokens in
+                  one call instead of two calls of 4096.
   config4         OPT-6.7B-shaped layer (configs[3]).
   config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]);
                   config5:<rho>:shared = the same with one FFN list for all token tiles
@@ -63,6 +65,12 @@ def make_workload(name: str):
         f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
         a = inputs.config3_attn()
         ffn_calls = 2
+    elif name == "opt1.3b_layer_onecall":
+        # the default layer with the FFN applied to all 8192 tokens in ONE call instead of two
+        # calls of configs[1]'s 4096 tokens: twice as many token tiles share each XCD's L2
+        f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
+        a = inputs.config3_attn()
+        ffn_calls = 1
     elif name == "opt1.3b_layer_shared":
         # the paper's own operating point (Sec. V-A): per FFN call ONE list of active neuron
         # blocks, predicted on the device from the call's tokens (scores, threshold, OR over
@@ -467,7 +475,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="opt1.3b_layer",
                     help="opt1.3b_layer (default) | opt1.3b_layer_shared | opt1.3b_layer_patterns | "
-                         "opt1.3b_layer_lora | opt1.3b_layer_f16 | config4 | config5:RHO")
+                         "opt1.3b_layer_lora | opt1.3b_layer_f16 | opt1.3b_layer_onecall | config4 | config5:RHO")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", metavar="FILE", default=None,
                     help="also run the configs[4] density sweep, one JSON line per density into FILE")
