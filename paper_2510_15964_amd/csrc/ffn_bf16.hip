@@ -443,10 +443,11 @@ __global__ __launch_bounds__(kThreads) void ffn_dsdn_bf16(
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
     uint16_t* __restrict__ out, const uint16_t* __restrict__ act2,
-    const uint16_t* __restrict__ W2) {
+    const uint16_t* __restrict__ W2, int group0) {
   using St = MultiStage<TT>;
   __shared__ __attribute__((aligned(1024))) uint16_t ring[St::kStages * St::kElems];
-  const int i0 = TT * balanced_tile(row_ptr, 0, gridDim.y, gt / TT, nnz_cap, blockIdx.y, false,
+  // the launch covers the tile groups group0 .. group0 + gridDim.y - 1
+  const int i0 = TT * balanced_tile(row_ptr, group0, gridDim.y, gt / TT, nnz_cap, blockIdx.y, false,
                                     reinterpret_cast<int*>(ring));
   const int n0 = blockIdx.x * kRowsA;
   const int rs = row_ptr[i0 / gt];
@@ -552,7 +553,8 @@ static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t*
   // The dsd launch has (column chunks) x (tile groups) workgroups, one per CU, all about equally
   // long.  When they make whole rounds plus a small rest, that rest would keep the launch alive
   // for a full round on a fraction of the chip: the tile groups of whole rounds go to this
-  // kernel, the remaining tiles to the one-tile kernel (two workgroups per CU, shorter rounds).
+  // kernel, the remaining tiles to a kernel with shorter rounds: pairs of tiles when this one
+  // takes four, else the one-tile kernel (two workgroups per CU).
   const int chunks = (d + kRowsA - 1) / kRowsA;
   int groups = Tt / TT;
   const long long wgs = (long long)chunks * groups, rest = wgs % kCUs;
@@ -560,9 +562,14 @@ static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t*
   if (groups > 0)
     hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3(chunks, groups), dim3(kThreads), 0, st,
                        (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
-                       nnz_cap, out, none, none);
-  if (groups * TT < Tt)
-    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3(chunks, Tt - groups * TT), dim3(kThreads), 0, st,
+                       nnz_cap, out, none, none, 0);
+  const int left = Tt - groups * TT;   // a multiple of TT
+  if (left > 0 && TT == 4)
+    hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, 2>), dim3(chunks, left / 2), dim3(kThreads), 0, st,
+                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       nnz_cap, out, none, none, groups * TT / 2);
+  else if (left > 0)
+    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3(chunks, left), dim3(kThreads), 0, st,
                        (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
                        nnz_cap, out, none, none, groups * TT);
 }

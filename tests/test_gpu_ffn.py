@@ -381,7 +381,7 @@ def test_several_token_tiles_per_workgroup(lx, oracle, dtype, T, d, F, G, densit
 
 def test_several_token_tiles_dsd_round_split(lx, oracle):
     """A shape whose four-tile dsd launch is whole rounds of workgroups plus a small rest
-    (3 column chunks x 90 tile groups = 270 for 256 CUs): the rest goes to the one-tile kernel.
+    (3 column chunks x 90 tile groups = 270 for 256 CUs): the rest, 20 tiles, goes to the two-tile kernel.
     The results equal those of one tile per workgroup bit for bit, and sampled tiles of both
     regions match the oracle."""
     import torch
