@@ -494,7 +494,10 @@ def main():
         from paper_2510_15964_amd.inputs import DENSITY_SWEEP
         os.makedirs(os.path.dirname(os.path.abspath(args.sweep)), exist_ok=True)
         with open(args.sweep, "w") as fh:
-            for wl in [f"config5:{rho}" for rho in DENSITY_SWEEP] + ["config5:1.0:shared"]:
+            # the densities with independent lists per token tile, then the paper's operating
+            # mode (one list per call for all its token tiles, Sec. V-A) at 10 %, 30 % and 100 %
+            for wl in [f"config5:{rho}" for rho in DENSITY_SWEEP] + [
+                    "config5:0.1:shared", "config5:0.3:shared", "config5:1.0:shared"]:
                 rho = wl.split(":", 1)[1]
                 r = run(wl, max(args.steps // 5, 5), 2, False)
                 log(f"config5 rho={rho}: {r['ms_per_step']:.3f} ms/step, "
