@@ -38,6 +38,24 @@ namespace lx {
 __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int gt, int w,
                                           int per, int& row, int& chunk) {
   const int lane = threadIdx.x % kWave;
+  if (gt >= rows && rows >= 8) {
+    // One list row for all token tiles: the items are a regular rows x C grid, and every XCD
+    // takes a rectangle of it, rows / xr tiles by C / (8 / xr) groups of entries, that it walks
+    // in columns.  The workgroups that run together on an XCD (32 consecutive slots) then share
+    // a few activation tiles and a few weight blocks alike, instead of two tiles and sixteen
+    // groups of blocks: a third fewer bytes miss its L2.
+    const int C = (row_ptr[1] - row_ptr[0] + per - 1) / per;
+    int xr = 8;
+    while (xr > 1 && (rows % xr != 0 || C % (8 / xr) != 0 || rows / xr < 4)) xr >>= 1;
+    if (C > 0 && rows % xr == 0 && C % (8 / xr) == 0) {
+      const int Rr = rows / xr, Cc = C / (8 / xr);
+      const int x = w % 8, s = w / 8;
+      if (s >= Rr * Cc) return false;
+      row = (x % xr) * Rr + s % Rr;
+      chunk = (x / xr) * Cc + s / Rr;
+      return true;
+    }
+  }
   int total = 0;
   for (int base = 0; base < rows; base += kWave) {
     const int r = base + lane;

@@ -313,6 +313,58 @@ def test_list_rows_shared_by_groups_of_token_tiles(lx, oracle, dtype, tile, T, d
     assert np.array_equal(host(Y2), host(Yd))
 
 
+@pytest.mark.parametrize("rows,nnz,tiles", [
+    (16, 16, 1),    # 4 groups of entries: XCD rectangles of 4 tiles x 2 groups
+    (16, 13, 1),    # the same with a ragged last group
+    (8, 29, 1),     # 8 groups: 4 tiles x 4 groups
+    (24, 8, 1),     # 6 tiles x 1 group
+    (40, 3, 1),     # one group: 5 tiles per XCD
+    (9, 8, 1),      # no cut divides 9 tiles: list order
+    (64, 16, 4),    # four tiles per workgroup: 16 tile groups x 4 groups of entries
+    (32, 8, 2),
+])
+def test_one_list_for_all_tiles_item_grid(lx, oracle, rows, nnz, tiles):
+    """One list row for all token tiles: the sdd kernels deal the regular (tile, group of four
+    entries) grid to the XCDs in rectangles where a cut divides it.  Y and dX equal, bit for bit,
+    those of the same problem given as one list row per tile (items in list order); the first
+    case is also checked against the oracle."""
+    import torch
+    T, d, Fb = rows * 64, 128, 32
+    F = Fb * 64
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, 0.5, 900 + rows + nnz, dtype="bf16", w_std=0.05)
+    row = np.zeros((1, Fb), np.uint8)
+    row[0, np.random.default_rng(nnz).choice(Fb, nnz, replace=False)] = 1
+    full = np.repeat(row, rows, axis=0)
+    X, Wu, Wd, dY = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down", "dY"))
+
+    def run(mask, tiles_per_wg):
+        bl = lx.lx_mask_compact(torch.from_numpy(np.ascontiguousarray(mask)).cuda())
+        nblocks = bl.nnz_cap * (rows // mask.shape[0])
+        ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(lx.LX_BF16, T, d, F, 64, 64, nblocks, 0) + 256,
+                         dtype=torch.uint8, device="cuda")
+        lx.lx_ffn_set_token_tiles_per_workgroup(tiles_per_wg)
+        try:
+            Hd = torch.zeros((nblocks * 4096,), dtype=X.dtype, device="cuda")
+            Yd = torch.full_like(X, float("nan"))
+            lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, 64, 64, Yd, Hd)
+            dXd = torch.full_like(X, float("nan"))
+            lx.lx_sparse_ffn_bwd_dx(dY, Hd, Wu, Wd, bl, 64, 64, dXd, ws)
+            torch.cuda.synchronize()
+        finally:
+            lx.lx_ffn_set_token_tiles_per_workgroup(0)
+        return host(Yd), host(dXd)
+
+    Ys, dXs = run(row, tiles)
+    Yt, dXt = run(full, 1)
+    assert np.isfinite(Ys).all() and np.isfinite(dXs).all()
+    assert np.array_equal(Ys, Yt) and np.array_equal(dXs, dXt)
+    if (rows, nnz) == (16, 16):
+        H, Y = oracle.ffn_fwd(c["X"], c["W_up"], c["W_down"], full, 64, 64)
+        _, dX = oracle.ffn_bwd_dx(c["dY"], c["W_up"], c["W_down"], full, round_to(H, "bf16") > 0, 64, 64)
+        for g, r in ((Ys, Y), (dXs, dX)):
+            assert rel_err_max(g, r) <= TOL["bf16"] and rel_err_fro(g, r) <= FRO["bf16"]
+
+
 @pytest.mark.parametrize("dtype,T,d,F,G,density,seed,bias", [
     ("bf16", 512, 192, 704, 2, 0.45, 181, False),   # two list rows, four tiles each; 11 blocks: ragged chunks of four
     ("bf16", 256, 128, 512, 1, 1.0, 182, True),     # one list for all tokens, dense, biases
