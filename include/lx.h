@@ -179,6 +179,34 @@ lx_status lx_attn_combine_patterns(const lx_blocklist* pool_r, const lx_blocklis
 lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_up,
                               const void* W_down, void* W_up_t, void* W_down_t, void* stream);
 
+/*
+ * Weights kept in CPU memory (Sec. VII-B, memory footprint: with only the active
+ * neurons computed, most of the MLP weights can stay on the CPU and only the
+ * active ones are moved to the GPU).  Copies the listed neuron blocks of a
+ * neuron-major matrix W [F,d] (the blk_n rows of a neuron block adjacent: W_up,
+ * or W_down_t as lx_ffn_pack_weights writes it) into the compact matrix
+ * Wc [nnz_cap*blk_n, d], entry k of the list becoming rows k*blk_n .. of Wc.
+ *   W    [F,d]: DEVICE memory, or HOST memory that the device can address
+ *        (allocated pinned, e.g. hipHostMalloc); read by the kernel on `stream`,
+ *        so the caller keeps it unchanged until the stream has passed the call
+ *   bl   DEVICE list with ONE row (the list shared by all token tiles),
+ *        cols = F/blk_n
+ *   Wc   out, DEVICE [bl->nnz_cap*blk_n, d]; rows of entries past the end of
+ *        the list are left as they were
+ *   compact_row_ptr / compact_col_idx   out, nullable: DEVICE int32[2] and
+ *        int32[bl->nnz_cap], the one-row list {0, n}, 0 .. of the compact matrix:
+ *        with it, Wc (and its transpose from lx_ffn_pack_weights) in place of the
+ *        full matrices and F' = nnz_cap*blk_n, the FFN calls below compute
+ *        exactly what they compute from the full matrices and bl.
+ * Errors: INVALID_ARG for null pointers, sizes that do not match, a list with
+ * more than one row, pointers not 16-byte aligned, or W in pageable host memory
+ * (nothing is launched); UNSUPPORTED for an unknown element type.
+ */
+lx_status lx_ffn_gather_weight_blocks(lx_dtype dt, int32_t d, int32_t F, int32_t blk_n,
+                                      const void* W, const lx_blocklist* bl, void* Wc,
+                                      int32_t* compact_row_ptr, int32_t* compact_col_idx,
+                                      void* stream);
+
 /* Workspace (bytes) for lx_sparse_ffn_fwd / lx_sparse_ffn_bwd_dx.
  * nnz_cap: capacity of the activation buffers in blocks, i.e. bl->nnz_cap times
  *   the number of token tiles per list row ((T/tile_t)/bl->rows, 1 for a list

@@ -213,6 +213,37 @@ lx_status lx_ffn_pack_weights(lx_dtype dt, int32_t d, int32_t F, const void* W_u
   return LX_OK;
 }
 
+lx_status lx_ffn_gather_weight_blocks(lx_dtype dt, int32_t d, int32_t F, int32_t blk_n,
+                                      const void* W, const lx_blocklist* bl, void* Wc,
+                                      int32_t* compact_row_ptr, int32_t* compact_col_idx,
+                                      void* stream) {
+  if (dt != LX_F32 && !is16(dt)) return LX_ERR_UNSUPPORTED;
+  if (d <= 0 || F <= 0 || blk_n <= 0 || F % blk_n != 0) return LX_ERR_INVALID_ARG;
+  if (!W || !Wc || !bl || !bl->row_ptr || !bl->col_idx) return LX_ERR_INVALID_ARG;
+  if (bl->rows != 1 || bl->cols != F / blk_n || bl->nnz_cap <= 0) return LX_ERR_INVALID_ARG;
+  const long long block_bytes = (long long)blk_n * d * (long long)esize(dt);
+  if (block_bytes % 16 != 0 || !aligned16(W) || !aligned16(Wc)) return LX_ERR_INVALID_ARG;
+  // The kernel reads W through the pointer it is given: only memory the device can address is
+  // accepted (device, managed, or host memory allocated pinned); for pinned host memory the
+  // device-side alias of the allocation is what the kernel gets.
+  hipPointerAttribute_t at;
+  if (hipPointerGetAttributes(&at, W) != hipSuccess) {
+    (void)hipGetLastError();
+    return LX_ERR_INVALID_ARG;
+  }
+  const void* src = W;
+  if (at.type == hipMemoryTypeHost) {
+    if (!at.devicePointer) return LX_ERR_INVALID_ARG;
+    src = at.devicePointer;
+  } else if (at.type != hipMemoryTypeDevice && at.type != hipMemoryTypeManaged) {
+    return LX_ERR_INVALID_ARG;
+  }
+  if (launch_gather_blocks(src, F / blk_n, block_bytes, bl->row_ptr, bl->col_idx, bl->nnz_cap, Wc,
+                           compact_row_ptr, compact_col_idx, (hipStream_t)stream) != hipSuccess)
+    return LX_ERR_RUNTIME;
+  return LX_OK;
+}
+
 size_t lx_sparse_ffn_fwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t F,
                                          int32_t tile_t, int32_t blk_n, int32_t nnz_cap,
                                          int32_t have_h_act) {

@@ -121,6 +121,11 @@ hipError_t launch_ffn_lora_bwd_bf16(int dt, int Tt, int gt, int d, int F, const 
 hipError_t launch_predict_bf16(int dt, int T, int d, int nblk, int tiles_per_group, const uint16_t* X,
                                const uint16_t* Wa_t, float thr, uint8_t* mask, hipStream_t st);
 hipError_t launch_transpose(int elem_bytes, const void* src, int R, int C, void* dst, hipStream_t st);
+// Listed blocks of W [Fb][block_bytes] (device or device-addressable host memory) -> Wc, in the
+// order of the one-row list; optionally the list of the compact matrix (see compact.hip).
+hipError_t launch_gather_blocks(const void* W, int Fb, long long block_bytes, const int* row_ptr,
+                                const int* col_idx, int cap, void* Wc, int* id_row_ptr,
+                                int* id_col_idx, hipStream_t stream);
 hipError_t launch_attn_fwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t set_attn_rows_per_wg(int r);   // 0 = automatic

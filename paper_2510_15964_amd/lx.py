@@ -28,6 +28,7 @@ LX_F32, LX_BF16, LX_F16 = 0, 1, 2
 
 EXPORTS = (
     "lx_status_string", "lx_mask_compact", "lx_mask_compact_pair", "lx_mask_compact_batch", "lx_ffn_pack_weights",
+    "lx_ffn_gather_weight_blocks",
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
@@ -63,6 +64,7 @@ _lib.lx_mask_compact_pair.argtypes = [_vp, _i32, _i32, _i32, _i64, _i64, _i64, _
                                       _i32, _vp]
 _lib.lx_mask_compact_batch.argtypes = [C.POINTER(lx_compact_job), _i32, _vp]
 _lib.lx_ffn_pack_weights.argtypes = [C.c_int, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+_lib.lx_ffn_gather_weight_blocks.argtypes = [C.c_int, _i32, _i32, _i32, _vp, _blp, _vp, _vp, _vp, _vp]
 for _n in ("lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes"):
     getattr(_lib, _n).restype = _sz
     getattr(_lib, _n).argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _i32, _i32]
@@ -234,6 +236,32 @@ def lx_ffn_pack_weights(W_up: torch.Tensor, W_down: torch.Tensor):
     _check(_lib.lx_ffn_pack_weights(_dt(W_up), d, F, _ptr(W_up), _ptr(W_down), _ptr(W_up_t),
                                     _ptr(W_down_t), _stream()), "lx_ffn_pack_weights")
     return W_up_t, W_down_t
+
+
+def lx_ffn_transpose(W: torch.Tensor) -> torch.Tensor:
+    """[R,C] -> [C,R] on the device (one half of lx_ffn_pack_weights)."""
+    R, Cc = W.shape
+    out = torch.empty((Cc, R), dtype=W.dtype, device=W.device)
+    _check(_lib.lx_ffn_pack_weights(_dt(W), Cc, R, _ptr(W), None, _ptr(out), None, _stream()),
+           "lx_ffn_pack_weights")
+    return out
+
+
+def lx_ffn_gather_weight_blocks(W: torch.Tensor, bl: BlockList, blk_n: int, out=None, compact=None):
+    """W [F,d]: device tensor or pinned host tensor; bl: one-row device list.  Returns
+    (Wc [nnz_cap*blk_n, d] on the device, one-row list of the compact matrix)."""
+    assert W.dim() == 2 and W.is_contiguous()
+    F, d = W.shape
+    dev = bl.row_ptr.device
+    if out is None:
+        out = torch.zeros((bl.nnz_cap * blk_n, d), dtype=W.dtype, device=dev)
+    if compact is None:
+        compact = BlockList(1, bl.nnz_cap, torch.empty(2, dtype=torch.int32, device=dev),
+                            torch.empty(bl.nnz_cap, dtype=torch.int32, device=dev), bl.nnz_cap)
+    _check(_lib.lx_ffn_gather_weight_blocks(_dt(W), d, F, blk_n, _ptr(W), C.byref(bl.c), _ptr(out),
+                                            _ptr(compact.row_ptr), _ptr(compact.col_idx), _stream()),
+           "lx_ffn_gather_weight_blocks")
+    return out, compact
 
 
 def lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_h_act) -> int:
