@@ -24,6 +24,8 @@ Workloads (recipes in paper_2510_15964_amd/inputs.py):
                   step (Sec. VI-A).
   opt1.3b_layer_onecall   the same layer with the FFN applied to all 8192 tokens in
                   one call instead of two calls of 4096.
+  opt1.3b_layer_hostw     the shared-list layer with the FFN weights in pinned host memory:
+                  every call moves the listed neuron blocks to the device first (Sec. VII-B).
   config4         OPT-6.7B-shaped layer (configs[3]).
   config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]);
                   config5:<rho>:shared = the same with one FFN list for all token tiles
@@ -78,6 +80,16 @@ def make_workload(name: str):
         f = inputs.ffn_bernoulli(8192, 2048, 8192, 64, 64, 0.11, seed=2100, dtype="bf16")
         f["predictor"] = inputs.predictor_planted(2048, 128, 0.11, seed=2100)
         f["mask"] = np.repeat(f["predictor"]["hot"][None].astype(np.uint8), 128, axis=0)
+        a = inputs.config3_attn()
+        ffn_calls = 2
+    elif name == "opt1.3b_layer_hostw":
+        # the shared-list layer with the FFN weights resident in pinned HOST memory (Sec. VII-B,
+        # memory footprint): every call gathers the listed neuron blocks of W_up and W_down_t over
+        # the host link, transposes them on the device and runs the FFN on the compact matrices
+        f = inputs.ffn_bernoulli(8192, 2048, 8192, 64, 64, 0.11, seed=2100, dtype="bf16")
+        f["predictor"] = inputs.predictor_planted(2048, 128, 0.11, seed=2100)
+        f["mask"] = np.repeat(f["predictor"]["hot"][None].astype(np.uint8), 128, axis=0)
+        f["host_weights"] = True
         a = inputs.config3_attn()
         ffn_calls = 2
     elif name == "opt1.3b_layer_lora":
@@ -160,6 +172,16 @@ class FfnJob:
                                                   max(self.nnz, 1), 1)
         self.ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
         self.used = float((self.mask_h.sum(0) > 0).mean())     # fraction of neuron blocks touched
+        self.hostw = bool(f.get("host_weights"))
+        if self.hostw:
+            # host copies of the two neuron-major matrices; device buffers for the listed blocks
+            self.Wu_h, self.Wdt_h = Wu.cpu().pin_memory(), Wdt.cpu().pin_memory()
+            cap = self.bl_run.nnz_cap
+            mk = lambda r, c: torch.zeros((r, c), dtype=self.X.dtype, device="cuda")
+            self.Wu_c, self.Wdt_c = mk(cap * 64, self.d), mk(cap * 64, self.d)
+            self.Wd_c, self.Wut_c = mk(self.d, cap * 64), mk(self.d, cap * 64)
+            self.cl = lx.BlockList(1, cap, torch.empty(2, dtype=torch.int32, device="cuda"),
+                                   torch.empty(cap, dtype=torch.int32, device="cuda"), cap)
         self.lora = f.get("lora")
         if self.lora is not None:
             self.A_pad, self.B_pad = dev(self.lora["A_pad"], self.dt), dev(self.lora["B_pad"], self.dt)
@@ -184,6 +206,15 @@ class FfnJob:
             lx.lx_sparse_ffn_lora_bwd(self.X, self.dY, self.H_act, self.U, self.Wut, self.Wdt,
                                       self.A_pad, self.B_pad, self.bl_run, self.dX, self.dA, self.dB,
                                       self.ws)
+            return
+        if self.hostw:
+            lx.lx_ffn_gather_weight_blocks(self.Wu_h, self.bl_run, 64, out=self.Wu_c, compact=self.cl)
+            lx.lx_ffn_gather_weight_blocks(self.Wdt_h, self.bl_run, 64, out=self.Wdt_c, compact=self.cl)
+            lx.lx_ffn_transpose(self.Wdt_c, out=self.Wd_c)
+            lx.lx_ffn_transpose(self.Wu_c, out=self.Wut_c)
+            lx.lx_sparse_ffn_fwd(self.X, self.Wu_c, self.Wd_c, self.cl, 64, 64, self.Y, self.H_act)
+            lx.lx_sparse_ffn_bwd_dx(self.dY, self.H_act, self.Wu_c, self.Wd_c, self.cl, 64, 64, self.dX,
+                                    self.ws, W_up_t=self.Wut_c, W_down_t=self.Wdt_c)
             return
         lx.lx_sparse_ffn_fwd(self.X, self.Wu, self.Wd, self.bl_run, 64, 64, self.Y, self.H_act)
         lx.lx_sparse_ffn_bwd_dx(self.dY, self.H_act, self.Wu, self.Wd, self.bl_run, 64, 64, self.dX,
@@ -475,7 +506,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="opt1.3b_layer",
                     help="opt1.3b_layer (default) | opt1.3b_layer_shared | opt1.3b_layer_patterns | "
-                         "opt1.3b_layer_lora | opt1.3b_layer_f16 | opt1.3b_layer_onecall | config4 | config5:RHO")
+                         "opt1.3b_layer_lora | opt1.3b_layer_f16 | opt1.3b_layer_onecall | opt1.3b_layer_hostw | "
+                         "config4 | config5:RHO")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", metavar="FILE", default=None,
                     help="also run the configs[4] density sweep, one JSON line per density into FILE")

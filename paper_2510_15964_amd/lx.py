@@ -238,10 +238,12 @@ def lx_ffn_pack_weights(W_up: torch.Tensor, W_down: torch.Tensor):
     return W_up_t, W_down_t
 
 
-def lx_ffn_transpose(W: torch.Tensor) -> torch.Tensor:
+def lx_ffn_transpose(W: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
     """[R,C] -> [C,R] on the device (one half of lx_ffn_pack_weights)."""
     R, Cc = W.shape
-    out = torch.empty((Cc, R), dtype=W.dtype, device=W.device)
+    if out is None:
+        out = torch.empty((Cc, R), dtype=W.dtype, device=W.device)
+    assert out.shape == (Cc, R) and out.is_contiguous()
     _check(_lib.lx_ffn_pack_weights(_dt(W), Cc, R, _ptr(W), None, _ptr(out), None, _stream()),
            "lx_ffn_pack_weights")
     return out
