@@ -153,6 +153,27 @@ def test_ffn_list_rows_must_divide_the_token_tiles(lxmod):
     assert _ffn_fwd(L, L.LX_BF16, 512, 128, 1024, 64, 64, _bl(L, 16, 16)) == L.LX_ERR_INVALID_ARG
 
 
+def test_gather_weight_blocks_validation(lxmod):
+    """Everything that can be wrong with the sizes, the list and the pointers' alignment is found
+    before the source pointer is looked at (and before any launch)."""
+    L = lxmod
+    f = L._lib.lx_ffn_gather_weight_blocks
+    def call(dt=L.LX_BF16, d=128, F=512, blk=64, W=FAKE, bl=None, Wc=FAKE):
+        bl = _bl(L, 1, F // blk if blk > 0 and F > 0 else 1) if bl is None else bl
+        return f(dt, d, F, blk, W, C.byref(bl), Wc, None, None, None)
+    assert call(dt=7) == L.LX_ERR_UNSUPPORTED
+    assert call(d=0) == L.LX_ERR_INVALID_ARG
+    assert call(F=500) == L.LX_ERR_INVALID_ARG                          # not whole neuron blocks
+    assert call(blk=0) == L.LX_ERR_INVALID_ARG
+    assert call(W=None) == L.LX_ERR_INVALID_ARG
+    assert call(Wc=None) == L.LX_ERR_INVALID_ARG
+    assert call(bl=_bl(L, 2, 8)) == L.LX_ERR_INVALID_ARG                # more than one list row
+    assert call(bl=_bl(L, 1, 9)) == L.LX_ERR_INVALID_ARG                # columns are not F / blk_n
+    assert call(bl=_bl(L, 1, 8, cap=0)) == L.LX_ERR_INVALID_ARG
+    assert call(W=C.c_void_p(0x1008)) == L.LX_ERR_INVALID_ARG           # not 16-byte aligned
+    assert call(dt=L.LX_F32, d=2, blk=1, F=8) == L.LX_ERR_INVALID_ARG   # a block is not whole 16-byte words
+
+
 def test_mlp_predict_validation(lxmod):
     L = lxmod
     f = L._lib.lx_mlp_predict_mask
