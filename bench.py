@@ -25,7 +25,9 @@ Workloads (recipes in paper_2510_15964_amd/inputs.py):
   opt1.3b_layer_onecall   the same layer with the FFN applied to all 8192 tokens in
                   one call instead of two calls of 4096.
   opt1.3b_layer_hostw     the shared-list layer with the FFN weights in pinned host memory:
-                  every call moves the listed neuron blocks to the device first (Sec. VII-B).
+                  every call moves the listed neuron blocks to the device first (Sec. VII-B);
+                  opt1.3b_layer_hostw_overlap = the same with the transfers on a second stream
+                  under the attention kernels.
   config4         OPT-6.7B-shaped layer (configs[3]).
   config5:<rho>   OPT-13B-shaped layer at block density rho (configs[4]);
                   config5:<rho>:shared = the same with one FFN list for all token tiles
@@ -82,14 +84,14 @@ def make_workload(name: str):
         f["mask"] = np.repeat(f["predictor"]["hot"][None].astype(np.uint8), 128, axis=0)
         a = inputs.config3_attn()
         ffn_calls = 2
-    elif name == "opt1.3b_layer_hostw":
+    elif name in ("opt1.3b_layer_hostw", "opt1.3b_layer_hostw_overlap"):
         # the shared-list layer with the FFN weights resident in pinned HOST memory (Sec. VII-B,
         # memory footprint): every call gathers the listed neuron blocks of W_up and W_down_t over
         # the host link, transposes them on the device and runs the FFN on the compact matrices
         f = inputs.ffn_bernoulli(8192, 2048, 8192, 64, 64, 0.11, seed=2100, dtype="bf16")
         f["predictor"] = inputs.predictor_planted(2048, 128, 0.11, seed=2100)
         f["mask"] = np.repeat(f["predictor"]["hot"][None].astype(np.uint8), 128, axis=0)
-        f["host_weights"] = True
+        f["host_weights"] = "overlap" if name.endswith("_overlap") else True
         a = inputs.config3_attn()
         ffn_calls = 2
     elif name == "opt1.3b_layer_lora":
@@ -173,6 +175,7 @@ class FfnJob:
         self.ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
         self.used = float((self.mask_h.sum(0) > 0).mean())     # fraction of neuron blocks touched
         self.hostw = bool(f.get("host_weights"))
+        self.gathered = False
         if self.hostw:
             # host copies of the two neuron-major matrices; device buffers for the listed blocks
             self.Wu_h, self.Wdt_h = Wu.cpu().pin_memory(), Wdt.cpu().pin_memory()
@@ -194,6 +197,14 @@ class FfnJob:
             self.ws_f = torch.empty(lx.lx_sparse_ffn_lora_fwd_workspace_bytes(self.T, self.d), dtype=torch.uint8,
                                     device="cuda")
 
+    def gather(self):
+        """Host-resident weights: the listed blocks of both neuron-major matrices -> device, on the
+        current stream."""
+        lx = self.lx
+        lx.lx_ffn_gather_weight_blocks(self.Wu_h, self.bl_run, 64, out=self.Wu_c, compact=self.cl)
+        lx.lx_ffn_gather_weight_blocks(self.Wdt_h, self.bl_run, 64, out=self.Wdt_c, compact=self.cl)
+        self.gathered = True
+
     def predict(self):
         if self.pred is not None:
             self.lx.lx_mlp_predict_mask(self.X, self.Wa_t, self.pred["thr"], self.T, mask=self.mask)
@@ -208,8 +219,9 @@ class FfnJob:
                                       self.ws)
             return
         if self.hostw:
-            lx.lx_ffn_gather_weight_blocks(self.Wu_h, self.bl_run, 64, out=self.Wu_c, compact=self.cl)
-            lx.lx_ffn_gather_weight_blocks(self.Wdt_h, self.bl_run, 64, out=self.Wdt_c, compact=self.cl)
+            if not self.gathered:
+                self.gather()
+            self.gathered = False
             lx.lx_ffn_transpose(self.Wdt_c, out=self.Wd_c)
             lx.lx_ffn_transpose(self.Wu_c, out=self.Wut_c)
             lx.lx_sparse_ffn_fwd(self.X, self.Wu_c, self.Wd_c, self.cl, 64, 64, self.Y, self.H_act)
@@ -402,11 +414,34 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     if attn.pool is None:
         cb.add(attn.mask, attn.bl_r).add(attn.mask, attn.bl_c, transpose=True)
 
+    # Host-resident weights: the gathers of a step need only its lists, use no LDS and are bound
+    # by the host link, so they run on a second stream (default priority) under the attention
+    # kernels, which then go first; each FFN call waits for its own gather.
+    overlap = f.get("host_weights") == "overlap"
+    if overlap:
+        side = torch.cuda.Stream()
+        ev_lists = torch.cuda.Event()
+        ev_done = [torch.cuda.Event() for _ in ffn_jobs]
+
     def step():
         for j in ffn_jobs:
             j.predict()
         lx.lx_mask_compact_batch(cb)
         attn.combine()
+        if overlap:
+            main = torch.cuda.current_stream()
+            ev_lists.record(main)
+            with torch.cuda.stream(side):
+                side.wait_event(ev_lists)
+                for j, ev in zip(ffn_jobs, ev_done):
+                    j.gather()
+                    ev.record(side)
+            attn.run()
+            for j, ev in zip(ffn_jobs, ev_done):
+                main.wait_event(ev)
+                j.run()
+            side.wait_stream(main)      # the next step's gathers overwrite what this step's kernels read
+            return
         for j in ffn_jobs:
             j.run()
         attn.run()

@@ -333,39 +333,42 @@ hipError_t launch_combine_patterns(const CombineList* lists, int n_lists, const 
 // Gather of the listed neuron blocks of a neuron-major weight matrix (Sec. VII-B, memory
 // footprint: the weights may stay in CPU memory, only the active ones are moved to the GPU).
 // W [Fb][block_bytes] -> Wc [entry][block_bytes] in the order of the one-row list; the source
-// may be device memory or host memory the device can address.  Workgroup (e, part): entry e,
-// 16-byte words part, part + parts, ...  Also writes the list of the compact matrix (row
-// pointers {0, n}, columns 0 .. n - 1) when asked to.
+// may be device memory or host memory the device can address.  A unit of work is 1024 16-byte
+// words of one entry; at most kGatherGroups workgroups walk the units with a grid stride: reads
+// over the host link are bound by the link, a few hundred KB in flight saturate it, and a CU whose
+// memory pipeline is waiting on such reads serves the other kernels on it slowly, so the gather
+// keeps to a few CUs.  Also writes the list of the compact matrix (row pointers {0, n}, columns
+// 0 .. n - 1) when asked to.
 // ---------------------------------------------------------------------------
-constexpr int kGatherThreads = 256;
+constexpr int kGatherThreads = 256, kGatherU = 4, kGatherGroups = 64;
+constexpr int kGatherUnit = kGatherThreads * kGatherU;   // words per unit
 __global__ __launch_bounds__(kGatherThreads) void gather_blocks_kernel(
     const uint4* __restrict__ W, int Fb, long long words_per_block, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int cap, uint4* __restrict__ Wc, int* __restrict__ id_row_ptr,
     int* __restrict__ id_col_idx) {
   const int rs = row_ptr[0];
   const int n = max(min(row_ptr[1], cap) - rs, 0);   // entries within the capacity of the list
-  const int e = blockIdx.x;
-  if (e == 0 && blockIdx.y == 0) {
+  if (blockIdx.x == 0) {
     if (id_row_ptr && threadIdx.x < 2) id_row_ptr[threadIdx.x] = threadIdx.x == 0 ? 0 : n;
     if (id_col_idx)
       for (int i = threadIdx.x; i < cap; i += kGatherThreads) id_col_idx[i] = i;
   }
-  if (e >= n) return;
-  const int j = col_idx[rs + e];
-  if (j < 0 || j >= Fb) return;                      // not a block of W: nothing is read
-  const uint4* __restrict__ src = W + (long long)j * words_per_block;
-  uint4* __restrict__ dst = Wc + (long long)e * words_per_block;
-  const long long step = (long long)gridDim.y * kGatherThreads;
-  constexpr int kU = 4;                              // loads in flight per thread
-  for (long long i0 = (long long)blockIdx.y * kGatherThreads + threadIdx.x; i0 < words_per_block;
-       i0 += step * kU) {
-    uint4 v[kU];
+  const long long per_block = (words_per_block + kGatherUnit - 1) / kGatherUnit;
+  const long long units = (long long)n * per_block;
+  for (long long u = blockIdx.x; u < units; u += gridDim.x) {
+    const int e = (int)(u / per_block);
+    const long long w0 = (u - (long long)e * per_block) * kGatherUnit + threadIdx.x;
+    const int j = col_idx[rs + e];
+    if (j < 0 || j >= Fb) continue;                  // not a block of W: nothing is read
+    const uint4* __restrict__ src = W + (long long)j * words_per_block;
+    uint4* __restrict__ dst = Wc + (long long)e * words_per_block;
+    uint4 v[kGatherU];
 #pragma unroll
-    for (int u = 0; u < kU; ++u)
-      if (i0 + u * step < words_per_block) v[u] = src[i0 + u * step];
+    for (int k = 0; k < kGatherU; ++k)
+      if (w0 + k * kGatherThreads < words_per_block) v[k] = src[w0 + k * kGatherThreads];
 #pragma unroll
-    for (int u = 0; u < kU; ++u)
-      if (i0 + u * step < words_per_block) dst[i0 + u * step] = v[u];
+    for (int k = 0; k < kGatherU; ++k)
+      if (w0 + k * kGatherThreads < words_per_block) dst[w0 + k * kGatherThreads] = v[k];
   }
 }
 
@@ -373,10 +376,9 @@ hipError_t launch_gather_blocks(const void* W, int Fb, long long block_bytes, co
                                 const int* col_idx, int cap, void* Wc, int* id_row_ptr,
                                 int* id_col_idx, hipStream_t stream) {
   const long long words = block_bytes / 16;
-  // enough workgroups per entry to keep ~16 KiB per workgroup, at most 64
-  long long parts = (words + 1023) / 1024;
-  parts = parts < 1 ? 1 : (parts > 64 ? 64 : parts);
-  hipLaunchKernelGGL(gather_blocks_kernel, dim3(cap, (unsigned)parts), dim3(kGatherThreads), 0, stream,
+  long long groups = (long long)cap * ((words + kGatherUnit - 1) / kGatherUnit);
+  groups = groups < 1 ? 1 : (groups > kGatherGroups ? kGatherGroups : groups);
+  hipLaunchKernelGGL(gather_blocks_kernel, dim3((unsigned)groups), dim3(kGatherThreads), 0, stream,
                      (const uint4*)W, Fb, words, row_ptr, col_idx, cap, (uint4*)Wc, id_row_ptr,
                      id_col_idx);
   return hipGetLastError();
