@@ -10,7 +10,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblx_sparse.so")
 SOURCES = ["lx_api.hip", "compact.hip", "ffn_f32.hip", "ffn_bf16.hip", "predict_bf16.hip", "lora_bf16.hip",
            "attn_bf16.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+# -Wno-inline-asm: the DMA helpers name m0 (a register the compiler reserves) as clobbered, which
+# is the point, and clang warns about every such statement
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -171,16 +171,20 @@ __device__ __forceinline__ void mma_tr(const TrOps<D>& t, const f32x16& p, f32x1
 // 32*part + 8*(v/4) + 4*(lane/32) + v%4) being KEYS and the lane (32*own + lane%32) the QUERY:
 // keys after the query get -inf.  mask_diag_t: the same with the roles exchanged (rows are
 // queries, the lane is the key).
-__device__ __forceinline__ void mask_diag(f32x16& s, int own, int part) {
+// `above`: the block lies wholly on the excluded side of the diagonal (a block the list should not
+// hold under a causal mask): every score of it is excluded.
+__device__ __forceinline__ void mask_diag(f32x16& s, int own, int part, bool above) {
   const int lane = threadIdx.x % kWave;
-  const int x = lane % 32 + 32 * (own - part) - 4 * (lane / 32);   // key 8*(v/4) + v%4 > x: excluded
+  // key 8*(v/4) + v%4 > x: excluded
+  const int x = above ? -1 : lane % 32 + 32 * (own - part) - 4 * (lane / 32);
 #pragma unroll
   for (int v = 0; v < 16; ++v)
     if (8 * (v / 4) + v % 4 > x) s[v] = -INFINITY;
 }
-__device__ __forceinline__ void mask_diag_t(f32x16& s, int own, int part) {
+__device__ __forceinline__ void mask_diag_t(f32x16& s, int own, int part, bool above) {
   const int lane = threadIdx.x % kWave;
-  const int x = lane % 32 + 32 * (own - part) - 4 * (lane / 32);   // query 8*(v/4) + v%4 < x: excluded
+  // query 8*(v/4) + v%4 < x: excluded
+  const int x = above ? 64 : lane % 32 + 32 * (own - part) - 4 * (lane / 32);
 #pragma unroll
   for (int v = 0; v < 16; ++v)
     if (8 * (v / 4) + v % 4 < x) s[v] = -INFINITY;
@@ -513,7 +517,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kFwdOcc64 : 2) void attn_fwd_bf16(co
     TrOps<D> vt;
     load_tr<D>(stg + 2 * 64 * D, lo, vt);
     __builtin_amdgcn_sched_barrier(0);
-    if (a.causal && col == qb) mask_diag(s_acc, own, part);
+    if (a.causal && col >= qb) mask_diag(s_acc, own, part, col > qb);
     float mloc = s_acc[0];
 #pragma unroll
     for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, s_acc[v]);
@@ -641,7 +645,10 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       ofr[s] = *reinterpret_cast<const uint4*>(a.O + qoff + 16 * s + 8 * h2);
-    lse2 = a.LSEin[soff] * kLog2e;
+    // a row whose listed blocks hold no allowed key has LSE = -inf: +inf here makes every
+    // probability exp2(score - inf) = 0, also for excluded scores (-inf), which -(-inf) would not
+    const float lse_in = a.LSEin[soff];
+    lse2 = lse_in == -INFINITY ? INFINITY : lse_in * kLog2e;
     float sum = 0.f;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
@@ -685,7 +692,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDqOcc64 : 2) void attn_bwd_dq_bf16(
     f32x16 s_acc, dp_acc;
     mma_rows<D, DT>(stg, lo, qf, s_acc);                    // S^T[key][q]
     mma_rows<D, DT>(stg + 2 * 64 * D, lo, dof, dp_acc);     // dP^T[key][q]
-    if (a.causal && col == qb) mask_diag(s_acc, own, part);   // excluded keys: P = exp2(-inf) = 0
+    if (a.causal && col >= qb) mask_diag(s_acc, own, part, col > qb);   // excluded keys: P = exp2(-inf) = 0
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[v], sc, -lse2));
@@ -809,7 +816,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : (WHICH == 0 ? 1 : 2)) vo
     mma_rows<D, DT>(stg, lo, kf, s_acc);                   // S[q][key]
     if (kDK) mma_rows<D, DT>(stg + 2 * 64 * D, lo, vf, dp_acc);     // dP[q][key]
     // diagonal block: here the rows of the score tile are queries and the lane is the key
-    if (a.causal && col == kb) mask_diag_t(s_acc, own, part);
+    if (a.causal && col <= kb) mask_diag_t(s_acc, own, part, col < kb);
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int q0 = 8 * g + 4 * h2;                 // four consecutive queries of this half

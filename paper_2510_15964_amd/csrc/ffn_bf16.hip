@@ -36,15 +36,18 @@ namespace lx {
 // the weight blocks an XCD needs are those of one eighth of the tiles.  Returns false past the
 // end.
 __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int rows, int gt, int w,
-                                          int per, int& row, int& chunk) {
+                                          int per, int nnz_cap, int& row, int& chunk) {
   const int lane = threadIdx.x % kWave;
+  // entries of a list row that lie within the capacity of the list buffers: the items are
+  // counted from these, so that their number never exceeds the bound the grid was sized from
+  auto row_len = [&](int lr) { return min(row_ptr[lr + 1], nnz_cap) - min(row_ptr[lr], nnz_cap); };
   if (gt >= rows && rows >= 8) {
     // One list row for all token tiles: the items are a regular rows x C grid, and every XCD
     // takes a rectangle of it, rows / xr tiles by C / (8 / xr) groups of entries, that it walks
     // in columns.  The workgroups that run together on an XCD (32 consecutive slots) then share
     // a few activation tiles and a few weight blocks alike, instead of two tiles and sixteen
     // groups of blocks: a third fewer bytes miss its L2.
-    const int C = (row_ptr[1] - row_ptr[0] + per - 1) / per;
+    const int C = (row_len(0) + per - 1) / per;
     int xr = 8;
     while (xr > 1 && (rows % xr != 0 || C % (8 / xr) != 0 || rows / xr < 4)) xr >>= 1;
     if (C > 0 && rows % xr == 0 && C % (8 / xr) == 0) {
@@ -60,7 +63,7 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   for (int base = 0; base < rows; base += kWave) {
     const int r = base + lane;
     int c = 0;
-    if (r < rows) c = (row_ptr[r / gt + 1] - row_ptr[r / gt] + per - 1) / per;
+    if (r < rows) c = (row_len(r / gt) + per - 1) / per;
 #pragma unroll
     for (int dlt = 32; dlt > 0; dlt >>= 1) c += __shfl_xor(c, dlt);
     total += c;
@@ -77,7 +80,7 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   for (int base = 0; base < rows; base += kWave) {
     const int r = base + lane;
     int c = 0;
-    if (r < rows) c = (row_ptr[r / gt + 1] - row_ptr[r / gt] + per - 1) / per;
+    if (r < rows) c = (row_len(r / gt) + per - 1) / per;
     int incl = c;
 #pragma unroll
     for (int dlt = 1; dlt < kWave; dlt <<= 1) {
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
     const uint16_t* __restrict__ A2, const uint16_t* __restrict__ W2) {
   __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
   int i, chunk;
-  if (!find_work(row_ptr, rows, gt, blockIdx.x, 4, i, chunk)) return;
+  if (!find_work(row_ptr, rows, gt, blockIdx.x, 4, nnz_cap, i, chunk)) return;
   const int rs = row_ptr[i / gt], n_i = row_ptr[i / gt + 1] - rs;
   const int first = chunk * 4;
   const int p0 = rs + first;
@@ -388,7 +391,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sddn_bf16(
   using St = MultiStage<TT>;
   __shared__ __attribute__((aligned(1024))) uint16_t ring[St::kStages * St::kElems];
   int grp, chunk;
-  if (!find_work(row_ptr, rows / TT, gt / TT, blockIdx.x, 4, grp, chunk)) return;
+  if (!find_work(row_ptr, rows / TT, gt / TT, blockIdx.x, 4, nnz_cap, grp, chunk)) return;
   const int i0 = TT * grp;                       // first tile of the group
   const int rs = row_ptr[i0 / gt], n_i = row_ptr[i0 / gt + 1] - rs;
   const int first = chunk * 4;

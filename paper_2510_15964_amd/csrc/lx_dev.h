@@ -58,13 +58,13 @@ __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
   const uint32_t l = __builtin_amdgcn_readfirstlane(lds_wave_base);   // must be a scalar register
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gptr)
-               : "memory");
+               : "memory", "m0");
 }
 // Same with 4 bytes per lane (lane l lands at lds_wave_base + 4*l).
 __device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_wave_base) {
   const uint32_t l = __builtin_amdgcn_readfirstlane(lds_wave_base);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(l), "v"(gptr)
-               : "memory");
+               : "memory", "m0");
 }
 // s_waitcnt vmcnt(N) alone (expcnt / lgkmcnt left open); N < 64.
 template <int N>

@@ -1,0 +1,90 @@
+"""The ideal 16-bit pipeline, emulated in fp64 (test infrastructure; imports neither the HIP binding
+nor the oracle).
+
+A 16-bit run of the operator cannot reproduce the fp64 oracle: whatever the kernel design, the
+factor that feeds the second matrix product (H, dZ for the FFN; P, dS for attention) exists only as
+a 16-bit value, and so does every output.  The functions here compute the operator in fp64 with
+exactly those roundings and no other: one rounding of the intermediate factor, one of the output;
+everything else (products, sums, softmax statistics) is exact to fp64.  The distance of their result
+from the oracle's is the error no 16-bit implementation can avoid on that input, and it is what the
+parity tests derive their element-wise gate from: a kernel may exceed it by a quarter, not more.
+
+The roundings, per tensor:
+  FFN        H = round(ReLU(X W_up^T + b));  Y = round(H W_down^T + b);
+             dZ = round((dY W_down) (.) [H > 0]);  dX = round(dZ W_up)
+  attention  P' = round(exp(S - m)) (unnormalised, as a fused kernel holds it), the row sum l of the
+             unrounded exponentials;  O = round(P' V / l);
+             Delta = rowsum(dO (.) O) from the stored (rounded) O;
+             P = round(exp(S - LSE));  dS = round(P_exact (.) (dO V^T - Delta));
+             dV = round(P^T dO);  dQ = round(scale dS K);  dK = round(scale dS^T Q)
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from paper_2510_15964_amd.inputs import bf16_round, f16_round
+
+
+def _r(a, dtype):
+    a32 = np.asarray(a, dtype=np.float32)
+    out = bf16_round(a32) if dtype == "bf16" else f16_round(a32) if dtype == "f16" else a32
+    return out.astype(np.float64)
+
+
+def ffn(c, mask=None, b_up=None, b_down=None, act=None):
+    """Emulated Y, H, dX of FFN workload dict `c` (as paper_2510_15964_amd.inputs builds them) under
+    block mask `mask` [T/tile, F/blk].  act: the activation map [T,F] the backward pass gates with
+    (default: the emulated rounded H > 0)."""
+    dt, tt, bn = c["dtype"], c["tile_t"], c["blk_n"]
+    mask = c["mask"] if mask is None else mask
+    X, Wu, Wd, dY = (np.asarray(c[k], np.float64) for k in ("X", "W_up", "W_down", "dY"))
+    M = np.kron(mask.astype(bool), np.ones((tt, bn), dtype=bool))
+    Z = X @ Wu.T
+    if b_up is not None:
+        Z = Z + np.asarray(b_up, np.float64)[None, :]
+    H = _r(np.where(M, np.maximum(Z, 0.0), 0.0), dt)
+    Y = H @ Wd.T
+    if b_down is not None:
+        Y = Y + np.asarray(b_down, np.float64)[None, :]
+    A = (H > 0) if act is None else np.asarray(act, bool)
+    dZ = _r(np.where(M & A, dY @ Wd, 0.0), dt)
+    return dict(H=H, Y=_r(Y, dt), dX=_r(dZ @ Wu, dt))
+
+
+def attn(c):
+    """Emulated O, dQ, dK, dV of attention workload dict `c` (inputs.attn_blocks)."""
+    dt = c.get("dtype", "bf16")
+    B, Hh, S, blk = c["B"], c["Hh"], c["S"], c["blk"]
+    Q, K, V, dO = (np.asarray(c[k], np.float64) for k in ("Q", "K", "V", "dO"))
+    mask = np.asarray(c["mask"], bool)
+    if mask.ndim == 3:
+        mask = mask[None]
+    el = np.kron(mask, np.ones((blk, blk), dtype=bool))               # [mb, Hh, S, S]
+    if c["causal"]:
+        el = el & np.tril(np.ones((S, S), dtype=bool))
+    ha = c.get("head_active")
+    if ha is not None:
+        el = el & np.asarray(ha, bool)[None, :, None, None]
+    el = np.broadcast_to(el, (B, Hh, S, S))
+    out = {k: np.zeros_like(Q) for k in ("O", "dQ", "dK", "dV")}
+    scale = float(c["scale"])
+    for b in range(B):
+        for h in range(Hh):
+            e = el[b, h]
+            q, k, v, do = Q[b, h], K[b, h], V[b, h], dO[b, h]
+            s = np.where(e, scale * (q @ k.T), -np.inf)
+            m = s.max(-1, keepdims=True)
+            m = np.where(np.isinf(m), 0.0, m)
+            E = np.exp(s - m)
+            l = E.sum(-1, keepdims=True)
+            ok = l > 0
+            ls = np.where(ok, l, 1.0)
+            O = _r(np.where(ok, (_r(E, dt) @ v) / ls, 0.0), dt)
+            P = np.where(e, E / ls, 0.0)                               # exp(S - LSE), exact
+            delta = (do * O).sum(-1, keepdims=True)
+            dS = _r(P * (do @ v.T - delta), dt)
+            out["O"][b, h] = O
+            out["dV"][b, h] = _r(_r(P, dt).T @ do, dt)
+            out["dQ"][b, h] = _r(scale * (dS @ k), dt)
+            out["dK"][b, h] = _r(scale * (dS.T @ q), dt)
+    return out

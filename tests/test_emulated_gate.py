@@ -1,0 +1,86 @@
+"""CPU: what an ideal 16-bit pipeline loses against the fp64 oracle (tests/emulate16.py), on inputs
+of the GPU parity tests.  These figures are the reason the element-wise error with an rms floor is
+not gated at the benchmark spec's 2e-2 for 16-bit runs, and they are what the GPU tests gate it at
+instead (at most a quarter above the emulated figure of the same input, per tensor)."""
+import numpy as np
+import pytest
+
+import emulate16
+from paper_2510_15964_amd import inputs
+from util import FRO, TOL, rel_err, rel_err_fro, rel_err_max, round_to
+
+
+def _attn_ref(oracle, c):
+    O, _ = oracle.attn_fwd(c["Q"], c["K"], c["V"], c["mask"], c["scale"], c["causal"],
+                           c["head_active"], c["blk"])
+    dQ, dK, dV = oracle.attn_bwd(c["Q"], c["K"], c["V"], c["dO"], c["mask"], c["scale"], c["causal"],
+                                 c["head_active"], c["blk"])
+    return dict(O=O, dQ=dQ, dK=dK, dV=dV)
+
+
+def test_attention_ideal_pipeline_exceeds_the_element_wise_gate(oracle):
+    """First case of the GPU test test_small_shapes (2 x 3 heads, 256 tokens, 40 % of the causal
+    blocks): rows with one allowed key next to rows with hundreds differ in scale by an order of
+    magnitude while the rms floor is global, so one rounding of P / dS and one of the output
+    already read 0.012 (O), 0.036 (dQ), 0.054 (dK) on the rms-floored element-wise error -- above
+    2e-2 for the gradients -- while the largest error against the largest magnitude and the
+    Frobenius error stay far inside their gates."""
+    c = inputs.attn_blocks(B=2, Hh=3, S=256, D=64, density=0.4, seed=1, dtype="bf16")
+    ref, em = _attn_ref(oracle, c), emulate16.attn(c)
+    floor = {k: rel_err(em[k], ref[k]) for k in ref}
+    print("ideal bf16 attention pipeline, rms-floored element-wise error:", floor)
+    assert floor["O"] == pytest.approx(0.012, abs=0.002)
+    assert floor["dQ"] == pytest.approx(0.036, abs=0.004)
+    assert floor["dK"] == pytest.approx(0.054, abs=0.005)
+    assert max(floor["dQ"], floor["dK"]) > TOL["bf16"]
+    for k in ref:
+        assert rel_err_max(em[k], ref[k]) <= 0.5 * TOL["bf16"], k
+        assert rel_err_fro(em[k], ref[k]) <= FRO["bf16"], k
+
+
+def test_attention_large_score_range_frobenius(oracle):
+    """The input of the GPU test test_large_score_range (queries scaled by 8: near-one-hot
+    probabilities): dS = P (dP - Delta) cancels strongly, so its one rounding weighs more in the
+    gradients than the two-roundoff Frobenius gate allows -- already for the ideal pipeline."""
+    c = inputs.attn_blocks(2, 2, 512, 64, 0.5, seed=41, dtype="bf16")
+    c["Q"] = c["Q"] * np.float32(8.0)
+    ref, em = _attn_ref(oracle, c), emulate16.attn(c)
+    fro = {k: rel_err_fro(em[k], ref[k]) for k in ref}
+    print("ideal bf16 attention pipeline, large score range, Frobenius error:", fro)
+    assert fro["O"] <= FRO["bf16"]
+    assert max(fro["dQ"], fro["dK"]) > 0.8 * FRO["bf16"]
+    assert max(fro.values()) <= 1e-2
+
+
+def test_ffn_ideal_pipeline_on_planted_support(oracle):
+    """Planted-support FFN input (the recipe of configs[1] at a small size): the gate channels make
+    rows of dX differ in scale, so the ideal pipeline's rms-floored error is a multiple of a bf16
+    roundoff (2^-9) although its max-norm and Frobenius errors are a fraction of their gates."""
+    c = inputs.ffn_planted_support(256, 256, 1024, 64, 64, 0.5, 4.0, seed=51)
+    H, Y = oracle.ffn_fwd(c["X"], c["W_up"], c["W_down"], c["mask"], 64, 64)
+    Hq = round_to(H, "bf16")
+    _, dX = oracle.ffn_bwd_dx(c["dY"], c["W_up"], c["W_down"], c["mask"], Hq > 0, 64, 64)
+    em = emulate16.ffn(c, act=Hq > 0)
+    assert np.array_equal(em["H"], Hq)          # the one rounding of H, nothing else
+    for name, g, r in (("Y", em["Y"], Y), ("dX", em["dX"], dX)):
+        print(f"ideal bf16 FFN pipeline {name}: rms-floored {rel_err(g, r):.4f} max-rel "
+              f"{rel_err_max(g, r):.4f} fro {rel_err_fro(g, r):.5f}")
+        assert rel_err(g, r) > 2.0 ** -9
+        assert rel_err_max(g, r) <= 0.5 * TOL["bf16"]
+        assert rel_err_fro(g, r) <= FRO["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_emulation_without_rounding_is_the_oracle(oracle, dtype, monkeypatch):
+    """With the rounding switched off the emulation is the oracle's definition in other code: it
+    reproduces the oracle to fp64 rounding, so whatever it reads with rounding on is rounding."""
+    monkeypatch.setattr(emulate16, "_r", lambda a, dt: np.asarray(a, np.float64))
+    c = inputs.attn_blocks(B=2, Hh=2, S=192, D=64, density=0.5, seed=3, dtype=dtype, head_keep=0.5)
+    ref, em = _attn_ref(oracle, c), emulate16.attn(c)
+    for k in ref:
+        assert rel_err(em[k], ref[k]) < 1e-12, k
+    f = inputs.ffn_bernoulli(128, 64, 256, 64, 64, 0.5, 7, dtype=dtype, w_std=0.1)
+    H, Y = oracle.ffn_fwd(f["X"], f["W_up"], f["W_down"], f["mask"], 64, 64)
+    _, dX = oracle.ffn_bwd_dx(f["dY"], f["W_up"], f["W_down"], f["mask"], H > 0, 64, 64)
+    ef = emulate16.ffn(f)
+    assert rel_err(ef["Y"], Y) < 1e-12 and rel_err(ef["dX"], dX) < 1e-12

@@ -4,7 +4,9 @@ import numpy as np
 import pytest
 
 from paper_2510_15964_amd import inputs
-from util import FRO, TOL, dev, host, rel_err, rel_err_fro, rel_err_max, lx_dtype
+import emulate16
+from util import (EMUL_FACTOR, FRO, TOL, assert_within_emulated, dev, host, rel_err, rel_err_fro,
+                  rel_err_max, lx_dtype)
 
 pytestmark = pytest.mark.gpu
 
@@ -50,26 +52,35 @@ def run_oracle(oracle, c):
                            c["head_active"], c["blk"])
     dQ, dK, dV = oracle.attn_bwd(c["Q"], c["K"], c["V"], c["dO"], c["mask"], c["scale"],
                                  c["causal"], c["head_active"], c["blk"])
-    return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV)
+    # the ideal 16-bit pipeline on the same input: what the element-wise gate is derived from
+    return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV, emul=emulate16.attn(c))
 
 
-def check(got, ref, label="", fro_grad=None, dtype="bf16"):
+def check(got, ref, label="", fro_from_emul=False, dtype="bf16"):
+    """Gates per tensor: max-rel <= TOL, Frobenius <= FRO, and the rms-floored element-wise error
+    at most EMUL_FACTOR times that of the ideal 16-bit pipeline on the same input (ref["emul"]).
+    fro_from_emul: the Frobenius gate of the gradients is EMUL_FACTOR times the ideal pipeline's
+    Frobenius error instead (inputs whose ideal pipeline already exceeds FRO)."""
     tol = TOL[dtype]
+    emul = ref["emul"]
     fro_gate = {k: FRO[dtype] for k in ("O", "dQ", "dK", "dV")}
-    if fro_grad is not None:
-        fro_gate.update(dQ=fro_grad, dK=fro_grad, dV=fro_grad)
+    if fro_from_emul:
+        fro_gate.update({k: max(FRO[dtype], EMUL_FACTOR * rel_err_fro(emul[k], ref[k]))
+                         for k in ("dQ", "dK", "dV")})
     ninf = np.isneginf(ref["LSE"])
     assert np.array_equal(np.isneginf(got["LSE"]), ninf), "rows without keys must give LSE = -inf"
     errs = {k: rel_err_max(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
     fro = {k: rel_err_fro(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
-    floor = {k: rel_err(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}   # reported only
+    floor = {k: rel_err(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
+    ideal = {k: rel_err(emul[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
     fin = ~ninf
     errs["LSE"] = float(np.max(np.abs(got["LSE"][fin] - ref["LSE"][fin]))) if fin.any() else 0.0
-    print(f"[attn {label}] max-rel {errs} fro {fro} rms-floored {floor}", flush=True)
+    print(f"[attn {label}] max-rel {errs} fro {fro} rms-floored {floor} (ideal pipeline {ideal})", flush=True)
     for k in ("O", "dQ", "dK", "dV"):
         assert np.isfinite(got[k]).all(), k
         assert errs[k] <= tol, (k, errs[k])
         assert fro[k] <= fro_gate[k], (k, fro[k])
+        assert_within_emulated(got[k], ref[k], emul[k], k)
     assert errs["LSE"] <= tol        # absolute, natural-log units
     # rows with no allowed key: exact zeros
     assert not got["O"][ninf].any() and not got["dQ"][ninf].any()
@@ -124,9 +135,11 @@ def test_large_score_range(lx, oracle):
     c = inputs.attn_blocks(2, 2, 512, 64, 0.5, seed=41, dtype="bf16")
     c["Q"] = c["Q"] * np.float32(8.0)          # exact in bf16
     # With near-one-hot probabilities dS = P (dP - Delta) cancels strongly, so the one bf16
-    # rounding of dS weighs more in the gradients' Frobenius error (measured 5.5e-3) than the
-    # two-roundoff gate derived for ordinary scores allows; the forward outputs keep that gate.
-    check(run_gpu(lx, c), run_oracle(oracle, c), "large score range", fro_grad=1e-2)
+    # rounding of dS weighs more in the gradients' Frobenius error than the two-roundoff gate
+    # derived for ordinary scores allows, already in the ideal pipeline (5.1e-3 for dQ:
+    # test_emulated_gate.py); the gradients are gated at a quarter above the ideal pipeline's
+    # Frobenius error on this input, the forward output keeps the ordinary gate.
+    check(run_gpu(lx, c), run_oracle(oracle, c), "large score range", fro_from_emul=True)
 
 
 def test_strided_layout(lx, oracle):
@@ -227,3 +240,20 @@ def test_rows_of_one_and_two_blocks(lx, oracle, r):
         finally:
             lx.lx_attn_set_rows_per_workgroup(0)
         check(got, run_oracle(oracle, c), f"band of {width}, rows per workgroup {r}")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_blocks_above_the_diagonal_of_a_causal_mask(lx, oracle, D):
+    """A list that holds blocks above the diagonal although the call is causal (a predictor or a
+    pattern pool may produce one): their keys all lie after the queries, so they contribute
+    nothing, as in the oracle, whose key test is k <= q wherever the block lies.  Row 0 of head 1
+    lists ONLY such blocks: no allowed key, O = 0, LSE = -inf."""
+    c = inputs.attn_blocks(2, 2, 320, D, 0.5, seed=61, dtype="bf16")
+    rng = np.random.default_rng(5)
+    nb = 320 // 64
+    up = np.triu(np.ones((nb, nb), np.uint8), 1)
+    c["mask"] = c["mask"] | (up[None, None] & (rng.random(c["mask"].shape) < 0.5)).astype(np.uint8)
+    c["mask"][0, 1, 0] = [0, 1, 0, 1, 1]
+    ref = run_oracle(oracle, c)
+    assert np.isneginf(ref["LSE"][:, 1, :64]).all()
+    check(run_gpu(lx, c), ref, f"blocks above the diagonal, D={D}")

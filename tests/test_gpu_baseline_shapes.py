@@ -1,0 +1,186 @@
+"""GPU parity at the launch shapes of the benchmark's large configurations (configs[3]: OPT-6.7B,
+configs[4]: OPT-13B density sweep) and of the benchmark's one-call layer: the full-size launch
+runs on the GPU, the oracle computes sampled token rows (FFN) or sampled heads (attention).
+
+FFN sampling.  Token rows are independent in both passes (the ReLU gate is element-wise), and the
+oracle is the plain definition for any tile height, so a few rows of a token tile, given to the
+oracle as a "tile" of that many rows with the tile's mask row, are exactly the outputs the
+full-size launch must produce for those rows.  The backward launch reads activations in which the
+sampled rows hold the oracle's H (rounded to the run dtype), so both sides gate alike.
+Sampled tiles come from both halves of the tile range (the work-item search of the sdd kernels
+scans 64 list rows at a time) and include the tiles with the longest and the shortest list (the
+first and the last rank of the dsd kernels' tile order)."""
+import numpy as np
+import pytest
+
+from paper_2510_15964_amd import inputs
+import emulate16
+from util import (FRO, TOL, assert_within_emulated, dev, host, rel_err, rel_err_fro, rel_err_max, round_to,
+                  lx_dtype)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lx():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2510_15964_amd import lx
+    return lx
+
+
+def sample_tiles(mask, extra=()):
+    """Tiles with the longest and the shortest non-empty list, the first and the last tile, and
+    `extra`."""
+    n = mask.sum(1)
+    order = np.lexsort((np.arange(len(n)), -n))          # rank of the dsd tile order
+    nz = [int(i) for i in order if n[i] > 0]
+    picks = [nz[0], nz[-1], 0, len(n) - 1, *extra] if nz else [0]
+    out = []
+    for i in picks:
+        if i not in out:
+            out.append(int(i))
+    return out
+
+
+def check_ffn_sampled(lx, oracle, c, tiles, rows, shared=False, tiles_per_wg=0, label=""):
+    """Full-size forward and backward launches of workload `c`; the oracle on token rows `rows`
+    (indices inside a tile) of each tile of `tiles`.  shared: one list row for all token tiles
+    (the mask rows are equal)."""
+    import torch
+    dt = c["dtype"]
+    T, d, F = c["T"], c["d"], c["F"]
+    mask = c["mask"]
+    Tt, Fb = mask.shape
+    X, Wu, Wd, dY = (dev(c[k], dt) for k in ("X", "W_up", "W_down", "dY"))
+    if shared:
+        assert (mask == mask[:1]).all()
+        lmask, gt = np.ascontiguousarray(mask[:1]), Tt
+    else:
+        lmask, gt = mask, 1
+    bl = lx.lx_mask_compact(torch.from_numpy(np.ascontiguousarray(lmask)).cuda())
+    rp = np.concatenate([[0], np.cumsum(lmask.sum(1, dtype=np.int64))])
+    nblocks = max(int(lmask.sum()) * gt, 1)
+    blr = lx.BlockList(bl.rows, bl.cols, bl.row_ptr, bl.col_idx, max(int(lmask.sum()), 1))
+    Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+    ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(lx_dtype(lx, dt), T, d, F, 64, 64, nblocks, 1)
+                     + 256, dtype=torch.uint8, device="cuda")
+    H_act = torch.full((nblocks * 4096 + 4096,), float("nan"), dtype=X.dtype, device="cuda")
+    Y = torch.full_like(X, float("nan"))
+    lx.lx_ffn_set_token_tiles_per_workgroup(tiles_per_wg)
+    try:
+        lx.lx_sparse_ffn_fwd(X, Wu, Wd, blr, 64, 64, Y, H_act)
+        torch.cuda.synchronize()
+        assert torch.isnan(H_act[nblocks * 4096:]).all(), "wrote past the H_act buffer"
+        assert not torch.isnan(H_act[:int(lmask.sum()) * gt * 4096]).any(), "a listed block was not written"
+        Hb = H_act[:nblocks * 4096].view(nblocks, 64, 64)
+        H_in = H_act.clone()
+        Hb_in = H_in[:nblocks * 4096].view(nblocks, 64, 64)
+        rows = np.asarray(rows)
+        refs = {}
+        for i in tiles:
+            tok = i * 64 + rows
+            r = i // gt
+            cols = np.nonzero(lmask[r])[0]
+            Ho, Yo = oracle.ffn_fwd(c["X"][tok], c["W_up"], c["W_down"], lmask[r:r + 1], len(rows), 64)
+            Hq = round_to(Ho, dt)
+            # block number of (tile i, entry k): row_ptr[r]*gt + k*gt + i%gt
+            blk = rp[r] * gt + np.arange(len(cols)) * gt + i % gt
+            Hg = host(Hb[torch.from_numpy(blk).cuda()][:, torch.from_numpy(rows).cuda()])   # [n, rows, 64]
+            Ho_c = Ho.reshape(len(rows), Fb, 64)[:, cols].transpose(1, 0, 2)
+            Hb_in[torch.from_numpy(blk).cuda()[:, None], torch.from_numpy(rows).cuda()[None, :]] = dev(
+                Hq.reshape(len(rows), Fb, 64)[:, cols].transpose(1, 0, 2), dt)
+            # the ideal 16-bit pipeline on the same rows (the element-wise gate), given only the
+            # listed neuron blocks of the weights
+            nrow = (cols[:, None] * 64 + np.arange(64)[None, :]).reshape(-1)
+            em = emulate16.ffn(dict(dtype=dt, tile_t=len(rows), blk_n=64, X=c["X"][tok], dY=c["dY"][tok],
+                                    W_up=c["W_up"][nrow], W_down=c["W_down"][:, nrow]),
+                               mask=np.ones((1, len(cols)), np.uint8),
+                               act=Hq.reshape(len(rows), Fb, 64)[:, cols].reshape(len(rows), -1) > 0)
+            em["H"] = em["H"].reshape(len(rows), len(cols), 64).transpose(1, 0, 2)
+            refs[i] = (tok, Hq, Yo, Hg, Ho_c, em)
+        dX = torch.full_like(X, float("nan"))
+        lx.lx_sparse_ffn_bwd_dx(dY, H_in, Wu, Wd, blr, 64, 64, dX, ws, W_up_t=Wut, W_down_t=Wdt)
+        torch.cuda.synchronize()
+    finally:
+        lx.lx_ffn_set_token_tiles_per_workgroup(0)
+    Yh, dXh = host(Y), host(dX)
+    assert np.isfinite(Yh).all() and np.isfinite(dXh).all()
+    for i in tiles:
+        tok, Hq, Yo, Hg, Ho_c, em = refs[i]
+        r = i // gt
+        _, dXo = oracle.ffn_bwd_dx(c["dY"][tok], c["W_up"], c["W_down"], lmask[r:r + 1], Hq > 0, len(rows), 64)
+        prs = dict(Y=(Yh[tok], Yo), dX=(dXh[tok], dXo))
+        if Ho_c.size:
+            prs["H"] = (Hg, Ho_c)
+        errs = {k: rel_err_max(*p) for k, p in prs.items()}
+        fro = {k: rel_err_fro(*p) for k, p in prs.items()}
+        print(f"[{label} tile {i}: {int(lmask[r].sum())} blocks, rows {list(rows)}] max-rel {errs} fro {fro} "
+              f"rms-floored { {k: rel_err(*p) for k, p in prs.items()} }", flush=True)
+        for k, (g, ref) in prs.items():
+            if not ref.any():
+                assert not g.any(), (i, k)
+                continue
+            assert errs[k] <= TOL[dt], (i, k, errs[k])
+            assert fro[k] <= FRO[dt], (i, k, fro[k])
+            assert_within_emulated(g, ref, em[k], f"tile {i} {k}")
+    # tiles without a listed block are exactly zero
+    for i in np.nonzero(mask.sum(1) == 0)[0]:
+        assert not Yh[i * 64:(i + 1) * 64].any() and not dXh[i * 64:(i + 1) * 64].any()
+
+
+ROWS8 = (0, 9, 18, 27, 36, 45, 54, 63)     # both 32-row halves, every residue of the lane groups
+
+
+def test_config4_ffn_full_size_sampled_rows(lx, oracle):
+    """configs[3] FFN: 128 token tiles in one call, d = 4096, F = 16384 (256 blocks per row)."""
+    c = inputs.config4_ffn()
+    check_ffn_sampled(lx, oracle, c, sample_tiles(c["mask"], (63, 64, 100)), ROWS8, label="config4")
+
+
+def test_onecall_layer_ffn_full_size_sampled_rows(lx, oracle):
+    """The benchmark's one-call layer: configs[1]'s recipe over 8192 tokens (128 token tiles)."""
+    c = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
+    check_ffn_sampled(lx, oracle, c, sample_tiles(c["mask"], (63, 64, 97)), ROWS8, label="onecall")
+
+
+@pytest.mark.parametrize("rho,rows", [(0.05, ROWS8), (0.3, (0, 27, 36, 63)), (1.0, (5, 58))])
+def test_config5_ffn_full_size_sampled_rows(lx, oracle, rho, rows):
+    """configs[4] FFN at three densities: d = 5120, F = 20480 (320 blocks per row), a list per tile."""
+    c = inputs.config5_ffn(rho)
+    tiles = sample_tiles(c["mask"], (31,))[:3 if rho >= 1.0 else 5]
+    check_ffn_sampled(lx, oracle, c, tiles, rows, label=f"config5 rho={rho}")
+
+
+@pytest.mark.parametrize("rho,rows", [(0.3, (0, 27, 36, 63)), (1.0, (5, 58))])
+def test_config5_ffn_shared_list_four_tiles_per_workgroup(lx, oracle, rho, rows):
+    """configs[4] FFN with ONE list row for all token tiles and four token tiles per workgroup:
+    the benchmark's config5:RHO:shared workloads (the dense path at rho = 1)."""
+    c = inputs.config5_ffn(rho)
+    c["mask"] = np.repeat(c["mask"][:1], c["mask"].shape[0], axis=0)
+    check_ffn_sampled(lx, oracle, c, (0, 30, 63), rows, shared=True, tiles_per_wg=4,
+                      label=f"config5 rho={rho} shared")
+
+
+@pytest.mark.parametrize("Tt,d,F,density,seed", [(128, 128, 1024, 0.3, 301), (192, 64, 640, 0.5, 302)])
+def test_more_than_64_token_tiles_small_d(lx, oracle, Tt, d, F, density, seed):
+    """More than 64 token tiles with a list per tile at a size the oracle computes in full: the
+    work-item search takes its second and third 64-row segment, and 192 tiles are more than the
+    dsd kernels rank."""
+    from test_gpu_ffn import compare
+    c = inputs.ffn_bernoulli(Tt * 64, d, F, 64, 64, density, seed, dtype="bf16", w_std=0.05)
+    c["mask"][70] = 0                       # an empty row inside the second segment
+    compare(lx, oracle, c)
+
+
+def test_config5_attention_full_size_sampled_heads(lx, oracle):
+    """configs[4] attention half at full size (2 x 40 heads x 2048 tokens, head size 128) at 30 %
+    density; the oracle checks sampled (batch, head) pairs."""
+    from test_gpu_attn import check, run_gpu, run_oracle
+    c = inputs.config5_attn(0.3)
+    got = run_gpu(lx, c)
+    for (b, h) in [(0, 0), (1, 39)]:
+        sub = dict(c, B=1, Hh=1, mask=c["mask"][:, h:h + 1], head_active=np.ones(1, np.uint8),
+                   **{k: c[k][b:b + 1, h:h + 1] for k in ("Q", "K", "V", "dO")})
+        check({k: v[b:b + 1, h:h + 1] for k, v in got.items()}, run_oracle(oracle, sub),
+              f"config5 attention b={b} h={h}")

@@ -4,7 +4,9 @@ import numpy as np
 import pytest
 
 from paper_2510_15964_amd import inputs
-from util import FRO, TOL, compact_blocks, dev, host, rel_err, rel_err_fro, rel_err_max, round_to, lx_dtype
+import emulate16
+from util import (FRO, TOL, assert_within_emulated, compact_blocks, dev, host, rel_err, rel_err_fro,
+                  rel_err_max, round_to, lx_dtype)
 
 pytestmark = pytest.mark.gpu
 
@@ -68,8 +70,14 @@ def run_oracle(oracle, c, mask=None, bias=False):
     # oracle's H rounded to the run dtype, so the ReLU gate is decided once
     Hq = round_to(H, dt)
     dZ, dX = oracle.ffn_bwd_dx(c["dY"], c["W_up"], c["W_down"], mask, Hq > 0, tt, bn)
-    return dict(H=H, Y=Y, dX=dX, Hq_act=compact_blocks(Hq, mask, tt, bn),
-                H_act=compact_blocks(H, mask, tt, bn))
+    out = dict(H=H, Y=Y, dX=dX, Hq_act=compact_blocks(Hq, mask, tt, bn),
+               H_act=compact_blocks(H, mask, tt, bn))
+    if dt != "f32":
+        # the ideal 16-bit pipeline on the same input: what the element-wise gate is derived from
+        em = emulate16.ffn(c, mask, c["b_up"] if bias else None, c["b_down"] if bias else None,
+                           act=Hq > 0)
+        out["emul"] = dict(H=compact_blocks(em["H"], mask, tt, bn), Y=em["Y"], dX=em["dX"])
+    return out
 
 
 def compare(lx, oracle, c, mask=None, packed=True, bias=False):
@@ -86,8 +94,10 @@ def compare(lx, oracle, c, mask=None, packed=True, bias=False):
     for k in pairs:
         assert errs[k] <= tol, (k, errs[k], tol)
         assert fro[k] <= FRO[c["dtype"]], (k, fro[k])
-        if c["dtype"] == "f32":          # fp32 also meets the stricter element-wise gate
+        if c["dtype"] == "f32":          # fp32 meets the element-wise gate as it stands
             assert floor[k] <= tol, (k, floor[k])
+        elif pairs[k][1].size:           # 16-bit: at most a quarter above the ideal 16-bit pipeline
+            assert_within_emulated(*pairs[k], ref["emul"][k], k)
     assert np.isfinite(got["Y"]).all() and np.isfinite(got["dX"]).all()
     return got, ref
 
@@ -195,6 +205,8 @@ def test_config2_bf16_full_size_sampled_tiles(lx, oracle):
         print(f"config2 tile {i}: n_active={int(c['mask'][i].sum())} max-rel {errs} fro {fro} "
               f"rms-floored {[rel_err(*p) for p in prs]}", flush=True)
         assert max(errs) <= TOL["bf16"] and max(fro) <= FRO["bf16"]
+        for name, p in zip(("H", "Y", "dX"), prs):
+            assert_within_emulated(*p, ref["emul"][name], name)
         # full-size launch and single-tile launch agree bit for bit on this tile
         assert np.array_equal(sub_got["Y"], got["Y"][sl])
     # tiles with no active block are exactly zero
@@ -238,6 +250,49 @@ def test_list_longer_than_its_capacity_is_truncated(lx, dtype, tile):
     for x, y in zip(a, b):
         assert np.isfinite(x).all()
         assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("Tt,G,tiles_per_wg", [(64, 64, 0), (128, 128, 0), (64, 16, 1), (64, 16, 2), (64, 16, 4)])
+def test_capacity_a_quarter_of_the_list(lx, Tt, G, tiles_per_wg):
+    """A capacity far below the list's length (a quarter of it), on enough tiles that the items
+    within the capacity would be dealt to workgroups the grid never launches if the item search
+    counted the entries beyond it: every call gives the bits of the truncated mask.  G list rows
+    for Tt token tiles (G < Tt: rows shared by Tt / G tiles, run with 1, 2 and 4 tiles per
+    workgroup)."""
+    import torch
+    T, d, F = Tt * 64, 128, 2048
+    c = inputs.ffn_bernoulli(T, d, F, 64, 64, 0.5, seed=78 + Tt + G, dtype="bf16", w_std=0.05)
+    gt = Tt // G
+    mask = np.ascontiguousarray(c["mask"][:G])
+    nnz = int(mask.sum())
+    cap = nnz // 4
+    trunc = mask.copy()
+    rr, cc = np.nonzero(mask)
+    trunc[rr[cap:], cc[cap:]] = 0
+    X, Wu, Wd, dY = (dev(c[k], "bf16") for k in ("X", "W_up", "W_down", "dY"))
+
+    def run(m):
+        bl = lx.lx_mask_compact(torch.from_numpy(m).cuda(), nnz_cap=cap)
+        nb = cap * gt
+        H = torch.full((nb * 4096 + 4096,), float("nan"), dtype=X.dtype, device="cuda")
+        Y = torch.full_like(X, float("nan"))
+        ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(lx.LX_BF16, T, d, F, 64, 64, nb, 0) + 256,
+                         dtype=torch.uint8, device="cuda")
+        dX = torch.full_like(X, float("nan"))
+        lx.lx_ffn_set_token_tiles_per_workgroup(tiles_per_wg)
+        try:
+            lx.lx_sparse_ffn_fwd(X, Wu, Wd, bl, 64, 64, Y, H)
+            assert torch.isnan(H[nb * 4096:]).all(), "wrote past the H_act buffer"
+            lx.lx_sparse_ffn_bwd_dx(dY, H, Wu, Wd, bl, 64, 64, dX, ws)
+            torch.cuda.synchronize()
+        finally:
+            lx.lx_ffn_set_token_tiles_per_workgroup(0)
+        return host(Y), host(dX), host(H[:nb * 4096])
+
+    a, b = run(mask), run(trunc)
+    for name, x, y in zip(("Y", "dX", "H"), a, b):
+        assert np.isfinite(x).all(), name        # every block within the capacity was written
+        assert np.array_equal(x, y), name
 
 
 def _grouped_compact(dense, rows_mask, gt, tt, bn):

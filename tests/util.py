@@ -18,6 +18,10 @@ import numpy as np
 # eighth of bfloat16's.
 TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2.5e-3}
 FRO = {"f32": 2e-6, "bf16": 5e-3, "f16": 6.25e-4}
+# 16-bit runs: the element-wise error with an rms floor (rel_err) is gated against what the ideal
+# 16-bit pipeline (tests/emulate16.py: one rounding of the intermediate factor, one of the output,
+# everything else exact) loses on the same input: at most EMUL_FACTOR times that figure.
+EMUL_FACTOR = 1.25
 
 
 def rel_err(got, ref) -> float:
@@ -33,6 +37,14 @@ def rel_err(got, ref) -> float:
     if rms == 0.0:
         return float(np.max(np.abs(g)))       # reference is all zero: must match exactly
     return float(np.max(np.abs(g - r) / np.maximum(np.abs(r), rms)))
+
+
+def assert_within_emulated(got, ref, emul, name, factor=EMUL_FACTOR):
+    """rel_err(got, ref) <= factor * rel_err(emul, ref): the kernel's element-wise error against the
+    oracle is at most `factor` times the ideal 16-bit pipeline's on the same input.  Returns both."""
+    e_got, e_emul = rel_err(got, ref), rel_err(emul, ref)
+    assert e_got <= factor * e_emul, (name, "rms-floored error", e_got, "ideal pipeline", e_emul)
+    return e_got, e_emul
 
 
 def rel_err_max(got, ref) -> float:
