@@ -485,6 +485,43 @@ lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int3
   return launch_attn_fwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
+// Shared by the two backward entry points: everything but where Delta and -LSE*log2(e) live.
+static lx_status attn_bwd_check(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                                const void* Q, const void* K, const void* V, const void* O,
+                                const float* LSE, const void* dO, const int64_t strides_bhs[3],
+                                const lx_blocklist* bl_rows, const lx_blocklist* bl_cols,
+                                int32_t mask_batch, void* dQ, void* dK, void* dV) {
+  lx_status s = check_attn(dt, B, Hh, S, D, strides_bhs, bl_rows, mask_batch);
+  if (s != LX_OK) return s;
+  s = check_attn(dt, B, Hh, S, D, strides_bhs, bl_cols, mask_batch);
+  if (s != LX_OK) return s;
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return LX_ERR_INVALID_ARG;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
+    return LX_ERR_INVALID_ARG;
+  return LX_OK;
+}
+static lx_status attn_bwd_run(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D, float scale,
+                              int32_t causal, const void* Q, const void* K, const void* V,
+                              const void* O, const float* LSE, const void* dO,
+                              const int64_t strides_bhs[3], const lx_blocklist* bl_rows,
+                              const lx_blocklist* bl_cols, int32_t mask_batch,
+                              const uint8_t* head_active, void* dQ, void* dK, void* dV,
+                              float* delta, float* neg_lse2, void* stream) {
+  AttnArgs a = {};
+  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
+  a.O = (const uint16_t*)O; a.dO = (const uint16_t*)dO; a.LSEin = LSE;
+  a.dQ = (uint16_t*)dQ; a.dK = (uint16_t*)dK; a.dV = (uint16_t*)dV;
+  a.Delta = delta;
+  a.NegLse2 = neg_lse2;
+  a.sb = strides_bhs[0]; a.sh = strides_bhs[1]; a.ss = strides_bhs[2];
+  a.row_ptr = bl_rows->row_ptr; a.col_idx = bl_rows->col_idx; a.nnz_cap = bl_rows->nnz_cap;
+  a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx; a.cnnz_cap = bl_cols->nnz_cap;
+  a.head_active = head_active;
+  a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
+  return launch_attn_bwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
 lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                                 float scale, int32_t causal, const void* Q, const void* K,
                                 const void* V, const void* O, const float* LSE, const void* dO,
@@ -492,28 +529,16 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
                                 const lx_blocklist* bl_cols, int32_t mask_batch,
                                 const uint8_t* head_active, void* dQ, void* dK, void* dV,
                                 void* workspace, size_t workspace_bytes, void* stream) {
-  lx_status s = check_attn(dt, B, Hh, S, D, strides_bhs, bl_rows, mask_batch);
+  lx_status s = attn_bwd_check(dt, B, Hh, S, D, Q, K, V, O, LSE, dO, strides_bhs, bl_rows, bl_cols,
+                               mask_batch, dQ, dK, dV);
   if (s != LX_OK) return s;
-  s = check_attn(dt, B, Hh, S, D, strides_bhs, bl_cols, mask_batch);
-  if (s != LX_OK) return s;
-  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return LX_ERR_INVALID_ARG;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) ||
-      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
-    return LX_ERR_INVALID_ARG;
+  if (!aligned16(workspace)) return LX_ERR_INVALID_ARG;
   if (!workspace || workspace_bytes < lx_sparse_attn_bwd_workspace_bytes(dt, B, Hh, S, D))
     return LX_ERR_WORKSPACE;
-  AttnArgs a = {};
-  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
-  a.O = (const uint16_t*)O; a.dO = (const uint16_t*)dO; a.LSEin = LSE;
-  a.dQ = (uint16_t*)dQ; a.dK = (uint16_t*)dK; a.dV = (uint16_t*)dV;
-  a.Delta = (float*)workspace;
-  a.NegLse2 = (float*)((char*)workspace + round256((size_t)B * Hh * S * sizeof(float)));
-  a.sb = strides_bhs[0]; a.sh = strides_bhs[1]; a.ss = strides_bhs[2];
-  a.row_ptr = bl_rows->row_ptr; a.col_idx = bl_rows->col_idx; a.nnz_cap = bl_rows->nnz_cap;
-  a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx; a.cnnz_cap = bl_cols->nnz_cap;
-  a.head_active = head_active;
-  a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
-  return launch_attn_bwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+  float* delta = (float*)workspace;
+  float* neg_lse2 = (float*)((char*)workspace + round256((size_t)B * Hh * S * sizeof(float)));
+  return attn_bwd_run(dt, B, Hh, S, D, scale, causal, Q, K, V, O, LSE, dO, strides_bhs, bl_rows,
+                      bl_cols, mask_batch, head_active, dQ, dK, dV, delta, neg_lse2, stream);
 }
 
 }  // extern "C"
