@@ -1,7 +1,7 @@
 """CPU: what an ideal 16-bit pipeline loses against the fp64 oracle (tests/emulate16.py), on inputs
 of the GPU parity tests.  These figures are the reason the element-wise error with an rms floor is
 not gated at the benchmark spec's 2e-2 for 16-bit runs, and they are what the GPU tests gate it at
-instead (at most a quarter above the emulated figure of the same input, per tensor)."""
+instead (at most util.EMUL_FACTOR times the emulated figure of the same input, per tensor)."""
 import numpy as np
 import pytest
 
@@ -68,6 +68,28 @@ def test_ffn_ideal_pipeline_on_planted_support(oracle):
         assert rel_err(g, r) > 2.0 ** -9
         assert rel_err_max(g, r) <= 0.5 * TOL["bf16"]
         assert rel_err_fro(g, r) <= FRO["bf16"]
+
+
+def test_equally_valid_realisations_spread_by_up_to_a_factor_of_two(oracle):
+    """The rms-floored figure is a maximum over ~10^5 rounding errors.  Moving the reference point
+    of the unnormalised probabilities (any upper bound of a row's scores gives the same softmax;
+    a fused kernel's running maximum is one such bound) changes which values are rounded and
+    nothing else, and the figure of one tensor moves by up to a factor of two: the GPU gate is
+    therefore taken from the envelope of several realisations, with util.EMUL_FACTOR on top.
+    dV, whose only rounded factor exp(S - LSE) does not depend on the reference point, is the same
+    in every realisation."""
+    c = inputs.attn_blocks(B=2, Hh=3, S=256, D=64, density=0.4, seed=1, dtype="bf16")
+    ref = _attn_ref(oracle, c)
+    figs = [{k: rel_err(em[k], ref[k]) for k in ref}
+            for em in (emulate16.attn(c, sh) for sh in (0.0, 0.37, 1.1, 2.9, 5.3))]
+    spread = {k: max(f[k] for f in figs) / min(f[k] for f in figs) for k in ref}
+    print("spread of the ideal pipeline's figure over five reference points:", spread)
+    assert spread["dV"] == pytest.approx(1.0, abs=1e-12)
+    assert 1.5 < max(spread["O"], spread["dK"]) < 2.5
+    for em in emulate16.attn_realisations(c):          # every realisation obeys the global gates
+        for k in ref:
+            assert rel_err_max(em[k], ref[k]) <= 0.5 * TOL["bf16"], k
+            assert rel_err_fro(em[k], ref[k]) <= FRO["bf16"], k
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])

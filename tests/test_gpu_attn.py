@@ -5,7 +5,7 @@ import pytest
 
 from paper_2510_15964_amd import inputs
 import emulate16
-from util import (EMUL_FACTOR, FRO, TOL, assert_within_emulated, dev, host, rel_err, rel_err_fro,
+from util import (FRO, TOL, assert_within_emulated, dev, host, rel_err, rel_err_fro,
                   rel_err_max, lx_dtype)
 
 pytestmark = pytest.mark.gpu
@@ -53,26 +53,27 @@ def run_oracle(oracle, c):
     dQ, dK, dV = oracle.attn_bwd(c["Q"], c["K"], c["V"], c["dO"], c["mask"], c["scale"],
                                  c["causal"], c["head_active"], c["blk"])
     # the ideal 16-bit pipeline on the same input: what the element-wise gate is derived from
-    return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV, emul=emulate16.attn(c))
+    return dict(O=O, LSE=L, dQ=dQ, dK=dK, dV=dV, emul=emulate16.attn_realisations(c))
 
 
 def check(got, ref, label="", fro_from_emul=False, dtype="bf16"):
     """Gates per tensor: max-rel <= TOL, Frobenius <= FRO, and the rms-floored element-wise error
-    at most EMUL_FACTOR times that of the ideal 16-bit pipeline on the same input (ref["emul"]).
-    fro_from_emul: the Frobenius gate of the gradients is EMUL_FACTOR times the ideal pipeline's
+    at most EMUL_FACTOR times that of the ideal 16-bit pipeline on the same input (ref["emul"]: the
+    realisations of emulate16.attn_realisations, whose largest figure counts).
+    fro_from_emul: the Frobenius gate of the gradients is a quarter above the ideal pipeline's
     Frobenius error instead (inputs whose ideal pipeline already exceeds FRO)."""
     tol = TOL[dtype]
     emul = ref["emul"]
     fro_gate = {k: FRO[dtype] for k in ("O", "dQ", "dK", "dV")}
     if fro_from_emul:
-        fro_gate.update({k: max(FRO[dtype], EMUL_FACTOR * rel_err_fro(emul[k], ref[k]))
+        fro_gate.update({k: max(FRO[dtype], 1.25 * max(rel_err_fro(e[k], ref[k]) for e in emul))
                          for k in ("dQ", "dK", "dV")})
     ninf = np.isneginf(ref["LSE"])
     assert np.array_equal(np.isneginf(got["LSE"]), ninf), "rows without keys must give LSE = -inf"
     errs = {k: rel_err_max(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
     fro = {k: rel_err_fro(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
     floor = {k: rel_err(got[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
-    ideal = {k: rel_err(emul[k], ref[k]) for k in ("O", "dQ", "dK", "dV")}
+    ideal = {k: max(rel_err(e[k], ref[k]) for e in emul) for k in ("O", "dQ", "dK", "dV")}
     fin = ~ninf
     errs["LSE"] = float(np.max(np.abs(got["LSE"][fin] - ref["LSE"][fin]))) if fin.any() else 0.0
     print(f"[attn {label}] max-rel {errs} fro {fro} rms-floored {floor} (ideal pipeline {ideal})", flush=True)
@@ -80,7 +81,7 @@ def check(got, ref, label="", fro_from_emul=False, dtype="bf16"):
         assert np.isfinite(got[k]).all(), k
         assert errs[k] <= tol, (k, errs[k])
         assert fro[k] <= fro_gate[k], (k, fro[k])
-        assert_within_emulated(got[k], ref[k], emul[k], k)
+        assert_within_emulated(got[k], ref[k], [e[k] for e in emul], k)
     assert errs["LSE"] <= tol        # absolute, natural-log units
     # rows with no allowed key: exact zeros
     assert not got["O"][ninf].any() and not got["dQ"][ninf].any()
@@ -138,7 +139,8 @@ def test_large_score_range(lx, oracle):
     # rounding of dS weighs more in the gradients' Frobenius error than the two-roundoff gate
     # derived for ordinary scores allows, already in the ideal pipeline (5.1e-3 for dQ:
     # test_emulated_gate.py); the gradients are gated at a quarter above the ideal pipeline's
-    # Frobenius error on this input, the forward output keeps the ordinary gate.
+    # Frobenius error on this input (a sum over all elements, stable between realisations),
+    # the forward output keeps the ordinary gate.
     check(run_gpu(lx, c), run_oracle(oracle, c), "large score range", fro_from_emul=True)
 
 
