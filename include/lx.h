@@ -366,6 +366,27 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lx_sparse_attn_bwd_dx for callers that cannot allocate device memory and have no workspace to
+ * hand over (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same computation with Delta and the rescaled LSE kept in a buffer that is part
+ * of the library's own device image (2 x 4 MiB per GPU, held until the process ends) instead of
+ * a caller's workspace.  The call allocates and frees nothing and calls no allocating routine.
+ * Arguments, layouts, results (bit for bit) and errors are those of lx_sparse_attn_bwd_dx, with
+ *   LX_ERR_WORKSPACE  if B*Hh*S exceeds 1 048 576 rows, the capacity of that buffer;
+ *   LX_ERR_RUNTIME    if the buffer's address on the current device cannot be obtained.
+ * All calls on one GPU share the buffer (the current device's copy is used; its contents after a
+ * call are unspecified): calls that overlap on one GPU -- different streams, or threads -- race;
+ * calls on one stream, or otherwise ordered, do not.
+ */
+lx_status lx_sparse_attn_bwd_dx_noalloc(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                                        float scale, int32_t causal, const void* Q, const void* K,
+                                        const void* V, const void* O, const float* LSE,
+                                        const void* dO, const int64_t strides_bhs[3],
+                                        const lx_blocklist* bl_rows, const lx_blocklist* bl_cols,
+                                        int32_t mask_batch, const uint8_t* head_active, void* dQ,
+                                        void* dK, void* dV, void* stream);
+
+/*
  * Measurement aid for benchmarks (no part of the operators of Sec. VI; it lets a
  * harness time one kernel of the path in place).  After lx_profile_begin every
  * launch of `kernel` is bracketed by a pair of HIP events recorded on the

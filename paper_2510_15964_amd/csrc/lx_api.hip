@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "../../include/lx.h"
@@ -58,6 +59,34 @@ static lx_status check_ffn(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t
     return LX_ERR_INVALID_ARG;
   if (bl->nnz_cap < 0 || (int64_t)bl->nnz_cap > (int64_t)bl->rows * bl->cols) return LX_ERR_INVALID_ARG;
   return LX_OK;
+}
+
+// ---- scratch of lx_sparse_attn_bwd_dx_noalloc ---------------------------------------------
+// Delta and -LSE*log2(e) of up to kScratchRows (batch, head, token) rows: 2 x 4 MiB that every GPU
+// the library runs on holds until the process ends.  `attn_scratch` is a host-side stand-in for
+// the array, not a device address: host code uses the per-device address that
+// hipGetSymbolAddress returns (each GPU holds its own copy of the array at its own address).
+constexpr size_t kScratchRows = (size_t)1 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) float attn_scratch[2 * kScratchRows];
+static float* g_scratch_dev[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+// Address of the current device's copy of the array (looked up once per device); allocates nothing.
+static hipError_t scratch_of_current_device(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_dev[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(attn_scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_dev[dev] = (float*)p;
+  }
+  *out = g_scratch_dev[dev];
+  return hipSuccess;
 }
 
 static size_t act_bytes(lx_dtype dt, int32_t tile_t, int32_t blk_n, int32_t nnz_cap) {
@@ -539,6 +568,30 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
   float* neg_lse2 = (float*)((char*)workspace + round256((size_t)B * Hh * S * sizeof(float)));
   return attn_bwd_run(dt, B, Hh, S, D, scale, causal, Q, K, V, O, LSE, dO, strides_bhs, bl_rows,
                       bl_cols, mask_batch, head_active, dQ, dK, dV, delta, neg_lse2, stream);
+}
+
+lx_status lx_sparse_attn_bwd_dx_noalloc(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+                                        float scale, int32_t causal, const void* Q, const void* K,
+                                        const void* V, const void* O, const float* LSE,
+                                        const void* dO, const int64_t strides_bhs[3],
+                                        const lx_blocklist* bl_rows, const lx_blocklist* bl_cols,
+                                        int32_t mask_batch, const uint8_t* head_active, void* dQ,
+                                        void* dK, void* dV, void* stream) {
+  lx_status s = attn_bwd_check(dt, B, Hh, S, D, Q, K, V, O, LSE, dO, strides_bhs, bl_rows, bl_cols,
+                               mask_batch, dQ, dK, dV);
+  if (s != LX_OK) return s;
+  const size_t rows = (size_t)B * Hh * S;
+  if (rows > kScratchRows) return LX_ERR_WORKSPACE;   // beyond the library's own scratch
+  float* scratch = nullptr;
+  if (scratch_of_current_device(&scratch) != hipSuccess) {
+    (void)hipGetLastError();
+    return LX_ERR_RUNTIME;
+  }
+  // both halves are written in full by the query-side kernel before the key-side kernel reads
+  // them: nothing of an earlier call is read, nothing has to be cleared
+  return attn_bwd_run(dt, B, Hh, S, D, scale, causal, Q, K, V, O, LSE, dO, strides_bhs, bl_rows,
+                      bl_cols, mask_batch, head_active, dQ, dK, dV, scratch, scratch + kScratchRows,
+                      stream);
 }
 
 }  // extern "C"

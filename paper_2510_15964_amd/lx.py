@@ -31,7 +31,7 @@ EXPORTS = (
     "lx_ffn_gather_weight_blocks",
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
-    "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_profile_begin", "lx_profile_end",
+    "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_sparse_attn_bwd_dx_noalloc", "lx_profile_begin", "lx_profile_end",
     "lx_attn_set_rows_per_workgroup", "lx_ffn_set_token_tiles_per_workgroup", "lx_mlp_predict_mask", "lx_attn_combine_patterns",
     "lx_sparse_ffn_lora_fwd_workspace_bytes", "lx_sparse_ffn_lora_bwd_workspace_bytes",
     "lx_sparse_ffn_lora_fwd", "lx_sparse_ffn_lora_bwd",
@@ -79,7 +79,9 @@ _lib.lx_sparse_attn_fwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32, _
 _lib.lx_sparse_attn_bwd_dx.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32, _vp, _vp, _vp,
                                        _vp, _vp, _vp, C.POINTER(_i64), _blp, _blp, _i32, _vp, _vp,
                                        _vp, _vp, _vp, _sz, _vp]
-
+_lib.lx_sparse_attn_bwd_dx_noalloc.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _f, _i32, _vp, _vp, _vp,
+                                               _vp, _vp, _vp, C.POINTER(_i64), _blp, _blp, _i32, _vp,
+                                               _vp, _vp, _vp, _vp]
 
 _lib.lx_profile_begin.argtypes = [_i32, _i32]
 _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
@@ -399,4 +401,19 @@ def lx_sparse_attn_bwd_dx(Q, K, V, O, LSE, dO, bl_rows: BlockList, bl_cols: Bloc
                                       _ptr(head_active), _ptr(dQ), _ptr(dK), _ptr(dV),
                                       _ptr(workspace), ws_bytes, _stream()),
            "lx_sparse_attn_bwd_dx")
+    return dQ, dK, dV
+
+
+def lx_sparse_attn_bwd_dx_noalloc(Q, K, V, O, LSE, dO, bl_rows: BlockList, bl_cols: BlockList,
+                                  scale: float, causal: bool, dQ, dK, dV, mask_batch: int = 1,
+                                  head_active=None):
+    B, Hh, S, D = Q.shape
+    for t in (K, V, O, dO, dQ, dK, dV):
+        assert t.stride() == Q.stride() and t.shape == Q.shape
+    _check(_lib.lx_sparse_attn_bwd_dx_noalloc(_dt(Q), B, Hh, S, D, scale, int(causal), _ptr(Q),
+                                              _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO),
+                                              _strides(Q), C.byref(bl_rows.c), C.byref(bl_cols.c),
+                                              mask_batch, _ptr(head_active), _ptr(dQ), _ptr(dK),
+                                              _ptr(dV), _stream()),
+           "lx_sparse_attn_bwd_dx_noalloc")
     return dQ, dK, dV
