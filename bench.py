@@ -53,6 +53,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 METRIC = "sparse FFN+attn fwd+bwd-dX tokens/s and active-FLOP MFMA util @10/30% density"
 PEAK_MFMA_BF16 = 2.5e15     # FLOP/s, dense MFMA on 16-bit operands (bf16 and fp16 alike), MI355X
 PEAK_HBM = 8.0e12           # B/s
+DEFAULT_WORKLOAD = "opt1.3b_layer"
 
 
 def log(*a):
@@ -137,15 +138,18 @@ def make_workload(name: str):
 class FfnJob:
     """One lx_sparse_ffn_fwd + lx_sparse_ffn_bwd_dx call pair on T tokens."""
 
-    def __init__(self, lx, torch, f, rows, Wu, Wd, Wut, Wdt):
+    def __init__(self, lx, torch, f, rows, wsets):
+        """wsets: list of (W_up, W_down, W_up_t, W_down_t) device copies of the frozen weights; a
+        step uses set number self.wsel (one set: cache-warm; several rotated: cache-cold)."""
         from util import dev, lx_dtype
         self.lx, self.torch = lx, torch
+        self.wsets, self.wsel = wsets, 0
+        Wu, Wd, Wut, Wdt = wsets[0]
         sl = slice(rows[0] * 64, rows[1] * 64)
         self.dt = f["dtype"]
         self.X = dev(f["X"][sl], self.dt)
         self.dY = dev(f["dY"][sl], self.dt)
         self.mask_h = np.ascontiguousarray(f["mask"][rows[0]:rows[1]])
-        self.Wu, self.Wd, self.Wut, self.Wdt = Wu, Wd, Wut, Wdt
         self.T, self.d = self.X.shape
         self.F = Wu.shape[0]
         Tt, Fb = self.mask_h.shape
@@ -196,6 +200,11 @@ class FfnJob:
                                   dtype=torch.uint8, device="cuda")
             self.ws_f = torch.empty(lx.lx_sparse_ffn_lora_fwd_workspace_bytes(self.T, self.d), dtype=torch.uint8,
                                     device="cuda")
+
+    Wu = property(lambda self: self.wsets[self.wsel][0])
+    Wd = property(lambda self: self.wsets[self.wsel][1])
+    Wut = property(lambda self: self.wsets[self.wsel][2])
+    Wdt = property(lambda self: self.wsets[self.wsel][3])
 
     def gather(self):
         """Host-resident weights: the listed blocks of both neuron-major matrices -> device, on the
@@ -303,18 +312,23 @@ class AttnJob:
 def measured_traffic(workload: str, kernel: str):
     """HBM bytes per launch of `kernel` as measured with rocprofv3's FETCH_SIZE / WRITE_SIZE
     counters (two --pmc runs of this script, scaled as the table's header explains); read from
-    the committed summary profiles/hbm_traffic_<workload>.txt, None if there is no entry."""
+    the committed summary profiles/hbm_traffic_<workload>.txt, None if there is no entry.  Also
+    returns the commit the table says it was measured at: a table older than the kernels is
+    stale, and the bench line says which kernels the figure belongs to."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                         f"hbm_traffic_{workload}.txt")
+    commit, traffic = None, None
     try:
         with open(path) as fh:
             for line in fh:
                 c = line.split()
-                if len(c) >= 5 and not line.startswith("#") and kernel in c[0].split("+"):
-                    return (float(c[1]) * float(c[2]) + float(c[3]) * float(c[4])) * 1024.0
+                if line.startswith("# measured_at_commit:"):
+                    commit = c[2]          # the kernels the table was measured on
+                elif len(c) >= 5 and not line.startswith("#") and kernel in c[0].split("+"):
+                    traffic = (float(c[1]) * float(c[2]) + float(c[3]) * float(c[4])) * 1024.0
     except (OSError, ValueError):
         pass
-    return None
+    return traffic, commit
 
 
 def kernel_model(lx, ffn_jobs, attn):
@@ -388,7 +402,35 @@ def cpu_baseline(f, a, ffn_tiles=3, attn_heads=24):
     }
 
 
-def run(workload: str, steps: int, warmup: int, with_cpu: bool):
+def measure_peaks(lx, torch):
+    """What the chip sustains, measured once before the timed region with the library's probes
+    (lx_probe_mfma_rate: an MFMA issue loop on registers; lx_probe_stream_copy: a 16-byte-per-lane
+    copy of 512 MiB, twice the capacity of the cache behind the fabric), best of five launches
+    each, timed with events on the launch stream."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.zero_()
+
+    def best(fn):
+        t = []
+        for _ in range(6):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            work = fn()
+            e1.record()
+            e1.synchronize()
+            t.append((e0.elapsed_time(e1) * 1e-3, work))
+        sec, work = min(t[1:])
+        return work / sec
+
+    mfma = best(lambda: lx.lx_probe_mfma_rate(4000, sink))
+    copy = best(lambda: lx.lx_probe_stream_copy(src, dst))
+    del src, dst
+    return {"mfma_bf16_tflops": mfma / 1e12, "stream_copy_gbs": copy / 1e9}
+
+
+def run(workload: str, steps: int, warmup: int, with_cpu: bool, cache: str = "warm", peaks=None):
     import torch
     from paper_2510_15964_amd import lx
     from util import dev
@@ -399,10 +441,16 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     lx.lx_ffn_set_token_tiles_per_workgroup(f.get("tiles_per_wg", 0))   # 0 = the library chooses
     Wu, Wd = dev(f["W_up"], f["dtype"]), dev(f["W_down"], f["dtype"])
     Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)            # one-time repack of frozen weights
+    wsets = [(Wu, Wd, Wut, Wdt)]
+    if cache == "cold":
+        # rotate among copies of the frozen weights that together exceed the 256 MB of cache
+        # behind the fabric (at least three), so that no step finds its weights there
+        one = sum(t.numel() * t.element_size() for t in wsets[0])
+        while len(wsets) < 3 or len(wsets) * one <= (256 << 20):
+            wsets.append(tuple(t.clone() for t in wsets[0]))
     Tt = f["mask"].shape[0]
     per = Tt // ffn_calls
-    ffn_jobs = [FfnJob(lx, torch, f, (i * per, (i + 1) * per), Wu, Wd, Wut, Wdt)
-                for i in range(ffn_calls)]
+    ffn_jobs = [FfnJob(lx, torch, f, (i * per, (i + 1) * per), wsets) for i in range(ffn_calls)]
     attn = AttnJob(lx, torch, a)
     tokens = a["B"] * a["S"]
     assert tokens == f["T"], "FFN and attention halves cover the same tokens"
@@ -422,10 +470,13 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
         side = torch.cuda.Stream()
         ev_lists = torch.cuda.Event()
         ev_done = [torch.cuda.Event() for _ in ffn_jobs]
+    counter = [0]
 
     def step():
         for j in ffn_jobs:
+            j.wsel = counter[0] % len(wsets)
             j.predict()
+        counter[0] += 1
         lx.lx_mask_compact_batch(cb)
         attn.combine()
         if overlap:
@@ -477,6 +528,17 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     dom_ms, dom_n = lx.lx_profile_end()
     dom_avg_s = dom_ms / max(dom_n, 1) * 1e-3
 
+    # spread of single steps: a second pass of `steps` steps, each bracketed by a pair of events on
+    # the launch stream (outside the timed region above, whose figure is the mean)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+
     ms_per_step = elapsed / steps * 1e3
     flops_step = sum(model[k][0] * model[k][1] for k in model)
     _, fl, by = model[dom]
@@ -484,11 +546,17 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     if t_mfma >= t_hbm:
         roof = {"bound": "mfma", "achieved": fl / dom_avg_s / 1e12, "peak": PEAK_MFMA_BF16 / 1e12,
                 "unit": "TFLOP/s"}
+        measured_peak = peaks["mfma_bf16_tflops"] if peaks else None
     else:
         roof = {"bound": "hbm", "achieved": by / dom_avg_s / 1e9, "peak": PEAK_HBM / 1e9,
                 "unit": "GB/s"}
+        measured_peak = peaks["stream_copy_gbs"] if peaks else None
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = measured_traffic(workload, lx.KERNEL_NAMES[dom])
+    if measured_peak:
+        roof["measured_peak"] = measured_peak            # the library's probe, same unit as `peak`
+        roof["frac_of_measured"] = roof["achieved"] / measured_peak
+    roof["traffic"], roof["traffic_measured_at_commit"] = measured_traffic(workload, lx.KERNEL_NAMES[dom])
+    roof["algorithmic_bytes"] = by
     roof["kernel"] = lx.KERNEL_NAMES[dom]
     roof["avg_launch_us"] = dom_avg_s * 1e6
     roof["launches_timed"] = dom_n
@@ -502,15 +570,20 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
     att_fl = flops_step - ffn_fl
     out = {
         "metric": METRIC, "value": tokens * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
-        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": per_step_ms[len(per_step_ms) // 2], "ms_per_step_min": per_step_ms[0],
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": f["dtype"], "data": "synthetic",
+        "cache": cache,
         "config": {
             "workload": workload, "tokens_per_step": tokens,
             "ffn": {"T_per_call": ffn_jobs[0].T, "calls": ffn_calls, "d": f["d"], "F": f["F"],
                     "block": "64x64", "block_density": float(f["mask"].mean()),
                     "active_blocks": int(f["mask"].sum()),
                     "list_rows_per_call": ffn_jobs[0].bl.rows,
-                    "token_tiles_per_workgroup": f.get("tiles_per_wg", 0) or "auto"},
+                    "token_tiles_per_workgroup": f.get("tiles_per_wg", 0) or "auto",
+                    "weight_sets": len(wsets),
+                    "weight_bytes_all_sets": len(wsets) * sum(t.numel() * t.element_size() for t in wsets[0])},
             "attn": {"B": a["B"], "heads": a["Hh"], "active_heads": attn.h_act, "S": a["S"],
                      "D": a["D"], "causal": bool(a["causal"]),
                      "block_density_in_causal_region": attn.density,
@@ -518,6 +591,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
                      **({"mask_source": "pattern pool, combined on the device every step"}
                         if attn.pool is not None else {})},
         },
+        "launches_per_step": int(sum(model[k][0] for k in model)),
         "active_tflops": flops_step / (elapsed / steps) / 1e12,
         "mfma_util_active_flops": flops_step / (elapsed / steps) / PEAK_MFMA_BF16,
         "ffn": {"ms_per_step_kernels": ffn_ms, "active_tflops": ffn_fl / (ffn_ms * 1e-3) / 1e12,
@@ -528,9 +602,32 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool):
                                   for k, v in per_kernel.items()},
         "roofline": roof,
     }
+    if peaks:
+        out["measured_peaks"] = peaks
+        out["mfma_util_active_flops_of_measured"] = (flops_step / (elapsed / steps) / 1e12
+                                                     / peaks["mfma_bf16_tflops"])
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(f, a)
     lx.lx_ffn_set_token_tiles_per_workgroup(0)
+    return out
+
+
+def density_efficiency(results):
+    """E(rho) = rho * t(dense) / t(rho) from whole-step times of configs[4] workloads (Sec. VII-C:
+    operator time against density): `results` maps workload name -> ms per step.  Two references:
+    the dense PATH (rho = 1 with one list for all token tiles and four token tiles per workgroup,
+    what a dense layer would run) and the sparse kernels themselves at rho = 1."""
+    dense_path = results.get("config5:1.0:shared")
+    dense_lists = results.get("config5:1.0")
+    out = {}
+    for wl, ms in results.items():
+        rho = float(wl.split(":")[1])
+        e = {"ms_per_step": ms}
+        if dense_path:
+            e["E_vs_dense_path"] = rho * dense_path / ms
+        if dense_lists:
+            e["E_vs_per_tile_lists_at_100pct"] = rho * dense_lists / ms
+        out[wl] = e
     return out
 
 
@@ -539,11 +636,17 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="opt1.3b_layer",
-                    help="opt1.3b_layer (default) | opt1.3b_layer_shared | opt1.3b_layer_patterns | "
-                         "opt1.3b_layer_lora | opt1.3b_layer_f16 | opt1.3b_layer_onecall | opt1.3b_layer_hostw | "
-                         "config4 | config5:RHO")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD,
+                    help="opt1.3b_layer (default) | opt1.3b_layer_twocalls | opt1.3b_layer_shared | "
+                         "opt1.3b_layer_patterns | opt1.3b_layer_lora | opt1.3b_layer_f16 | "
+                         "opt1.3b_layer_hostw | config4 | config5:RHO[:shared]")
+    ap.add_argument("--cache", choices=("warm", "cold"), default="warm",
+                    help="cold: every step uses another of several copies of the frozen weights "
+                         "(more than 256 MB in total), so that none is found in cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the legs next to the headline: measured peaks, the cache-cold "
+                         "variant and the density-efficiency runs of configs[4]")
     ap.add_argument("--sweep", metavar="FILE", default=None,
                     help="also run the configs[4] density sweep, one JSON line per density into FILE")
     args = ap.parse_args()
@@ -556,21 +659,50 @@ def main():
         __graft_entry__.build()
     from oracle import build as oracle_build
     oracle_build.build(force=False)
-    res = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    peaks = None
+    if not args.no_extras:
+        import torch
+        from paper_2510_15964_amd import lx
+        torch.cuda.set_device(0)
+        peaks = measure_peaks(lx, torch)
+        log(f"measured peaks: {peaks}")
+    res = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, args.cache, peaks)
+    if not args.no_extras:
+        if args.cache == "warm":
+            cold = run(args.workload, max(args.steps // 2, 5), 2, False, "cold", peaks)
+            res["cache_cold"] = {k: cold[k] for k in ("value", "ms_per_step", "ms_per_step_median",
+                                                      "ms_per_step_min")}
+            res["cache_cold"]["weight_bytes_all_sets"] = cold["config"]["ffn"]["weight_bytes_all_sets"]
+            res["cache_cold"]["roofline_frac"] = cold["roofline"]["frac"]
+            log(f"cache-cold: {cold['ms_per_step']:.3f} ms/step")
+        # density efficiency at the benchmark spec's 10 % and 30 % (configs[4] shapes), short runs
+        ms = {}
+        for wl in ("config5:1.0:shared", "config5:0.1", "config5:0.3", "config5:0.1:shared",
+                   "config5:0.3:shared"):
+            r = run(wl, 5, 2, False)
+            ms[wl] = r["ms_per_step"]
+            log(f"{wl}: {r['ms_per_step']:.3f} ms/step, FFN at {100 * r['ffn']['mfma_util']:.1f} % of the MFMA peak")
+            if wl == "config5:1.0:shared":
+                res["dense_path"] = {"workload": wl, "ms_per_step": r["ms_per_step"],
+                                     "ffn_mfma_util": r["ffn"]["mfma_util"],
+                                     "ffn_active_tflops": r["ffn"]["active_tflops"]}
+        res["density_efficiency"] = density_efficiency(ms)
     if args.sweep:
         from paper_2510_15964_amd.inputs import DENSITY_SWEEP
         os.makedirs(os.path.dirname(os.path.abspath(args.sweep)), exist_ok=True)
+        # the densities with independent lists per token tile, then the paper's operating
+        # mode (one list per call for all its token tiles, Sec. V-A) at 10 %, 30 % and 100 %
+        lines = {}
+        for wl in [f"config5:{rho}" for rho in DENSITY_SWEEP] + [
+                "config5:0.1:shared", "config5:0.3:shared", "config5:1.0:shared"]:
+            r = run(wl, max(args.steps // 5, 5), 2, False, "warm", peaks)
+            log(f"{wl}: {r['ms_per_step']:.3f} ms/step, {r['active_tflops']:.1f} active TFLOP/s")
+            lines[wl] = r
+        eff = density_efficiency({wl: r["ms_per_step"] for wl, r in lines.items()})
         with open(args.sweep, "w") as fh:
-            # the densities with independent lists per token tile, then the paper's operating
-            # mode (one list per call for all its token tiles, Sec. V-A) at 10 %, 30 % and 100 %
-            for wl in [f"config5:{rho}" for rho in DENSITY_SWEEP] + [
-                    "config5:0.1:shared", "config5:0.3:shared", "config5:1.0:shared"]:
-                rho = wl.split(":", 1)[1]
-                r = run(wl, max(args.steps // 5, 5), 2, False)
-                log(f"config5 rho={rho}: {r['ms_per_step']:.3f} ms/step, "
-                    f"{r['active_tflops']:.1f} active TFLOP/s")
+            for wl, r in lines.items():
+                r["density_efficiency"] = eff[wl]
                 fh.write(json.dumps(r) + "\n")
-                fh.flush()
     print(json.dumps(res), flush=True)
 
 

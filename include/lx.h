@@ -71,6 +71,12 @@ typedef enum { LX_F32 = 0, LX_BF16 = 1, LX_F16 = 2 } lx_dtype;
  * than nnz_cap (a bound that was too small), every call ignores the entries
  * after the first nnz_cap in list order: the results are those of the
  * truncated list and nothing outside the stated buffers is read or written.
+ * (The attention backward call takes two lists of the same mask; each is
+ * truncated by itself, so dQ and dK/dV then belong to different truncations:
+ * give both lists the capacity of the mask's true block count.)
+ *
+ * Setting the environment variable LX_LOG=1 makes every entry point that
+ * enqueues work print one line with its name, sizes and status to stderr.
  */
 typedef struct {
   int32_t rows;
@@ -400,14 +406,30 @@ lx_status lx_profile_begin(int32_t kernel, int32_t max_launches);
 lx_status lx_profile_end(float* total_ms, int32_t* launches);
 
 /*
+ * Measurement aids for benchmarks (no part of the operators of Sec. VI): what the chip sustains
+ * on the two resources the operators are priced against, so that fractions of a MEASURED peak
+ * can be stated next to fractions of the data-sheet one.  Both only enqueue one kernel on
+ * `stream`; the caller times it (HIP events on that stream).
+ *   lx_probe_mfma_rate    every wavefront of a chip-filling launch issues `iters` rounds of eight
+ *                         independent 32x32x16 bf16 MFMAs on registers; *flops (HOST, out) = the
+ *                         FLOP of the launch; sink: DEVICE float[1], never written in practice.
+ *   lx_probe_stream_copy  dst[0..bytes) = src[0..bytes) with 16-byte accesses (bytes % 16 == 0,
+ *                         both pointers 16-byte aligned, buffers must not overlap): the launch
+ *                         moves 2 * bytes.
+ * Errors: INVALID_ARG for null pointers, iters outside 1 .. 2^24, sizes or alignment as stated.
+ */
+lx_status lx_probe_mfma_rate(int32_t iters, float* sink, double* flops, void* stream);
+lx_status lx_probe_stream_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/*
  * Tuning knob of the attention kernels (Sec. VI-A leaves the launch shape open).
  * A workgroup walks the block lists of `rows` rows of the mask (query blocks in
  * the forward and dQ kernels, key blocks in the dK/dV kernel) of one (batch,
  * head) as one stream of blocks.  rows = 0 (the default) lets the library
- * choose from the problem size; 1..8 fixes it for all later calls of this
- * process.  Results do not depend on it: it changes neither the arithmetic of
- * a row nor its order.  Not thread-safe; returns LX_ERR_INVALID_ARG outside
- * 0..8.
+ * choose from the problem size; 1..8 fixes it for all later calls of the
+ * calling host thread (the setting is per thread: concurrent callers on other
+ * threads keep theirs).  Results do not depend on it: it changes neither the
+ * arithmetic of a row nor its order.  Returns LX_ERR_INVALID_ARG outside 0..8.
  */
 lx_status lx_attn_set_rows_per_workgroup(int32_t rows);
 
@@ -420,10 +442,10 @@ lx_status lx_attn_set_rows_per_workgroup(int32_t rows);
  * lose where one tile per workgroup just fills the chip.  tiles = 0 (the
  * default) lets the library choose (more than one only when the groups alone
  * outnumber the CUs); 1, 2 or 4 asks for at most that many for all later calls
- * of this process (the library falls back to 2 or 1 where the list rows are not
- * shared accordingly, and always uses 1 in the LoRA calls).  Results are
- * bit-identical for every value.  Not thread-safe; returns LX_ERR_INVALID_ARG
- * for other values.
+ * of the calling host thread (per-thread setting; the library falls back to 2
+ * or 1 where the list rows are not shared accordingly, and always uses 1 in the
+ * LoRA calls).  Results are bit-identical for every value.  Returns
+ * LX_ERR_INVALID_ARG for other values.
  */
 lx_status lx_ffn_set_token_tiles_per_workgroup(int32_t tiles);
 

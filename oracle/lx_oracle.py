@@ -19,7 +19,10 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        if os.environ.get("LX_ORACLE_SANITIZED") == "1":     # the ASan + UBSan build (CPU tests)
+            path = _build.build_sanitized(force=False)
+        else:
+            path = _build.build(force=False)
         _lib = C.CDLL(path)
     return _lib
 

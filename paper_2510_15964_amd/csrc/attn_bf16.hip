@@ -907,7 +907,7 @@ __global__ __launch_bounds__(kAT, D == 64 ? kDkvOcc64 : (WHICH == 0 ? 1 : 2)) vo
 // Rows per workgroup: the smallest count with which all workgroups of the launch are resident at
 // once on the chip's `slots` workgroup slots (a causal mask keeps the groups balanced for every
 // count, because slots are filled in pairs k, 2G-1-k), unless the caller fixed the number.
-static int g_rows_per_wg = 0;
+static thread_local int g_rows_per_wg = 0;   // one value per host thread
 hipError_t set_attn_rows_per_wg(int r) {
   if (r < 0 || r > kRMax) return hipErrorInvalidValue;
   g_rows_per_wg = r;

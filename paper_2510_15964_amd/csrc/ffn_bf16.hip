@@ -115,14 +115,17 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[kNI][2]) {
 // tile) and W2 [F,64] (rows of the listed blocks): acc += A2_i W2_j^T, the low-rank branch
 // z = W x + B (A x) of Sec. II-C with A2 = X A^T computed beforehand and W2 = B, both padded to
 // rank 64.
-template <int DT, int MODE, bool LORA>
-__global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
+// NST: stages of the transfer ring.  Three stages leave room for one workgroup per CU, two for two:
+// the launcher takes two when the items are more than one but at most two per CU, so that all
+// of them are resident at once instead of running as a full round and a partly filled one.
+template <int DT, int MODE, bool LORA, int NST = kSddStages>
+__global__ __launch_bounds__(kThreads, NST == 2 ? 2 : 1) void ffn_sdd_bf16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int rows, int gt, int K, int nnz_cap,
     uint16_t* __restrict__ out_act, const uint16_t* __restrict__ gate_act,
     const uint16_t* __restrict__ A2, const uint16_t* __restrict__ W2) {
-  __shared__ __attribute__((aligned(1024))) uint16_t ring[kSddStages * kStageElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t ring[NST * kStageElems];
   int i, chunk;
   if (!find_work(row_ptr, rows, gt, blockIdx.x, 4, nnz_cap, i, chunk)) return;
   const int rs = row_ptr[i / gt], n_i = row_ptr[i / gt + 1] - rs;
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(kThreads) void ffn_sdd_bf16(
   zero_acc(acc);
   const int blk_w = kNI * wave / 2;          // list entry (of the four) this wave works on
   const int ksteps = K / kBK;
-  run_ring<DT, kSddStages>(ksteps + (LORA ? 1 : 0), blk_w < nb, src, src2,
+  run_ring<DT, NST>(ksteps + (LORA ? 1 : 0), blk_w < nb, src, src2,
                        [=](int s, long long& ob, long long& oa) {
                          const bool alt = LORA && s == ksteps;
                          ob = oa = alt ? 0 : (long long)s * kBK;
@@ -534,8 +537,9 @@ static dim3 sdd_grid(int Tt, int gt, int nnz_cap) {
   return dim3(8 * 8 * ((Lub + 7) / 8));
 }
 
-// Token tiles per workgroup: 0 = chosen here; 1, 2 or 4 = asked for by the caller.
-static int g_ffn_tiles_per_wg = 0;
+// Token tiles per workgroup: 0 = chosen here; 1, 2 or 4 = asked for by the caller.  One value
+// per host thread: a thread that sets the knob changes its own later calls only.
+static thread_local int g_ffn_tiles_per_wg = 0;
 hipError_t set_ffn_tiles_per_wg(int n) {
   if (n != 0 && n != 1 && n != 2 && n != 4) return hipErrorInvalidValue;
   g_ffn_tiles_per_wg = n;
@@ -616,11 +620,20 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
   }
   const dim3 g1 = sdd_grid(Tt, gt, nnz_cap);
   const uint16_t* none = nullptr;
+  // more than one item per CU but at most two: two resident workgroups of two stages each
+  const long long items_ub = ((long long)nnz_cap * gt + 3) / 4 + Tt;
+  const bool two_resident = items_ub > kCUs && items_ub <= 2 * kCUs;
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
-    if (pass == 0)
+    if (pass == 0 && two_resident)
+      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false, 2>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+    else if (pass == 0)
       hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+    else if (two_resident)
+      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false, 2>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
+                         col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
     else
       hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
                          col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);

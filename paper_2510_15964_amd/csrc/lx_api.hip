@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstdio>
+#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -35,6 +37,22 @@ static void prof_clear() {
   g_prof_id = -1;
   g_prof_n = 0;
 }
+
+// LX_LOG=1: one line per call on stderr (read once; any other value: silent)
+static bool log_on() {
+  static const bool on = [] {
+    const char* v = std::getenv("LX_LOG");
+    return v && v[0] == '1';
+  }();
+  return on;
+}
+#define LX_LOGF(...)                          \
+  do {                                        \
+    if (log_on()) {                           \
+      std::fprintf(stderr, "[lx] " __VA_ARGS__); \
+      std::fputc('\n', stderr);               \
+    }                                         \
+  } while (0)
 
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -148,6 +166,20 @@ lx_status lx_profile_end(float* total_ms, int32_t* launches) {
   return rc;
 }
 
+lx_status lx_probe_mfma_rate(int32_t iters, float* sink, double* flops, void* stream) {
+  if (iters <= 0 || iters > (1 << 24) || !sink || !flops) return LX_ERR_INVALID_ARG;
+  *flops = probe_mfma_flops(iters);
+  return launch_probe_mfma(iters, sink, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+}
+
+lx_status lx_probe_stream_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst || bytes == 0 || bytes % 16 != 0 || !aligned16(src) || !aligned16(dst))
+    return LX_ERR_INVALID_ARG;
+  return launch_probe_copy(src, dst, (long long)(bytes / 16), (hipStream_t)stream) == hipSuccess
+             ? LX_OK
+             : LX_ERR_RUNTIME;
+}
+
 lx_status lx_attn_set_rows_per_workgroup(int32_t rows) {
   return set_attn_rows_per_wg(rows) == hipSuccess ? LX_OK : LX_ERR_INVALID_ARG;
 }
@@ -156,7 +188,7 @@ lx_status lx_ffn_set_token_tiles_per_workgroup(int32_t tiles) {
   return set_ffn_tiles_per_wg(tiles) == hipSuccess ? LX_OK : LX_ERR_INVALID_ARG;
 }
 
-lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
+static lx_status mask_compact_impl(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols,
                           int64_t batch_stride, int64_t row_stride, int64_t col_stride,
                           int32_t* row_ptr, int32_t* col_idx, int32_t col_idx_cap, void* stream) {
   if (!mask || !row_ptr || !col_idx) return LX_ERR_INVALID_ARG;
@@ -183,7 +215,7 @@ lx_status lx_mask_compact_pair(const uint8_t* mask, int32_t batch, int32_t rows,
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
-lx_status lx_mask_compact_batch(const lx_compact_job* jobs, int32_t n_jobs, void* stream) {
+static lx_status mask_compact_batch_impl(const lx_compact_job* jobs, int32_t n_jobs, void* stream) {
   if (!jobs || n_jobs <= 0 || n_jobs > 8) return LX_ERR_INVALID_ARG;
   CompactJob cj[8];
   for (int i = 0; i < n_jobs; ++i) {
@@ -289,7 +321,7 @@ size_t lx_sparse_ffn_bwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int3
   return b;
 }
 
-lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+static lx_status ffn_fwd_impl(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
                             int32_t blk_n, const void* X, const void* W_up, const void* b_up,
                             const void* W_down, const void* b_down, const lx_blocklist* bl,
                             void* Y, void* H_act, void* workspace, size_t workspace_bytes,
@@ -321,7 +353,7 @@ lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
-lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
+static lx_status ffn_bwd_dx_impl(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t,
                                int32_t blk_n, const void* dY, const void* H_act,
                                const void* W_up, const void* W_down, const void* W_up_t,
                                const void* W_down_t, const lx_blocklist* bl, void* dX,
@@ -495,7 +527,7 @@ static lx_status check_attn(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32
   return LX_OK;
 }
 
-lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+static lx_status attn_fwd_impl(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                              float scale, int32_t causal, const void* Q, const void* K,
                              const void* V, const int64_t strides_bhs[3],
                              const lx_blocklist* bl, int32_t mask_batch,
@@ -551,7 +583,7 @@ static lx_status attn_bwd_run(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int
   return launch_attn_bwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
-lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+static lx_status attn_bwd_dx_impl(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                                 float scale, int32_t causal, const void* Q, const void* K,
                                 const void* V, const void* O, const float* LSE, const void* dO,
                                 const int64_t strides_bhs[3], const lx_blocklist* bl_rows,
@@ -570,7 +602,7 @@ lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, i
                       bl_cols, mask_batch, head_active, dQ, dK, dV, delta, neg_lse2, stream);
 }
 
-lx_status lx_sparse_attn_bwd_dx_noalloc(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
+static lx_status attn_bwd_dx_noalloc_impl(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                                         float scale, int32_t causal, const void* Q, const void* K,
                                         const void* V, const void* O, const float* LSE,
                                         const void* dO, const int64_t strides_bhs[3],
@@ -592,6 +624,48 @@ lx_status lx_sparse_attn_bwd_dx_noalloc(lx_dtype dt, int32_t B, int32_t Hh, int3
   return attn_bwd_run(dt, B, Hh, S, D, scale, causal, Q, K, V, O, LSE, dO, strides_bhs, bl_rows,
                       bl_cols, mask_batch, head_active, dQ, dK, dV, scratch, scratch + kScratchRows,
                       stream);
+}
+
+lx_status lx_sparse_ffn_fwd(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t, int32_t blk_n, const void* X, const void* W_up, const void* b_up, const void* W_down, const void* b_down, const lx_blocklist* bl, void* Y, void* H_act, void* workspace, size_t workspace_bytes, void* stream) {
+  const lx_status s = ffn_fwd_impl(dt, T, d, F, tile_t, blk_n, X, W_up, b_up, W_down, b_down, bl, Y, H_act, workspace, workspace_bytes, stream);
+  LX_LOGF("lx_sparse_ffn_fwd dt=%d T=%d d=%d F=%d tile=%dx%d list rows=%d nnz_cap=%d ws=%zu -> %s", (int)dt, T, d, F, tile_t, blk_n, bl ? bl->rows : -1, bl ? bl->nnz_cap : -1, workspace_bytes, lx_status_string(s));
+  return s;
+}
+
+lx_status lx_sparse_ffn_bwd_dx(lx_dtype dt, int32_t T, int32_t d, int32_t F, int32_t tile_t, int32_t blk_n, const void* dY, const void* H_act, const void* W_up, const void* W_down, const void* W_up_t, const void* W_down_t, const lx_blocklist* bl, void* dX, void* workspace, size_t workspace_bytes, void* stream) {
+  const lx_status s = ffn_bwd_dx_impl(dt, T, d, F, tile_t, blk_n, dY, H_act, W_up, W_down, W_up_t, W_down_t, bl, dX, workspace, workspace_bytes, stream);
+  LX_LOGF("lx_sparse_ffn_bwd_dx dt=%d T=%d d=%d F=%d tile=%dx%d list rows=%d nnz_cap=%d packed=%d ws=%zu -> %s", (int)dt, T, d, F, tile_t, blk_n, bl ? bl->rows : -1, bl ? bl->nnz_cap : -1, (int)(W_up_t && W_down_t), workspace_bytes, lx_status_string(s));
+  return s;
+}
+
+lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D, float scale, int32_t causal, const void* Q, const void* K, const void* V, const int64_t strides_bhs[3], const lx_blocklist* bl, int32_t mask_batch, const uint8_t* head_active, void* O, float* LSE, void* stream) {
+  const lx_status s = attn_fwd_impl(dt, B, Hh, S, D, scale, causal, Q, K, V, strides_bhs, bl, mask_batch, head_active, O, LSE, stream);
+  LX_LOGF("lx_sparse_attn_fwd dt=%d B=%d Hh=%d S=%d D=%d causal=%d mask_batch=%d nnz_cap=%d -> %s", (int)dt, B, Hh, S, D, causal, mask_batch, bl ? bl->nnz_cap : -1, lx_status_string(s));
+  return s;
+}
+
+lx_status lx_sparse_attn_bwd_dx(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D, float scale, int32_t causal, const void* Q, const void* K, const void* V, const void* O, const float* LSE, const void* dO, const int64_t strides_bhs[3], const lx_blocklist* bl_rows, const lx_blocklist* bl_cols, int32_t mask_batch, const uint8_t* head_active, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes, void* stream) {
+  const lx_status s = attn_bwd_dx_impl(dt, B, Hh, S, D, scale, causal, Q, K, V, O, LSE, dO, strides_bhs, bl_rows, bl_cols, mask_batch, head_active, dQ, dK, dV, workspace, workspace_bytes, stream);
+  LX_LOGF("lx_sparse_attn_bwd_dx dt=%d B=%d Hh=%d S=%d D=%d causal=%d mask_batch=%d ws=%zu -> %s", (int)dt, B, Hh, S, D, causal, mask_batch, workspace_bytes, lx_status_string(s));
+  return s;
+}
+
+lx_status lx_sparse_attn_bwd_dx_noalloc(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D, float scale, int32_t causal, const void* Q, const void* K, const void* V, const void* O, const float* LSE, const void* dO, const int64_t strides_bhs[3], const lx_blocklist* bl_rows, const lx_blocklist* bl_cols, int32_t mask_batch, const uint8_t* head_active, void* dQ, void* dK, void* dV, void* stream) {
+  const lx_status s = attn_bwd_dx_noalloc_impl(dt, B, Hh, S, D, scale, causal, Q, K, V, O, LSE, dO, strides_bhs, bl_rows, bl_cols, mask_batch, head_active, dQ, dK, dV, stream);
+  LX_LOGF("lx_sparse_attn_bwd_dx_noalloc dt=%d B=%d Hh=%d S=%d D=%d causal=%d mask_batch=%d -> %s", (int)dt, B, Hh, S, D, causal, mask_batch, lx_status_string(s));
+  return s;
+}
+
+lx_status lx_mask_compact_batch(const lx_compact_job* jobs, int32_t n_jobs, void* stream) {
+  const lx_status s = mask_compact_batch_impl(jobs, n_jobs, stream);
+  LX_LOGF("lx_mask_compact_batch jobs=%d -> %s", n_jobs, lx_status_string(s));
+  return s;
+}
+
+lx_status lx_mask_compact(const uint8_t* mask, int32_t batch, int32_t rows, int32_t cols, int64_t batch_stride, int64_t row_stride, int64_t col_stride, int32_t* row_ptr, int32_t* col_idx, int32_t col_idx_cap, void* stream) {
+  const lx_status s = mask_compact_impl(mask, batch, rows, cols, batch_stride, row_stride, col_stride, row_ptr, col_idx, col_idx_cap, stream);
+  LX_LOGF("lx_mask_compact batch=%d rows=%d cols=%d cap=%d -> %s", batch, rows, cols, col_idx_cap, lx_status_string(s));
+  return s;
 }
 
 }  // extern "C"

@@ -128,6 +128,10 @@ hipError_t launch_gather_blocks(const void* W, int Fb, long long block_bytes, co
                                 int* id_col_idx, hipStream_t stream);
 hipError_t launch_attn_fwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_bwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStream_t st);
+// measurement aids (probe.hip)
+hipError_t launch_probe_mfma(int iters, float* sink, hipStream_t st);
+double probe_mfma_flops(int iters);
+hipError_t launch_probe_copy(const void* src, void* dst, long long units16, hipStream_t st);
 hipError_t set_attn_rows_per_wg(int r);   // 0 = automatic
 hipError_t set_ffn_tiles_per_wg(int n);   // 0 = automatic, 1, 2
 

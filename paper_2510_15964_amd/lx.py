@@ -34,7 +34,7 @@ EXPORTS = (
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_sparse_attn_bwd_dx_noalloc", "lx_profile_begin", "lx_profile_end",
     "lx_attn_set_rows_per_workgroup", "lx_ffn_set_token_tiles_per_workgroup", "lx_mlp_predict_mask", "lx_attn_combine_patterns",
     "lx_sparse_ffn_lora_fwd_workspace_bytes", "lx_sparse_ffn_lora_bwd_workspace_bytes",
-    "lx_sparse_ffn_lora_fwd", "lx_sparse_ffn_lora_bwd",
+    "lx_sparse_ffn_lora_fwd", "lx_sparse_ffn_lora_bwd", "lx_probe_mfma_rate", "lx_probe_stream_copy",
 )
 (LX_K_COMPACT, LX_K_FFN_UP, LX_K_FFN_DOWN, LX_K_FFN_DH, LX_K_FFN_DX, LX_K_ATTN_FWD,
  LX_K_ATTN_BWD_DQ, LX_K_ATTN_BWD_DKV, LX_K_TRANSPOSE, LX_K_PREDICT, LX_K_COMBINE,
@@ -83,6 +83,8 @@ _lib.lx_sparse_attn_bwd_dx_noalloc.argtypes = [C.c_int, _i32, _i32, _i32, _i32, 
                                                _vp, _vp, _vp, C.POINTER(_i64), _blp, _blp, _i32, _vp,
                                                _vp, _vp, _vp, _vp]
 
+_lib.lx_probe_mfma_rate.argtypes = [_i32, _vp, C.POINTER(C.c_double), _vp]
+_lib.lx_probe_stream_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.lx_profile_begin.argtypes = [_i32, _i32]
 _lib.lx_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.lx_attn_set_rows_per_workgroup.argtypes = [_i32]
@@ -417,3 +419,18 @@ def lx_sparse_attn_bwd_dx_noalloc(Q, K, V, O, LSE, dO, bl_rows: BlockList, bl_co
                                               _ptr(dV), _stream()),
            "lx_sparse_attn_bwd_dx_noalloc")
     return dQ, dK, dV
+
+
+def lx_probe_mfma_rate(iters: int, sink: torch.Tensor) -> float:
+    """Enqueues the MFMA rate probe; returns the FLOP of the launch."""
+    fl = C.c_double(0.0)
+    _check(_lib.lx_probe_mfma_rate(iters, _ptr(sink), C.byref(fl), _stream()), "lx_probe_mfma_rate")
+    return fl.value
+
+
+def lx_probe_stream_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
+    """Enqueues the stream-copy probe; returns the bytes moved (read + written)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(_lib.lx_probe_stream_copy(_ptr(src), _ptr(dst), n, _stream()), "lx_probe_stream_copy")
+    return 2 * n
