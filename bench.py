@@ -10,20 +10,22 @@ outside it.
 Workloads (recipes in paper_2510_15964_amd/inputs.py):
   opt1.3b_layer   default.  An OPT-1.3B-shaped layer over 8 x 1024 tokens:
                   attention = configs[2] (30 % of causal blocks), FFN =
-                  configs[1] (planted ReLU support, ~10 % blocks) applied to the
-                  8192 tokens as two X[4096,2048] calls that share the weights.
-  opt1.3b_layer_shared    the same layer with the FFN masks predicted on the
+                  configs[1]'s shape and recipe (planted ReLU support, ~10 %
+                  blocks, a list per 64-token tile) applied to the 8192 tokens
+                  in one call: 8 kernel launches per step.
+  opt1.3b_layer_twocalls  the same layer with the FFN as two X[4096,2048] calls
+                  (configs[1]'s own token count) that share the weights: 12 launches.
+  The variants below keep the two-call FFN, the shape their parity tests cover:
+  opt1.3b_layer_shared    the FFN masks predicted on the
                   device every step (MLP predictor, one list for all tokens of
                   a call: the paper's operating point, Sec. V-A).
-  opt1.3b_layer_lora      the same layer with a LoRA branch (rank 16) on the FFN
+  opt1.3b_layer_lora      a LoRA branch (rank 16) on the FFN
                   up-projection, including the gradients of A and B (Sec. II-C/D).
-  opt1.3b_layer_f16       the same layer in IEEE half precision (fp16 operands,
+  opt1.3b_layer_f16       IEEE half precision (fp16 operands,
                   fp32 accumulation; the paper's parameter precision, Sec. VII-A).
-  opt1.3b_layer_patterns  the same layer with per-head attention patterns from
+  opt1.3b_layer_patterns  per-head attention patterns from
                   a pool, combined into the block lists on the device every
                   step (Sec. VI-A).
-  opt1.3b_layer_onecall   the same layer with the FFN applied to all 8192 tokens in
-                  one call instead of two calls of 4096.
   opt1.3b_layer_hostw     the shared-list layer with the FFN weights in pinned host memory:
                   every call moves the listed neuron blocks to the device first (Sec. VII-B);
                   opt1.3b_layer_hostw_overlap = the same with the transfers on a second stream
@@ -67,15 +69,17 @@ def log(*a):
 def make_workload(name: str):
     from paper_2510_15964_amd import inputs
     if name == "opt1.3b_layer":
-        f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
-        a = inputs.config3_attn()
-        ffn_calls = 2
-    elif name == "opt1.3b_layer_onecall":
-        # the default layer with the FFN applied to all 8192 tokens in ONE call instead of two
-        # calls of configs[1]'s 4096 tokens: twice as many token tiles share each XCD's L2
+        # attention = configs[2]; FFN = configs[1]'s shape and planted-support recipe over the
+        # layer's 8 x 1024 = 8192 tokens in ONE call (128 token tiles, a list per tile)
         f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
         a = inputs.config3_attn()
         ffn_calls = 1
+    elif name == "opt1.3b_layer_twocalls":
+        # the same layer with the FFN as two calls of configs[1]'s own 4096 tokens that share the
+        # frozen weights: four more launches per step, and half as many token tiles share an XCD's L2
+        f = inputs.ffn_planted_support(8192, 2048, 8192, 64, 64, 0.5, 4.0, seed=2000)
+        a = inputs.config3_attn()
+        ffn_calls = 2
     elif name == "opt1.3b_layer_shared":
         # the paper's own operating point (Sec. V-A): per FFN call ONE list of active neuron
         # blocks, predicted on the device from the call's tokens (scores, threshold, OR over
@@ -176,7 +180,11 @@ class FfnJob:
         self.dX = torch.empty_like(self.X)
         nb = lx.lx_sparse_ffn_bwd_workspace_bytes(lx_dtype(lx, self.dt), self.T, self.d, self.F, 64, 64,
                                                   max(self.nnz, 1), 1)
-        self.ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        # extra workspace with which the second product of a pass splits the lists of its last
+        # round of workgroups (one list row only; 0 bytes where the library would not split)
+        extra = lx.lx_sparse_ffn_split_workspace_bytes(lx_dtype(lx, self.dt), self.T, self.d, 64, self.bl_run)
+        self.ws = torch.empty(nb + extra, dtype=torch.uint8, device="cuda")
+        self.ws_fwd = torch.empty(extra, dtype=torch.uint8, device="cuda") if extra else None
         self.used = float((self.mask_h.sum(0) > 0).mean())     # fraction of neuron blocks touched
         self.hostw = bool(f.get("host_weights"))
         self.gathered = False
@@ -237,7 +245,8 @@ class FfnJob:
             lx.lx_sparse_ffn_bwd_dx(self.dY, self.H_act, self.Wu_c, self.Wd_c, self.cl, 64, 64, self.dX,
                                     self.ws, W_up_t=self.Wut_c, W_down_t=self.Wdt_c)
             return
-        lx.lx_sparse_ffn_fwd(self.X, self.Wu, self.Wd, self.bl_run, 64, 64, self.Y, self.H_act)
+        lx.lx_sparse_ffn_fwd(self.X, self.Wu, self.Wd, self.bl_run, 64, 64, self.Y, self.H_act,
+                             workspace=self.ws_fwd)
         lx.lx_sparse_ffn_bwd_dx(self.dY, self.H_act, self.Wu, self.Wd, self.bl_run, 64, 64, self.dX,
                                 self.ws, W_up_t=self.Wut, W_down_t=self.Wdt)
 
@@ -675,6 +684,14 @@ def main():
             res["cache_cold"]["weight_bytes_all_sets"] = cold["config"]["ffn"]["weight_bytes_all_sets"]
             res["cache_cold"]["roofline_frac"] = cold["roofline"]["frac"]
             log(f"cache-cold: {cold['ms_per_step']:.3f} ms/step")
+        if args.workload == DEFAULT_WORKLOAD:
+            # the same layer with the FFN as two calls of configs[1]'s own 4096 tokens
+            two = run("opt1.3b_layer_twocalls", max(args.steps // 2, 5), 2, False, "warm", peaks)
+            res["ffn_as_two_calls"] = {k: two[k] for k in ("value", "ms_per_step", "ms_per_step_median",
+                                                          "launches_per_step")}
+            res["ffn_as_two_calls"]["roofline"] = {k: two["roofline"][k] for k in ("kernel", "bound", "frac",
+                                                                                  "avg_launch_us")}
+            log(f"FFN as two calls of 4096 tokens: {two['ms_per_step']:.3f} ms/step")
         # density efficiency at the benchmark spec's 10 % and 30 % (configs[4] shapes), short runs
         ms = {}
         for wl in ("config5:1.0:shared", "config5:0.1", "config5:0.3", "config5:0.1:shared",

@@ -227,6 +227,22 @@ size_t lx_sparse_ffn_bwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int3
                                          int32_t have_packed);
 
 /*
+ * Optional extra workspace of the two FFN calls (16-bit types).  With ONE list row for all token
+ * tiles the second product of a pass (Y, dX) runs as (group of token tiles) x (256 output
+ * columns) units, all equally long; when they make whole rounds of workgroups plus a small rest,
+ * that rest would keep a fraction of the chip busy for a full round.  Given this many bytes
+ * BEYOND what lx_sparse_ffn_fwd_workspace_bytes / lx_sparse_ffn_bwd_workspace_bytes return (the
+ * same pointer, a larger workspace_bytes), the calls cut the lists of the rest's units into
+ * pieces that fill the last round and add the pieces' fp32 partial sums in a fixed order
+ * (reproducible; the outputs of those units then differ in the last bit from the unsplit sum).
+ * Returns 0 where no split would be made (several list rows, units that fill their rounds, lists
+ * whose bound bl->nnz_cap is too short to cut); a workspace without the extra bytes is always
+ * valid and gives the unsplit sums.
+ */
+size_t lx_sparse_ffn_split_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t tile_t,
+                                           const lx_blocklist* bl);
+
+/*
  * Sparse FFN forward (Sec. VI-B neuron-centric tiled products; forward
  * equations of Sec. II-C with ReLU).  For every listed (token tile i, neuron
  * block j):   H_ij = ReLU(X_i W_up[j,:]^T + b_up[j]);

@@ -73,8 +73,12 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   // workgroups that run at the same time come from different token tiles and, the lists being
   // sorted, from the same region of the neuron axis: the weight blocks that several tiles of
   // the XCD use are then fetched into its L2 once (with all blocks listed: once per eight tiles).
+  // (With more items than the 32 workgroups an XCD runs at a time the launch proceeds in rounds,
+  // and what matters is what ONE round touches: consecutive items then, i.e. a few tiles and
+  // their blocks per round, rather than every other item of all the XCD's tiles in each round --
+  // measured on 128 tiles in one call: 303 -> 250 MB fetched per launch.)
   const int q = (L + 7) / 8, slot = w / 8;
-  const int pos = (slot % 8) * q + slot / 8, work = (w % 8) * L + pos;
+  const int pos = L > 32 ? slot : (slot % 8) * q + slot / 8, work = (w % 8) * L + pos;
   if (slot >= 8 * q || pos >= L || work >= total) return false;
   int running = 0;
   for (int base = 0; base < rows; base += kWave) {
@@ -467,15 +471,35 @@ __global__ __launch_bounds__(kThreads) void ffn_dsdn_bf16(
     const uint16_t* __restrict__ bias, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int gt, int ncols_out, int nnz_cap,
     uint16_t* __restrict__ out, const uint16_t* __restrict__ act2,
-    const uint16_t* __restrict__ W2, int group0) {
+    const uint16_t* __restrict__ W2, int group0, int lin0, int nchunks, int ksplit,
+    float* __restrict__ part) {
   using St = MultiStage<TT>;
   __shared__ __attribute__((aligned(1024))) uint16_t ring[St::kStages * St::kElems];
-  // the launch covers the tile groups group0 .. group0 + gridDim.y - 1
-  const int i0 = TT * balanced_tile(row_ptr, group0, gridDim.y, gt / TT, nnz_cap, blockIdx.y, false,
-                                    reinterpret_cast<int*>(ring));
-  const int n0 = blockIdx.x * kRowsA;
-  const int rs = row_ptr[i0 / gt];
-  const int n_i = min(row_ptr[i0 / gt + 1], nnz_cap) - rs;   // <= 0: nothing within the capacity
+  // ksplit == 0: 2-D grid (column chunk, tile group), the launch covers the tile groups group0 ..
+  // group0 + gridDim.y - 1.  ksplit >= 1: 1-D grid over (unit, piece): unit lin0 + blockIdx.x /
+  // ksplit of the (tile group, column chunk) pairs numbered chunk-fastest, and piece blockIdx.x %
+  // ksplit of the unit's list; with `part` the accumulators go there as they are, fp32, for
+  // ffn_dsd_reduce to add the pieces of a unit in order (fills the chip when the units of the last
+  // round of workgroups are few).
+  int i0, n0, piece = 0;
+  if (ksplit == 0) {
+    i0 = TT * balanced_tile(row_ptr, group0, gridDim.y, gt / TT, nnz_cap, blockIdx.y, false,
+                            reinterpret_cast<int*>(ring));
+    n0 = blockIdx.x * kRowsA;
+  } else {
+    const int lin = lin0 + blockIdx.x / ksplit;
+    piece = blockIdx.x % ksplit;
+    i0 = TT * (lin / nchunks);
+    n0 = (lin % nchunks) * kRowsA;
+  }
+  const int rs0 = row_ptr[i0 / gt];
+  const int n_all = min(row_ptr[i0 / gt + 1], nnz_cap) - rs0;   // <= 0: nothing within the capacity
+  // this piece's range of the list (the whole list unless ksplit > 1)
+  const int nn = n_all > 0 ? n_all : 0;
+  const int s_lo = ksplit > 1 ? (int)((long long)nn * piece / ksplit) : 0;
+  const int s_hi = ksplit > 1 ? (int)((long long)nn * (piece + 1) / ksplit) : nn;
+  const int rs = rs0 + s_lo;
+  const int n_i = s_hi - s_lo;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int rg = wave % 4, th = wave / 4;        // 64 output columns of the 256, half of the tiles
   const bool wave_on = n0 + 64 * rg < ncols_out;
@@ -519,12 +543,75 @@ __global__ __launch_bounds__(kThreads) void ffn_dsdn_bf16(
         if (wave_on) mma_step64<DT, TT>(stage, rg, th, acc);
       });
   if (!wave_on) return;
+  if (part) {   // the piece's partial sums: [wave][accumulator][lane][16 registers] (ffn_dsd_reduce reads them the same way)
+    f32x4* dst = reinterpret_cast<f32x4*>(part + ((size_t)blockIdx.x * kFW + wave) * (2 * TT * 16) * kWave) + lane * 4;
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int y = 0; y < TT; ++y)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v4 = {acc[x][y][4 * q], acc[x][y][4 * q + 1], acc[x][y][4 * q + 2], acc[x][y][4 * q + 3]};
+          dst[(x * TT + y) * (kWave * 4) + q] = v4;
+        }
+    return;
+  }
   // ncols_out is a multiple of 64 (the host checks d % 64 == 0): a wave's 64 columns are all inside
   const int n = n0 + 64 * rg;
 #pragma unroll
   for (int t = 0; t < TT / 2; ++t)
     store_tile64<DT, 2, TT>(acc, t, out + (long long)(i0 + (TT / 2) * th + t) * 64 * ncols_out + n,
                             ncols_out, bias ? bias + n : nullptr, nullptr);
+}
+
+// Adds the ksplit pieces of each unit that ffn_dsdn_bf16 left in `part` (piece 0 first, fixed
+// order: reproducible) and writes the unit's tile like the kernel's own epilogue: workgroup
+// (b, t) is unit lin0 + b and the t-th token tile of each of the kernel's wavefronts; its threads
+// hold the same accumulator elements as in the kernel.
+template <int DT, int TT, int T>
+__device__ __forceinline__ void dsd_reduce_tile(const float* __restrict__ part, int ksplit, int wave,
+                                                int lane, uint16_t* __restrict__ out_tile, long long ld,
+                                                const uint16_t* __restrict__ bias) {
+  f32x16 acc[2][TT];       // only [.][2T], [.][2T + 1] are used
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < TT; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+  for (int p = 0; p < ksplit; ++p) {
+    const f32x4* src = reinterpret_cast<const f32x4*>(
+        part + (((size_t)blockIdx.x * ksplit + p) * kFW + wave) * (2 * TT * 16) * kWave) + lane * 4;
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v4 = src[(x * TT + 2 * T + ti) * (kWave * 4) + q];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[x][2 * T + ti][4 * q + e] += v4[e];
+        }
+  }
+  store_tile64<DT, 2, TT>(acc, T, out_tile, ld, bias, nullptr);
+}
+template <int DT, int TT>
+__global__ __launch_bounds__(kThreads) void ffn_dsd_reduce(const float* __restrict__ part, int ksplit,
+                                                           int lin0, int nchunks, int ncols_out,
+                                                           const uint16_t* __restrict__ bias,
+                                                           uint16_t* __restrict__ out) {
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int rg = wave % 4, th = wave / 4;
+  const int lin = lin0 + blockIdx.x, t = blockIdx.y;       // t < TT / 2
+  const int i0 = TT * (lin / nchunks), n0 = (lin % nchunks) * kRowsA;
+  if (n0 + 64 * rg >= ncols_out) return;
+  const int n = n0 + 64 * rg;
+  uint16_t* out_tile = out + (long long)(i0 + (TT / 2) * th + t) * 64 * ncols_out + n;
+  const uint16_t* b = bias ? bias + n : nullptr;
+  if (TT == 4 && t == 1)
+    dsd_reduce_tile<DT, TT, TT == 4 ? 1 : 0>(part, ksplit, wave, lane, out_tile, ncols_out, b);
+  else
+    dsd_reduce_tile<DT, TT, 0>(part, ksplit, wave, lane, out_tile, ncols_out, b);
 }
 
 // pass 0 (forward):  A = X,  W1 = W_up [F,d],     W2 = W_down [d,F], act_out = H_act, out = Y
@@ -557,11 +644,49 @@ static int tiles_per_wg(int Tt, int gt) {
   return 1;
 }
 
+// Floats one piece of a split dsd unit leaves in the partial-sum buffer (TT token tiles).
+static size_t dsd_piece_floats(int tt) { return (size_t)kFW * 2 * tt * 16 * kWave; }
+// How the multi-tile dsd launch is cut when its (tile group, column chunk) units make whole
+// rounds of workgroups plus a small rest: the rest's lists are split into `pieces` pieces each,
+// so that the last round fills the chip too, and the pieces are added afterwards.  pieces = 0:
+// no split (nothing to gain, one list row only, or the bound on the list is too short to cut).
+struct DsdSplit {
+  long long full;   // units that run whole
+  int rest;         // units whose list is split
+  int pieces;
+};
+static DsdSplit dsd_split(int Tt, int gt, int d, int tt, int nnz_cap) {
+  DsdSplit sp = {0, 0, 0};
+  const int chunks = (d + kRowsA - 1) / kRowsA;
+  const long long units = (long long)chunks * (Tt / tt);
+  const long long rest = units % kCUs;
+  if (gt != Tt || rest == 0 || rest * 5 >= kCUs * 3) return sp;      // one list row for all tiles only
+  const int pieces = (int)(kCUs / rest < 4 ? kCUs / rest : 4);
+  if (pieces < 2 || nnz_cap < 16 * pieces) return sp;
+  sp.full = units - rest;
+  sp.rest = (int)rest;
+  sp.pieces = pieces;
+  return sp;
+}
+// Bytes of partial sums the split needs for T tokens and d output columns with one list row of
+// at most nnz_cap entries, for the tile count the library would choose (0: no split).
+size_t ffn_dsd_split_bytes(int Tt, int d, int nnz_cap) {
+  size_t need = 0;
+  for (int tt = 4; tt > 1; tt /= 2) {
+    if (Tt % tt != 0) continue;
+    const DsdSplit sp = dsd_split(Tt, Tt, d, tt, nnz_cap);
+    const size_t b = (size_t)sp.rest * sp.pieces * dsd_piece_floats(tt) * sizeof(float);
+    need = b > need ? b : need;
+  }
+  return need;
+}
+
 template <int DT, int TT>
 static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t* A, const uint16_t* W1,
                          const uint16_t* b1, const uint16_t* W2, const uint16_t* b2,
                          const int* row_ptr, const int* col_idx, int nnz_cap, uint16_t* act_out,
-                         const uint16_t* act_gate, uint16_t* out, hipStream_t st) {
+                         const uint16_t* act_gate, uint16_t* out, float* part, size_t part_bytes,
+                         hipStream_t st) {
   const uint16_t* none = nullptr;
   const dim3 g1 = sdd_grid(Tt / TT, gt / TT, nnz_cap);
   {
@@ -582,17 +707,35 @@ static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t*
   // takes four, else the one-tile kernel (two workgroups per CU).
   const int chunks = (d + kRowsA - 1) / kRowsA;
   int groups = Tt / TT;
+  // With room for partial sums: the units of the whole rounds run as they are, the lists of the
+  // rest are cut into pieces that fill the last round, and the pieces are added in order.
+  const DsdSplit sp = dsd_split(Tt, gt, d, TT, nnz_cap);
+  if (part && sp.pieces > 0 &&
+      (size_t)sp.rest * sp.pieces * dsd_piece_floats(TT) * sizeof(float) <= part_bytes) {
+    float* nopart = nullptr;
+    if (sp.full > 0)
+      hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3((unsigned)sp.full), dim3(kThreads), 0, st,
+                         (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                         nnz_cap, out, none, none, 0, 0, chunks, 1, nopart);
+    hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3(sp.rest * sp.pieces), dim3(kThreads), 0, st,
+                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       nnz_cap, out, none, none, 0, (int)sp.full, chunks, sp.pieces, part);
+    hipLaunchKernelGGL((ffn_dsd_reduce<DT, TT>), dim3(sp.rest, TT / 2), dim3(kThreads), 0, st,
+                       (const float*)part, sp.pieces, (int)sp.full, chunks, d, b2, out);
+    return;
+  }
+  float* nopart = nullptr;
   const long long wgs = (long long)chunks * groups, rest = wgs % kCUs;
   if (wgs > kCUs && rest > 0 && rest * 5 < kCUs * 3) groups = (int)((wgs - rest) / chunks);
   if (groups > 0)
     hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3(chunks, groups), dim3(kThreads), 0, st,
                        (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
-                       nnz_cap, out, none, none, 0);
+                       nnz_cap, out, none, none, 0, 0, chunks, 0, nopart);
   const int left = Tt - groups * TT;   // a multiple of TT
   if (left > 0 && TT == 4)
     hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, 2>), dim3(chunks, left / 2), dim3(kThreads), 0, st,
                        (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
-                       nnz_cap, out, none, none, groups * TT / 2);
+                       nnz_cap, out, none, none, groups * TT / 2, 0, chunks, 0, nopart);
   else if (left > 0)
     hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3(chunks, left), dim3(kThreads), 0, st,
                        (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
@@ -604,25 +747,27 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
-                           hipStream_t st) {
+                           float* part, size_t part_bytes, hipStream_t st) {
   (void)Fb;
   if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
   const int tt = tiles_per_wg(Tt, gt);
   if (tt == 4) {
     launch_multi<DT, 4>(pass, Tt, gt, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap, act_out,
-                        act_gate, out, st);
+                        act_gate, out, part, part_bytes, st);
     return hipGetLastError();
   }
   if (tt == 2) {
     launch_multi<DT, 2>(pass, Tt, gt, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap, act_out,
-                        act_gate, out, st);
+                        act_gate, out, part, part_bytes, st);
     return hipGetLastError();
   }
   const dim3 g1 = sdd_grid(Tt, gt, nnz_cap);
   const uint16_t* none = nullptr;
   // more than one item per CU but at most two: two resident workgroups of two stages each
-  const long long items_ub = ((long long)nnz_cap * gt + 3) / 4 + Tt;
-  const bool two_resident = items_ub > kCUs && items_ub <= 2 * kCUs;
+  // (the item count is known on the device only; a list row of n entries makes ceil(n / 4) items,
+  // 3/8 of an item more than n / 4 on average, which is what the estimate adds per tile)
+  const long long items_est = ((long long)nnz_cap * gt + 3) / 4 + (3 * (long long)Tt + 7) / 8;
+  const bool two_resident = items_est > kCUs && items_est <= 2 * kCUs;
   {
     ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
     if (pass == 0 && two_resident)
@@ -734,9 +879,9 @@ hipError_t launch_ffn_bf16(int dt, int pass, int Tt, int gt, int Fb, int d, int 
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
-                           hipStream_t st) {
+                           float* part, size_t part_bytes, hipStream_t st) {
   return LX_BY_DT(launch_ffn_bf16_t, pass, Tt, gt, Fb, d, F, A, W1, b1, W2, b2, row_ptr, col_idx,
-                  nnz_cap, act_out, act_gate, out, st);
+                  nnz_cap, act_out, act_gate, out, part, part_bytes, st);
 }
 hipError_t launch_ffn_lora_fwd_bf16(int dt, int Tt, int gt, int d, int F, const uint16_t* X,
                                     const uint16_t* W_up, const uint16_t* A_pad,

@@ -312,6 +312,12 @@ size_t lx_sparse_ffn_fwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int3
   return have_h_act ? 0 : act_bytes(dt, tile_t, blk_n, nnz_cap);
 }
 
+size_t lx_sparse_ffn_split_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t tile_t,
+                                          const lx_blocklist* bl) {
+  if (!is16(dt) || T <= 0 || d <= 0 || tile_t != 64 || T % 64 != 0 || !bl || bl->rows != 1) return 0;
+  return ffn_dsd_split_bytes(T / 64, d, bl->nnz_cap);
+}
+
 size_t lx_sparse_ffn_bwd_workspace_bytes(lx_dtype dt, int32_t T, int32_t d, int32_t F,
                                          int32_t tile_t, int32_t blk_n, int32_t nnz_cap,
                                          int32_t have_packed) {
@@ -335,11 +341,16 @@ static lx_status ffn_fwd_impl(lx_dtype dt, int32_t T, int32_t d, int32_t F, int3
   const int gt = (T / tile_t) / bl->rows;     // token tiles per list row
   if ((int64_t)bl->nnz_cap * gt > (int64_t)1 << 30) return LX_ERR_INVALID_ARG;
   void* act = H_act;
+  size_t used = 0;
   if (!act) {
     const size_t need = lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, bl->nnz_cap * gt, 0);
     if (!workspace || workspace_bytes < need) return LX_ERR_WORKSPACE;
     act = workspace;
+    used = need;
   }
+  // whatever the workspace holds beyond that may take the partial sums of split lists
+  float* part = workspace && workspace_bytes > used ? (float*)((char*)workspace + used) : nullptr;
+  const size_t part_bytes = part ? workspace_bytes - used : 0;
   hipError_t e;
   if (dt == LX_F32)
     e = launch_ffn_f32(0, tile_t, T / tile_t, gt, bl->cols, d, F, (const float*)X, (const float*)W_up,
@@ -349,7 +360,7 @@ static lx_status ffn_fwd_impl(lx_dtype dt, int32_t T, int32_t d, int32_t F, int3
     e = launch_ffn_bf16(dt16(dt), 0, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)X, (const uint16_t*)W_up,
                         (const uint16_t*)b_up, (const uint16_t*)W_down, (const uint16_t*)b_down,
                         bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)act, nullptr, (uint16_t*)Y,
-                        (hipStream_t)stream);
+                        part, part_bytes, (hipStream_t)stream);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
@@ -384,7 +395,11 @@ static lx_status ffn_bwd_dx_impl(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
     if (launch_transpose((int)esize(dt), W_down, d, F, wdt, st) != hipSuccess) return LX_ERR_RUNTIME;
     W_up_t = wut;
     W_down_t = wdt;
+    ws += round256((size_t)d * F * esize(dt));
   }
+  // whatever the workspace holds beyond the query's size may take the partial sums of split lists
+  float* part = workspace_bytes > need ? (float*)((char*)workspace + need) : nullptr;
+  const size_t part_bytes = part ? workspace_bytes - need : 0;
   hipError_t e;
   if (dt == LX_F32)
     e = launch_ffn_f32(1, tile_t, T / tile_t, gt, bl->cols, d, F, (const float*)dY,
@@ -394,7 +409,7 @@ static lx_status ffn_bwd_dx_impl(lx_dtype dt, int32_t T, int32_t d, int32_t F, i
     e = launch_ffn_bf16(dt16(dt), 1, T / tile_t, gt, bl->cols, d, F, (const uint16_t*)dY,
                         (const uint16_t*)W_down_t, nullptr, (const uint16_t*)W_up_t, nullptr,
                         bl->row_ptr, bl->col_idx, bl->nnz_cap, (uint16_t*)dz, (const uint16_t*)H_act,
-                        (uint16_t*)dX, st);
+                        (uint16_t*)dX, part, part_bytes, st);
   return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 

@@ -74,7 +74,10 @@ hipError_t launch_ffn_bf16(int dt, int pass, int Tt, int gt, int Fb, int d, int 
                            const uint16_t* W1, const uint16_t* b1, const uint16_t* W2,
                            const uint16_t* b2, const int* row_ptr, const int* col_idx, int nnz_cap,
                            uint16_t* act_out, const uint16_t* act_gate, uint16_t* out,
-                           hipStream_t st);
+                           float* part, size_t part_bytes, hipStream_t st);
+// bytes of partial sums with which the second product of a pass, given ONE list row of at most
+// nnz_cap entries for all Tt token tiles, splits the lists of its last round of workgroups (0: never)
+size_t ffn_dsd_split_bytes(int Tt, int d, int nnz_cap);
 // Splits of the low-rank products of the LoRA branch over workgroups so that they fill the chip;
 // the partial sums are added in a fixed order.  U = X A^T: over K; dB: over ranges of token
 // tiles per neuron block; dA: over ranges of token tiles per 64-column chunk.

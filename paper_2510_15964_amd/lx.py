@@ -30,6 +30,7 @@ EXPORTS = (
     "lx_status_string", "lx_mask_compact", "lx_mask_compact_pair", "lx_mask_compact_batch", "lx_ffn_pack_weights",
     "lx_ffn_gather_weight_blocks",
     "lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes",
+    "lx_sparse_ffn_split_workspace_bytes",
     "lx_sparse_ffn_fwd", "lx_sparse_ffn_bwd_dx", "lx_sparse_attn_bwd_workspace_bytes",
     "lx_sparse_attn_fwd", "lx_sparse_attn_bwd_dx", "lx_sparse_attn_bwd_dx_noalloc", "lx_profile_begin", "lx_profile_end",
     "lx_attn_set_rows_per_workgroup", "lx_ffn_set_token_tiles_per_workgroup", "lx_mlp_predict_mask", "lx_attn_combine_patterns",
@@ -68,6 +69,8 @@ _lib.lx_ffn_gather_weight_blocks.argtypes = [C.c_int, _i32, _i32, _i32, _vp, _bl
 for _n in ("lx_sparse_ffn_fwd_workspace_bytes", "lx_sparse_ffn_bwd_workspace_bytes"):
     getattr(_lib, _n).restype = _sz
     getattr(_lib, _n).argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _i32, _i32]
+_lib.lx_sparse_ffn_split_workspace_bytes.restype = _sz
+_lib.lx_sparse_ffn_split_workspace_bytes.argtypes = [C.c_int, _i32, _i32, _i32, _blp]
 _lib.lx_sparse_attn_bwd_workspace_bytes.restype = _sz
 _lib.lx_sparse_attn_bwd_workspace_bytes.argtypes = [C.c_int, _i32, _i32, _i32, _i32]
 _lib.lx_sparse_ffn_fwd.argtypes = [C.c_int, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
@@ -276,6 +279,10 @@ def lx_sparse_ffn_fwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_
 
 def lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed) -> int:
     return _lib.lx_sparse_ffn_bwd_workspace_bytes(dt, T, d, F, tile_t, blk_n, nnz_cap, have_packed)
+
+
+def lx_sparse_ffn_split_workspace_bytes(dt, T, d, tile_t, bl: "BlockList") -> int:
+    return _lib.lx_sparse_ffn_split_workspace_bytes(dt, T, d, tile_t, C.byref(bl.c))
 
 
 def lx_sparse_ffn_lora_fwd_workspace_bytes(T, d) -> int:

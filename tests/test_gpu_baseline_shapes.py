@@ -43,10 +43,11 @@ def sample_tiles(mask, extra=()):
     return out
 
 
-def check_ffn_sampled(lx, oracle, c, tiles, rows, shared=False, tiles_per_wg=0, label=""):
+def check_ffn_sampled(lx, oracle, c, tiles, rows, shared=False, tiles_per_wg=0, label="", split=False):
     """Full-size forward and backward launches of workload `c`; the oracle on token rows `rows`
     (indices inside a tile) of each tile of `tiles`.  shared: one list row for all token tiles
-    (the mask rows are equal)."""
+    (the mask rows are equal).  split: both calls get the extra workspace with which the second
+    product of a pass splits the lists of its last round of workgroups.  Returns Y and dX."""
     import torch
     dt = c["dtype"]
     T, d, F = c["T"], c["d"], c["F"]
@@ -63,13 +64,16 @@ def check_ffn_sampled(lx, oracle, c, tiles, rows, shared=False, tiles_per_wg=0, 
     nblocks = max(int(lmask.sum()) * gt, 1)
     blr = lx.BlockList(bl.rows, bl.cols, bl.row_ptr, bl.col_idx, max(int(lmask.sum()), 1))
     Wut, Wdt = lx.lx_ffn_pack_weights(Wu, Wd)
+    extra = lx.lx_sparse_ffn_split_workspace_bytes(lx_dtype(lx, dt), T, d, 64, blr) if split else 0
+    assert not split or extra > 0, "this shape would not split"
     ws = torch.empty(lx.lx_sparse_ffn_bwd_workspace_bytes(lx_dtype(lx, dt), T, d, F, 64, 64, nblocks, 1)
-                     + 256, dtype=torch.uint8, device="cuda")
+                     + max(extra, 256), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(extra, dtype=torch.uint8, device="cuda") if split else None
     H_act = torch.full((nblocks * 4096 + 4096,), float("nan"), dtype=X.dtype, device="cuda")
     Y = torch.full_like(X, float("nan"))
     lx.lx_ffn_set_token_tiles_per_workgroup(tiles_per_wg)
     try:
-        lx.lx_sparse_ffn_fwd(X, Wu, Wd, blr, 64, 64, Y, H_act)
+        lx.lx_sparse_ffn_fwd(X, Wu, Wd, blr, 64, 64, Y, H_act, workspace=ws_f)
         torch.cuda.synchronize()
         assert torch.isnan(H_act[nblocks * 4096:]).all(), "wrote past the H_act buffer"
         assert not torch.isnan(H_act[:int(lmask.sum()) * gt * 4096]).any(), "a listed block was not written"
@@ -127,6 +131,7 @@ def check_ffn_sampled(lx, oracle, c, tiles, rows, shared=False, tiles_per_wg=0, 
     # tiles without a listed block are exactly zero
     for i in np.nonzero(mask.sum(1) == 0)[0]:
         assert not Yh[i * 64:(i + 1) * 64].any() and not dXh[i * 64:(i + 1) * 64].any()
+    return Yh, dXh
 
 
 ROWS8 = (0, 9, 18, 27, 36, 45, 54, 63)     # both 32-row halves, every residue of the lane groups
@@ -160,6 +165,37 @@ def test_config5_ffn_shared_list_four_tiles_per_workgroup(lx, oracle, rho, rows)
     c["mask"] = np.repeat(c["mask"][:1], c["mask"].shape[0], axis=0)
     check_ffn_sampled(lx, oracle, c, (0, 30, 63), rows, shared=True, tiles_per_wg=4,
                       label=f"config5 rho={rho} shared")
+
+
+def test_config5_dense_path_with_split_lists(lx, oracle):
+    """The benchmark's dense path (configs[4] at density 1, one list row, four token tiles per
+    workgroup) with the extra workspace: the 320 (tile group, column chunk) units of the second
+    product are 256 whole ones and 64 whose lists are cut into four pieces (fp32 partial sums
+    added in order).  Tiles 0 and 30 lie in the whole units, tile 63 in the split ones."""
+    c = inputs.config5_ffn(1.0)
+    check_ffn_sampled(lx, oracle, c, (0, 30, 63), (5, 58), shared=True, tiles_per_wg=4, split=True,
+                      label="config5 dense, split lists")
+
+
+def test_split_lists_against_unsplit(lx, oracle):
+    """One list row, 260 groups of four tiles x one column chunk = 256 whole units + 4 units cut
+    into four pieces: the whole units give the bits of the call without the extra workspace, the
+    split ones agree to rounding of the fp32 sums (and with the oracle on sampled rows)."""
+    Tt = 260 * 4
+    c = inputs.ffn_bernoulli(Tt * 64, 256, 6144, 64, 64, 1.0, 311, dtype="bf16", w_std=0.05)
+    c["mask"][:, ::7] = 0                         # 82 of 96 blocks listed, the same for every tile
+    tiles = (3, 1023, 1030, 1039)
+    Ys, dXs = check_ffn_sampled(lx, oracle, c, tiles, (0, 63), shared=True, tiles_per_wg=4, split=True,
+                                label="split")
+    Yu, dXu = check_ffn_sampled(lx, oracle, c, tiles, (0, 63), shared=True, tiles_per_wg=4, split=False,
+                                label="unsplit")
+    whole = slice(0, 256 * 4 * 64)
+    cut = slice(256 * 4 * 64, Tt * 64)
+    assert np.array_equal(Ys[whole], Yu[whole]) and np.array_equal(dXs[whole], dXu[whole])
+    for a, b in ((Ys[cut], Yu[cut]), (dXs[cut], dXu[cut])):
+        assert rel_err_max(a, b) <= 2.0 ** -7            # one bf16 rounding step at most
+        print("elements that differ between split and unsplit sums:", int(np.count_nonzero(a != b)),
+              "of", a.size, flush=True)
 
 
 @pytest.mark.parametrize("Tt,d,F,density,seed", [(128, 128, 1024, 0.3, 301), (192, 64, 640, 0.5, 302)])
