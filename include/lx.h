@@ -49,7 +49,7 @@ typedef enum {
  * Element type of the tensors of a call.  LX_BF16 and LX_F16 (IEEE half, the parameter
  * precision of Sec. VII-A) run the same kernels: 16-bit operands, products accumulated in
  * fp32, outputs rounded to nearest even; softmax statistics and the gradients of the LoRA
- * matrices are fp32 for both.  LX_F32 is the correctness configuration of the FFN.
+ * matrices are fp32 for both.  LX_F32 is the correctness configuration of the FFN and of attention.
  */
 typedef enum { LX_F32 = 0, LX_BF16 = 1, LX_F16 = 2 } lx_dtype;
 
@@ -361,7 +361,9 @@ size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, in
  *            mask_batch is 1 (mask shared over the batch, Sec. V-A) or B.
  *   head_active  uint8[Hh] or NULL (all heads active)
  *   LSE      out float32 [B,Hh,S] contiguous
- * Supported: LX_BF16 / LX_F16, D in {64, 128}, S % 64 == 0.
+ * Supported: LX_BF16 / LX_F16 / LX_F32, D in {64, 128}, S % 64 == 0.  LX_F32 (float tensors,
+ * fp32 arithmetic throughout) is the correctness configuration, like the fp32 FFN: plain
+ * multiply-adds, not tuned.
  */
 lx_status lx_sparse_attn_fwd(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                              float scale, int32_t causal, const void* Q, const void* K,

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblx_sparse.so")
 SOURCES = ["lx_api.hip", "compact.hip", "ffn_f32.hip", "ffn_bf16.hip", "predict_bf16.hip", "lora_bf16.hip",
-           "attn_bf16.hip", "probe.hip"]
+           "attn_bf16.hip", "attn_f32.hip", "probe.hip"]
 # -Wno-inline-asm: the DMA helpers name m0 (a register the compiler reserves) as clobbered, which
 # is the point, and clang warns about every such statement
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-inline-asm",

@@ -526,7 +526,7 @@ size_t lx_sparse_attn_bwd_workspace_bytes(lx_dtype dt, int32_t B, int32_t Hh, in
 
 static lx_status check_attn(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,
                             const int64_t strides[3], const lx_blocklist* bl, int32_t mask_batch) {
-  if (!is16(dt)) return LX_ERR_UNSUPPORTED;
+  if (!is16(dt) && dt != LX_F32) return LX_ERR_UNSUPPORTED;
   if (B <= 0 || Hh <= 0 || S <= 0 || D <= 0) return LX_ERR_INVALID_ARG;
   if (D != 64 && D != 128) return LX_ERR_UNSUPPORTED;
   if (S % 64 != 0) return LX_ERR_UNSUPPORTED;
@@ -558,7 +558,9 @@ static lx_status attn_fwd_impl(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, in
   a.row_ptr = bl->row_ptr; a.col_idx = bl->col_idx; a.nnz_cap = bl->nnz_cap;
   a.head_active = head_active;
   a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
-  return launch_attn_fwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+  const hipError_t e = dt == LX_F32 ? launch_attn_fwd_f32(D, B, a, (hipStream_t)stream)
+                                    : launch_attn_fwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
 // Shared by the two backward entry points: everything but where Delta and -LSE*log2(e) live.
@@ -595,7 +597,9 @@ static lx_status attn_bwd_run(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int
   a.crow_ptr = bl_cols->row_ptr; a.ccol_idx = bl_cols->col_idx; a.cnnz_cap = bl_cols->nnz_cap;
   a.head_active = head_active;
   a.Hh = Hh; a.S = S; a.mask_batch = mask_batch; a.causal = causal ? 1 : 0; a.scale = scale;
-  return launch_attn_bwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream) == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
+  const hipError_t e = dt == LX_F32 ? launch_attn_bwd_f32(D, B, a, (hipStream_t)stream)
+                                    : launch_attn_bwd_bf16(dt16(dt), D, B, a, (hipStream_t)stream);
+  return e == hipSuccess ? LX_OK : LX_ERR_RUNTIME;
 }
 
 static lx_status attn_bwd_dx_impl(lx_dtype dt, int32_t B, int32_t Hh, int32_t S, int32_t D,

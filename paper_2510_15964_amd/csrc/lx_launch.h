@@ -135,6 +135,9 @@ hipError_t launch_attn_bwd_bf16(int dt, int D, int B, const AttnArgs& a, hipStre
 hipError_t launch_probe_mfma(int iters, float* sink, hipStream_t st);
 double probe_mfma_flops(int iters);
 hipError_t launch_probe_copy(const void* src, void* dst, long long units16, hipStream_t st);
+// fp32 attention (attn_f32.hip): AttnArgs' tensor pointers then hold float tensors
+hipError_t launch_attn_fwd_f32(int D, int B, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_bwd_f32(int D, int B, const AttnArgs& a, hipStream_t st);
 hipError_t set_attn_rows_per_wg(int r);   // 0 = automatic
 hipError_t set_ffn_tiles_per_wg(int n);   // 0 = automatic, 1, 2
 

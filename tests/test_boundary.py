@@ -123,7 +123,8 @@ def test_attn_validation(lxmod):
         return f(dt, B, Hh, S, D, 0.125, 1, Q, FAKE, FAKE, strides, C.byref(blist), mb, None, FAKE,
                  FAKE, None)
 
-    assert call(dt=L.LX_F32) == L.LX_ERR_UNSUPPORTED
+    assert call(dt=7) == L.LX_ERR_UNSUPPORTED            # no such element type
+    assert call(dt=L.LX_F32, D=96) == L.LX_ERR_UNSUPPORTED
     assert call(D=96) == L.LX_ERR_UNSUPPORTED
     assert call(S=250) == L.LX_ERR_UNSUPPORTED
     assert call(Q=None) == L.LX_ERR_INVALID_ARG

@@ -81,7 +81,10 @@ def check(got, ref, label="", fro_from_emul=False, dtype="bf16"):
         assert np.isfinite(got[k]).all(), k
         assert errs[k] <= tol, (k, errs[k])
         assert fro[k] <= fro_gate[k], (k, fro[k])
-        assert_within_emulated(got[k], ref[k], [e[k] for e in emul], k)
+        if dtype == "f32":               # fp32 meets the element-wise gate as it stands
+            assert floor[k] <= tol, (k, floor[k])
+        else:                            # 16-bit: against the ideal 16-bit pipeline on this input
+            assert_within_emulated(got[k], ref[k], [e[k] for e in emul], k)
     assert errs["LSE"] <= tol        # absolute, natural-log units
     # rows with no allowed key: exact zeros
     assert not got["O"][ninf].any() and not got["dQ"][ninf].any()
@@ -259,3 +262,34 @@ def test_blocks_above_the_diagonal_of_a_causal_mask(lx, oracle, D):
     ref = run_oracle(oracle, c)
     assert np.isneginf(ref["LSE"][:, 1, :64]).all()
     check(run_gpu(lx, c), ref, f"blocks above the diagonal, D={D}")
+
+
+@pytest.mark.parametrize("kw,seed", [
+    (dict(B=2, Hh=3, S=256, D=64, density=0.4), 81),
+    (dict(B=1, Hh=2, S=320, D=128, density=0.5), 82),
+    (dict(B=1, Hh=4, S=256, D=64, density=0.3, causal=False), 83),
+    (dict(B=2, Hh=4, S=128, D=128, density=0.5, head_keep=0.5), 84),
+    (dict(B=3, Hh=2, S=192, D=64, density=0.4, mask_batch=3), 85),
+    (dict(B=1, Hh=2, S=128, D=64, density=0.0), 86),
+    (dict(B=1, Hh=2, S=1024, D=64, density=0.3), 87),          # configs[2]'s sequence length
+])
+def test_fp32_attention(lx, oracle, kw, seed):
+    """LX_F32 attention (the correctness configuration): forward and backward within the fp32 gates
+    of the oracle -- 1e-5 on the largest error, on the element-wise error with an rms floor and on
+    LSE, 2e-6 on the Frobenius error."""
+    c = inputs.attn_blocks(seed=seed, dtype="f32", **kw)
+    check(run_gpu(lx, c), run_oracle(oracle, c), f"f32 {kw}", dtype="f32")
+
+
+def test_fp32_attention_strided_and_above_diagonal(lx, oracle):
+    c = inputs.attn_blocks(2, 2, 320, 64, 0.5, seed=88, dtype="f32")
+    nb = 320 // 64
+    up = np.triu(np.ones((nb, nb), np.uint8), 1)
+    c["mask"] = c["mask"] | (up[None, None] & (np.random.default_rng(6).random(c["mask"].shape) < 0.5)).astype(np.uint8)
+    c["mask"][0, 1, 0] = [0, 1, 0, 1, 1]        # row 0 of head 1: only blocks above the diagonal
+    ref = run_oracle(oracle, c)
+    a = run_gpu(lx, c, layout="bshd")
+    b = run_gpu(lx, c, layout="bhsd")
+    for k in a:
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
+    check(a, ref, "f32 bshd, blocks above the diagonal", dtype="f32")
