@@ -130,9 +130,12 @@ def make_workload(name: str):
         a = inputs.config5_attn(rho)
         ffn_calls = 1
         if len(parts) > 2 and parts[2] == "shared":
-            # the same layer with ONE list row for all token tiles (row 0 of the mask, repeated)
-            # and up to four token tiles per FFN workgroup: the dense path at rho = 1
+            # the same layer with ONE list row for all token tiles (row 0 of the mask, repeated), which
+            # lets a workgroup take up to four token tiles: the dense path at rho = 1
             f["mask"] = np.repeat(f["mask"][:1], f["mask"].shape[0], axis=0)
+            # four token tiles per workgroup asked for: measured faster at these shapes than the
+            # library's own choice also where that leaves CUs without a workgroup (10 %: 128 items of
+            # four tiles 0.71 ms per step, 256 items of two tiles 0.78 ms)
             f["shared_list"], f["tiles_per_wg"] = True, 4
     else:
         raise SystemExit(f"unknown workload {name!r}")

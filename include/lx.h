@@ -458,8 +458,9 @@ lx_status lx_attn_set_rows_per_workgroup(int32_t rows);
  * the weight bytes moved per product to 0.6 / 0.4 but also the number of
  * workgroups to a half / a quarter, so they pay for dense or large layers and
  * lose where one tile per workgroup just fills the chip.  tiles = 0 (the
- * default) lets the library choose (more than one only when the groups alone
- * outnumber the CUs); 1, 2 or 4 asks for at most that many for all later calls
+ * default) lets the library choose: the largest group with which the work
+ * items -- tile groups x groups of four list entries, counted from the list's
+ * capacity nnz_cap -- still number at least one per CU; 1, 2 or 4 asks for at most that many for all later calls
  * of the calling host thread (per-thread setting; the library falls back to 2
  * or 1 where the list rows are not shared accordingly, and always uses 1 in the
  * LoRA calls).  Results are bit-identical for every value.  Returns

@@ -633,14 +633,23 @@ hipError_t set_ffn_tiles_per_wg(int n) {
   return hipSuccess;
 }
 // Groups of tiles need list rows shared by a multiple of that many tiles; left to itself the
-// library takes them only when the groups alone outnumber the CUs (the number of list entries,
-// which decides whether fewer, larger workgroups still fill the chip, is known on the device
-// only).
-static int tiles_per_wg(int Tt, int gt) {
+// library takes the largest group that still fills the chip, judged by the capacity of the list
+// (the true number of entries is known on the device only: a capacity far above it makes the
+// choice too optimistic, and the caller's knob overrides it).
+static int tiles_per_wg(int Tt, int gt, int nnz_cap) {
   const int want = g_ffn_tiles_per_wg;
   if (want == 1) return 1;
-  for (int tt = 4; tt > 1; tt /= 2)
-    if (gt % tt == 0 && (want == 0 ? Tt / tt >= kCUs : want >= tt)) return tt;
+  for (int tt = 4; tt > 1; tt /= 2) {
+    if (gt % tt != 0) continue;
+    if (want != 0) {
+      if (want >= tt) return tt;
+      continue;
+    }
+    // left to itself: the largest group whose work items (tile groups x groups of four list
+    // entries, by the host-known bound on the entries) still give every CU a workgroup
+    const long long items = (long long)(gt / tt) * ((nnz_cap + 3) / 4);
+    if (Tt / tt >= kCUs || items >= kCUs) return tt;
+  }
   return 1;
 }
 
@@ -750,7 +759,7 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
                            float* part, size_t part_bytes, hipStream_t st) {
   (void)Fb;
   if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
-  const int tt = tiles_per_wg(Tt, gt);
+  const int tt = tiles_per_wg(Tt, gt, nnz_cap);
   if (tt == 4) {
     launch_multi<DT, 4>(pass, Tt, gt, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap, act_out,
                         act_gate, out, part, part_bytes, st);

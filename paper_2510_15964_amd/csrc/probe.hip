@@ -34,8 +34,16 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __res
 __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src,
                                                          uint4* __restrict__ dst, long long n) {
   const long long stride = (long long)gridDim.x * blockDim.x;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-    dst[i] = src[i];
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  // four loads in flight per lane before the first store
+  for (; i + 3 * stride < n; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n; i += stride) dst[i] = src[i];
 }
 
 constexpr int kProbeWgs = kCUs * 4;   // 4 workgroups of 4 wavefronts per CU: 4 wavefronts per SIMD

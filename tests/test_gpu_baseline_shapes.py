@@ -157,14 +157,16 @@ def test_config5_ffn_full_size_sampled_rows(lx, oracle, rho, rows):
     check_ffn_sampled(lx, oracle, c, tiles, rows, label=f"config5 rho={rho}")
 
 
-@pytest.mark.parametrize("rho,rows", [(0.3, (0, 27, 36, 63)), (1.0, (5, 58))])
-def test_config5_ffn_shared_list_four_tiles_per_workgroup(lx, oracle, rho, rows):
-    """configs[4] FFN with ONE list row for all token tiles and four token tiles per workgroup:
-    the benchmark's config5:RHO:shared workloads (the dense path at rho = 1)."""
+@pytest.mark.parametrize("rho,rows,tiles_per_wg", [(0.1, ROWS8, 0), (0.3, (0, 27, 36, 63), 0), (0.3, (0, 27, 36, 63), 4),
+                                                   (1.0, (5, 58), 4)])
+def test_config5_ffn_shared_list_several_tiles_per_workgroup(lx, oracle, rho, rows, tiles_per_wg):
+    """configs[4] FFN with ONE list row for all token tiles: the benchmark's config5:RHO:shared
+    workloads (the dense path at rho = 1), with the library's own choice of token tiles per
+    workgroup (0: two at 10 %, four at 30 %) and with four asked for."""
     c = inputs.config5_ffn(rho)
     c["mask"] = np.repeat(c["mask"][:1], c["mask"].shape[0], axis=0)
-    check_ffn_sampled(lx, oracle, c, (0, 30, 63), rows, shared=True, tiles_per_wg=4,
-                      label=f"config5 rho={rho} shared")
+    check_ffn_sampled(lx, oracle, c, (0, 30, 63), rows, shared=True, tiles_per_wg=tiles_per_wg,
+                      label=f"config5 rho={rho} shared, tiles per workgroup {tiles_per_wg or 'auto'}")
 
 
 def test_config5_dense_path_with_split_lists(lx, oracle):
