@@ -73,12 +73,8 @@ __device__ __forceinline__ bool find_work(const int* __restrict__ row_ptr, int r
   // workgroups that run at the same time come from different token tiles and, the lists being
   // sorted, from the same region of the neuron axis: the weight blocks that several tiles of
   // the XCD use are then fetched into its L2 once (with all blocks listed: once per eight tiles).
-  // (With more items than the 32 workgroups an XCD runs at a time the launch proceeds in rounds,
-  // and what matters is what ONE round touches: consecutive items then, i.e. a few tiles and
-  // their blocks per round, rather than every other item of all the XCD's tiles in each round --
-  // measured on 128 tiles in one call: 303 -> 250 MB fetched per launch.)
   const int q = (L + 7) / 8, slot = w / 8;
-  const int pos = L > 32 ? slot : (slot % 8) * q + slot / 8, work = (w % 8) * L + pos;
+  const int pos = (slot % 8) * q + slot / 8, work = (w % 8) * L + pos;
   if (slot >= 8 * q || pos >= L || work >= total) return false;
   int running = 0;
   for (int base = 0; base < rows; base += kWave) {
