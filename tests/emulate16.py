@@ -13,9 +13,9 @@ The figure is a maximum over 10^5 .. 10^6 rounding errors, so it depends on whic
 be rounded.  For attention a fused kernel is free in one respect that changes those values: the
 reference point the unnormalised probabilities are taken against (any upper bound of the row's
 scores gives the same softmax).  attn() therefore takes that reference point as a parameter and
-attn_realisations() returns the pipeline for several of them; between them the figure of one
-tensor varies by up to a factor of two (test_emulated_gate.py), and the gate is taken from their
-envelope.
+attn_realisations() returns the pipeline for eight of them, spread over the one period (a factor
+of two) after which the rounding repeats; between them the figure of one tensor varies by up to a
+factor of two (test_emulated_gate.py), and the gate is taken from their envelope.
 
 The roundings, per tensor:
   FFN        H = round(ReLU(X W_up^T + b));  Y = round(H W_down^T + b);
@@ -102,9 +102,14 @@ def attn(c, ref_shift=0.0):
     return out
 
 
-# offsets (natural-log units) of the softmax reference point above the row maximum: within the
-# slack of 8 log2 units = 5.5 that the forward kernel's running maximum may lag behind
-REF_SHIFTS = (0.0, 1.1, 5.3)
+# Offsets (natural-log units) of the softmax reference point above the row maximum.  Rounding to a
+# binary floating-point format commutes with scaling by two, so the realisation depends on the
+# offset modulo ln 2 only: eight equally spaced points cover that period.  (Three arbitrary points
+# were too few: a row whose probabilities are dominated by a few keys gets an O that is off by the
+# rounding error of those few P' as a whole, Delta = rowsum(dO (.) O) inherits it, and dQ of that
+# row moves by (error of Delta) * scale * P K -- a figure that, on a random input, only some
+# reference points show.)
+REF_SHIFTS = tuple(float(k) / 8.0 * float(np.log(2.0)) for k in range(8))
 
 
 def attn_realisations(c):

@@ -24,7 +24,7 @@ FRO = {"f32": 2e-6, "bf16": 5e-3, "f16": 6.25e-4}
 # is the maximum of ~10^5 rounding errors and so depends on which values get rounded; equally valid
 # realisations of the ideal pipeline differ by up to a factor of two in it (test_emulated_gate.py),
 # hence a factor of one half above the envelope of the emulated realisations rather than a quarter
-# (largest ratio seen over 545 tensors of the GPU tests: 1.38 against a single realisation).
+# (largest ratio seen: 1.30 over 1920 tensors of random attention cases, 1.23 over the GPU tests).
 EMUL_FACTOR = 1.5
 
 
@@ -63,8 +63,9 @@ def rel_err_rows(got, ref) -> float:
 
 
 ROW_FLOOR = 1e-3
-# largest ratio of the kernels' per-row figure to the ideal pipeline's over the 412 tensors of the
-# GPU tests: 1.12 (most are exactly 1: the worst row is an output-rounding error either way)
+# largest ratio of the kernels' per-row figure to the ideal pipeline's: 1.04 over the tensors of the
+# GPU tests, 1.26 over random attention cases (most are exactly 1: the worst row is an
+# output-rounding error either way)
 ROW_FACTOR = EMUL_FACTOR
 
 
