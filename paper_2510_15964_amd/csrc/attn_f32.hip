@@ -1,7 +1,12 @@
 // fp32 block-sparse attention (Sec. VI-A: SDD, softmax, DSD over a block list; Sec. V-C for the
 // backward pass): the correctness configuration of the attention operator, as ffn_f32.hip is for
-// the FFN.  Plain fp32 multiply-adds from LDS tiles, no matrix unit, fp32 everywhere (scores,
-// statistics, sums), so that the results stay within 1e-5 of the fp64 definition; not tuned.
+// the FFN.  Plain multiply-adds from fp32 LDS tiles, no matrix unit; not tuned.  Tensors, the
+// score / probability tile and the statistics handed from kernel to kernel are fp32; every SUM
+// (dot products over the head dimension, sums over keys or queries, Delta) is accumulated in
+// double.  With fp32 sums the outputs stay within 1e-5 of the fp64 definition on the largest
+// error, but not element by element: a row's O carries the ~1e-6 of its accumulation as a whole,
+// Delta = rowsum(dO (.) O) inherits it, and dQ of that row moves by (error of Delta) * scale * P K,
+// which reads up to 2e-5 against the row's own small gradients.
 //
 // One workgroup of 256 threads per 64-row block of its OWN rows: a query block in the forward and
 // query-side backward kernels (it walks the row list), a key block in the key-side backward
@@ -66,10 +71,11 @@ __global__ __launch_bounds__(kFT) void attn_fwd_f32(const AttnArgs a, const floa
   const int rs = a.row_ptr[hd.list_row0 + qb];
   const int n = hd.on ? max(min(a.row_ptr[hd.list_row0 + qb + 1], a.nnz_cap) - rs, 0) : 0;
   constexpr int kC = D / 4;                     // output columns of this thread
-  float o[kC];
+  double o[kC];
 #pragma unroll
-  for (int c = 0; c < kC; ++c) o[c] = 0.f;
-  float m = -INFINITY, l = 0.f;                 // running maximum and sum of query r (same in all four p)
+  for (int c = 0; c < kC; ++c) o[c] = 0.0;
+  float m = -INFINITY;                          // running maximum of query r (same in all four p)
+  double l = 0.0;                               // ... and sum
   if (n > 0) load_tile<D>(q_t, Q + hd.base + (long long)qb * 64 * a.ss, a.ss);
   for (int it = 0; it < n; ++it) {
     const int kb = a.col_idx[rs + it];
@@ -80,10 +86,10 @@ __global__ __launch_bounds__(kFT) void attn_fwd_f32(const AttnArgs a, const floa
 #pragma unroll 1
     for (int j = 0; j < 16; ++j) {              // scores of query r against keys 16p + j
       const int k = 16 * p + j;
-      float s = 0.f;
+      double acc = 0.0;
 #pragma unroll 8
-      for (int c = 0; c < D; ++c) s += q_t[r * T::kLd + c] * k_t[k * T::kLd + c];
-      s *= a.scale;
+      for (int c = 0; c < D; ++c) acc += (double)q_t[r * T::kLd + c] * (double)k_t[k * T::kLd + c];
+      float s = (float)(acc * (double)a.scale);
       if (a.causal && kb * 64 + k > qb * 64 + r) s = -INFINITY;   // a key after the query
       s_t[r * 65 + k] = s;
     }
@@ -93,27 +99,27 @@ __global__ __launch_bounds__(kFT) void attn_fwd_f32(const AttnArgs a, const floa
     for (int k = 0; k < 64; ++k) mb = fmaxf(mb, s_t[r * 65 + k]);
     const float m_new = fmaxf(m, mb);
     if (m_new != -INFINITY) {                   // else: no allowed key so far, nothing to add
-      const float alpha = expf(m - m_new);    // exp(-inf) = 0 where m was -inf
-      float sum = 0.f;
+      const double alpha = exp((double)m - (double)m_new);    // exp(-inf) = 0 where m was -inf
+      double sum = 0.0;
 #pragma unroll
       for (int c = 0; c < kC; ++c) o[c] *= alpha;
 #pragma unroll 2
       for (int k = 0; k < 64; ++k) {
-        const float pr = expf(s_t[r * 65 + k] - m_new);
+        const double pr = exp((double)s_t[r * 65 + k] - (double)m_new);
         sum += pr;
         const float* vrow = v_t + k * T::kLd + p * kC;
 #pragma unroll
-        for (int c = 0; c < kC; ++c) o[c] += pr * vrow[c];
+        for (int c = 0; c < kC; ++c) o[c] += pr * (double)vrow[c];
       }
       l = l * alpha + sum;
       m = m_new;
     }
   }
-  const float inv = l > 0.f ? 1.f / l : 0.f;
+  const double inv = l > 0.0 ? 1.0 / l : 0.0;
   float* orow = O + hd.base + (long long)(qb * 64 + r) * a.ss + p * kC;
 #pragma unroll
-  for (int c = 0; c < kC; ++c) orow[c] = o[c] * inv;
-  if (p == 0) a.LSE[hd.stat + qb * 64 + r] = l > 0.f ? m + logf(l) : -INFINITY;
+  for (int c = 0; c < kC; ++c) orow[c] = (float)(o[c] * inv);
+  if (p == 0) a.LSE[hd.stat + qb * 64 + r] = l > 0.0 ? (float)((double)m + log(l)) : -INFINITY;
 }
 
 // backward, query side: Delta = rowsum(dO (.) O) and dQ of one query block
@@ -135,18 +141,18 @@ __global__ __launch_bounds__(kFT) void attn_bwd_dq_f32(const AttnArgs a, const f
   const int rs = a.row_ptr[hd.list_row0 + qb];
   const int n = hd.on ? max(min(a.row_ptr[hd.list_row0 + qb + 1], a.nnz_cap) - rs, 0) : 0;
   constexpr int kC = D / 4;
-  float g[kC];
+  double g[kC];
 #pragma unroll
-  for (int c = 0; c < kC; ++c) g[c] = 0.f;
+  for (int c = 0; c < kC; ++c) g[c] = 0.0;
   const long long row = hd.base + (long long)(qb * 64 + r) * a.ss;
   const float lse = a.LSEin[hd.stat + qb * 64 + r];
-  float delta = 0.f;
+  double delta = 0.0;
   if (n > 0) {
     load_tile<D>(q_t, Q + hd.base + (long long)qb * 64 * a.ss, a.ss);
     load_tile<D>(do_t, dO + hd.base + (long long)qb * 64 * a.ss, a.ss);
-    for (int c = 0; c < D; ++c) delta += dO[row + c] * O[row + c];
+    for (int c = 0; c < D; ++c) delta += (double)dO[row + c] * (double)O[row + c];
   }
-  if (p == 0) a.Delta[hd.stat + qb * 64 + r] = delta;      // for the key-side kernel
+  if (p == 0) a.Delta[hd.stat + qb * 64 + r] = (float)delta;      // for the key-side kernel
   for (int it = 0; it < n; ++it) {
     const int kb = a.col_idx[rs + it];
     __syncthreads();
@@ -156,28 +162,28 @@ __global__ __launch_bounds__(kFT) void attn_bwd_dq_f32(const AttnArgs a, const f
 #pragma unroll 1
     for (int j = 0; j < 16; ++j) {
       const int k = 16 * p + j;
-      float s = 0.f, dp = 0.f;
+      double s = 0.0, dp = 0.0;
 #pragma unroll 8
       for (int c = 0; c < D; ++c) {
-        s += q_t[r * T::kLd + c] * k_t[k * T::kLd + c];
-        dp += do_t[r * T::kLd + c] * v_t[k * T::kLd + c];
+        s += (double)q_t[r * T::kLd + c] * (double)k_t[k * T::kLd + c];
+        dp += (double)do_t[r * T::kLd + c] * (double)v_t[k * T::kLd + c];
       }
       const bool allowed = !(a.causal && kb * 64 + k > qb * 64 + r) && lse != -INFINITY;
-      const float pr = allowed ? expf(s * a.scale - lse) : 0.f;
-      s_t[r * 65 + k] = pr * (dp - delta);
+      const double pr = allowed ? exp(s * (double)a.scale - (double)lse) : 0.0;
+      s_t[r * 65 + k] = (float)(pr * (dp - delta));
     }
     __syncthreads();
 #pragma unroll 2
     for (int k = 0; k < 64; ++k) {
-      const float ds = s_t[r * 65 + k];
+      const double ds = s_t[r * 65 + k];
       const float* krow = k_t + k * T::kLd + p * kC;
 #pragma unroll
-      for (int c = 0; c < kC; ++c) g[c] += ds * krow[c];
+      for (int c = 0; c < kC; ++c) g[c] += ds * (double)krow[c];
     }
   }
   float* grow = dQ + row + p * kC;
 #pragma unroll
-  for (int c = 0; c < kC; ++c) grow[c] = g[c] * a.scale;
+  for (int c = 0; c < kC; ++c) grow[c] = (float)(g[c] * (double)a.scale);
 }
 
 // backward, key side: dK and dV of one key block (walks the column list: entries = query blocks)
@@ -199,9 +205,9 @@ __global__ __launch_bounds__(kFT) void attn_bwd_dkv_f32(const AttnArgs a, const 
   const int rs = a.crow_ptr[hd.list_row0 + kb];
   const int n = hd.on ? max(min(a.crow_ptr[hd.list_row0 + kb + 1], a.cnnz_cap) - rs, 0) : 0;
   constexpr int kC = D / 4;
-  float gk[kC], gv[kC];
+  double gk[kC], gv[kC];
 #pragma unroll
-  for (int c = 0; c < kC; ++c) gk[c] = gv[c] = 0.f;
+  for (int c = 0; c < kC; ++c) gk[c] = gv[c] = 0.0;
   if (n > 0) {
     load_tile<D>(k_t, K + hd.base + (long long)kb * 64 * a.ss, a.ss);
     load_tile<D>(v_t, V + hd.base + (long long)kb * 64 * a.ss, a.ss);
@@ -216,25 +222,25 @@ __global__ __launch_bounds__(kFT) void attn_bwd_dkv_f32(const AttnArgs a, const 
 #pragma unroll
     for (int j = 0; j < 16; ++j) {              // key r against queries 16p + j
       const int q = 16 * p + j;
-      float s = 0.f, dp = 0.f;
+      double s = 0.0, dp = 0.0;
 #pragma unroll 8
       for (int c = 0; c < D; ++c) {
-        s += q_t[q * T::kLd + c] * k_t[r * T::kLd + c];
-        dp += do_t[q * T::kLd + c] * v_t[r * T::kLd + c];
+        s += (double)q_t[q * T::kLd + c] * (double)k_t[r * T::kLd + c];
+        dp += (double)do_t[q * T::kLd + c] * (double)v_t[r * T::kLd + c];
       }
       const float lse = a.LSEin[hd.stat + qb * 64 + q];
       const bool allowed = !(a.causal && kb * 64 + r > qb * 64 + q) && lse != -INFINITY;
-      const float pr = allowed ? expf(s * a.scale - lse) : 0.f;
-      s_t[r * 65 + q] = pr;
-      ds_keep[j] = pr * (dp - a.Delta[hd.stat + qb * 64 + q]);
+      const double pr = allowed ? exp(s * (double)a.scale - (double)lse) : 0.0;
+      s_t[r * 65 + q] = (float)pr;
+      ds_keep[j] = (float)(pr * (dp - (double)a.Delta[hd.stat + qb * 64 + q]));
     }
     __syncthreads();
 #pragma unroll 2
     for (int q = 0; q < 64; ++q) {              // dV += P^T dO
-      const float pr = s_t[r * 65 + q];
+      const double pr = s_t[r * 65 + q];
       const float* drow = do_t + q * T::kLd + p * kC;
 #pragma unroll
-      for (int c = 0; c < kC; ++c) gv[c] += pr * drow[c];
+      for (int c = 0; c < kC; ++c) gv[c] += pr * (double)drow[c];
     }
     __syncthreads();
 #pragma unroll
@@ -242,17 +248,17 @@ __global__ __launch_bounds__(kFT) void attn_bwd_dkv_f32(const AttnArgs a, const 
     __syncthreads();
 #pragma unroll 2
     for (int q = 0; q < 64; ++q) {              // dK += dS^T Q
-      const float ds = s_t[r * 65 + q];
+      const double ds = s_t[r * 65 + q];
       const float* qrow = q_t + q * T::kLd + p * kC;
 #pragma unroll
-      for (int c = 0; c < kC; ++c) gk[c] += ds * qrow[c];
+      for (int c = 0; c < kC; ++c) gk[c] += ds * (double)qrow[c];
     }
   }
   const long long row = hd.base + (long long)(kb * 64 + r) * a.ss + p * kC;
 #pragma unroll
   for (int c = 0; c < kC; ++c) {
-    dV[row + c] = gv[c];
-    dK[row + c] = gk[c] * a.scale;
+    dV[row + c] = (float)gv[c];
+    dK[row + c] = (float)(gk[c] * (double)a.scale);
   }
 }
 

@@ -48,6 +48,26 @@ def test_attention_random_shapes(lx, oracle, seed):
         lx.lx_attn_set_rows_per_workgroup(0)
 
 
+@pytest.mark.parametrize("seed", [131, 242])
+def test_attention_random_shapes_fp32(lx, oracle, seed):
+    """The fp32 correctness kernels on random shapes and options, at the fp32 gates."""
+    from test_gpu_attn import check, run_gpu, run_oracle
+    rng = np.random.default_rng(seed)
+    try:
+        for _ in range(5):
+            B, Hh, S = int(rng.integers(1, 3)), int(rng.integers(1, 5)), 64 * int(rng.integers(1, 8))
+            D = int(rng.choice([64, 128]))
+            a = inputs.attn_blocks(B, Hh, S, D, float(rng.choice([0.0, 0.1, 0.4, 1.0])),
+                                   int(rng.integers(1, 10 ** 6)), dtype="f32",
+                                   causal=bool(rng.integers(0, 2)), head_keep=float(rng.choice([1.0, 0.6])),
+                                   force_diagonal=bool(rng.integers(0, 2)), mask_batch=int(rng.choice([1, B])))
+            layout = str(rng.choice(["bhsd", "bshd"]))
+            check(run_gpu(lx, a, layout=layout), run_oracle(oracle, a),
+                  f"random f32 B={B} H={Hh} S={S} D={D} {layout}", dtype="f32")
+    finally:
+        lx.lx_attn_set_rows_per_workgroup(0)
+
+
 @pytest.mark.parametrize("seed", [121, 232])
 def test_lora_random_shapes(lx, oracle, seed):
     from test_gpu_lora import check, make_case, run_both
