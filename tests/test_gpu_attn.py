@@ -281,6 +281,23 @@ def test_fp32_attention(lx, oracle, kw, seed):
     check(run_gpu(lx, c), run_oracle(oracle, c), f"f32 {kw}", dtype="f32")
 
 
+@pytest.mark.parametrize("B,Hh,S,D,density,causal,dtype,rows", [
+    (1, 2, 4160, 64, 0.04, True, "bf16", 0),        # 65 row blocks per head
+    (1, 1, 4224, 128, 0.05, False, "f16", 3),
+    (1, 1, 4160, 64, 0.05, True, "f32", 0),
+])
+def test_more_than_64_row_blocks_per_head(lx, oracle, B, Hh, S, D, density, causal, dtype, rows):
+    """Sequences of more than 4096 tokens: a head has more rows than the 64 lanes that rank the
+    rows of a head group by list length, so the rows are dealt to the workgroups in the fixed
+    order instead."""
+    c = inputs.attn_blocks(B, Hh, S, D, density, seed=95, dtype=dtype, causal=causal)
+    lx.lx_attn_set_rows_per_workgroup(rows)
+    try:
+        check(run_gpu(lx, c), run_oracle(oracle, c), f"long {dtype} S={S} D={D}", dtype=dtype)
+    finally:
+        lx.lx_attn_set_rows_per_workgroup(0)
+
+
 def test_fp32_attention_strided_and_above_diagonal(lx, oracle):
     c = inputs.attn_blocks(2, 2, 320, 64, 0.5, seed=88, dtype="f32")
     nb = 320 // 64
