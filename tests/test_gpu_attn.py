@@ -298,6 +298,18 @@ def test_more_than_64_row_blocks_per_head(lx, oracle, B, Hh, S, D, density, caus
         lx.lx_attn_set_rows_per_workgroup(0)
 
 
+def test_more_entries_than_one_fill_of_the_block_table(lx, oracle):
+    """A workgroup's sequence of ring entries (a row's own tiles, then its listed blocks) is written
+    into an LDS table of 512 entries at a time: eight dense rows of 65 blocks are 528 entries, so
+    the walk refills the table in the middle of a row."""
+    c = inputs.attn_blocks(1, 1, 4160, 64, 1.0, seed=97, dtype="bf16", causal=False)
+    lx.lx_attn_set_rows_per_workgroup(8)
+    try:
+        check(run_gpu(lx, c), run_oracle(oracle, c), "two table fills")
+    finally:
+        lx.lx_attn_set_rows_per_workgroup(0)
+
+
 def test_fp32_attention_strided_and_above_diagonal(lx, oracle):
     c = inputs.attn_blocks(2, 2, 320, 64, 0.5, seed=88, dtype="f32")
     nb = 320 // 64
