@@ -116,6 +116,7 @@ constexpr int kRMax = 8;   // rows of the mask per workgroup, at most
 // dispatched first).  The row pointers of all slots are fetched once and kept in a small LDS table.
 struct RowSet {
   const int* tab;   // LDS: blk[kRMax] (-1 = slot not used), rs[kRMax], n[kRMax], head[kRMax]
+  int reg;          // the same table, entry i in lane i of every wavefront (one LDS read for all accessors)
   // The rows are those of `heads` consecutive heads, h0 .. (nb1 blocks each, their list rows one
   // after the other from head_row0), ranked and dealt together: heads whose lists differ in
   // length then share their workgroups instead of each keeping G of its own.
@@ -142,11 +143,23 @@ struct RowSet {
           // entries beyond the capacity of the index buffer are ignored
           n = head_on ? max(min(row_ptr[head_row0 + tid + 1], cap) - rs, 0) : 0;
         }
-        int rank = 0;
-        for (int q = 0; q < nblk; ++q) {
-          const int nq = __builtin_amdgcn_readlane(n, q);
-          rank += (nq > n || (nq == n && q < tid)) ? 1 : 0;
+        // rank = rows with a longer list + rows before this one with an equally long list, by a
+        // radix walk over the bits of the length with one ballot per bit: `gt` collects the lanes
+        // known to be longer, `eq` those equal in the bits seen so far (lanes past the last row
+        // carry key 0, below every row's)
+        const unsigned key = (unsigned)(n + 1);
+        unsigned long long gt = 0, eq = ~0ull;
+#pragma unroll
+        for (int bit = 6; bit >= 0; --bit) {     // a list has at most 64 entries here
+          const unsigned long long set = __ballot((key >> bit) & 1u);
+          if ((key >> bit) & 1u) {
+            eq &= set;
+          } else {
+            gt |= eq & set;
+            eq &= ~set;
+          }
         }
+        const int rank = __popcll(gt) + __popcll(eq & ((1ull << tid) - 1ull));
         const int j = rank / G, pos = rank - j * G;
         if (valid && ((j & 1) ? G - 1 - pos : pos) == g) {
           tab_lds[j] = tid - hh * nb1;
@@ -183,18 +196,13 @@ struct RowSet {
       tab_lds[3 * kRMax + j] = h0;
     }
     __syncthreads();
+    reg = tab_lds[threadIdx.x % (4 * kRMax)];
   }
-  // k is wave-uniform; so are the results, and they are made scalar registers
-  __device__ __forceinline__ int blk(int k) const { return __builtin_amdgcn_readfirstlane(tab[k]); }
-  __device__ __forceinline__ int rs(int k) const {
-    return __builtin_amdgcn_readfirstlane(tab[kRMax + k]);
-  }
-  __device__ __forceinline__ int n(int k) const {
-    return __builtin_amdgcn_readfirstlane(tab[2 * kRMax + k]);
-  }
-  __device__ __forceinline__ int head(int k) const {
-    return __builtin_amdgcn_readfirstlane(tab[3 * kRMax + k]);
-  }
+  // k is wave-uniform; the results are scalars taken from the register copy of the table
+  __device__ __forceinline__ int blk(int k) const { return __builtin_amdgcn_readlane(reg, k); }
+  __device__ __forceinline__ int rs(int k) const { return __builtin_amdgcn_readlane(reg, kRMax + k); }
+  __device__ __forceinline__ int n(int k) const { return __builtin_amdgcn_readlane(reg, 2 * kRMax + k); }
+  __device__ __forceinline__ int head(int k) const { return __builtin_amdgcn_readlane(reg, 3 * kRMax + k); }
 };
 
 // ---------------------------------------------------------------------------
@@ -333,19 +341,21 @@ __device__ __forceinline__ float max_g(float x) {
 // ---------------------------------------------------------------------------
 // The work of a workgroup as ONE sequence of ring entries, built once into an LDS table: for
 // every row slot with a non-empty list an OWN entry (the row's own tiles travel through the
-// ring like any block, so a row starts without a load of its own) followed by its listed
-// blocks, the last one flagged.  Entry: bits 0..23 block index, 24..26 row slot.
+// ring like any block, so a row starts without a load of its own), in the dQ kernel an AUX entry
+// (a third own tile), then its listed blocks, the last one flagged.  Entry: bits 0..23 block
+// index, 24..26 row slot.
 // ---------------------------------------------------------------------------
 constexpr int kTabCap = 512;                       // entries per fill of the table
-constexpr int kEOwn = 1 << 30, kELast = 1 << 29;
+constexpr int kEOwn = 1 << 30, kELast = 1 << 29, kEAux = 1 << 28;
 
 __device__ __forceinline__ int entry_blk(int e) { return e & 0xFFFFFF; }
 __device__ __forceinline__ int entry_slot(int e) { return (e >> 24) & 7; }
 
 // Entries first .. first+cnt-1 of the sequence -> tab[0 .. cnt).  Uniform control flow; ends
-// with a barrier.  offs[i]: first entry of slot i (offs[kRMax] = length of the sequence).
+// with a barrier.  offs[i]: first entry of slot i (offs[kRMax] = length of the sequence); pre:
+// entries of a row before its first block (1: OWN; 2: OWN, AUX).
 __device__ __forceinline__ void fill_table(int* tab, const RowSet& rows, const int* __restrict__ col_idx,
-                                           const int (&offs)[kRMax + 1], int first, int cnt) {
+                                           const int (&offs)[kRMax + 1], int first, int cnt, int pre) {
   for (int e = first + (int)threadIdx.x; e < first + cnt; e += kAT) {
     int j = 0, o = 0;
 #pragma unroll
@@ -354,10 +364,11 @@ __device__ __forceinline__ void fill_table(int* tab, const RowSet& rows, const i
         j = i;
         o = offs[i];
       }
-    const int it = e - o - 1;                      // -1: the row's OWN entry
+    const int it = e - o - pre;                    // < 0: the row's OWN (first) or AUX entry
     const int n = rows.tab[2 * kRMax + j];
     const int blk = it < 0 ? rows.tab[j] : col_idx[rows.tab[kRMax + j] + it];
-    tab[e - first] = blk | (j << 24) | (it < 0 ? kEOwn : 0) | (it == n - 1 ? kELast : 0);
+    tab[e - first] = blk | (j << 24) | (it == -pre ? kEOwn : 0) | (it < 0 && it > -pre ? kEAux : 0) |
+                     (it == n - 1 ? kELast : 0);
   }
   __syncthreads();
 }
@@ -400,25 +411,31 @@ __device__ __forceinline__ void store_acc16_asm(const f32x4 (&acc)[D / 16], floa
 }
 
 // Walk over the sequence with a ring of NS stages: the transfers of entry t + NS - 1 are issued
-// while entry t is computed.  issue_own / issue_blk(stage, e) start the transfers of an entry and
-// issue exactly XOWN / XBLK vector-memory instructions per wavefront; row_begin(stage, e) takes the
-// own rows' operands out of the stage of an OWN entry; comp(stage, e) consumes a block;
-// row_end(e) stores the row's results with exactly YST store instructions per wavefront.  No other
-// vector-memory instruction may be issued inside the walk: a wavefront waits for the transfers of
-// entry t by counting what it has issued since (in order: the transfers of the entries after t
-// and the stores of the rows that ended meanwhile).
-template <int NS, int XOWN, int XBLK, int YST, class IssueOwn, class IssueBlk, class RowBegin, class Comp,
-          class RowEnd>
+// while entry t is computed.  issue_own / issue_aux / issue_blk(stage, e) start the transfers of an
+// entry and issue exactly XOWN / XAUX / XBLK vector-memory instructions per wavefront (XAUX < 0: the
+// rows have no AUX entry); row_begin(stage, e) takes the own rows' operands out of the stage of an
+// OWN entry; aux(stage, e) consumes an AUX entry and issues exactly YAUX store instructions;
+// comp(stage, e) consumes a block; row_end(e) stores the row's results with exactly YST store
+// instructions per wavefront.  No other vector-memory instruction may be issued inside the walk: a
+// wavefront waits for the transfers of entry t by counting what it has issued since (in order: the
+// transfers of the entries after t and the stores issued meanwhile).
+struct NoAux {
+  __device__ __forceinline__ void operator()(int, int) const {}
+};
+template <int NS, int XOWN, int XAUX, int XBLK, int YAUX, int YST, class IssueOwn, class IssueAux, class IssueBlk,
+          class RowBegin, class Aux, class Comp, class RowEnd>
 __device__ __forceinline__ void walk_table(int* tab, const RowSet& rows, const int* __restrict__ col_idx,
-                                           IssueOwn issue_own, IssueBlk issue_blk, RowBegin row_begin,
-                                           Comp comp, RowEnd row_end) {
+                                           IssueOwn issue_own, IssueAux issue_aux, IssueBlk issue_blk,
+                                           RowBegin row_begin, Aux aux, Comp comp, RowEnd row_end) {
   static_assert(NS >= 2 && NS <= 4, "ring depth");
+  static_assert(YAUX < 256 && YST < 256, "store counts are kept a byte each");
+  constexpr int kPre = XAUX >= 0 ? 2 : 1;
   int offs[kRMax + 1];
   offs[0] = 0;
 #pragma unroll
   for (int i = 0; i < kRMax; ++i) {
     const int ni = rows.n(i);
-    offs[i + 1] = offs[i] + (ni > 0 ? ni + 1 : 0);
+    offs[i + 1] = offs[i] + (ni > 0 ? ni + kPre : 0);
   }
   const int total = offs[kRMax];
   auto entry = [&](int i) { return __builtin_amdgcn_readfirstlane(tab[i]); };
@@ -426,36 +443,46 @@ __device__ __forceinline__ void walk_table(int* tab, const RowSet& rows, const i
     const int e = entry(i);
     if (e & kEOwn)
       issue_own(stage, e);
+    else if (XAUX >= 0 && (e & kEAux))
+      issue_aux(stage, e);
     else
       issue_blk(stage, e);
   };
+  auto issued_by = [&](int e) { return (e & kEOwn) ? XOWN : (XAUX >= 0 && (e & kEAux)) ? XAUX : XBLK; };
   for (int first = 0; first < total; first += kTabCap) {
     const int cnt = min(kTabCap, total - first);
     if (first > 0) lds_barrier();        // the previous table and the stages are no longer read
-    fill_table(tab, rows, col_idx, offs, first, cnt);
+    fill_table(tab, rows, col_idx, offs, first, cnt, kPre);
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i)
       if (i < cnt) issue(i, i);
-    int pend = 0;                        // bit i: the row of entry t-1-i ended (its stores were issued)
+    unsigned hist = 0;                   // byte i: store instructions issued while entry t-1-i was consumed
     int stage = 0, istage = NS - 1;      // stage of entry t, stage entry t + NS - 1 goes to
     for (int t = 0; t < cnt; ++t) {
       const int e = entry(t);
-      int n = YST * __builtin_popcount(pend & ((1 << (NS - 1)) - 1));
+      int n = 0;
+#pragma unroll
+      for (int u = 0; u < NS - 1; ++u) n += (hist >> (8 * u)) & 0xFF;
 #pragma unroll
       for (int u = 1; u <= NS - 2; ++u)
-        if (t + u < cnt) n += (entry(t + u) & kEOwn) ? XOWN : XBLK;
+        if (t + u < cnt) n += issued_by(entry(t + u));
       wait_vmcnt_dyn(n);
       lds_barrier();
       if (t + NS - 1 < cnt) issue(istage, t + NS - 1);
-      bool last = false;
+      int stores = 0;
       if (e & kEOwn) {
         row_begin(stage, e);
+      } else if (XAUX >= 0 && (e & kEAux)) {
+        aux(stage, e);
+        stores = YAUX;
       } else {
         comp(stage, e);
-        last = (e & kELast) != 0;
-        if (last) row_end(e);
+        if (e & kELast) {
+          row_end(e);
+          stores = YST;
+        }
       }
-      pend = (pend << 1) | (last ? 1 : 0);
+      hist = (hist << 8) | (unsigned)stores;
       stage = stage + 1 == NS ? 0 : stage + 1;
       istage = istage + 1 == NS ? 0 : istage + 1;
     }
@@ -472,7 +499,7 @@ __global__ __launch_bounds__(kAT, OCC) void attn_fwd_bf16(const AttnArgs a) {
   __shared__ int btab[kTabCap];
   constexpr uint32_t kStage = 4 * 64 * D, kTile = 2 * 64 * D;   // bytes
   const int nqb = a.S / 64;
-  const int h0 = blockIdx.x * a.vheads, b = blockIdx.y;
+  const int b = blockIdx.x, h0 = blockIdx.y * a.vheads;   // batch entry fastest: see the launchers
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int g = lane / 16, ql = 16 * wave + lane % 16;    // this lane's query inside the block
   auto base_of = [&](int hh) { return (long long)b * a.sb + (long long)hh * a.sh; };
@@ -574,8 +601,8 @@ __global__ __launch_bounds__(kAT, OCC) void attn_fwd_bf16(const AttnArgs a) {
     // (the four lanes of a query store the same value)
     store4(a.LSE + soff, any ? (m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY);
   };
-  walk_table<NS, TileDma<D>::kPerWave, 2 * TileDma<D>::kPerWave, D / 16 + 1>(
-      btab, rows, a.col_idx, issue_own, issue_blk, row_begin, comp, row_end);
+  walk_table<NS, TileDma<D>::kPerWave, -1, 2 * TileDma<D>::kPerWave, 0, D / 16 + 1>(
+      btab, rows, a.col_idx, issue_own, NoAux(), issue_blk, row_begin, NoAux(), comp, row_end);
 }
 
 // ---------------------------------------------------------------------------
@@ -583,65 +610,35 @@ __global__ __launch_bounds__(kAT, OCC) void attn_fwd_bf16(const AttnArgs a) {
 // ---------------------------------------------------------------------------
 template <int D, int DT, int NS, int OCC>
 __global__ __launch_bounds__(kAT, OCC) void attn_bwd_dq_bf16(const AttnArgs a) {
-  __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[NS][2 * 64 * D];   // stage: K, V (or Q, dO) tile
+  __shared__ __attribute__((aligned(2 * 64 * D))) uint16_t st[NS][2 * 64 * D];   // stage: K, V (or Q, dO; or O) tile
+  __shared__ __attribute__((aligned(256))) float slse[NS][4][16];   // stage, wavefront: LSE of its 16 own rows
   __shared__ int rowtab[4 * kRMax];
   __shared__ int btab[kTabCap];
   constexpr uint32_t kStage = 4 * 64 * D, kTile = 2 * 64 * D;
   const int nqb = a.S / 64;
-  const int h0 = blockIdx.x * a.vheads, b = blockIdx.y;
+  const int b = blockIdx.x, h0 = blockIdx.y * a.vheads;   // batch entry fastest: see the launchers
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int g = lane / 16, ql = 16 * wave + lane % 16;
   auto base_of = [&](int hh) { return (long long)b * a.sb + (long long)hh * a.sh; };
   auto stat_of = [&](int hh) { return ((long long)b * a.Hh + hh) * a.S; };
-  const uint32_t st_addr = lds_addr(&st[0][0]);
+  const uint32_t st_addr = lds_addr(&st[0][0]), slse_addr = lds_addr(&slse[0][0][0]);
   const uint32_t own_off = tile_off<D>(ql, 8 * g);
 
   RowSet rows;
   rows.init(rowtab, a.row_ptr, a.nnz_cap, ((a.mask_batch == 1 ? 0 : b) * a.Hh + h0) * nqb, nqb,
             a.vheads, h0, a.head_active, blockIdx.z, gridDim.z, a.rows_per_wg, true);
-  // Per row slot, before the walk (whose vector-memory instructions are counted): rows without a
-  // listed block get dQ = 0, Delta = 0; for the others Delta = rowsum(dO . O) and -LSE in log2
-  // units are computed here, kept in registers and written for the key-side kernel.
-  float delta_all[kRMax], lse2_all[kRMax];
-#pragma unroll
-  for (int j = 0; j < kRMax; ++j) {
-    delta_all[j] = 0.f;
-    lse2_all[j] = INFINITY;
-    if (rows.blk(j) < 0) continue;
-    const int hh = rows.head(j);
-    const long long roff = base_of(hh) + (long long)(rows.blk(j) * 64 + ql) * a.ss;
-    const long long so = stat_of(hh) + rows.blk(j) * 64 + ql;
-    if (rows.n(j) == 0) {
+  // rows without a listed block (or of an inactive head): dQ = 0, Delta = 0, nothing to read
+  for (int j = 0; j < kRMax; ++j)
+    if (rows.blk(j) >= 0 && rows.n(j) == 0) {
       f32x4 z[D / 16];
       zero4(z);
-      store_acc16<D, DT>(z, 0.f, a.dQ + roff);
+      const int hh = rows.head(j);
+      store_acc16<D, DT>(z, 0.f, a.dQ + base_of(hh) + (long long)(rows.blk(j) * 64 + ql) * a.ss);
       if (g == 0) {
-        a.Delta[so] = 0.f;
-        a.NegLse2[so] = INFINITY;
+        a.Delta[stat_of(hh) + rows.blk(j) * 64 + ql] = 0.f;
+        a.NegLse2[stat_of(hh) + rows.blk(j) * 64 + ql] = INFINITY;
       }
-      continue;
     }
-    float sum = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk) {
-      const uint4 of = *reinterpret_cast<const uint4*>(a.O + roff + 32 * kk + 8 * g);
-      const uint4 df = *reinterpret_cast<const uint4*>(a.dO + roff + 32 * kk + 8 * g);
-      const uint32_t x[4] = {df.x, df.y, df.z, df.w};
-      const uint32_t y[4] = {of.x, of.y, of.z, of.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        sum += to_f32<DT>(x[q] & 0xFFFFu) * to_f32<DT>(y[q] & 0xFFFFu) + to_f32<DT>(x[q] >> 16) * to_f32<DT>(y[q] >> 16);
-    }
-    delta_all[j] = sum_g(sum);
-    // a row whose listed blocks hold no allowed key has LSE = -inf: +inf here makes every
-    // probability exp2(score - inf) = 0, also for excluded scores (-inf), which -(-inf) would not
-    const float lse_in = a.LSEin[so];
-    lse2_all[j] = lse_in == -INFINITY ? INFINITY : lse_in * kLog2e;
-    if (g == 0) {
-      a.Delta[so] = delta_all[j];
-      a.NegLse2[so] = -lse2_all[j];
-    }
-  }
 
   TileDma<D> dma;
   dma.init(a.ss);
@@ -650,6 +647,7 @@ __global__ __launch_bounds__(kAT, OCC) void attn_bwd_dq_bf16(const AttnArgs a) {
   const float sc = a.scale * kLog2e;
   int qb = 0;
   long long qoff = 0;
+  long long soff = 0;
   uint4 qf[D / 32], dof[D / 32];
   float delta = 0.f, lse2 = 0.f;
   f32x4 dq_acc[D / 16];
@@ -659,6 +657,13 @@ __global__ __launch_bounds__(kAT, OCC) void attn_bwd_dq_bf16(const AttnArgs a) {
     const uint32_t dst = st_addr + stage * kStage;
     dma.issue(dst, a.Q + t0);
     dma.issue(dst + kTile, a.dO + t0);
+  };
+  // the row's O tile, needed once for Delta = rowsum(dO . O), and the LSE of its 64 queries
+  // (lanes 0-15 of wavefront w bring those of its own rows 16w .. 16w+15)
+  auto issue_aux = [&](int stage, int e) {
+    const int hh = rows.head(entry_slot(e)), blk = entry_blk(e);
+    dma.issue(st_addr + stage * kStage, a.O + base_of(hh) + (long long)blk * 64 * a.ss);
+    if (lane < 16) dma4(a.LSEin + stat_of(hh) + blk * 64 + ql, slse_addr + stage * 256 + wave * 64);
   };
   auto issue_blk = [&](int stage, int e) {
     const long long t0 = base_of(rows.head(entry_slot(e))) + (long long)entry_blk(e) * 64 * a.ss;
@@ -670,19 +675,36 @@ __global__ __launch_bounds__(kAT, OCC) void attn_bwd_dq_bf16(const AttnArgs a) {
     qb = entry_blk(e);
     const int slot = entry_slot(e);
     qoff = base_of(rows.head(slot)) + (long long)(qb * 64 + ql) * a.ss;
+    soff = stat_of(rows.head(slot)) + qb * 64 + ql;
     const uint32_t q0 = (st_addr + stage * kStage) | own_off;
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) {
       qf[kk] = lds_read16(q0 ^ tile_off<D>(0, 32 * kk));
       dof[kk] = lds_read16((q0 + kTile) ^ tile_off<D>(0, 32 * kk));
     }
-#pragma unroll
-    for (int j = 0; j < kRMax; ++j)
-      if (slot == j) {
-        delta = delta_all[j];
-        lse2 = lse2_all[j];
-      }
     zero4(dq_acc);
+  };
+  // Delta and -LSE in log2 units of the row, kept for its blocks and written for the key-side kernel
+  auto aux = [&](int stage, int) {
+    const uint32_t o0 = (st_addr + stage * kStage) | own_off;
+    float sum = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) {
+      const uint4 of = lds_read16(o0 ^ tile_off<D>(0, 32 * kk));
+      const uint32_t x[4] = {dof[kk].x, dof[kk].y, dof[kk].z, dof[kk].w};
+      const uint32_t y[4] = {of.x, of.y, of.z, of.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        sum += to_f32<DT>(x[q] & 0xFFFFu) * to_f32<DT>(y[q] & 0xFFFFu) + to_f32<DT>(x[q] >> 16) * to_f32<DT>(y[q] >> 16);
+    }
+    delta = sum_g(sum);
+    // a row whose listed blocks hold no allowed key has LSE = -inf: +inf here makes every
+    // probability exp2(score - inf) = 0, also for excluded scores (-inf), which -(-inf) would not
+    const float lse_in = slse[stage][wave][lane % 16];
+    lse2 = lse_in == -INFINITY ? INFINITY : lse_in * kLog2e;
+    // (the four lanes of a query store the same values)
+    store4(a.Delta + soff, delta);
+    store4(a.NegLse2 + soff, -lse2);
   };
   auto comp = [&](int stage, int e) {
     const int col = entry_blk(e);
@@ -704,8 +726,8 @@ __global__ __launch_bounds__(kAT, OCC) void attn_bwd_dq_bf16(const AttnArgs a) {
     mma_tr16<D, DT>(kt, s, dq_acc);             // dQ^T += K^T dS^T
   };
   auto row_end = [&](int) { store_acc16_asm<D, DT>(dq_acc, a.scale, a.dQ + qoff); };
-  walk_table<NS, 2 * TileDma<D>::kPerWave, 2 * TileDma<D>::kPerWave, D / 16>(
-      btab, rows, a.col_idx, issue_own, issue_blk, row_begin, comp, row_end);
+  walk_table<NS, 2 * TileDma<D>::kPerWave, TileDma<D>::kPerWave + 1, 2 * TileDma<D>::kPerWave, 2, D / 16>(
+      btab, rows, a.col_idx, issue_own, issue_aux, issue_blk, row_begin, aux, comp, row_end);
 }
 
 // ---------------------------------------------------------------------------
@@ -720,7 +742,7 @@ __global__ __launch_bounds__(kAT, OCC) void attn_bwd_dkv_bf16(const AttnArgs a) 
   __shared__ int btab[kTabCap];
   constexpr uint32_t kStage = 4 * 64 * D, kTile = 2 * 64 * D;
   const int nkb = a.S / 64;
-  const int h0 = blockIdx.x * a.vheads, b = blockIdx.y;
+  const int b = blockIdx.x, h0 = blockIdx.y * a.vheads;   // batch entry fastest: see the launchers
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int g = lane / 16, kl = 16 * wave + lane % 16;    // this lane's key inside the block
   auto base_of = [&](int hh) { return (long long)b * a.sb + (long long)hh * a.sh; };
@@ -815,8 +837,8 @@ __global__ __launch_bounds__(kAT, OCC) void attn_bwd_dkv_bf16(const AttnArgs a) 
     store_acc16_asm<D, DT>(dv_acc, 1.f, a.dV + koff);
     store_acc16_asm<D, DT>(dk_acc, a.scale, a.dK + koff);
   };
-  walk_table<NS, 2 * TileDma<D>::kPerWave, 2 * TileDma<D>::kPerWave + 1, 2 * (D / 16)>(
-      btab, rows, a.ccol_idx, issue_own, issue_blk, row_begin, comp, row_end);
+  walk_table<NS, 2 * TileDma<D>::kPerWave, -1, 2 * TileDma<D>::kPerWave + 1, 0, 2 * (D / 16)>(
+      btab, rows, a.ccol_idx, issue_own, NoAux(), issue_blk, row_begin, NoAux(), comp, row_end);
 }
 
 // Rows per workgroup: the smallest count with which all workgroups of the launch are resident at
@@ -843,6 +865,10 @@ static int rows_per_wg(int nblk, int heads, int B, int slots) {
   return r > nblk ? nblk : r;
 }
 
+// Grid: (batch entry, head group, workgroup of the group).  Workgroups go to the eight XCDs round
+// robin by their linear index, so with the batch entry fastest an XCD gets the same mix of heads
+// as every other one (the masks of the batch entries are the same or alike, those of the heads
+// are not), and all workgroups of a (batch, head) pair share one L2.
 template <int D, int DT>
 static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
   ProfScope ps(kKAttnFwd, st);
@@ -851,7 +877,7 @@ static hipError_t launch_fwd(AttnArgs a, int B, hipStream_t st) {
   constexpr int kNs = D == 64 ? kFwdNs64 : 2, kOcc = D == 64 ? kFwdOcc64 : 2;
   a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * kOcc);
   const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-  hipLaunchKernelGGL((attn_fwd_bf16<D, DT, kNs, kOcc>), dim3(a.Hh / a.vheads, B, G * a.vheads), dim3(kAT), 0,
+  hipLaunchKernelGGL((attn_fwd_bf16<D, DT, kNs, kOcc>), dim3(B, a.Hh / a.vheads, G * a.vheads), dim3(kAT), 0,
                      st, a);
   return hipGetLastError();
 }
@@ -865,7 +891,7 @@ static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
     constexpr int kNs = D == 64 ? kDqNs64 : 2, kOcc = D == 64 ? kDqOcc64 : 2;
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * kOcc);
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL((attn_bwd_dq_bf16<D, DT, kNs, kOcc>), dim3(a.Hh / a.vheads, B, G * a.vheads),
+    hipLaunchKernelGGL((attn_bwd_dq_bf16<D, DT, kNs, kOcc>), dim3(B, a.Hh / a.vheads, G * a.vheads),
                        dim3(kAT), 0, st, a);
   }
   hipError_t e = hipGetLastError();
@@ -875,7 +901,7 @@ static hipError_t launch_bwd(AttnArgs a, int B, hipStream_t st) {
     constexpr int kNs = D == 64 ? kDkvNs64 : 2, kOcc = D == 64 ? kDkvOcc64 : 2;
     a.rows_per_wg = rows_per_wg(nblk, a.Hh, B, kCUs * kOcc);
     const int G = (nblk + a.rows_per_wg - 1) / a.rows_per_wg;
-    hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT, kNs, kOcc>), dim3(a.Hh / a.vheads, B, G * a.vheads),
+    hipLaunchKernelGGL((attn_bwd_dkv_bf16<D, DT, kNs, kOcc>), dim3(B, a.Hh / a.vheads, G * a.vheads),
                        dim3(kAT), 0, st, a);
   }
   return hipGetLastError();
