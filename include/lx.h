@@ -463,8 +463,11 @@ lx_status lx_attn_set_rows_per_workgroup(int32_t rows);
  * capacity nnz_cap -- still number at least one per CU; 1, 2 or 4 asks for at most that many for all later calls
  * of the calling host thread (per-thread setting; the library falls back to 2
  * or 1 where the list rows are not shared accordingly, and always uses 1 in the
- * LoRA calls).  Results are bit-identical for every value.  Returns
- * LX_ERR_INVALID_ARG for other values.
+ * LoRA calls).  The value governs the second product of a pass; the first
+ * product takes that group size or a smaller one, whichever makes its rounds
+ * of workgroups (one work item per CU) cheapest by the list's capacity.
+ * Results are bit-identical for every value.  Returns LX_ERR_INVALID_ARG for
+ * other values.
  */
 lx_status lx_ffn_set_token_tiles_per_workgroup(int32_t tiles);
 

@@ -686,24 +686,54 @@ size_t ffn_dsd_split_bytes(int Tt, int d, int nnz_cap) {
   return need;
 }
 
+// First product of a pass for groups of TT token tiles.
 template <int DT, int TT>
-static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t* A, const uint16_t* W1,
-                         const uint16_t* b1, const uint16_t* W2, const uint16_t* b2,
-                         const int* row_ptr, const int* col_idx, int nnz_cap, uint16_t* act_out,
-                         const uint16_t* act_gate, uint16_t* out, float* part, size_t part_bytes,
-                         hipStream_t st) {
+static void launch_sdd_multi(int pass, int Tt, int gt, int d, const uint16_t* A, const uint16_t* W1,
+                             const uint16_t* b1, const int* row_ptr, const int* col_idx, int nnz_cap,
+                             uint16_t* act_out, const uint16_t* act_gate, hipStream_t st) {
   const uint16_t* none = nullptr;
   const dim3 g1 = sdd_grid(Tt / TT, gt / TT, nnz_cap);
-  {
-    ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
-    if (pass == 0)
-      hipLaunchKernelGGL((ffn_sddn_bf16<DT, 0, false, TT>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
-                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
-    else
-      hipLaunchKernelGGL((ffn_sddn_bf16<DT, 1, false, TT>), g1, dim3(kThreads), 0, st, A, W1, none,
-                         row_ptr, col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
-  }
-  if (hipPeekAtLastError() != hipSuccess) return;
+  ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
+  if (pass == 0)
+    hipLaunchKernelGGL((ffn_sddn_bf16<DT, 0, false, TT>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+                       col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+  else
+    hipLaunchKernelGGL((ffn_sddn_bf16<DT, 1, false, TT>), g1, dim3(kThreads), 0, st, A, W1, none,
+                       row_ptr, col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
+}
+// ... one token tile per workgroup
+template <int DT>
+static void launch_sdd_one(int pass, int Tt, int gt, int d, const uint16_t* A, const uint16_t* W1,
+                           const uint16_t* b1, const int* row_ptr, const int* col_idx, int nnz_cap,
+                           uint16_t* act_out, const uint16_t* act_gate, hipStream_t st) {
+  const dim3 g1 = sdd_grid(Tt, gt, nnz_cap);
+  const uint16_t* none = nullptr;
+  // more than one item per CU but at most two: two resident workgroups of two stages each
+  // (the item count is known on the device only; a list row of n entries makes ceil(n / 4) items,
+  // 3/8 of an item more than n / 4 on average, which is what the estimate adds per tile)
+  const long long items_est = ((long long)nnz_cap * gt + 3) / 4 + (3 * (long long)Tt + 7) / 8;
+  const bool two_resident = items_est > kCUs && items_est <= 2 * kCUs;
+  ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
+  if (pass == 0 && two_resident)
+    hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false, 2>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+                       col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+  else if (pass == 0)
+    hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
+                       col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
+  else if (two_resident)
+    hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false, 2>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
+                       col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
+  else
+    hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
+                       col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
+}
+
+// Second product of a pass for groups of TT token tiles.
+template <int DT, int TT>
+static void launch_dsd_multi(int pass, int Tt, int gt, int d, int F, const uint16_t* W2, const uint16_t* b2,
+                             const int* row_ptr, const int* col_idx, int nnz_cap, const uint16_t* act,
+                             uint16_t* out, float* part, size_t part_bytes, hipStream_t st) {
+  const uint16_t* none = nullptr;
   ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
   // The dsd launch has (column chunks) x (tile groups) workgroups, one per CU, all about equally
   // long.  When they make whole rounds plus a small rest, that rest would keep the launch alive
@@ -720,10 +750,10 @@ static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t*
     float* nopart = nullptr;
     if (sp.full > 0)
       hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3((unsigned)sp.full), dim3(kThreads), 0, st,
-                         (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                         act, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
                          nnz_cap, out, none, none, 0, 0, chunks, 1, nopart);
     hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3(sp.rest * sp.pieces), dim3(kThreads), 0, st,
-                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       act, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
                        nnz_cap, out, none, none, 0, (int)sp.full, chunks, sp.pieces, part);
     hipLaunchKernelGGL((ffn_dsd_reduce<DT, TT>), dim3(sp.rest, TT / 2), dim3(kThreads), 0, st,
                        (const float*)part, sp.pieces, (int)sp.full, chunks, d, b2, out);
@@ -734,16 +764,16 @@ static void launch_multi(int pass, int Tt, int gt, int d, int F, const uint16_t*
   if (wgs > kCUs && rest > 0 && rest * 5 < kCUs * 3) groups = (int)((wgs - rest) / chunks);
   if (groups > 0)
     hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, TT>), dim3(chunks, groups), dim3(kThreads), 0, st,
-                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       act, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
                        nnz_cap, out, none, none, 0, 0, chunks, 0, nopart);
   const int left = Tt - groups * TT;   // a multiple of TT
   if (left > 0 && TT == 4)
     hipLaunchKernelGGL((ffn_dsdn_bf16<DT, false, 2>), dim3(chunks, left / 2), dim3(kThreads), 0, st,
-                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       act, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
                        nnz_cap, out, none, none, groups * TT / 2, 0, chunks, 0, nopart);
   else if (left > 0)
     hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3(chunks, left), dim3(kThreads), 0, st,
-                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
+                       act, W2, (long long)F, b2, row_ptr, col_idx, gt, d,
                        nnz_cap, out, none, none, groups * TT);
 }
 
@@ -756,44 +786,46 @@ static hipError_t launch_ffn_bf16_t(int pass, int Tt, int gt, int Fb, int d, int
   (void)Fb;
   if (((long long)nnz_cap * gt + 3) / 4 + Tt > (1ll << 30)) return hipErrorInvalidValue;
   const int tt = tiles_per_wg(Tt, gt, nnz_cap);
-  if (tt == 4) {
-    launch_multi<DT, 4>(pass, Tt, gt, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap, act_out,
-                        act_gate, out, part, part_bytes, st);
-    return hipGetLastError();
+  // The first product may take smaller groups than the second (the activation blocks are laid out
+  // the same for every group size): its work items, tile groups x groups of four list entries,
+  // run in rounds of one per CU, and a round lasts as long as one item's K-steps, whose time is
+  // the step's matrix instructions plus its transfers (512 clocks of the first per token tile,
+  // 2 clocks per 128-byte row of the second).  The group size with the cheapest rounds wins: e.g.
+  // 89 entries for 64 tiles are 368 items = two rounds of four tiles but 736 = three rounds of
+  // two, which cost less; 33 entries are one round of four tiles against two of two.
+  int tts = tt;
+  long long best = -1;
+  for (int t = tt; t >= 1; t /= 2) {
+    // (host-known bound: the entries of all list rows in groups of four, a ragged group per further row)
+    const long long items = (long long)(gt / t) * ((nnz_cap + 3) / 4 + (Tt / gt - 1));
+    const long long rounds = (items + kCUs - 1) / kCUs;
+    const long long cost = rounds * (512 * t + 2 * (64 * t + 256));
+    if (best < 0 || cost < best) {
+      best = cost;
+      tts = t;
+    }
   }
-  if (tt == 2) {
-    launch_multi<DT, 2>(pass, Tt, gt, d, F, A, W1, b1, W2, b2, row_ptr, col_idx, nnz_cap, act_out,
-                        act_gate, out, part, part_bytes, st);
-    return hipGetLastError();
-  }
-  const dim3 g1 = sdd_grid(Tt, gt, nnz_cap);
-  const uint16_t* none = nullptr;
-  // more than one item per CU but at most two: two resident workgroups of two stages each
-  // (the item count is known on the device only; a list row of n entries makes ceil(n / 4) items,
-  // 3/8 of an item more than n / 4 on average, which is what the estimate adds per tile)
-  const long long items_est = ((long long)nnz_cap * gt + 3) / 4 + (3 * (long long)Tt + 7) / 8;
-  const bool two_resident = items_est > kCUs && items_est <= 2 * kCUs;
-  {
-    ProfScope ps(pass == 0 ? kKFfnUp : kKFfnDh, st);
-    if (pass == 0 && two_resident)
-      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false, 2>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
-                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
-    else if (pass == 0)
-      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 0, false>), g1, dim3(kThreads), 0, st, A, W1, b1, row_ptr,
-                         col_idx, Tt, gt, d, nnz_cap, act_out, none, none, none);
-    else if (two_resident)
-      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false, 2>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
-                         col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
-    else
-      hipLaunchKernelGGL((ffn_sdd_bf16<DT, 1, false>), g1, dim3(kThreads), 0, st, A, W1, none, row_ptr,
-                         col_idx, Tt, gt, d, nnz_cap, act_out, act_gate, none, none);
-  }
+  if (tts == 4)
+    launch_sdd_multi<DT, 4>(pass, Tt, gt, d, A, W1, b1, row_ptr, col_idx, nnz_cap, act_out, act_gate, st);
+  else if (tts == 2)
+    launch_sdd_multi<DT, 2>(pass, Tt, gt, d, A, W1, b1, row_ptr, col_idx, nnz_cap, act_out, act_gate, st);
+  else
+    launch_sdd_one<DT>(pass, Tt, gt, d, A, W1, b1, row_ptr, col_idx, nnz_cap, act_out, act_gate, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
-  hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
-                     (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap,
-                     out, none, none, 0);
+  if (tt == 4) {
+    launch_dsd_multi<DT, 4>(pass, Tt, gt, d, F, W2, b2, row_ptr, col_idx, nnz_cap, act_out, out, part,
+                            part_bytes, st);
+  } else if (tt == 2) {
+    launch_dsd_multi<DT, 2>(pass, Tt, gt, d, F, W2, b2, row_ptr, col_idx, nnz_cap, act_out, out, part,
+                            part_bytes, st);
+  } else {
+    const uint16_t* none = nullptr;
+    ProfScope ps(pass == 0 ? kKFfnDown : kKFfnDx, st);
+    hipLaunchKernelGGL((ffn_dsd_bf16<DT, false>), dim3((d + kRowsA - 1) / kRowsA, Tt), dim3(kThreads), 0, st,
+                       (const uint16_t*)act_out, W2, (long long)F, b2, row_ptr, col_idx, gt, d, nnz_cap,
+                       out, none, none, 0);
+  }
   return hipGetLastError();
 }
 
