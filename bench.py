@@ -442,7 +442,8 @@ def measure_peaks(lx, torch):
     return {"mfma_bf16_tflops": mfma / 1e12, "stream_copy_gbs": copy / 1e9}
 
 
-def run(workload: str, steps: int, warmup: int, with_cpu: bool, cache: str = "warm", peaks=None):
+def run(workload: str, steps: int, warmup: int, with_cpu: bool, cache: str = "warm", peaks=None,
+        two_streams: bool = False):
     import torch
     from paper_2510_15964_amd import lx
     from util import dev
@@ -555,7 +556,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, cache: str = "wa
     # stream each (the lists first, then both halves side by side).  Reported next to the headline,
     # never as `value`: in a transformer layer the FFN consumes what attention produced.
     two_streams_ms = None
-    if not f.get("host_weights") and attn.pool is None and ffn_jobs[0].pred is None:
+    if two_streams and not f.get("host_weights") and attn.pool is None and ffn_jobs[0].pred is None:
         side = torch.cuda.Stream()
         ev_lists, ev_attn = torch.cuda.Event(), torch.cuda.Event()
 
@@ -713,7 +714,8 @@ def main():
         torch.cuda.set_device(0)
         peaks = measure_peaks(lx, torch)
         log(f"measured peaks: {peaks}")
-    res = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, args.cache, peaks)
+    res = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, args.cache, peaks,
+              two_streams=not args.no_extras)
     if not args.no_extras:
         if args.cache == "warm":
             cold = run(args.workload, max(args.steps // 2, 5), 2, False, "cold", peaks)
