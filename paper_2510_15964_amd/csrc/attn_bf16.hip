@@ -54,9 +54,10 @@ namespace lx {
 constexpr int kAT = 256;                 // threads per workgroup
 constexpr int kAW = kAT / kWave;         // wavefronts per workgroup
 // ring stages / resident workgroups per CU (= wavefronts per SIMD) the kernels are compiled
-// for, head size 64: forward 2 / 4, dQ 3 / 3, dK/dV 3 / 3 (measured against 3 / 3, 2 / 3 and
-// 2 / 2 or 4 / 2); head size 128: 2 / 2 everywhere (a stage is 32 KiB)
-constexpr int kFwdNs64 = 2, kFwdOcc64 = 4, kDqNs64 = 3, kDqOcc64 = 3, kDkvNs64 = 3, kDkvOcc64 = 3;
+// for, head size 64: forward 2 / 4, dQ 2 / 4 (128 registers, four of them spilled), dK/dV 3 / 3
+// (measured against 3 / 3, 3 / 3 and 2 / 3, and 2 / 2 or 4 / 2); head size 128: 2 / 2
+// everywhere (a stage is 32 KiB)
+constexpr int kFwdNs64 = 2, kFwdOcc64 = 4, kDqNs64 = 2, kDqOcc64 = 4, kDkvNs64 = 3, kDkvOcc64 = 3;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 8.f;            // log2 units; see the forward kernel
