@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   int* __restrict__ col_idx = job.col_idx;
   __shared__ int offs[kChunkRows];
   __shared__ int wave_tot[kCompactWaves];
-  __shared__ uint8_t stage[kStageBytes];
+  __shared__ __attribute__((aligned(16))) uint8_t stage[kStageBytes + 16];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int total_rows = batch * rows;
   const int parts = compact_parts(total_rows, cols), part = blockIdx.y;
@@ -108,18 +108,21 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   const int rpw = kWave / cp;           // rows per wave pass
   const int sub = lane / cp, cl = lane % cp;
   const unsigned long long field = cp == 64 ? ~0ull : ((1ull << cp) - 1ull);
+  // all rows of all masks are one contiguous range of bytes, row after row
+  const bool rowmajor = cstride == 1 && rstride == cols && (batch == 1 || bstride == (long long)rows * cols);
   int carry = 0;
   if (row_lo > 0) {      // active entries of the rows before this part
     const long long before = (long long)row_lo * cols;
     int cnt = 0;
-    // Whole masks before this part whose rows * cols bytes are one contiguous range (either
-    // orientation) are counted 16 bytes per load; the rows of the mask the part starts in, and
-    // masks with other strides, byte by byte below.
+    // Bytes before this part that are one contiguous range are counted 16 bytes per load: all of
+    // them when the rows lie one after the other, else the whole masks before the part when each
+    // mask is contiguous in the other orientation; the rest (the rows of the mask the part
+    // starts in, masks with other strides) byte by byte below.
     long long done = 0;
-    const bool dense = bstride == (long long)rows * cols &&
-                       ((cstride == 1 && rstride == cols) || (rstride == 1 && cstride == rows));
-    if (dense && row_lo >= rows) {
-      const long long nbytes = (long long)(row_lo / rows) * rows * cols;
+    const bool dense = bstride == (long long)rows * cols && rstride == 1 && cstride == rows;
+    const long long nbytes = rowmajor ? before
+                             : (dense && row_lo >= rows ? (long long)(row_lo / rows) * rows * cols : 0);
+    if (nbytes > 0) {
       long long head = (16 - (long long)(reinterpret_cast<uintptr_t>(mask) & 15)) & 15;
       head = head < nbytes ? head : nbytes;
       if (tid < head) cnt += mask[tid] != 0;
@@ -166,18 +169,42 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompactJ
   }
   for (int chunk = row_lo; chunk < row_hi; chunk += chunk_rows) {
     const int n = min(chunk_rows, row_hi - chunk);
-    if (staged) {
+    int soff = 0;          // where the chunk's first byte sits in `stage`
+    if (staged && rowmajor) {
+      // a contiguous range: 16 bytes per load, placed so that source and stage are aligned alike
+      const uint8_t* __restrict__ src = mask + (long long)chunk * cols;
+      const int len = n * cols;
+      soff = (int)(reinterpret_cast<uintptr_t>(src) & 15);
+      const int head = min((16 - soff) & 15, len);
+      if (tid < head) stage[soff + tid] = src[tid];
+      const int nvec = (len - head) / 16;
+      const uint4* __restrict__ vp = reinterpret_cast<const uint4*>(src + head);
+      uint4* sp = reinterpret_cast<uint4*>(stage + soff + head);
+      for (int i = tid; i < nvec; i += kCompactThreads) sp[i] = vp[i];
+      const int tail = head + nvec * 16;                   // fewer than 16 bytes remain
+      if (tail + tid < len) stage[soff + tail + tid] = src[tail + tid];
+      __syncthreads();
+    } else if (staged) {
+      // any strides: byte loads, eight in flight per thread
+      constexpr int kBatch = 8;
       MaskCursor cur;
       cur.init((long long)chunk * cols + tid, rows, cols);
-      for (int idx = tid; idx < n * cols; idx += kCompactThreads) {
-        stage[idx] = mask[cur.offset(bstride, rstride, cstride)];
-        cur.advance();
+      for (int i0 = tid; i0 < n * cols; i0 += kCompactThreads * kBatch) {
+        uint8_t v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          v[u] = i0 + u * kCompactThreads < n * cols ? mask[cur.offset(bstride, rstride, cstride)] : (uint8_t)0;
+          cur.advance();
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+          if (i0 + u * kCompactThreads < n * cols) stage[i0 + u * kCompactThreads] = v[u];
       }
       __syncthreads();
     }
     auto is_on = [&](int r, int c) -> bool {
       if (c >= cols) return false;
-      if (staged) return stage[r * cols + c] != 0;
+      if (staged) return stage[soff + r * cols + c] != 0;
       const int gr = chunk + r;
       return mask[(long long)(gr / rows) * bstride + (long long)(gr % rows) * rstride +
                   (long long)c * cstride] != 0;
